@@ -1,0 +1,229 @@
+"""CPU oracle for the RS-DGC local gradient compressor -- TEST INFRASTRUCTURE.
+
+Thin ctypes layer over ``rsdgc_oracle.c`` (plain C, double-precision window
+statistics, full-sort ranking).  Only the tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; the GPU library and its
+Python binding never do, and share no code with it.
+
+Step numbering (used in the function names' docstrings) follows the paper:
+Eq. 12 (accumulate), Eqs. 6-10 (NSI), Eq. 11 (k), Algorithm 1 (ranking),
+Section III-C (keep whole neighbourhoods, emit indices), Eq. 12 (residual,
+decompression).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import List, NamedTuple, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rsdgc_oracle.c")
+_LIB = os.path.join(_HERE, "librsdgc_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no fast-math, no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-ffp-contract=off",
+               "-fno-fast-math", "-Wall", "-Wextra", _SRC, "-o", _LIB, "-lm"]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    i64, f64, c_int = ctypes.c_int64, ctypes.c_double, ctypes.c_int
+    fp = ctypes.POINTER(ctypes.c_float)
+    u32p = ctypes.POINTER(ctypes.c_uint32)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    lib.rsdgc_oracle_accumulate.argtypes = [fp, fp, fp, i64]
+    lib.rsdgc_oracle_accumulate.restype = None
+    lib.rsdgc_oracle_nsi_at.argtypes = [fp, i64, i64, c_int, f64, i64, i64]
+    lib.rsdgc_oracle_nsi_at.restype = f64
+    lib.rsdgc_oracle_nsi.argtypes = [fp, i64, i64, c_int, f64, fp]
+    lib.rsdgc_oracle_nsi.restype = None
+    lib.rsdgc_oracle_k.argtypes = [i64, c_int, f64]
+    lib.rsdgc_oracle_k.restype = i64
+    lib.rsdgc_oracle_select.argtypes = [fp, i64, i64, u32p, fp]
+    lib.rsdgc_oracle_select.restype = c_int
+    lib.rsdgc_oracle_dilate.argtypes = [u32p, i64, i64, i64, c_int, u8p]
+    lib.rsdgc_oracle_dilate.restype = None
+    lib.rsdgc_oracle_emit.argtypes = [fp, u8p, i64, u32p, fp]
+    lib.rsdgc_oracle_emit.restype = i64
+    lib.rsdgc_oracle_residual.argtypes = [fp, u8p, i64, fp]
+    lib.rsdgc_oracle_residual.restype = None
+    lib.rsdgc_oracle_decompress.argtypes = [u32p, fp, i64, fp, i64, c_int]
+    lib.rsdgc_oracle_decompress.restype = None
+    lib.rsdgc_oracle_compress_layer.argtypes = [fp, fp, i64, i64, c_int, f64, f64,
+                                                u32p, fp, u32p, i64p, fp, fp, fp]
+    lib.rsdgc_oracle_compress_layer.restype = i64
+    _lib = lib
+    return lib
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _p(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _check_p(p: int) -> None:
+    if p < 1 or p % 2 == 0:
+        raise ValueError("neighbourhood side p must be odd and >= 1")
+
+
+# ------------------------------------------------------------------ steps
+def accumulate(r, g) -> np.ndarray:
+    """Eq. 12 line 2 (u = g): v = r + g, one float32 add per element."""
+    r, g = _f32(r), _f32(g)
+    assert r.shape == g.shape
+    v = np.empty_like(r)
+    _load().rsdgc_oracle_accumulate(_p(r, ctypes.c_float), _p(g, ctypes.c_float),
+                                    _p(v, ctypes.c_float), r.size)
+    return v
+
+
+def nsi_at(v, p: int, alpha: float, x0: int, y0: int) -> float:
+    """Eqs. 8-10 at one centre, in double (not rounded to float32)."""
+    _check_p(p)
+    v = _f32(v)
+    R, C = v.shape
+    return float(_load().rsdgc_oracle_nsi_at(_p(v, ctypes.c_float), R, C, p, float(alpha),
+                                             int(x0), int(y0)))
+
+
+def nsi(v, p: int, alpha: float) -> np.ndarray:
+    """NSI map (float32) of one R x C layer."""
+    _check_p(p)
+    v = _f32(v)
+    R, C = v.shape
+    out = np.empty((R, C), dtype=np.float32)
+    _load().rsdgc_oracle_nsi(_p(v, ctypes.c_float), R, C, p, float(alpha),
+                             _p(out, ctypes.c_float))
+    return out
+
+
+def keep_count(G: int, p: int, rho: float) -> int:
+    """Eq. 11: number of neighbourhoods kept in a layer of G elements."""
+    _check_p(p)
+    return int(_load().rsdgc_oracle_k(int(G), p, float(rho)))
+
+
+def select(nsi_map, k: int) -> Tuple[np.ndarray, Optional[float]]:
+    """Algorithm 1 ranking: indices (ascending) of the k top-ranked centres and
+    the k-th largest score (None when k == 0)."""
+    s = _f32(nsi_map).reshape(-1)
+    k = int(k)
+    centres = np.empty(max(k, 0), dtype=np.uint32)
+    tau = ctypes.c_float(0.0)
+    rc = _load().rsdgc_oracle_select(_p(s, ctypes.c_float), s.size, k,
+                                     _p(centres, ctypes.c_uint32), ctypes.byref(tau))
+    if rc != 0:
+        raise MemoryError("oracle ranking ran out of memory")
+    return centres, (float(tau.value) if k > 0 else None)
+
+
+def dilate(centres, R: int, C: int, p: int) -> np.ndarray:
+    """Mask (uint8, R x C) of all elements inside a selected neighbourhood."""
+    _check_p(p)
+    c = np.ascontiguousarray(centres, dtype=np.uint32)
+    mask = np.empty((R, C), dtype=np.uint8)
+    _load().rsdgc_oracle_dilate(_p(c, ctypes.c_uint32), c.size, R, C, p,
+                                _p(mask, ctypes.c_uint8))
+    return mask
+
+
+def emit(v, mask) -> Tuple[np.ndarray, np.ndarray]:
+    """Kept (index, value) pairs in ascending flat index."""
+    v = _f32(v).reshape(-1)
+    m = np.ascontiguousarray(mask, dtype=np.uint8).reshape(-1)
+    cap = int(m.astype(bool).sum())
+    idx = np.empty(cap, dtype=np.uint32)
+    val = np.empty(cap, dtype=np.float32)
+    n = _load().rsdgc_oracle_emit(_p(v, ctypes.c_float), _p(m, ctypes.c_uint8), v.size,
+                                  _p(idx, ctypes.c_uint32), _p(val, ctypes.c_float))
+    assert n == cap
+    return idx, val
+
+
+def residual(v, mask) -> np.ndarray:
+    """r_new = 0 where sent, v elsewhere."""
+    vv = _f32(v)
+    m = np.ascontiguousarray(mask, dtype=np.uint8).reshape(-1)
+    out = np.empty(vv.size, dtype=np.float32)
+    _load().rsdgc_oracle_residual(_p(vv.reshape(-1), ctypes.c_float), _p(m, ctypes.c_uint8),
+                                  vv.size, _p(out, ctypes.c_float))
+    return out.reshape(vv.shape)
+
+
+def decompress(idx, val, G: int, dense: Optional[np.ndarray] = None,
+               accumulate_into: bool = False) -> np.ndarray:
+    """Scatter pairs into a dense float32 vector of G elements."""
+    idx = np.ascontiguousarray(idx, dtype=np.uint32)
+    val = _f32(val)
+    if dense is None:
+        dense = np.zeros(G, dtype=np.float32)
+    assert dense.dtype == np.float32 and dense.size == G and dense.flags.c_contiguous
+    _load().rsdgc_oracle_decompress(_p(idx, ctypes.c_uint32), _p(val, ctypes.c_float),
+                                    idx.size, _p(dense.reshape(-1), ctypes.c_float), G,
+                                    1 if accumulate_into else 0)
+    return dense
+
+
+# ------------------------------------------------------------ whole layers
+class LayerResult(NamedTuple):
+    idx: np.ndarray       # uint32, ascending flat indices of kept elements
+    val: np.ndarray       # float32, v at those indices
+    centres: np.ndarray   # uint32, ascending flat indices of selected centres
+    k: int                # Eq. 11
+    tau: Optional[float]  # k-th largest NSI (float32 value), None if k == 0
+    nsi: np.ndarray       # float32 R x C
+    v: np.ndarray         # float32 R x C, accumulated gradient
+    r_new: np.ndarray     # float32 R x C
+
+
+def compress_layer(g, r, p: int, alpha: float, rho: float) -> LayerResult:
+    """Steps 1-7 for one layer.  g, r: R x C float32; r is NOT modified."""
+    _check_p(p)
+    g = _f32(g)
+    r_new = _f32(r).copy()
+    assert g.ndim == 2 and g.shape == r_new.shape
+    R, C = g.shape
+    G = R * C
+    k = keep_count(G, p, rho)
+    cap = min(k * p * p, G)
+    idx = np.empty(max(cap, 1), dtype=np.uint32)
+    val = np.empty(max(cap, 1), dtype=np.float32)
+    centres = np.empty(max(k, 1), dtype=np.uint32)
+    k_out = ctypes.c_int64(0)
+    tau = ctypes.c_float(0.0)
+    nsi_map = np.empty((R, C), dtype=np.float32)
+    v = np.empty((R, C), dtype=np.float32)
+    n = _load().rsdgc_oracle_compress_layer(
+        _p(g, ctypes.c_float), _p(r_new, ctypes.c_float), R, C, p, float(alpha), float(rho),
+        _p(idx, ctypes.c_uint32), _p(val, ctypes.c_float), _p(centres, ctypes.c_uint32),
+        ctypes.byref(k_out), ctypes.byref(tau), _p(nsi_map, ctypes.c_float),
+        _p(v, ctypes.c_float))
+    if n < 0:
+        raise MemoryError("oracle ran out of memory")
+    assert k_out.value == k
+    return LayerResult(idx[:n].copy(), val[:n].copy(), centres[:k].copy(), k,
+                       float(tau.value) if k > 0 else None, nsi_map, v, r_new)
+
+
+def compress_model(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray], p: int,
+                   alpha: float, ratios: Sequence[float]) -> List[LayerResult]:
+    """All layers of one iteration, each independently (per-layer selection)."""
+    assert len(grads) == len(residuals) == len(ratios)
+    return [compress_layer(g, r, p, alpha, rho) for g, r, rho in zip(grads, residuals, ratios)]
