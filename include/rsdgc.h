@@ -1,0 +1,150 @@
+/*
+ * rsdgc.h -- C ABI of the MI355X (gfx950) RS-DGC local gradient compressor.
+ *
+ * The library implements the per-iteration, per-node sparsifier Sparse(.) of
+ * the paper's Eq. 2: for every layer the gradient, plus the residual carried
+ * over from earlier iterations (Eq. 12), is viewed as an R x C matrix
+ * (Section III-C), the Neighborhood Statistics Indicator (Eqs. 6-10) is
+ * evaluated at every element, the k_l = ceil(G_l / p^2 * rho_l) best-ranked
+ * neighbourhoods (Eq. 11, Algorithm 1) are kept whole, and their elements are
+ * emitted as compacted (index, value) pairs while the rest stays in the
+ * residual.
+ *
+ * Conventions
+ *   - All matrices are float32, row-major, R rows x C columns; for a
+ *     convolution weight R = out_ch, C = in_ch * kh * kw.
+ *   - "arena": one float32 device array holding all layers back to back; layer
+ *     l starts at element rsdgc_layer_offset(plan, l), a multiple of 64.
+ *     Padding elements between layers are never read or written.
+ *   - Pointers marked [device] must be device memory of the current HIP
+ *     device; [host] is ordinary host memory.  The caller owns every buffer;
+ *     the library never allocates, frees or synchronises device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All device work is enqueued on it and the call returns without waiting.
+ *   - Every function returning int returns RSDGC_OK (0) or a negative
+ *     RSDGC_E* code.  Arguments are validated before anything is enqueued, so
+ *     on RSDGC_EINVAL no buffer has been touched.  Nothing throws or aborts
+ *     across this boundary.
+ *   - Non-finite gradient values are not detected; results for them are
+ *     unspecified (the paper does not treat them).
+ *   - A plan may be used by one stream at a time.
+ */
+#ifndef RSDGC_H
+#define RSDGC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RSDGC_OK        0
+#define RSDGC_EINVAL   (-1)  /* bad argument (null pointer, shape, p, alpha, ratio) */
+#define RSDGC_ENOMEM   (-2)  /* host allocation failed */
+#define RSDGC_EHIP     (-3)  /* a HIP call failed; see rsdgc_last_hip_error() */
+
+#define RSDGC_MAX_P     7    /* largest supported neighbourhood side */
+
+typedef struct rsdgc_plan_s rsdgc_plan_t;              /* opaque host object */
+typedef struct { int64_t rows, cols; } rsdgc_shape_t;  /* matrix view of one layer */
+
+/* ---------------------------------------------------------------- plan --
+ * rsdgc_plan: describe the model once (host only, no HIP call).
+ *   shapes      [host] n_layers matrix views; rows, cols >= 1, rows*cols < 2^32.
+ *   p           neighbourhood side of Eq. 7, odd, 1..RSDGC_MAX_P, used for
+ *               every layer unless p_per_layer != NULL.  Half width (p-1)/2;
+ *               window slots outside the matrix count as zeros and the
+ *               divisor of Eqs. 9-10 is always p*p.
+ *   p_per_layer [host] optional n_layers values overriding p (Section III-C:
+ *               p is chosen per kind of layer).
+ *   alpha       mixing weight of Eq. 8, in [0, 1].
+ *   keep_ratio  [host] n_layers per-layer keep fractions rho_l of Eq. 5, each
+ *               in [0, 1] (0.001 keeps one element in a thousand).
+ *   out_plan    receives the plan; destroy with rsdgc_plan_destroy.
+ * The plan fixes k_l (Eq. 11, evaluated in double as ceil((G_l / p^2) * rho_l),
+ * clamped to [0, G_l]), arena offsets, output segment offsets and capacities
+ * and the workspace size.                                                   */
+int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
+               const int32_t *p_per_layer, double alpha,
+               const double *keep_ratio, rsdgc_plan_t **out_plan);
+
+/* New per-layer keep ratios (the paper refreshes them once per epoch,
+ * Section III-B / Algorithm 1).  Recomputes k_l, output offsets, capacities.
+ * The workspace size does not change.                                       */
+int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio);
+
+void rsdgc_plan_destroy(rsdgc_plan_t *plan);
+
+/* Host queries; l in [0, n_layers).  Invalid arguments give -1 (0 for size_t). */
+int32_t rsdgc_n_layers(const rsdgc_plan_t *plan);
+int64_t rsdgc_total_elems(const rsdgc_plan_t *plan);             /* arena length incl. padding */
+int64_t rsdgc_layer_offset(const rsdgc_plan_t *plan, int32_t l); /* arena offset of layer l    */
+int64_t rsdgc_layer_elems(const rsdgc_plan_t *plan, int32_t l);  /* G_l = rows * cols          */
+int64_t rsdgc_layer_k(const rsdgc_plan_t *plan, int32_t l);      /* Eq. 11                      */
+int64_t rsdgc_out_offset(const rsdgc_plan_t *plan, int32_t l);   /* start of layer l's pairs    */
+int64_t rsdgc_out_capacity(const rsdgc_plan_t *plan);            /* sum_l min(k_l p_l^2, G_l)   */
+int64_t rsdgc_centre_offset(const rsdgc_plan_t *plan, int32_t l);/* start of layer l's centres  */
+int64_t rsdgc_centre_capacity(const rsdgc_plan_t *plan);         /* sum_l k_l                   */
+size_t  rsdgc_workspace_bytes(const rsdgc_plan_t *plan);
+
+/* ------------------------------------------------------------- compress --
+ * One iteration of the sparsifier for all layers (Eq. 2's Sparse, Algorithm 1
+ * inner loop, Eq. 12 with u = g).
+ *   grad      [device, const] float32 arena: this iteration's gradient g.
+ *   residual  [device, in/out] float32 arena: on entry the carried residual r
+ *             (all zeros before the first iteration); v = r + g is formed with
+ *             one float32 add; on exit r = +0 where v was emitted, v elsewhere.
+ *   out_idx   [device] uint32, rsdgc_out_capacity entries.  Layer l's pairs
+ *   out_val   [device] float32, same length.     start at rsdgc_out_offset(l);
+ *             idx is the flat row-major index x*C + y inside the layer,
+ *             strictly ascending; val is v[idx] bit for bit.  Entries past
+ *             out_counts[l] inside a segment are left untouched.
+ *   out_counts        [device] int32[n_layers]: pairs emitted per layer
+ *                     (k_l <= count <= min(k_l p^2, G_l), or 0 when k_l = 0).
+ *   out_centre_idx    [device, nullable] uint32, rsdgc_centre_capacity entries:
+ *                     the selected neighbourhood centres of layer l, ascending,
+ *                     from rsdgc_centre_offset(l) -- the "neighbourhood index"
+ *                     of Section III-C.
+ *   out_centre_counts [device, nullable] int32[n_layers]: selected centres per
+ *                     layer; always equals k_l.
+ *   workspace [device] rsdgc_workspace_bytes bytes, 256-byte aligned.  It is
+ *             the plan's device-side state: keep the same buffer, unmodified,
+ *             between calls that use this plan (switching to another buffer is
+ *             allowed at any time and is detected by its address).
+ * Ranking ties are resolved towards the lower flat index; exactly k_l centres
+ * are selected.  Scores are float32 roundings of double-precision window
+ * statistics.                                                               */
+int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual,
+                   uint32_t *out_idx, float *out_val, int32_t *out_counts,
+                   uint32_t *out_centre_idx, int32_t *out_centre_counts,
+                   void *workspace, void *stream);
+
+/* NSI map only (Eqs. 8-10 at every element of every layer), for inspection:
+ *   residual [device, nullable] NULL means an all-zero residual.
+ *   nsi_out  [device] float32 arena; padding elements are not written.
+ * Neither grad nor residual is modified.                                    */
+int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual,
+              float *nsi_out, void *workspace, void *stream);
+
+/* ----------------------------------------------------------- decompress --
+ * Scatter one message back into a dense arena (the sum over nodes of
+ * sparse(v) in Eq. 12's third line is formed by calling this once per
+ * message with accumulate = 1).
+ *   idx, val, counts  [device] as produced by rsdgc_compress with this plan.
+ *   dense             [device] float32 arena.
+ *   accumulate = 0: every layer element of dense is overwritten (zeros where
+ *                   nothing was sent);  != 0: dense[idx] += val.            */
+int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
+                     const int32_t *counts, float *dense, int accumulate,
+                     void *workspace, void *stream);
+
+/* ----------------------------------------------------------- diagnostics */
+const char *rsdgc_strerror(int code);
+/* Text of the last HIP error seen by this thread inside the library ("" if none). */
+const char *rsdgc_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSDGC_H */

@@ -1,0 +1,200 @@
+"""ctypes binding of librsdgc.so: argument marshalling only.
+
+Function names mirror the C ABI declared in ``include/rsdgc.h``.  Device buffers are
+torch tensors (torch is used for device memory and streams only); their addresses are
+handed to the library unchanged.  There is no CPU fallback: if the library has not been
+built, ``load()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librsdgc.so")
+
+RSDGC_OK, RSDGC_EINVAL, RSDGC_ENOMEM, RSDGC_EHIP = 0, -1, -2, -3
+RSDGC_MAX_P = 7
+
+EXPORTS = [
+    "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_destroy", "rsdgc_n_layers",
+    "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
+    "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
+    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_nsi", "rsdgc_decompress",
+    "rsdgc_strerror", "rsdgc_last_hip_error",
+]
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [("rows", ctypes.c_int64), ("cols", ctypes.c_int64)]
+
+
+class RsdgcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        lib = load()
+        msg = lib.rsdgc_strerror(code).decode()
+        hip = lib.rsdgc_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} ({code})" + (f" [{hip}]" if code == RSDGC_EHIP and hip else ""))
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load librsdgc.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2312_17530_amd.build` "
+            "(or __graft_entry__.build()); there is no fallback implementation")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+    lib.rsdgc_plan.argtypes = [ctypes.POINTER(Shape), i32, i32, ctypes.POINTER(i32), f64,
+                               ctypes.POINTER(f64), ctypes.POINTER(vp)]
+    lib.rsdgc_plan.restype = ctypes.c_int
+    lib.rsdgc_plan_set_ratios.argtypes = [vp, ctypes.POINTER(f64)]
+    lib.rsdgc_plan_set_ratios.restype = ctypes.c_int
+    lib.rsdgc_plan_destroy.argtypes = [vp]
+    lib.rsdgc_plan_destroy.restype = None
+    lib.rsdgc_n_layers.argtypes = [vp]
+    lib.rsdgc_n_layers.restype = i32
+    for name in ["rsdgc_total_elems", "rsdgc_out_capacity", "rsdgc_centre_capacity"]:
+        getattr(lib, name).argtypes = [vp]
+        getattr(lib, name).restype = i64
+    for name in ["rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k", "rsdgc_out_offset",
+                 "rsdgc_centre_offset"]:
+        getattr(lib, name).argtypes = [vp, i32]
+        getattr(lib, name).restype = i64
+    lib.rsdgc_workspace_bytes.argtypes = [vp]
+    lib.rsdgc_workspace_bytes.restype = ctypes.c_size_t
+    lib.rsdgc_compress.argtypes = [vp] * 10
+    lib.rsdgc_compress.restype = ctypes.c_int
+    lib.rsdgc_nsi.argtypes = [vp] * 6
+    lib.rsdgc_nsi.restype = ctypes.c_int
+    lib.rsdgc_decompress.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
+    lib.rsdgc_decompress.restype = ctypes.c_int
+    lib.rsdgc_strerror.argtypes = [ctypes.c_int]
+    lib.rsdgc_strerror.restype = ctypes.c_char_p
+    lib.rsdgc_last_hip_error.argtypes = []
+    lib.rsdgc_last_hip_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(code: int, where: str) -> None:
+    if code != RSDGC_OK:
+        raise RsdgcError(code, where)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor, None for None."""
+    if t is None:
+        return None
+    assert t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    h = stream if isinstance(stream, int) else stream.cuda_stream
+    return h or None
+
+
+class Plan:
+    """Owner of one rsdgc_plan_t (host object)."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            load().rsdgc_plan_destroy(h)
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def n_layers(self) -> int:
+        return load().rsdgc_n_layers(self._h)
+
+    @property
+    def total_elems(self) -> int:
+        return load().rsdgc_total_elems(self._h)
+
+    @property
+    def out_capacity(self) -> int:
+        return load().rsdgc_out_capacity(self._h)
+
+    @property
+    def centre_capacity(self) -> int:
+        return load().rsdgc_centre_capacity(self._h)
+
+    @property
+    def workspace_bytes(self) -> int:
+        return load().rsdgc_workspace_bytes(self._h)
+
+    def layer_offset(self, l: int) -> int:
+        return load().rsdgc_layer_offset(self._h, l)
+
+    def layer_elems(self, l: int) -> int:
+        return load().rsdgc_layer_elems(self._h, l)
+
+    def layer_k(self, l: int) -> int:
+        return load().rsdgc_layer_k(self._h, l)
+
+    def out_offset(self, l: int) -> int:
+        return load().rsdgc_out_offset(self._h, l)
+
+    def centre_offset(self, l: int) -> int:
+        return load().rsdgc_centre_offset(self._h, l)
+
+
+def rsdgc_plan(shapes: Sequence[Tuple[int, int]], p: int, alpha: float,
+               keep_ratio: Sequence[float], p_per_layer: Optional[Sequence[int]] = None) -> Plan:
+    lib = load()
+    n = len(shapes)
+    if len(keep_ratio) != n or (p_per_layer is not None and len(p_per_layer) != n):
+        raise RsdgcError(RSDGC_EINVAL, "rsdgc_plan")
+    arr = (Shape * max(n, 1))(*[Shape(int(r), int(c)) for r, c in shapes])
+    ratios = (ctypes.c_double * max(len(keep_ratio), 1))(*[float(x) for x in keep_ratio])
+    pp = None
+    if p_per_layer is not None:
+        pp = (ctypes.c_int32 * max(n, 1))(*[int(x) for x in p_per_layer])
+    out = ctypes.c_void_p()
+    _check(lib.rsdgc_plan(arr, n, int(p), pp, float(alpha), ratios, ctypes.byref(out)), "rsdgc_plan")
+    return Plan(out.value)
+
+
+def rsdgc_plan_set_ratios(plan: Plan, keep_ratio: Sequence[float]) -> None:
+    if len(keep_ratio) != plan.n_layers:
+        raise RsdgcError(RSDGC_EINVAL, "rsdgc_plan_set_ratios")
+    ratios = (ctypes.c_double * len(keep_ratio))(*[float(x) for x in keep_ratio])
+    _check(load().rsdgc_plan_set_ratios(plan.handle, ratios), "rsdgc_plan_set_ratios")
+
+
+def rsdgc_compress(plan: Plan, grad, residual, out_idx, out_val, out_counts, workspace,
+                   out_centre_idx=None, out_centre_counts=None, stream=None) -> None:
+    _check(load().rsdgc_compress(plan.handle, _ptr(grad), _ptr(residual), _ptr(out_idx),
+                                 _ptr(out_val), _ptr(out_counts), _ptr(out_centre_idx),
+                                 _ptr(out_centre_counts), _ptr(workspace), _stream(stream)),
+           "rsdgc_compress")
+
+
+def rsdgc_nsi(plan: Plan, grad, residual, nsi_out, workspace, stream=None) -> None:
+    _check(load().rsdgc_nsi(plan.handle, _ptr(grad), _ptr(residual), _ptr(nsi_out),
+                            _ptr(workspace), _stream(stream)), "rsdgc_nsi")
+
+
+def rsdgc_decompress(plan: Plan, idx, val, counts, dense, accumulate: bool, workspace,
+                     stream=None) -> None:
+    _check(load().rsdgc_decompress(plan.handle, _ptr(idx), _ptr(val), _ptr(counts), _ptr(dense),
+                                   1 if accumulate else 0, _ptr(workspace), _stream(stream)),
+           "rsdgc_decompress")

@@ -1,0 +1,99 @@
+// Internal definitions shared by the host-side plan and the HIP kernels.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/rsdgc.h"
+
+namespace rsdgc {
+
+// ---- geometry constants (device and host agree on these) -----------------
+constexpr int kTileRows = 32;        // NSI tile: output rows per workgroup
+constexpr int kTileCols = 128;       // NSI tile: output columns per workgroup
+constexpr int kChunk = 8192;         // elements per workgroup in the 1-D passes
+constexpr int kHistBins = 4096;      // widest radix digit (12 bits)
+constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements
+
+// One layer as the kernels see it (80 bytes).
+struct LayerDev {
+    int64_t elem_off;    // offset of the layer in the g / r / NSI arenas (elements)
+    int64_t out_off;     // first pair of the layer in out_idx / out_val
+    int64_t centre_off;  // first entry of the layer in out_centre_idx
+    uint32_t R, C, G, k;
+    uint32_t p, tiles_x, tile_begin, n_tiles;  // tile_begin: first tile inside its p-group launch
+    uint32_t chunk_begin, n_chunks;
+    uint32_t cap, pad_[3];
+};
+static_assert(sizeof(LayerDev) == 80, "LayerDev layout");
+
+// Per-layer selection state (32 bytes), lives in the workspace.
+struct SelState {
+    unsigned long long T;   // threshold on the composite key (score bits << 32 | ~index)
+    uint32_t k_rem;         // centres still to take inside the current bucket
+    uint32_t done;          // threshold is final
+    uint32_t n_centres;     // centres selected (diagnostic, equals k)
+    uint32_t n_pairs;       // pairs emitted
+    uint32_t pad_[2];
+};
+static_assert(sizeof(SelState) == 32, "SelState layout");
+
+// Directory entry used to map a workgroup id to a layer by binary search.
+struct DirEntry {
+    uint32_t begin;   // first tile (or chunk) of the layer
+    uint32_t layer;
+};
+
+// Byte offsets of the workspace sections (all multiples of 256).
+struct WsLayout {
+    size_t layers = 0;      // LayerDev[n_layers]
+    size_t tile_dir = 0;    // DirEntry[] per p-group, each closed by a sentinel
+    size_t chunk_dir = 0;   // DirEntry[n_layers + 1]
+    size_t state = 0;       // SelState[n_layers]
+    size_t hist = 0;        // uint32[n_layers][kHistBins]
+    size_t chunk_cnt = 0;   // uint32[n_chunks]  kept elements per chunk, then their prefix
+    size_t chunk_ccnt = 0;  // uint32[n_chunks]  selected centres per chunk, then prefix
+    size_t mask = 0;        // uint32[total_elems / 32]  kept-element bitmask
+    size_t cmask = 0;       // uint32[total_elems / 32]  selected-centre bitmask
+    size_t nsi = 0;         // float[total_elems]
+    size_t total = 0;
+    size_t table_bytes = 0; // bytes uploaded from the host (layers .. chunk_dir end)
+    size_t zero_begin = 0, zero_end = 0;  // region cleared at the start of every compress
+};
+
+struct PGroup {           // layers sharing one neighbourhood side: one NSI launch
+    int p = 0;
+    uint32_t n_tiles = 0;
+    uint32_t dir_begin = 0;   // index of the group's first DirEntry in tile_dir
+    uint32_t dir_count = 0;   // entries excluding the sentinel
+};
+
+}  // namespace rsdgc
+
+struct rsdgc_plan_s {
+    int32_t n_layers = 0;
+    double alpha = 0.5;
+    std::vector<rsdgc_shape_t> shapes;
+    std::vector<int32_t> p;
+    std::vector<double> ratio;
+    std::vector<rsdgc::LayerDev> layers;
+    std::vector<rsdgc::PGroup> groups;
+    std::vector<rsdgc::DirEntry> tile_dir;
+    std::vector<rsdgc::DirEntry> chunk_dir;
+    int64_t total_elems = 0;
+    int64_t out_capacity = 0;
+    int64_t centre_capacity = 0;
+    uint32_t n_chunks = 0;
+    rsdgc::WsLayout ws;
+    std::vector<unsigned char> table;   // host image of the uploaded tables
+    // device-side bookkeeping
+    uint64_t version = 1;               // bumped by set_ratios
+    const void *uploaded_ws = nullptr;
+    uint64_t uploaded_version = 0;
+};
+
+namespace rsdgc {
+// Host-only helpers implemented in rsdgc_plan.cpp.
+int64_t keep_count(int64_t G, int p, double rho);   // Eq. 11
+int build_tables(rsdgc_plan_s *plan);               // fills layers, dirs, ws, table
+}  // namespace rsdgc

@@ -1,0 +1,786 @@
+// HIP kernels (gfx950, wave64) and the device-facing entry points of the C ABI.
+//
+// Pipeline of one rsdgc_compress call, all layers per launch:
+//   clear      zero histograms, bitmasks, counters
+//   nsi        v = r + g (Eq. 12), window statistics and NSI (Eqs. 6-10) per element,
+//              NSI map to the workspace, 12-bit histogram of the score bits per layer
+//   find/refine radix select of the k_l-th largest composite key per layer
+//              (Algorithm 1's ranking; Eq. 11's k_l), most significant digit first
+//   mark       selected centres set the bits of their p x p window (Section III-C:
+//              whole neighbourhoods are kept)
+//   count/scan kept elements per chunk and their prefix sums
+//   emit       ordered (index, value) pairs and the residual update (Eq. 12)
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+
+#include "rsdgc_internal.h"
+
+using namespace rsdgc;
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e, const char *what) {
+    std::snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+    return RSDGC_EHIP;
+}
+#define HIP_TRY(expr)                                        \
+    do {                                                     \
+        hipError_t e_ = (expr);                              \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
+    } while (0)
+
+// Radix digits of the 63-bit composite key  K = (score bits << 32) | ~index,
+// most significant first.  Scores are non-negative floats, so their bit pattern
+// orders like the value; ~index makes the lower index the larger key.
+constexpr int kLevels = 6;
+__host__ __device__ constexpr int level_shift(int lv) {
+    return lv == 0 ? 51 : lv == 1 ? 41 : lv == 2 ? 32 : lv == 3 ? 21 : lv == 4 ? 10 : 0;
+}
+__host__ __device__ constexpr int level_bits(int lv) {
+    return lv == 0 ? 12 : lv == 1 ? 10 : lv == 2 ? 9 : lv == 3 ? 11 : lv == 4 ? 11 : 10;
+}
+
+__device__ __forceinline__ unsigned long long composite_key(uint32_t score_bits, uint32_t index) {
+    return (static_cast<unsigned long long>(score_bits & 0x7fffffffu) << 32) |
+           static_cast<unsigned long long>(~index);
+}
+
+// Entry e with dir[e].begin <= id < dir[e + 1].begin  (dir has n entries + a sentinel).
+__device__ __forceinline__ uint32_t dir_lookup(const DirEntry *__restrict__ dir, uint32_t n,
+                                               uint32_t id) {
+    uint32_t lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (dir[mid].begin <= id) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin by id; give each XCD one contiguous
+// range of tiles so that neighbouring tiles (which share halo rows/columns) meet in
+// the same L2.
+__device__ __forceinline__ uint32_t xcd_contiguous(uint32_t bid, uint32_t n) {
+    const uint32_t xcd = bid & 7u, slot = bid >> 3;
+    const uint32_t per = n >> 3, rem = n & 7u;
+    return xcd * per + (xcd < rem ? xcd : rem) + slot;
+}
+
+// Inclusive scan over the 256 threads of a workgroup (4 waves of 64).
+__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_tot /*[4]*/) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    if (lane == 63) wave_tot[wave] = v;
+    __syncthreads();
+    uint32_t add = 0;
+#pragma unroll
+    for (int w = 0; w < 3; ++w)
+        if (w < wave) add += wave_tot[w];
+    const uint32_t r = v + add;
+    __syncthreads();   // wave_tot may be reused by the caller
+    return r;
+}
+
+// ---------------------------------------------------------------- clear --
+__global__ __launch_bounds__(256) void k_clear(uint4 *__restrict__ p, size_t n16) {
+    const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    for (size_t j = i; j < n16; j += stride) p[j] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ void k_init_state(const LayerDev *__restrict__ layers, SelState *__restrict__ state,
+                             int n_layers) {
+    const int l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= n_layers) return;
+    SelState s;
+    const uint32_t k = layers[l].k;
+    s.T = k == 0 ? ~0ull : 0ull;   // no key reaches ~0: nothing is selected when k = 0
+    s.k_rem = k;
+    s.done = k == 0 ? 1u : 0u;
+    s.n_centres = 0;
+    s.n_pairs = 0;
+    s.pad_[0] = s.pad_[1] = 0;
+    state[l] = s;
+}
+
+// ------------------------------------------------------------------ nsi --
+// One workgroup = one 32 x 128 tile of one layer.  The tile of v = r + g plus a halo of
+// h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
+// down 8 rows of 2 adjacent columns, keeping per-row horizontal sums of |w|, w and w^2
+// (double) for the last P rows in registers.  The variance is formed as
+// (P^2 * sum w^2 - (sum w)^2) / P^4 in double, which is exactly 0 for a constant window
+// and keeps equal windows at equal scores wherever they lie.
+template <int P, bool HIST>
+__global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers,
+                                             const DirEntry *__restrict__ dir, uint32_t n_dir,
+                                             uint32_t n_tiles, const float *__restrict__ grad,
+                                             const float *__restrict__ resid,
+                                             float *__restrict__ nsi_out,
+                                             uint32_t *__restrict__ hist, double alpha) {
+    constexpr int H = (P - 1) / 2;
+    constexpr int ROWS = kTileRows + 2 * H;
+    constexpr int PADL = 4;
+    constexpr int PITCH = kTileCols + 2 * PADL;   // 136 floats
+    constexpr int VEC_PER_ROW = PITCH / 4;        // 34
+    constexpr int RPT = 8;                        // output rows per thread
+    __shared__ __attribute__((aligned(16))) float tile[ROWS * PITCH];
+    __shared__ uint32_t lhist[HIST ? kHistBins : 1];
+
+    const int tid = threadIdx.x;
+    const uint32_t t_id = xcd_contiguous(blockIdx.x, n_tiles);
+    const uint32_t e = dir_lookup(dir, n_dir, t_id);
+    const uint32_t l = dir[e].layer;
+    const LayerDev L = layers[l];
+    const uint32_t local = t_id - dir[e].begin;
+    const int trow = static_cast<int>(local / L.tiles_x);
+    const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
+    const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
+    const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
+    const float *__restrict__ g = grad + L.elem_off;
+    const float *__restrict__ r = resid ? resid + L.elem_off : nullptr;
+
+    if (HIST) {
+#pragma unroll
+        for (int b = tid; b < kHistBins; b += 256) lhist[b] = 0;
+    }
+
+    // ---- load v = r + g for the tile and its halo; zero outside the matrix
+    if ((C & 3) == 0) {
+        constexpr int NVEC = ROWS * VEC_PER_ROW;
+        constexpr int ITER = (NVEC + 255) / 256;
+        float4 gv[ITER], rv[ITER];
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const int s = tid + it * 256;
+            const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
+            const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
+            gv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            rv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (s < NVEC && x >= 0 && x < R && y >= 0 && y < C) {
+                const size_t off = static_cast<size_t>(x) * C + y;
+                gv[it] = *reinterpret_cast<const float4 *>(g + off);
+                if (r) rv[it] = *reinterpret_cast<const float4 *>(r + off);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const int s = tid + it * 256;
+            if (s < NVEC) {
+                float4 v;
+                v.x = rv[it].x + gv[it].x;
+                v.y = rv[it].y + gv[it].y;
+                v.z = rv[it].z + gv[it].z;
+                v.w = rv[it].w + gv[it].w;
+                *reinterpret_cast<float4 *>(&tile[s * 4]) = v;   // s*4 == rr*PITCH + 4*j4
+            }
+        }
+    } else {
+        for (int s = tid; s < ROWS * PITCH; s += 256) {
+            const int rr = s / PITCH, j = s - rr * PITCH;
+            const int x = x0 - H + rr, y = y0 - PADL + j;
+            float v = 0.f;
+            if (x >= 0 && x < R && y >= 0 && y < C) {
+                const size_t off = static_cast<size_t>(x) * C + y;
+                v = (r ? r[off] : 0.f) + g[off];
+            }
+            tile[s] = v;
+        }
+    }
+    __syncthreads();
+
+    // ---- window statistics
+    const int tx = tid & 63, ty = tid >> 6;
+    const int c0 = 2 * tx;
+    const int row_base = ty * RPT;
+    const double n = static_cast<double>(P * P);
+    const double inv_n = 1.0 / n;
+    const double beta = 1.0 - alpha;
+    const bool pair_store = (C & 1) == 0;
+
+    double hs_a[P][2], hs_s[P][2], hs_q[P][2];
+#pragma unroll
+    for (int i = 0; i < RPT + 2 * H; ++i) {
+        const float *row = &tile[(row_base + i) * PITCH + PADL + c0 - H];
+        double w[2 * H + 2];
+#pragma unroll
+        for (int j = 0; j < 2 * H + 2; ++j) w[j] = static_cast<double>(row[j]);
+        const int slot = i % P;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            double sa = fabs(w[c]), ss = w[c], sq = w[c] * w[c];
+#pragma unroll
+            for (int j = 1; j < P; ++j) {
+                sa += fabs(w[c + j]);
+                ss += w[c + j];
+                sq = fma(w[c + j], w[c + j], sq);
+            }
+            hs_a[slot][c] = sa;
+            hs_s[slot][c] = ss;
+            hs_q[slot][c] = sq;
+        }
+        if (i >= 2 * H) {
+            const int o = i - 2 * H;   // output row inside the thread's strip
+            float out[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                double sa = hs_a[o % P][c], ss = hs_s[o % P][c], sq = hs_q[o % P][c];
+#pragma unroll
+                for (int j = 1; j < P; ++j) {
+                    sa += hs_a[(o + j) % P][c];
+                    ss += hs_s[(o + j) % P][c];
+                    sq += hs_q[(o + j) % P][c];
+                }
+                const double mean_abs = sa * inv_n;                                   // Eq. 9
+                double d = __dsub_rn(__dmul_rn(n, sq), __dmul_rn(ss, ss));            // P^4 * variance
+                d = d > 0.0 ? d : 0.0;
+                const double sd = sqrt(d) * inv_n;                                    // Eq. 10
+                out[c] = static_cast<float>(__dadd_rn(__dmul_rn(alpha, mean_abs),
+                                                      __dmul_rn(beta, sd)));          // Eq. 8
+            }
+            const int x = x0 + row_base + o, y = y0 + c0;
+            if (x < R && y < C) {
+                const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
+                const bool two = y + 1 < C;
+                if (two && pair_store) {
+                    *reinterpret_cast<float2 *>(nsi_out + off) = make_float2(out[0], out[1]);
+                } else {
+                    nsi_out[off] = out[0];
+                    if (two) nsi_out[off + 1] = out[1];
+                }
+                if (HIST) {
+                    atomicAdd(&lhist[(__float_as_uint(out[0]) & 0x7fffffffu) >> 19], 1u);
+                    if (two) atomicAdd(&lhist[(__float_as_uint(out[1]) & 0x7fffffffu) >> 19], 1u);
+                }
+            }
+        }
+    }
+
+    if (HIST) {
+        __syncthreads();
+        uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins;
+#pragma unroll
+        for (int b = tid; b < kHistBins; b += 256) {
+            const uint32_t c = lhist[b];
+            if (c) atomicAdd(&gh[b], c);
+        }
+    }
+}
+
+// ----------------------------------------------------------------- find --
+// One workgroup per layer: walk the digit histogram from the top, fix the digit that
+// holds the k_rem-th largest key, clear the histogram for the next level.
+__global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
+                                              uint32_t *__restrict__ hist, int shift, int bits) {
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t found;
+    const int l = blockIdx.x, tid = threadIdx.x;
+    uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
+    const int nb = 1 << bits, per = nb >> 8;
+    const SelState st = state[l];
+    if (tid == 0) found = 0;
+    if (!st.done) {
+        // thread t owns bins [hi - per, hi), hi = nb - t * per  (t = 0 holds the top bins)
+        const int hi = nb - tid * per;
+        uint32_t own = 0;
+        for (int b = hi - 1; b >= hi - per; --b) own += h[b];
+        const uint32_t incl = block_scan_incl(own, wave_tot);
+        const uint32_t excl = incl - own;
+        if (excl < st.k_rem && st.k_rem <= incl) {
+            uint32_t acc = excl;
+            for (int b = hi - 1; b >= hi - per; --b) {
+                const uint32_t c = h[b];
+                if (acc + c >= st.k_rem) {
+                    SelState ns = st;
+                    ns.T = st.T | (static_cast<unsigned long long>(b) << shift);
+                    ns.k_rem = st.k_rem - acc;
+                    ns.done = (c == ns.k_rem) ? 1u : 0u;   // whole bucket taken: lower digits stay 0
+                    state[l] = ns;
+                    found = 1;
+                    break;
+                }
+                acc += c;
+            }
+        }
+        __syncthreads();
+        if (tid == 0 && !found) {          // fewer keys than k_rem (cannot happen for finite input)
+            SelState ns = st;
+            ns.done = 1;
+            state[l] = ns;
+        }
+    }
+    __syncthreads();
+    for (int b = tid; b < nb; b += 256) h[b] = 0;
+}
+
+// --------------------------------------------------------------- refine --
+// Histogram of the next digit over the keys that match the threshold prefix so far.
+__global__ __launch_bounds__(256) void k_refine(const LayerDev *__restrict__ layers,
+                                                const DirEntry *__restrict__ chunk_dir,
+                                                uint32_t n_layers,
+                                                const SelState *__restrict__ state,
+                                                uint32_t *__restrict__ hist,
+                                                const uint32_t *__restrict__ keys, int shift,
+                                                int bits, int shift_prev) {
+    __shared__ uint32_t lh[2048];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const SelState st = state[l];
+    if (st.done) return;
+    const LayerDev L = layers[l];
+    const int nb = 1 << bits;
+    for (int b = tid; b < nb; b += 256) lh[b] = 0;
+    __syncthreads();
+    const uint32_t start = (c - L.chunk_begin) * kChunk;
+    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+    const uint32_t *__restrict__ src = keys + L.elem_off + start;
+    const unsigned long long want = st.T >> shift_prev;
+#pragma unroll 2
+    for (int j = 0; j < kChunk / 1024; ++j) {
+        const uint32_t e = j * 1024 + 4 * tid;
+        if (e >= len) break;
+        uint32_t kk[4] = {0, 0, 0, 0};
+        if (e + 3 < len) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(src + e);
+            kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
+        } else {
+            for (uint32_t q = 0; q < 4 && e + q < len; ++q) kk[q] = src[e + q];
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            if (e + q < len) {
+                const unsigned long long K = composite_key(kk[q], start + e + q);
+                if ((K >> shift_prev) == want)
+                    atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins;
+    for (int b = tid; b < nb; b += 256) {
+        const uint32_t v = lh[b];
+        if (v) atomicAdd(&gh[b], v);
+    }
+}
+
+// ----------------------------------------------------------------- mark --
+__device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos, uint32_t nbits) {
+    const size_t w = pos >> 5;
+    const uint32_t b = static_cast<uint32_t>(pos & 31);
+    const uint32_t bits = (1u << nbits) - 1u;          // nbits <= RSDGC_MAX_P
+    atomicOr(&mask[w], bits << b);
+    if (b + nbits > 32) atomicOr(&mask[w + 1], bits >> (32 - b));
+}
+
+// Every centre whose composite key reaches the layer's threshold marks its window.
+__global__ __launch_bounds__(256) void k_mark(const LayerDev *__restrict__ layers,
+                                              const DirEntry *__restrict__ chunk_dir,
+                                              uint32_t n_layers, SelState *__restrict__ state,
+                                              const uint32_t *__restrict__ keys,
+                                              uint32_t *__restrict__ mask,
+                                              uint32_t *__restrict__ cmask) {
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const LayerDev L = layers[l];
+    if (L.k == 0) return;
+    const unsigned long long T = state[l].T;
+    const uint32_t start = (c - L.chunk_begin) * kChunk;
+    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+    const uint32_t *__restrict__ src = keys + L.elem_off + start;
+    const int h = (static_cast<int>(L.p) - 1) / 2;
+    const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
+    uint32_t n_sel = 0;
+#pragma unroll 2
+    for (int j = 0; j < kChunk / 1024; ++j) {
+        const uint32_t e = j * 1024 + 4 * tid;
+        if (e >= len) break;
+        uint32_t kk[4] = {0, 0, 0, 0};
+        if (e + 3 < len) {
+            const uint4 q = *reinterpret_cast<const uint4 *>(src + e);
+            kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
+        } else {
+            for (uint32_t q = 0; q < 4 && e + q < len; ++q) kk[q] = src[e + q];
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            const uint32_t i = start + e + q;
+            if (e + q < len && composite_key(kk[q], i) >= T) {
+                ++n_sel;
+                const int xc = static_cast<int>(i / L.C);
+                const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * L.C);
+                const int ylo = max(0, yc - h), yhi = min(C - 1, yc + h);
+                for (int x = max(0, xc - h); x <= min(R - 1, xc + h); ++x)
+                    set_bits(mask, static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + ylo,
+                             static_cast<uint32_t>(yhi - ylo + 1));
+                if (cmask) {
+                    const size_t pos = static_cast<size_t>(L.elem_off) + i;
+                    atomicOr(&cmask[pos >> 5], 1u << (pos & 31));
+                }
+            }
+        }
+    }
+    // wave-level sum, one atomic per wave
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) n_sel += __shfl_down(n_sel, d, 64);
+    if ((tid & 63) == 0 && n_sel) atomicAdd(&state[l].n_centres, n_sel);
+}
+
+// ---------------------------------------------------------------- count --
+__global__ __launch_bounds__(256) void k_count(const LayerDev *__restrict__ layers,
+                                               const DirEntry *__restrict__ chunk_dir,
+                                               uint32_t n_layers,
+                                               const uint32_t *__restrict__ mask,
+                                               const uint32_t *__restrict__ cmask,
+                                               uint32_t *__restrict__ chunk_cnt,
+                                               uint32_t *__restrict__ chunk_ccnt) {
+    __shared__ uint32_t wave_tot[4];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const LayerDev L = layers[l];
+    const uint32_t start = (c - L.chunk_begin) * kChunk;
+    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+    const size_t w0 = (static_cast<size_t>(L.elem_off) + start) >> 5;
+    const uint32_t nwords = (len + 31) >> 5;
+    const uint32_t a = static_cast<uint32_t>(tid) < nwords ? __popc(mask[w0 + tid]) : 0;
+    const uint32_t sa = block_scan_incl(a, wave_tot);
+    if (tid == 255) chunk_cnt[c] = sa;
+    if (cmask) {
+        const uint32_t b = static_cast<uint32_t>(tid) < nwords ? __popc(cmask[w0 + tid]) : 0;
+        const uint32_t sb = block_scan_incl(b, wave_tot);
+        if (tid == 255) chunk_ccnt[c] = sb;
+    }
+}
+
+// ----------------------------------------------------------------- scan --
+// One workgroup per layer: exclusive prefix of the per-chunk counts, totals out.
+__global__ __launch_bounds__(256) void k_scan(const LayerDev *__restrict__ layers,
+                                              SelState *__restrict__ state,
+                                              uint32_t *__restrict__ chunk_cnt,
+                                              uint32_t *__restrict__ chunk_ccnt,
+                                              int32_t *__restrict__ out_counts,
+                                              int32_t *__restrict__ out_centre_counts,
+                                              int with_centres) {
+    __shared__ uint32_t wave_tot[4];
+    const int l = blockIdx.x, tid = threadIdx.x;
+    const LayerDev L = layers[l];
+    const uint32_t n = L.n_chunks, per = (n + 255) / 256;
+    const uint32_t lo = min(n, tid * per), hi = min(n, lo + per);
+    for (int pass = 0; pass < (with_centres ? 2 : 1); ++pass) {
+        uint32_t *__restrict__ a = (pass == 0 ? chunk_cnt : chunk_ccnt) + L.chunk_begin;
+        uint32_t own = 0;
+        for (uint32_t i = lo; i < hi; ++i) own += a[i];
+        const uint32_t incl = block_scan_incl(own, wave_tot);
+        uint32_t run = incl - own;
+        for (uint32_t i = lo; i < hi; ++i) {
+            const uint32_t v = a[i];
+            a[i] = run;
+            run += v;
+        }
+        if (tid == 255 && pass == 0) {
+            out_counts[l] = static_cast<int32_t>(incl);
+            state[l].n_pairs = incl;
+        }
+    }
+    if (tid == 0 && out_centre_counts) out_centre_counts[l] = static_cast<int32_t>(state[l].n_centres);
+}
+
+// ----------------------------------------------------------------- emit --
+// Streams g and r once more: v = r + g; kept elements go out in ascending index order at
+// the position given by the chunk prefix plus the popcount of the mask bits before them;
+// the residual becomes +0 where kept and v elsewhere.
+__global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layers,
+                                              const DirEntry *__restrict__ chunk_dir,
+                                              uint32_t n_layers, const float *__restrict__ grad,
+                                              float *__restrict__ resid,
+                                              const uint32_t *__restrict__ mask,
+                                              const uint32_t *__restrict__ chunk_base,
+                                              uint32_t *__restrict__ out_idx,
+                                              float *__restrict__ out_val) {
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t s_word[256];
+    __shared__ uint32_t s_pref[256];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const LayerDev L = layers[l];
+    const uint32_t start = (c - L.chunk_begin) * kChunk;
+    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+    const size_t base = static_cast<size_t>(L.elem_off) + start;
+    const uint32_t nwords = (len + 31) >> 5;
+    const uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(base >> 5) + tid] : 0;
+    const uint32_t cnt = __popc(word);
+    s_word[tid] = word;
+    const uint32_t incl = block_scan_incl(cnt, wave_tot);
+    s_pref[tid] = incl - cnt;
+    __syncthreads();
+    const float *__restrict__ g = grad + base;
+    float *__restrict__ r = resid + base;
+    const size_t obase = static_cast<size_t>(L.out_off) + chunk_base[c];
+#pragma unroll 2
+    for (int j = 0; j < kChunk / 1024; ++j) {
+        const uint32_t e = j * 1024 + 4 * tid;
+        if (e >= len) break;
+        const uint32_t w = s_word[e >> 5];
+        const uint32_t sh = e & 31;
+        const uint32_t bits = (w >> sh) & 0xfu;
+        if (e + 3 < len) {
+            const float4 gv = *reinterpret_cast<const float4 *>(g + e);
+            const float4 rv = *reinterpret_cast<const float4 *>(r + e);
+            float v[4] = {rv.x + gv.x, rv.y + gv.y, rv.z + gv.z, rv.w + gv.w};
+            if (bits) {
+                uint32_t pos = s_pref[e >> 5] + __popc(w & ((1u << sh) - 1u));
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (bits & (1u << q)) {
+                        out_idx[obase + pos] = start + e + q;
+                        out_val[obase + pos] = v[q];
+                        ++pos;
+                        v[q] = 0.f;
+                    }
+            }
+            *reinterpret_cast<float4 *>(r + e) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+            uint32_t pos = s_pref[e >> 5] + __popc(w & ((1u << sh) - 1u));
+            for (uint32_t q = 0; q < 4 && e + q < len; ++q) {
+                float v = r[e + q] + g[e + q];
+                if (bits & (1u << q)) {
+                    out_idx[obase + pos] = start + e + q;
+                    out_val[obase + pos] = v;
+                    ++pos;
+                    v = 0.f;
+                }
+                r[e + q] = v;
+            }
+        }
+    }
+}
+
+// Ascending list of the selected centres of every layer.
+__global__ __launch_bounds__(256) void k_emit_centres(const LayerDev *__restrict__ layers,
+                                                      const DirEntry *__restrict__ chunk_dir,
+                                                      uint32_t n_layers,
+                                                      const uint32_t *__restrict__ cmask,
+                                                      const uint32_t *__restrict__ chunk_cbase,
+                                                      uint32_t *__restrict__ out_centre_idx) {
+    __shared__ uint32_t wave_tot[4];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const LayerDev L = layers[l];
+    const uint32_t start = (c - L.chunk_begin) * kChunk;
+    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+    const size_t base = static_cast<size_t>(L.elem_off) + start;
+    const uint32_t nwords = (len + 31) >> 5;
+    uint32_t word = static_cast<uint32_t>(tid) < nwords ? cmask[(base >> 5) + tid] : 0;
+    const uint32_t cnt = __popc(word);
+    const uint32_t incl = block_scan_incl(cnt, wave_tot);
+    size_t pos = static_cast<size_t>(L.centre_off) + chunk_cbase[c] + (incl - cnt);
+    while (word) {
+        const int b = __ffs(word) - 1;
+        word &= word - 1;
+        out_centre_idx[pos++] = start + 32u * tid + b;
+    }
+}
+
+// ----------------------------------------------------------- decompress --
+__global__ __launch_bounds__(256) void k_zero_layers(const LayerDev *__restrict__ layers,
+                                                     const DirEntry *__restrict__ chunk_dir,
+                                                     uint32_t n_layers, float *__restrict__ dense) {
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const LayerDev L = layers[l];
+    const uint32_t start = (c - L.chunk_begin) * kChunk;
+    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+    float *__restrict__ d = dense + L.elem_off + start;
+    for (int j = 0; j < kChunk / 1024; ++j) {
+        const uint32_t e = j * 1024 + 4 * tid;
+        if (e >= len) break;
+        if (e + 3 < len) {
+            *reinterpret_cast<float4 *>(d + e) = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+            for (uint32_t q = 0; q < 4 && e + q < len; ++q) d[e + q] = 0.f;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_scatter(const LayerDev *__restrict__ layers, int n_layers,
+                                                 long long capacity,
+                                                 const uint32_t *__restrict__ idx,
+                                                 const float *__restrict__ val,
+                                                 const int32_t *__restrict__ counts,
+                                                 float *__restrict__ dense, int accumulate) {
+    const long long j = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+    if (j >= capacity) return;
+    int lo = 0, hi = n_layers;            // last layer whose segment starts at or before j
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (layers[mid].out_off <= j) lo = mid; else hi = mid;
+    }
+    const LayerDev L = layers[lo];
+    const long long q = j - L.out_off;
+    if (q >= counts[lo] || q >= static_cast<long long>(L.cap)) return;
+    const uint32_t i = idx[j];
+    if (i >= L.G) return;                 // malformed message: ignore the pair
+    float *d = dense + L.elem_off + i;
+    if (accumulate) *d = *d + val[j]; else *d = val[j];
+}
+
+// ------------------------------------------------------------ host side --
+int upload_tables(rsdgc_plan_s *plan, void *workspace, hipStream_t stream) {
+    if (plan->uploaded_ws == workspace && plan->uploaded_version == plan->version) return RSDGC_OK;
+    HIP_TRY(hipMemcpyAsync(workspace, plan->table.data(), plan->ws.table_bytes,
+                           hipMemcpyHostToDevice, stream));
+    plan->uploaded_ws = workspace;
+    plan->uploaded_version = plan->version;
+    return RSDGC_OK;
+}
+
+template <bool HIST>
+int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const float *resid,
+               float *nsi_out, hipStream_t stream) {
+    const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
+    const DirEntry *tile_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.tile_dir);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(ws + plan->ws.hist);
+    for (const PGroup &g : plan->groups) {
+        const DirEntry *dir = tile_dir + g.dir_begin;
+        const dim3 grid(g.n_tiles), block(256);
+        switch (g.p) {
+#define RSDGC_NSI_CASE(PP)                                                                   \
+    case PP:                                                                                 \
+        hipLaunchKernelGGL((k_nsi<PP, HIST>), grid, block, 0, stream, layers, dir, g.dir_count, \
+                           g.n_tiles, grad, resid, nsi_out, hist, plan->alpha);              \
+        break;
+            RSDGC_NSI_CASE(1)
+            RSDGC_NSI_CASE(3)
+            RSDGC_NSI_CASE(5)
+            RSDGC_NSI_CASE(7)
+#undef RSDGC_NSI_CASE
+            default: return RSDGC_EINVAL;
+        }
+        HIP_TRY(hipGetLastError());
+    }
+    return RSDGC_OK;
+}
+
+bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *rsdgc_last_hip_error(void) { return g_hip_error; }
+
+int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint32_t *out_idx,
+                   float *out_val, int32_t *out_counts, uint32_t *out_centre_idx,
+                   int32_t *out_centre_counts, void *workspace, void *stream_) {
+    if (!plan || !grad || !residual || !out_idx || !out_val || !out_counts || !workspace)
+        return RSDGC_EINVAL;
+    if (!aligned256(workspace) || !aligned16(grad) || !aligned16(residual)) return RSDGC_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    char *ws = static_cast<char *>(workspace);
+    const WsLayout &w = plan->ws;
+    const int L = plan->n_layers;
+    const uint32_t n_chunks = plan->n_chunks;
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+
+    const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + w.layers);
+    const DirEntry *chunk_dir = reinterpret_cast<const DirEntry *>(ws + w.chunk_dir);
+    SelState *state = reinterpret_cast<SelState *>(ws + w.state);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(ws + w.hist);
+    uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
+    uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
+    uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
+    uint32_t *cmask = out_centre_idx ? reinterpret_cast<uint32_t *>(ws + w.cmask) : nullptr;
+    float *nsi = reinterpret_cast<float *>(ws + w.nsi);
+
+    // clear: state .. mask (and the centre mask only when it is used)
+    {
+        const size_t end = out_centre_idx ? w.zero_end : w.cmask;
+        const size_t n16 = (end - w.zero_begin) / 16;
+        const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
+        hipLaunchKernelGGL(k_clear, dim3(blocks), dim3(256), 0, stream,
+                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16);
+        hipLaunchKernelGGL(k_init_state, dim3((L + 63) / 64), dim3(64), 0, stream, layers, state, L);
+        HIP_TRY(hipGetLastError());
+    }
+    rc = launch_nsi<true>(plan, ws, grad, residual, nsi, stream);
+    if (rc != RSDGC_OK) return rc;
+
+    hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(0),
+                       level_bits(0));
+    for (int lv = 1; lv < kLevels; ++lv) {
+        hipLaunchKernelGGL(k_refine, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
+                           static_cast<uint32_t>(L), state, hist,
+                           reinterpret_cast<const uint32_t *>(nsi), level_shift(lv), level_bits(lv),
+                           level_shift(lv - 1));
+        hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(lv),
+                           level_bits(lv));
+    }
+    HIP_TRY(hipGetLastError());
+
+    hipLaunchKernelGGL(k_mark, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
+                       static_cast<uint32_t>(L), state, reinterpret_cast<const uint32_t *>(nsi),
+                       mask, cmask);
+    hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
+                       static_cast<uint32_t>(L), mask, cmask, chunk_cnt, chunk_ccnt);
+    hipLaunchKernelGGL(k_scan, dim3(L), dim3(256), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
+                       out_counts, out_centre_counts, cmask ? 1 : 0);
+    hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
+                       static_cast<uint32_t>(L), grad, residual, mask, chunk_cnt, out_idx, out_val);
+    if (cmask)
+        hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
+                           static_cast<uint32_t>(L), cmask, chunk_ccnt, out_centre_idx);
+    HIP_TRY(hipGetLastError());
+    return RSDGC_OK;
+}
+
+int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual, float *nsi_out,
+              void *workspace, void *stream_) {
+    if (!plan || !grad || !nsi_out || !workspace) return RSDGC_EINVAL;
+    if (!aligned256(workspace) || !aligned16(grad) || !aligned16(nsi_out) ||
+        (residual && !aligned16(residual)))
+        return RSDGC_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+    return launch_nsi<false>(plan, static_cast<char *>(workspace), grad, residual, nsi_out, stream);
+}
+
+int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
+                     const int32_t *counts, float *dense, int accumulate, void *workspace,
+                     void *stream_) {
+    if (!plan || !idx || !val || !counts || !dense || !workspace) return RSDGC_EINVAL;
+    if (!aligned256(workspace) || !aligned16(dense)) return RSDGC_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    char *ws = static_cast<char *>(workspace);
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+    const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
+    const DirEntry *chunk_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.chunk_dir);
+    if (!accumulate)
+        hipLaunchKernelGGL(k_zero_layers, dim3(plan->n_chunks), dim3(256), 0, stream, layers,
+                           chunk_dir, static_cast<uint32_t>(plan->n_layers), dense);
+    if (plan->out_capacity > 0) {
+        const unsigned blocks = static_cast<unsigned>((plan->out_capacity + 255) / 256);
+        hipLaunchKernelGGL(k_scatter, dim3(blocks), dim3(256), 0, stream, layers, plan->n_layers,
+                           static_cast<long long>(plan->out_capacity), idx, val, counts, dense,
+                           accumulate);
+    }
+    HIP_TRY(hipGetLastError());
+    return RSDGC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,207 @@
+// Host side of the C ABI: plan construction, validation, queries.
+// No HIP call happens in this file.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "rsdgc_internal.h"
+
+namespace rsdgc {
+
+// Eq. 11: k = ceil((G / p^2) * rho), evaluated in double in that order,
+// clamped to [0, G].
+int64_t keep_count(int64_t G, int p, double rho) {
+    const double per_window = static_cast<double>(G) / static_cast<double>(int64_t(p) * int64_t(p));
+    const double kf = std::ceil(per_window * rho);
+    if (!(kf > 0.0)) return 0;
+    if (kf > static_cast<double>(G)) return G;
+    return static_cast<int64_t>(kf);
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int build_tables(rsdgc_plan_s *plan) {
+    const int L = plan->n_layers;
+    plan->layers.assign(L, LayerDev{});
+    plan->groups.clear();
+    plan->tile_dir.clear();
+    plan->chunk_dir.clear();
+
+    int64_t elem_off = 0, out_off = 0, centre_off = 0;
+    uint32_t chunk_begin = 0;
+    for (int l = 0; l < L; ++l) {
+        LayerDev &d = plan->layers[l];
+        const int64_t R = plan->shapes[l].rows, C = plan->shapes[l].cols, G = R * C;
+        const int p = plan->p[l];
+        const int64_t k = keep_count(G, p, plan->ratio[l]);
+        int64_t cap = k * p * p;
+        if (cap > G) cap = G;
+        d.elem_off = elem_off;
+        d.out_off = out_off;
+        d.centre_off = centre_off;
+        d.R = static_cast<uint32_t>(R);
+        d.C = static_cast<uint32_t>(C);
+        d.G = static_cast<uint32_t>(G);
+        d.k = static_cast<uint32_t>(k);
+        d.p = static_cast<uint32_t>(p);
+        d.tiles_x = static_cast<uint32_t>((C + kTileCols - 1) / kTileCols);
+        d.n_tiles = d.tiles_x * static_cast<uint32_t>((R + kTileRows - 1) / kTileRows);
+        d.chunk_begin = chunk_begin;
+        d.n_chunks = static_cast<uint32_t>((G + kChunk - 1) / kChunk);
+        d.cap = static_cast<uint32_t>(cap);
+        plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(l)});
+        chunk_begin += d.n_chunks;
+        elem_off += (G + kLayerAlign - 1) / kLayerAlign * kLayerAlign;
+        out_off += cap;
+        centre_off += k;
+    }
+    plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(L)});
+    plan->n_chunks = chunk_begin;
+    plan->total_elems = elem_off;
+    plan->out_capacity = out_off;
+    plan->centre_capacity = centre_off;
+
+    // one NSI launch per distinct neighbourhood side
+    for (int p = 1; p <= RSDGC_MAX_P; p += 2) {
+        PGroup g;
+        g.p = p;
+        g.dir_begin = static_cast<uint32_t>(plan->tile_dir.size());
+        for (int l = 0; l < L; ++l) {
+            if (plan->p[l] != p) continue;
+            plan->layers[l].tile_begin = g.n_tiles;
+            plan->tile_dir.push_back(DirEntry{g.n_tiles, static_cast<uint32_t>(l)});
+            g.n_tiles += plan->layers[l].n_tiles;
+            ++g.dir_count;
+        }
+        if (g.dir_count == 0) continue;
+        plan->tile_dir.push_back(DirEntry{g.n_tiles, static_cast<uint32_t>(L)});  // sentinel
+        plan->groups.push_back(g);
+    }
+
+    // workspace layout
+    WsLayout &w = plan->ws;
+    const size_t A = 256;
+    const size_t words = static_cast<size_t>(plan->total_elems / 32);
+    size_t off = 0;
+    w.layers = off;      off = align_up(off + sizeof(LayerDev) * L, A);
+    w.tile_dir = off;    off = align_up(off + sizeof(DirEntry) * plan->tile_dir.size(), A);
+    w.chunk_dir = off;   off = align_up(off + sizeof(DirEntry) * plan->chunk_dir.size(), A);
+    w.table_bytes = off;
+    w.zero_begin = off;
+    w.state = off;       off = align_up(off + sizeof(SelState) * L, A);
+    w.hist = off;        off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
+    w.chunk_cnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.chunk_ccnt = off;  off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.mask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
+    w.cmask = off;       off = align_up(off + sizeof(uint32_t) * words, A);
+    w.zero_end = off;
+    w.nsi = off;         off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
+    w.total = off;
+
+    plan->table.assign(w.table_bytes, 0);
+    std::memcpy(plan->table.data() + w.layers, plan->layers.data(), sizeof(LayerDev) * L);
+    std::memcpy(plan->table.data() + w.tile_dir, plan->tile_dir.data(),
+                sizeof(DirEntry) * plan->tile_dir.size());
+    std::memcpy(plan->table.data() + w.chunk_dir, plan->chunk_dir.data(),
+                sizeof(DirEntry) * plan->chunk_dir.size());
+    ++plan->version;
+    return RSDGC_OK;
+}
+
+static bool ratio_ok(double r) { return r >= 0.0 && r <= 1.0; }  // false for NaN
+
+}  // namespace rsdgc
+
+using namespace rsdgc;
+
+extern "C" {
+
+int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
+               const int32_t *p_per_layer, double alpha, const double *keep_ratio,
+               rsdgc_plan_t **out_plan) {
+    if (!shapes || !keep_ratio || !out_plan || n_layers < 1) return RSDGC_EINVAL;
+    *out_plan = nullptr;
+    if (!(alpha >= 0.0 && alpha <= 1.0)) return RSDGC_EINVAL;
+    int64_t total = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int pl = p_per_layer ? p_per_layer[l] : p;
+        if (pl < 1 || pl > RSDGC_MAX_P || pl % 2 == 0) return RSDGC_EINVAL;
+        const int64_t R = shapes[l].rows, C = shapes[l].cols;
+        if (R < 1 || C < 1 || R > 0x7fffffffLL || C > 0x7fffffffLL) return RSDGC_EINVAL;
+        if (R > 0xffffffffLL / C) return RSDGC_EINVAL;            // G_l must fit uint32
+        if (!ratio_ok(keep_ratio[l])) return RSDGC_EINVAL;
+        total += R * C + kLayerAlign;
+        if (total > (int64_t(1) << 40)) return RSDGC_EINVAL;
+    }
+    if ((total + kChunk - 1) / kChunk + n_layers > 0x7fffffffLL) return RSDGC_EINVAL;
+    rsdgc_plan_s *plan = new (std::nothrow) rsdgc_plan_s;
+    if (!plan) return RSDGC_ENOMEM;
+    try {
+        plan->n_layers = n_layers;
+        plan->alpha = alpha;
+        plan->shapes.assign(shapes, shapes + n_layers);
+        plan->p.resize(n_layers);
+        for (int l = 0; l < n_layers; ++l) plan->p[l] = p_per_layer ? p_per_layer[l] : p;
+        plan->ratio.assign(keep_ratio, keep_ratio + n_layers);
+        build_tables(plan);
+    } catch (const std::bad_alloc &) {
+        delete plan;
+        return RSDGC_ENOMEM;
+    }
+    *out_plan = plan;
+    return RSDGC_OK;
+}
+
+int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio) {
+    if (!plan || !keep_ratio) return RSDGC_EINVAL;
+    for (int l = 0; l < plan->n_layers; ++l)
+        if (!ratio_ok(keep_ratio[l])) return RSDGC_EINVAL;
+    try {
+        plan->ratio.assign(keep_ratio, keep_ratio + plan->n_layers);
+        build_tables(plan);
+    } catch (const std::bad_alloc &) {
+        return RSDGC_ENOMEM;
+    }
+    return RSDGC_OK;
+}
+
+void rsdgc_plan_destroy(rsdgc_plan_t *plan) { delete plan; }
+
+int32_t rsdgc_n_layers(const rsdgc_plan_t *plan) { return plan ? plan->n_layers : -1; }
+int64_t rsdgc_total_elems(const rsdgc_plan_t *plan) { return plan ? plan->total_elems : -1; }
+
+static bool layer_ok(const rsdgc_plan_t *plan, int32_t l) {
+    return plan && l >= 0 && l < plan->n_layers;
+}
+int64_t rsdgc_layer_offset(const rsdgc_plan_t *plan, int32_t l) {
+    return layer_ok(plan, l) ? plan->layers[l].elem_off : -1;
+}
+int64_t rsdgc_layer_elems(const rsdgc_plan_t *plan, int32_t l) {
+    return layer_ok(plan, l) ? int64_t(plan->layers[l].G) : -1;
+}
+int64_t rsdgc_layer_k(const rsdgc_plan_t *plan, int32_t l) {
+    return layer_ok(plan, l) ? int64_t(plan->layers[l].k) : -1;
+}
+int64_t rsdgc_out_offset(const rsdgc_plan_t *plan, int32_t l) {
+    return layer_ok(plan, l) ? plan->layers[l].out_off : -1;
+}
+int64_t rsdgc_out_capacity(const rsdgc_plan_t *plan) { return plan ? plan->out_capacity : -1; }
+int64_t rsdgc_centre_offset(const rsdgc_plan_t *plan, int32_t l) {
+    return layer_ok(plan, l) ? plan->layers[l].centre_off : -1;
+}
+int64_t rsdgc_centre_capacity(const rsdgc_plan_t *plan) {
+    return plan ? plan->centre_capacity : -1;
+}
+size_t rsdgc_workspace_bytes(const rsdgc_plan_t *plan) { return plan ? plan->ws.total : 0; }
+
+const char *rsdgc_strerror(int code) {
+    switch (code) {
+        case RSDGC_OK: return "ok";
+        case RSDGC_EINVAL: return "invalid argument";
+        case RSDGC_ENOMEM: return "host allocation failed";
+        case RSDGC_EHIP: return "HIP call failed";
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

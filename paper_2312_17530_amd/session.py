@@ -1,0 +1,91 @@
+"""Device-memory plumbing around the binding: one object that owns the torch buffers a
+plan needs (arenas, outputs, workspace) and moves host arrays in and out of them.
+No arithmetic of the method happens here."""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding
+
+
+class Session:
+    def __init__(self, shapes, p: int, alpha: float, ratios: Sequence[float],
+                 p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0",
+                 want_centres: bool = True):
+        self.shapes = [(int(r), int(c)) for r, c in shapes]
+        self.plan = binding.rsdgc_plan(self.shapes, p, alpha, ratios, p_per_layer)
+        self.device = torch.device(device)
+        n = self.plan.total_elems
+        L = self.plan.n_layers
+        dev = self.device
+        self.grad = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.residual = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.out_idx = torch.zeros(max(1, self.plan.out_capacity), dtype=torch.int32, device=dev)
+        self.out_val = torch.zeros(max(1, self.plan.out_capacity), dtype=torch.float32, device=dev)
+        self.out_counts = torch.zeros(L, dtype=torch.int32, device=dev)
+        self.want_centres = want_centres
+        self.out_centre_idx = (torch.zeros(max(1, self.plan.centre_capacity), dtype=torch.int32,
+                                           device=dev) if want_centres else None)
+        self.out_centre_counts = torch.zeros(L, dtype=torch.int32, device=dev)
+        self.workspace = torch.zeros(self.plan.workspace_bytes, dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.offsets = [self.plan.layer_offset(l) for l in range(L)]
+        self.sizes = [self.plan.layer_elems(l) for l in range(L)]
+
+    # ---- host <-> arena
+    def pack(self, arrays: Sequence[np.ndarray], arena: torch.Tensor) -> None:
+        host = np.zeros(self.plan.total_elems, dtype=np.float32)
+        for a, off, sz in zip(arrays, self.offsets, self.sizes):
+            host[off:off + sz] = np.asarray(a, dtype=np.float32).reshape(-1)
+        arena.copy_(torch.from_numpy(host))
+
+    def unpack(self, arena: torch.Tensor) -> List[np.ndarray]:
+        host = arena.cpu().numpy()
+        return [host[off:off + sz].reshape(sh).copy()
+                for off, sz, sh in zip(self.offsets, self.sizes, self.shapes)]
+
+    def set_grad(self, arrays):
+        self.pack(arrays, self.grad)
+
+    def set_residual(self, arrays):
+        self.pack(arrays, self.residual)
+
+    # ---- calls
+    def compress(self, stream=None) -> None:
+        binding.rsdgc_compress(self.plan, self.grad, self.residual, self.out_idx, self.out_val,
+                               self.out_counts, self.workspace, self.out_centre_idx,
+                               self.out_centre_counts, stream)
+
+    def nsi(self, use_residual: bool = True) -> List[np.ndarray]:
+        out = torch.zeros_like(self.grad)
+        binding.rsdgc_nsi(self.plan, self.grad, self.residual if use_residual else None, out,
+                          self.workspace)
+        torch.cuda.synchronize()
+        return self.unpack(out)
+
+    def decompress(self, accumulate: bool = False, dense: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if dense is None:
+            dense = torch.full_like(self.grad, 7.0)   # non-zero: overwrite mode must clear it
+        binding.rsdgc_decompress(self.plan, self.out_idx, self.out_val, self.out_counts, dense,
+                                 accumulate, self.workspace)
+        return dense
+
+    # ---- results on the host
+    def results(self):
+        """Per layer: (idx uint32, val float32, centres uint32, n_centres)."""
+        torch.cuda.synchronize()
+        counts = self.out_counts.cpu().numpy()
+        ccounts = self.out_centre_counts.cpu().numpy()
+        idx = self.out_idx.cpu().numpy().view(np.uint32)
+        val = self.out_val.cpu().numpy()
+        cidx = self.out_centre_idx.cpu().numpy().view(np.uint32) if self.want_centres else None
+        out = []
+        for l in range(self.plan.n_layers):
+            o, n = self.plan.out_offset(l), int(counts[l])
+            co, k = self.plan.centre_offset(l), self.plan.layer_k(l)
+            out.append((idx[o:o + n].copy(), val[o:o + n].copy(),
+                        cidx[co:co + k].copy() if cidx is not None else None, int(ccounts[l])))
+        return out

@@ -1,0 +1,168 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Needs a real MI355X."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2312_17530_amd import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _session(shapes, p, alpha, ratios, p_per_layer=None):
+    from paper_2312_17530_amd.session import Session
+    return Session(shapes, p, alpha, ratios, p_per_layer)
+
+
+def run_and_check(shapes, p_list, alpha, ratios, grads_per_iter, name="case", check_nsi=True):
+    """Runs every iteration on GPU and oracle from identical state and applies the parity rule.
+    Returns (number of layer-iterations compared, number that matched the oracle exactly)."""
+    import torch
+    sess = _session(shapes, p_list[0], alpha, ratios, p_list)
+    L = len(shapes)
+    resid = [np.zeros(sh, dtype=np.float32) for sh in shapes]
+    n_cmp = n_exact = 0
+    for t, grads in enumerate(grads_per_iter):
+        sess.set_grad(grads)
+        sess.set_residual(resid)
+        if check_nsi:
+            gpu_nsi = sess.nsi(use_residual=True)
+        sess.compress()
+        torch.cuda.synchronize()
+        res = sess.results()
+        gpu_r = sess.unpack(sess.residual)
+        dense = sess.unpack(sess.decompress(accumulate=False))
+        new_resid = []
+        for l in range(L):
+            o = oracle.compress_layer(grads[l], resid[l], p_list[l], alpha, ratios[l])
+            tag = f"{name}[t={t},l={l},{shapes[l]},p={p_list[l]}]"
+            assert sess.plan.layer_k(l) == o.k, tag
+            if check_nsi:
+                ok = parity.nsi_close(gpu_nsi[l], o.nsi, o.v, p_list[l])
+                assert ok.all(), f"{tag}: {int((~ok).sum())} scores outside tolerance"
+            gi, gv, gc, gn = res[l]
+            exact = parity.check_layer(tag, shapes[l], p_list[l], o.k, o.tau, o.nsi, o.centres,
+                                       o.idx, o.val, o.r_new, o.v, gi, gv, gc, gn, gpu_r[l])
+            # decompress(accumulate=0) + residual == v, bitwise
+            d = dense[l].reshape(-1)
+            want = np.zeros(d.size, dtype=np.float32)
+            want[gi] = gv
+            assert np.array_equal(d.view(np.uint32), want.view(np.uint32)), f"{tag}: decompress"
+            n_cmp += 1
+            n_exact += int(exact)
+            # continue from the oracle's state (identical unless the tolerance band was used)
+            new_resid.append(o.r_new)
+        resid = new_resid
+    return n_cmp, n_exact
+
+
+def test_config0_single_layer_512():
+    w = synth.config(0)
+    n, ex = run_and_check(w.shapes, [w.p], w.alpha, w.ratios, [synth.gradients(w, 0)], w.name)
+    assert n == 1 and ex == 1
+
+
+RAGGED = [(1, 1), (1, 40), (40, 1), (2, 2), (33, 129), (45, 61), (64, 27), (200, 45), (31, 257),
+          (100, 300), (32, 128), (64, 256), (65, 130), (7, 1000)]
+
+
+@pytest.mark.parametrize("alpha", [0.5, 0.0, 1.0, 0.25])
+def test_ragged_shapes_mixed_p_two_iterations(alpha):
+    rng = np.random.default_rng(int(alpha * 100) + 7)
+    shapes = RAGGED
+    p_list = [1, 3, 5, 7, 3, 5, 3, 3, 7, 5, 3, 1, 3, 5]
+    ratios = [1.0, 0.1, 0.1, 1.0, 0.02, 0.05, 0.02, 0.01, 0.3, 0.001, 0.5, 0.07, 0.0, 1.0]
+    its = []
+    for t in range(2):
+        its.append([synth.layer_gradient(sh, 1e-3 * (l + 1), 11, t, l) for l, sh in enumerate(shapes)])
+    n, ex = run_and_check(shapes, p_list, alpha, ratios, its, "ragged")
+    assert n == 2 * len(shapes)
+    assert ex >= n - 2          # the tolerance band is allowed, but should hardly ever be needed
+
+
+def test_degenerate_inputs_follow_index_tie_break():
+    shapes = [(40, 70), (64, 128), (50, 50), (33, 40), (16, 300), (90, 45)]
+    zeros = np.zeros(shapes[0], dtype=np.float32)
+    const = np.full(shapes[1], -0.375, dtype=np.float32)
+    impulse = np.zeros(shapes[2], dtype=np.float32)
+    impulse[20, 31] = 3.0
+    impulse[5, 5] = -3.0
+    xs, ys = np.meshgrid(np.arange(33), np.arange(40), indexing="ij")
+    checker = np.where((xs + ys) % 2 == 0, 0.5, -0.5).astype(np.float32)
+    rng = np.random.default_rng(99)
+    ints = rng.integers(-3, 4, size=shapes[4]).astype(np.float32)       # masses of exact ties
+    ramp = (np.arange(90 * 45, dtype=np.float32).reshape(90, 45) * np.float32(1e-3) + np.float32(5.0))
+    grads = [zeros, const, impulse, checker, ints, ramp]
+    for p, alpha in [(3, 0.5), (5, 0.5), (3, 1.0), (3, 0.0), (1, 1.0)]:
+        ratios = [0.3, 0.2, 0.05, 0.1, 0.15, 0.25]
+        n, ex = run_and_check(shapes, [p] * len(shapes), alpha, ratios, [grads, grads],
+                              f"degenerate(p={p},alpha={alpha})")
+        assert ex == n, "exact ties must resolve exactly like the oracle (lower index wins)"
+
+
+def test_config1_resnet18_two_iterations():
+    w = synth.config(1)
+    its = [synth.gradients(w, t) for t in range(w.iterations)]
+    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name)
+    assert n == 2 * w.n_layers
+    assert ex >= n - 2
+
+
+def test_config2_resnet50_dynamic_ratios():
+    w = synth.config(2)
+    its = [synth.gradients(w, 0)]
+    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name)
+    assert n == w.n_layers
+    assert ex >= n - 2
+
+
+def test_set_ratios_and_determinism():
+    import torch
+    w = synth.scaled_down(synth.config(2), 256, 512)
+    grads = synth.gradients(w, 0)
+    sess = _session(w.shapes, w.p, w.alpha, w.ratios)
+    sess.set_grad(grads)
+    sess.compress()
+    a = [(i.copy(), v.copy()) for i, v, _, _ in sess.results()]
+    ra = sess.residual.clone()
+    sess.residual.zero_()
+    sess.compress()
+    b = sess.results()
+    for (ia, va), (ib, vb, _, _) in zip(a, b):
+        assert np.array_equal(ia, ib) and np.array_equal(va.view(np.uint32), vb.view(np.uint32))
+    assert torch.equal(ra, sess.residual)
+    # same plan, new ratios: same result as a fresh plan with those ratios
+    from paper_2312_17530_amd import binding
+    new = [min(1.0, r * 0.5) for r in w.ratios]
+    binding.rsdgc_plan_set_ratios(sess.plan, new)
+    fresh = _session(w.shapes, w.p, w.alpha, new)
+    assert sess.plan.out_capacity == fresh.plan.out_capacity
+    sess.residual.zero_()
+    fresh.set_grad(grads)
+    sess.compress()
+    fresh.compress()
+    for l, ((i1, v1, c1, n1), (i2, v2, c2, n2)) in enumerate(zip(sess.results(), fresh.results())):
+        assert n1 == n2 == fresh.plan.layer_k(l)
+        # out buffers of `sess` were sized for the larger ratios; offsets follow the new plan
+        assert np.array_equal(i1, i2) and np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
+        assert np.array_equal(c1, c2)
+
+
+def test_decompress_accumulate_sums_messages():
+    import torch
+    w = synth.config(0)
+    grads = synth.gradients(w, 0)
+    sess = _session(w.shapes, w.p, w.alpha, w.ratios)
+    sess.set_grad(grads)
+    sess.compress()
+    idx, val, _, _ = sess.results()[0]
+    dense = torch.full_like(sess.grad, 1.0)
+    sess.decompress(accumulate=True, dense=dense)
+    sess.decompress(accumulate=True, dense=dense)
+    torch.cuda.synchronize()
+    got = dense.cpu().numpy()
+    want = np.ones(got.size, dtype=np.float32)
+    want = oracle.decompress(idx, val, want.size, dense=want, accumulate_into=True)
+    want = oracle.decompress(idx, val, want.size, dense=want, accumulate_into=True)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
