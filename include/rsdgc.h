@@ -139,6 +139,18 @@ int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
                      const int32_t *counts, float *dense, int accumulate,
                      void *workspace, void *stream);
 
+/* ------------------------------------------------------------ profiling --
+ * Per-stage GPU time of rsdgc_compress, measured with HIP events recorded on the
+ * caller's stream between the stages.  rsdgc_profile_begin creates the events for up
+ * to max_calls calls (further calls are not recorded); rsdgc_profile_end waits for the
+ * recorded events, writes the mean milliseconds per call of each stage into
+ * stage_ms[RSDGC_N_STAGES] [host], the number of recorded calls into *n_calls [host],
+ * and destroys the events.  Stages: see rsdgc_stage_name.                        */
+#define RSDGC_N_STAGES 7
+int rsdgc_profile_begin(rsdgc_plan_t *plan, int32_t max_calls);
+int rsdgc_profile_end(rsdgc_plan_t *plan, double *stage_ms, int32_t *n_calls);
+const char *rsdgc_stage_name(int32_t stage);
+
 /* ----------------------------------------------------------- diagnostics */
 const char *rsdgc_strerror(int code);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */

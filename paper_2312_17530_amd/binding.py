@@ -22,8 +22,10 @@ EXPORTS = [
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
     "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_nsi", "rsdgc_decompress",
+    "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
 ]
+RSDGC_N_STAGES = 7
 
 
 class Shape(ctypes.Structure):
@@ -51,6 +53,10 @@ def load() -> ctypes.CDLL:
         raise RuntimeError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2312_17530_amd.build` "
             "(or __graft_entry__.build()); there is no fallback implementation")
+    # PyTorch ships its own HIP runtime; it has to be in the process before this library
+    # is loaded so that both resolve the same runtime (device pointers and streams are
+    # only meaningful inside the runtime that created them).
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
     lib.rsdgc_plan.argtypes = [ctypes.POINTER(Shape), i32, i32, ctypes.POINTER(i32), f64,
@@ -77,6 +83,12 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_nsi.restype = ctypes.c_int
     lib.rsdgc_decompress.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
     lib.rsdgc_decompress.restype = ctypes.c_int
+    lib.rsdgc_profile_begin.argtypes = [vp, i32]
+    lib.rsdgc_profile_begin.restype = ctypes.c_int
+    lib.rsdgc_profile_end.argtypes = [vp, ctypes.POINTER(f64), ctypes.POINTER(i32)]
+    lib.rsdgc_profile_end.restype = ctypes.c_int
+    lib.rsdgc_stage_name.argtypes = [i32]
+    lib.rsdgc_stage_name.restype = ctypes.c_char_p
     lib.rsdgc_strerror.argtypes = [ctypes.c_int]
     lib.rsdgc_strerror.restype = ctypes.c_char_p
     lib.rsdgc_last_hip_error.argtypes = []
@@ -198,3 +210,16 @@ def rsdgc_decompress(plan: Plan, idx, val, counts, dense, accumulate: bool, work
     _check(load().rsdgc_decompress(plan.handle, _ptr(idx), _ptr(val), _ptr(counts), _ptr(dense),
                                    1 if accumulate else 0, _ptr(workspace), _stream(stream)),
            "rsdgc_decompress")
+
+
+def rsdgc_profile_begin(plan: Plan, max_calls: int) -> None:
+    _check(load().rsdgc_profile_begin(plan.handle, int(max_calls)), "rsdgc_profile_begin")
+
+
+def rsdgc_profile_end(plan: Plan):
+    """Returns ({stage name: mean ms per call}, number of recorded calls)."""
+    lib = load()
+    ms = (ctypes.c_double * RSDGC_N_STAGES)()
+    n = ctypes.c_int32(0)
+    _check(lib.rsdgc_profile_end(plan.handle, ms, ctypes.byref(n)), "rsdgc_profile_end")
+    return {lib.rsdgc_stage_name(i).decode(): ms[i] for i in range(RSDGC_N_STAGES)}, n.value

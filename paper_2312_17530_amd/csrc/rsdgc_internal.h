@@ -90,6 +90,10 @@ struct rsdgc_plan_s {
     uint64_t version = 1;               // bumped by set_ratios
     const void *uploaded_ws = nullptr;
     uint64_t uploaded_version = 0;
+    // optional per-stage timing: (RSDGC_N_STAGES + 1) events per recorded call (hipEvent_t)
+    std::vector<void *> prof_events;
+    int prof_max_calls = 0;
+    int prof_calls = 0;
 };
 
 namespace rsdgc {

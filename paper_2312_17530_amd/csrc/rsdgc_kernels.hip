@@ -148,7 +148,6 @@ __global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers
     const float *__restrict__ r = resid ? resid + L.elem_off : nullptr;
 
     if (HIST) {
-#pragma unroll
         for (int b = tid; b < kHistBins; b += 256) lhist[b] = 0;
     }
 
@@ -266,7 +265,6 @@ __global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers
     if (HIST) {
         __syncthreads();
         uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins;
-#pragma unroll
         for (int b = tid; b < kHistBins; b += 256) {
             const uint32_t c = lhist[b];
             if (c) atomicAdd(&gh[b], c);
@@ -673,6 +671,24 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
     return RSDGC_OK;
 }
 
+// Records the event that closes `stage` (and opens the next) when profiling is on.
+struct StageMarks {
+    rsdgc_plan_s *plan;
+    hipStream_t stream;
+    int base;   // index of this call's first event, -1 when not recording
+    StageMarks(rsdgc_plan_s *p, hipStream_t s) : plan(p), stream(s), base(-1) {
+        if (!p->prof_events.empty() && p->prof_calls < p->prof_max_calls) {
+            base = p->prof_calls * (RSDGC_N_STAGES + 1);
+            ++p->prof_calls;
+            (void)hipEventRecord(static_cast<hipEvent_t>(p->prof_events[base]), s);
+        }
+    }
+    void close(int stage) {
+        if (base >= 0)
+            (void)hipEventRecord(static_cast<hipEvent_t>(plan->prof_events[base + stage + 1]), stream);
+    }
+};
+
 bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -706,6 +722,7 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     uint32_t *cmask = out_centre_idx ? reinterpret_cast<uint32_t *>(ws + w.cmask) : nullptr;
     float *nsi = reinterpret_cast<float *>(ws + w.nsi);
 
+    StageMarks marks(plan, stream);
     // clear: state .. mask (and the centre mask only when it is used)
     {
         const size_t end = out_centre_idx ? w.zero_end : w.cmask;
@@ -716,8 +733,10 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
         hipLaunchKernelGGL(k_init_state, dim3((L + 63) / 64), dim3(64), 0, stream, layers, state, L);
         HIP_TRY(hipGetLastError());
     }
+    marks.close(0);
     rc = launch_nsi<true>(plan, ws, grad, residual, nsi, stream);
     if (rc != RSDGC_OK) return rc;
+    marks.close(1);
 
     hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(0),
                        level_bits(0));
@@ -730,21 +749,84 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
                            level_bits(lv));
     }
     HIP_TRY(hipGetLastError());
+    marks.close(2);
 
     hipLaunchKernelGGL(k_mark, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                        static_cast<uint32_t>(L), state, reinterpret_cast<const uint32_t *>(nsi),
                        mask, cmask);
+    marks.close(3);
     hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                        static_cast<uint32_t>(L), mask, cmask, chunk_cnt, chunk_ccnt);
     hipLaunchKernelGGL(k_scan, dim3(L), dim3(256), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
                        out_counts, out_centre_counts, cmask ? 1 : 0);
+    marks.close(4);
     hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                        static_cast<uint32_t>(L), grad, residual, mask, chunk_cnt, out_idx, out_val);
+    marks.close(5);
     if (cmask)
         hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                            static_cast<uint32_t>(L), cmask, chunk_ccnt, out_centre_idx);
+    marks.close(6);
     HIP_TRY(hipGetLastError());
     return RSDGC_OK;
+}
+
+static void destroy_events(rsdgc_plan_s *plan) {
+    for (void *e : plan->prof_events) (void)hipEventDestroy(static_cast<hipEvent_t>(e));
+    plan->prof_events.clear();
+    plan->prof_max_calls = plan->prof_calls = 0;
+}
+
+int rsdgc_profile_begin(rsdgc_plan_t *plan, int32_t max_calls) {
+    if (!plan || max_calls < 1 || max_calls > 4096) return RSDGC_EINVAL;
+    destroy_events(plan);
+    const int n = max_calls * (RSDGC_N_STAGES + 1);
+    try {
+        plan->prof_events.reserve(n);
+    } catch (const std::bad_alloc &) {
+        return RSDGC_ENOMEM;
+    }
+    for (int i = 0; i < n; ++i) {
+        hipEvent_t e;
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) {
+            destroy_events(plan);
+            return hip_fail(err, "hipEventCreate");
+        }
+        plan->prof_events.push_back(e);
+    }
+    plan->prof_max_calls = max_calls;
+    plan->prof_calls = 0;
+    return RSDGC_OK;
+}
+
+int rsdgc_profile_end(rsdgc_plan_t *plan, double *stage_ms, int32_t *n_calls) {
+    if (!plan || !stage_ms || !n_calls) return RSDGC_EINVAL;
+    for (int s = 0; s < RSDGC_N_STAGES; ++s) stage_ms[s] = 0.0;
+    *n_calls = plan->prof_calls;
+    int rc = RSDGC_OK;
+    for (int c = 0; c < plan->prof_calls && rc == RSDGC_OK; ++c) {
+        const int base = c * (RSDGC_N_STAGES + 1);
+        hipError_t err = hipEventSynchronize(static_cast<hipEvent_t>(plan->prof_events[base + RSDGC_N_STAGES]));
+        if (err != hipSuccess) { rc = hip_fail(err, "hipEventSynchronize"); break; }
+        for (int s = 0; s < RSDGC_N_STAGES; ++s) {
+            float ms = 0.f;
+            err = hipEventElapsedTime(&ms, static_cast<hipEvent_t>(plan->prof_events[base + s]),
+                                      static_cast<hipEvent_t>(plan->prof_events[base + s + 1]));
+            if (err != hipSuccess) { rc = hip_fail(err, "hipEventElapsedTime"); break; }
+            stage_ms[s] += ms;
+        }
+    }
+    if (rc == RSDGC_OK && plan->prof_calls > 0)
+        for (int s = 0; s < RSDGC_N_STAGES; ++s) stage_ms[s] /= plan->prof_calls;
+    destroy_events(plan);
+    return rc;
+}
+
+const char *rsdgc_stage_name(int32_t stage) {
+    static const char *names[RSDGC_N_STAGES] = {"clear", "nsi", "select", "mark", "count_scan",
+                                                "emit", "centres"};
+    return (stage >= 0 && stage < RSDGC_N_STAGES) ? names[stage] : "";
 }
 
 int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual, float *nsi_out,

@@ -165,7 +165,14 @@ int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio) {
     return RSDGC_OK;
 }
 
-void rsdgc_plan_destroy(rsdgc_plan_t *plan) { delete plan; }
+void rsdgc_plan_destroy(rsdgc_plan_t *plan) {
+    if (plan) {
+        int32_t n = 0;
+        double ms[RSDGC_N_STAGES];
+        if (!plan->prof_events.empty()) rsdgc_profile_end(plan, ms, &n);   // releases the events
+        delete plan;
+    }
+}
 
 int32_t rsdgc_n_layers(const rsdgc_plan_t *plan) { return plan ? plan->n_layers : -1; }
 int64_t rsdgc_total_elems(const rsdgc_plan_t *plan) { return plan ? plan->total_elems : -1; }
