@@ -118,9 +118,11 @@ def main() -> int:
     ms_per_step = dt / args.steps * 1e3
     value = G * args.steps / dt
     counts = sess.out_counts.cpu().numpy()
-    ccounts = sess.out_centre_counts.cpu().numpy()
     ks = [sess.plan.layer_k(l) for l in range(w.n_layers)]
-    assert list(ccounts) == ks, "selected-centre counts differ from Eq. 11"
+    if args.centres:
+        ccounts = sess.out_centre_counts.cpu().numpy()
+        assert list(ccounts) == ks, "selected-centre counts differ from Eq. 11"
+    assert all(k <= c <= min(k * w.p * w.p, r * cc) for k, c, (r, cc) in zip(ks, counts, w.shapes))
     n_pairs = int(counts.sum())
 
     roofline = None

@@ -49,6 +49,7 @@ struct WsLayout {
     size_t layers = 0;      // LayerDev[n_layers]
     size_t tile_dir = 0;    // DirEntry[] per p-group, each closed by a sentinel
     size_t chunk_dir = 0;   // DirEntry[n_layers + 1]
+    size_t all_tile_dir = 0;// DirEntry[n_layers + 1]: tiles of all layers in layer order
     size_t state = 0;       // SelState[n_layers]
     size_t hist = 0;        // uint32[n_layers][kHistBins]
     size_t chunk_cnt = 0;   // uint32[n_chunks]  kept elements per chunk, then their prefix
@@ -80,6 +81,8 @@ struct rsdgc_plan_s {
     std::vector<rsdgc::PGroup> groups;
     std::vector<rsdgc::DirEntry> tile_dir;
     std::vector<rsdgc::DirEntry> chunk_dir;
+    std::vector<rsdgc::DirEntry> all_tile_dir;
+    uint32_t n_tiles_all = 0;
     int64_t total_elems = 0;
     int64_t out_capacity = 0;
     int64_t centre_capacity = 0;

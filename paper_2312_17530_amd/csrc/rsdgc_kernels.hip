@@ -370,66 +370,108 @@ __global__ __launch_bounds__(256) void k_refine(const LayerDev *__restrict__ lay
 }
 
 // ----------------------------------------------------------------- mark --
-__device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos, uint32_t nbits) {
+// OR a 64-bit group of mask bits that starts at bit position pos into a bitmask whose
+// words may be shared with other workgroups (rows that are not a multiple of 32 long).
+__device__ __forceinline__ void or_bits_shared(uint32_t *__restrict__ mask, size_t pos,
+                                               unsigned long long v) {
+    if (!v) return;
     const size_t w = pos >> 5;
     const uint32_t b = static_cast<uint32_t>(pos & 31);
-    const uint32_t bits = (1u << nbits) - 1u;          // nbits <= RSDGC_MAX_P
-    atomicOr(&mask[w], bits << b);
-    if (b + nbits > 32) atomicOr(&mask[w + 1], bits >> (32 - b));
+    const uint32_t p0 = static_cast<uint32_t>(v << b);
+    const uint32_t p1 = static_cast<uint32_t>(b ? (v >> (32 - b)) : (v >> 32));
+    const uint32_t p2 = b ? static_cast<uint32_t>(v >> (64 - b)) : 0u;
+    if (p0) atomicOr(&mask[w], p0);
+    if (p1) atomicOr(&mask[w + 1], p1);
+    if (p2) atomicOr(&mask[w + 2], p2);
 }
 
-// Every centre whose composite key reaches the layer's threshold marks its window.
+// One workgroup = one 32 x 128 tile (the NSI tiling).  Every centre of the tile and of a
+// halo of h rows / columns is compared with the layer's threshold; the per-row results
+// become 64-bit ballot words in LDS, the p x p box dilation (Section III-C: whole
+// neighbourhoods are kept) is done on those words with shifts and ORs, and the tile's
+// mask words are written with plain stores (rows that are a multiple of 32 long) -- no
+// global atomics on the common path.
 __global__ __launch_bounds__(256) void k_mark(const LayerDev *__restrict__ layers,
-                                              const DirEntry *__restrict__ chunk_dir,
-                                              uint32_t n_layers, SelState *__restrict__ state,
+                                              const DirEntry *__restrict__ dir, uint32_t n_layers,
+                                              uint32_t n_tiles, const SelState *__restrict__ state,
                                               const uint32_t *__restrict__ keys,
                                               uint32_t *__restrict__ mask,
                                               uint32_t *__restrict__ cmask) {
-    const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    constexpr int MAXH = (RSDGC_MAX_P - 1) / 2;
+    __shared__ unsigned long long bits[kTileRows + 2 * MAXH][4];   // [row][left, seg0, seg1, right]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t t_id = xcd_contiguous(blockIdx.x, n_tiles);
+    const uint32_t e = dir_lookup(dir, n_layers, t_id);
+    const uint32_t l = dir[e].layer;
     const LayerDev L = layers[l];
-    if (L.k == 0) return;
+    if (L.k == 0) return;                       // nothing selected: the mask stays clear
     const unsigned long long T = state[l].T;
-    const uint32_t start = (c - L.chunk_begin) * kChunk;
-    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-    const uint32_t *__restrict__ src = keys + L.elem_off + start;
     const int h = (static_cast<int>(L.p) - 1) / 2;
+    const int rows_ext = kTileRows + 2 * h;
+    const uint32_t local = t_id - dir[e].begin;
+    const int trow = static_cast<int>(local / L.tiles_x);
+    const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
     const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
-    uint32_t n_sel = 0;
-#pragma unroll 2
-    for (int j = 0; j < kChunk / 1024; ++j) {
-        const uint32_t e = j * 1024 + 4 * tid;
-        if (e >= len) break;
-        uint32_t kk[4] = {0, 0, 0, 0};
-        if (e + 3 < len) {
-            const uint4 q = *reinterpret_cast<const uint4 *>(src + e);
-            kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
-        } else {
-            for (uint32_t q = 0; q < 4 && e + q < len; ++q) kk[q] = src[e + q];
+    const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
+    const uint32_t *__restrict__ src = keys + L.elem_off;
+
+    for (int it = wave; it < rows_ext * 2; it += 4) {
+        const int rr = it >> 1, seg = it & 1;
+        const int x = x0 - h + rr, y = y0 + 64 * seg + lane;
+        bool flag = false;
+        if (x >= 0 && x < R && y < C) {
+            const uint32_t i = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+            flag = composite_key(src[i], i) >= T;
         }
-#pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            const uint32_t i = start + e + q;
-            if (e + q < len && composite_key(kk[q], i) >= T) {
-                ++n_sel;
-                const int xc = static_cast<int>(i / L.C);
-                const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * L.C);
-                const int ylo = max(0, yc - h), yhi = min(C - 1, yc + h);
-                for (int x = max(0, xc - h); x <= min(R - 1, xc + h); ++x)
-                    set_bits(mask, static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + ylo,
-                             static_cast<uint32_t>(yhi - ylo + 1));
-                if (cmask) {
-                    const size_t pos = static_cast<size_t>(L.elem_off) + i;
-                    atomicOr(&cmask[pos >> 5], 1u << (pos & 31));
+        const unsigned long long w = __ballot(flag);
+        if (lane == 0) bits[rr][1 + seg] = w;
+    }
+    if (wave < 2 && lane < rows_ext) {          // halo columns: lane = row; wave 0 left, wave 1 right
+        unsigned long long hw = 0;
+        const int x = x0 - h + lane;
+        if (x >= 0 && x < R) {
+            for (int d = 1; d <= h; ++d) {
+                const int y = wave == 0 ? y0 - d : y0 + kTileCols + (d - 1);
+                if (y >= 0 && y < C) {
+                    const uint32_t i = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+                    if (composite_key(src[i], i) >= T)
+                        hw |= wave == 0 ? (1ull << (64 - d)) : (1ull << (d - 1));
                 }
             }
         }
+        bits[lane][wave == 0 ? 0 : 3] = hw;
     }
-    // wave-level sum, one atomic per wave
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) n_sel += __shfl_down(n_sel, d, 64);
-    if ((tid & 63) == 0 && n_sel) atomicAdd(&state[l].n_centres, n_sel);
+    __syncthreads();
+    if (wave != 0) return;
+
+    const int r = lane >> 1, seg = lane & 1;    // 32 rows x 2 segments = 64 items
+    const int x = x0 + r, yb = y0 + 64 * seg;
+    if (x >= R || yb >= C) return;
+    unsigned long long acc = 0;
+    for (int rr = r; rr <= r + 2 * h; ++rr) {
+        const unsigned long long W = bits[rr][1 + seg], Lw = bits[rr][seg], Rw = bits[rr][2 + seg];
+        unsigned long long hd = W;
+        for (int d = 1; d <= h; ++d)
+            hd |= (W << d) | (Lw >> (64 - d)) | (W >> d) | (Rw << (64 - d));
+        acc |= hd;
+    }
+    const int ncols = min(64, C - yb);
+    const unsigned long long valid = ncols >= 64 ? ~0ull : ((1ull << ncols) - 1ull);
+    acc &= valid;
+    const unsigned long long own = bits[r + h][1 + seg];
+    const size_t pos = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + yb;
+    if ((C & 31) == 0) {                         // the tile owns its mask words
+        const size_t w = pos >> 5;
+        mask[w] = static_cast<uint32_t>(acc);
+        if (ncols > 32) mask[w + 1] = static_cast<uint32_t>(acc >> 32);
+        if (cmask) {
+            cmask[w] = static_cast<uint32_t>(own);
+            if (ncols > 32) cmask[w + 1] = static_cast<uint32_t>(own >> 32);
+        }
+    } else {
+        or_bits_shared(mask, pos, acc);
+        if (cmask) or_bits_shared(cmask, pos, own);
+    }
 }
 
 // ---------------------------------------------------------------- count --
@@ -488,8 +530,11 @@ __global__ __launch_bounds__(256) void k_scan(const LayerDev *__restrict__ layer
             out_counts[l] = static_cast<int32_t>(incl);
             state[l].n_pairs = incl;
         }
+        if (tid == 255 && pass == 1) {
+            state[l].n_centres = incl;
+            if (out_centre_counts) out_centre_counts[l] = static_cast<int32_t>(incl);
+        }
     }
-    if (tid == 0 && out_centre_counts) out_centre_counts[l] = static_cast<int32_t>(state[l].n_centres);
 }
 
 // ----------------------------------------------------------------- emit --
@@ -719,13 +764,14 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
     uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
     uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
-    uint32_t *cmask = out_centre_idx ? reinterpret_cast<uint32_t *>(ws + w.cmask) : nullptr;
+    const bool want_centres = out_centre_idx || out_centre_counts;
+    uint32_t *cmask = want_centres ? reinterpret_cast<uint32_t *>(ws + w.cmask) : nullptr;
     float *nsi = reinterpret_cast<float *>(ws + w.nsi);
 
     StageMarks marks(plan, stream);
     // clear: state .. mask (and the centre mask only when it is used)
     {
-        const size_t end = out_centre_idx ? w.zero_end : w.cmask;
+        const size_t end = want_centres ? w.zero_end : w.cmask;
         const size_t n16 = (end - w.zero_begin) / 16;
         const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
         hipLaunchKernelGGL(k_clear, dim3(blocks), dim3(256), 0, stream,
@@ -751,9 +797,10 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     HIP_TRY(hipGetLastError());
     marks.close(2);
 
-    hipLaunchKernelGGL(k_mark, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
-                       static_cast<uint32_t>(L), state, reinterpret_cast<const uint32_t *>(nsi),
-                       mask, cmask);
+    hipLaunchKernelGGL(k_mark, dim3(plan->n_tiles_all), dim3(256), 0, stream, layers,
+                       reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir),
+                       static_cast<uint32_t>(L), plan->n_tiles_all, state,
+                       reinterpret_cast<const uint32_t *>(nsi), mask, cmask);
     marks.close(3);
     hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                        static_cast<uint32_t>(L), mask, cmask, chunk_cnt, chunk_ccnt);
@@ -763,7 +810,7 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                        static_cast<uint32_t>(L), grad, residual, mask, chunk_cnt, out_idx, out_val);
     marks.close(5);
-    if (cmask)
+    if (out_centre_idx)
         hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                            static_cast<uint32_t>(L), cmask, chunk_ccnt, out_centre_idx);
     marks.close(6);

@@ -26,9 +26,10 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->groups.clear();
     plan->tile_dir.clear();
     plan->chunk_dir.clear();
+    plan->all_tile_dir.clear();
 
     int64_t elem_off = 0, out_off = 0, centre_off = 0;
-    uint32_t chunk_begin = 0;
+    uint32_t chunk_begin = 0, tile_begin_all = 0;
     for (int l = 0; l < L; ++l) {
         LayerDev &d = plan->layers[l];
         const int64_t R = plan->shapes[l].rows, C = plan->shapes[l].cols, G = R * C;
@@ -51,12 +52,16 @@ int build_tables(rsdgc_plan_s *plan) {
         d.cap = static_cast<uint32_t>(cap);
         plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(l)});
         chunk_begin += d.n_chunks;
+        plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(l)});
+        tile_begin_all += d.n_tiles;
         elem_off += (G + kLayerAlign - 1) / kLayerAlign * kLayerAlign;
         out_off += cap;
         centre_off += k;
     }
     plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(L)});
     plan->n_chunks = chunk_begin;
+    plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(L)});
+    plan->n_tiles_all = tile_begin_all;
     plan->total_elems = elem_off;
     plan->out_capacity = out_off;
     plan->centre_capacity = centre_off;
@@ -86,6 +91,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.layers = off;      off = align_up(off + sizeof(LayerDev) * L, A);
     w.tile_dir = off;    off = align_up(off + sizeof(DirEntry) * plan->tile_dir.size(), A);
     w.chunk_dir = off;   off = align_up(off + sizeof(DirEntry) * plan->chunk_dir.size(), A);
+    w.all_tile_dir = off; off = align_up(off + sizeof(DirEntry) * plan->all_tile_dir.size(), A);
     w.table_bytes = off;
     w.zero_begin = off;
     w.state = off;       off = align_up(off + sizeof(SelState) * L, A);
@@ -104,6 +110,8 @@ int build_tables(rsdgc_plan_s *plan) {
                 sizeof(DirEntry) * plan->tile_dir.size());
     std::memcpy(plan->table.data() + w.chunk_dir, plan->chunk_dir.data(),
                 sizeof(DirEntry) * plan->chunk_dir.size());
+    std::memcpy(plan->table.data() + w.all_tile_dir, plan->all_tile_dir.data(),
+                sizeof(DirEntry) * plan->all_tile_dir.size());
     ++plan->version;
     return RSDGC_OK;
 }

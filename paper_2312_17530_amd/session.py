@@ -57,7 +57,7 @@ class Session:
     def compress(self, stream=None) -> None:
         binding.rsdgc_compress(self.plan, self.grad, self.residual, self.out_idx, self.out_val,
                                self.out_counts, self.workspace, self.out_centre_idx,
-                               self.out_centre_counts, stream)
+                               self.out_centre_counts if self.want_centres else None, stream)
 
     def nsi(self, use_residual: bool = True) -> List[np.ndarray]:
         out = torch.zeros_like(self.grad)

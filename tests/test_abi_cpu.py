@@ -1,0 +1,142 @@
+"""Boundary tests that need no GPU: the C-ABI library loads, exports every symbol the header
+declares, validates its arguments, and does the host arithmetic of the plan (Eq. 11 counts,
+arena offsets, output capacities) correctly.  No kernel is launched."""
+import ctypes
+import os
+import re
+from fractions import Fraction
+
+import pytest
+
+from paper_2312_17530_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    header = open(os.path.join(ROOT, "include", "rsdgc.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(rsdgc_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(binding.EXPORTS)
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+
+
+def test_plan_counts_match_golden_eq11():
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, "eq11_keep_counts.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    for G, p, rho, k in rows:
+        G, p, rho, k = int(G), int(p), float(rho), int(k)
+        # factor G into a matrix; any factorisation must give the same count
+        rows_ = 1
+        for cand in (4096, 512, 64, 9, 3, 2):
+            if G % cand == 0:
+                rows_ = cand
+                break
+        plan = binding.rsdgc_plan([(rows_, G // rows_)], p, 0.5, [rho])
+        assert plan.layer_k(0) == k
+        assert plan.centre_capacity == k
+        assert plan.out_capacity == min(k * p * p, G)
+
+
+def test_plan_layout_of_the_five_workloads():
+    want_total = [262144, 11189952, 23547072, 139740864, 102760448]
+    want_layers = [1, 21, 54, 19, 1]
+    for i in range(5):
+        w = synth.config(i)
+        assert w.total_elems == want_total[i] and w.n_layers == want_layers[i]
+        plan = binding.rsdgc_plan(w.shapes, w.p, w.alpha, w.ratios)
+        assert plan.n_layers == w.n_layers
+        off, out_off, c_off = 0, 0, 0
+        for l, (r, c) in enumerate(w.shapes):
+            G = r * c
+            assert plan.layer_offset(l) == off and off % 64 == 0
+            assert plan.layer_elems(l) == G
+            exact = Fraction(G, w.p * w.p) * Fraction(w.ratios[l])
+            k = plan.layer_k(l)
+            assert abs(k - exact) < 1 + 1e-6 and k >= exact - 1e-6          # a ceiling of Eq. 11
+            assert plan.out_offset(l) == out_off and plan.centre_offset(l) == c_off
+            off += (G + 63) // 64 * 64
+            out_off += min(k * w.p * w.p, G)
+            c_off += k
+        assert plan.total_elems == off
+        assert plan.out_capacity == out_off and plan.centre_capacity == c_off
+        # workspace holds at least a float32 score map and two bitmasks
+        assert plan.workspace_bytes >= 4 * off + 2 * off // 8
+        assert plan.workspace_bytes % 256 == 0
+    # configuration 0: the survey's worked number
+    assert binding.rsdgc_plan([(512, 512)], 3, 0.5, [0.02]).layer_k(0) == 583
+
+
+@pytest.mark.parametrize("kwargs", [
+    dict(shapes=[(0, 5)]), dict(shapes=[(5, -1)]), dict(p=2), dict(p=0), dict(p=9),
+    dict(alpha=-0.1), dict(alpha=1.5), dict(alpha=float("nan")), dict(ratios=[1.5]),
+    dict(ratios=[-0.01]), dict(ratios=[float("nan")]), dict(shapes=[(70000, 70000)]),
+    dict(p_per_layer=[4]), dict(shapes=[]),
+])
+def test_plan_rejects_bad_arguments(kwargs):
+    args = dict(shapes=[(8, 8)], p=3, alpha=0.5, ratios=[0.1], p_per_layer=None)
+    args.update(kwargs)
+    if "shapes" in kwargs and "ratios" not in kwargs:
+        args["ratios"] = [0.1] * len(args["shapes"])
+    with pytest.raises(binding.RsdgcError) as ei:
+        binding.rsdgc_plan(args["shapes"], args["p"], args["alpha"], args["ratios"], args["p_per_layer"])
+    assert ei.value.code == binding.RSDGC_EINVAL
+
+
+def test_set_ratios_recomputes_counts_and_validates():
+    plan = binding.rsdgc_plan([(512, 512), (64, 27)], 3, 0.5, [0.02, 0.02])
+    ws = plan.workspace_bytes
+    assert [plan.layer_k(0), plan.layer_k(1)] == [583, 4]
+    binding.rsdgc_plan_set_ratios(plan, [0.0, 1.0])
+    assert [plan.layer_k(0), plan.layer_k(1)] == [0, 192]
+    assert plan.out_capacity == min(192 * 9, 1728) and plan.out_offset(1) == 0
+    assert plan.workspace_bytes == ws
+    with pytest.raises(binding.RsdgcError):
+        binding.rsdgc_plan_set_ratios(plan, [0.5, 2.0])
+    assert [plan.layer_k(0), plan.layer_k(1)] == [0, 192]      # unchanged after the error
+
+
+def test_per_layer_neighbourhood_side():
+    plan = binding.rsdgc_plan([(90, 90), (90, 90), (90, 90)], 3, 0.5, [0.1, 0.1, 0.1], [1, 3, 5])
+    assert [plan.layer_k(l) for l in range(3)] == [810, 90, 33]
+    assert plan.out_capacity == 810 + 810 + 825
+
+
+def test_device_entry_points_validate_before_touching_the_gpu():
+    lib = binding.load()
+    plan = binding.rsdgc_plan([(8, 8)], 3, 0.5, [0.1])
+    null = None
+    # null plan / null buffers -> RSDGC_EINVAL, nothing enqueued (this box may have no GPU at all)
+    assert lib.rsdgc_compress(null, null, null, null, null, null, null, null, null, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_compress(plan.handle, null, null, null, null, null, null, null, null, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_nsi(plan.handle, null, null, null, null, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_decompress(plan.handle, null, null, null, null, 0, null, null) == binding.RSDGC_EINVAL
+    # misaligned workspace / arenas are refused as well (addresses are never dereferenced here)
+    a = 4096
+    assert lib.rsdgc_compress(plan.handle, a, a, a, a, a, null, null, a + 8, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_compress(plan.handle, a + 4, a, a, a, a, null, null, a, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_profile_begin(plan.handle, 0) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_profile_end(null, null, null) == binding.RSDGC_EINVAL
+
+
+def test_queries_on_bad_arguments_and_strerror():
+    lib = binding.load()
+    plan = binding.rsdgc_plan([(8, 8)], 3, 0.5, [0.1])
+    assert lib.rsdgc_layer_k(plan.handle, 1) == -1 and lib.rsdgc_layer_offset(plan.handle, -1) == -1
+    assert lib.rsdgc_n_layers(None) == -1 and lib.rsdgc_workspace_bytes(None) == 0
+    assert lib.rsdgc_strerror(0) == b"ok"
+    assert b"invalid" in lib.rsdgc_strerror(binding.RSDGC_EINVAL)
+    assert lib.rsdgc_strerror(-99) == b"unknown error code"
+    assert lib.rsdgc_stage_name(1) == b"nsi" and lib.rsdgc_stage_name(99) == b""
+    lib.rsdgc_plan_destroy(None)     # harmless
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "librsdgc.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        binding.load()
