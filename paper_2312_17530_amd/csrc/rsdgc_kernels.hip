@@ -111,6 +111,26 @@ __global__ void k_init_state(const LayerDev *__restrict__ layers, SelState *__re
     state[l] = s;
 }
 
+// Eqs. 8-10 from the window sums sa = sum|w|, ss = sum w, sq = sum w^2 (n = p*p slots):
+//   mean = sa / n,  std = sqrt(n*sq - ss^2) / n,  NSI = alpha*mean + (1-alpha)*std.
+// n*sq - ss^2 is formed from two separately rounded products so that it is exactly 0 for a
+// constant window.  The square root is one v_rsq_f64 seed, one coupled Newton step and one
+// residual correction (about 1 ulp in double); the floor 1e-300 stands in for 0 and
+// vanishes when the score is rounded to float32.
+__device__ __forceinline__ double nsi_from_sums(double sa, double ss, double sq, double n,
+                                                double ca, double cb) {
+    double d = __dsub_rn(__dmul_rn(n, sq), __dmul_rn(ss, ss));
+    d = fmax(d, 1e-300);
+    const double y = __builtin_amdgcn_rsq(d);
+    double g = d * y, h = 0.5 * y;
+    const double r = fma(-h, g, 0.5);
+    g = fma(g, r, g);
+    h = fma(h, r, h);
+    const double e = fma(-g, g, d);
+    g = fma(e, h, g);
+    return fma(cb, g, ca * sa);
+}
+
 // ------------------------------------------------------------------ nsi --
 // One workgroup = one 32 x 128 tile of one layer.  The tile of v = r + g plus a halo of
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
@@ -200,8 +220,8 @@ __global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers
     const int c0 = 2 * tx;
     const int row_base = ty * RPT;
     const double n = static_cast<double>(P * P);
-    const double inv_n = 1.0 / n;
-    const double beta = 1.0 - alpha;
+    const double ca = alpha / n;            // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
+    const double cb = (1.0 - alpha) / n;
     const bool pair_store = (C & 1) == 0;
 
     double hs_a[P][2], hs_s[P][2], hs_q[P][2];
@@ -237,12 +257,7 @@ __global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers
                     ss += hs_s[(o + j) % P][c];
                     sq += hs_q[(o + j) % P][c];
                 }
-                const double mean_abs = sa * inv_n;                                   // Eq. 9
-                double d = __dsub_rn(__dmul_rn(n, sq), __dmul_rn(ss, ss));            // P^4 * variance
-                d = d > 0.0 ? d : 0.0;
-                const double sd = sqrt(d) * inv_n;                                    // Eq. 10
-                out[c] = static_cast<float>(__dadd_rn(__dmul_rn(alpha, mean_abs),
-                                                      __dmul_rn(beta, sd)));          // Eq. 8
+                out[c] = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
             }
             const int x = x0 + row_base + o, y = y0 + c0;
             if (x < R && y < C) {
