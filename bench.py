@@ -36,7 +36,9 @@ MEASURED_TRAFFIC_BYTES = {}
 
 def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int) -> float:
     """Bytes a stage has to move by its own contract (float32 data)."""
-    if stage == "nsi":        # read g, read r, write the score map
+    if stage == "capture":    # read g, read r (candidates are a fraction of a percent)
+        return 8.0 * n_elems
+    if stage == "full_map":   # read g, read r, write the score map
         return 12.0 * n_elems
     if stage == "emit":       # read g, read r, write r, write (index, value) pairs
         return 12.0 * n_elems + 8.0 * n_pairs
@@ -77,6 +79,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-stage HIP events")
     ap.add_argument("--centres", action="store_true", help="also emit the selected-centre lists")
+    ap.add_argument("--full-map", action="store_true",
+                    help="force the full-score-map ranking path for every layer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the compressor is per-rank and has no "
@@ -94,7 +98,8 @@ def main() -> int:
 
     w = synth.config(args.config)
     grads = synth.gradients(w, 0)
-    sess = Session(w.shapes, w.p, w.alpha, w.ratios, want_centres=args.centres)
+    sess = Session(w.shapes, w.p, w.alpha, w.ratios, want_centres=args.centres,
+                   path=binding.RSDGC_PATH_FULL_MAP if args.full_map else binding.RSDGC_PATH_AUTO)
     sess.set_grad(grads)
     G = w.total_elems
     stream = torch.cuda.current_stream()
@@ -127,7 +132,7 @@ def main() -> int:
 
     roofline = None
     if stages:
-        dom = max(("nsi", "emit", "select", "mark"), key=lambda s: stages.get(s, 0.0))
+        dom = max(("capture", "full_map", "emit", "select", "mark"), key=lambda s: stages.get(s, 0.0))
         dur_s = stages[dom] * 1e-3
         alg = stage_algorithmic_bytes(dom, G, n_pairs)
         achieved = alg / dur_s / 1e9
@@ -145,6 +150,7 @@ def main() -> int:
         "config": {"workload": w.name, "layers": w.n_layers, "elements": G, "p": w.p,
                    "alpha": w.alpha, "mean_keep_ratio": float(np.average(w.ratios, weights=[r * c for r, c in w.shapes])),
                    "pairs_emitted_last_step": n_pairs, "centre_lists": bool(args.centres),
+                   "ranking_path": "full_map" if args.full_map else "auto",
                    "residual": "carried across steps"},
         "roofline": roofline,
         "stages_ms": {k: round(v, 5) for k, v in stages.items()},

@@ -74,6 +74,17 @@ int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
  * The workspace size does not change.                                       */
 int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio);
 
+/* How the per-layer ranking (Algorithm 1) is carried out; the result is the same.
+ *   RSDGC_PATH_AUTO      large layers record only the centres whose score reaches a
+ *                        bound estimated from a sample of the layer and rank those;
+ *                        a layer falls back to the full map when the bound turns out
+ *                        too high or a tile holds too many such centres (default).
+ *   RSDGC_PATH_FULL_MAP  every layer writes its full score map and ranks it with
+ *                        histogram passes over all elements.                       */
+#define RSDGC_PATH_AUTO      0
+#define RSDGC_PATH_FULL_MAP  1
+int rsdgc_plan_set_path(rsdgc_plan_t *plan, int32_t path);
+
 void rsdgc_plan_destroy(rsdgc_plan_t *plan);
 
 /* Host queries; l in [0, n_layers).  Invalid arguments give -1 (0 for size_t). */
@@ -146,10 +157,15 @@ int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
  * recorded events, writes the mean milliseconds per call of each stage into
  * stage_ms[RSDGC_N_STAGES] [host], the number of recorded calls into *n_calls [host],
  * and destroys the events.  Stages: see rsdgc_stage_name.                        */
-#define RSDGC_N_STAGES 7
+#define RSDGC_N_STAGES 9
 int rsdgc_profile_begin(rsdgc_plan_t *plan, int32_t max_calls);
 int rsdgc_profile_end(rsdgc_plan_t *plan, double *stage_ms, int32_t *n_calls);
 const char *rsdgc_stage_name(int32_t stage);
+
+/* Which ranking path each layer took in the last rsdgc_compress that used `workspace`:
+ * paths[l] [host, n_layers] = 0 candidates above a sampled bound, 1 full score map,
+ * 2 nothing to select (k_l = 0).  Waits for `stream`, then copies from the device.   */
+int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream);
 
 /* ----------------------------------------------------------- diagnostics */
 const char *rsdgc_strerror(int code);

@@ -18,14 +18,15 @@ RSDGC_OK, RSDGC_EINVAL, RSDGC_ENOMEM, RSDGC_EHIP = 0, -1, -2, -3
 RSDGC_MAX_P = 7
 
 EXPORTS = [
-    "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_destroy", "rsdgc_n_layers",
+    "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
     "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_nsi", "rsdgc_decompress",
-    "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
+    "rsdgc_last_paths", "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
 ]
-RSDGC_N_STAGES = 7
+RSDGC_N_STAGES = 9
+RSDGC_PATH_AUTO, RSDGC_PATH_FULL_MAP = 0, 1
 
 
 class Shape(ctypes.Structure):
@@ -64,6 +65,8 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_plan.restype = ctypes.c_int
     lib.rsdgc_plan_set_ratios.argtypes = [vp, ctypes.POINTER(f64)]
     lib.rsdgc_plan_set_ratios.restype = ctypes.c_int
+    lib.rsdgc_plan_set_path.argtypes = [vp, i32]
+    lib.rsdgc_plan_set_path.restype = ctypes.c_int
     lib.rsdgc_plan_destroy.argtypes = [vp]
     lib.rsdgc_plan_destroy.restype = None
     lib.rsdgc_n_layers.argtypes = [vp]
@@ -83,6 +86,8 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_nsi.restype = ctypes.c_int
     lib.rsdgc_decompress.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
     lib.rsdgc_decompress.restype = ctypes.c_int
+    lib.rsdgc_last_paths.argtypes = [vp, vp, ctypes.POINTER(i32), vp]
+    lib.rsdgc_last_paths.restype = ctypes.c_int
     lib.rsdgc_profile_begin.argtypes = [vp, i32]
     lib.rsdgc_profile_begin.restype = ctypes.c_int
     lib.rsdgc_profile_end.argtypes = [vp, ctypes.POINTER(f64), ctypes.POINTER(i32)]
@@ -192,6 +197,10 @@ def rsdgc_plan_set_ratios(plan: Plan, keep_ratio: Sequence[float]) -> None:
     _check(load().rsdgc_plan_set_ratios(plan.handle, ratios), "rsdgc_plan_set_ratios")
 
 
+def rsdgc_plan_set_path(plan: Plan, path: int) -> None:
+    _check(load().rsdgc_plan_set_path(plan.handle, int(path)), "rsdgc_plan_set_path")
+
+
 def rsdgc_compress(plan: Plan, grad, residual, out_idx, out_val, out_counts, workspace,
                    out_centre_idx=None, out_centre_counts=None, stream=None) -> None:
     _check(load().rsdgc_compress(plan.handle, _ptr(grad), _ptr(residual), _ptr(out_idx),
@@ -223,3 +232,11 @@ def rsdgc_profile_end(plan: Plan):
     n = ctypes.c_int32(0)
     _check(lib.rsdgc_profile_end(plan.handle, ms, ctypes.byref(n)), "rsdgc_profile_end")
     return {lib.rsdgc_stage_name(i).decode(): ms[i] for i in range(RSDGC_N_STAGES)}, n.value
+
+
+def rsdgc_last_paths(plan: Plan, workspace, stream=None):
+    """Ranking path per layer of the last compress call (0 candidates, 1 full map, 2 none)."""
+    out = (ctypes.c_int32 * plan.n_layers)()
+    _check(load().rsdgc_last_paths(plan.handle, _ptr(workspace), out, _stream(stream)),
+           "rsdgc_last_paths")
+    return list(out)

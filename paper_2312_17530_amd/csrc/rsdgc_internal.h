@@ -14,59 +14,99 @@ constexpr int kTileCols = 128;       // NSI tile: output columns per workgroup
 constexpr int kChunk = 8192;         // elements per workgroup in the 1-D passes
 constexpr int kHistBins = 4096;      // widest radix digit (12 bits)
 constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements
+constexpr int kSlotCap = 256;        // candidate centres one tile can record
+constexpr int kSlotGroup = 64;       // tile slots per workgroup in the candidate passes
+constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 
-// One layer as the kernels see it (80 bytes).
+// How the k_l-th largest score of a layer is found (per layer, decided on the device).
+enum LayerMode : uint32_t {
+    kModeCandidates = 0,  // scores above a sampled bound are recorded per tile; exact select on them
+    kModeFullMap = 1,     // score map + histogram over every element (always exact, more traffic)
+    kModeSkip = 2,        // k_l = 0: nothing is selected
+};
+
+// One tile in 16, picked by a multiplicative hash of its index inside the layer.
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+inline bool tile_is_sampled(uint32_t local_tile) {
+    return ((local_tile * 2654435761u) >> 28) == 0u;
+}
+
+// One layer as the kernels see it.
 struct LayerDev {
     int64_t elem_off;    // offset of the layer in the g / r / NSI arenas (elements)
     int64_t out_off;     // first pair of the layer in out_idx / out_val
     int64_t centre_off;  // first entry of the layer in out_centre_idx
     uint32_t R, C, G, k;
-    uint32_t p, tiles_x, tile_begin, n_tiles;  // tile_begin: first tile inside its p-group launch
-    uint32_t chunk_begin, n_chunks;
-    uint32_t cap, pad_[3];
+    uint32_t p, tiles_x, tile_begin, n_tiles;   // tile_begin: first tile inside its p-group launch
+    uint32_t chunk_begin, n_chunks, cap, tile_begin_all;  // tile_begin_all: first tile over all layers
+    uint32_t large;         // 1: eligible for the candidate path
+    uint32_t group_begin;   // first slot group of the layer
+    uint32_t n_groups;      // ceil(n_tiles / kSlotGroup)
+    uint32_t hint_target;   // sampled scores wanted at or above the candidate bound
+    uint32_t n_sampled;     // sampled tiles of the layer
+    uint32_t pad_[3];
 };
-static_assert(sizeof(LayerDev) == 80, "LayerDev layout");
+static_assert(sizeof(LayerDev) == 104, "LayerDev layout");
 
 // Per-layer selection state (32 bytes), lives in the workspace.
 struct SelState {
     unsigned long long T;   // threshold on the composite key (score bits << 32 | ~index)
     uint32_t k_rem;         // centres still to take inside the current bucket
     uint32_t done;          // threshold is final
-    uint32_t n_centres;     // centres selected (diagnostic, equals k)
+    uint32_t mode;          // LayerMode
+    uint32_t hint_key;      // candidate bound (score bits), candidate path only
+    uint32_t n_centres;     // centres selected (only counted when centre lists are requested)
     uint32_t n_pairs;       // pairs emitted
-    uint32_t pad_[2];
 };
 static_assert(sizeof(SelState) == 32, "SelState layout");
 
 // Directory entry used to map a workgroup id to a layer by binary search.
 struct DirEntry {
-    uint32_t begin;   // first tile (or chunk) of the layer
+    uint32_t begin;   // first tile / chunk / slot group of the layer
     uint32_t layer;
+};
+
+// A sampled tile: which layer, which tile inside it.
+struct SampleEntry {
+    uint32_t layer;
+    uint32_t local_tile;
 };
 
 // Byte offsets of the workspace sections (all multiples of 256).
 struct WsLayout {
-    size_t layers = 0;      // LayerDev[n_layers]
-    size_t tile_dir = 0;    // DirEntry[] per p-group, each closed by a sentinel
-    size_t chunk_dir = 0;   // DirEntry[n_layers + 1]
-    size_t all_tile_dir = 0;// DirEntry[n_layers + 1]: tiles of all layers in layer order
-    size_t state = 0;       // SelState[n_layers]
-    size_t hist = 0;        // uint32[n_layers][kHistBins]
-    size_t chunk_cnt = 0;   // uint32[n_chunks]  kept elements per chunk, then their prefix
-    size_t chunk_ccnt = 0;  // uint32[n_chunks]  selected centres per chunk, then prefix
-    size_t mask = 0;        // uint32[total_elems / 32]  kept-element bitmask
-    size_t cmask = 0;       // uint32[total_elems / 32]  selected-centre bitmask
-    size_t nsi = 0;         // float[total_elems]
+    // uploaded tables
+    size_t layers = 0;       // LayerDev[n_layers]
+    size_t tile_dir = 0;     // DirEntry[] per p-group, each closed by a sentinel
+    size_t chunk_dir = 0;    // DirEntry[n_layers + 1]
+    size_t all_tile_dir = 0; // DirEntry[n_layers + 1]: tiles of all layers in layer order
+    size_t group_dir = 0;    // DirEntry[n_layers + 1]: slot groups
+    size_t samples = 0;      // SampleEntry[] per p-group
+    size_t table_bytes = 0;  // bytes uploaded from the host
+    // cleared at the start of every compress
+    size_t zero_begin = 0;
+    size_t state = 0;        // SelState[n_layers]
+    size_t hist = 0;         // uint32[n_layers][kHistBins]
+    size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk, then their prefix
+    size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk, then prefix
+    size_t mask = 0;         // uint32[total_elems / 32]  kept-element bitmask
+    size_t cmask = 0;        // uint32[total_elems / 32]  selected-centre bitmask
+    size_t zero_end = 0;
+    // not cleared
+    size_t slot_cnt = 0;     // uint32[n_tiles_all]  candidates recorded per tile
+    size_t slot_ent = 0;     // uint64[n_tiles_all][kSlotCap]  their composite keys
+    size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
     size_t total = 0;
-    size_t table_bytes = 0; // bytes uploaded from the host (layers .. chunk_dir end)
-    size_t zero_begin = 0, zero_end = 0;  // region cleared at the start of every compress
 };
 
-struct PGroup {           // layers sharing one neighbourhood side: one NSI launch
+struct PGroup {           // layers sharing one neighbourhood side: one launch per NSI pass
     int p = 0;
     uint32_t n_tiles = 0;
-    uint32_t dir_begin = 0;   // index of the group's first DirEntry in tile_dir
-    uint32_t dir_count = 0;   // entries excluding the sentinel
+    uint32_t dir_begin = 0;     // index of the group's first DirEntry in tile_dir
+    uint32_t dir_count = 0;     // entries excluding the sentinel
+    uint32_t sample_begin = 0;  // index of the group's first SampleEntry
+    uint32_t n_samples = 0;
 };
 
 }  // namespace rsdgc
@@ -82,7 +122,11 @@ struct rsdgc_plan_s {
     std::vector<rsdgc::DirEntry> tile_dir;
     std::vector<rsdgc::DirEntry> chunk_dir;
     std::vector<rsdgc::DirEntry> all_tile_dir;
+    std::vector<rsdgc::DirEntry> group_dir;
+    std::vector<rsdgc::SampleEntry> samples;
     uint32_t n_tiles_all = 0;
+    uint32_t n_slot_groups = 0;
+    bool any_large = false;
     int64_t total_elems = 0;
     int64_t out_capacity = 0;
     int64_t centre_capacity = 0;
@@ -93,6 +137,7 @@ struct rsdgc_plan_s {
     uint64_t version = 1;               // bumped by set_ratios
     const void *uploaded_ws = nullptr;
     uint64_t uploaded_version = 0;
+    bool allow_candidates = true;       // false forces the full-map path for every layer
     // optional per-stage timing: (RSDGC_N_STAGES + 1) events per recorded call (hipEvent_t)
     std::vector<void *> prof_events;
     int prof_max_calls = 0;

@@ -1,13 +1,19 @@
 // HIP kernels (gfx950, wave64) and the device-facing entry points of the C ABI.
 //
 // Pipeline of one rsdgc_compress call, all layers per launch:
-//   clear      zero histograms, bitmasks, counters
-//   nsi        v = r + g (Eq. 12), window statistics and NSI (Eqs. 6-10) per element,
-//              NSI map to the workspace, 12-bit histogram of the score bits per layer
-//   find/refine radix select of the k_l-th largest composite key per layer
-//              (Algorithm 1's ranking; Eq. 11's k_l), most significant digit first
-//   mark       selected centres set the bits of their p x p window (Section III-C:
-//              whole neighbourhoods are kept)
+//   clear      zero histograms, bitmasks, counters; per-layer state
+//   sample     NSI (Eqs. 6-10) on one tile in 16 of the large layers -> score histogram
+//   hint       per large layer: a score bound with about 2 k_l centres expected above it
+//   capture    v = r + g (Eq. 12) and NSI for every element of the large layers; centres whose
+//              score reaches the bound are recorded per tile (no score map, no histogram)
+//   validate   a layer whose bound caught fewer than k_l centres, or overfilled a tile,
+//              falls back to the full map
+//   full map   small layers and fall-backs: NSI map + 12-bit histogram over every element
+//   find/refine radix select of the k_l-th largest composite key per layer (Algorithm 1's
+//              ranking; Eq. 11's k_l), most significant digit first, over the recorded
+//              candidates or over the map
+//   mark       selected centres set the bits of their p x p window (Section III-C: whole
+//              neighbourhoods are kept)
 //   count/scan kept elements per chunk and their prefix sums
 //   emit       ordered (index, value) pairs and the residual update (Eq. 12)
 #include <hip/hip_runtime.h>
@@ -101,13 +107,14 @@ __global__ void k_init_state(const LayerDev *__restrict__ layers, SelState *__re
     const int l = blockIdx.x * blockDim.x + threadIdx.x;
     if (l >= n_layers) return;
     SelState s;
-    const uint32_t k = layers[l].k;
-    s.T = k == 0 ? ~0ull : 0ull;   // no key reaches ~0: nothing is selected when k = 0
-    s.k_rem = k;
-    s.done = k == 0 ? 1u : 0u;
+    const LayerDev L = layers[l];
+    s.T = L.k == 0 ? ~0ull : 0ull;   // no key reaches ~0: nothing is selected when k = 0
+    s.k_rem = L.k;
+    s.done = L.k == 0 ? 1u : 0u;
+    s.mode = L.k == 0 ? kModeSkip : (L.large ? kModeCandidates : kModeFullMap);
+    s.hint_key = 0;
     s.n_centres = 0;
     s.n_pairs = 0;
-    s.pad_[0] = s.pad_[1] = 0;
     state[l] = s;
 }
 
@@ -132,44 +139,83 @@ __device__ __forceinline__ double nsi_from_sums(double sa, double ss, double sq,
 }
 
 // ------------------------------------------------------------------ nsi --
+// What one launch of the NSI kernel produces.
+enum NsiPass : int {
+    kPassMapOnly = 0,   // score map to a caller buffer (rsdgc_nsi)
+    kPassFullMap = 1,   // score map + 12-bit histogram, layers in full-map mode
+    kPassCapture = 2,   // candidates (score >= bound) recorded per tile, layers in candidate mode
+    kPassSample = 3,    // 12-bit histogram of the sampled tiles of the large layers
+};
+
+struct NsiArgs {
+    const LayerDev *layers;
+    const DirEntry *dir;          // tile directory of the launch (all but kPassSample)
+    uint32_t n_dir;
+    uint32_t n_tiles;
+    const SampleEntry *samples;   // kPassSample
+    const float *grad;
+    const float *resid;           // nullable: all-zero residual
+    float *nsi_out;               // score map (kPassMapOnly, kPassFullMap)
+    uint32_t *hist;               // [n_layers][kHistBins]
+    const SelState *state;
+    uint32_t *slot_cnt;           // [n_tiles_all]
+    unsigned long long *slot_ent; // [n_tiles_all][kSlotCap]
+    double alpha;
+};
+
 // One workgroup = one 32 x 128 tile of one layer.  The tile of v = r + g plus a halo of
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
 // down 8 rows of 2 adjacent columns, keeping per-row horizontal sums of |w|, w and w^2
 // (double) for the last P rows in registers.  The variance is formed as
 // (P^2 * sum w^2 - (sum w)^2) / P^4 in double, which is exactly 0 for a constant window
 // and keeps equal windows at equal scores wherever they lie.
-template <int P, bool HIST>
-__global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers,
-                                             const DirEntry *__restrict__ dir, uint32_t n_dir,
-                                             uint32_t n_tiles, const float *__restrict__ grad,
-                                             const float *__restrict__ resid,
-                                             float *__restrict__ nsi_out,
-                                             uint32_t *__restrict__ hist, double alpha) {
+template <int P, int PASS>
+__global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     constexpr int H = (P - 1) / 2;
     constexpr int ROWS = kTileRows + 2 * H;
     constexpr int PADL = 4;
     constexpr int PITCH = kTileCols + 2 * PADL;   // 136 floats
     constexpr int VEC_PER_ROW = PITCH / 4;        // 34
     constexpr int RPT = 8;                        // output rows per thread
+    constexpr bool HIST = PASS == kPassFullMap || PASS == kPassSample;
+    constexpr bool MAP = PASS == kPassMapOnly || PASS == kPassFullMap;
+    constexpr bool CAPTURE = PASS == kPassCapture;
     __shared__ __attribute__((aligned(16))) float tile[ROWS * PITCH];
     __shared__ uint32_t lhist[HIST ? kHistBins : 1];
+    __shared__ unsigned long long cand[CAPTURE ? kSlotCap : 1];
+    __shared__ uint32_t ncand;
 
     const int tid = threadIdx.x;
-    const uint32_t t_id = xcd_contiguous(blockIdx.x, n_tiles);
-    const uint32_t e = dir_lookup(dir, n_dir, t_id);
-    const uint32_t l = dir[e].layer;
-    const LayerDev L = layers[l];
-    const uint32_t local = t_id - dir[e].begin;
+    uint32_t l, local;
+    if (PASS == kPassSample) {
+        const SampleEntry se = a.samples[blockIdx.x];
+        l = se.layer;
+        local = se.local_tile;
+    } else {
+        const uint32_t t_id = xcd_contiguous(blockIdx.x, a.n_tiles);
+        const uint32_t e = dir_lookup(a.dir, a.n_dir, t_id);
+        l = a.dir[e].layer;
+        local = t_id - a.dir[e].begin;
+    }
+    uint32_t hint_key = 0;
+    if (PASS != kPassMapOnly) {
+        const SelState st = a.state[l];
+        if (PASS == kPassFullMap && st.mode != kModeFullMap) return;
+        if ((PASS == kPassCapture || PASS == kPassSample) && st.mode != kModeCandidates) return;
+        hint_key = st.hint_key;
+    }
+    const LayerDev L = a.layers[l];
     const int trow = static_cast<int>(local / L.tiles_x);
     const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
     const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
     const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
-    const float *__restrict__ g = grad + L.elem_off;
-    const float *__restrict__ r = resid ? resid + L.elem_off : nullptr;
+    const float *__restrict__ g = a.grad + L.elem_off;
+    const float *__restrict__ r = a.resid ? a.resid + L.elem_off : nullptr;
 
     if (HIST) {
         for (int b = tid; b < kHistBins; b += 256) lhist[b] = 0;
     }
+    if (CAPTURE && tid == 0) ncand = 0;
 
     // ---- load v = r + g for the tile and its halo; zero outside the matrix
     if ((C & 3) == 0) {
@@ -220,8 +266,8 @@ __global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers
     const int c0 = 2 * tx;
     const int row_base = ty * RPT;
     const double n = static_cast<double>(P * P);
-    const double ca = alpha / n;            // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
-    const double cb = (1.0 - alpha) / n;
+    const double ca = a.alpha / n;          // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
+    const double cb = (1.0 - a.alpha) / n;
     const bool pair_store = (C & 1) == 0;
 
     double hs_a[P][2], hs_s[P][2], hs_q[P][2];
@@ -261,17 +307,32 @@ __global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers
             }
             const int x = x0 + row_base + o, y = y0 + c0;
             if (x < R && y < C) {
-                const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
                 const bool two = y + 1 < C;
-                if (two && pair_store) {
-                    *reinterpret_cast<float2 *>(nsi_out + off) = make_float2(out[0], out[1]);
-                } else {
-                    nsi_out[off] = out[0];
-                    if (two) nsi_out[off + 1] = out[1];
+                const uint32_t key0 = __float_as_uint(out[0]) & 0x7fffffffu;
+                const uint32_t key1 = __float_as_uint(out[1]) & 0x7fffffffu;
+                if (MAP) {
+                    const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
+                    if (two && pair_store) {
+                        *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[1]);
+                    } else {
+                        a.nsi_out[off] = out[0];
+                        if (two) a.nsi_out[off + 1] = out[1];
+                    }
                 }
                 if (HIST) {
-                    atomicAdd(&lhist[(__float_as_uint(out[0]) & 0x7fffffffu) >> 19], 1u);
-                    if (two) atomicAdd(&lhist[(__float_as_uint(out[1]) & 0x7fffffffu) >> 19], 1u);
+                    atomicAdd(&lhist[key0 >> 19], 1u);
+                    if (two) atomicAdd(&lhist[key1 >> 19], 1u);
+                }
+                if (CAPTURE) {
+                    const uint32_t i0 = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+                    if (key0 >= hint_key) {
+                        const uint32_t pos = atomicAdd(&ncand, 1u);
+                        if (pos < kSlotCap) cand[pos] = composite_key(key0, i0);
+                    }
+                    if (two && key1 >= hint_key) {
+                        const uint32_t pos = atomicAdd(&ncand, 1u);
+                        if (pos < kSlotCap) cand[pos] = composite_key(key1, i0 + 1);
+                    }
                 }
             }
         }
@@ -279,11 +340,95 @@ __global__ __launch_bounds__(256) void k_nsi(const LayerDev *__restrict__ layers
 
     if (HIST) {
         __syncthreads();
-        uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins;
+        uint32_t *__restrict__ gh = a.hist + static_cast<size_t>(l) * kHistBins;
         for (int b = tid; b < kHistBins; b += 256) {
             const uint32_t c = lhist[b];
             if (c) atomicAdd(&gh[b], c);
         }
+    }
+    if (CAPTURE) {
+        __syncthreads();
+        const uint32_t slot = L.tile_begin_all + local;
+        const uint32_t nc = ncand;                 // may exceed kSlotCap: the validator sees that
+        if (tid == 0) a.slot_cnt[slot] = nc;
+        unsigned long long *__restrict__ dst = a.slot_ent + static_cast<size_t>(slot) * kSlotCap;
+        for (uint32_t i = tid; i < min(nc, static_cast<uint32_t>(kSlotCap)); i += 256) dst[i] = cand[i];
+    }
+}
+
+// ----------------------------------------------------------------- hint --
+// One workgroup per large layer: walk the sampled-score histogram from the top until
+// hint_target scores lie at or above a bucket; that bucket's lower edge is the candidate
+// bound.  A layer whose sample cannot supply the target goes to the full map.
+__global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layers,
+                                              SelState *__restrict__ state,
+                                              uint32_t *__restrict__ hist) {
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t found;
+    const int l = blockIdx.x, tid = threadIdx.x;
+    const SelState st = state[l];
+    if (st.mode != kModeCandidates) return;      // its histogram is untouched (still zero)
+    const uint32_t target = layers[l].hint_target;
+    uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
+    constexpr int per = kHistBins / 256;
+    if (tid == 0) found = 0;
+    const int hi = kHistBins - tid * per;
+    uint32_t own = 0;
+    for (int b = hi - 1; b >= hi - per; --b) own += h[b];
+    const uint32_t incl = block_scan_incl(own, wave_tot);
+    const uint32_t excl = incl - own;
+    if (excl < target && target <= incl) {
+        uint32_t acc = excl;
+        for (int b = hi - 1; b >= hi - per; --b) {
+            acc += h[b];
+            if (acc >= target) {
+                SelState ns = st;
+                ns.hint_key = static_cast<uint32_t>(b) << 19;
+                state[l] = ns;
+                found = 1;
+                break;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0 && !found) {
+        SelState ns = st;
+        ns.mode = kModeFullMap;
+        state[l] = ns;
+    }
+    for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
+}
+
+// ------------------------------------------------------------- validate --
+// One workgroup per candidate-mode layer: the recorded candidates are usable only if no
+// tile overflowed its slot and at least k_l centres were recorded (then the k_l best of
+// the layer are all among them).  Otherwise the layer falls back to the full map.
+__global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ layers,
+                                                  SelState *__restrict__ state,
+                                                  const uint32_t *__restrict__ slot_cnt) {
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t overflow;
+    const int l = blockIdx.x, tid = threadIdx.x;
+    const SelState st = state[l];
+    if (st.mode != kModeCandidates) return;
+    const LayerDev L = layers[l];
+    if (tid == 0) overflow = 0;
+    __syncthreads();
+    unsigned long long sum = 0;
+    bool over = false;
+    for (uint32_t t = tid; t < L.n_tiles; t += 256) {
+        const uint32_t c = slot_cnt[L.tile_begin_all + t];
+        over = over || c > static_cast<uint32_t>(kSlotCap);
+        sum += c;
+    }
+    if (over) overflow = 1;
+    const uint32_t capped = sum > 0xffffffffull ? 0xffffffffu : static_cast<uint32_t>(sum);
+    // totals above 2^32 cannot occur (G_l < 2^32); the scan is on 32-bit partial sums
+    const uint32_t incl = block_scan_incl(capped, wave_tot);
+    if (tid == 255 && (overflow || incl < L.k)) {
+        SelState ns = st;
+        ns.mode = kModeFullMap;
+        state[l] = ns;
     }
 }
 
@@ -335,42 +480,72 @@ __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
 
 // --------------------------------------------------------------- refine --
 // Histogram of the next digit over the keys that match the threshold prefix so far.
+// Workgroups [0, n_map_blocks) each take one 8192-element chunk of the score map of a
+// full-map layer; the rest each take kSlotGroup tile slots of a candidate-mode layer.
 __global__ __launch_bounds__(256) void k_refine(const LayerDev *__restrict__ layers,
                                                 const DirEntry *__restrict__ chunk_dir,
-                                                uint32_t n_layers,
+                                                const DirEntry *__restrict__ group_dir,
+                                                uint32_t n_layers, uint32_t n_map_blocks,
                                                 const SelState *__restrict__ state,
                                                 uint32_t *__restrict__ hist,
-                                                const uint32_t *__restrict__ keys, int shift,
-                                                int bits, int shift_prev) {
-    __shared__ uint32_t lh[2048];
+                                                const uint32_t *__restrict__ keys,
+                                                const uint32_t *__restrict__ slot_cnt,
+                                                const unsigned long long *__restrict__ slot_ent,
+                                                int shift, int bits, int shift_prev) {
+    __shared__ uint32_t lh[kHistBins];
+    __shared__ uint32_t cnts[kSlotGroup];
     const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
-    const SelState st = state[l];
-    if (st.done) return;
-    const LayerDev L = layers[l];
     const int nb = 1 << bits;
-    for (int b = tid; b < nb; b += 256) lh[b] = 0;
-    __syncthreads();
-    const uint32_t start = (c - L.chunk_begin) * kChunk;
-    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-    const uint32_t *__restrict__ src = keys + L.elem_off + start;
-    const unsigned long long want = st.T >> shift_prev;
+    uint32_t l;
+    if (blockIdx.x < n_map_blocks) {
+        const uint32_t c = blockIdx.x;
+        l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+        const SelState st = state[l];
+        if (st.done || st.mode != kModeFullMap) return;
+        const LayerDev L = layers[l];
+        for (int b = tid; b < nb; b += 256) lh[b] = 0;
+        __syncthreads();
+        const uint32_t start = (c - L.chunk_begin) * kChunk;
+        const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+        const uint32_t *__restrict__ src = keys + L.elem_off + start;
+        const unsigned long long want = st.T >> shift_prev;
 #pragma unroll 2
-    for (int j = 0; j < kChunk / 1024; ++j) {
-        const uint32_t e = j * 1024 + 4 * tid;
-        if (e >= len) break;
-        uint32_t kk[4] = {0, 0, 0, 0};
-        if (e + 3 < len) {
-            const uint4 q = *reinterpret_cast<const uint4 *>(src + e);
-            kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
-        } else {
-            for (uint32_t q = 0; q < 4 && e + q < len; ++q) kk[q] = src[e + q];
-        }
+        for (int j = 0; j < kChunk / 1024; ++j) {
+            const uint32_t e = j * 1024 + 4 * tid;
+            if (e >= len) break;
+            uint32_t kk[4] = {0, 0, 0, 0};
+            if (e + 3 < len) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(src + e);
+                kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
+            } else {
+                for (uint32_t q = 0; q < 4 && e + q < len; ++q) kk[q] = src[e + q];
+            }
 #pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            if (e + q < len) {
-                const unsigned long long K = composite_key(kk[q], start + e + q);
+            for (uint32_t q = 0; q < 4; ++q) {
+                if (e + q < len) {
+                    const unsigned long long K = composite_key(kk[q], start + e + q);
+                    if ((K >> shift_prev) == want)
+                        atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
+                }
+            }
+        }
+    } else {
+        const uint32_t gidx = blockIdx.x - n_map_blocks;
+        l = group_dir[dir_lookup(group_dir, n_layers, gidx)].layer;
+        const SelState st = state[l];
+        if (st.done || st.mode != kModeCandidates) return;
+        const LayerDev L = layers[l];
+        const uint32_t first = (gidx - L.group_begin) * kSlotGroup;
+        const uint32_t ntile = min(static_cast<uint32_t>(kSlotGroup), L.n_tiles - first);
+        const uint32_t slot0 = L.tile_begin_all + first;
+        if (static_cast<uint32_t>(tid) < ntile) cnts[tid] = slot_cnt[slot0 + tid];
+        for (int b = tid; b < nb; b += 256) lh[b] = 0;
+        __syncthreads();
+        const unsigned long long want = st.T >> shift_prev;
+#pragma unroll 4
+        for (uint32_t sl = 0; sl < ntile; ++sl) {
+            if (static_cast<uint32_t>(tid) < cnts[sl]) {       // validated: cnts[sl] <= kSlotCap
+                const unsigned long long K = slot_ent[static_cast<size_t>(slot0 + sl) * kSlotCap + tid];
                 if ((K >> shift_prev) == want)
                     atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
             }
@@ -400,7 +575,20 @@ __device__ __forceinline__ void or_bits_shared(uint32_t *__restrict__ mask, size
     if (p2) atomicOr(&mask[w + 2], p2);
 }
 
-// One workgroup = one 32 x 128 tile (the NSI tiling).  Every centre of the tile and of a
+// Set nbits (<= RSDGC_MAX_P) consecutive mask bits starting at bit position pos.
+__device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos, uint32_t nbits) {
+    const size_t w = pos >> 5;
+    const uint32_t b = static_cast<uint32_t>(pos & 31);
+    const uint32_t bits = (1u << nbits) - 1u;
+    atomicOr(&mask[w], bits << b);
+    if (b + nbits > 32) atomicOr(&mask[w + 1], bits >> (32 - b));
+}
+
+// One workgroup = one 32 x 128 tile (the NSI tiling).
+// Candidate-mode layers: the tile's recorded candidates that reach the threshold OR the
+// bits of their window into the (cleared) mask; the words they touch are nearly all
+// distinct, which is the case global atomics handle well.
+// Full-map layers: every centre of the tile and of a
 // halo of h rows / columns is compared with the layer's threshold; the per-row results
 // become 64-bit ballot words in LDS, the p x p box dilation (Section III-C: whole
 // neighbourhoods are kept) is done on those words with shifts and ORs, and the tile's
@@ -410,6 +598,8 @@ __global__ __launch_bounds__(256) void k_mark(const LayerDev *__restrict__ layer
                                               const DirEntry *__restrict__ dir, uint32_t n_layers,
                                               uint32_t n_tiles, const SelState *__restrict__ state,
                                               const uint32_t *__restrict__ keys,
+                                              const uint32_t *__restrict__ slot_cnt,
+                                              const unsigned long long *__restrict__ slot_ent,
                                               uint32_t *__restrict__ mask,
                                               uint32_t *__restrict__ cmask) {
     constexpr int MAXH = (RSDGC_MAX_P - 1) / 2;
@@ -419,11 +609,34 @@ __global__ __launch_bounds__(256) void k_mark(const LayerDev *__restrict__ layer
     const uint32_t e = dir_lookup(dir, n_layers, t_id);
     const uint32_t l = dir[e].layer;
     const LayerDev L = layers[l];
-    if (L.k == 0) return;                       // nothing selected: the mask stays clear
-    const unsigned long long T = state[l].T;
+    const SelState st = state[l];
+    if (st.mode == kModeSkip) return;           // nothing selected: the mask stays clear
+    const unsigned long long T = st.T;
     const int h = (static_cast<int>(L.p) - 1) / 2;
     const int rows_ext = kTileRows + 2 * h;
     const uint32_t local = t_id - dir[e].begin;
+    if (st.mode == kModeCandidates) {
+        const uint32_t slot = L.tile_begin_all + local;
+        const uint32_t cnt = slot_cnt[slot];
+        if (static_cast<uint32_t>(tid) < cnt) {
+            const unsigned long long K = slot_ent[static_cast<size_t>(slot) * kSlotCap + tid];
+            if (K >= T) {
+                const uint32_t i = ~static_cast<uint32_t>(K);
+                const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
+                const int xc = static_cast<int>(i / L.C);
+                const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * L.C);
+                const int ylo = max(0, yc - h), yhi = min(C - 1, yc + h);
+                for (int x = max(0, xc - h); x <= min(R - 1, xc + h); ++x)
+                    set_bits(mask, static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + ylo,
+                             static_cast<uint32_t>(yhi - ylo + 1));
+                if (cmask) {
+                    const size_t pos = static_cast<size_t>(L.elem_off) + i;
+                    atomicOr(&cmask[pos >> 5], 1u << (pos & 31));
+                }
+            }
+        }
+        return;
+    }
     const int trow = static_cast<int>(local / L.tiles_x);
     const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
     const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
@@ -583,7 +796,9 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
     __syncthreads();
     const float *__restrict__ g = grad + base;
     float *__restrict__ r = resid + base;
-    const size_t obase = static_cast<size_t>(L.out_off) + chunk_base[c];
+    const uint32_t cbase = chunk_base[c];
+    const size_t obase = static_cast<size_t>(L.out_off) + cbase;
+    const uint32_t room = L.cap > cbase ? L.cap - cbase : 0u;   // never write past the segment
 #pragma unroll 2
     for (int j = 0; j < kChunk / 1024; ++j) {
         const uint32_t e = j * 1024 + 4 * tid;
@@ -600,8 +815,10 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
 #pragma unroll
                 for (int q = 0; q < 4; ++q)
                     if (bits & (1u << q)) {
-                        out_idx[obase + pos] = start + e + q;
-                        out_val[obase + pos] = v[q];
+                        if (pos < room) {
+                            out_idx[obase + pos] = start + e + q;
+                            out_val[obase + pos] = v[q];
+                        }
                         ++pos;
                         v[q] = 0.f;
                     }
@@ -612,8 +829,10 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
             for (uint32_t q = 0; q < 4 && e + q < len; ++q) {
                 float v = r[e + q] + g[e + q];
                 if (bits & (1u << q)) {
-                    out_idx[obase + pos] = start + e + q;
-                    out_val[obase + pos] = v;
+                    if (pos < room) {
+                        out_idx[obase + pos] = start + e + q;
+                        out_val[obase + pos] = v;
+                    }
                     ++pos;
                     v = 0.f;
                 }
@@ -642,11 +861,12 @@ __global__ __launch_bounds__(256) void k_emit_centres(const LayerDev *__restrict
     uint32_t word = static_cast<uint32_t>(tid) < nwords ? cmask[(base >> 5) + tid] : 0;
     const uint32_t cnt = __popc(word);
     const uint32_t incl = block_scan_incl(cnt, wave_tot);
-    size_t pos = static_cast<size_t>(L.centre_off) + chunk_cbase[c] + (incl - cnt);
+    uint32_t rank = chunk_cbase[c] + (incl - cnt);
     while (word) {
         const int b = __ffs(word) - 1;
         word &= word - 1;
-        out_centre_idx[pos++] = start + 32u * tid + b;
+        if (rank < L.k) out_centre_idx[static_cast<size_t>(L.centre_off) + rank] = start + 32u * tid + b;
+        ++rank;
     }
 }
 
@@ -704,20 +924,36 @@ int upload_tables(rsdgc_plan_s *plan, void *workspace, hipStream_t stream) {
     return RSDGC_OK;
 }
 
-template <bool HIST>
+// One launch of the NSI kernel per neighbourhood side.  kPassSample runs over the sampled
+// tiles of the large layers, every other pass over all tiles (workgroups of layers that
+// are in another mode leave at once).
+template <int PASS>
 int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const float *resid,
                float *nsi_out, hipStream_t stream) {
-    const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
+    NsiArgs a;
+    a.layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
+    a.grad = grad;
+    a.resid = resid;
+    a.nsi_out = nsi_out;
+    a.hist = reinterpret_cast<uint32_t *>(ws + plan->ws.hist);
+    a.state = reinterpret_cast<const SelState *>(ws + plan->ws.state);
+    a.slot_cnt = reinterpret_cast<uint32_t *>(ws + plan->ws.slot_cnt);
+    a.slot_ent = reinterpret_cast<unsigned long long *>(ws + plan->ws.slot_ent);
+    a.alpha = plan->alpha;
     const DirEntry *tile_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.tile_dir);
-    uint32_t *hist = reinterpret_cast<uint32_t *>(ws + plan->ws.hist);
+    const SampleEntry *samples = reinterpret_cast<const SampleEntry *>(ws + plan->ws.samples);
     for (const PGroup &g : plan->groups) {
-        const DirEntry *dir = tile_dir + g.dir_begin;
-        const dim3 grid(g.n_tiles), block(256);
+        a.dir = tile_dir + g.dir_begin;
+        a.n_dir = g.dir_count;
+        a.n_tiles = g.n_tiles;
+        a.samples = samples + g.sample_begin;
+        const uint32_t blocks = PASS == kPassSample ? g.n_samples : g.n_tiles;
+        if (blocks == 0) continue;
+        const dim3 grid(blocks), block(256);
         switch (g.p) {
-#define RSDGC_NSI_CASE(PP)                                                                   \
-    case PP:                                                                                 \
-        hipLaunchKernelGGL((k_nsi<PP, HIST>), grid, block, 0, stream, layers, dir, g.dir_count, \
-                           g.n_tiles, grad, resid, nsi_out, hist, plan->alpha);              \
+#define RSDGC_NSI_CASE(PP)                                                          \
+    case PP:                                                                        \
+        hipLaunchKernelGGL((k_nsi<PP, PASS>), grid, block, 0, stream, a);            \
         break;
             RSDGC_NSI_CASE(1)
             RSDGC_NSI_CASE(3)
@@ -795,41 +1031,77 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
         HIP_TRY(hipGetLastError());
     }
     marks.close(0);
-    rc = launch_nsi<true>(plan, ws, grad, residual, nsi, stream);
-    if (rc != RSDGC_OK) return rc;
-    marks.close(1);
 
-    hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(0),
-                       level_bits(0));
-    for (int lv = 1; lv < kLevels; ++lv) {
-        hipLaunchKernelGGL(k_refine, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
-                           static_cast<uint32_t>(L), state, hist,
-                           reinterpret_cast<const uint32_t *>(nsi), level_shift(lv), level_bits(lv),
-                           level_shift(lv - 1));
+    const DirEntry *group_dir = reinterpret_cast<const DirEntry *>(ws + w.group_dir);
+    const uint32_t *slot_cnt = reinterpret_cast<const uint32_t *>(ws + w.slot_cnt);
+    const unsigned long long *slot_ent = reinterpret_cast<const unsigned long long *>(ws + w.slot_ent);
+    if (plan->any_large) {
+        rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, stream);
+        if (rc != RSDGC_OK) return rc;
+        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist);
+        marks.close(1);
+        rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, stream);
+        if (rc != RSDGC_OK) return rc;
+        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, slot_cnt);
+        marks.close(2);
+    } else {
+        marks.close(1);
+        marks.close(2);
+    }
+    rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, stream);
+    if (rc != RSDGC_OK) return rc;
+    marks.close(3);
+
+    // radix select; level 0 of the full-map layers was histogrammed by the NSI pass
+    for (int lv = 0; lv < kLevels; ++lv) {
+        const uint32_t n_map_blocks = lv == 0 ? 0u : n_chunks;
+        const uint32_t n_slot_blocks = plan->any_large ? plan->n_slot_groups : 0u;
+        if (n_map_blocks + n_slot_blocks > 0)
+            hipLaunchKernelGGL(k_refine, dim3(n_map_blocks + n_slot_blocks), dim3(256), 0, stream,
+                               layers, chunk_dir, group_dir, static_cast<uint32_t>(L), n_map_blocks,
+                               state, hist, reinterpret_cast<const uint32_t *>(nsi), slot_cnt,
+                               slot_ent, level_shift(lv), level_bits(lv),
+                               lv == 0 ? 63 : level_shift(lv - 1));
         hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(lv),
                            level_bits(lv));
     }
     HIP_TRY(hipGetLastError());
-    marks.close(2);
+    marks.close(4);
 
     hipLaunchKernelGGL(k_mark, dim3(plan->n_tiles_all), dim3(256), 0, stream, layers,
                        reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir),
                        static_cast<uint32_t>(L), plan->n_tiles_all, state,
-                       reinterpret_cast<const uint32_t *>(nsi), mask, cmask);
-    marks.close(3);
+                       reinterpret_cast<const uint32_t *>(nsi), slot_cnt, slot_ent, mask, cmask);
+    marks.close(5);
     hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                        static_cast<uint32_t>(L), mask, cmask, chunk_cnt, chunk_ccnt);
     hipLaunchKernelGGL(k_scan, dim3(L), dim3(256), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
                        out_counts, out_centre_counts, cmask ? 1 : 0);
-    marks.close(4);
+    marks.close(6);
     hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                        static_cast<uint32_t>(L), grad, residual, mask, chunk_cnt, out_idx, out_val);
-    marks.close(5);
+    marks.close(7);
     if (out_centre_idx)
         hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                            static_cast<uint32_t>(L), cmask, chunk_ccnt, out_centre_idx);
-    marks.close(6);
+    marks.close(8);
     HIP_TRY(hipGetLastError());
+    return RSDGC_OK;
+}
+
+int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream_) {
+    if (!plan || !workspace || !paths) return RSDGC_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    std::vector<SelState> host;
+    try {
+        host.resize(plan->n_layers);
+    } catch (const std::bad_alloc &) {
+        return RSDGC_ENOMEM;
+    }
+    HIP_TRY(hipStreamSynchronize(stream));
+    HIP_TRY(hipMemcpy(host.data(), static_cast<const char *>(workspace) + plan->ws.state,
+                      sizeof(SelState) * plan->n_layers, hipMemcpyDeviceToHost));
+    for (int l = 0; l < plan->n_layers; ++l) paths[l] = static_cast<int32_t>(host[l].mode);
     return RSDGC_OK;
 }
 
@@ -886,8 +1158,8 @@ int rsdgc_profile_end(rsdgc_plan_t *plan, double *stage_ms, int32_t *n_calls) {
 }
 
 const char *rsdgc_stage_name(int32_t stage) {
-    static const char *names[RSDGC_N_STAGES] = {"clear", "nsi", "select", "mark", "count_scan",
-                                                "emit", "centres"};
+    static const char *names[RSDGC_N_STAGES] = {"clear", "sample", "capture", "full_map", "select",
+                                                "mark", "count_scan", "emit", "centres"};
     return (stage >= 0 && stage < RSDGC_N_STAGES) ? names[stage] : "";
 }
 
@@ -900,7 +1172,8 @@ int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual, floa
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
-    return launch_nsi<false>(plan, static_cast<char *>(workspace), grad, residual, nsi_out, stream);
+    return launch_nsi<kPassMapOnly>(plan, static_cast<char *>(workspace), grad, residual, nsi_out,
+                                    stream);
 }
 
 int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,

@@ -1,5 +1,6 @@
 // Host side of the C ABI: plan construction, validation, queries.
-// No HIP call happens in this file.
+// No HIP call is made from this file (destroying a plan that still holds profiling
+// events releases them through rsdgc_profile_end).
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -27,9 +28,12 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->tile_dir.clear();
     plan->chunk_dir.clear();
     plan->all_tile_dir.clear();
+    plan->group_dir.clear();
+    plan->samples.clear();
+    plan->any_large = false;
 
     int64_t elem_off = 0, out_off = 0, centre_off = 0;
-    uint32_t chunk_begin = 0, tile_begin_all = 0;
+    uint32_t chunk_begin = 0, tile_begin_all = 0, group_begin = 0;
     for (int l = 0; l < L; ++l) {
         LayerDev &d = plan->layers[l];
         const int64_t R = plan->shapes[l].rows, C = plan->shapes[l].cols, G = R * C;
@@ -50,35 +54,65 @@ int build_tables(rsdgc_plan_s *plan) {
         d.chunk_begin = chunk_begin;
         d.n_chunks = static_cast<uint32_t>((G + kChunk - 1) / kChunk);
         d.cap = static_cast<uint32_t>(cap);
+        d.tile_begin_all = tile_begin_all;
+        d.group_begin = group_begin;
+        d.n_groups = (d.n_tiles + kSlotGroup - 1) / kSlotGroup;
+
+        // Candidate path: the bound comes from the scores of a sample of the layer's tiles.
+        // It is taken where about twice k_l centres are expected above the bound; a layer is
+        // eligible when it has enough sampled tiles for that estimate and when the expected
+        // number of candidates per tile leaves ample room in a tile's slot.
+        uint32_t n_sampled = 0;
+        for (uint32_t t = 0; t < d.n_tiles; ++t) n_sampled += tile_is_sampled(t) ? 1u : 0u;
+        d.n_sampled = n_sampled;
+        const double frac = d.n_tiles ? double(n_sampled) / double(d.n_tiles) : 0.0;
+        const double want = 2.0 * double(k) * frac;
+        const double per_tile = d.n_tiles ? 3.0 * double(k) / double(d.n_tiles) : 0.0;
+        d.large = (plan->allow_candidates && k > 0 && n_sampled >= uint32_t(kMinSampledTiles) &&
+                   per_tile <= kSlotCap / 4.0) ? 1u : 0u;
+        d.hint_target = d.large ? static_cast<uint32_t>(std::ceil(want + 4.0 * std::sqrt(want) + 8.0)) : 0u;
+        plan->any_large = plan->any_large || d.large;
+
         plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(l)});
-        chunk_begin += d.n_chunks;
         plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(l)});
+        plan->group_dir.push_back(DirEntry{group_begin, static_cast<uint32_t>(l)});
+        chunk_begin += d.n_chunks;
         tile_begin_all += d.n_tiles;
+        group_begin += d.n_groups;
         elem_off += (G + kLayerAlign - 1) / kLayerAlign * kLayerAlign;
         out_off += cap;
         centre_off += k;
     }
     plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(L)});
-    plan->n_chunks = chunk_begin;
     plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(L)});
+    plan->group_dir.push_back(DirEntry{group_begin, static_cast<uint32_t>(L)});
+    plan->n_chunks = chunk_begin;
     plan->n_tiles_all = tile_begin_all;
+    plan->n_slot_groups = group_begin;
     plan->total_elems = elem_off;
     plan->out_capacity = out_off;
     plan->centre_capacity = centre_off;
 
-    // one NSI launch per distinct neighbourhood side
+    // one launch of each NSI pass per distinct neighbourhood side
     for (int p = 1; p <= RSDGC_MAX_P; p += 2) {
         PGroup g;
         g.p = p;
         g.dir_begin = static_cast<uint32_t>(plan->tile_dir.size());
+        g.sample_begin = static_cast<uint32_t>(plan->samples.size());
         for (int l = 0; l < L; ++l) {
             if (plan->p[l] != p) continue;
-            plan->layers[l].tile_begin = g.n_tiles;
+            LayerDev &d = plan->layers[l];
+            d.tile_begin = g.n_tiles;
             plan->tile_dir.push_back(DirEntry{g.n_tiles, static_cast<uint32_t>(l)});
-            g.n_tiles += plan->layers[l].n_tiles;
+            g.n_tiles += d.n_tiles;
             ++g.dir_count;
+            if (d.large)
+                for (uint32_t t = 0; t < d.n_tiles; ++t)
+                    if (tile_is_sampled(t))
+                        plan->samples.push_back(SampleEntry{static_cast<uint32_t>(l), t});
         }
         if (g.dir_count == 0) continue;
+        g.n_samples = static_cast<uint32_t>(plan->samples.size()) - g.sample_begin;
         plan->tile_dir.push_back(DirEntry{g.n_tiles, static_cast<uint32_t>(L)});  // sentinel
         plan->groups.push_back(g);
     }
@@ -87,21 +121,28 @@ int build_tables(rsdgc_plan_s *plan) {
     WsLayout &w = plan->ws;
     const size_t A = 256;
     const size_t words = static_cast<size_t>(plan->total_elems / 32);
+    // sized for the worst case so that new ratios never change the workspace size
+    size_t max_samples = 0;
+    for (int l = 0; l < L; ++l) max_samples += plan->layers[l].n_sampled;
     size_t off = 0;
-    w.layers = off;      off = align_up(off + sizeof(LayerDev) * L, A);
-    w.tile_dir = off;    off = align_up(off + sizeof(DirEntry) * plan->tile_dir.size(), A);
-    w.chunk_dir = off;   off = align_up(off + sizeof(DirEntry) * plan->chunk_dir.size(), A);
-    w.all_tile_dir = off; off = align_up(off + sizeof(DirEntry) * plan->all_tile_dir.size(), A);
+    w.layers = off;       off = align_up(off + sizeof(LayerDev) * L, A);
+    w.tile_dir = off;     off = align_up(off + sizeof(DirEntry) * (L + (RSDGC_MAX_P + 1) / 2), A);
+    w.chunk_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + 1), A);
+    w.all_tile_dir = off; off = align_up(off + sizeof(DirEntry) * (L + 1), A);
+    w.group_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + 1), A);
+    w.samples = off;      off = align_up(off + sizeof(SampleEntry) * (max_samples + 1), A);
     w.table_bytes = off;
     w.zero_begin = off;
-    w.state = off;       off = align_up(off + sizeof(SelState) * L, A);
-    w.hist = off;        off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
-    w.chunk_cnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
-    w.chunk_ccnt = off;  off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
-    w.mask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
-    w.cmask = off;       off = align_up(off + sizeof(uint32_t) * words, A);
+    w.state = off;        off = align_up(off + sizeof(SelState) * L, A);
+    w.hist = off;         off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
+    w.chunk_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.mask = off;         off = align_up(off + sizeof(uint32_t) * words, A);
+    w.cmask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
     w.zero_end = off;
-    w.nsi = off;         off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
+    w.slot_cnt = off;     off = align_up(off + sizeof(uint32_t) * plan->n_tiles_all, A);
+    w.slot_ent = off;     off = align_up(off + sizeof(uint64_t) * kSlotCap * size_t(plan->n_tiles_all), A);
+    w.nsi = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
     w.total = off;
 
     plan->table.assign(w.table_bytes, 0);
@@ -112,6 +153,11 @@ int build_tables(rsdgc_plan_s *plan) {
                 sizeof(DirEntry) * plan->chunk_dir.size());
     std::memcpy(plan->table.data() + w.all_tile_dir, plan->all_tile_dir.data(),
                 sizeof(DirEntry) * plan->all_tile_dir.size());
+    std::memcpy(plan->table.data() + w.group_dir, plan->group_dir.data(),
+                sizeof(DirEntry) * plan->group_dir.size());
+    if (!plan->samples.empty())
+        std::memcpy(plan->table.data() + w.samples, plan->samples.data(),
+                    sizeof(SampleEntry) * plan->samples.size());
     ++plan->version;
     return RSDGC_OK;
 }
@@ -166,6 +212,17 @@ int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio) {
         if (!ratio_ok(keep_ratio[l])) return RSDGC_EINVAL;
     try {
         plan->ratio.assign(keep_ratio, keep_ratio + plan->n_layers);
+        build_tables(plan);
+    } catch (const std::bad_alloc &) {
+        return RSDGC_ENOMEM;
+    }
+    return RSDGC_OK;
+}
+
+int rsdgc_plan_set_path(rsdgc_plan_t *plan, int32_t path) {
+    if (!plan || (path != RSDGC_PATH_AUTO && path != RSDGC_PATH_FULL_MAP)) return RSDGC_EINVAL;
+    try {
+        plan->allow_candidates = (path == RSDGC_PATH_AUTO);
         build_tables(plan);
     } catch (const std::bad_alloc &) {
         return RSDGC_ENOMEM;

@@ -14,9 +14,11 @@ from . import binding
 class Session:
     def __init__(self, shapes, p: int, alpha: float, ratios: Sequence[float],
                  p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0",
-                 want_centres: bool = True):
+                 want_centres: bool = True, path: int = binding.RSDGC_PATH_AUTO):
         self.shapes = [(int(r), int(c)) for r, c in shapes]
         self.plan = binding.rsdgc_plan(self.shapes, p, alpha, ratios, p_per_layer)
+        if path != binding.RSDGC_PATH_AUTO:
+            binding.rsdgc_plan_set_path(self.plan, path)
         self.device = torch.device(device)
         n = self.plan.total_elems
         L = self.plan.n_layers

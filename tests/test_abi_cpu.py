@@ -131,7 +131,7 @@ def test_queries_on_bad_arguments_and_strerror():
     assert lib.rsdgc_strerror(0) == b"ok"
     assert b"invalid" in lib.rsdgc_strerror(binding.RSDGC_EINVAL)
     assert lib.rsdgc_strerror(-99) == b"unknown error code"
-    assert lib.rsdgc_stage_name(1) == b"nsi" and lib.rsdgc_stage_name(99) == b""
+    assert lib.rsdgc_stage_name(2) == b"capture" and lib.rsdgc_stage_name(99) == b""
     lib.rsdgc_plan_destroy(None)     # harmless
 
 

@@ -10,16 +10,20 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 
-def _session(shapes, p, alpha, ratios, p_per_layer=None):
+AUTO, FULL_MAP = 0, 1     # ranking paths of the library (same result, different traffic)
+
+
+def _session(shapes, p, alpha, ratios, p_per_layer=None, path=AUTO):
     from paper_2312_17530_amd.session import Session
-    return Session(shapes, p, alpha, ratios, p_per_layer)
+    return Session(shapes, p, alpha, ratios, p_per_layer, path=path)
 
 
-def run_and_check(shapes, p_list, alpha, ratios, grads_per_iter, name="case", check_nsi=True):
+def run_and_check(shapes, p_list, alpha, ratios, grads_per_iter, name="case", check_nsi=True,
+                  path=AUTO):
     """Runs every iteration on GPU and oracle from identical state and applies the parity rule.
     Returns (number of layer-iterations compared, number that matched the oracle exactly)."""
     import torch
-    sess = _session(shapes, p_list[0], alpha, ratios, p_list)
+    sess = _session(shapes, p_list[0], alpha, ratios, p_list, path)
     L = len(shapes)
     resid = [np.zeros(sh, dtype=np.float32) for sh in shapes]
     n_cmp = n_exact = 0
@@ -101,20 +105,54 @@ def test_degenerate_inputs_follow_index_tie_break():
         assert ex == n, "exact ties must resolve exactly like the oracle (lower index wins)"
 
 
-def test_config1_resnet18_two_iterations():
+@pytest.mark.parametrize("path", [AUTO, FULL_MAP])
+def test_config1_resnet18_two_iterations(path):
     w = synth.config(1)
     its = [synth.gradients(w, t) for t in range(w.iterations)]
-    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name)
+    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name, path=path)
     assert n == 2 * w.n_layers
     assert ex >= n - 2
 
 
-def test_config2_resnet50_dynamic_ratios():
+@pytest.mark.parametrize("path", [AUTO, FULL_MAP])
+def test_config2_resnet50_dynamic_ratios(path):
     w = synth.config(2)
     its = [synth.gradients(w, 0)]
-    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name)
+    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name, path=path)
     assert n == w.n_layers
     assert ex >= n - 2
+
+
+def _tile_is_sampled(t):
+    """The library samples one tile in 16 by this hash of the tile's index inside its layer."""
+    return ((t * 2654435761) & 0xFFFFFFFF) >> 28 == 0
+
+
+def test_candidate_path_falls_back_when_its_bound_fails():
+    """Large layers rank only the centres above a bound estimated from sampled tiles.  Inputs
+    built to defeat that estimate must still give the oracle's result (through the full map)."""
+    R, C = 512, 4608                      # 16 x 36 tiles of 32 x 128
+    rng = np.random.default_rng(123)
+    base = (rng.standard_normal((R, C)) * 1e-3).astype(np.float32)
+    tiles_x = C // 128
+    # (a) the sampled tiles carry far larger values than the rest: the bound comes out too high
+    hot_sampled = base.copy()
+    # (b) one tile holds thousands of top-ranked centres: its candidate slot overflows
+    hot_tile = base.copy()
+    hot_tile[64:96, 256:384] *= np.float32(50.0)
+    n_sampled = 0
+    for t in range((R // 32) * tiles_x):
+        if _tile_is_sampled(t):
+            n_sampled += 1
+            tr, tc = divmod(t, tiles_x)
+            hot_sampled[tr * 32:(tr + 1) * 32, tc * 128:(tc + 1) * 128] *= np.float32(30.0)
+    assert n_sampled >= 8, "the layer must be large enough to take the candidate path"
+    # (c) a well-behaved layer next to them keeps using the candidate path
+    shapes = [(R, C), (R, C), (R, C)]
+    grads = [hot_sampled, hot_tile, base]
+    for ratios in ([0.3, 0.02, 0.02], [0.02, 0.2, 0.01]):
+        n, ex = run_and_check(shapes, [3, 3, 3], 0.5, ratios, [grads, grads], "fallback")
+        assert n == 6 and ex >= 5
 
 
 def test_set_ratios_and_determinism():
