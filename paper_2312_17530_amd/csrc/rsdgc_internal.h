@@ -16,6 +16,7 @@ constexpr int kHistBins = 4096;      // widest radix digit (12 bits)
 constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements
 constexpr int kSlotCap = 256;        // candidate centres one tile can record
 constexpr int kSlotGroup = 64;       // tile slots per workgroup in the candidate passes
+constexpr int kCandBins = 256;       // 12-bit score buckets above the bound that a capture workgroup counts
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 
 // How the k_l-th largest score of a layer is found (per layer, decided on the device).
@@ -50,17 +51,19 @@ struct LayerDev {
 };
 static_assert(sizeof(LayerDev) == 104, "LayerDev layout");
 
-// Per-layer selection state (32 bytes), lives in the workspace.
+// Per-layer selection state (40 bytes), lives in the workspace.
 struct SelState {
     unsigned long long T;   // threshold on the composite key (score bits << 32 | ~index)
     uint32_t k_rem;         // centres still to take inside the current bucket
     uint32_t done;          // threshold is final
     uint32_t mode;          // LayerMode
     uint32_t hint_key;      // candidate bound (score bits), candidate path only
+    uint32_t overflow;      // candidate path: a tile slot or the histogram window overflowed
     uint32_t n_centres;     // centres selected (only counted when centre lists are requested)
     uint32_t n_pairs;       // pairs emitted
+    uint32_t pad_;
 };
-static_assert(sizeof(SelState) == 32, "SelState layout");
+static_assert(sizeof(SelState) == 40, "SelState layout");
 
 // Directory entry used to map a workgroup id to a layer by binary search.
 struct DirEntry {

@@ -44,6 +44,7 @@ int hip_fail(hipError_t e, const char *what) {
 // most significant first.  Scores are non-negative floats, so their bit pattern
 // orders like the value; ~index makes the lower index the larger key.
 constexpr int kLevels = 6;
+constexpr uint32_t kNumCUs = 256;   // MI355X
 __host__ __device__ constexpr int level_shift(int lv) {
     return lv == 0 ? 51 : lv == 1 ? 41 : lv == 2 ? 32 : lv == 3 ? 21 : lv == 4 ? 10 : 0;
 }
@@ -113,8 +114,10 @@ __global__ void k_init_state(const LayerDev *__restrict__ layers, SelState *__re
     s.done = L.k == 0 ? 1u : 0u;
     s.mode = L.k == 0 ? kModeSkip : (L.large ? kModeCandidates : kModeFullMap);
     s.hint_key = 0;
+    s.overflow = 0;
     s.n_centres = 0;
     s.n_pairs = 0;
+    s.pad_ = 0;
     state[l] = s;
 }
 
@@ -158,17 +161,23 @@ struct NsiArgs {
     float *nsi_out;               // score map (kPassMapOnly, kPassFullMap)
     uint32_t *hist;               // [n_layers][kHistBins]
     const SelState *state;
+    SelState *state_rw;           // same array; only the overflow flag is written (capture)
     uint32_t *slot_cnt;           // [n_tiles_all]
     unsigned long long *slot_ent; // [n_tiles_all][kSlotCap]
     double alpha;
 };
 
-// One workgroup = one 32 x 128 tile of one layer.  The tile of v = r + g plus a halo of
+// Work unit: one 32 x 128 tile of one layer.  The tile of v = r + g plus a halo of
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
 // down 8 rows of 2 adjacent columns, keeping per-row horizontal sums of |w|, w and w^2
 // (double) for the last P rows in registers.  The variance is formed as
 // (P^2 * sum w^2 - (sum w)^2) / P^4 in double, which is exactly 0 for a constant window
 // and keeps equal windows at equal scores wherever they lie.
+//
+// A workgroup walks a contiguous range of tiles (ranges are laid out so that each XCD gets
+// one contiguous stretch of the launch: neighbouring tiles share halo rows in one L2).
+// Its LDS histogram is flushed to the layer's global histogram only when the layer
+// changes or the range ends, so a launch issues few same-address global atomics.
 template <int P, int PASS>
 __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     constexpr int H = (P - 1) / 2;
@@ -177,182 +186,229 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     constexpr int PITCH = kTileCols + 2 * PADL;   // 136 floats
     constexpr int VEC_PER_ROW = PITCH / 4;        // 34
     constexpr int RPT = 8;                        // output rows per thread
-    constexpr bool HIST = PASS == kPassFullMap || PASS == kPassSample;
     constexpr bool MAP = PASS == kPassMapOnly || PASS == kPassFullMap;
     constexpr bool CAPTURE = PASS == kPassCapture;
+    constexpr bool FULLHIST = PASS == kPassFullMap || PASS == kPassSample;
+    constexpr int NBINS = FULLHIST ? kHistBins : (CAPTURE ? kCandBins : 1);
     __shared__ __attribute__((aligned(16))) float tile[ROWS * PITCH];
-    __shared__ uint32_t lhist[HIST ? kHistBins : 1];
+    __shared__ uint32_t lhist[NBINS];
     __shared__ unsigned long long cand[CAPTURE ? kSlotCap : 1];
     __shared__ uint32_t ncand;
 
     const int tid = threadIdx.x;
-    uint32_t l, local;
-    if (PASS == kPassSample) {
-        const SampleEntry se = a.samples[blockIdx.x];
-        l = se.layer;
-        local = se.local_tile;
-    } else {
-        const uint32_t t_id = xcd_contiguous(blockIdx.x, a.n_tiles);
-        const uint32_t e = dir_lookup(a.dir, a.n_dir, t_id);
-        l = a.dir[e].layer;
-        local = t_id - a.dir[e].begin;
-    }
-    uint32_t hint_key = 0;
-    if (PASS != kPassMapOnly) {
-        const SelState st = a.state[l];
-        if (PASS == kPassFullMap && st.mode != kModeFullMap) return;
-        if ((PASS == kPassCapture || PASS == kPassSample) && st.mode != kModeCandidates) return;
-        hint_key = st.hint_key;
-    }
-    const LayerDev L = a.layers[l];
-    const int trow = static_cast<int>(local / L.tiles_x);
-    const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
-    const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
-    const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
-    const float *__restrict__ g = a.grad + L.elem_off;
-    const float *__restrict__ r = a.resid ? a.resid + L.elem_off : nullptr;
+    // grid-stride share of the launch's work items (tiles, or sampled tiles): at any moment
+    // the resident workgroups work on one compact stretch of tiles, so neighbouring tiles'
+    // halo rows are still in cache; inside a stretch each XCD takes one contiguous part
+    const uint32_t n_items = a.n_tiles;
+    const uint32_t first = xcd_contiguous(blockIdx.x, gridDim.x), stride = gridDim.x, last = n_items;
+    if (first >= last) return;
 
-    if (HIST) {
-        for (int b = tid; b < kHistBins; b += 256) lhist[b] = 0;
-    }
+    if (NBINS > 1)
+        for (int b = tid; b < NBINS; b += 256) lhist[b] = 0;
     if (CAPTURE && tid == 0) ncand = 0;
-
-    // ---- load v = r + g for the tile and its halo; zero outside the matrix
-    if ((C & 3) == 0) {
-        constexpr int NVEC = ROWS * VEC_PER_ROW;
-        constexpr int ITER = (NVEC + 255) / 256;
-        float4 gv[ITER], rv[ITER];
-#pragma unroll
-        for (int it = 0; it < ITER; ++it) {
-            const int s = tid + it * 256;
-            const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
-            const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
-            gv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            rv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (s < NVEC && x >= 0 && x < R && y >= 0 && y < C) {
-                const size_t off = static_cast<size_t>(x) * C + y;
-                gv[it] = *reinterpret_cast<const float4 *>(g + off);
-                if (r) rv[it] = *reinterpret_cast<const float4 *>(r + off);
-            }
-        }
-#pragma unroll
-        for (int it = 0; it < ITER; ++it) {
-            const int s = tid + it * 256;
-            if (s < NVEC) {
-                float4 v;
-                v.x = rv[it].x + gv[it].x;
-                v.y = rv[it].y + gv[it].y;
-                v.z = rv[it].z + gv[it].z;
-                v.w = rv[it].w + gv[it].w;
-                *reinterpret_cast<float4 *>(&tile[s * 4]) = v;   // s*4 == rr*PITCH + 4*j4
-            }
-        }
-    } else {
-        for (int s = tid; s < ROWS * PITCH; s += 256) {
-            const int rr = s / PITCH, j = s - rr * PITCH;
-            const int x = x0 - H + rr, y = y0 - PADL + j;
-            float v = 0.f;
-            if (x >= 0 && x < R && y >= 0 && y < C) {
-                const size_t off = static_cast<size_t>(x) * C + y;
-                v = (r ? r[off] : 0.f) + g[off];
-            }
-            tile[s] = v;
-        }
-    }
     __syncthreads();
 
-    // ---- window statistics
+    uint32_t e = 0;                       // directory entry of the current layer
+    if (PASS != kPassSample) e = dir_lookup(a.dir, a.n_dir, first);
+    uint32_t cur_l = 0xffffffffu;         // layer whose counts sit in lhist
+    uint32_t hint_key = 0, hint_bin = 0;
+    bool active = true;
+    LayerDev L;
+
+    const double n = static_cast<double>(P * P);
+    const double ca = a.alpha / n;        // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
+    const double cb = (1.0 - a.alpha) / n;
     const int tx = tid & 63, ty = tid >> 6;
     const int c0 = 2 * tx;
     const int row_base = ty * RPT;
-    const double n = static_cast<double>(P * P);
-    const double ca = a.alpha / n;          // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
-    const double cb = (1.0 - a.alpha) / n;
-    const bool pair_store = (C & 1) == 0;
 
-    double hs_a[P][2], hs_s[P][2], hs_q[P][2];
-#pragma unroll
-    for (int i = 0; i < RPT + 2 * H; ++i) {
-        const float *row = &tile[(row_base + i) * PITCH + PADL + c0 - H];
-        double w[2 * H + 2];
-#pragma unroll
-        for (int j = 0; j < 2 * H + 2; ++j) w[j] = static_cast<double>(row[j]);
-        const int slot = i % P;
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            double sa = fabs(w[c]), ss = w[c], sq = w[c] * w[c];
-#pragma unroll
-            for (int j = 1; j < P; ++j) {
-                sa += fabs(w[c + j]);
-                ss += w[c + j];
-                sq = fma(w[c + j], w[c + j], sq);
-            }
-            hs_a[slot][c] = sa;
-            hs_s[slot][c] = ss;
-            hs_q[slot][c] = sq;
+    for (uint32_t t = first; t < last; t += stride) {
+        uint32_t l, local;
+        if (PASS == kPassSample) {
+            const SampleEntry se = a.samples[t];
+            l = se.layer;
+            local = se.local_tile;
+        } else {
+            while (t >= a.dir[e + 1].begin) ++e;
+            l = a.dir[e].layer;
+            local = t - a.dir[e].begin;
         }
-        if (i >= 2 * H) {
-            const int o = i - 2 * H;   // output row inside the thread's strip
-            float out[2];
+        if (l != cur_l) {
+            if (NBINS > 1 && cur_l != 0xffffffffu && active) {   // flush the finished layer's counts
+                uint32_t *__restrict__ gh = a.hist + static_cast<size_t>(cur_l) * kHistBins + hint_bin;
+                for (int b = tid; b < NBINS; b += 256) {
+                    const uint32_t c = lhist[b];
+                    if (c) { atomicAdd(&gh[b], c); lhist[b] = 0; }
+                }
+                __syncthreads();
+            }
+            cur_l = l;
+            L = a.layers[l];
+            active = true;
+            hint_key = 0;
+            hint_bin = 0;
+            if (PASS != kPassMapOnly) {
+                const SelState st = a.state[l];
+                if (PASS == kPassFullMap) active = st.mode == kModeFullMap;
+                else active = st.mode == kModeCandidates;
+                if (CAPTURE) { hint_key = st.hint_key; hint_bin = hint_key >> 19; }
+            }
+        }
+        if (!active) {                    // skip the rest of this layer
+            if (PASS != kPassSample) {
+                const uint32_t nb = a.dir[e + 1].begin;          // first tile of the next layer
+                t += (nb - t + stride - 1) / stride * stride - stride;   // loop increment adds the last stride
+            }
+            continue;
+        }
+
+        const int trow = static_cast<int>(local / L.tiles_x);
+        const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
+        const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
+        const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
+        const float *__restrict__ g = a.grad + L.elem_off;
+        const float *__restrict__ r = a.resid ? a.resid + L.elem_off : nullptr;
+
+        // ---- load v = r + g for the tile and its halo; zero outside the matrix
+        if ((C & 3) == 0) {
+            constexpr int NVEC = ROWS * VEC_PER_ROW;
+            constexpr int ITER = (NVEC + 255) / 256;
+            float4 gv[ITER], rv[ITER];
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                const int s = tid + it * 256;
+                const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
+                const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
+                gv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                rv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (s < NVEC && x >= 0 && x < R && y >= 0 && y < C) {
+                    const size_t off = static_cast<size_t>(x) * C + y;
+                    gv[it] = *reinterpret_cast<const float4 *>(g + off);
+                    if (r) rv[it] = *reinterpret_cast<const float4 *>(r + off);
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                const int s = tid + it * 256;
+                if (s < NVEC) {
+                    float4 v;
+                    v.x = rv[it].x + gv[it].x;
+                    v.y = rv[it].y + gv[it].y;
+                    v.z = rv[it].z + gv[it].z;
+                    v.w = rv[it].w + gv[it].w;
+                    *reinterpret_cast<float4 *>(&tile[s * 4]) = v;   // s*4 == rr*PITCH + 4*j4
+                }
+            }
+        } else {
+            for (int s = tid; s < ROWS * PITCH; s += 256) {
+                const int rr = s / PITCH, j = s - rr * PITCH;
+                const int x = x0 - H + rr, y = y0 - PADL + j;
+                float v = 0.f;
+                if (x >= 0 && x < R && y >= 0 && y < C) {
+                    const size_t off = static_cast<size_t>(x) * C + y;
+                    v = (r ? r[off] : 0.f) + g[off];
+                }
+                tile[s] = v;
+            }
+        }
+        __syncthreads();
+
+        // ---- window statistics
+        const bool pair_store = (C & 1) == 0;
+        double hs_a[P][2], hs_s[P][2], hs_q[P][2];
+#pragma unroll
+        for (int i = 0; i < RPT + 2 * H; ++i) {
+            const float *row = &tile[(row_base + i) * PITCH + PADL + c0 - H];
+            double w[2 * H + 2];
+#pragma unroll
+            for (int j = 0; j < 2 * H + 2; ++j) w[j] = static_cast<double>(row[j]);
+            const int slot = i % P;
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
-                double sa = hs_a[o % P][c], ss = hs_s[o % P][c], sq = hs_q[o % P][c];
+                double sa = fabs(w[c]), ss = w[c], sq = w[c] * w[c];
 #pragma unroll
                 for (int j = 1; j < P; ++j) {
-                    sa += hs_a[(o + j) % P][c];
-                    ss += hs_s[(o + j) % P][c];
-                    sq += hs_q[(o + j) % P][c];
+                    sa += fabs(w[c + j]);
+                    ss += w[c + j];
+                    sq = fma(w[c + j], w[c + j], sq);
                 }
-                out[c] = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
+                hs_a[slot][c] = sa;
+                hs_s[slot][c] = ss;
+                hs_q[slot][c] = sq;
             }
-            const int x = x0 + row_base + o, y = y0 + c0;
-            if (x < R && y < C) {
-                const bool two = y + 1 < C;
-                const uint32_t key0 = __float_as_uint(out[0]) & 0x7fffffffu;
-                const uint32_t key1 = __float_as_uint(out[1]) & 0x7fffffffu;
-                if (MAP) {
-                    const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
-                    if (two && pair_store) {
-                        *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[1]);
-                    } else {
-                        a.nsi_out[off] = out[0];
-                        if (two) a.nsi_out[off + 1] = out[1];
+            if (i >= 2 * H) {
+                const int o = i - 2 * H;   // output row inside the thread's strip
+                float out[2];
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    double sa = hs_a[o % P][c], ss = hs_s[o % P][c], sq = hs_q[o % P][c];
+#pragma unroll
+                    for (int j = 1; j < P; ++j) {
+                        sa += hs_a[(o + j) % P][c];
+                        ss += hs_s[(o + j) % P][c];
+                        sq += hs_q[(o + j) % P][c];
                     }
+                    out[c] = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
                 }
-                if (HIST) {
-                    atomicAdd(&lhist[key0 >> 19], 1u);
-                    if (two) atomicAdd(&lhist[key1 >> 19], 1u);
-                }
-                if (CAPTURE) {
-                    const uint32_t i0 = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
-                    if (key0 >= hint_key) {
-                        const uint32_t pos = atomicAdd(&ncand, 1u);
-                        if (pos < kSlotCap) cand[pos] = composite_key(key0, i0);
+                const int x = x0 + row_base + o, y = y0 + c0;
+                if (x < R && y < C) {
+                    const bool two = y + 1 < C;
+                    const uint32_t key0 = __float_as_uint(out[0]) & 0x7fffffffu;
+                    const uint32_t key1 = __float_as_uint(out[1]) & 0x7fffffffu;
+                    if (MAP) {
+                        const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
+                        if (two && pair_store) {
+                            *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[1]);
+                        } else {
+                            a.nsi_out[off] = out[0];
+                            if (two) a.nsi_out[off + 1] = out[1];
+                        }
                     }
-                    if (two && key1 >= hint_key) {
-                        const uint32_t pos = atomicAdd(&ncand, 1u);
-                        if (pos < kSlotCap) cand[pos] = composite_key(key1, i0 + 1);
+                    if (FULLHIST) {
+                        atomicAdd(&lhist[key0 >> 19], 1u);
+                        if (two) atomicAdd(&lhist[key1 >> 19], 1u);
+                    }
+                    if (CAPTURE) {
+                        const uint32_t i0 = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+                        if (key0 >= hint_key) {
+                            const uint32_t pos = atomicAdd(&ncand, 1u);
+                            if (pos < kSlotCap) cand[pos] = composite_key(key0, i0);
+                            atomicAdd(&lhist[min((key0 >> 19) - hint_bin, static_cast<uint32_t>(kCandBins - 1))], 1u);
+                            if ((key0 >> 19) - hint_bin >= static_cast<uint32_t>(kCandBins - 1)) a.state_rw[l].overflow = 1u;
+                        }
+                        if (two && key1 >= hint_key) {
+                            const uint32_t pos = atomicAdd(&ncand, 1u);
+                            if (pos < kSlotCap) cand[pos] = composite_key(key1, i0 + 1);
+                            atomicAdd(&lhist[min((key1 >> 19) - hint_bin, static_cast<uint32_t>(kCandBins - 1))], 1u);
+                            if ((key1 >> 19) - hint_bin >= static_cast<uint32_t>(kCandBins - 1)) a.state_rw[l].overflow = 1u;
+                        }
                     }
                 }
             }
+        }
+        __syncthreads();                  // all reads of the tile (and of cand) are complete
+
+        if (CAPTURE) {
+            const uint32_t slot = L.tile_begin_all + local;
+            const uint32_t nc = ncand;
+            unsigned long long *__restrict__ dst = a.slot_ent + static_cast<size_t>(slot) * kSlotCap;
+            for (uint32_t i = tid; i < min(nc, static_cast<uint32_t>(kSlotCap)); i += 256) dst[i] = cand[i];
+            if (tid == 0) {
+                a.slot_cnt[slot] = min(nc, static_cast<uint32_t>(kSlotCap));
+                if (nc > static_cast<uint32_t>(kSlotCap)) a.state_rw[l].overflow = 1u;
+            }
+            __syncthreads();
+            if (tid == 0) ncand = 0;
+            // the next tile's first barrier orders this reset before any new append
         }
     }
 
-    if (HIST) {
-        __syncthreads();
-        uint32_t *__restrict__ gh = a.hist + static_cast<size_t>(l) * kHistBins;
-        for (int b = tid; b < kHistBins; b += 256) {
+    if (NBINS > 1 && cur_l != 0xffffffffu && active) {
+        uint32_t *__restrict__ gh = a.hist + static_cast<size_t>(cur_l) * kHistBins + hint_bin;
+        for (int b = tid; b < NBINS; b += 256) {
             const uint32_t c = lhist[b];
             if (c) atomicAdd(&gh[b], c);
         }
-    }
-    if (CAPTURE) {
-        __syncthreads();
-        const uint32_t slot = L.tile_begin_all + local;
-        const uint32_t nc = ncand;                 // may exceed kSlotCap: the validator sees that
-        if (tid == 0) a.slot_cnt[slot] = nc;
-        unsigned long long *__restrict__ dst = a.slot_ent + static_cast<size_t>(slot) * kSlotCap;
-        for (uint32_t i = tid; i < min(nc, static_cast<uint32_t>(kSlotCap)); i += 256) dst[i] = cand[i];
     }
 }
 
@@ -401,34 +457,30 @@ __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layer
 
 // ------------------------------------------------------------- validate --
 // One workgroup per candidate-mode layer: the recorded candidates are usable only if no
-// tile overflowed its slot and at least k_l centres were recorded (then the k_l best of
-// the layer are all among them).  Otherwise the layer falls back to the full map.
+// tile slot and no histogram window overflowed and at least k_l centres were recorded
+// (then the k_l best of the layer are all among them).  Otherwise the layer falls back to
+// the full map, and its histogram is cleared for that pass.
 __global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ layers,
                                                   SelState *__restrict__ state,
-                                                  const uint32_t *__restrict__ slot_cnt) {
+                                                  uint32_t *__restrict__ hist) {
     __shared__ uint32_t wave_tot[4];
-    __shared__ uint32_t overflow;
     const int l = blockIdx.x, tid = threadIdx.x;
     const SelState st = state[l];
     if (st.mode != kModeCandidates) return;
-    const LayerDev L = layers[l];
-    if (tid == 0) overflow = 0;
+    uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
+    uint32_t own = 0;
+    for (int b = tid; b < kHistBins; b += 256) own += h[b];
+    const uint32_t total = block_scan_incl(own, wave_tot);
+    __shared__ uint32_t fail;
+    if (tid == 255) fail = (st.overflow || total < layers[l].k) ? 1u : 0u;
     __syncthreads();
-    unsigned long long sum = 0;
-    bool over = false;
-    for (uint32_t t = tid; t < L.n_tiles; t += 256) {
-        const uint32_t c = slot_cnt[L.tile_begin_all + t];
-        over = over || c > static_cast<uint32_t>(kSlotCap);
-        sum += c;
-    }
-    if (over) overflow = 1;
-    const uint32_t capped = sum > 0xffffffffull ? 0xffffffffu : static_cast<uint32_t>(sum);
-    // totals above 2^32 cannot occur (G_l < 2^32); the scan is on 32-bit partial sums
-    const uint32_t incl = block_scan_incl(capped, wave_tot);
-    if (tid == 255 && (overflow || incl < L.k)) {
-        SelState ns = st;
-        ns.mode = kModeFullMap;
-        state[l] = ns;
+    if (fail) {
+        for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
+        if (tid == 0) {
+            SelState ns = st;
+            ns.mode = kModeFullMap;
+            state[l] = ns;
+        }
     }
 }
 
@@ -924,6 +976,16 @@ int upload_tables(rsdgc_plan_s *plan, void *workspace, hipStream_t stream) {
     return RSDGC_OK;
 }
 
+// Workgroups of 256 threads of `kernel` that the whole device keeps resident at once: a
+// persistent launch of exactly this many workgroups runs as a single balanced wave.
+template <typename K>
+uint32_t resident_workgroups(K kernel) {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess || per_cu < 1)
+        per_cu = 2;
+    return kNumCUs * static_cast<uint32_t>(per_cu);
+}
+
 // One launch of the NSI kernel per neighbourhood side.  kPassSample runs over the sampled
 // tiles of the large layers, every other pass over all tiles (workgroups of layers that
 // are in another mode leave at once).
@@ -937,6 +999,7 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
     a.nsi_out = nsi_out;
     a.hist = reinterpret_cast<uint32_t *>(ws + plan->ws.hist);
     a.state = reinterpret_cast<const SelState *>(ws + plan->ws.state);
+    a.state_rw = reinterpret_cast<SelState *>(ws + plan->ws.state);
     a.slot_cnt = reinterpret_cast<uint32_t *>(ws + plan->ws.slot_cnt);
     a.slot_ent = reinterpret_cast<unsigned long long *>(ws + plan->ws.slot_ent);
     a.alpha = plan->alpha;
@@ -947,14 +1010,19 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
         a.n_dir = g.dir_count;
         a.n_tiles = g.n_tiles;
         a.samples = samples + g.sample_begin;
-        const uint32_t blocks = PASS == kPassSample ? g.n_samples : g.n_tiles;
-        if (blocks == 0) continue;
-        const dim3 grid(blocks), block(256);
+        // work items of this launch and the number of workgroups that share them
+        const uint32_t items = PASS == kPassSample ? g.n_samples : g.n_tiles;
+        if (items == 0) continue;
+        a.n_tiles = items;
+        const dim3 block(256);
         switch (g.p) {
-#define RSDGC_NSI_CASE(PP)                                                          \
-    case PP:                                                                        \
-        hipLaunchKernelGGL((k_nsi<PP, PASS>), grid, block, 0, stream, a);            \
-        break;
+#define RSDGC_NSI_CASE(PP)                                                                  \
+    case PP: {                                                                              \
+        static const uint32_t resident = resident_workgroups(k_nsi<PP, PASS>);              \
+        const dim3 grid(std::min<uint32_t>(items, resident));                               \
+        hipLaunchKernelGGL((k_nsi<PP, PASS>), grid, block, 0, stream, a);                    \
+        break;                                                                              \
+    }
             RSDGC_NSI_CASE(1)
             RSDGC_NSI_CASE(3)
             RSDGC_NSI_CASE(5)
@@ -1042,7 +1110,7 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
         marks.close(1);
         rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, stream);
         if (rc != RSDGC_OK) return rc;
-        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, slot_cnt);
+        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist);
         marks.close(2);
     } else {
         marks.close(1);
@@ -1052,16 +1120,14 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     if (rc != RSDGC_OK) return rc;
     marks.close(3);
 
-    // radix select; level 0 of the full-map layers was histogrammed by the NSI pass
+    // radix select; level 0 was histogrammed by the NSI passes
     for (int lv = 0; lv < kLevels; ++lv) {
-        const uint32_t n_map_blocks = lv == 0 ? 0u : n_chunks;
         const uint32_t n_slot_blocks = plan->any_large ? plan->n_slot_groups : 0u;
-        if (n_map_blocks + n_slot_blocks > 0)
-            hipLaunchKernelGGL(k_refine, dim3(n_map_blocks + n_slot_blocks), dim3(256), 0, stream,
-                               layers, chunk_dir, group_dir, static_cast<uint32_t>(L), n_map_blocks,
+        if (lv > 0)
+            hipLaunchKernelGGL(k_refine, dim3(n_chunks + n_slot_blocks), dim3(256), 0, stream,
+                               layers, chunk_dir, group_dir, static_cast<uint32_t>(L), n_chunks,
                                state, hist, reinterpret_cast<const uint32_t *>(nsi), slot_cnt,
-                               slot_ent, level_shift(lv), level_bits(lv),
-                               lv == 0 ? 63 : level_shift(lv - 1));
+                               slot_ent, level_shift(lv), level_bits(lv), level_shift(lv - 1));
         hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(lv),
                            level_bits(lv));
     }
