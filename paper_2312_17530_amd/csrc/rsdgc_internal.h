@@ -17,6 +17,8 @@ constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements
 constexpr int kSlotCap = 256;        // candidate centres one tile can record
 constexpr int kSlotGroup = 64;       // tile slots per workgroup in the candidate passes
 constexpr int kCandBins = 256;       // 12-bit score buckets above the bound that a capture workgroup counts
+constexpr int kListMin = 8192;       // smallest threshold-bucket list of a layer (entries)
+constexpr int kListDiv = 32;         // ... or 1/32 of the layer, whichever is larger
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 
 // How the k_l-th largest score of a layer is found (per layer, decided on the device).
@@ -47,7 +49,9 @@ struct LayerDev {
     uint32_t n_groups;      // ceil(n_tiles / kSlotGroup)
     uint32_t hint_target;   // sampled scores wanted at or above the candidate bound
     uint32_t n_sampled;     // sampled tiles of the layer
-    uint32_t pad_[3];
+    uint32_t list_off;      // first entry of the layer's threshold-bucket list
+    uint32_t list_cap;      // its capacity
+    uint32_t pad_;
 };
 static_assert(sizeof(LayerDev) == 104, "LayerDev layout");
 
@@ -93,12 +97,14 @@ struct WsLayout {
     size_t hist = 0;         // uint32[n_layers][kHistBins]
     size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk, then their prefix
     size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk, then prefix
+    size_t list_cnt = 0;     // uint32[n_layers]  keys gathered from the threshold bucket
     size_t mask = 0;         // uint32[total_elems / 32]  kept-element bitmask
     size_t cmask = 0;        // uint32[total_elems / 32]  selected-centre bitmask
     size_t zero_end = 0;
     // not cleared
     size_t slot_cnt = 0;     // uint32[n_tiles_all]  candidates recorded per tile
     size_t slot_ent = 0;     // uint64[n_tiles_all][kSlotCap]  their composite keys
+    size_t list_ent = 0;     // uint64[sum list_cap]  composite keys of each layer's threshold bucket
     size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
     size_t total = 0;
 };

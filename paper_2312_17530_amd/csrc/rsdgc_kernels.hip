@@ -77,8 +77,9 @@ __device__ __forceinline__ uint32_t xcd_contiguous(uint32_t bid, uint32_t n) {
     return xcd * per + (xcd < rem ? xcd : rem) + slot;
 }
 
-// Inclusive scan over the 256 threads of a workgroup (4 waves of 64).
-__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_tot /*[4]*/) {
+// Inclusive scan over the NW * 64 threads of a workgroup.
+template <int NW>
+__device__ __forceinline__ uint32_t block_scan_incl_n(uint32_t v, uint32_t *wave_tot /*[NW]*/) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -89,11 +90,16 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_t
     __syncthreads();
     uint32_t add = 0;
 #pragma unroll
-    for (int w = 0; w < 3; ++w)
+    for (int w = 0; w < NW - 1; ++w)
         if (w < wave) add += wave_tot[w];
     const uint32_t r = v + add;
     __syncthreads();   // wave_tot may be reused by the caller
     return r;
+}
+
+// Inclusive scan over the 256 threads of a workgroup (4 waves of 64).
+__device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_tot /*[4]*/) {
+    return block_scan_incl_n<4>(v, wave_tot);
 }
 
 // ---------------------------------------------------------------- clear --
@@ -530,84 +536,322 @@ __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
     for (int b = tid; b < nb; b += 256) h[b] = 0;
 }
 
-// --------------------------------------------------------------- refine --
-// Histogram of the next digit over the keys that match the threshold prefix so far.
-// Workgroups [0, n_map_blocks) each take one 8192-element chunk of the score map of a
-// full-map layer; the rest each take kSlotGroup tile slots of a candidate-mode layer.
-__global__ __launch_bounds__(256) void k_refine(const LayerDev *__restrict__ layers,
+// --------------------------------------------------------------- gather --
+// After the first digit: the keys of each layer's threshold bucket (those whose top
+// 12 score bits equal the chosen digit) are copied into the layer's list, and their next
+// digit is histogrammed.  Workgroups [0, n_map_wgs) stride over the 8192-element chunks of
+// the score map (full-map layers); the others stride over the slot groups (candidate-mode
+// layers).  Matches are staged in LDS and appended with one atomic per flush.
+constexpr int kStage = 4096;
+
+struct GatherStage {
+    unsigned long long ent[kStage];
+    uint32_t hist1[1 << level_bits(1)];
+    uint32_t n;
+    uint32_t base;
+};
+
+// Appends the staged keys to the layer's list; with_hist also adds the staged second-digit
+// counts to the layer's global histogram (done once per layer per workgroup).
+__device__ __forceinline__ void gather_flush(GatherStage &st, const LayerDev &L,
+                                             uint32_t *__restrict__ list_cnt, uint32_t l,
+                                             unsigned long long *__restrict__ list_ent,
+                                             uint32_t *__restrict__ hist, bool with_hist) {
+    __syncthreads();
+    const uint32_t n = st.n;
+    if (n != 0) {                          // uniform
+        if (threadIdx.x == 0) st.base = atomicAdd(&list_cnt[l], n);
+        __syncthreads();
+        const uint32_t base = st.base;
+        for (uint32_t i = threadIdx.x; i < n; i += 256)
+            if (base + i < L.list_cap) list_ent[static_cast<size_t>(L.list_off) + base + i] = st.ent[i];
+        __syncthreads();
+        if (threadIdx.x == 0) st.n = 0;
+    }
+    if (with_hist) {
+        uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins;
+        for (int b = threadIdx.x; b < (1 << level_bits(1)); b += 256) {
+            const uint32_t c = st.hist1[b];
+            if (c) { atomicAdd(&gh[b], c); st.hist1[b] = 0; }
+        }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ layers,
                                                 const DirEntry *__restrict__ chunk_dir,
                                                 const DirEntry *__restrict__ group_dir,
-                                                uint32_t n_layers, uint32_t n_map_blocks,
+                                                uint32_t n_layers, uint32_t n_map_wgs,
+                                                uint32_t n_chunks, uint32_t n_groups,
                                                 const SelState *__restrict__ state,
-                                                uint32_t *__restrict__ hist,
                                                 const uint32_t *__restrict__ keys,
                                                 const uint32_t *__restrict__ slot_cnt,
                                                 const unsigned long long *__restrict__ slot_ent,
-                                                int shift, int bits, int shift_prev) {
-    __shared__ uint32_t lh[kHistBins];
-    __shared__ uint32_t cnts[kSlotGroup];
+                                                uint32_t *__restrict__ list_cnt,
+                                                unsigned long long *__restrict__ list_ent,
+                                                uint32_t *__restrict__ hist) {
+    __shared__ GatherStage stage;
+    __shared__ uint32_t pref[kSlotGroup + 1];
     const int tid = threadIdx.x;
-    const int nb = 1 << bits;
-    uint32_t l;
-    if (blockIdx.x < n_map_blocks) {
-        const uint32_t c = blockIdx.x;
-        l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
-        const SelState st = state[l];
-        if (st.done || st.mode != kModeFullMap) return;
-        const LayerDev L = layers[l];
-        for (int b = tid; b < nb; b += 256) lh[b] = 0;
-        __syncthreads();
-        const uint32_t start = (c - L.chunk_begin) * kChunk;
-        const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-        const uint32_t *__restrict__ src = keys + L.elem_off + start;
-        const unsigned long long want = st.T >> shift_prev;
-#pragma unroll 2
-        for (int j = 0; j < kChunk / 1024; ++j) {
-            const uint32_t e = j * 1024 + 4 * tid;
-            if (e >= len) break;
-            uint32_t kk[4] = {0, 0, 0, 0};
-            if (e + 3 < len) {
-                const uint4 q = *reinterpret_cast<const uint4 *>(src + e);
-                kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
-            } else {
-                for (uint32_t q = 0; q < 4 && e + q < len; ++q) kk[q] = src[e + q];
-            }
+    const bool is_map = blockIdx.x < n_map_wgs;
+    const uint32_t first = is_map ? blockIdx.x : blockIdx.x - n_map_wgs;
+    const uint32_t stride = is_map ? n_map_wgs : gridDim.x - n_map_wgs;
+    const uint32_t n_items = is_map ? n_chunks : n_groups;
+    const DirEntry *__restrict__ dir = is_map ? chunk_dir : group_dir;
+    if (first >= n_items) return;
+    if (tid == 0) stage.n = 0;
+    for (int b = tid; b < (1 << level_bits(1)); b += 256) stage.hist1[b] = 0;
+    __syncthreads();
+    constexpr int shift1 = level_shift(1);
+    constexpr uint32_t mask1 = (1u << level_bits(1)) - 1u;
+
+    uint32_t e = dir_lookup(dir, n_layers, first);
+    uint32_t cur_l = 0xffffffffu;
+    bool active = false;
+    uint32_t digit0 = 0;
+    LayerDev L;
+    for (uint32_t it = first; it < n_items; it += stride) {
+        while (it >= dir[e + 1].begin) ++e;
+        const uint32_t l = dir[e].layer;
+        if (l != cur_l) {
+            if (active) gather_flush(stage, L, list_cnt, cur_l, list_ent, hist, true);
+            cur_l = l;
+            L = layers[l];
+            const SelState st = state[l];
+            active = !st.done && st.mode == (is_map ? kModeFullMap : kModeCandidates);
+            digit0 = static_cast<uint32_t>(st.T >> level_shift(0));
+        }
+        if (!active) {                     // on to this workgroup's first item of the next layer
+            const uint32_t nb = dir[e + 1].begin;
+            it += (nb - it + stride - 1) / stride * stride - stride;
+            continue;
+        }
+        if (is_map) {
+            const uint32_t start = (it - L.chunk_begin) * kChunk;
+            const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+            const uint32_t *__restrict__ src = keys + L.elem_off + start;
+            for (int j = 0; j < kChunk / 1024; ++j) {
+                if (static_cast<uint32_t>(j) * 1024u >= len) break;       // uniform
+                __syncthreads();
+                if (stage.n + 1024u > static_cast<uint32_t>(kStage))
+                    gather_flush(stage, L, list_cnt, l, list_ent, hist, false);
+                const uint32_t e4 = j * 1024 + 4 * tid;
+                if (e4 < len) {
+                    uint32_t kk[4] = {0, 0, 0, 0};
+                    if (e4 + 3 < len) {
+                        const uint4 q = *reinterpret_cast<const uint4 *>(src + e4);
+                        kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
+                    } else {
+                        for (uint32_t q = 0; q < 4 && e4 + q < len; ++q) kk[q] = src[e4 + q];
+                    }
 #pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) {
-                if (e + q < len) {
-                    const unsigned long long K = composite_key(kk[q], start + e + q);
+                    for (uint32_t q = 0; q < 4; ++q)
+                        if (e4 + q < len && ((kk[q] & 0x7fffffffu) >> 19) == digit0) {
+                            const unsigned long long K = composite_key(kk[q], start + e4 + q);
+                            stage.ent[atomicAdd(&stage.n, 1u)] = K;
+                            atomicAdd(&stage.hist1[static_cast<uint32_t>(K >> shift1) & mask1], 1u);
+                        }
+                }
+            }
+        } else {
+            const uint32_t firstt = (it - L.group_begin) * kSlotGroup;
+            const uint32_t ntile = min(static_cast<uint32_t>(kSlotGroup), L.n_tiles - firstt);
+            const uint32_t slot0 = L.tile_begin_all + firstt;
+            __syncthreads();
+            if (static_cast<uint32_t>(tid) < ntile) pref[tid + 1] = slot_cnt[slot0 + tid];
+            __syncthreads();
+            if (tid == 0) {                // serial prefix of at most 64 slot counts (in LDS)
+                uint32_t run = 0;
+                pref[0] = 0;
+                for (uint32_t sl = 1; sl <= ntile; ++sl) {
+                    run += pref[sl];
+                    pref[sl] = run;
+                }
+            }
+            __syncthreads();
+            const uint32_t total = pref[ntile];
+            for (uint32_t j0 = 0; j0 < total; j0 += 256) {
+                __syncthreads();
+                if (stage.n + 256u > static_cast<uint32_t>(kStage))
+                    gather_flush(stage, L, list_cnt, l, list_ent, hist, false);
+                const uint32_t j = j0 + tid;
+                if (j < total) {
+                    uint32_t lo = 0, hi = ntile;          // slot with pref[lo] <= j < pref[lo + 1]
+                    while (hi - lo > 1) {
+                        const uint32_t mid = (lo + hi) >> 1;
+                        if (pref[mid] <= j) lo = mid; else hi = mid;
+                    }
+                    const unsigned long long K =
+                        slot_ent[static_cast<size_t>(slot0 + lo) * kSlotCap + (j - pref[lo])];
+                    if (static_cast<uint32_t>(K >> level_shift(0)) == digit0) {
+                        stage.ent[atomicAdd(&stage.n, 1u)] = K;
+                        atomicAdd(&stage.hist1[static_cast<uint32_t>(K >> shift1) & mask1], 1u);
+                    }
+                }
+            }
+        }
+    }
+    if (active) gather_flush(stage, L, list_cnt, cur_l, list_ent, hist, true);
+}
+
+// --------------------------------------------------------------- finish --
+// Digit that holds the k_rem-th largest key of a histogram in LDS (counted from the top);
+// every thread of the workgroup returns the same result.
+struct DigitResult {
+    uint32_t digit, above, count, found;
+};
+
+template <int NW>
+__device__ __forceinline__ DigitResult block_find_digit(const uint32_t *h, int nb, uint32_t k_rem,
+                                                        uint32_t *wave_tot /*[NW]*/, DigitResult *res) {
+    const int tid = threadIdx.x;
+    const int per = nb >> 8;               // the first 256 threads own the bins, top bins first
+    if (tid == 0) res->found = 0;
+    const int hi = nb - tid * per;
+    uint32_t own = 0;
+    if (tid < 256)
+        for (int b = hi - 1; b >= hi - per; --b) own += h[b];
+    const uint32_t incl = block_scan_incl_n<NW>(own, wave_tot);
+    const uint32_t excl = incl - own;
+    if (tid < 256 && excl < k_rem && k_rem <= incl) {
+        uint32_t acc = excl;
+        for (int b = hi - 1; b >= hi - per; --b) {
+            const uint32_t c = h[b];
+            if (acc + c >= k_rem) {
+                res->digit = static_cast<uint32_t>(b);
+                res->above = acc;
+                res->count = c;
+                res->found = 1;
+                break;
+            }
+            acc += c;
+        }
+    }
+    __syncthreads();
+    const DigitResult r = *res;
+    __syncthreads();
+    return r;
+}
+
+// One workgroup (1024 threads) per layer finishes the radix select.  The second digit comes
+// from the histogram the gather pass left; one pass over the layer's threshold-bucket list
+// then keeps the keys that share both digits (a few hundred at most, staged in LDS), and
+// the remaining score digits and -- only if equal scores straddle the k-th rank -- the digits
+// of ~index (the lower index wins) are resolved on that staged set.
+// Slow but exact routes: if the staged set overflows, the later digits are histogrammed
+// from the list; if the bucket did not fit the list at all (a huge number of nearly equal
+// scores, e.g. an all-zero layer), every digit is histogrammed by streaming the layer's keys
+// from the score map or the tile slots.
+constexpr int kFinishThreads = 1024;
+constexpr int kFinishStage = 2048;
+
+__global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__restrict__ layers,
+                                                           SelState *__restrict__ state,
+                                                           const uint32_t *__restrict__ hist,
+                                                           const uint32_t *__restrict__ list_cnt,
+                                                           const unsigned long long *__restrict__ list_ent,
+                                                           const uint32_t *__restrict__ keys,
+                                                           const uint32_t *__restrict__ slot_cnt,
+                                                           const unsigned long long *__restrict__ slot_ent) {
+    __shared__ uint32_t lh[2048];
+    __shared__ unsigned long long sel[kFinishStage];
+    __shared__ uint32_t nsel;
+    __shared__ uint32_t wave_tot[kFinishThreads / 64];
+    __shared__ DigitResult res;
+    constexpr int NW = kFinishThreads / 64;
+    const int l = blockIdx.x, tid = threadIdx.x;
+    const SelState st = state[l];
+    if (st.done || st.mode == kModeSkip) return;
+    const LayerDev L = layers[l];
+    const uint32_t n = list_cnt[l];
+    const bool use_list = n <= L.list_cap;
+    const unsigned long long *__restrict__ list = list_ent + L.list_off;
+    unsigned long long T = st.T;
+    uint32_t k_rem = st.k_rem;
+    bool done = false;
+    int lv = 1;
+    bool staged = false;
+    if (use_list) {
+        // second digit from the gather pass's histogram
+        const DigitResult r = block_find_digit<NW>(hist + static_cast<size_t>(l) * kHistBins,
+                                                   1 << level_bits(1), k_rem, wave_tot, &res);
+        if (r.found) {
+            T |= static_cast<unsigned long long>(r.digit) << level_shift(1);
+            k_rem -= r.above;
+            done = r.count == k_rem;
+            lv = 2;
+            if (!done) {                   // keep the keys that share both digits
+                if (tid == 0) nsel = 0;
+                __syncthreads();
+                const unsigned long long want = T >> level_shift(1);
+                constexpr uint32_t U = 8;  // independent loads in flight per thread
+                for (uint32_t i0 = 0; i0 < n; i0 += U * kFinishThreads) {
+                    unsigned long long K[U];
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u) {
+                        const uint32_t i = i0 + u * kFinishThreads + tid;
+                        K[u] = i < n ? list[i] : ~0ull;        // ~0 never matches a prefix
+                    }
+#pragma unroll
+                    for (uint32_t u = 0; u < U; ++u)
+                        if ((K[u] >> level_shift(1)) == want) {
+                            const uint32_t pos = atomicAdd(&nsel, 1u);
+                            if (pos < static_cast<uint32_t>(kFinishStage)) sel[pos] = K[u];
+                        }
+                }
+                __syncthreads();
+                staged = nsel <= static_cast<uint32_t>(kFinishStage);
+            }
+        } else {
+            done = true;                   // fewer keys than k_rem (cannot happen for finite input)
+        }
+    }
+    for (; lv < kLevels && !done; ++lv) {
+        const int shift = level_shift(lv), nb = 1 << level_bits(lv), shift_prev = level_shift(lv - 1);
+        for (int b = tid; b < nb; b += kFinishThreads) lh[b] = 0;
+        __syncthreads();
+        const unsigned long long want = T >> shift_prev;
+        if (staged) {
+            const uint32_t m = nsel;
+            for (uint32_t i = tid; i < m; i += kFinishThreads) {
+                const unsigned long long K = sel[i];
+                if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
+            }
+        } else if (use_list) {
+            for (uint32_t i = tid; i < n; i += kFinishThreads) {
+                const unsigned long long K = list[i];
+                if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
+            }
+        } else if (st.mode == kModeFullMap) {
+            const uint32_t *__restrict__ src = keys + L.elem_off;
+            for (uint32_t i = tid; i < L.G; i += kFinishThreads) {
+                const unsigned long long K = composite_key(src[i], i);
+                if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
+            }
+        } else {
+            for (uint32_t t = tid >> 8; t < L.n_tiles; t += kFinishThreads / 256) {
+                const uint32_t slot = L.tile_begin_all + t;
+                const uint32_t i = tid & 255;
+                if (i < slot_cnt[slot]) {
+                    const unsigned long long K = slot_ent[static_cast<size_t>(slot) * kSlotCap + i];
                     if ((K >> shift_prev) == want)
                         atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
                 }
             }
         }
-    } else {
-        const uint32_t gidx = blockIdx.x - n_map_blocks;
-        l = group_dir[dir_lookup(group_dir, n_layers, gidx)].layer;
-        const SelState st = state[l];
-        if (st.done || st.mode != kModeCandidates) return;
-        const LayerDev L = layers[l];
-        const uint32_t first = (gidx - L.group_begin) * kSlotGroup;
-        const uint32_t ntile = min(static_cast<uint32_t>(kSlotGroup), L.n_tiles - first);
-        const uint32_t slot0 = L.tile_begin_all + first;
-        if (static_cast<uint32_t>(tid) < ntile) cnts[tid] = slot_cnt[slot0 + tid];
-        for (int b = tid; b < nb; b += 256) lh[b] = 0;
         __syncthreads();
-        const unsigned long long want = st.T >> shift_prev;
-#pragma unroll 4
-        for (uint32_t sl = 0; sl < ntile; ++sl) {
-            if (static_cast<uint32_t>(tid) < cnts[sl]) {       // validated: cnts[sl] <= kSlotCap
-                const unsigned long long K = slot_ent[static_cast<size_t>(slot0 + sl) * kSlotCap + tid];
-                if ((K >> shift_prev) == want)
-                    atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
-            }
-        }
+        const DigitResult r = block_find_digit<NW>(lh, nb, k_rem, wave_tot, &res);
+        if (!r.found) break;               // fewer keys than k_rem (cannot happen for finite input)
+        T |= static_cast<unsigned long long>(r.digit) << shift;
+        k_rem -= r.above;
+        done = r.count == k_rem;           // whole bucket taken: lower digits stay 0
     }
-    __syncthreads();
-    uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins;
-    for (int b = tid; b < nb; b += 256) {
-        const uint32_t v = lh[b];
-        if (v) atomicAdd(&gh[b], v);
+    if (tid == 0) {
+        SelState ns = st;
+        ns.T = T;
+        ns.k_rem = k_rem;
+        ns.done = 1;
+        state[l] = ns;
     }
 }
 
@@ -1120,16 +1364,21 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     if (rc != RSDGC_OK) return rc;
     marks.close(3);
 
-    // radix select; level 0 was histogrammed by the NSI passes
-    for (int lv = 0; lv < kLevels; ++lv) {
-        const uint32_t n_slot_blocks = plan->any_large ? plan->n_slot_groups : 0u;
-        if (lv > 0)
-            hipLaunchKernelGGL(k_refine, dim3(n_chunks + n_slot_blocks), dim3(256), 0, stream,
-                               layers, chunk_dir, group_dir, static_cast<uint32_t>(L), n_chunks,
-                               state, hist, reinterpret_cast<const uint32_t *>(nsi), slot_cnt,
-                               slot_ent, level_shift(lv), level_bits(lv), level_shift(lv - 1));
-        hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(lv),
-                           level_bits(lv));
+    // radix select: first digit from the histograms of the NSI passes, then the keys of each
+    // layer's threshold bucket are gathered and one workgroup per layer finishes on them
+    {
+        uint32_t *list_cnt = reinterpret_cast<uint32_t *>(ws + w.list_cnt);
+        unsigned long long *list_ent = reinterpret_cast<unsigned long long *>(ws + w.list_ent);
+        hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(0),
+                           level_bits(0));
+        const uint32_t n_map_wgs = std::min<uint32_t>(n_chunks, kNumCUs * 4u);
+        const uint32_t n_slot_wgs = plan->any_large ? std::min<uint32_t>(plan->n_slot_groups, kNumCUs * 4u) : 0u;
+        hipLaunchKernelGGL(k_gather, dim3(n_map_wgs + n_slot_wgs), dim3(256), 0, stream, layers,
+                           chunk_dir, group_dir, static_cast<uint32_t>(L), n_map_wgs, n_chunks,
+                           plan->n_slot_groups, state, reinterpret_cast<const uint32_t *>(nsi),
+                           slot_cnt, slot_ent, list_cnt, list_ent, hist);
+        hipLaunchKernelGGL(k_finish, dim3(L), dim3(kFinishThreads), 0, stream, layers, state, hist, list_cnt, list_ent,
+                           reinterpret_cast<const uint32_t *>(nsi), slot_cnt, slot_ent);
     }
     HIP_TRY(hipGetLastError());
     marks.close(4);

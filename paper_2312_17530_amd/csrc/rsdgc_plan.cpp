@@ -1,6 +1,7 @@
 // Host side of the C ABI: plan construction, validation, queries.
 // No HIP call is made from this file (destroying a plan that still holds profiling
 // events releases them through rsdgc_profile_end).
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -34,6 +35,7 @@ int build_tables(rsdgc_plan_s *plan) {
 
     int64_t elem_off = 0, out_off = 0, centre_off = 0;
     uint32_t chunk_begin = 0, tile_begin_all = 0, group_begin = 0;
+    uint64_t list_off = 0;
     for (int l = 0; l < L; ++l) {
         LayerDev &d = plan->layers[l];
         const int64_t R = plan->shapes[l].rows, C = plan->shapes[l].cols, G = R * C;
@@ -57,6 +59,9 @@ int build_tables(rsdgc_plan_s *plan) {
         d.tile_begin_all = tile_begin_all;
         d.group_begin = group_begin;
         d.n_groups = (d.n_tiles + kSlotGroup - 1) / kSlotGroup;
+        d.list_off = static_cast<uint32_t>(list_off);
+        d.list_cap = static_cast<uint32_t>(std::min<int64_t>(G, std::max<int64_t>(kListMin, G / kListDiv)));
+        list_off += d.list_cap;
 
         // Candidate path: the bound comes from the scores of a sample of the layer's tiles.
         // It is taken where about twice k_l centres are expected above the bound; a layer is
@@ -137,11 +142,13 @@ int build_tables(rsdgc_plan_s *plan) {
     w.hist = off;         off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
     w.chunk_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * L, A);
     w.mask = off;         off = align_up(off + sizeof(uint32_t) * words, A);
     w.cmask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
     w.zero_end = off;
     w.slot_cnt = off;     off = align_up(off + sizeof(uint32_t) * plan->n_tiles_all, A);
     w.slot_ent = off;     off = align_up(off + sizeof(uint64_t) * kSlotCap * size_t(plan->n_tiles_all), A);
+    w.list_ent = off;     off = align_up(off + sizeof(uint64_t) * static_cast<size_t>(list_off), A);
     w.nsi = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
     w.total = off;
 
@@ -173,7 +180,7 @@ extern "C" {
 int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
                const int32_t *p_per_layer, double alpha, const double *keep_ratio,
                rsdgc_plan_t **out_plan) {
-    if (!shapes || !keep_ratio || !out_plan || n_layers < 1) return RSDGC_EINVAL;
+    if (!shapes || !keep_ratio || !out_plan || n_layers < 1 || n_layers > 65536) return RSDGC_EINVAL;
     *out_plan = nullptr;
     if (!(alpha >= 0.0 && alpha <= 1.0)) return RSDGC_EINVAL;
     int64_t total = 0;
@@ -185,7 +192,7 @@ int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
         if (R > 0xffffffffLL / C) return RSDGC_EINVAL;            // G_l must fit uint32
         if (!ratio_ok(keep_ratio[l])) return RSDGC_EINVAL;
         total += R * C + kLayerAlign;
-        if (total > (int64_t(1) << 40)) return RSDGC_EINVAL;
+        if (total > (int64_t(1) << 34)) return RSDGC_EINVAL;         // 64 GiB per float32 arena
     }
     if ((total + kChunk - 1) / kChunk + n_layers > 0x7fffffffLL) return RSDGC_EINVAL;
     rsdgc_plan_s *plan = new (std::nothrow) rsdgc_plan_s;
