@@ -880,45 +880,68 @@ __device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos
     if (b + nbits > 32) atomicOr(&mask[w + 1], bits >> (32 - b));
 }
 
-// One workgroup = one 32 x 128 tile (the NSI tiling).
-// Candidate-mode layers: the tile's recorded candidates that reach the threshold OR the
-// bits of their window into the (cleared) mask; the words they touch are nearly all
-// distinct, which is the case global atomics handle well.
-// Full-map layers: every centre of the tile and of a
-// halo of h rows / columns is compared with the layer's threshold; the per-row results
-// become 64-bit ballot words in LDS, the p x p box dilation (Section III-C: whole
-// neighbourhoods are kept) is done on those words with shifts and ORs, and the tile's
-// mask words are written with plain stores (rows that are a multiple of 32 long) -- no
-// global atomics on the common path.
-__global__ __launch_bounds__(256) void k_mark(const LayerDev *__restrict__ layers,
-                                              const DirEntry *__restrict__ dir, uint32_t n_layers,
-                                              uint32_t n_tiles, const SelState *__restrict__ state,
-                                              const uint32_t *__restrict__ keys,
-                                              const uint32_t *__restrict__ slot_cnt,
-                                              const unsigned long long *__restrict__ slot_ent,
-                                              uint32_t *__restrict__ mask,
-                                              uint32_t *__restrict__ cmask) {
-    constexpr int MAXH = (RSDGC_MAX_P - 1) / 2;
-    __shared__ unsigned long long bits[kTileRows + 2 * MAXH][4];   // [row][left, seg0, seg1, right]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t t_id = xcd_contiguous(blockIdx.x, n_tiles);
-    const uint32_t e = dir_lookup(dir, n_layers, t_id);
-    const uint32_t l = dir[e].layer;
-    const LayerDev L = layers[l];
-    const SelState st = state[l];
-    if (st.mode == kModeSkip) return;           // nothing selected: the mask stays clear
-    const unsigned long long T = st.T;
-    const int h = (static_cast<int>(L.p) - 1) / 2;
-    const int rows_ext = kTileRows + 2 * h;
-    const uint32_t local = t_id - dir[e].begin;
-    if (st.mode == kModeCandidates) {
-        const uint32_t slot = L.tile_begin_all + local;
-        const uint32_t cnt = slot_cnt[slot];
-        if (static_cast<uint32_t>(tid) < cnt) {
-            const unsigned long long K = slot_ent[static_cast<size_t>(slot) * kSlotCap + tid];
+// Candidate-mode layers: workgroups stride over the slot groups; every recorded candidate
+// that reaches its layer's threshold ORs the bits of its window into the (cleared) mask.
+// The words touched are nearly all distinct, which is the case global atomics handle well.
+__global__ __launch_bounds__(256) void k_mark_cand(const LayerDev *__restrict__ layers,
+                                                   const DirEntry *__restrict__ group_dir,
+                                                   uint32_t n_layers, uint32_t n_groups,
+                                                   const SelState *__restrict__ state,
+                                                   const uint32_t *__restrict__ slot_cnt,
+                                                   const unsigned long long *__restrict__ slot_ent,
+                                                   uint32_t *__restrict__ mask,
+                                                   uint32_t *__restrict__ cmask) {
+    __shared__ uint32_t pref[kSlotGroup + 1];
+    const int tid = threadIdx.x;
+    const uint32_t first = blockIdx.x, stride = gridDim.x;
+    if (first >= n_groups) return;
+    uint32_t e = dir_lookup(group_dir, n_layers, first);
+    uint32_t cur_l = 0xffffffffu;
+    bool active = false;
+    unsigned long long T = 0;
+    LayerDev L;
+    for (uint32_t it = first; it < n_groups; it += stride) {
+        while (it >= group_dir[e + 1].begin) ++e;
+        const uint32_t l = group_dir[e].layer;
+        if (l != cur_l) {
+            cur_l = l;
+            L = layers[l];
+            const SelState st = state[l];
+            active = st.mode == kModeCandidates;
+            T = st.T;
+        }
+        if (!active) {
+            const uint32_t nb = group_dir[e + 1].begin;
+            it += (nb - it + stride - 1) / stride * stride - stride;
+            continue;
+        }
+        const uint32_t firstt = (it - L.group_begin) * kSlotGroup;
+        const uint32_t ntile = min(static_cast<uint32_t>(kSlotGroup), L.n_tiles - firstt);
+        const uint32_t slot0 = L.tile_begin_all + firstt;
+        __syncthreads();
+        if (static_cast<uint32_t>(tid) < ntile) pref[tid + 1] = slot_cnt[slot0 + tid];
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t run = 0;
+            pref[0] = 0;
+            for (uint32_t sl = 1; sl <= ntile; ++sl) {
+                run += pref[sl];
+                pref[sl] = run;
+            }
+        }
+        __syncthreads();
+        const uint32_t total = pref[ntile];
+        const int h = (static_cast<int>(L.p) - 1) / 2;
+        const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
+        for (uint32_t j = tid; j < total; j += 256) {
+            uint32_t lo = 0, hi = ntile;              // slot with pref[lo] <= j < pref[lo + 1]
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (pref[mid] <= j) lo = mid; else hi = mid;
+            }
+            const unsigned long long K = slot_ent[static_cast<size_t>(slot0 + lo) * kSlotCap + (j - pref[lo])];
             if (K >= T) {
                 const uint32_t i = ~static_cast<uint32_t>(K);
-                const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
                 const int xc = static_cast<int>(i / L.C);
                 const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * L.C);
                 const int ylo = max(0, yc - h), yhi = min(C - 1, yc + h);
@@ -931,70 +954,113 @@ __global__ __launch_bounds__(256) void k_mark(const LayerDev *__restrict__ layer
                 }
             }
         }
-        return;
     }
-    const int trow = static_cast<int>(local / L.tiles_x);
-    const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
-    const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
-    const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
-    const uint32_t *__restrict__ src = keys + L.elem_off;
+}
 
-    for (int it = wave; it < rows_ext * 2; it += 4) {
-        const int rr = it >> 1, seg = it & 1;
-        const int x = x0 - h + rr, y = y0 + 64 * seg + lane;
-        bool flag = false;
-        if (x >= 0 && x < R && y < C) {
-            const uint32_t i = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
-            flag = composite_key(src[i], i) >= T;
+// Full-map layers: workgroups stride over the 32 x 128 tiles (the NSI tiling).  Every centre
+// of a tile and of a halo of h rows / columns is compared with the layer's threshold; the
+// per-row results become 64-bit ballot words in LDS, the p x p box dilation (Section III-C:
+// whole neighbourhoods are kept) is done on those words with shifts and ORs, and the tile's
+// mask words are written with plain stores (rows that are a multiple of 32 long) -- no
+// global atomics on that path.
+__global__ __launch_bounds__(256) void k_mark_map(const LayerDev *__restrict__ layers,
+                                                  const DirEntry *__restrict__ dir, uint32_t n_layers,
+                                                  uint32_t n_tiles, const SelState *__restrict__ state,
+                                                  const uint32_t *__restrict__ keys,
+                                                  uint32_t *__restrict__ mask,
+                                                  uint32_t *__restrict__ cmask) {
+    constexpr int MAXH = (RSDGC_MAX_P - 1) / 2;
+    __shared__ unsigned long long bits[kTileRows + 2 * MAXH][4];   // [row][left, seg0, seg1, right]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t first = blockIdx.x, stride = gridDim.x;
+    if (first >= n_tiles) return;
+    uint32_t e = dir_lookup(dir, n_layers, first);
+    uint32_t cur_l = 0xffffffffu;
+    bool active = false;
+    unsigned long long T = 0;
+    LayerDev L;
+    for (uint32_t t = first; t < n_tiles; t += stride) {
+        while (t >= dir[e + 1].begin) ++e;
+        const uint32_t l = dir[e].layer;
+        if (l != cur_l) {
+            cur_l = l;
+            L = layers[l];
+            const SelState st = state[l];
+            active = st.mode == kModeFullMap;
+            T = st.T;
         }
-        const unsigned long long w = __ballot(flag);
-        if (lane == 0) bits[rr][1 + seg] = w;
-    }
-    if (wave < 2 && lane < rows_ext) {          // halo columns: lane = row; wave 0 left, wave 1 right
-        unsigned long long hw = 0;
-        const int x = x0 - h + lane;
-        if (x >= 0 && x < R) {
-            for (int d = 1; d <= h; ++d) {
-                const int y = wave == 0 ? y0 - d : y0 + kTileCols + (d - 1);
-                if (y >= 0 && y < C) {
-                    const uint32_t i = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
-                    if (composite_key(src[i], i) >= T)
-                        hw |= wave == 0 ? (1ull << (64 - d)) : (1ull << (d - 1));
+        if (!active) {
+            const uint32_t nb = dir[e + 1].begin;
+            t += (nb - t + stride - 1) / stride * stride - stride;
+            continue;
+        }
+        const int h = (static_cast<int>(L.p) - 1) / 2;
+        const int rows_ext = kTileRows + 2 * h;
+        const uint32_t local = t - dir[e].begin;
+        const int trow = static_cast<int>(local / L.tiles_x);
+        const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
+        const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
+        const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
+        const uint32_t *__restrict__ src = keys + L.elem_off;
+
+        for (int it = wave; it < rows_ext * 2; it += 4) {
+            const int rr = it >> 1, seg = it & 1;
+            const int x = x0 - h + rr, y = y0 + 64 * seg + lane;
+            bool flag = false;
+            if (x >= 0 && x < R && y < C) {
+                const uint32_t i = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+                flag = composite_key(src[i], i) >= T;
+            }
+            const unsigned long long w = __ballot(flag);
+            if (lane == 0) bits[rr][1 + seg] = w;
+        }
+        if (wave < 2 && lane < rows_ext) {      // halo columns: lane = row; wave 0 left, wave 1 right
+            unsigned long long hw = 0;
+            const int x = x0 - h + lane;
+            if (x >= 0 && x < R) {
+                for (int d = 1; d <= h; ++d) {
+                    const int y = wave == 0 ? y0 - d : y0 + kTileCols + (d - 1);
+                    if (y >= 0 && y < C) {
+                        const uint32_t i = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+                        if (composite_key(src[i], i) >= T)
+                            hw |= wave == 0 ? (1ull << (64 - d)) : (1ull << (d - 1));
+                    }
                 }
             }
+            bits[lane][wave == 0 ? 0 : 3] = hw;
         }
-        bits[lane][wave == 0 ? 0 : 3] = hw;
-    }
-    __syncthreads();
-    if (wave != 0) return;
+        __syncthreads();
 
-    const int r = lane >> 1, seg = lane & 1;    // 32 rows x 2 segments = 64 items
-    const int x = x0 + r, yb = y0 + 64 * seg;
-    if (x >= R || yb >= C) return;
-    unsigned long long acc = 0;
-    for (int rr = r; rr <= r + 2 * h; ++rr) {
-        const unsigned long long W = bits[rr][1 + seg], Lw = bits[rr][seg], Rw = bits[rr][2 + seg];
-        unsigned long long hd = W;
-        for (int d = 1; d <= h; ++d)
-            hd |= (W << d) | (Lw >> (64 - d)) | (W >> d) | (Rw << (64 - d));
-        acc |= hd;
-    }
-    const int ncols = min(64, C - yb);
-    const unsigned long long valid = ncols >= 64 ? ~0ull : ((1ull << ncols) - 1ull);
-    acc &= valid;
-    const unsigned long long own = bits[r + h][1 + seg];
-    const size_t pos = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + yb;
-    if ((C & 31) == 0) {                         // the tile owns its mask words
-        const size_t w = pos >> 5;
-        mask[w] = static_cast<uint32_t>(acc);
-        if (ncols > 32) mask[w + 1] = static_cast<uint32_t>(acc >> 32);
-        if (cmask) {
-            cmask[w] = static_cast<uint32_t>(own);
-            if (ncols > 32) cmask[w + 1] = static_cast<uint32_t>(own >> 32);
+        const int r = lane >> 1, seg = lane & 1;    // wave 0: 32 rows x 2 segments = 64 items
+        const int x = x0 + r, yb = y0 + 64 * seg;
+        if (wave == 0 && x < R && yb < C) {
+            unsigned long long acc = 0;
+            for (int rr = r; rr <= r + 2 * h; ++rr) {
+                const unsigned long long W = bits[rr][1 + seg], Lw = bits[rr][seg], Rw = bits[rr][2 + seg];
+                unsigned long long hd = W;
+                for (int d = 1; d <= h; ++d)
+                    hd |= (W << d) | (Lw >> (64 - d)) | (W >> d) | (Rw << (64 - d));
+                acc |= hd;
+            }
+            const int ncols = min(64, C - yb);
+            const unsigned long long valid = ncols >= 64 ? ~0ull : ((1ull << ncols) - 1ull);
+            acc &= valid;
+            const unsigned long long own = bits[r + h][1 + seg];
+            const size_t pos = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + yb;
+            if ((C & 31) == 0) {                     // the tile owns its mask words
+                const size_t w = pos >> 5;
+                mask[w] = static_cast<uint32_t>(acc);
+                if (ncols > 32) mask[w + 1] = static_cast<uint32_t>(acc >> 32);
+                if (cmask) {
+                    cmask[w] = static_cast<uint32_t>(own);
+                    if (ncols > 32) cmask[w + 1] = static_cast<uint32_t>(own >> 32);
+                }
+            } else {
+                or_bits_shared(mask, pos, acc);
+                if (cmask) or_bits_shared(cmask, pos, own);
+            }
         }
-    } else {
-        or_bits_shared(mask, pos, acc);
-        if (cmask) or_bits_shared(cmask, pos, own);
+        __syncthreads();                        // the ballot words are reused by the next tile
     }
 }
 
@@ -1026,35 +1092,37 @@ __global__ __launch_bounds__(256) void k_count(const LayerDev *__restrict__ laye
 }
 
 // ----------------------------------------------------------------- scan --
-// One workgroup per layer: exclusive prefix of the per-chunk counts, totals out.
-__global__ __launch_bounds__(256) void k_scan(const LayerDev *__restrict__ layers,
-                                              SelState *__restrict__ state,
-                                              uint32_t *__restrict__ chunk_cnt,
-                                              uint32_t *__restrict__ chunk_ccnt,
-                                              int32_t *__restrict__ out_counts,
-                                              int32_t *__restrict__ out_centre_counts,
-                                              int with_centres) {
-    __shared__ uint32_t wave_tot[4];
+// One workgroup (1024 threads) per layer: exclusive prefix of the per-chunk counts, totals out.
+constexpr int kScanThreads = 1024;
+
+__global__ __launch_bounds__(kScanThreads) void k_scan(const LayerDev *__restrict__ layers,
+                                                       SelState *__restrict__ state,
+                                                       uint32_t *__restrict__ chunk_cnt,
+                                                       uint32_t *__restrict__ chunk_ccnt,
+                                                       int32_t *__restrict__ out_counts,
+                                                       int32_t *__restrict__ out_centre_counts,
+                                                       int with_centres) {
+    __shared__ uint32_t wave_tot[kScanThreads / 64];
     const int l = blockIdx.x, tid = threadIdx.x;
     const LayerDev L = layers[l];
-    const uint32_t n = L.n_chunks, per = (n + 255) / 256;
+    const uint32_t n = L.n_chunks, per = (n + kScanThreads - 1) / kScanThreads;
     const uint32_t lo = min(n, tid * per), hi = min(n, lo + per);
     for (int pass = 0; pass < (with_centres ? 2 : 1); ++pass) {
         uint32_t *__restrict__ a = (pass == 0 ? chunk_cnt : chunk_ccnt) + L.chunk_begin;
         uint32_t own = 0;
         for (uint32_t i = lo; i < hi; ++i) own += a[i];
-        const uint32_t incl = block_scan_incl(own, wave_tot);
+        const uint32_t incl = block_scan_incl_n<kScanThreads / 64>(own, wave_tot);
         uint32_t run = incl - own;
         for (uint32_t i = lo; i < hi; ++i) {
             const uint32_t v = a[i];
             a[i] = run;
             run += v;
         }
-        if (tid == 255 && pass == 0) {
+        if (tid == kScanThreads - 1 && pass == 0) {
             out_counts[l] = static_cast<int32_t>(incl);
             state[l].n_pairs = incl;
         }
-        if (tid == 255 && pass == 1) {
+        if (tid == kScanThreads - 1 && pass == 1) {
             state[l].n_centres = incl;
             if (out_centre_counts) out_centre_counts[l] = static_cast<int32_t>(incl);
         }
@@ -1383,14 +1451,18 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     HIP_TRY(hipGetLastError());
     marks.close(4);
 
-    hipLaunchKernelGGL(k_mark, dim3(plan->n_tiles_all), dim3(256), 0, stream, layers,
-                       reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir),
+    if (plan->any_large)
+        hipLaunchKernelGGL(k_mark_cand, dim3(std::min<uint32_t>(plan->n_slot_groups, kNumCUs * 8u)),
+                           dim3(256), 0, stream, layers, group_dir, static_cast<uint32_t>(L),
+                           plan->n_slot_groups, state, slot_cnt, slot_ent, mask, cmask);
+    hipLaunchKernelGGL(k_mark_map, dim3(std::min<uint32_t>(plan->n_tiles_all, kNumCUs * 8u)), dim3(256),
+                       0, stream, layers, reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir),
                        static_cast<uint32_t>(L), plan->n_tiles_all, state,
-                       reinterpret_cast<const uint32_t *>(nsi), slot_cnt, slot_ent, mask, cmask);
+                       reinterpret_cast<const uint32_t *>(nsi), mask, cmask);
     marks.close(5);
     hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
                        static_cast<uint32_t>(L), mask, cmask, chunk_cnt, chunk_ccnt);
-    hipLaunchKernelGGL(k_scan, dim3(L), dim3(256), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
+    hipLaunchKernelGGL(k_scan, dim3(L), dim3(kScanThreads), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
                        out_counts, out_centre_counts, cmask ? 1 : 0);
     marks.close(6);
     hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
