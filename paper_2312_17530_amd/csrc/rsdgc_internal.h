@@ -28,12 +28,17 @@ enum LayerMode : uint32_t {
     kModeSkip = 2,        // k_l = 0: nothing is selected
 };
 
-// One tile in 16, picked by a multiplicative hash of its index inside the layer.
+// Sampled tiles of a layer: one tile in 2^shift, picked by a multiplicative hash of the
+// tile's index inside the layer.  Larger layers are sampled more thinly (the estimate only
+// needs a few hundred tiles).
 #if defined(__HIPCC__)
 __host__ __device__
 #endif
-inline bool tile_is_sampled(uint32_t local_tile) {
-    return ((local_tile * 2654435761u) >> 28) == 0u;
+inline bool tile_is_sampled(uint32_t local_tile, uint32_t shift) {
+    return ((local_tile * 2654435761u) >> (32u - shift)) == 0u;
+}
+inline uint32_t sample_shift(uint32_t n_tiles) {
+    return n_tiles >= 16384u ? 6u : n_tiles >= 4096u ? 5u : 4u;
 }
 
 // One layer as the kernels see it.
@@ -91,9 +96,9 @@ struct WsLayout {
     size_t group_dir = 0;    // DirEntry[n_layers + 1]: slot groups
     size_t samples = 0;      // SampleEntry[] per p-group
     size_t table_bytes = 0;  // bytes uploaded from the host
+    size_t state = 0;        // SelState[n_layers], rewritten at the start of every compress
     // cleared at the start of every compress
     size_t zero_begin = 0;
-    size_t state = 0;        // SelState[n_layers]
     size_t hist = 0;         // uint32[n_layers][kHistBins]
     size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk, then their prefix
     size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk, then prefix

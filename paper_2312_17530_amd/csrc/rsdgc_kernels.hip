@@ -102,29 +102,32 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_t
     return block_scan_incl_n<4>(v, wave_tot);
 }
 
-// ---------------------------------------------------------------- clear --
-__global__ __launch_bounds__(256) void k_clear(uint4 *__restrict__ p, size_t n16) {
+// ---------------------------------------------------------------- begin --
+// Start of a compress call: all workgroups but the last clear the histograms, counters and
+// bitmasks; the last one writes every layer's initial selection state.
+__global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16,
+                                               const LayerDev *__restrict__ layers,
+                                               SelState *__restrict__ state, int n_layers) {
+    if (blockIdx.x + 1 == gridDim.x) {
+        for (int l = threadIdx.x; l < n_layers; l += 256) {
+            SelState s;
+            const LayerDev L = layers[l];
+            s.T = L.k == 0 ? ~0ull : 0ull;   // no key reaches ~0: nothing is selected when k = 0
+            s.k_rem = L.k;
+            s.done = L.k == 0 ? 1u : 0u;
+            s.mode = L.k == 0 ? kModeSkip : (L.large ? kModeCandidates : kModeFullMap);
+            s.hint_key = 0;
+            s.overflow = 0;
+            s.n_centres = 0;
+            s.n_pairs = 0;
+            s.pad_ = 0;
+            state[l] = s;
+        }
+        return;
+    }
     const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
-    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    const size_t stride = static_cast<size_t>(gridDim.x - 1) * 256;
     for (size_t j = i; j < n16; j += stride) p[j] = make_uint4(0, 0, 0, 0);
-}
-
-__global__ void k_init_state(const LayerDev *__restrict__ layers, SelState *__restrict__ state,
-                             int n_layers) {
-    const int l = blockIdx.x * blockDim.x + threadIdx.x;
-    if (l >= n_layers) return;
-    SelState s;
-    const LayerDev L = layers[l];
-    s.T = L.k == 0 ? ~0ull : 0ull;   // no key reaches ~0: nothing is selected when k = 0
-    s.k_rem = L.k;
-    s.done = L.k == 0 ? 1u : 0u;
-    s.mode = L.k == 0 ? kModeSkip : (L.large ? kModeCandidates : kModeFullMap);
-    s.hint_key = 0;
-    s.overflow = 0;
-    s.n_centres = 0;
-    s.n_pairs = 0;
-    s.pad_ = 0;
-    state[l] = s;
 }
 
 // Eqs. 8-10 from the window sums sa = sum|w|, ss = sum w, sq = sum w^2 (n = p*p slots):
@@ -356,37 +359,43 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                     }
                     out[c] = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
                 }
-                const int x = x0 + row_base + o, y = y0 + c0;
-                if (x < R && y < C) {
-                    const bool two = y + 1 < C;
-                    const uint32_t key0 = __float_as_uint(out[0]) & 0x7fffffffu;
-                    const uint32_t key1 = __float_as_uint(out[1]) & 0x7fffffffu;
-                    if (MAP) {
-                        const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
-                        if (two && pair_store) {
-                            *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[1]);
-                        } else {
-                            a.nsi_out[off] = out[0];
-                            if (two) a.nsi_out[off + 1] = out[1];
+                const uint32_t key0 = __float_as_uint(out[0]) & 0x7fffffffu;
+                const uint32_t key1 = __float_as_uint(out[1]) & 0x7fffffffu;
+                if (CAPTURE) {
+                    // common case: neither centre reaches the bound -- nothing else to do
+                    if (key0 >= hint_key || key1 >= hint_key) {
+                        const int x = x0 + row_base + o, y = y0 + c0;
+                        if (x < R && y < C) {
+                            const uint32_t i0 = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+#pragma unroll
+                            for (int c = 0; c < 2; ++c) {
+                                const uint32_t key = c == 0 ? key0 : key1;
+                                if (key >= hint_key && y + c < C) {
+                                    const uint32_t pos = atomicAdd(&ncand, 1u);
+                                    if (pos < kSlotCap) cand[pos] = composite_key(key, i0 + c);
+                                    const uint32_t rel = (key >> 19) - hint_bin;
+                                    atomicAdd(&lhist[min(rel, static_cast<uint32_t>(kCandBins - 1))], 1u);
+                                    if (rel >= static_cast<uint32_t>(kCandBins - 1)) a.state_rw[l].overflow = 1u;
+                                }
+                            }
                         }
                     }
-                    if (FULLHIST) {
-                        atomicAdd(&lhist[key0 >> 19], 1u);
-                        if (two) atomicAdd(&lhist[key1 >> 19], 1u);
-                    }
-                    if (CAPTURE) {
-                        const uint32_t i0 = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
-                        if (key0 >= hint_key) {
-                            const uint32_t pos = atomicAdd(&ncand, 1u);
-                            if (pos < kSlotCap) cand[pos] = composite_key(key0, i0);
-                            atomicAdd(&lhist[min((key0 >> 19) - hint_bin, static_cast<uint32_t>(kCandBins - 1))], 1u);
-                            if ((key0 >> 19) - hint_bin >= static_cast<uint32_t>(kCandBins - 1)) a.state_rw[l].overflow = 1u;
+                } else {
+                    const int x = x0 + row_base + o, y = y0 + c0;
+                    if (x < R && y < C) {
+                        const bool two = y + 1 < C;
+                        if (MAP) {
+                            const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
+                            if (two && pair_store) {
+                                *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[1]);
+                            } else {
+                                a.nsi_out[off] = out[0];
+                                if (two) a.nsi_out[off + 1] = out[1];
+                            }
                         }
-                        if (two && key1 >= hint_key) {
-                            const uint32_t pos = atomicAdd(&ncand, 1u);
-                            if (pos < kSlotCap) cand[pos] = composite_key(key1, i0 + 1);
-                            atomicAdd(&lhist[min((key1 >> 19) - hint_bin, static_cast<uint32_t>(kCandBins - 1))], 1u);
-                            if ((key1 >> 19) - hint_bin >= static_cast<uint32_t>(kCandBins - 1)) a.state_rw[l].overflow = 1u;
+                        if (FULLHIST) {
+                            atomicAdd(&lhist[key0 >> 19], 1u);
+                            if (two) atomicAdd(&lhist[key1 >> 19], 1u);
                         }
                     }
                 }
@@ -1405,9 +1414,8 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
         const size_t end = want_centres ? w.zero_end : w.cmask;
         const size_t n16 = (end - w.zero_begin) / 16;
         const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
-        hipLaunchKernelGGL(k_clear, dim3(blocks), dim3(256), 0, stream,
-                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16);
-        hipLaunchKernelGGL(k_init_state, dim3((L + 63) / 64), dim3(64), 0, stream, layers, state, L);
+        hipLaunchKernelGGL(k_begin, dim3(blocks + 1), dim3(256), 0, stream,
+                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, layers, state, L);
         HIP_TRY(hipGetLastError());
     }
     marks.close(0);

@@ -68,7 +68,8 @@ int build_tables(rsdgc_plan_s *plan) {
         // eligible when it has enough sampled tiles for that estimate and when the expected
         // number of candidates per tile leaves ample room in a tile's slot.
         uint32_t n_sampled = 0;
-        for (uint32_t t = 0; t < d.n_tiles; ++t) n_sampled += tile_is_sampled(t) ? 1u : 0u;
+        const uint32_t sshift = sample_shift(d.n_tiles);
+        for (uint32_t t = 0; t < d.n_tiles; ++t) n_sampled += tile_is_sampled(t, sshift) ? 1u : 0u;
         d.n_sampled = n_sampled;
         const double frac = d.n_tiles ? double(n_sampled) / double(d.n_tiles) : 0.0;
         const double want = 2.0 * double(k) * frac;
@@ -113,7 +114,7 @@ int build_tables(rsdgc_plan_s *plan) {
             ++g.dir_count;
             if (d.large)
                 for (uint32_t t = 0; t < d.n_tiles; ++t)
-                    if (tile_is_sampled(t))
+                    if (tile_is_sampled(t, sample_shift(d.n_tiles)))
                         plan->samples.push_back(SampleEntry{static_cast<uint32_t>(l), t});
         }
         if (g.dir_count == 0) continue;
@@ -137,8 +138,8 @@ int build_tables(rsdgc_plan_s *plan) {
     w.group_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + 1), A);
     w.samples = off;      off = align_up(off + sizeof(SampleEntry) * (max_samples + 1), A);
     w.table_bytes = off;
+    w.state = off;        off = align_up(off + sizeof(SelState) * L, A);   // written in full each call
     w.zero_begin = off;
-    w.state = off;        off = align_up(off + sizeof(SelState) * L, A);
     w.hist = off;         off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
     w.chunk_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);

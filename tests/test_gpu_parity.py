@@ -124,7 +124,8 @@ def test_config2_resnet50_dynamic_ratios(path):
 
 
 def _tile_is_sampled(t):
-    """The library samples one tile in 16 by this hash of the tile's index inside its layer."""
+    """The library samples one tile in 16 (layers below 4096 tiles) by this hash of the tile's
+    index inside its layer."""
     return ((t * 2654435761) & 0xFFFFFFFF) >> 28 == 0
 
 
