@@ -31,21 +31,20 @@ METRIC = "gradient elements compressed/sec (full-model, 1 GPU) and % of HBM peak
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); the summaries are
 # in profiles/.  Keyed by (workload name, stage).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    ("vgg19_45c", "emit"): 1.717e9,      # profiles/hbm_traffic_vgg19.md
+    ("vgg19_45c", "capture"): 1.2965e9,  # profiles/hbm_traffic_vgg19.md
+}
 
 
-def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int) -> float:
+def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems: int) -> float:
     """Bytes a stage has to move by its own contract (float32 data)."""
-    if stage == "capture":    # read g, read r (candidates are a fraction of a percent)
-        return 8.0 * n_elems
-    if stage == "full_map":   # read g, read r, write the score map
-        return 12.0 * n_elems
+    if stage == "capture":    # read g, read r of the candidate-mode layers (candidates are < 1 %)
+        return 8.0 * n_cand_elems
+    if stage == "full_map":   # read g, read r, write the score map of the full-map layers
+        return 12.0 * (n_elems - n_cand_elems)
     if stage == "emit":       # read g, read r, write r, write (index, value) pairs
         return 12.0 * n_elems + 8.0 * n_pairs
-    if stage == "select":     # two refinement passes over the score map
-        return 8.0 * n_elems
-    if stage == "mark":       # one pass over the score map
-        return 4.0 * n_elems
     return 0.0
 
 
@@ -79,6 +78,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not record per-stage HIP events")
     ap.add_argument("--centres", action="store_true", help="also emit the selected-centre lists")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy three times before the timed region "
+                         "(reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--full-map", action="store_true",
                     help="force the full-score-map ranking path for every layer")
     args = ap.parse_args()
@@ -103,6 +105,14 @@ def main() -> int:
     sess.set_grad(grads)
     G = w.total_elems
     stream = torch.cuda.current_stream()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         sess.compress(stream)
@@ -132,14 +142,17 @@ def main() -> int:
 
     roofline = None
     if stages:
-        dom = max(("capture", "full_map", "emit", "select", "mark"), key=lambda s: stages.get(s, 0.0))
+        paths = binding.rsdgc_last_paths(sess.plan, sess.workspace)
+        n_cand = sum(r * c for (r, c), pth in zip(w.shapes, paths) if pth == 0)
+        dom = max(("capture", "full_map", "emit"), key=lambda s: stages.get(s, 0.0))
         dur_s = stages[dom] * 1e-3
-        alg = stage_algorithmic_bytes(dom, G, n_pairs)
+        alg = stage_algorithmic_bytes(dom, G, n_pairs, n_cand)
         achieved = alg / dur_s / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                     "algorithmic_bytes": alg, "avg_ms": stages[dom],
+                    "elements_on_candidate_path": n_cand,
                     "path_algorithmic_bytes": 12.0 * G + 8.0 * n_pairs,
                     "path_frac": (12.0 * G + 8.0 * n_pairs) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS}
 
