@@ -48,7 +48,7 @@ def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems
     return 0.0
 
 
-def cpu_baseline(workload, grads, budget_elems: int = 40_000_000):
+def cpu_baseline(workload, grads, budget_elems: int = 150_000_000):
     """Times the CPU oracle as it stands on a bounded sample of the same workload."""
     import oracle
     order = sorted(range(workload.n_layers), key=lambda l: grads[l].size)
