@@ -131,8 +131,8 @@ class Plan:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
-            load().rsdgc_plan_destroy(h)
+        if h and _lib is not None:        # at interpreter shutdown the module may already be gone
+            _lib.rsdgc_plan_destroy(h)
 
     @property
     def handle(self):

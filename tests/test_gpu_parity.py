@@ -205,3 +205,42 @@ def test_decompress_accumulate_sums_messages():
     want = oracle.decompress(idx, val, want.size, dense=want, accumulate_into=True)
     want = oracle.decompress(idx, val, want.size, dense=want, accumulate_into=True)
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_compress_can_be_captured_in_a_hip_graph_and_replayed():
+    """rsdgc_compress enqueues kernels only (no allocation, no synchronisation, no memset node),
+    so a caller may capture it.  Every replay must reproduce the eager result, with eager work
+    and synchronisations between the replays."""
+    import torch
+    w = synth.config(1)
+    grads = synth.gradients(w, 0)
+    sess = _session(w.shapes, w.p, w.alpha, w.ratios)
+    sess.set_grad(grads)
+    sess.compress()                                  # first call uploads the plan's tables
+    torch.cuda.synchronize()
+    sess.residual.zero_()
+    sess.compress()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (sess.out_idx, sess.out_val, sess.out_counts, sess.residual,
+                               sess.out_centre_idx, sess.out_centre_counts)]
+    graph = torch.cuda.CUDAGraph()
+    sess.residual.zero_()
+    with torch.cuda.graph(graph):
+        sess.compress()
+    for rep in range(3):
+        for t in (sess.out_idx, sess.out_val, sess.out_counts, sess.out_centre_idx,
+                  sess.out_centre_counts, sess.residual):
+            t.zero_()                                # eager work between replays
+        scratch = torch.randn(1 << 20, device="cuda").sum().item()
+        assert np.isfinite(scratch)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (sess.out_idx, sess.out_val, sess.out_counts, sess.residual, sess.out_centre_idx,
+               sess.out_centre_counts)
+        counts = ref[2].cpu().numpy()
+        for l in range(w.n_layers):                  # entries past the counts are unspecified
+            o, n = sess.plan.out_offset(l), int(counts[l])
+            assert torch.equal(got[0][o:o + n], ref[0][o:o + n]), (rep, l)
+            assert torch.equal(got[1][o:o + n], ref[1][o:o + n]), (rep, l)
+        assert torch.equal(got[2], ref[2]) and torch.equal(got[3], ref[3]), rep
+        assert torch.equal(got[4], ref[4]) and torch.equal(got[5], ref[5]), rep

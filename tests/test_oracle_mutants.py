@@ -1,0 +1,148 @@
+"""Do the oracle's pins bite?  Each case plants ONE plausible mistake in a private copy of the
+oracle's C source (a dropped term, a wrong sign or index, a wrong divisor, a reversed order),
+builds it on the CPU and runs a compact battery of the pins against it.  The unmodified oracle
+must pass the whole battery; every mutant must fail at least one pin.  Nothing here touches
+the GPU or the GPU library."""
+import ctypes
+import importlib.util
+import math
+import os
+import subprocess
+
+import numpy as np
+import pytest
+from scipy import ndimage
+
+from tests.brute import brute_compress
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "rsdgc_oracle.c")
+
+
+def _load_variant(tmp_path, name, source_text):
+    """A second, independent instance of the oracle package bound to another C file."""
+    c_path = os.path.join(tmp_path, f"{name}.c")
+    so_path = os.path.join(tmp_path, f"lib{name}.so")
+    with open(c_path, "w") as f:
+        f.write(source_text)
+    subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-ffp-contract=off",
+                           c_path, "-o", so_path, "-lm"])
+    spec = importlib.util.spec_from_file_location(f"oracle_variant_{name}",
+                                                  os.path.join(ROOT, "oracle", "__init__.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    mod._SRC, mod._LIB = c_path, so_path
+    return mod
+
+
+def _replace_nth(text, old, new, n=0):
+    parts = text.split(old)
+    assert len(parts) > n + 1, f"pattern not found {n + 1} times: {old!r}"
+    return old.join(parts[:n + 1]) + new + old.join(parts[n + 1:])
+
+
+def battery(orc):
+    """Names of the pins the given oracle instance fails."""
+    fails = []
+
+    def check(name, cond):
+        if not cond:
+            fails.append(name)
+
+    rng = np.random.default_rng(2024)
+    # Eq. 11
+    check("k_golden", [orc.keep_count(262144, 3, 0.02), orc.keep_count(102760448, 5, 0.001),
+                       orc.keep_count(10, 3, 1.0), orc.keep_count(1000, 1, 0.0015)] == [583, 4111, 2, 2])
+    # Eq. 12 add
+    r = rng.standard_normal(1000).astype(np.float32)
+    g = rng.standard_normal(1000).astype(np.float32)
+    check("accumulate", np.array_equal(orc.accumulate(r, g), r + g))
+    # Eqs. 8-10: closed forms
+    c = -3.5
+    m = orc.nsi(np.full((7, 9), c, np.float32), 3, 0.25).astype(np.float64)
+    a = abs(c)
+    check("const_interior", np.allclose(m[1:-1, 1:-1], 0.25 * a, rtol=1e-6))
+    check("const_edge", np.allclose(m[0, 1:-1], a * (0.25 * 2 / 3 + 0.75 * math.sqrt(2) / 3), rtol=1e-6))
+    check("const_corner", np.isclose(m[0, 0], a * (0.25 * 4 / 9 + 0.75 * math.sqrt(20) / 9), rtol=1e-6))
+    v = np.zeros((23, 29), np.float32)
+    v[11, 14] = -0.75
+    for p in (3, 5):
+        mm = orc.nsi(v, p, 0.5).astype(np.float64)
+        check(f"impulse_p{p}", np.isclose(mm[11, 14], 0.75 * (0.5 + 0.5 * math.sqrt(p * p - 1)) / (p * p), rtol=1e-6))
+    # library box filters, non-square, offset mean
+    for p, shape in ((3, (37, 53)), (5, (5, 64)), (1, (9, 4))):
+        x = (rng.standard_normal(shape) + 0.7).astype(np.float32)
+        x64 = x.astype(np.float64)
+        box_abs = ndimage.uniform_filter(np.abs(x64), size=p, mode="constant")
+        box = ndimage.uniform_filter(x64, size=p, mode="constant")
+        box_sq = ndimage.uniform_filter(x64 * x64, size=p, mode="constant")
+        std = np.sqrt(np.maximum(box_sq - box * box, 0))
+        check(f"box_a1_p{p}", np.allclose(orc.nsi(x, p, 1.0), box_abs, rtol=1e-6, atol=1e-7))
+        check(f"box_a0_p{p}", np.allclose(orc.nsi(x, p, 0.0), std, rtol=1e-5, atol=1e-6))
+        check(f"box_mix_p{p}", np.allclose(orc.nsi(x, p, 0.3), 0.3 * box_abs + 0.7 * std, rtol=1e-5, atol=1e-6))
+    # ranking
+    s = rng.integers(0, 40, size=3000).astype(np.float32)
+    centres, tau = orc.select(s, 137)
+    order = sorted(range(s.size), key=lambda i: (-float(s[i]), i))
+    check("select", centres.tolist() == sorted(order[:137]) and tau == float(s[order[136]]))
+    # dilation
+    cs = np.sort(rng.choice(33 * 47, size=20, replace=False)).astype(np.uint32)
+    seed = np.zeros((33, 47), bool)
+    seed.ravel()[cs] = True
+    check("dilate", np.array_equal(orc.dilate(cs, 33, 47, 3).astype(bool),
+                                   ndimage.binary_dilation(seed, structure=np.ones((3, 3), bool))))
+    # one whole iteration: invariants and brute force
+    gg = (rng.standard_normal((13, 17)) * 1e-2).astype(np.float32)
+    rr = (rng.standard_normal((13, 17)) * 1e-2).astype(np.float32)
+    res = orc.compress_layer(gg, rr, 3, 0.5, 0.3)
+    vv = rr + gg
+    dense = orc.decompress(res.idx, res.val, vv.size).reshape(vv.shape)
+    check("sent_plus_residual", np.array_equal(dense + res.r_new, vv))
+    check("values", np.array_equal(res.val, vv.ravel()[res.idx]))
+    b = brute_compress(gg.tolist(), rr.tolist(), 3, 0.5, 0.3)
+    check("brute", res.k == b["k"] and res.centres.tolist() == b["centres"] and res.idx.tolist() == b["idx"]
+          and res.r_new.ravel().tolist() == b["r_new"])
+    d2 = np.ones(10, np.float32)
+    orc.decompress(np.array([2, 5], np.uint32), np.array([0.5, -1.0], np.float32), 10, dense=d2, accumulate_into=True)
+    check("decompress_acc", d2.tolist() == [1, 1, 1.5, 1, 1, 0, 1, 1, 1, 1])
+    return fails
+
+
+MUTANTS = [
+    ("signed_mean", "sum_abs += fabs(w);", "sum_abs += w;", 0),
+    ("std_about_abs_mean", "const double mean = sum / n;", "const double mean = sum_abs / n;", 0),
+    ("abs_deviation", "sq += d * d;", "sq += fabs(d);", 0),
+    ("variance_not_std", "const double std = sqrt(sq / n);", "const double std = sq / n;", 0),
+    ("sample_std", "sqrt(sq / n)", "sqrt(sq / (n - 1.0))", 0),
+    ("alpha_swapped", "return alpha * mean_abs + (1.0 - alpha) * std;",
+     "return (1.0 - alpha) * mean_abs + alpha * std;", 0),
+    ("replicate_border", "        return 0.0;\n    return (double)v[x * C + y];",
+     "        return (double)v[(x < 0 ? 0 : x >= R ? R - 1 : x) * C + (y < 0 ? 0 : y >= C ? C - 1 : y)];\n"
+     "    return (double)v[x * C + y];", 0),
+    ("divisor_p", "const double n = (double)p * (double)p;", "const double n = (double)p;", 0),
+    ("k_floor", "double kf = ceil(q * rho);", "double kf = floor(q * rho);", 0),
+    ("k_divides_by_p", "(double)((int64_t)p * (int64_t)p)", "(double)p", 0),
+    ("ties_to_higher_index", "if (p->index < q->index) return -1;\n    if (p->index > q->index) return 1;",
+     "if (p->index < q->index) return 1;\n    if (p->index > q->index) return -1;", 0),
+    ("rank_ascending", "if (p->score > q->score) return -1;\n    if (p->score < q->score) return 1;",
+     "if (p->score > q->score) return 1;\n    if (p->score < q->score) return -1;", 0),
+    ("one_sided_window", "for (int dx = -h; dx <= h; ++dx)", "for (int dx = -h; dx < h; ++dx)", 0),
+    ("one_sided_dilation", "for (int dx = -h; dx <= h; ++dx)", "for (int dx = -h; dx < h; ++dx)", 2),
+    ("residual_keeps_sent", "r_new[i] = mask[i] ? 0.0f : v[i];", "r_new[i] = v[i];", 0),
+    ("emit_abs_value", "val[n] = v[i];", "val[n] = fabsf(v[i]);", 0),
+    ("accumulate_subtracts", "volatile float s = r[i] + g[i];", "volatile float s = r[i] - g[i];", 0),
+    ("decompress_overwrites", "volatile float s = dense[idx[j]] + val[j];", "volatile float s = val[j];", 0),
+]
+
+
+def test_unmodified_oracle_passes_the_battery(tmp_path):
+    orc = _load_variant(str(tmp_path), "plain", open(SRC).read())
+    assert battery(orc) == []
+
+
+@pytest.mark.parametrize("name,old,new,nth", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_every_planted_mistake_is_caught(tmp_path, name, old, new, nth):
+    text = _replace_nth(open(SRC).read(), old, new, nth)
+    orc = _load_variant(str(tmp_path), name, text)
+    fails = battery(orc)
+    assert fails, f"mutant {name} slipped through every pin"
