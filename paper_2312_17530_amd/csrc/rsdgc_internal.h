@@ -18,6 +18,7 @@ constexpr int kSlotCap = 256;        // candidate centres one tile can record
 constexpr int kSlotGroup = 64;       // tile slots per workgroup in the candidate passes
 constexpr int kCandBins = 256;       // 12-bit score buckets above the bound that a capture workgroup counts
 constexpr int kListMin = 8192;       // smallest threshold-bucket list of a layer (entries)
+constexpr int kList2Cap = 2048;      // keys sharing the first two digits that a layer can stage
 constexpr int kListDiv = 32;         // ... or 1/32 of the layer, whichever is larger
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 
@@ -103,6 +104,7 @@ struct WsLayout {
     size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk, then their prefix
     size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk, then prefix
     size_t list_cnt = 0;     // uint32[n_layers]  keys gathered from the threshold bucket
+    size_t list2_cnt = 0;    // uint32[n_layers]  of those, keys that also share the second digit
     size_t mask = 0;         // uint32[total_elems / 32]  kept-element bitmask
     size_t cmask = 0;        // uint32[total_elems / 32]  selected-centre bitmask
     size_t zero_end = 0;
@@ -110,6 +112,7 @@ struct WsLayout {
     size_t slot_cnt = 0;     // uint32[n_tiles_all]  candidates recorded per tile
     size_t slot_ent = 0;     // uint64[n_tiles_all][kSlotCap]  their composite keys
     size_t list_ent = 0;     // uint64[sum list_cap]  composite keys of each layer's threshold bucket
+    size_t list2_ent = 0;    // uint64[n_layers][kList2Cap]  keys sharing the first two digits
     size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
     size_t total = 0;
 };

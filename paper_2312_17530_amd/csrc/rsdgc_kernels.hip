@@ -742,34 +742,82 @@ __device__ __forceinline__ DigitResult block_find_digit(const uint32_t *h, int n
     return r;
 }
 
-// One workgroup (1024 threads) per layer finishes the radix select.  The second digit comes
-// from the histogram the gather pass left; one pass over the layer's threshold-bucket list
-// then keeps the keys that share both digits (a few hundred at most, staged in LDS), and
-// the remaining score digits and -- only if equal scores straddle the k-th rank -- the digits
-// of ~index (the lower index wins) are resolved on that staged set.
-// Slow but exact routes: if the staged set overflows, the later digits are histogrammed
-// from the list; if the bucket did not fit the list at all (a huge number of nearly equal
-// scores, e.g. an all-zero layer), every digit is histogrammed by streaming the layer's keys
-// from the score map or the tile slots.
+// --------------------------------------------------------------- filter --
+// After the second digit: kFilterSplit workgroups per layer go through the layer's
+// threshold-bucket list and keep the keys that share both digits (typically a few dozen) in
+// the layer's second, small list.
+constexpr int kFilterSplit = 32;
 constexpr int kFinishThreads = 1024;
-constexpr int kFinishStage = 2048;
+
+__global__ __launch_bounds__(kFinishThreads) void k_filter(const LayerDev *__restrict__ layers,
+                                                           const SelState *__restrict__ state,
+                                                           const uint32_t *__restrict__ list_cnt,
+                                                           const unsigned long long *__restrict__ list_ent,
+                                                           uint32_t *__restrict__ list2_cnt,
+                                                           unsigned long long *__restrict__ list2_ent) {
+    __shared__ unsigned long long stage[kList2Cap];
+    __shared__ uint32_t nstage, base;
+    const int l = blockIdx.x / kFilterSplit, part = blockIdx.x % kFilterSplit, tid = threadIdx.x;
+    const SelState st = state[l];
+    if (st.done || st.mode == kModeSkip) return;
+    const LayerDev L = layers[l];
+    const uint32_t n = list_cnt[l];
+    if (n > L.list_cap) return;            // the bucket did not fit: the finish streams the layer
+    const unsigned long long *__restrict__ list = list_ent + L.list_off;
+    if (tid == 0) nstage = 0;
+    __syncthreads();
+    const unsigned long long want = st.T >> level_shift(1);
+    constexpr uint32_t U = 4;              // independent loads in flight per thread
+    for (uint32_t i0 = part * U * kFinishThreads; i0 < n; i0 += kFilterSplit * U * kFinishThreads) {
+        unsigned long long K[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t i = i0 + u * kFinishThreads + tid;
+            K[u] = i < n ? list[i] : ~0ull;                    // ~0 never matches a prefix
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u)
+            if ((K[u] >> level_shift(1)) == want) {
+                const uint32_t pos = atomicAdd(&nstage, 1u);
+                if (pos < static_cast<uint32_t>(kList2Cap)) stage[pos] = K[u];
+            }
+    }
+    __syncthreads();
+    const uint32_t m = nstage;
+    if (m == 0) return;                    // uniform
+    if (tid == 0) base = atomicAdd(&list2_cnt[l], m);          // counts past the capacity too
+    __syncthreads();
+    const uint32_t b0 = base;
+    for (uint32_t i = tid; i < min(m, static_cast<uint32_t>(kList2Cap)); i += kFinishThreads)
+        if (b0 + i < static_cast<uint32_t>(kList2Cap))
+            list2_ent[static_cast<size_t>(l) * kList2Cap + b0 + i] = stage[i];
+}
+
+// One workgroup (1024 threads) per layer finishes the radix select on the layer's second list
+// (staged in LDS): the remaining score digits and -- only if equal scores straddle the k-th
+// rank -- the digits of ~index, so that the lower index wins.
+// Slow but exact routes: if the second list overflowed, the later digits are histogrammed
+// from the threshold-bucket list; if that did not fit either (a huge number of nearly equal
+// scores, e.g. an all-zero layer), they are histogrammed by streaming the layer's keys from
+// the score map or the tile slots.
+constexpr int kFinishStage = kList2Cap;
 
 __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__restrict__ layers,
                                                            SelState *__restrict__ state,
-                                                           const uint32_t *__restrict__ hist,
                                                            const uint32_t *__restrict__ list_cnt,
                                                            const unsigned long long *__restrict__ list_ent,
+                                                           const uint32_t *__restrict__ list2_cnt,
+                                                           const unsigned long long *__restrict__ list2_ent,
                                                            const uint32_t *__restrict__ keys,
                                                            const uint32_t *__restrict__ slot_cnt,
                                                            const unsigned long long *__restrict__ slot_ent) {
     __shared__ uint32_t lh[2048];
     __shared__ unsigned long long sel[kFinishStage];
-    __shared__ uint32_t nsel;
     __shared__ uint32_t wave_tot[kFinishThreads / 64];
     __shared__ DigitResult res;
     constexpr int NW = kFinishThreads / 64;
     const int l = blockIdx.x, tid = threadIdx.x;
-    const SelState st = state[l];
+    const SelState st = state[l];          // first two digits are fixed
     if (st.done || st.mode == kModeSkip) return;
     const LayerDev L = layers[l];
     const uint32_t n = list_cnt[l];
@@ -778,42 +826,13 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
     unsigned long long T = st.T;
     uint32_t k_rem = st.k_rem;
     bool done = false;
-    int lv = 1;
-    bool staged = false;
-    if (use_list) {
-        // second digit from the gather pass's histogram
-        const DigitResult r = block_find_digit<NW>(hist + static_cast<size_t>(l) * kHistBins,
-                                                   1 << level_bits(1), k_rem, wave_tot, &res);
-        if (r.found) {
-            T |= static_cast<unsigned long long>(r.digit) << level_shift(1);
-            k_rem -= r.above;
-            done = r.count == k_rem;
-            lv = 2;
-            if (!done) {                   // keep the keys that share both digits
-                if (tid == 0) nsel = 0;
-                __syncthreads();
-                const unsigned long long want = T >> level_shift(1);
-                constexpr uint32_t U = 8;  // independent loads in flight per thread
-                for (uint32_t i0 = 0; i0 < n; i0 += U * kFinishThreads) {
-                    unsigned long long K[U];
-#pragma unroll
-                    for (uint32_t u = 0; u < U; ++u) {
-                        const uint32_t i = i0 + u * kFinishThreads + tid;
-                        K[u] = i < n ? list[i] : ~0ull;        // ~0 never matches a prefix
-                    }
-#pragma unroll
-                    for (uint32_t u = 0; u < U; ++u)
-                        if ((K[u] >> level_shift(1)) == want) {
-                            const uint32_t pos = atomicAdd(&nsel, 1u);
-                            if (pos < static_cast<uint32_t>(kFinishStage)) sel[pos] = K[u];
-                        }
-                }
-                __syncthreads();
-                staged = nsel <= static_cast<uint32_t>(kFinishStage);
-            }
-        } else {
-            done = true;                   // fewer keys than k_rem (cannot happen for finite input)
-        }
+    int lv = 2;
+    const uint32_t nsel = use_list ? list2_cnt[l] : 0xffffffffu;
+    const bool staged = nsel <= static_cast<uint32_t>(kFinishStage);
+    if (staged) {
+        for (uint32_t i = tid; i < nsel; i += kFinishThreads)
+            sel[i] = list2_ent[static_cast<size_t>(l) * kList2Cap + i];
+        __syncthreads();
     }
     for (; lv < kLevels && !done; ++lv) {
         const int shift = level_shift(lv), nb = 1 << level_bits(lv), shift_prev = level_shift(lv - 1);
@@ -1453,8 +1472,15 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
                            chunk_dir, group_dir, static_cast<uint32_t>(L), n_map_wgs, n_chunks,
                            plan->n_slot_groups, state, reinterpret_cast<const uint32_t *>(nsi),
                            slot_cnt, slot_ent, list_cnt, list_ent, hist);
-        hipLaunchKernelGGL(k_finish, dim3(L), dim3(kFinishThreads), 0, stream, layers, state, hist, list_cnt, list_ent,
-                           reinterpret_cast<const uint32_t *>(nsi), slot_cnt, slot_ent);
+        uint32_t *list2_cnt = reinterpret_cast<uint32_t *>(ws + w.list2_cnt);
+        unsigned long long *list2_ent = reinterpret_cast<unsigned long long *>(ws + w.list2_ent);
+        hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(1),
+                           level_bits(1));
+        hipLaunchKernelGGL(k_filter, dim3(L * kFilterSplit), dim3(kFinishThreads), 0, stream, layers,
+                           state, list_cnt, list_ent, list2_cnt, list2_ent);
+        hipLaunchKernelGGL(k_finish, dim3(L), dim3(kFinishThreads), 0, stream, layers, state, list_cnt,
+                           list_ent, list2_cnt, list2_ent, reinterpret_cast<const uint32_t *>(nsi),
+                           slot_cnt, slot_ent);
     }
     HIP_TRY(hipGetLastError());
     marks.close(4);

@@ -144,12 +144,14 @@ int build_tables(rsdgc_plan_s *plan) {
     w.chunk_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * L, A);
+    w.list2_cnt = off;    off = align_up(off + sizeof(uint32_t) * L, A);
     w.mask = off;         off = align_up(off + sizeof(uint32_t) * words, A);
     w.cmask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
     w.zero_end = off;
     w.slot_cnt = off;     off = align_up(off + sizeof(uint32_t) * plan->n_tiles_all, A);
     w.slot_ent = off;     off = align_up(off + sizeof(uint64_t) * kSlotCap * size_t(plan->n_tiles_all), A);
     w.list_ent = off;     off = align_up(off + sizeof(uint64_t) * static_cast<size_t>(list_off), A);
+    w.list2_ent = off;    off = align_up(off + sizeof(uint64_t) * kList2Cap * size_t(L), A);
     w.nsi = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
     w.total = off;
 
