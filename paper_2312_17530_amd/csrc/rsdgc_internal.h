@@ -96,6 +96,7 @@ struct WsLayout {
     size_t all_tile_dir = 0; // DirEntry[n_layers + 1]: tiles of all layers in layer order
     size_t group_dir = 0;    // DirEntry[n_layers + 1]: slot groups
     size_t samples = 0;      // SampleEntry[] per p-group
+    size_t chunk_layer = 0;  // uint32[n_chunks]: layer of every 8192-element chunk
     size_t table_bytes = 0;  // bytes uploaded from the host
     size_t state = 0;        // SelState[n_layers], rewritten at the start of every compress
     // cleared at the start of every compress

@@ -1094,8 +1094,7 @@ __global__ __launch_bounds__(256) void k_mark_map(const LayerDev *__restrict__ l
 
 // ---------------------------------------------------------------- count --
 __global__ __launch_bounds__(256) void k_count(const LayerDev *__restrict__ layers,
-                                               const DirEntry *__restrict__ chunk_dir,
-                                               uint32_t n_layers,
+                                               const uint32_t *__restrict__ chunk_layer,
                                                const uint32_t *__restrict__ mask,
                                                const uint32_t *__restrict__ cmask,
                                                uint32_t *__restrict__ chunk_cnt,
@@ -1103,7 +1102,7 @@ __global__ __launch_bounds__(256) void k_count(const LayerDev *__restrict__ laye
     __shared__ uint32_t wave_tot[4];
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const uint32_t l = chunk_layer[c];
     const LayerDev L = layers[l];
     const uint32_t start = (c - L.chunk_begin) * kChunk;
     const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
@@ -1162,8 +1161,7 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(const LayerDev *__restric
 // the position given by the chunk prefix plus the popcount of the mask bits before them;
 // the residual becomes +0 where kept and v elsewhere.
 __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layers,
-                                              const DirEntry *__restrict__ chunk_dir,
-                                              uint32_t n_layers, const float *__restrict__ grad,
+                                              const uint32_t *__restrict__ chunk_layer, const float *__restrict__ grad,
                                               float *__restrict__ resid,
                                               const uint32_t *__restrict__ mask,
                                               const uint32_t *__restrict__ chunk_base,
@@ -1174,23 +1172,59 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
     __shared__ uint32_t s_pref[256];
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const uint32_t l = chunk_layer[c];
     const LayerDev L = layers[l];
     const uint32_t start = (c - L.chunk_begin) * kChunk;
     const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
     const size_t base = static_cast<size_t>(L.elem_off) + start;
     const uint32_t nwords = (len + 31) >> 5;
     const uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(base >> 5) + tid] : 0;
-    const uint32_t cnt = __popc(word);
-    s_word[tid] = word;
-    const uint32_t incl = block_scan_incl(cnt, wave_tot);
-    s_pref[tid] = incl - cnt;
-    __syncthreads();
     const float *__restrict__ g = grad + base;
     float *__restrict__ r = resid + base;
     const uint32_t cbase = chunk_base[c];
     const size_t obase = static_cast<size_t>(L.out_off) + cbase;
     const uint32_t room = L.cap > cbase ? L.cap - cbase : 0u;   // never write past the segment
+    const bool whole = len == static_cast<uint32_t>(kChunk);
+    // A whole chunk: every load is issued before the mask scan, so the scan's latency and the
+    // loads overlap and each thread keeps 16 wide loads in flight.
+    float4 gq[kChunk / 1024], rq[kChunk / 1024];
+    if (whole) {
+#pragma unroll
+        for (int j = 0; j < kChunk / 1024; ++j) {
+            gq[j] = *reinterpret_cast<const float4 *>(g + j * 1024 + 4 * tid);
+            rq[j] = *reinterpret_cast<const float4 *>(r + j * 1024 + 4 * tid);
+        }
+    }
+    const uint32_t cnt = __popc(word);
+    s_word[tid] = word;
+    const uint32_t incl = block_scan_incl(cnt, wave_tot);
+    s_pref[tid] = incl - cnt;
+    __syncthreads();
+    if (whole) {
+#pragma unroll
+        for (int j = 0; j < kChunk / 1024; ++j) {
+            const uint32_t e = j * 1024 + 4 * tid;
+            const uint32_t w = s_word[e >> 5];
+            const uint32_t sh = e & 31;
+            const uint32_t bits = (w >> sh) & 0xfu;
+            float v[4] = {rq[j].x + gq[j].x, rq[j].y + gq[j].y, rq[j].z + gq[j].z, rq[j].w + gq[j].w};
+            if (bits) {
+                uint32_t pos = s_pref[e >> 5] + __popc(w & ((1u << sh) - 1u));
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (bits & (1u << q)) {
+                        if (pos < room) {
+                            out_idx[obase + pos] = start + e + q;
+                            out_val[obase + pos] = v[q];
+                        }
+                        ++pos;
+                        v[q] = 0.f;
+                    }
+            }
+            *reinterpret_cast<float4 *>(r + e) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+        return;
+    }
 #pragma unroll 2
     for (int j = 0; j < kChunk / 1024; ++j) {
         const uint32_t e = j * 1024 + 4 * tid;
@@ -1236,15 +1270,14 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
 
 // Ascending list of the selected centres of every layer.
 __global__ __launch_bounds__(256) void k_emit_centres(const LayerDev *__restrict__ layers,
-                                                      const DirEntry *__restrict__ chunk_dir,
-                                                      uint32_t n_layers,
+                                                      const uint32_t *__restrict__ chunk_layer,
                                                       const uint32_t *__restrict__ cmask,
                                                       const uint32_t *__restrict__ chunk_cbase,
                                                       uint32_t *__restrict__ out_centre_idx) {
     __shared__ uint32_t wave_tot[4];
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const uint32_t l = chunk_layer[c];
     const LayerDev L = layers[l];
     const uint32_t start = (c - L.chunk_begin) * kChunk;
     const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
@@ -1264,11 +1297,10 @@ __global__ __launch_bounds__(256) void k_emit_centres(const LayerDev *__restrict
 
 // ----------------------------------------------------------- decompress --
 __global__ __launch_bounds__(256) void k_zero_layers(const LayerDev *__restrict__ layers,
-                                                     const DirEntry *__restrict__ chunk_dir,
-                                                     uint32_t n_layers, float *__restrict__ dense) {
+                                                     const uint32_t *__restrict__ chunk_layer, float *__restrict__ dense) {
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_dir[dir_lookup(chunk_dir, n_layers, c)].layer;
+    const uint32_t l = chunk_layer[c];
     const LayerDev L = layers[l];
     const uint32_t start = (c - L.chunk_begin) * kChunk;
     const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
@@ -1494,17 +1526,16 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
                        static_cast<uint32_t>(L), plan->n_tiles_all, state,
                        reinterpret_cast<const uint32_t *>(nsi), mask, cmask);
     marks.close(5);
-    hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
-                       static_cast<uint32_t>(L), mask, cmask, chunk_cnt, chunk_ccnt);
+    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + w.chunk_layer);
+    hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, mask, cmask, chunk_cnt, chunk_ccnt);
     hipLaunchKernelGGL(k_scan, dim3(L), dim3(kScanThreads), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
                        out_counts, out_centre_counts, cmask ? 1 : 0);
     marks.close(6);
-    hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
-                       static_cast<uint32_t>(L), grad, residual, mask, chunk_cnt, out_idx, out_val);
+    hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, grad, residual, mask, chunk_cnt, out_idx, out_val);
     marks.close(7);
     if (out_centre_idx)
-        hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_dir,
-                           static_cast<uint32_t>(L), cmask, chunk_ccnt, out_centre_idx);
+        hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer,
+                           cmask, chunk_ccnt, out_centre_idx);
     marks.close(8);
     HIP_TRY(hipGetLastError());
     return RSDGC_OK;
@@ -1607,10 +1638,10 @@ int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
     const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
-    const DirEntry *chunk_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.chunk_dir);
+    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + plan->ws.chunk_layer);
     if (!accumulate)
         hipLaunchKernelGGL(k_zero_layers, dim3(plan->n_chunks), dim3(256), 0, stream, layers,
-                           chunk_dir, static_cast<uint32_t>(plan->n_layers), dense);
+                           chunk_layer, dense);
     if (plan->out_capacity > 0) {
         const unsigned blocks = static_cast<unsigned>((plan->out_capacity + 255) / 256);
         hipLaunchKernelGGL(k_scatter, dim3(blocks), dim3(256), 0, stream, layers, plan->n_layers,

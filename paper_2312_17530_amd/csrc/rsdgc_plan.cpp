@@ -137,6 +137,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.all_tile_dir = off; off = align_up(off + sizeof(DirEntry) * (L + 1), A);
     w.group_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + 1), A);
     w.samples = off;      off = align_up(off + sizeof(SampleEntry) * (max_samples + 1), A);
+    w.chunk_layer = off;  off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.table_bytes = off;
     w.state = off;        off = align_up(off + sizeof(SelState) * L, A);   // written in full each call
     w.zero_begin = off;
@@ -168,6 +169,12 @@ int build_tables(rsdgc_plan_s *plan) {
     if (!plan->samples.empty())
         std::memcpy(plan->table.data() + w.samples, plan->samples.data(),
                     sizeof(SampleEntry) * plan->samples.size());
+    {
+        uint32_t *cl = reinterpret_cast<uint32_t *>(plan->table.data() + w.chunk_layer);
+        for (int l = 0; l < L; ++l)
+            for (uint32_t c = 0; c < plan->layers[l].n_chunks; ++c)
+                cl[plan->layers[l].chunk_begin + c] = static_cast<uint32_t>(l);
+    }
     ++plan->version;
     return RSDGC_OK;
 }
