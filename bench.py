@@ -30,21 +30,27 @@ METRIC = "gradient elements compressed/sec (full-model, 1 GPU) and % of HBM peak
 
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); the summaries are
-# in profiles/.  Keyed by (workload name, stage).  None = not measured.
+# in profiles/.  Keyed by (workload name, stage, residual update).  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("vgg19_45c", "emit"): 1.717e9,      # profiles/hbm_traffic_vgg19.md
-    ("vgg19_45c", "capture"): 1.2965e9,  # profiles/hbm_traffic_vgg19.md
+    ("vgg19_45c", "emit", "in_place"): 1.717e9,      # profiles/hbm_traffic_vgg19.md
+    ("vgg19_45c", "capture", "in_place"): 1.2965e9,  # profiles/hbm_traffic_vgg19.md
 }
 
 
-def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems: int) -> float:
-    """Bytes a stage has to move by its own contract (float32 data)."""
+def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems: int,
+                            in_place: bool) -> float:
+    """Bytes a stage has to move by its own contract (float32 data).  With two residual
+    arenas the NSI passes also store v = r + g (4 more bytes per element) and the emit only
+    touches the kept elements; in place the emit streams g and r again and rewrites r."""
+    v_store = 0.0 if in_place else 4.0
     if stage == "capture":    # read g, read r of the candidate-mode layers (candidates are < 1 %)
-        return 8.0 * n_cand_elems
+        return (8.0 + v_store) * n_cand_elems
     if stage == "full_map":   # read g, read r, write the score map of the full-map layers
-        return 12.0 * (n_elems - n_cand_elems)
-    if stage == "emit":       # read g, read r, write r, write (index, value) pairs
-        return 12.0 * n_elems + 8.0 * n_pairs
+        return (12.0 + v_store) * (n_elems - n_cand_elems)
+    if stage == "emit":
+        if in_place:          # read g, read r, write r, write (index, value) pairs
+            return 12.0 * n_elems + 8.0 * n_pairs
+        return n_elems / 8.0 + 16.0 * n_pairs   # mask bits; per pair: read v, write +0, index, value
     return 0.0
 
 
@@ -81,6 +87,9 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy three times before the timed region "
                          "(reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--in-place", action="store_true",
+                    help="update the residual in its own arena (one more streaming pass) instead of "
+                         "writing the new residual to a second arena")
     ap.add_argument("--full-map", action="store_true",
                     help="force the full-score-map ranking path for every layer")
     args = ap.parse_args()
@@ -101,7 +110,8 @@ def main() -> int:
     w = synth.config(args.config)
     grads = synth.gradients(w, 0)
     sess = Session(w.shapes, w.p, w.alpha, w.ratios, want_centres=args.centres,
-                   path=binding.RSDGC_PATH_FULL_MAP if args.full_map else binding.RSDGC_PATH_AUTO)
+                   path=binding.RSDGC_PATH_FULL_MAP if args.full_map else binding.RSDGC_PATH_AUTO,
+                   in_place=args.in_place)
     sess.set_grad(grads)
     G = w.total_elems
     stream = torch.cuda.current_stream()
@@ -155,11 +165,11 @@ def main() -> int:
         n_cand = sum(r * c for (r, c), pth in zip(w.shapes, paths) if pth == 0)
         dom = max(("capture", "full_map", "emit"), key=lambda s: stages.get(s, 0.0))
         dur_s = stages[dom] * 1e-3
-        alg = stage_algorithmic_bytes(dom, G, n_pairs, n_cand)
+        alg = stage_algorithmic_bytes(dom, G, n_pairs, n_cand, args.in_place)
         achieved = alg / dur_s / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom, "in_place" if args.in_place else "two_arenas")),
                     "algorithmic_bytes": alg, "avg_ms": stages[dom],
                     "elements_on_candidate_path": n_cand,
                     "path_algorithmic_bytes": 12.0 * G + 8.0 * n_pairs,
@@ -173,7 +183,8 @@ def main() -> int:
                    "alpha": w.alpha, "mean_keep_ratio": float(np.average(w.ratios, weights=[r * c for r, c in w.shapes])),
                    "pairs_emitted_last_step": n_pairs, "centre_lists": bool(args.centres),
                    "ranking_path": "full_map" if args.full_map else "auto",
-                   "residual": "carried across steps"},
+                   "residual": "carried across steps",
+                   "residual_update": "in_place" if args.in_place else "two_arenas"},
         "roofline": roofline,
         "stages_ms": {k: round(v, 5) for k, v in stages.items()},
         "stages_recorded_calls": n_rec,

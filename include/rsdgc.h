@@ -103,9 +103,17 @@ size_t  rsdgc_workspace_bytes(const rsdgc_plan_t *plan);
  * One iteration of the sparsifier for all layers (Eq. 2's Sparse, Algorithm 1
  * inner loop, Eq. 12 with u = g).
  *   grad      [device, const] float32 arena: this iteration's gradient g.
- *   residual  [device, in/out] float32 arena: on entry the carried residual r
- *             (all zeros before the first iteration); v = r + g is formed with
- *             one float32 add; on exit r = +0 where v was emitted, v elsewhere.
+ *   residual  [device, const] float32 arena: the carried residual r (all
+ *             zeros before the first iteration); v = r + g is formed with one
+ *             float32 add.
+ *   residual_out [device] float32 arena that receives the new residual: +0
+ *             where v was emitted, v elsewhere.  Either a second arena that
+ *             overlaps neither residual nor grad (the caller swaps the two
+ *             pointers between iterations; v is stored while the scores are
+ *             computed and only the kept elements are touched afterwards:
+ *             12 bytes of HBM traffic per element), or residual_out == residual
+ *             for an update in place (one more streaming pass over g and r:
+ *             20 bytes per element).  Any other overlap is RSDGC_EINVAL.
  *   out_idx   [device] uint32, rsdgc_out_capacity entries.  Layer l's pairs
  *   out_val   [device] float32, same length.     start at rsdgc_out_offset(l);
  *             idx is the flat row-major index x*C + y inside the layer,
@@ -126,8 +134,8 @@ size_t  rsdgc_workspace_bytes(const rsdgc_plan_t *plan);
  * Ranking ties are resolved towards the lower flat index; exactly k_l centres
  * are selected.  Scores are float32 roundings of double-precision window
  * statistics.                                                               */
-int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual,
-                   uint32_t *out_idx, float *out_val, int32_t *out_counts,
+int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
+                   float *residual_out, uint32_t *out_idx, float *out_val, int32_t *out_counts,
                    uint32_t *out_centre_idx, int32_t *out_centre_counts,
                    void *workspace, void *stream);
 

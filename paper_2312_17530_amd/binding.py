@@ -80,7 +80,7 @@ def load() -> ctypes.CDLL:
         getattr(lib, name).restype = i64
     lib.rsdgc_workspace_bytes.argtypes = [vp]
     lib.rsdgc_workspace_bytes.restype = ctypes.c_size_t
-    lib.rsdgc_compress.argtypes = [vp] * 10
+    lib.rsdgc_compress.argtypes = [vp] * 11
     lib.rsdgc_compress.restype = ctypes.c_int
     lib.rsdgc_nsi.argtypes = [vp] * 6
     lib.rsdgc_nsi.restype = ctypes.c_int
@@ -201,9 +201,10 @@ def rsdgc_plan_set_path(plan: Plan, path: int) -> None:
     _check(load().rsdgc_plan_set_path(plan.handle, int(path)), "rsdgc_plan_set_path")
 
 
-def rsdgc_compress(plan: Plan, grad, residual, out_idx, out_val, out_counts, workspace,
+def rsdgc_compress(plan: Plan, grad, residual, residual_out, out_idx, out_val, out_counts, workspace,
                    out_centre_idx=None, out_centre_counts=None, stream=None) -> None:
-    _check(load().rsdgc_compress(plan.handle, _ptr(grad), _ptr(residual), _ptr(out_idx),
+    """residual_out is a second arena, or the same tensor as residual for an update in place."""
+    _check(load().rsdgc_compress(plan.handle, _ptr(grad), _ptr(residual), _ptr(residual_out), _ptr(out_idx),
                                  _ptr(out_val), _ptr(out_counts), _ptr(out_centre_idx),
                                  _ptr(out_centre_counts), _ptr(workspace), _stream(stream)),
            "rsdgc_compress")

@@ -168,6 +168,7 @@ struct NsiArgs {
     const float *grad;
     const float *resid;           // nullable: all-zero residual
     float *nsi_out;               // score map (kPassMapOnly, kPassFullMap)
+    float *v_out;                 // nullable: second residual arena that receives v = r + g
     uint32_t *hist;               // [n_layers][kHistBins]
     const SelState *state;
     SelState *state_rw;           // same array; only the overflow flag is written (capture)
@@ -198,6 +199,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     constexpr bool MAP = PASS == kPassMapOnly || PASS == kPassFullMap;
     constexpr bool CAPTURE = PASS == kPassCapture;
     constexpr bool FULLHIST = PASS == kPassFullMap || PASS == kPassSample;
+    constexpr bool STORE_V = PASS == kPassFullMap || PASS == kPassCapture;
     constexpr int NBINS = FULLHIST ? kHistBins : (CAPTURE ? kCandBins : 1);
     __shared__ __attribute__((aligned(16))) float tile[ROWS * PITCH];
     __shared__ uint32_t lhist[NBINS];
@@ -306,6 +308,12 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                     v.z = rv[it].z + gv[it].z;
                     v.w = rv[it].w + gv[it].w;
                     *reinterpret_cast<float4 *>(&tile[s * 4]) = v;   // s*4 == rr*PITCH + 4*j4
+                    if (STORE_V && a.v_out) {      // the tile's own elements (not the halo) go out once
+                        const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
+                        const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
+                        if (rr >= H && rr < H + kTileRows && j4 >= 1 && j4 <= kTileCols / 4 && x < R && y < C)
+                            *reinterpret_cast<float4 *>(a.v_out + L.elem_off + static_cast<size_t>(x) * C + y) = v;
+                    }
                 }
             }
         } else {
@@ -316,6 +324,8 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                 if (x >= 0 && x < R && y >= 0 && y < C) {
                     const size_t off = static_cast<size_t>(x) * C + y;
                     v = (r ? r[off] : 0.f) + g[off];
+                    if (STORE_V && a.v_out && rr >= H && rr < H + kTileRows && j >= PADL && j < PADL + kTileCols)
+                        a.v_out[L.elem_off + off] = v;
                 }
                 tile[s] = v;
             }
@@ -1268,6 +1278,66 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
     }
 }
 
+// Two-buffer form of the emit: the NSI passes have already stored v = r + g in the second
+// residual arena, so only the kept elements are touched -- their value goes out and the
+// arena gets +0 there.  A chunk without kept elements costs one read of its mask words.  A
+// layer with k_l = 0 went through no NSI pass; its v is formed here.
+__global__ __launch_bounds__(256) void k_emit_sparse(const LayerDev *__restrict__ layers,
+                                                     const uint32_t *__restrict__ chunk_layer,
+                                                     const SelState *__restrict__ state,
+                                                     const float *__restrict__ grad,
+                                                     const float *__restrict__ resid_in,
+                                                     float *__restrict__ v_arena,
+                                                     const uint32_t *__restrict__ mask,
+                                                     const uint32_t *__restrict__ chunk_base,
+                                                     uint32_t *__restrict__ out_idx,
+                                                     float *__restrict__ out_val) {
+    __shared__ uint32_t wave_tot[4];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const uint32_t l = chunk_layer[c];
+    const LayerDev L = layers[l];
+    const uint32_t start = (c - L.chunk_begin) * kChunk;
+    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
+    const size_t base = static_cast<size_t>(L.elem_off) + start;
+    float *__restrict__ v = v_arena + base;
+    if (state[l].mode == kModeSkip) {
+        const float *__restrict__ g = grad + base;
+        const float *__restrict__ r = resid_in + base;
+        for (uint32_t e = 4 * tid; e < len; e += 1024) {
+            if (e + 3 < len) {
+                const float4 gv = *reinterpret_cast<const float4 *>(g + e);
+                const float4 rv = *reinterpret_cast<const float4 *>(r + e);
+                *reinterpret_cast<float4 *>(v + e) = make_float4(rv.x + gv.x, rv.y + gv.y, rv.z + gv.z, rv.w + gv.w);
+            } else {
+                for (uint32_t q = 0; q < 4 && e + q < len; ++q) v[e + q] = r[e + q] + g[e + q];
+            }
+        }
+        return;
+    }
+    const uint32_t nwords = (len + 31) >> 5;
+    uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(base >> 5) + tid] : 0;
+    if (!__syncthreads_or(word != 0u)) return;
+    const uint32_t cnt = __popc(word);
+    const uint32_t incl = block_scan_incl(cnt, wave_tot);
+    const uint32_t cbase = chunk_base[c];
+    const size_t obase = static_cast<size_t>(L.out_off) + cbase;
+    const uint32_t room = L.cap > cbase ? L.cap - cbase : 0u;   // never write past the segment
+    uint32_t pos = incl - cnt;
+    while (word) {
+        const uint32_t b = static_cast<uint32_t>(__ffs(word)) - 1u;
+        word &= word - 1u;
+        const uint32_t e = 32u * static_cast<uint32_t>(tid) + b;
+        if (e >= len) break;                // (mask bits exist only for elements of the layer)
+        if (pos < room) {
+            out_idx[obase + pos] = start + e;
+            out_val[obase + pos] = v[e];
+        }
+        v[e] = 0.f;
+        ++pos;
+    }
+}
+
 // Ascending list of the selected centres of every layer.
 __global__ __launch_bounds__(256) void k_emit_centres(const LayerDev *__restrict__ layers,
                                                       const uint32_t *__restrict__ chunk_layer,
@@ -1363,8 +1433,9 @@ uint32_t resident_workgroups(K kernel) {
 // are in another mode leave at once).
 template <int PASS>
 int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const float *resid,
-               float *nsi_out, hipStream_t stream) {
+               float *nsi_out, float *v_out, hipStream_t stream) {
     NsiArgs a;
+    a.v_out = v_out;
     a.layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
     a.grad = grad;
     a.resid = resid;
@@ -1434,12 +1505,22 @@ extern "C" {
 
 const char *rsdgc_last_hip_error(void) { return g_hip_error; }
 
-int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint32_t *out_idx,
-                   float *out_val, int32_t *out_counts, uint32_t *out_centre_idx,
-                   int32_t *out_centre_counts, void *workspace, void *stream_) {
-    if (!plan || !grad || !residual || !out_idx || !out_val || !out_counts || !workspace)
+int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
+                   float *residual_out, uint32_t *out_idx, float *out_val, int32_t *out_counts,
+                   uint32_t *out_centre_idx, int32_t *out_centre_counts, void *workspace,
+                   void *stream_) {
+    if (!plan || !grad || !residual || !residual_out || !out_idx || !out_val || !out_counts || !workspace)
         return RSDGC_EINVAL;
-    if (!aligned256(workspace) || !aligned16(grad) || !aligned16(residual)) return RSDGC_EINVAL;
+    if (!aligned256(workspace) || !aligned16(grad) || !aligned16(residual) || !aligned16(residual_out))
+        return RSDGC_EINVAL;
+    const bool in_place = residual_out == residual;
+    if (!in_place) {    // two arenas: they must not overlap, and the new one must not be the gradient
+        const uintptr_t bytes = static_cast<uintptr_t>(plan->total_elems) * sizeof(float);
+        const uintptr_t o = reinterpret_cast<uintptr_t>(residual_out);
+        const uintptr_t r = reinterpret_cast<uintptr_t>(residual), g = reinterpret_cast<uintptr_t>(grad);
+        if ((o < r + bytes && r < o + bytes) || (o < g + bytes && g < o + bytes)) return RSDGC_EINVAL;
+    }
+    float *v_out = in_place ? nullptr : residual_out;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     char *ws = static_cast<char *>(workspace);
     const WsLayout &w = plan->ws;
@@ -1475,11 +1556,11 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     const uint32_t *slot_cnt = reinterpret_cast<const uint32_t *>(ws + w.slot_cnt);
     const unsigned long long *slot_ent = reinterpret_cast<const unsigned long long *>(ws + w.slot_ent);
     if (plan->any_large) {
-        rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, stream);
+        rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, nullptr, stream);
         if (rc != RSDGC_OK) return rc;
         hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist);
         marks.close(1);
-        rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, stream);
+        rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, v_out, stream);
         if (rc != RSDGC_OK) return rc;
         hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist);
         marks.close(2);
@@ -1487,7 +1568,7 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
         marks.close(1);
         marks.close(2);
     }
-    rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, stream);
+    rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, stream);
     if (rc != RSDGC_OK) return rc;
     marks.close(3);
 
@@ -1531,7 +1612,12 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, float *residual, uint3
     hipLaunchKernelGGL(k_scan, dim3(L), dim3(kScanThreads), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
                        out_counts, out_centre_counts, cmask ? 1 : 0);
     marks.close(6);
-    hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, grad, residual, mask, chunk_cnt, out_idx, out_val);
+    if (in_place)
+        hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, grad,
+                           residual_out, mask, chunk_cnt, out_idx, out_val);
+    else
+        hipLaunchKernelGGL(k_emit_sparse, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, state,
+                           grad, residual, residual_out, mask, chunk_cnt, out_idx, out_val);
     marks.close(7);
     if (out_centre_idx)
         hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer,
@@ -1625,7 +1711,7 @@ int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual, floa
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
     return launch_nsi<kPassMapOnly>(plan, static_cast<char *>(workspace), grad, residual, nsi_out,
-                                    stream);
+                                    nullptr, stream);
 }
 
 int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,

@@ -14,7 +14,8 @@ from . import binding
 class Session:
     def __init__(self, shapes, p: int, alpha: float, ratios: Sequence[float],
                  p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0",
-                 want_centres: bool = True, path: int = binding.RSDGC_PATH_AUTO):
+                 want_centres: bool = True, path: int = binding.RSDGC_PATH_AUTO,
+                 in_place: bool = False):
         self.shapes = [(int(r), int(c)) for r, c in shapes]
         self.plan = binding.rsdgc_plan(self.shapes, p, alpha, ratios, p_per_layer)
         if path != binding.RSDGC_PATH_AUTO:
@@ -24,7 +25,11 @@ class Session:
         L = self.plan.n_layers
         dev = self.device
         self.grad = torch.zeros(n, dtype=torch.float32, device=dev)
+        # `residual` is always the newest residual: with two arenas compress() writes the
+        # other one and the two names are swapped afterwards
         self.residual = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.in_place = in_place
+        self.residual_next = None if in_place else torch.zeros(n, dtype=torch.float32, device=dev)
         self.out_idx = torch.zeros(max(1, self.plan.out_capacity), dtype=torch.int32, device=dev)
         self.out_val = torch.zeros(max(1, self.plan.out_capacity), dtype=torch.float32, device=dev)
         self.out_counts = torch.zeros(L, dtype=torch.int32, device=dev)
@@ -57,9 +62,12 @@ class Session:
 
     # ---- calls
     def compress(self, stream=None) -> None:
-        binding.rsdgc_compress(self.plan, self.grad, self.residual, self.out_idx, self.out_val,
+        target = self.residual if self.in_place else self.residual_next
+        binding.rsdgc_compress(self.plan, self.grad, self.residual, target, self.out_idx, self.out_val,
                                self.out_counts, self.workspace, self.out_centre_idx,
                                self.out_centre_counts if self.want_centres else None, stream)
+        if not self.in_place:
+            self.residual, self.residual_next = self.residual_next, self.residual
 
     def nsi(self, use_residual: bool = True) -> List[np.ndarray]:
         out = torch.zeros_like(self.grad)

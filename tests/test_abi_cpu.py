@@ -111,14 +111,20 @@ def test_device_entry_points_validate_before_touching_the_gpu():
     plan = binding.rsdgc_plan([(8, 8)], 3, 0.5, [0.1])
     null = None
     # null plan / null buffers -> RSDGC_EINVAL, nothing enqueued (this box may have no GPU at all)
-    assert lib.rsdgc_compress(null, null, null, null, null, null, null, null, null, null) == binding.RSDGC_EINVAL
-    assert lib.rsdgc_compress(plan.handle, null, null, null, null, null, null, null, null, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_compress(null, null, null, null, null, null, null, null, null, null, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_compress(plan.handle, null, null, null, null, null, null, null, null, null, null) == binding.RSDGC_EINVAL
     assert lib.rsdgc_nsi(plan.handle, null, null, null, null, null) == binding.RSDGC_EINVAL
     assert lib.rsdgc_decompress(plan.handle, null, null, null, null, 0, null, null) == binding.RSDGC_EINVAL
     # misaligned workspace / arenas are refused as well (addresses are never dereferenced here)
     a = 4096
-    assert lib.rsdgc_compress(plan.handle, a, a, a, a, a, null, null, a + 8, null) == binding.RSDGC_EINVAL
-    assert lib.rsdgc_compress(plan.handle, a + 4, a, a, a, a, null, null, a, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_compress(plan.handle, a, a, a, a, a, a, null, null, a + 8, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_compress(plan.handle, a + 4, a, a, a, a, a, null, null, a, null) == binding.RSDGC_EINVAL
+    # the new residual goes to the same arena or to one that overlaps neither input: the plan's
+    # arena is 64 floats (256 bytes) here, so a second arena 128 bytes further on overlaps
+    assert plan.total_elems == 64
+    assert lib.rsdgc_compress(plan.handle, a, 2 * a, 2 * a + 128, a, a, a, null, null, a, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_compress(plan.handle, a, 2 * a, a + 128, a, a, a, null, null, a, null) == binding.RSDGC_EINVAL
+    assert lib.rsdgc_compress(plan.handle, a, 2 * a, a, a, a, a, null, null, a, null) == binding.RSDGC_EINVAL
     assert lib.rsdgc_profile_begin(plan.handle, 0) == binding.RSDGC_EINVAL
     assert lib.rsdgc_profile_end(null, null, null) == binding.RSDGC_EINVAL
 

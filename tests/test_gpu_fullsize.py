@@ -88,6 +88,33 @@ def test_vgg19_full_size_against_oracle_then_two_carried_iterations():
     assert n_exact >= w.n_layers - 2
 
 
+def test_vgg19_full_size_in_place_equals_two_arenas():
+    """The update in place and the two-arena form run different emit kernels; at full size
+    their outputs must be the same bytes, over two iterations that carry the residual."""
+    import torch
+    from paper_2312_17530_amd.session import Session
+    w = synth.config(3)
+    a = Session(w.shapes, w.p, w.alpha, w.ratios, in_place=False)
+    b = Session(w.shapes, w.p, w.alpha, w.ratios, in_place=True)
+    for t in range(2):
+        grads = synth.gradients(w, t)
+        a.set_grad(grads)
+        b.grad.copy_(a.grad)
+        a.compress()
+        b.compress()
+        torch.cuda.synchronize()
+        assert torch.equal(a.out_counts, b.out_counts), t
+        assert torch.equal(a.out_centre_counts, b.out_centre_counts), t
+        assert torch.equal(a.residual.view(torch.int32), b.residual.view(torch.int32)), t
+        counts = a.out_counts.cpu().numpy()
+        for l in range(w.n_layers):
+            o, n = a.plan.out_offset(l), int(counts[l])
+            assert torch.equal(a.out_idx[o:o + n], b.out_idx[o:o + n]), (t, l)
+            assert torch.equal(a.out_val[o:o + n].view(torch.int32), b.out_val[o:o + n].view(torch.int32)), (t, l)
+            co, k = a.plan.centre_offset(l), a.plan.layer_k(l)
+            assert torch.equal(a.out_centre_idx[co:co + k], b.out_centre_idx[co:co + k]), (t, l)
+
+
 def test_fc6_stress_p5_student_t_against_oracle_then_one_carried_iteration():
     w, n_exact = _run(4, extra_iterations=1)
     assert n_exact == 1

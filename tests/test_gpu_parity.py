@@ -13,17 +13,24 @@ pytestmark = pytest.mark.gpu
 AUTO, FULL_MAP = 0, 1     # ranking paths of the library (same result, different traffic)
 
 
-def _session(shapes, p, alpha, ratios, p_per_layer=None, path=AUTO):
+@pytest.fixture(params=[False, True], ids=["two_arenas", "in_place"])
+def in_place(request):
+    """Where the new residual goes: a second arena (the form bench.py times) or the same one."""
+    return request.param
+
+
+def _session(shapes, p, alpha, ratios, p_per_layer=None, path=AUTO, in_place=False):
     from paper_2312_17530_amd.session import Session
-    return Session(shapes, p, alpha, ratios, p_per_layer, path=path)
+    return Session(shapes, p, alpha, ratios, p_per_layer, path=path, in_place=in_place)
 
 
 def run_and_check(shapes, p_list, alpha, ratios, grads_per_iter, name="case", check_nsi=True,
-                  path=AUTO):
+                  path=AUTO, in_place=False):
     """Runs every iteration on GPU and oracle from identical state and applies the parity rule.
     Returns (number of layer-iterations compared, number that matched the oracle exactly)."""
     import torch
-    sess = _session(shapes, p_list[0], alpha, ratios, p_list, path)
+    sess = _session(shapes, p_list[0], alpha, ratios, p_list, path, in_place)
+    name = f"{name}/{'in_place' if in_place else 'two_arenas'}"
     L = len(shapes)
     resid = [np.zeros(sh, dtype=np.float32) for sh in shapes]
     n_cmp = n_exact = 0
@@ -61,9 +68,10 @@ def run_and_check(shapes, p_list, alpha, ratios, grads_per_iter, name="case", ch
     return n_cmp, n_exact
 
 
-def test_config0_single_layer_512():
+def test_config0_single_layer_512(in_place):
     w = synth.config(0)
-    n, ex = run_and_check(w.shapes, [w.p], w.alpha, w.ratios, [synth.gradients(w, 0)], w.name)
+    n, ex = run_and_check(w.shapes, [w.p], w.alpha, w.ratios, [synth.gradients(w, 0)], w.name,
+                          in_place=in_place)
     assert n == 1 and ex == 1
 
 
@@ -72,7 +80,7 @@ RAGGED = [(1, 1), (1, 40), (40, 1), (2, 2), (33, 129), (45, 61), (64, 27), (200,
 
 
 @pytest.mark.parametrize("alpha", [0.5, 0.0, 1.0, 0.25])
-def test_ragged_shapes_mixed_p_two_iterations(alpha):
+def test_ragged_shapes_mixed_p_two_iterations(alpha, in_place):
     rng = np.random.default_rng(int(alpha * 100) + 7)
     shapes = RAGGED
     p_list = [1, 3, 5, 7, 3, 5, 3, 3, 7, 5, 3, 1, 3, 5]
@@ -80,7 +88,7 @@ def test_ragged_shapes_mixed_p_two_iterations(alpha):
     its = []
     for t in range(2):
         its.append([synth.layer_gradient(sh, 1e-3 * (l + 1), 11, t, l) for l, sh in enumerate(shapes)])
-    n, ex = run_and_check(shapes, p_list, alpha, ratios, its, "ragged")
+    n, ex = run_and_check(shapes, p_list, alpha, ratios, its, "ragged", in_place=in_place)
     assert n == 2 * len(shapes)
     assert ex >= n - 2          # the tolerance band is allowed, but should hardly ever be needed
 
@@ -106,10 +114,11 @@ def test_degenerate_inputs_follow_index_tie_break():
 
 
 @pytest.mark.parametrize("path", [AUTO, FULL_MAP])
-def test_config1_resnet18_two_iterations(path):
+def test_config1_resnet18_two_iterations(path, in_place):
     w = synth.config(1)
     its = [synth.gradients(w, t) for t in range(w.iterations)]
-    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name, path=path)
+    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name, path=path,
+                          in_place=in_place)
     assert n == 2 * w.n_layers
     assert ex >= n - 2
 
@@ -129,7 +138,7 @@ def _tile_is_sampled(t):
     return ((t * 2654435761) & 0xFFFFFFFF) >> 28 == 0
 
 
-def test_candidate_path_falls_back_when_its_bound_fails():
+def test_candidate_path_falls_back_when_its_bound_fails(in_place):
     """Large layers rank only the centres above a bound estimated from sampled tiles.  Inputs
     built to defeat that estimate must still give the oracle's result (through the full map)."""
     R, C = 512, 4608                      # 16 x 36 tiles of 32 x 128
@@ -152,7 +161,8 @@ def test_candidate_path_falls_back_when_its_bound_fails():
     shapes = [(R, C), (R, C), (R, C)]
     grads = [hot_sampled, hot_tile, base]
     for ratios in ([0.3, 0.02, 0.02], [0.02, 0.2, 0.01]):
-        n, ex = run_and_check(shapes, [3, 3, 3], 0.5, ratios, [grads, grads], "fallback")
+        n, ex = run_and_check(shapes, [3, 3, 3], 0.5, ratios, [grads, grads], "fallback",
+                              in_place=in_place)
         assert n == 6 and ex >= 5
 
 
@@ -207,14 +217,14 @@ def test_decompress_accumulate_sums_messages():
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
-def test_compress_can_be_captured_in_a_hip_graph_and_replayed():
+def test_compress_can_be_captured_in_a_hip_graph_and_replayed(in_place):
     """rsdgc_compress enqueues kernels only (no allocation, no synchronisation, no memset node),
     so a caller may capture it.  Every replay must reproduce the eager result, with eager work
     and synchronisations between the replays."""
     import torch
     w = synth.config(1)
     grads = synth.gradients(w, 0)
-    sess = _session(w.shapes, w.p, w.alpha, w.ratios)
+    sess = _session(w.shapes, w.p, w.alpha, w.ratios, in_place=in_place)
     sess.set_grad(grads)
     sess.compress()                                  # first call uploads the plan's tables
     torch.cuda.synchronize()
@@ -225,11 +235,12 @@ def test_compress_can_be_captured_in_a_hip_graph_and_replayed():
                                sess.out_centre_idx, sess.out_centre_counts)]
     graph = torch.cuda.CUDAGraph()
     sess.residual.zero_()
+    source = sess.residual                           # the arena the captured call reads
     with torch.cuda.graph(graph):
-        sess.compress()
+        sess.compress()                              # with two arenas sess.residual is now the other one
     for rep in range(3):
         for t in (sess.out_idx, sess.out_val, sess.out_counts, sess.out_centre_idx,
-                  sess.out_centre_counts, sess.residual):
+                  sess.out_centre_counts, sess.residual, source):
             t.zero_()                                # eager work between replays
         scratch = torch.randn(1 << 20, device="cuda").sum().item()
         assert np.isfinite(scratch)
