@@ -45,8 +45,8 @@ def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems
     v_store = 0.0 if in_place else 4.0
     if stage == "capture":    # read g, read r of the candidate-mode layers (candidates are < 1 %)
         return (8.0 + v_store) * n_cand_elems
-    if stage == "full_map":   # read g, read r, write the score map of the full-map layers
-        return (12.0 + v_store) * (n_elems - n_cand_elems)
+    if stage == "first_pass":  # read g, read r, write the score map of the layers ranked on the full map
+        return (12.0 + v_store) * (n_elems - n_cand_elems)   # (the sampled tiles of the others not counted)
     if stage == "emit":
         if in_place:          # read g, read r, write r, write (index, value) pairs
             return 12.0 * n_elems + 8.0 * n_pairs
@@ -163,7 +163,7 @@ def main() -> int:
     if stages:
         paths = binding.rsdgc_last_paths(sess.plan, sess.workspace)
         n_cand = sum(r * c for (r, c), pth in zip(w.shapes, paths) if pth == 0)
-        dom = max(("capture", "full_map", "emit"), key=lambda s: stages.get(s, 0.0))
+        dom = max(("first_pass", "capture", "emit"), key=lambda s: stages.get(s, 0.0))
         dur_s = stages[dom] * 1e-3
         alg = stage_algorithmic_bytes(dom, G, n_pairs, n_cand, args.in_place)
         achieved = alg / dur_s / 1e9

@@ -15,7 +15,7 @@ constexpr int kChunk = 8192;         // elements per workgroup in the 1-D passes
 constexpr int kHistBins = 4096;      // widest radix digit (12 bits)
 constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements
 constexpr int kSlotCap = 256;        // candidate centres one tile can record
-constexpr int kSlotGroup = 64;       // tile slots per workgroup in the candidate passes
+constexpr int kSlotGroup = 16;       // tile slots per work item of the candidate passes (<= 64)
 constexpr int kCandBins = 256;       // 12-bit score buckets above the bound that a capture workgroup counts
 constexpr int kListMin = 8192;       // smallest threshold-bucket list of a layer (entries)
 constexpr int kList2Cap = 2048;      // keys sharing the first two digits that a layer can stage
@@ -97,6 +97,10 @@ struct WsLayout {
     size_t group_dir = 0;    // DirEntry[n_layers + 1]: slot groups
     size_t samples = 0;      // SampleEntry[] per p-group
     size_t chunk_layer = 0;  // uint32[n_chunks]: layer of every 8192-element chunk
+    size_t group_layer = 0;  // uint32[n_slot_groups]: layer of every slot group
+    size_t cand_groups = 0;  // uint32[]: slot groups of the large layers (work list of the candidate passes)
+    size_t map_chunks = 0;   // uint32[]: chunks of the other layers that select something
+    size_t map_tiles = 0;    // SampleEntry[]: tiles of those layers
     size_t table_bytes = 0;  // bytes uploaded from the host
     size_t state = 0;        // SelState[n_layers], rewritten at the start of every compress
     // cleared at the start of every compress
@@ -106,6 +110,7 @@ struct WsLayout {
     size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk, then prefix
     size_t list_cnt = 0;     // uint32[n_layers]  keys gathered from the threshold bucket
     size_t list2_cnt = 0;    // uint32[n_layers]  of those, keys that also share the second digit
+    size_t flags = 0;        // uint32[64]  [0]: some large layer fell back to the full map
     size_t mask = 0;         // uint32[total_elems / 32]  kept-element bitmask
     size_t cmask = 0;        // uint32[total_elems / 32]  selected-centre bitmask
     size_t zero_end = 0;
@@ -142,6 +147,9 @@ struct rsdgc_plan_s {
     std::vector<rsdgc::DirEntry> all_tile_dir;
     std::vector<rsdgc::DirEntry> group_dir;
     std::vector<rsdgc::SampleEntry> samples;
+    std::vector<uint32_t> cand_groups;
+    std::vector<uint32_t> map_chunks;
+    std::vector<rsdgc::SampleEntry> map_tiles;
     uint32_t n_tiles_all = 0;
     uint32_t n_slot_groups = 0;
     bool any_large = false;

@@ -97,6 +97,38 @@ __device__ __forceinline__ uint32_t block_scan_incl_n(uint32_t v, uint32_t *wave
     return r;
 }
 
+// Exclusive prefix of the candidate counts of ntile (<= 64) consecutive tile slots into
+// pref[0 .. 64]; pref[ntile] is their total.  Called by every thread of the workgroup.
+__device__ __forceinline__ void slot_prefix(uint32_t *pref /*[65]*/, const uint32_t *__restrict__ slot_cnt,
+                                            uint32_t slot0, uint32_t ntile) {
+    __syncthreads();                       // earlier readers of pref are done
+    if (threadIdx.x < 64) {
+        const uint32_t lane = threadIdx.x;
+        uint32_t v = lane < ntile ? slot_cnt[slot0 + lane] : 0u;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(v, d, 64);
+            if (lane >= static_cast<uint32_t>(d)) v += o;
+        }
+        pref[lane + 1] = v;
+        if (lane == 0) pref[0] = 0;
+    }
+    __syncthreads();
+}
+
+// Position for one appended item per flagged lane: one atomic on the LDS counter per wave.
+// Called by all 64 lanes of a wave; the result is meaningful for flagged lanes only.
+__device__ __forceinline__ uint32_t wave_append(uint32_t *counter, bool flag) {
+    const unsigned long long m = __ballot(flag);
+    if (m == 0ull) return 0u;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t leader = static_cast<uint32_t>(__ffsll(static_cast<long long>(m))) - 1u;
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(counter, static_cast<uint32_t>(__popcll(m)));
+    base = __shfl(base, static_cast<int>(leader), 64);
+    return base + static_cast<uint32_t>(__popcll(m & ((1ull << lane) - 1ull)));
+}
+
 // Inclusive scan over the 256 threads of a workgroup (4 waves of 64).
 __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_tot /*[4]*/) {
     return block_scan_incl_n<4>(v, wave_tot);
@@ -154,9 +186,10 @@ __device__ __forceinline__ double nsi_from_sums(double sa, double ss, double sq,
 // What one launch of the NSI kernel produces.
 enum NsiPass : int {
     kPassMapOnly = 0,   // score map to a caller buffer (rsdgc_nsi)
-    kPassFullMap = 1,   // score map + 12-bit histogram, layers in full-map mode
+    kPassFullMap = 1,   // score map + 12-bit histogram of the large layers that fell back to the full map
     kPassCapture = 2,   // candidates (score >= bound) recorded per tile, layers in candidate mode
-    kPassSample = 3,    // 12-bit histogram of the sampled tiles of the large layers
+    kPassSample = 3,    // first pass over the plan's tile list: 12-bit histogram of the sampled tiles
+                        // of the large layers; score map + histogram of every tile of the others
 };
 
 struct NsiArgs {
@@ -169,6 +202,7 @@ struct NsiArgs {
     const float *resid;           // nullable: all-zero residual
     float *nsi_out;               // score map (kPassMapOnly, kPassFullMap)
     float *v_out;                 // nullable: second residual arena that receives v = r + g
+    const uint32_t *flags;        // [0] != 0: some large layer fell back to the full map
     uint32_t *hist;               // [n_layers][kHistBins]
     const SelState *state;
     SelState *state_rw;           // same array; only the overflow flag is written (capture)
@@ -199,7 +233,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     constexpr bool MAP = PASS == kPassMapOnly || PASS == kPassFullMap;
     constexpr bool CAPTURE = PASS == kPassCapture;
     constexpr bool FULLHIST = PASS == kPassFullMap || PASS == kPassSample;
-    constexpr bool STORE_V = PASS == kPassFullMap || PASS == kPassCapture;
+    constexpr bool STORE_V = PASS != kPassMapOnly;
     constexpr int NBINS = FULLHIST ? kHistBins : (CAPTURE ? kCandBins : 1);
     __shared__ __attribute__((aligned(16))) float tile[ROWS * PITCH];
     __shared__ uint32_t lhist[NBINS];
@@ -213,6 +247,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     const uint32_t n_items = a.n_tiles;
     const uint32_t first = xcd_contiguous(blockIdx.x, gridDim.x), stride = gridDim.x, last = n_items;
     if (first >= last) return;
+    if (PASS == kPassFullMap && a.flags[0] == 0u) return;   // no layer fell back: nothing to do
 
     if (NBINS > 1)
         for (int b = tid; b < NBINS; b += 256) lhist[b] = 0;
@@ -224,6 +259,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     uint32_t cur_l = 0xffffffffu;         // layer whose counts sit in lhist
     uint32_t hint_key = 0, hint_bin = 0;
     bool active = true;
+    bool whole = true;                    // every tile of the layer is visited: v and the scores go out
     LayerDev L;
 
     const double n = static_cast<double>(P * P);
@@ -258,9 +294,10 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
             active = true;
             hint_key = 0;
             hint_bin = 0;
-            if (PASS != kPassMapOnly) {
+            whole = PASS != kPassSample || L.large == 0u;
+            if (PASS == kPassFullMap || PASS == kPassCapture) {
                 const SelState st = a.state[l];
-                if (PASS == kPassFullMap) active = st.mode == kModeFullMap;
+                if (PASS == kPassFullMap) active = st.mode == kModeFullMap && L.large != 0u;
                 else active = st.mode == kModeCandidates;
                 if (CAPTURE) { hint_key = st.hint_key; hint_bin = hint_key >> 19; }
             }
@@ -308,7 +345,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                     v.z = rv[it].z + gv[it].z;
                     v.w = rv[it].w + gv[it].w;
                     *reinterpret_cast<float4 *>(&tile[s * 4]) = v;   // s*4 == rr*PITCH + 4*j4
-                    if (STORE_V && a.v_out) {      // the tile's own elements (not the halo) go out once
+                    if (STORE_V && a.v_out && whole) {   // the tile's own elements (not the halo) go out once
                         const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
                         const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
                         if (rr >= H && rr < H + kTileRows && j4 >= 1 && j4 <= kTileCols / 4 && x < R && y < C)
@@ -324,7 +361,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                 if (x >= 0 && x < R && y >= 0 && y < C) {
                     const size_t off = static_cast<size_t>(x) * C + y;
                     v = (r ? r[off] : 0.f) + g[off];
-                    if (STORE_V && a.v_out && rr >= H && rr < H + kTileRows && j >= PADL && j < PADL + kTileCols)
+                    if (STORE_V && a.v_out && whole && rr >= H && rr < H + kTileRows && j >= PADL && j < PADL + kTileCols)
                         a.v_out[L.elem_off + off] = v;
                 }
                 tile[s] = v;
@@ -394,7 +431,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                     const int x = x0 + row_base + o, y = y0 + c0;
                     if (x < R && y < C) {
                         const bool two = y + 1 < C;
-                        if (MAP) {
+                        if (MAP || (PASS == kPassSample && whole)) {
                             const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
                             if (two && pair_store) {
                                 *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[1]);
@@ -443,7 +480,8 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
 // bound.  A layer whose sample cannot supply the target goes to the full map.
 __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layers,
                                               SelState *__restrict__ state,
-                                              uint32_t *__restrict__ hist) {
+                                              uint32_t *__restrict__ hist,
+                                              uint32_t *__restrict__ flags) {
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t found;
     const int l = blockIdx.x, tid = threadIdx.x;
@@ -476,6 +514,7 @@ __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layer
         SelState ns = st;
         ns.mode = kModeFullMap;
         state[l] = ns;
+        flags[0] = 1u;                     // the fallback pass has work
     }
     for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
 }
@@ -487,7 +526,8 @@ __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layer
 // the full map, and its histogram is cleared for that pass.
 __global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ layers,
                                                   SelState *__restrict__ state,
-                                                  uint32_t *__restrict__ hist) {
+                                                  uint32_t *__restrict__ hist,
+                                                  uint32_t *__restrict__ flags) {
     __shared__ uint32_t wave_tot[4];
     const int l = blockIdx.x, tid = threadIdx.x;
     const SelState st = state[l];
@@ -505,6 +545,7 @@ __global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ l
             SelState ns = st;
             ns.mode = kModeFullMap;
             state[l] = ns;
+            flags[0] = 1u;                 // the fallback pass has work
         }
     }
 }
@@ -558,9 +599,14 @@ __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
 // --------------------------------------------------------------- gather --
 // After the first digit: the keys of each layer's threshold bucket (those whose top
 // 12 score bits equal the chosen digit) are copied into the layer's list, and their next
-// digit is histogrammed.  Workgroups [0, n_map_wgs) stride over the 8192-element chunks of
-// the score map (full-map layers); the others stride over the slot groups (candidate-mode
-// layers).  Matches are staged in LDS and appended with one atomic per flush.
+// digit is histogrammed.  Three kinds of workgroups share the launch:
+//   [0, n_map_wgs)              stride over the plan's list of 8192-element score-map chunks
+//                               (layers that are always ranked on the full map);
+//   [n_map_wgs, +n_slot_wgs)    stride over the plan's list of slot groups (large layers,
+//                               where they are still in candidate mode);
+//   the last n_fb_wgs           only when some large layer fell back to the full map: they
+//                               walk all chunks and take those of such layers.
+// Matches are staged in LDS and appended with one atomic per flush.
 constexpr int kStage = 4096;
 
 struct GatherStage {
@@ -597,11 +643,19 @@ __device__ __forceinline__ void gather_flush(GatherStage &st, const LayerDev &L,
     __syncthreads();
 }
 
+struct GatherLists {
+    const DirEntry *chunk_dir;     // all chunks by layer (fallback walk)
+    const uint32_t *chunk_layer;   // [n_chunks]
+    const uint32_t *group_layer;   // [n_slot_groups]
+    const uint32_t *map_chunks;    // [n_map_chunks]
+    const uint32_t *cand_groups;   // [n_cand_groups]
+    const uint32_t *flags;
+    uint32_t n_layers, n_chunks, n_map_chunks, n_cand_groups;
+    uint32_t n_map_wgs, n_slot_wgs;   // the remaining workgroups are fallback walkers
+};
+
 __global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ layers,
-                                                const DirEntry *__restrict__ chunk_dir,
-                                                const DirEntry *__restrict__ group_dir,
-                                                uint32_t n_layers, uint32_t n_map_wgs,
-                                                uint32_t n_chunks, uint32_t n_groups,
+                                                const GatherLists gl,
                                                 const SelState *__restrict__ state,
                                                 const uint32_t *__restrict__ keys,
                                                 const uint32_t *__restrict__ slot_cnt,
@@ -610,43 +664,58 @@ __global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ lay
                                                 unsigned long long *__restrict__ list_ent,
                                                 uint32_t *__restrict__ hist) {
     __shared__ GatherStage stage;
-    __shared__ uint32_t pref[kSlotGroup + 1];
+    __shared__ uint32_t pref[65];
     const int tid = threadIdx.x;
-    const bool is_map = blockIdx.x < n_map_wgs;
-    const uint32_t first = is_map ? blockIdx.x : blockIdx.x - n_map_wgs;
-    const uint32_t stride = is_map ? n_map_wgs : gridDim.x - n_map_wgs;
-    const uint32_t n_items = is_map ? n_chunks : n_groups;
-    const DirEntry *__restrict__ dir = is_map ? chunk_dir : group_dir;
+    // role 0: listed score-map chunks, 1: listed slot groups, 2: fallback walk over all chunks
+    const int role = blockIdx.x < gl.n_map_wgs ? 0 : blockIdx.x < gl.n_map_wgs + gl.n_slot_wgs ? 1 : 2;
+    const bool is_map = role != 1;
+    const uint32_t first = role == 0 ? blockIdx.x : role == 1 ? blockIdx.x - gl.n_map_wgs
+                                                              : blockIdx.x - gl.n_map_wgs - gl.n_slot_wgs;
+    const uint32_t stride = role == 0 ? gl.n_map_wgs : role == 1 ? gl.n_slot_wgs
+                                                                 : gridDim.x - gl.n_map_wgs - gl.n_slot_wgs;
+    const uint32_t n_items = role == 0 ? gl.n_map_chunks : role == 1 ? gl.n_cand_groups : gl.n_chunks;
+    const DirEntry *__restrict__ dir = gl.chunk_dir;
     if (first >= n_items) return;
+    if (role == 2 && gl.flags[0] == 0u) return;
     if (tid == 0) stage.n = 0;
     for (int b = tid; b < (1 << level_bits(1)); b += 256) stage.hist1[b] = 0;
     __syncthreads();
     constexpr int shift1 = level_shift(1);
     constexpr uint32_t mask1 = (1u << level_bits(1)) - 1u;
 
-    uint32_t e = dir_lookup(dir, n_layers, first);
+    uint32_t e = role == 2 ? dir_lookup(dir, gl.n_layers, first) : 0u;
     uint32_t cur_l = 0xffffffffu;
     bool active = false;
     uint32_t digit0 = 0;
     LayerDev L;
     for (uint32_t it = first; it < n_items; it += stride) {
-        while (it >= dir[e + 1].begin) ++e;
-        const uint32_t l = dir[e].layer;
+        uint32_t id, l;                    // chunk or slot group, and its layer
+        if (role == 2) {
+            while (it >= dir[e + 1].begin) ++e;
+            l = dir[e].layer;
+            id = it;
+        } else {
+            id = role == 0 ? gl.map_chunks[it] : gl.cand_groups[it];
+            l = role == 0 ? gl.chunk_layer[id] : gl.group_layer[id];
+        }
         if (l != cur_l) {
             if (active) gather_flush(stage, L, list_cnt, cur_l, list_ent, hist, true);
             cur_l = l;
             L = layers[l];
             const SelState st = state[l];
             active = !st.done && st.mode == (is_map ? kModeFullMap : kModeCandidates);
+            if (role == 2) active = active && L.large != 0u;      // the others are on the list
             digit0 = static_cast<uint32_t>(st.T >> level_shift(0));
         }
-        if (!active) {                     // on to this workgroup's first item of the next layer
-            const uint32_t nb = dir[e + 1].begin;
-            it += (nb - it + stride - 1) / stride * stride - stride;
+        if (!active) {
+            if (role == 2) {               // on to this workgroup's first chunk of the next layer
+                const uint32_t nb = dir[e + 1].begin;
+                it += (nb - it + stride - 1) / stride * stride - stride;
+            }
             continue;
         }
         if (is_map) {
-            const uint32_t start = (it - L.chunk_begin) * kChunk;
+            const uint32_t start = (id - L.chunk_begin) * kChunk;
             const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
             const uint32_t *__restrict__ src = keys + L.elem_off + start;
             for (int j = 0; j < kChunk / 1024; ++j) {
@@ -655,57 +724,50 @@ __global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ lay
                 if (stage.n + 1024u > static_cast<uint32_t>(kStage))
                     gather_flush(stage, L, list_cnt, l, list_ent, hist, false);
                 const uint32_t e4 = j * 1024 + 4 * tid;
-                if (e4 < len) {
-                    uint32_t kk[4] = {0, 0, 0, 0};
-                    if (e4 + 3 < len) {
-                        const uint4 q = *reinterpret_cast<const uint4 *>(src + e4);
-                        kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
-                    } else {
-                        for (uint32_t q = 0; q < 4 && e4 + q < len; ++q) kk[q] = src[e4 + q];
-                    }
+                uint32_t kk[4] = {0, 0, 0, 0};
+                if (e4 + 3 < len) {
+                    const uint4 q = *reinterpret_cast<const uint4 *>(src + e4);
+                    kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
+                } else {
+                    for (uint32_t q = 0; q < 4 && e4 + q < len; ++q) kk[q] = src[e4 + q];
+                }
 #pragma unroll
-                    for (uint32_t q = 0; q < 4; ++q)
-                        if (e4 + q < len && ((kk[q] & 0x7fffffffu) >> 19) == digit0) {
-                            const unsigned long long K = composite_key(kk[q], start + e4 + q);
-                            stage.ent[atomicAdd(&stage.n, 1u)] = K;
-                            atomicAdd(&stage.hist1[static_cast<uint32_t>(K >> shift1) & mask1], 1u);
-                        }
+                for (uint32_t q = 0; q < 4; ++q) {
+                    const bool hit = e4 + q < len && ((kk[q] & 0x7fffffffu) >> 19) == digit0;
+                    const uint32_t pos = wave_append(&stage.n, hit);
+                    if (hit) {
+                        const unsigned long long K = composite_key(kk[q], start + e4 + q);
+                        stage.ent[pos] = K;
+                        atomicAdd(&stage.hist1[static_cast<uint32_t>(K >> shift1) & mask1], 1u);
+                    }
                 }
             }
         } else {
-            const uint32_t firstt = (it - L.group_begin) * kSlotGroup;
+            const uint32_t firstt = (id - L.group_begin) * kSlotGroup;
             const uint32_t ntile = min(static_cast<uint32_t>(kSlotGroup), L.n_tiles - firstt);
             const uint32_t slot0 = L.tile_begin_all + firstt;
-            __syncthreads();
-            if (static_cast<uint32_t>(tid) < ntile) pref[tid + 1] = slot_cnt[slot0 + tid];
-            __syncthreads();
-            if (tid == 0) {                // serial prefix of at most 64 slot counts (in LDS)
-                uint32_t run = 0;
-                pref[0] = 0;
-                for (uint32_t sl = 1; sl <= ntile; ++sl) {
-                    run += pref[sl];
-                    pref[sl] = run;
-                }
-            }
-            __syncthreads();
+            slot_prefix(pref, slot_cnt, slot0, ntile);
             const uint32_t total = pref[ntile];
             for (uint32_t j0 = 0; j0 < total; j0 += 256) {
                 __syncthreads();
                 if (stage.n + 256u > static_cast<uint32_t>(kStage))
                     gather_flush(stage, L, list_cnt, l, list_ent, hist, false);
                 const uint32_t j = j0 + tid;
+                unsigned long long K = 0;
+                bool hit = false;
                 if (j < total) {
                     uint32_t lo = 0, hi = ntile;          // slot with pref[lo] <= j < pref[lo + 1]
                     while (hi - lo > 1) {
                         const uint32_t mid = (lo + hi) >> 1;
                         if (pref[mid] <= j) lo = mid; else hi = mid;
                     }
-                    const unsigned long long K =
-                        slot_ent[static_cast<size_t>(slot0 + lo) * kSlotCap + (j - pref[lo])];
-                    if (static_cast<uint32_t>(K >> level_shift(0)) == digit0) {
-                        stage.ent[atomicAdd(&stage.n, 1u)] = K;
-                        atomicAdd(&stage.hist1[static_cast<uint32_t>(K >> shift1) & mask1], 1u);
-                    }
+                    K = slot_ent[static_cast<size_t>(slot0 + lo) * kSlotCap + (j - pref[lo])];
+                    hit = static_cast<uint32_t>(K >> level_shift(0)) == digit0;
+                }
+                const uint32_t pos = wave_append(&stage.n, hit);
+                if (hit) {
+                    stage.ent[pos] = K;
+                    atomicAdd(&stage.hist1[static_cast<uint32_t>(K >> shift1) & mask1], 1u);
                 }
             }
         }
@@ -918,29 +980,30 @@ __device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos
     if (b + nbits > 32) atomicOr(&mask[w + 1], bits >> (32 - b));
 }
 
-// Candidate-mode layers: workgroups stride over the slot groups; every recorded candidate
-// that reaches its layer's threshold ORs the bits of its window into the (cleared) mask.
-// The words touched are nearly all distinct, which is the case global atomics handle well.
+// Candidate-mode layers: workgroups stride over the plan's list of slot groups of the large
+// layers; every recorded candidate that reaches its layer's threshold ORs the bits of its
+// window into the (cleared) mask.  The words touched are nearly all distinct, which is the
+// case global atomics handle well.
 __global__ __launch_bounds__(256) void k_mark_cand(const LayerDev *__restrict__ layers,
-                                                   const DirEntry *__restrict__ group_dir,
-                                                   uint32_t n_layers, uint32_t n_groups,
+                                                   const uint32_t *__restrict__ cand_groups,
+                                                   const uint32_t *__restrict__ group_layer,
+                                                   uint32_t n_groups,
                                                    const SelState *__restrict__ state,
                                                    const uint32_t *__restrict__ slot_cnt,
                                                    const unsigned long long *__restrict__ slot_ent,
                                                    uint32_t *__restrict__ mask,
                                                    uint32_t *__restrict__ cmask) {
-    __shared__ uint32_t pref[kSlotGroup + 1];
+    __shared__ uint32_t pref[65];
     const int tid = threadIdx.x;
     const uint32_t first = blockIdx.x, stride = gridDim.x;
     if (first >= n_groups) return;
-    uint32_t e = dir_lookup(group_dir, n_layers, first);
     uint32_t cur_l = 0xffffffffu;
     bool active = false;
     unsigned long long T = 0;
     LayerDev L;
     for (uint32_t it = first; it < n_groups; it += stride) {
-        while (it >= group_dir[e + 1].begin) ++e;
-        const uint32_t l = group_dir[e].layer;
+        const uint32_t id = cand_groups[it];
+        const uint32_t l = group_layer[id];
         if (l != cur_l) {
             cur_l = l;
             L = layers[l];
@@ -948,26 +1011,11 @@ __global__ __launch_bounds__(256) void k_mark_cand(const LayerDev *__restrict__ 
             active = st.mode == kModeCandidates;
             T = st.T;
         }
-        if (!active) {
-            const uint32_t nb = group_dir[e + 1].begin;
-            it += (nb - it + stride - 1) / stride * stride - stride;
-            continue;
-        }
-        const uint32_t firstt = (it - L.group_begin) * kSlotGroup;
+        if (!active) continue;
+        const uint32_t firstt = (id - L.group_begin) * kSlotGroup;
         const uint32_t ntile = min(static_cast<uint32_t>(kSlotGroup), L.n_tiles - firstt);
         const uint32_t slot0 = L.tile_begin_all + firstt;
-        __syncthreads();
-        if (static_cast<uint32_t>(tid) < ntile) pref[tid + 1] = slot_cnt[slot0 + tid];
-        __syncthreads();
-        if (tid == 0) {
-            uint32_t run = 0;
-            pref[0] = 0;
-            for (uint32_t sl = 1; sl <= ntile; ++sl) {
-                run += pref[sl];
-                pref[sl] = run;
-            }
-        }
-        __syncthreads();
+        slot_prefix(pref, slot_cnt, slot0, ntile);
         const uint32_t total = pref[ntile];
         const int h = (static_cast<int>(L.p) - 1) / 2;
         const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
@@ -1001,40 +1049,59 @@ __global__ __launch_bounds__(256) void k_mark_cand(const LayerDev *__restrict__ 
 // whole neighbourhoods are kept) is done on those words with shifts and ORs, and the tile's
 // mask words are written with plain stores (rows that are a multiple of 32 long) -- no
 // global atomics on that path.
+// Workgroups [0, n_list_wgs) stride over the plan's list of tiles of the layers that are always
+// ranked on the full map; the others run only when some large layer fell back to it, walk
+// all tiles and take those of such layers.
 __global__ __launch_bounds__(256) void k_mark_map(const LayerDev *__restrict__ layers,
                                                   const DirEntry *__restrict__ dir, uint32_t n_layers,
-                                                  uint32_t n_tiles, const SelState *__restrict__ state,
+                                                  uint32_t n_tiles, const SampleEntry *__restrict__ map_tiles,
+                                                  uint32_t n_map_tiles, uint32_t n_list_wgs,
+                                                  const uint32_t *__restrict__ flags,
+                                                  const SelState *__restrict__ state,
                                                   const uint32_t *__restrict__ keys,
                                                   uint32_t *__restrict__ mask,
                                                   uint32_t *__restrict__ cmask) {
     constexpr int MAXH = (RSDGC_MAX_P - 1) / 2;
     __shared__ unsigned long long bits[kTileRows + 2 * MAXH][4];   // [row][left, seg0, seg1, right]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t first = blockIdx.x, stride = gridDim.x;
-    if (first >= n_tiles) return;
-    uint32_t e = dir_lookup(dir, n_layers, first);
+    const bool listed = blockIdx.x < n_list_wgs;
+    const uint32_t first = listed ? blockIdx.x : blockIdx.x - n_list_wgs;
+    const uint32_t stride = listed ? n_list_wgs : gridDim.x - n_list_wgs;
+    const uint32_t n_items = listed ? n_map_tiles : n_tiles;
+    if (first >= n_items) return;
+    if (!listed && flags[0] == 0u) return;
+    uint32_t e = listed ? 0u : dir_lookup(dir, n_layers, first);
     uint32_t cur_l = 0xffffffffu;
     bool active = false;
     unsigned long long T = 0;
     LayerDev L;
-    for (uint32_t t = first; t < n_tiles; t += stride) {
-        while (t >= dir[e + 1].begin) ++e;
-        const uint32_t l = dir[e].layer;
+    for (uint32_t t = first; t < n_items; t += stride) {
+        uint32_t l, local;
+        if (listed) {
+            const SampleEntry se = map_tiles[t];
+            l = se.layer;
+            local = se.local_tile;
+        } else {
+            while (t >= dir[e + 1].begin) ++e;
+            l = dir[e].layer;
+            local = t - dir[e].begin;
+        }
         if (l != cur_l) {
             cur_l = l;
             L = layers[l];
             const SelState st = state[l];
-            active = st.mode == kModeFullMap;
+            active = st.mode == kModeFullMap && (listed || L.large != 0u);
             T = st.T;
         }
         if (!active) {
-            const uint32_t nb = dir[e + 1].begin;
-            t += (nb - t + stride - 1) / stride * stride - stride;
+            if (!listed) {
+                const uint32_t nb = dir[e + 1].begin;
+                t += (nb - t + stride - 1) / stride * stride - stride;
+            }
             continue;
         }
         const int h = (static_cast<int>(L.p) - 1) / 2;
         const int rows_ext = kTileRows + 2 * h;
-        const uint32_t local = t - dir[e].begin;
         const int trow = static_cast<int>(local / L.tiles_x);
         const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * L.tiles_x);
         const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
@@ -1293,6 +1360,8 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const LayerDev *__restrict_
                                                      uint32_t *__restrict__ out_idx,
                                                      float *__restrict__ out_val) {
     __shared__ uint32_t wave_tot[4];
+    __shared__ uint16_t s_list[kChunk];
+    __shared__ uint32_t s_total;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
     const uint32_t l = chunk_layer[c];
@@ -1320,21 +1389,29 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const LayerDev *__restrict_
     if (!__syncthreads_or(word != 0u)) return;
     const uint32_t cnt = __popc(word);
     const uint32_t incl = block_scan_incl(cnt, wave_tot);
-    const uint32_t cbase = chunk_base[c];
-    const size_t obase = static_cast<size_t>(L.out_off) + cbase;
-    const uint32_t room = L.cap > cbase ? L.cap - cbase : 0u;   // never write past the segment
+    // the chunk's kept elements, in ascending order, as offsets inside the chunk
     uint32_t pos = incl - cnt;
     while (word) {
         const uint32_t b = static_cast<uint32_t>(__ffs(word)) - 1u;
         word &= word - 1u;
-        const uint32_t e = 32u * static_cast<uint32_t>(tid) + b;
+        s_list[pos++] = static_cast<uint16_t>(32u * static_cast<uint32_t>(tid) + b);
+    }
+    if (tid == 255) s_total = incl;
+    __syncthreads();
+    const uint32_t total = s_total;
+    const uint32_t cbase = chunk_base[c];
+    const size_t obase = static_cast<size_t>(L.out_off) + cbase;
+    const uint32_t room = L.cap > cbase ? L.cap - cbase : 0u;   // never write past the segment
+    // one kept element per thread: independent loads, coalesced pair stores
+    for (uint32_t i = tid; i < total; i += 256) {
+        const uint32_t e = s_list[i];
         if (e >= len) break;                // (mask bits exist only for elements of the layer)
-        if (pos < room) {
-            out_idx[obase + pos] = start + e;
-            out_val[obase + pos] = v[e];
+        const float val = v[e];
+        if (i < room) {
+            out_idx[obase + i] = start + e;
+            out_val[obase + i] = val;
         }
         v[e] = 0.f;
-        ++pos;
     }
 }
 
@@ -1436,6 +1513,7 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
                float *nsi_out, float *v_out, hipStream_t stream) {
     NsiArgs a;
     a.v_out = v_out;
+    a.flags = reinterpret_cast<const uint32_t *>(ws + plan->ws.flags);
     a.layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
     a.grad = grad;
     a.resid = resid;
@@ -1533,6 +1611,7 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
     const DirEntry *chunk_dir = reinterpret_cast<const DirEntry *>(ws + w.chunk_dir);
     SelState *state = reinterpret_cast<SelState *>(ws + w.state);
     uint32_t *hist = reinterpret_cast<uint32_t *>(ws + w.hist);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(ws + w.flags);
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
     uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
     uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
@@ -1552,24 +1631,30 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
     }
     marks.close(0);
 
-    const DirEntry *group_dir = reinterpret_cast<const DirEntry *>(ws + w.group_dir);
+    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + w.chunk_layer);
+    const uint32_t *group_layer = reinterpret_cast<const uint32_t *>(ws + w.group_layer);
+    const uint32_t *cand_groups = reinterpret_cast<const uint32_t *>(ws + w.cand_groups);
+    const uint32_t n_cand_groups = static_cast<uint32_t>(plan->cand_groups.size());
     const uint32_t *slot_cnt = reinterpret_cast<const uint32_t *>(ws + w.slot_cnt);
     const unsigned long long *slot_ent = reinterpret_cast<const unsigned long long *>(ws + w.slot_ent);
+    // first pass: the sampled tiles of the large layers (histogram only) and every tile of the
+    // other layers (scores, histogram, v) share one launch
+    rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, stream);
+    if (rc != RSDGC_OK) return rc;
     if (plan->any_large) {
-        rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, nullptr, stream);
-        if (rc != RSDGC_OK) return rc;
-        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist);
+        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
         marks.close(1);
         rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, v_out, stream);
         if (rc != RSDGC_OK) return rc;
-        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist);
+        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
         marks.close(2);
+        // large layers whose candidate bound failed (rare): their workgroups find nothing to do otherwise
+        rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, stream);
+        if (rc != RSDGC_OK) return rc;
     } else {
         marks.close(1);
         marks.close(2);
     }
-    rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, stream);
-    if (rc != RSDGC_OK) return rc;
     marks.close(3);
 
     // radix select: first digit from the histograms of the NSI passes, then the keys of each
@@ -1579,12 +1664,24 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
         unsigned long long *list_ent = reinterpret_cast<unsigned long long *>(ws + w.list_ent);
         hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(0),
                            level_bits(0));
-        const uint32_t n_map_wgs = std::min<uint32_t>(n_chunks, kNumCUs * 4u);
-        const uint32_t n_slot_wgs = plan->any_large ? std::min<uint32_t>(plan->n_slot_groups, kNumCUs * 4u) : 0u;
-        hipLaunchKernelGGL(k_gather, dim3(n_map_wgs + n_slot_wgs), dim3(256), 0, stream, layers,
-                           chunk_dir, group_dir, static_cast<uint32_t>(L), n_map_wgs, n_chunks,
-                           plan->n_slot_groups, state, reinterpret_cast<const uint32_t *>(nsi),
-                           slot_cnt, slot_ent, list_cnt, list_ent, hist);
+        GatherLists gl;
+        gl.chunk_dir = chunk_dir;
+        gl.chunk_layer = chunk_layer;
+        gl.group_layer = group_layer;
+        gl.map_chunks = reinterpret_cast<const uint32_t *>(ws + w.map_chunks);
+        gl.cand_groups = cand_groups;
+        gl.flags = flags;
+        gl.n_layers = static_cast<uint32_t>(L);
+        gl.n_chunks = n_chunks;
+        gl.n_map_chunks = static_cast<uint32_t>(plan->map_chunks.size());
+        gl.n_cand_groups = n_cand_groups;
+        gl.n_map_wgs = std::min<uint32_t>(gl.n_map_chunks, kNumCUs * 4u);
+        gl.n_slot_wgs = std::min<uint32_t>(n_cand_groups, kNumCUs * 4u);
+        const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(n_chunks, kNumCUs * 2u) : 0u;
+        if (gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs > 0)
+            hipLaunchKernelGGL(k_gather, dim3(gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs), dim3(256), 0,
+                               stream, layers, gl, state, reinterpret_cast<const uint32_t *>(nsi),
+                               slot_cnt, slot_ent, list_cnt, list_ent, hist);
         uint32_t *list2_cnt = reinterpret_cast<uint32_t *>(ws + w.list2_cnt);
         unsigned long long *list2_ent = reinterpret_cast<unsigned long long *>(ws + w.list2_ent);
         hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(1),
@@ -1599,15 +1696,21 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
     marks.close(4);
 
     if (plan->any_large)
-        hipLaunchKernelGGL(k_mark_cand, dim3(std::min<uint32_t>(plan->n_slot_groups, kNumCUs * 8u)),
-                           dim3(256), 0, stream, layers, group_dir, static_cast<uint32_t>(L),
-                           plan->n_slot_groups, state, slot_cnt, slot_ent, mask, cmask);
-    hipLaunchKernelGGL(k_mark_map, dim3(std::min<uint32_t>(plan->n_tiles_all, kNumCUs * 8u)), dim3(256),
-                       0, stream, layers, reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir),
-                       static_cast<uint32_t>(L), plan->n_tiles_all, state,
-                       reinterpret_cast<const uint32_t *>(nsi), mask, cmask);
+        hipLaunchKernelGGL(k_mark_cand, dim3(std::min<uint32_t>(n_cand_groups, kNumCUs * 8u)),
+                           dim3(256), 0, stream, layers, cand_groups, group_layer, n_cand_groups, state,
+                           slot_cnt, slot_ent, mask, cmask);
+    {
+        const uint32_t n_map_tiles = static_cast<uint32_t>(plan->map_tiles.size());
+        const uint32_t n_list_wgs = std::min<uint32_t>(n_map_tiles, kNumCUs * 8u);
+        const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(plan->n_tiles_all, kNumCUs * 4u) : 0u;
+        if (n_list_wgs + n_fb_wgs > 0)
+            hipLaunchKernelGGL(k_mark_map, dim3(n_list_wgs + n_fb_wgs), dim3(256), 0, stream, layers,
+                               reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir),
+                               static_cast<uint32_t>(L), plan->n_tiles_all,
+                               reinterpret_cast<const SampleEntry *>(ws + w.map_tiles), n_map_tiles,
+                               n_list_wgs, flags, state, reinterpret_cast<const uint32_t *>(nsi), mask, cmask);
+    }
     marks.close(5);
-    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + w.chunk_layer);
     hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, mask, cmask, chunk_cnt, chunk_ccnt);
     hipLaunchKernelGGL(k_scan, dim3(L), dim3(kScanThreads), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
                        out_counts, out_centre_counts, cmask ? 1 : 0);
@@ -1696,7 +1799,7 @@ int rsdgc_profile_end(rsdgc_plan_t *plan, double *stage_ms, int32_t *n_calls) {
 }
 
 const char *rsdgc_stage_name(int32_t stage) {
-    static const char *names[RSDGC_N_STAGES] = {"clear", "sample", "capture", "full_map", "select",
+    static const char *names[RSDGC_N_STAGES] = {"clear", "first_pass", "capture", "fallback_map", "select",
                                                 "mark", "count_scan", "emit", "centres"};
     return (stage >= 0 && stage < RSDGC_N_STAGES) ? names[stage] : "";
 }

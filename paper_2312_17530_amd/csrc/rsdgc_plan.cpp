@@ -31,6 +31,9 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->all_tile_dir.clear();
     plan->group_dir.clear();
     plan->samples.clear();
+    plan->cand_groups.clear();
+    plan->map_chunks.clear();
+    plan->map_tiles.clear();
     plan->any_large = false;
 
     int64_t elem_off = 0, out_off = 0, centre_off = 0;
@@ -99,6 +102,19 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->out_capacity = out_off;
     plan->centre_capacity = centre_off;
 
+    // static work lists of the passes after the NSI kernels: which slot groups can hold
+    // candidates, which chunks / tiles belong to layers that are ranked on the full map
+    for (int l = 0; l < L; ++l) {
+        const LayerDev &d = plan->layers[l];
+        if (d.large) {
+            for (uint32_t g = 0; g < d.n_groups; ++g) plan->cand_groups.push_back(d.group_begin + g);
+        } else if (d.k > 0) {
+            for (uint32_t c = 0; c < d.n_chunks; ++c) plan->map_chunks.push_back(d.chunk_begin + c);
+            for (uint32_t t = 0; t < d.n_tiles; ++t)
+                plan->map_tiles.push_back(SampleEntry{static_cast<uint32_t>(l), t});
+        }
+    }
+
     // one launch of each NSI pass per distinct neighbourhood side
     for (int p = 1; p <= RSDGC_MAX_P; p += 2) {
         PGroup g;
@@ -112,10 +128,11 @@ int build_tables(rsdgc_plan_s *plan) {
             plan->tile_dir.push_back(DirEntry{g.n_tiles, static_cast<uint32_t>(l)});
             g.n_tiles += d.n_tiles;
             ++g.dir_count;
-            if (d.large)
-                for (uint32_t t = 0; t < d.n_tiles; ++t)
-                    if (tile_is_sampled(t, sample_shift(d.n_tiles)))
-                        plan->samples.push_back(SampleEntry{static_cast<uint32_t>(l), t});
+            // tile list of the first NSI pass: the sampled tiles of a large layer, every tile
+            // of any other layer that selects something
+            for (uint32_t t = 0; t < d.n_tiles; ++t)
+                if (d.large ? tile_is_sampled(t, sample_shift(d.n_tiles)) : d.k > 0)
+                    plan->samples.push_back(SampleEntry{static_cast<uint32_t>(l), t});
         }
         if (g.dir_count == 0) continue;
         g.n_samples = static_cast<uint32_t>(plan->samples.size()) - g.sample_begin;
@@ -128,8 +145,7 @@ int build_tables(rsdgc_plan_s *plan) {
     const size_t A = 256;
     const size_t words = static_cast<size_t>(plan->total_elems / 32);
     // sized for the worst case so that new ratios never change the workspace size
-    size_t max_samples = 0;
-    for (int l = 0; l < L; ++l) max_samples += plan->layers[l].n_sampled;
+    const size_t max_samples = plan->n_tiles_all;
     size_t off = 0;
     w.layers = off;       off = align_up(off + sizeof(LayerDev) * L, A);
     w.tile_dir = off;     off = align_up(off + sizeof(DirEntry) * (L + (RSDGC_MAX_P + 1) / 2), A);
@@ -138,6 +154,10 @@ int build_tables(rsdgc_plan_s *plan) {
     w.group_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + 1), A);
     w.samples = off;      off = align_up(off + sizeof(SampleEntry) * (max_samples + 1), A);
     w.chunk_layer = off;  off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.group_layer = off;  off = align_up(off + sizeof(uint32_t) * plan->n_slot_groups, A);
+    w.cand_groups = off;  off = align_up(off + sizeof(uint32_t) * plan->n_slot_groups, A);
+    w.map_chunks = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.map_tiles = off;    off = align_up(off + sizeof(SampleEntry) * (size_t(plan->n_tiles_all) + 1), A);
     w.table_bytes = off;
     w.state = off;        off = align_up(off + sizeof(SelState) * L, A);   // written in full each call
     w.zero_begin = off;
@@ -146,6 +166,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * L, A);
     w.list2_cnt = off;    off = align_up(off + sizeof(uint32_t) * L, A);
+    w.flags = off;        off = align_up(off + sizeof(uint32_t) * 64, A);
     w.mask = off;         off = align_up(off + sizeof(uint32_t) * words, A);
     w.cmask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
     w.zero_end = off;
@@ -171,10 +192,23 @@ int build_tables(rsdgc_plan_s *plan) {
                     sizeof(SampleEntry) * plan->samples.size());
     {
         uint32_t *cl = reinterpret_cast<uint32_t *>(plan->table.data() + w.chunk_layer);
-        for (int l = 0; l < L; ++l)
+        uint32_t *gl = reinterpret_cast<uint32_t *>(plan->table.data() + w.group_layer);
+        for (int l = 0; l < L; ++l) {
             for (uint32_t c = 0; c < plan->layers[l].n_chunks; ++c)
                 cl[plan->layers[l].chunk_begin + c] = static_cast<uint32_t>(l);
+            for (uint32_t g = 0; g < plan->layers[l].n_groups; ++g)
+                gl[plan->layers[l].group_begin + g] = static_cast<uint32_t>(l);
+        }
     }
+    if (!plan->cand_groups.empty())
+        std::memcpy(plan->table.data() + w.cand_groups, plan->cand_groups.data(),
+                    sizeof(uint32_t) * plan->cand_groups.size());
+    if (!plan->map_chunks.empty())
+        std::memcpy(plan->table.data() + w.map_chunks, plan->map_chunks.data(),
+                    sizeof(uint32_t) * plan->map_chunks.size());
+    if (!plan->map_tiles.empty())
+        std::memcpy(plan->table.data() + w.map_tiles, plan->map_tiles.data(),
+                    sizeof(SampleEntry) * plan->map_tiles.size());
     ++plan->version;
     return RSDGC_OK;
 }
