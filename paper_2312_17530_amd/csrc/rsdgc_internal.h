@@ -15,7 +15,7 @@ constexpr int kChunk = 8192;         // elements per workgroup in the 1-D passes
 constexpr int kHistBins = 4096;      // widest radix digit (12 bits)
 constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements
 constexpr int kSlotCap = 256;        // candidate centres one tile can record
-constexpr int kSlotGroup = 16;       // tile slots per work item of the candidate passes (<= 64)
+constexpr int kSlotGroup = 16;       // tile slots per work item of the candidate passes (4 per wave)
 constexpr int kCandBins = 256;       // 12-bit score buckets above the bound that a capture workgroup counts
 constexpr int kListMin = 8192;       // smallest threshold-bucket list of a layer (entries)
 constexpr int kList2Cap = 2048;      // keys sharing the first two digits that a layer can stage
@@ -87,6 +87,23 @@ struct SampleEntry {
     uint32_t local_tile;
 };
 
+// Work item of the candidate passes: kSlotGroup (or fewer) consecutive tile slots of a large layer.
+struct GroupEntry {
+    uint32_t layer;
+    uint32_t slot0;      // first tile slot (index over the tiles of all layers)
+    uint32_t ntile;      // slots in the group
+    uint32_t pad_;
+};
+
+// Work item of the score-map passes: one 8192-element chunk of a layer ranked on the full map.
+struct ChunkEntry {
+    uint32_t layer;
+    uint32_t start;      // first element of the chunk inside the layer
+    uint32_t len;        // elements in the chunk
+    uint32_t pad_;
+    uint64_t arena_off;  // elem_off + start
+};
+
 // Byte offsets of the workspace sections (all multiples of 256).
 struct WsLayout {
     // uploaded tables
@@ -94,12 +111,10 @@ struct WsLayout {
     size_t tile_dir = 0;     // DirEntry[] per p-group, each closed by a sentinel
     size_t chunk_dir = 0;    // DirEntry[n_layers + 1]
     size_t all_tile_dir = 0; // DirEntry[n_layers + 1]: tiles of all layers in layer order
-    size_t group_dir = 0;    // DirEntry[n_layers + 1]: slot groups
     size_t samples = 0;      // SampleEntry[] per p-group
     size_t chunk_layer = 0;  // uint32[n_chunks]: layer of every 8192-element chunk
-    size_t group_layer = 0;  // uint32[n_slot_groups]: layer of every slot group
-    size_t cand_groups = 0;  // uint32[]: slot groups of the large layers (work list of the candidate passes)
-    size_t map_chunks = 0;   // uint32[]: chunks of the other layers that select something
+    size_t cand_groups = 0;  // GroupEntry[]: slot groups of the large layers (work list of the candidate passes)
+    size_t map_chunks = 0;   // ChunkEntry[]: chunks of the other layers that select something
     size_t map_tiles = 0;    // SampleEntry[]: tiles of those layers
     size_t table_bytes = 0;  // bytes uploaded from the host
     size_t state = 0;        // SelState[n_layers], rewritten at the start of every compress
@@ -145,10 +160,9 @@ struct rsdgc_plan_s {
     std::vector<rsdgc::DirEntry> tile_dir;
     std::vector<rsdgc::DirEntry> chunk_dir;
     std::vector<rsdgc::DirEntry> all_tile_dir;
-    std::vector<rsdgc::DirEntry> group_dir;
     std::vector<rsdgc::SampleEntry> samples;
-    std::vector<uint32_t> cand_groups;
-    std::vector<uint32_t> map_chunks;
+    std::vector<rsdgc::GroupEntry> cand_groups;
+    std::vector<rsdgc::ChunkEntry> map_chunks;
     std::vector<rsdgc::SampleEntry> map_tiles;
     uint32_t n_tiles_all = 0;
     uint32_t n_slot_groups = 0;

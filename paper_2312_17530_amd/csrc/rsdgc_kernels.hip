@@ -97,25 +97,6 @@ __device__ __forceinline__ uint32_t block_scan_incl_n(uint32_t v, uint32_t *wave
     return r;
 }
 
-// Exclusive prefix of the candidate counts of ntile (<= 64) consecutive tile slots into
-// pref[0 .. 64]; pref[ntile] is their total.  Called by every thread of the workgroup.
-__device__ __forceinline__ void slot_prefix(uint32_t *pref /*[65]*/, const uint32_t *__restrict__ slot_cnt,
-                                            uint32_t slot0, uint32_t ntile) {
-    __syncthreads();                       // earlier readers of pref are done
-    if (threadIdx.x < 64) {
-        const uint32_t lane = threadIdx.x;
-        uint32_t v = lane < ntile ? slot_cnt[slot0 + lane] : 0u;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t o = __shfl_up(v, d, 64);
-            if (lane >= static_cast<uint32_t>(d)) v += o;
-        }
-        pref[lane + 1] = v;
-        if (lane == 0) pref[0] = 0;
-    }
-    __syncthreads();
-}
-
 // Position for one appended item per flagged lane: one atomic on the LDS counter per wave.
 // Called by all 64 lanes of a wave; the result is meaningful for flagged lanes only.
 __device__ __forceinline__ uint32_t wave_append(uint32_t *counter, bool flag) {
@@ -553,8 +534,11 @@ __global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ l
 // ----------------------------------------------------------------- find --
 // One workgroup per layer: walk the digit histogram from the top, fix the digit that
 // holds the k_rem-th largest key, clear the histogram for the next level.
+// The layer's counts may be spread over `copies` histograms of 2^bits bins laid end to end
+// (writers pick a copy by workgroup id so that fewer atomics meet in one cache line).
 __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
-                                              uint32_t *__restrict__ hist, int shift, int bits) {
+                                              uint32_t *__restrict__ hist, int shift, int bits,
+                                              int copies) {
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t found;
     const int l = blockIdx.x, tid = threadIdx.x;
@@ -566,13 +550,15 @@ __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
         // thread t owns bins [hi - per, hi), hi = nb - t * per  (t = 0 holds the top bins)
         const int hi = nb - tid * per;
         uint32_t own = 0;
-        for (int b = hi - 1; b >= hi - per; --b) own += h[b];
+        for (int cp = 0; cp < copies; ++cp)
+            for (int b = hi - 1; b >= hi - per; --b) own += h[cp * nb + b];
         const uint32_t incl = block_scan_incl(own, wave_tot);
         const uint32_t excl = incl - own;
         if (excl < st.k_rem && st.k_rem <= incl) {
             uint32_t acc = excl;
             for (int b = hi - 1; b >= hi - per; --b) {
-                const uint32_t c = h[b];
+                uint32_t c = 0;
+                for (int cp = 0; cp < copies; ++cp) c += h[cp * nb + b];
                 if (acc + c >= st.k_rem) {
                     SelState ns = st;
                     ns.T = st.T | (static_cast<unsigned long long>(b) << shift);
@@ -593,7 +579,7 @@ __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
         }
     }
     __syncthreads();
-    for (int b = tid; b < nb; b += 256) h[b] = 0;
+    for (int b = tid; b < nb * copies; b += 256) h[b] = 0;
 }
 
 // --------------------------------------------------------------- gather --
@@ -607,7 +593,8 @@ __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
 //   the last n_fb_wgs           only when some large layer fell back to the full map: they
 //                               walk all chunks and take those of such layers.
 // Matches are staged in LDS and appended with one atomic per flush.
-constexpr int kStage = 4096;
+constexpr int kStage = 2048;            // staged keys per workgroup (a round adds at most 1024)
+constexpr int kHist1Copies = kHistBins >> level_bits(1);   // second-digit histograms per layer (4)
 
 struct GatherStage {
     unsigned long long ent[kStage];
@@ -634,7 +621,8 @@ __device__ __forceinline__ void gather_flush(GatherStage &st, const LayerDev &L,
         if (threadIdx.x == 0) st.n = 0;
     }
     if (with_hist) {
-        uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins;
+        uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins +
+                                    (blockIdx.x % kHist1Copies) * (1u << level_bits(1));
         for (int b = threadIdx.x; b < (1 << level_bits(1)); b += 256) {
             const uint32_t c = st.hist1[b];
             if (c) { atomicAdd(&gh[b], c); st.hist1[b] = 0; }
@@ -643,15 +631,32 @@ __device__ __forceinline__ void gather_flush(GatherStage &st, const LayerDev &L,
     __syncthreads();
 }
 
+// One round of at most 1024 appends (4 per thread) is about to start: make room for it.
+__device__ __forceinline__ void gather_make_room(GatherStage &st, const LayerDev &L,
+                                                 uint32_t *__restrict__ list_cnt, uint32_t l,
+                                                 unsigned long long *__restrict__ list_ent,
+                                                 uint32_t *__restrict__ hist) {
+    __syncthreads();                       // appends of the previous round are counted
+    if (st.n + 1024u > static_cast<uint32_t>(kStage))          // uniform
+        gather_flush(st, L, list_cnt, l, list_ent, hist, false);
+}
+
+// Stages key K (of a flagged lane) and counts its second digit.  Called by whole waves.
+__device__ __forceinline__ void gather_stage_key(GatherStage &st, bool hit, unsigned long long K) {
+    const uint32_t pos = wave_append(&st.n, hit);
+    if (hit) {
+        st.ent[pos] = K;
+        atomicAdd(&st.hist1[static_cast<uint32_t>(K >> level_shift(1)) & ((1u << level_bits(1)) - 1u)], 1u);
+    }
+}
+
 struct GatherLists {
-    const DirEntry *chunk_dir;     // all chunks by layer (fallback walk)
-    const uint32_t *chunk_layer;   // [n_chunks]
-    const uint32_t *group_layer;   // [n_slot_groups]
-    const uint32_t *map_chunks;    // [n_map_chunks]
-    const uint32_t *cand_groups;   // [n_cand_groups]
+    const DirEntry *chunk_dir;       // all chunks by layer (fallback walk)
+    const ChunkEntry *map_chunks;    // [n_map_chunks]
+    const GroupEntry *cand_groups;   // [n_cand_groups]
     const uint32_t *flags;
     uint32_t n_layers, n_chunks, n_map_chunks, n_cand_groups;
-    uint32_t n_map_wgs, n_slot_wgs;   // the remaining workgroups are fallback walkers
+    uint32_t n_map_wgs, n_slot_wgs;  // the remaining workgroups are fallback walkers
 };
 
 __global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ layers,
@@ -664,11 +669,9 @@ __global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ lay
                                                 unsigned long long *__restrict__ list_ent,
                                                 uint32_t *__restrict__ hist) {
     __shared__ GatherStage stage;
-    __shared__ uint32_t pref[65];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // role 0: listed score-map chunks, 1: listed slot groups, 2: fallback walk over all chunks
     const int role = blockIdx.x < gl.n_map_wgs ? 0 : blockIdx.x < gl.n_map_wgs + gl.n_slot_wgs ? 1 : 2;
-    const bool is_map = role != 1;
     const uint32_t first = role == 0 ? blockIdx.x : role == 1 ? blockIdx.x - gl.n_map_wgs
                                                               : blockIdx.x - gl.n_map_wgs - gl.n_slot_wgs;
     const uint32_t stride = role == 0 ? gl.n_map_wgs : role == 1 ? gl.n_slot_wgs
@@ -680,8 +683,6 @@ __global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ lay
     if (tid == 0) stage.n = 0;
     for (int b = tid; b < (1 << level_bits(1)); b += 256) stage.hist1[b] = 0;
     __syncthreads();
-    constexpr int shift1 = level_shift(1);
-    constexpr uint32_t mask1 = (1u << level_bits(1)) - 1u;
 
     uint32_t e = role == 2 ? dir_lookup(dir, gl.n_layers, first) : 0u;
     uint32_t cur_l = 0xffffffffu;
@@ -689,21 +690,25 @@ __global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ lay
     uint32_t digit0 = 0;
     LayerDev L;
     for (uint32_t it = first; it < n_items; it += stride) {
-        uint32_t id, l;                    // chunk or slot group, and its layer
-        if (role == 2) {
+        uint32_t l;
+        ChunkEntry ce = {};
+        GroupEntry ge = {};
+        if (role == 0) {
+            ce = gl.map_chunks[it];
+            l = ce.layer;
+        } else if (role == 1) {
+            ge = gl.cand_groups[it];
+            l = ge.layer;
+        } else {
             while (it >= dir[e + 1].begin) ++e;
             l = dir[e].layer;
-            id = it;
-        } else {
-            id = role == 0 ? gl.map_chunks[it] : gl.cand_groups[it];
-            l = role == 0 ? gl.chunk_layer[id] : gl.group_layer[id];
         }
         if (l != cur_l) {
             if (active) gather_flush(stage, L, list_cnt, cur_l, list_ent, hist, true);
             cur_l = l;
             L = layers[l];
             const SelState st = state[l];
-            active = !st.done && st.mode == (is_map ? kModeFullMap : kModeCandidates);
+            active = !st.done && st.mode == (role == 1 ? kModeCandidates : kModeFullMap);
             if (role == 2) active = active && L.large != 0u;      // the others are on the list
             digit0 = static_cast<uint32_t>(st.T >> level_shift(0));
         }
@@ -714,60 +719,66 @@ __global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ lay
             }
             continue;
         }
-        if (is_map) {
-            const uint32_t start = (id - L.chunk_begin) * kChunk;
-            const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-            const uint32_t *__restrict__ src = keys + L.elem_off + start;
+        if (role != 1) {
+            if (role == 2) {
+                ce.start = (it - L.chunk_begin) * kChunk;
+                ce.len = min(static_cast<uint32_t>(kChunk), L.G - ce.start);
+                ce.arena_off = static_cast<uint64_t>(L.elem_off) + ce.start;
+            }
+            const uint32_t start = ce.start, len = ce.len;
+            const uint32_t *__restrict__ src = keys + ce.arena_off;
+            // the whole chunk is requested before any of it is used
+            uint4 q[kChunk / 1024];
+#pragma unroll
+            for (int j = 0; j < kChunk / 1024; ++j) {
+                const uint32_t e4 = j * 1024 + 4 * tid;
+                q[j] = make_uint4(0, 0, 0, 0);
+                if (e4 + 3 < len) {
+                    q[j] = *reinterpret_cast<const uint4 *>(src + e4);
+                } else if (e4 < len) {
+                    q[j].x = src[e4];
+                    if (e4 + 1 < len) q[j].y = src[e4 + 1];
+                    if (e4 + 2 < len) q[j].z = src[e4 + 2];
+                }
+            }
+#pragma unroll
             for (int j = 0; j < kChunk / 1024; ++j) {
                 if (static_cast<uint32_t>(j) * 1024u >= len) break;       // uniform
-                __syncthreads();
-                if (stage.n + 1024u > static_cast<uint32_t>(kStage))
-                    gather_flush(stage, L, list_cnt, l, list_ent, hist, false);
+                gather_make_room(stage, L, list_cnt, l, list_ent, hist);
                 const uint32_t e4 = j * 1024 + 4 * tid;
-                uint32_t kk[4] = {0, 0, 0, 0};
-                if (e4 + 3 < len) {
-                    const uint4 q = *reinterpret_cast<const uint4 *>(src + e4);
-                    kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
-                } else {
-                    for (uint32_t q = 0; q < 4 && e4 + q < len; ++q) kk[q] = src[e4 + q];
-                }
+                const uint32_t kk[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
 #pragma unroll
-                for (uint32_t q = 0; q < 4; ++q) {
-                    const bool hit = e4 + q < len && ((kk[q] & 0x7fffffffu) >> 19) == digit0;
-                    const uint32_t pos = wave_append(&stage.n, hit);
-                    if (hit) {
-                        const unsigned long long K = composite_key(kk[q], start + e4 + q);
-                        stage.ent[pos] = K;
-                        atomicAdd(&stage.hist1[static_cast<uint32_t>(K >> shift1) & mask1], 1u);
-                    }
+                for (uint32_t c = 0; c < 4; ++c) {
+                    const bool hit = e4 + c < len && ((kk[c] & 0x7fffffffu) >> 19) == digit0;
+                    gather_stage_key(stage, hit, composite_key(kk[c], start + e4 + c));
                 }
             }
         } else {
-            const uint32_t firstt = (id - L.group_begin) * kSlotGroup;
-            const uint32_t ntile = min(static_cast<uint32_t>(kSlotGroup), L.n_tiles - firstt);
-            const uint32_t slot0 = L.tile_begin_all + firstt;
-            slot_prefix(pref, slot_cnt, slot0, ntile);
-            const uint32_t total = pref[ntile];
-            for (uint32_t j0 = 0; j0 < total; j0 += 256) {
-                __syncthreads();
-                if (stage.n + 256u > static_cast<uint32_t>(kStage))
-                    gather_flush(stage, L, list_cnt, l, list_ent, hist, false);
-                const uint32_t j = j0 + tid;
-                unsigned long long K = 0;
-                bool hit = false;
-                if (j < total) {
-                    uint32_t lo = 0, hi = ntile;          // slot with pref[lo] <= j < pref[lo + 1]
-                    while (hi - lo > 1) {
-                        const uint32_t mid = (lo + hi) >> 1;
-                        if (pref[mid] <= j) lo = mid; else hi = mid;
-                    }
-                    K = slot_ent[static_cast<size_t>(slot0 + lo) * kSlotCap + (j - pref[lo])];
-                    hit = static_cast<uint32_t>(K >> level_shift(0)) == digit0;
+            // each wave takes 4 of the group's tile slots; a round covers 64 entries of each
+            uint32_t cnt[kSlotGroup / 4];
+#pragma unroll
+            for (int c = 0; c < kSlotGroup / 4; ++c) {
+                const uint32_t sl = wave + 4 * c;
+                cnt[c] = sl < ge.ntile ? min(slot_cnt[ge.slot0 + sl], static_cast<uint32_t>(kSlotCap)) : 0u;
+            }
+            uint32_t longest = 0;
+#pragma unroll
+            for (int c = 0; c < kSlotGroup / 4; ++c) longest = max(longest, cnt[c]);
+            const int rounds = __syncthreads_or(longest > 64u) ? kSlotCap / 64 : 1;   // uniform
+            for (int rd = 0; rd < rounds; ++rd) {
+                unsigned long long K[kSlotGroup / 4];
+                const uint32_t j = 64u * rd + lane;
+#pragma unroll
+                for (int c = 0; c < kSlotGroup / 4; ++c) {
+                    K[c] = 0;
+                    if (j < cnt[c])
+                        K[c] = slot_ent[static_cast<size_t>(ge.slot0 + wave + 4 * c) * kSlotCap + j];
                 }
-                const uint32_t pos = wave_append(&stage.n, hit);
-                if (hit) {
-                    stage.ent[pos] = K;
-                    atomicAdd(&stage.hist1[static_cast<uint32_t>(K >> shift1) & mask1], 1u);
+                gather_make_room(stage, L, list_cnt, l, list_ent, hist);
+#pragma unroll
+                for (int c = 0; c < kSlotGroup / 4; ++c) {
+                    const bool hit = j < cnt[c] && static_cast<uint32_t>(K[c] >> level_shift(0)) == digit0;
+                    gather_stage_key(stage, hit, K[c]);
                 }
             }
         }
@@ -981,62 +992,64 @@ __device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos
 }
 
 // Candidate-mode layers: workgroups stride over the plan's list of slot groups of the large
-// layers; every recorded candidate that reaches its layer's threshold ORs the bits of its
-// window into the (cleared) mask.  The words touched are nearly all distinct, which is the
-// case global atomics handle well.
-__global__ __launch_bounds__(256) void k_mark_cand(const LayerDev *__restrict__ layers,
-                                                   const uint32_t *__restrict__ cand_groups,
-                                                   const uint32_t *__restrict__ group_layer,
-                                                   uint32_t n_groups,
-                                                   const SelState *__restrict__ state,
-                                                   const uint32_t *__restrict__ slot_cnt,
-                                                   const unsigned long long *__restrict__ slot_ent,
-                                                   uint32_t *__restrict__ mask,
-                                                   uint32_t *__restrict__ cmask) {
-    __shared__ uint32_t pref[65];
-    const int tid = threadIdx.x;
-    const uint32_t first = blockIdx.x, stride = gridDim.x;
-    if (first >= n_groups) return;
+// layers, each wave taking 4 tile slots of a group; every recorded candidate that reaches its
+// layer's threshold ORs the bits of its window into the (cleared) mask.  The words touched
+// are nearly all distinct, which is the case global atomics handle well.
+__device__ __forceinline__ void mark_candidates(const LayerDev *__restrict__ layers,
+                                                const GroupEntry *__restrict__ groups, uint32_t n_groups,
+                                                uint32_t first, uint32_t stride,
+                                                const SelState *__restrict__ state,
+                                                const uint32_t *__restrict__ slot_cnt,
+                                                const unsigned long long *__restrict__ slot_ent,
+                                                uint32_t *__restrict__ mask, uint32_t *__restrict__ cmask) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t cur_l = 0xffffffffu;
     bool active = false;
     unsigned long long T = 0;
     LayerDev L;
     for (uint32_t it = first; it < n_groups; it += stride) {
-        const uint32_t id = cand_groups[it];
-        const uint32_t l = group_layer[id];
-        if (l != cur_l) {
-            cur_l = l;
-            L = layers[l];
-            const SelState st = state[l];
+        const GroupEntry ge = groups[it];
+        if (ge.layer != cur_l) {
+            cur_l = ge.layer;
+            L = layers[cur_l];
+            const SelState st = state[cur_l];
             active = st.mode == kModeCandidates;
             T = st.T;
         }
         if (!active) continue;
-        const uint32_t firstt = (id - L.group_begin) * kSlotGroup;
-        const uint32_t ntile = min(static_cast<uint32_t>(kSlotGroup), L.n_tiles - firstt);
-        const uint32_t slot0 = L.tile_begin_all + firstt;
-        slot_prefix(pref, slot_cnt, slot0, ntile);
-        const uint32_t total = pref[ntile];
         const int h = (static_cast<int>(L.p) - 1) / 2;
         const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
-        for (uint32_t j = tid; j < total; j += 256) {
-            uint32_t lo = 0, hi = ntile;              // slot with pref[lo] <= j < pref[lo + 1]
-            while (hi - lo > 1) {
-                const uint32_t mid = (lo + hi) >> 1;
-                if (pref[mid] <= j) lo = mid; else hi = mid;
+        uint32_t cnt[kSlotGroup / 4];
+#pragma unroll
+        for (int c = 0; c < kSlotGroup / 4; ++c) {
+            const uint32_t sl = wave + 4 * c;
+            cnt[c] = sl < ge.ntile ? min(slot_cnt[ge.slot0 + sl], static_cast<uint32_t>(kSlotCap)) : 0u;
+        }
+        uint32_t longest = 0;
+#pragma unroll
+        for (int c = 0; c < kSlotGroup / 4; ++c) longest = max(longest, cnt[c]);   // wave-uniform
+        for (uint32_t j0 = 0; j0 < longest; j0 += 64) {
+            const uint32_t j = j0 + lane;
+            unsigned long long K[kSlotGroup / 4];
+#pragma unroll
+            for (int c = 0; c < kSlotGroup / 4; ++c) {
+                K[c] = 0;
+                if (j < cnt[c]) K[c] = slot_ent[static_cast<size_t>(ge.slot0 + wave + 4 * c) * kSlotCap + j];
             }
-            const unsigned long long K = slot_ent[static_cast<size_t>(slot0 + lo) * kSlotCap + (j - pref[lo])];
-            if (K >= T) {
-                const uint32_t i = ~static_cast<uint32_t>(K);
-                const int xc = static_cast<int>(i / L.C);
-                const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * L.C);
-                const int ylo = max(0, yc - h), yhi = min(C - 1, yc + h);
-                for (int x = max(0, xc - h); x <= min(R - 1, xc + h); ++x)
-                    set_bits(mask, static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + ylo,
-                             static_cast<uint32_t>(yhi - ylo + 1));
-                if (cmask) {
-                    const size_t pos = static_cast<size_t>(L.elem_off) + i;
-                    atomicOr(&cmask[pos >> 5], 1u << (pos & 31));
+#pragma unroll
+            for (int c = 0; c < kSlotGroup / 4; ++c) {
+                if (j < cnt[c] && K[c] >= T) {
+                    const uint32_t i = ~static_cast<uint32_t>(K[c]);
+                    const int xc = static_cast<int>(i / L.C);
+                    const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * L.C);
+                    const int ylo = max(0, yc - h), yhi = min(C - 1, yc + h);
+                    for (int x = max(0, xc - h); x <= min(R - 1, xc + h); ++x)
+                        set_bits(mask, static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + ylo,
+                                 static_cast<uint32_t>(yhi - ylo + 1));
+                    if (cmask) {
+                        const size_t pos = static_cast<size_t>(L.elem_off) + i;
+                        atomicOr(&cmask[pos >> 5], 1u << (pos & 31));
+                    }
                 }
             }
         }
@@ -1049,27 +1062,50 @@ __global__ __launch_bounds__(256) void k_mark_cand(const LayerDev *__restrict__ 
 // whole neighbourhoods are kept) is done on those words with shifts and ORs, and the tile's
 // mask words are written with plain stores (rows that are a multiple of 32 long) -- no
 // global atomics on that path.
-// Workgroups [0, n_list_wgs) stride over the plan's list of tiles of the layers that are always
-// ranked on the full map; the others run only when some large layer fell back to it, walk
-// all tiles and take those of such layers.
-__global__ __launch_bounds__(256) void k_mark_map(const LayerDev *__restrict__ layers,
-                                                  const DirEntry *__restrict__ dir, uint32_t n_layers,
-                                                  uint32_t n_tiles, const SampleEntry *__restrict__ map_tiles,
-                                                  uint32_t n_map_tiles, uint32_t n_list_wgs,
-                                                  const uint32_t *__restrict__ flags,
-                                                  const SelState *__restrict__ state,
-                                                  const uint32_t *__restrict__ keys,
-                                                  uint32_t *__restrict__ mask,
-                                                  uint32_t *__restrict__ cmask) {
+// One launch marks everything.  Workgroups [0, n_cand_wgs) take the candidate-mode layers (see
+// mark_candidates); the next n_list_wgs stride over the plan's list of tiles of the layers
+// that are always ranked on the full map; the others run only when some large layer fell back
+// to it, walk all tiles and take those of such layers.
+struct MarkArgs {
+    const LayerDev *layers;
+    const SelState *state;
+    const GroupEntry *cand_groups;
+    uint32_t n_cand_groups, n_cand_wgs;
+    const uint32_t *slot_cnt;
+    const unsigned long long *slot_ent;
+    const DirEntry *dir;             // tiles of all layers in layer order (fallback walk)
+    uint32_t n_layers, n_tiles;
+    const SampleEntry *map_tiles;
+    uint32_t n_map_tiles, n_list_wgs;
+    const uint32_t *flags;
+    const uint32_t *keys;            // score map
+    uint32_t *mask, *cmask;
+};
+
+__global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
     constexpr int MAXH = (RSDGC_MAX_P - 1) / 2;
     __shared__ unsigned long long bits[kTileRows + 2 * MAXH][4];   // [row][left, seg0, seg1, right]
+    if (blockIdx.x < m.n_cand_wgs) {
+        mark_candidates(m.layers, m.cand_groups, m.n_cand_groups, blockIdx.x, m.n_cand_wgs, m.state,
+                        m.slot_cnt, m.slot_ent, m.mask, m.cmask);
+        return;
+    }
+    const LayerDev *__restrict__ layers = m.layers;
+    const DirEntry *__restrict__ dir = m.dir;
+    const SampleEntry *__restrict__ map_tiles = m.map_tiles;
+    const SelState *__restrict__ state = m.state;
+    const uint32_t *__restrict__ keys = m.keys;
+    uint32_t *__restrict__ mask = m.mask;
+    uint32_t *__restrict__ cmask = m.cmask;
+    const uint32_t n_layers = m.n_layers;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool listed = blockIdx.x < n_list_wgs;
-    const uint32_t first = listed ? blockIdx.x : blockIdx.x - n_list_wgs;
-    const uint32_t stride = listed ? n_list_wgs : gridDim.x - n_list_wgs;
-    const uint32_t n_items = listed ? n_map_tiles : n_tiles;
+    const uint32_t bid = blockIdx.x - m.n_cand_wgs;
+    const bool listed = bid < m.n_list_wgs;
+    const uint32_t first = listed ? bid : bid - m.n_list_wgs;
+    const uint32_t stride = listed ? m.n_list_wgs : gridDim.x - m.n_cand_wgs - m.n_list_wgs;
+    const uint32_t n_items = listed ? m.n_map_tiles : m.n_tiles;
     if (first >= n_items) return;
-    if (!listed && flags[0] == 0u) return;
+    if (!listed && m.flags[0] == 0u) return;
     uint32_t e = listed ? 0u : dir_lookup(dir, n_layers, first);
     uint32_t cur_l = 0xffffffffu;
     bool active = false;
@@ -1632,8 +1668,7 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
     marks.close(0);
 
     const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + w.chunk_layer);
-    const uint32_t *group_layer = reinterpret_cast<const uint32_t *>(ws + w.group_layer);
-    const uint32_t *cand_groups = reinterpret_cast<const uint32_t *>(ws + w.cand_groups);
+    const GroupEntry *cand_groups = reinterpret_cast<const GroupEntry *>(ws + w.cand_groups);
     const uint32_t n_cand_groups = static_cast<uint32_t>(plan->cand_groups.size());
     const uint32_t *slot_cnt = reinterpret_cast<const uint32_t *>(ws + w.slot_cnt);
     const unsigned long long *slot_ent = reinterpret_cast<const unsigned long long *>(ws + w.slot_ent);
@@ -1663,12 +1698,10 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
         uint32_t *list_cnt = reinterpret_cast<uint32_t *>(ws + w.list_cnt);
         unsigned long long *list_ent = reinterpret_cast<unsigned long long *>(ws + w.list_ent);
         hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(0),
-                           level_bits(0));
+                           level_bits(0), 1);
         GatherLists gl;
         gl.chunk_dir = chunk_dir;
-        gl.chunk_layer = chunk_layer;
-        gl.group_layer = group_layer;
-        gl.map_chunks = reinterpret_cast<const uint32_t *>(ws + w.map_chunks);
+        gl.map_chunks = reinterpret_cast<const ChunkEntry *>(ws + w.map_chunks);
         gl.cand_groups = cand_groups;
         gl.flags = flags;
         gl.n_layers = static_cast<uint32_t>(L);
@@ -1685,7 +1718,7 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
         uint32_t *list2_cnt = reinterpret_cast<uint32_t *>(ws + w.list2_cnt);
         unsigned long long *list2_ent = reinterpret_cast<unsigned long long *>(ws + w.list2_ent);
         hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(1),
-                           level_bits(1));
+                           level_bits(1), kHist1Copies);
         hipLaunchKernelGGL(k_filter, dim3(L * kFilterSplit), dim3(kFinishThreads), 0, stream, layers,
                            state, list_cnt, list_ent, list2_cnt, list2_ent);
         hipLaunchKernelGGL(k_finish, dim3(L), dim3(kFinishThreads), 0, stream, layers, state, list_cnt,
@@ -1695,20 +1728,28 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
     HIP_TRY(hipGetLastError());
     marks.close(4);
 
-    if (plan->any_large)
-        hipLaunchKernelGGL(k_mark_cand, dim3(std::min<uint32_t>(n_cand_groups, kNumCUs * 8u)),
-                           dim3(256), 0, stream, layers, cand_groups, group_layer, n_cand_groups, state,
-                           slot_cnt, slot_ent, mask, cmask);
     {
-        const uint32_t n_map_tiles = static_cast<uint32_t>(plan->map_tiles.size());
-        const uint32_t n_list_wgs = std::min<uint32_t>(n_map_tiles, kNumCUs * 8u);
+        MarkArgs m;
+        m.layers = layers;
+        m.state = state;
+        m.cand_groups = cand_groups;
+        m.n_cand_groups = n_cand_groups;
+        m.n_cand_wgs = std::min<uint32_t>(n_cand_groups, kNumCUs * 8u);
+        m.slot_cnt = slot_cnt;
+        m.slot_ent = slot_ent;
+        m.dir = reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir);
+        m.n_layers = static_cast<uint32_t>(L);
+        m.n_tiles = plan->n_tiles_all;
+        m.map_tiles = reinterpret_cast<const SampleEntry *>(ws + w.map_tiles);
+        m.n_map_tiles = static_cast<uint32_t>(plan->map_tiles.size());
+        m.n_list_wgs = std::min<uint32_t>(m.n_map_tiles, kNumCUs * 8u);
+        m.flags = flags;
+        m.keys = reinterpret_cast<const uint32_t *>(nsi);
+        m.mask = mask;
+        m.cmask = cmask;
         const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(plan->n_tiles_all, kNumCUs * 4u) : 0u;
-        if (n_list_wgs + n_fb_wgs > 0)
-            hipLaunchKernelGGL(k_mark_map, dim3(n_list_wgs + n_fb_wgs), dim3(256), 0, stream, layers,
-                               reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir),
-                               static_cast<uint32_t>(L), plan->n_tiles_all,
-                               reinterpret_cast<const SampleEntry *>(ws + w.map_tiles), n_map_tiles,
-                               n_list_wgs, flags, state, reinterpret_cast<const uint32_t *>(nsi), mask, cmask);
+        const uint32_t n_wgs = m.n_cand_wgs + m.n_list_wgs + n_fb_wgs;
+        if (n_wgs > 0) hipLaunchKernelGGL(k_mark, dim3(n_wgs), dim3(256), 0, stream, m);
     }
     marks.close(5);
     hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, mask, cmask, chunk_cnt, chunk_ccnt);

@@ -29,7 +29,6 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->tile_dir.clear();
     plan->chunk_dir.clear();
     plan->all_tile_dir.clear();
-    plan->group_dir.clear();
     plan->samples.clear();
     plan->cand_groups.clear();
     plan->map_chunks.clear();
@@ -84,7 +83,6 @@ int build_tables(rsdgc_plan_s *plan) {
 
         plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(l)});
         plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(l)});
-        plan->group_dir.push_back(DirEntry{group_begin, static_cast<uint32_t>(l)});
         chunk_begin += d.n_chunks;
         tile_begin_all += d.n_tiles;
         group_begin += d.n_groups;
@@ -94,7 +92,6 @@ int build_tables(rsdgc_plan_s *plan) {
     }
     plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(L)});
     plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(L)});
-    plan->group_dir.push_back(DirEntry{group_begin, static_cast<uint32_t>(L)});
     plan->n_chunks = chunk_begin;
     plan->n_tiles_all = tile_begin_all;
     plan->n_slot_groups = group_begin;
@@ -107,9 +104,18 @@ int build_tables(rsdgc_plan_s *plan) {
     for (int l = 0; l < L; ++l) {
         const LayerDev &d = plan->layers[l];
         if (d.large) {
-            for (uint32_t g = 0; g < d.n_groups; ++g) plan->cand_groups.push_back(d.group_begin + g);
+            for (uint32_t g = 0; g < d.n_groups; ++g) {
+                const uint32_t t0 = g * kSlotGroup;
+                plan->cand_groups.push_back(GroupEntry{static_cast<uint32_t>(l), d.tile_begin_all + t0,
+                                                       std::min<uint32_t>(kSlotGroup, d.n_tiles - t0), 0u});
+            }
         } else if (d.k > 0) {
-            for (uint32_t c = 0; c < d.n_chunks; ++c) plan->map_chunks.push_back(d.chunk_begin + c);
+            for (uint32_t c = 0; c < d.n_chunks; ++c) {
+                const uint32_t start = c * kChunk;
+                plan->map_chunks.push_back(ChunkEntry{static_cast<uint32_t>(l), start,
+                                                      std::min<uint32_t>(kChunk, d.G - start), 0u,
+                                                      static_cast<uint64_t>(d.elem_off) + start});
+            }
             for (uint32_t t = 0; t < d.n_tiles; ++t)
                 plan->map_tiles.push_back(SampleEntry{static_cast<uint32_t>(l), t});
         }
@@ -151,12 +157,10 @@ int build_tables(rsdgc_plan_s *plan) {
     w.tile_dir = off;     off = align_up(off + sizeof(DirEntry) * (L + (RSDGC_MAX_P + 1) / 2), A);
     w.chunk_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + 1), A);
     w.all_tile_dir = off; off = align_up(off + sizeof(DirEntry) * (L + 1), A);
-    w.group_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + 1), A);
     w.samples = off;      off = align_up(off + sizeof(SampleEntry) * (max_samples + 1), A);
     w.chunk_layer = off;  off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
-    w.group_layer = off;  off = align_up(off + sizeof(uint32_t) * plan->n_slot_groups, A);
-    w.cand_groups = off;  off = align_up(off + sizeof(uint32_t) * plan->n_slot_groups, A);
-    w.map_chunks = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.cand_groups = off;  off = align_up(off + sizeof(GroupEntry) * plan->n_slot_groups, A);
+    w.map_chunks = off;   off = align_up(off + sizeof(ChunkEntry) * plan->n_chunks, A);
     w.map_tiles = off;    off = align_up(off + sizeof(SampleEntry) * (size_t(plan->n_tiles_all) + 1), A);
     w.table_bytes = off;
     w.state = off;        off = align_up(off + sizeof(SelState) * L, A);   // written in full each call
@@ -185,27 +189,21 @@ int build_tables(rsdgc_plan_s *plan) {
                 sizeof(DirEntry) * plan->chunk_dir.size());
     std::memcpy(plan->table.data() + w.all_tile_dir, plan->all_tile_dir.data(),
                 sizeof(DirEntry) * plan->all_tile_dir.size());
-    std::memcpy(plan->table.data() + w.group_dir, plan->group_dir.data(),
-                sizeof(DirEntry) * plan->group_dir.size());
     if (!plan->samples.empty())
         std::memcpy(plan->table.data() + w.samples, plan->samples.data(),
                     sizeof(SampleEntry) * plan->samples.size());
     {
         uint32_t *cl = reinterpret_cast<uint32_t *>(plan->table.data() + w.chunk_layer);
-        uint32_t *gl = reinterpret_cast<uint32_t *>(plan->table.data() + w.group_layer);
-        for (int l = 0; l < L; ++l) {
+        for (int l = 0; l < L; ++l)
             for (uint32_t c = 0; c < plan->layers[l].n_chunks; ++c)
                 cl[plan->layers[l].chunk_begin + c] = static_cast<uint32_t>(l);
-            for (uint32_t g = 0; g < plan->layers[l].n_groups; ++g)
-                gl[plan->layers[l].group_begin + g] = static_cast<uint32_t>(l);
-        }
     }
     if (!plan->cand_groups.empty())
         std::memcpy(plan->table.data() + w.cand_groups, plan->cand_groups.data(),
-                    sizeof(uint32_t) * plan->cand_groups.size());
+                    sizeof(GroupEntry) * plan->cand_groups.size());
     if (!plan->map_chunks.empty())
         std::memcpy(plan->table.data() + w.map_chunks, plan->map_chunks.data(),
-                    sizeof(uint32_t) * plan->map_chunks.size());
+                    sizeof(ChunkEntry) * plan->map_chunks.size());
     if (!plan->map_tiles.empty())
         std::memcpy(plan->table.data() + w.map_tiles, plan->map_tiles.data(),
                     sizeof(SampleEntry) * plan->map_tiles.size());

@@ -132,6 +132,25 @@ def test_config2_resnet50_dynamic_ratios(path):
     assert ex >= n - 2
 
 
+def test_large_layers_with_rows_that_are_not_whole_mask_words(in_place):
+    """Layers large enough for the candidate path whose row length is not a multiple of 32:
+    their tiles share mask words, so marking goes through atomics instead of tile-owned words.
+    A layer with C % 32 == 0 sits between them (tile-owned words)."""
+    shapes = [(700, 1100), (1000, 2570), (640, 1536), (2100, 333)]
+    p_list = [3, 5, 3, 7]
+    ratios = [0.02, 0.01, 0.03, 0.05]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 31, t, l) for l, sh in enumerate(shapes)]
+           for t in range(2)]
+    from paper_2312_17530_amd import binding
+    n, ex = run_and_check(shapes, p_list, 0.5, ratios, its, "large_unaligned", in_place=in_place)
+    assert n == 2 * len(shapes) and ex >= n - 1
+    sess = _session(shapes, 3, 0.5, ratios, p_list)
+    sess.set_grad(its[0])
+    sess.compress()
+    paths = binding.rsdgc_last_paths(sess.plan, sess.workspace)
+    assert [paths[0], paths[1], paths[3]] == [0, 0, 0], "expected the candidate path"
+
+
 def _tile_is_sampled(t):
     """The library samples one tile in 16 (layers below 4096 tiles) by this hash of the tile's
     index inside its layer."""
