@@ -32,8 +32,7 @@ METRIC = "gradient elements compressed/sec (full-model, 1 GPU) and % of HBM peak
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); the summaries are
 # in profiles/.  Keyed by (workload name, stage, residual update).  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("vgg19_45c", "emit", "in_place"): 1.717e9,      # profiles/hbm_traffic_vgg19.md
-    ("vgg19_45c", "capture", "in_place"): 1.2965e9,  # profiles/hbm_traffic_vgg19.md
+    ("vgg19_45c", "capture", "two_arenas"): 1.8972e9,   # profiles/hbm_traffic_vgg19.md, k_nsi<3, 2>
 }
 
 
