@@ -1,21 +1,25 @@
 // HIP kernels (gfx950, wave64) and the device-facing entry points of the C ABI.
 //
 // Pipeline of one rsdgc_compress call, all layers per launch:
-//   clear      zero histograms, bitmasks, counters; per-layer state
-//   sample     NSI (Eqs. 6-10) on one tile in 16 of the large layers -> score histogram
+//   clear      zero histograms, bitmasks, counters, flags; per-layer state
+//   first pass NSI (Eqs. 6-10) on one tile in 16 .. 64 of the large layers -> score histogram;
+//              in the same launch every tile of the other layers: v = r + g (Eq. 12), NSI
+//              map and exact 12-bit histogram
 //   hint       per large layer: a score bound with about 2 k_l centres expected above it
-//   capture    v = r + g (Eq. 12) and NSI for every element of the large layers; centres whose
-//              score reaches the bound are recorded per tile (no score map, no histogram)
+//   capture    v = r + g and NSI for every element of the large layers; centres whose score
+//              reaches the bound are recorded per tile (no score map); with a second
+//              residual arena v is stored there as it is formed
 //   validate   a layer whose bound caught fewer than k_l centres, or overfilled a tile,
-//              falls back to the full map
-//   full map   small layers and fall-backs: NSI map + 12-bit histogram over every element
-//   find/refine radix select of the k_l-th largest composite key per layer (Algorithm 1's
-//              ranking; Eq. 11's k_l), most significant digit first, over the recorded
-//              candidates or over the map
+//              falls back to the full map (a flag tells the fallback kernels there is work)
+//   select     radix select of the k_l-th largest composite key per layer (Algorithm 1's
+//              ranking; Eq. 11's k_l), most significant digit first: find, gather the
+//              threshold bucket, find, filter, finish
 //   mark       selected centres set the bits of their p x p window (Section III-C: whole
 //              neighbourhoods are kept)
 //   count/scan kept elements per chunk and their prefix sums
-//   emit       ordered (index, value) pairs and the residual update (Eq. 12)
+//   emit       ordered (index, value) pairs and the residual update (Eq. 12): either only the
+//              kept elements are touched (second arena), or g and r are streamed again
+//              (update in place)
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
