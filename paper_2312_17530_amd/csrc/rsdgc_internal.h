@@ -104,6 +104,18 @@ struct ChunkEntry {
     uint64_t arena_off;  // elem_off + start
 };
 
+// Everything the 1-D passes need to know about one 8192-element chunk (one load instead of a
+// chain chunk -> layer -> layer table).
+struct ChunkInfo {
+    uint64_t arena_off;  // elem_off + start
+    uint64_t out_off;    // first pair of the chunk's layer in out_idx / out_val
+    uint32_t layer;
+    uint32_t start;      // first element of the chunk inside the layer
+    uint32_t len;        // elements in the chunk
+    uint32_t cap;        // capacity of the layer's output segment
+};
+static_assert(sizeof(ChunkInfo) == 32, "ChunkInfo layout");
+
 // Byte offsets of the workspace sections (all multiples of 256).
 struct WsLayout {
     // uploaded tables
@@ -113,6 +125,7 @@ struct WsLayout {
     size_t all_tile_dir = 0; // DirEntry[n_layers + 1]: tiles of all layers in layer order
     size_t samples = 0;      // SampleEntry[] per p-group
     size_t chunk_layer = 0;  // uint32[n_chunks]: layer of every 8192-element chunk
+    size_t chunk_info = 0;   // ChunkInfo[n_chunks]
     size_t cand_groups = 0;  // GroupEntry[]: slot groups of the large layers (work list of the candidate passes)
     size_t map_chunks = 0;   // ChunkEntry[]: chunks of the other layers that select something
     size_t map_tiles = 0;    // SampleEntry[]: tiles of those layers

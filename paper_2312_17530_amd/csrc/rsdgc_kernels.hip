@@ -1210,8 +1210,7 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
 }
 
 // ---------------------------------------------------------------- count --
-__global__ __launch_bounds__(256) void k_count(const LayerDev *__restrict__ layers,
-                                               const uint32_t *__restrict__ chunk_layer,
+__global__ __launch_bounds__(256) void k_count(const ChunkInfo *__restrict__ chunk_info,
                                                const uint32_t *__restrict__ mask,
                                                const uint32_t *__restrict__ cmask,
                                                uint32_t *__restrict__ chunk_cnt,
@@ -1219,12 +1218,9 @@ __global__ __launch_bounds__(256) void k_count(const LayerDev *__restrict__ laye
     __shared__ uint32_t wave_tot[4];
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_layer[c];
-    const LayerDev L = layers[l];
-    const uint32_t start = (c - L.chunk_begin) * kChunk;
-    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-    const size_t w0 = (static_cast<size_t>(L.elem_off) + start) >> 5;
-    const uint32_t nwords = (len + 31) >> 5;
+    const ChunkInfo ci = chunk_info[c];
+    const size_t w0 = ci.arena_off >> 5;
+    const uint32_t nwords = (ci.len + 31) >> 5;
     const uint32_t a = static_cast<uint32_t>(tid) < nwords ? __popc(mask[w0 + tid]) : 0;
     const uint32_t sa = block_scan_incl(a, wave_tot);
     if (tid == 255) chunk_cnt[c] = sa;
@@ -1389,8 +1385,7 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
 // residual arena, so only the kept elements are touched -- their value goes out and the
 // arena gets +0 there.  A chunk without kept elements costs one read of its mask words.  A
 // layer with k_l = 0 went through no NSI pass; its v is formed here.
-__global__ __launch_bounds__(256) void k_emit_sparse(const LayerDev *__restrict__ layers,
-                                                     const uint32_t *__restrict__ chunk_layer,
+__global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict__ chunk_info,
                                                      const SelState *__restrict__ state,
                                                      const float *__restrict__ grad,
                                                      const float *__restrict__ resid_in,
@@ -1404,13 +1399,15 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const LayerDev *__restrict_
     __shared__ uint32_t s_total;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_layer[c];
-    const LayerDev L = layers[l];
-    const uint32_t start = (c - L.chunk_begin) * kChunk;
-    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-    const size_t base = static_cast<size_t>(L.elem_off) + start;
+    const ChunkInfo ci = chunk_info[c];
+    const uint32_t start = ci.start, len = ci.len;
+    const size_t base = ci.arena_off;
     float *__restrict__ v = v_arena + base;
-    if (state[l].mode == kModeSkip) {
+    // the three loads that depend only on the chunk's entry go out together
+    const uint32_t nwords = (len + 31) >> 5;
+    uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(base >> 5) + tid] : 0;
+    const uint32_t cbase = chunk_base[c];
+    if (state[ci.layer].mode == kModeSkip) {
         const float *__restrict__ g = grad + base;
         const float *__restrict__ r = resid_in + base;
         for (uint32_t e = 4 * tid; e < len; e += 1024) {
@@ -1424,8 +1421,6 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const LayerDev *__restrict_
         }
         return;
     }
-    const uint32_t nwords = (len + 31) >> 5;
-    uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(base >> 5) + tid] : 0;
     if (!__syncthreads_or(word != 0u)) return;
     const uint32_t cnt = __popc(word);
     const uint32_t incl = block_scan_incl(cnt, wave_tot);
@@ -1439,9 +1434,8 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const LayerDev *__restrict_
     if (tid == 255) s_total = incl;
     __syncthreads();
     const uint32_t total = s_total;
-    const uint32_t cbase = chunk_base[c];
-    const size_t obase = static_cast<size_t>(L.out_off) + cbase;
-    const uint32_t room = L.cap > cbase ? L.cap - cbase : 0u;   // never write past the segment
+    const size_t obase = static_cast<size_t>(ci.out_off) + cbase;
+    const uint32_t room = ci.cap > cbase ? ci.cap - cbase : 0u;   // never write past the segment
     // one kept element per thread: independent loads, coalesced pair stores
     for (uint32_t i = tid; i < total; i += 256) {
         const uint32_t e = s_list[i];
@@ -1756,7 +1750,8 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
         if (n_wgs > 0) hipLaunchKernelGGL(k_mark, dim3(n_wgs), dim3(256), 0, stream, m);
     }
     marks.close(5);
-    hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, mask, cmask, chunk_cnt, chunk_ccnt);
+    const ChunkInfo *chunk_info = reinterpret_cast<const ChunkInfo *>(ws + w.chunk_info);
+    hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, chunk_info, mask, cmask, chunk_cnt, chunk_ccnt);
     hipLaunchKernelGGL(k_scan, dim3(L), dim3(kScanThreads), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
                        out_counts, out_centre_counts, cmask ? 1 : 0);
     marks.close(6);
@@ -1764,8 +1759,8 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
         hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, grad,
                            residual_out, mask, chunk_cnt, out_idx, out_val);
     else
-        hipLaunchKernelGGL(k_emit_sparse, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, state,
-                           grad, residual, residual_out, mask, chunk_cnt, out_idx, out_val);
+        hipLaunchKernelGGL(k_emit_sparse, dim3(n_chunks), dim3(256), 0, stream, chunk_info, state, grad,
+                           residual, residual_out, mask, chunk_cnt, out_idx, out_val);
     marks.close(7);
     if (out_centre_idx)
         hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer,

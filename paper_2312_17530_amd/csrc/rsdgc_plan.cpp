@@ -159,6 +159,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.all_tile_dir = off; off = align_up(off + sizeof(DirEntry) * (L + 1), A);
     w.samples = off;      off = align_up(off + sizeof(SampleEntry) * (max_samples + 1), A);
     w.chunk_layer = off;  off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.chunk_info = off;   off = align_up(off + sizeof(ChunkInfo) * plan->n_chunks, A);
     w.cand_groups = off;  off = align_up(off + sizeof(GroupEntry) * plan->n_slot_groups, A);
     w.map_chunks = off;   off = align_up(off + sizeof(ChunkEntry) * plan->n_chunks, A);
     w.map_tiles = off;    off = align_up(off + sizeof(SampleEntry) * (size_t(plan->n_tiles_all) + 1), A);
@@ -194,9 +195,17 @@ int build_tables(rsdgc_plan_s *plan) {
                     sizeof(SampleEntry) * plan->samples.size());
     {
         uint32_t *cl = reinterpret_cast<uint32_t *>(plan->table.data() + w.chunk_layer);
-        for (int l = 0; l < L; ++l)
-            for (uint32_t c = 0; c < plan->layers[l].n_chunks; ++c)
-                cl[plan->layers[l].chunk_begin + c] = static_cast<uint32_t>(l);
+        ChunkInfo *ci = reinterpret_cast<ChunkInfo *>(plan->table.data() + w.chunk_info);
+        for (int l = 0; l < L; ++l) {
+            const LayerDev &d = plan->layers[l];
+            for (uint32_t c = 0; c < d.n_chunks; ++c) {
+                cl[d.chunk_begin + c] = static_cast<uint32_t>(l);
+                const uint32_t start = c * kChunk;
+                ci[d.chunk_begin + c] = ChunkInfo{static_cast<uint64_t>(d.elem_off) + start,
+                                                  static_cast<uint64_t>(d.out_off), static_cast<uint32_t>(l),
+                                                  start, std::min<uint32_t>(kChunk, d.G - start), d.cap};
+            }
+        }
     }
     if (!plan->cand_groups.empty())
         std::memcpy(plan->table.data() + w.cand_groups, plan->cand_groups.data(),
