@@ -32,7 +32,13 @@ METRIC = "gradient elements compressed/sec (full-model, 1 GPU) and % of HBM peak
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); the summaries are
 # in profiles/.  Keyed by (workload name, stage, residual update).  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("vgg19_45c", "capture", "two_arenas"): 1.8972e9,   # profiles/hbm_traffic_vgg19.md, k_nsi<3, 2>
+    ("vgg19_45c", "capture", "two_arenas"): 1.8972e9,          # profiles/hbm_traffic_vgg19.md, k_nsi<3, 2>
+    ("fc6_25088x4096_t3", "capture", "two_arenas"): 1.4263e9,  # profiles/hbm_traffic_fc6_p5.md, k_nsi<5, 2>
+}
+# the same counters summed over all kernels of one rsdgc_compress call
+MEASURED_PATH_TRAFFIC_BYTES = {
+    ("vgg19_45c", "two_arenas"): 2.3559e9,
+    ("fc6_25088x4096_t3", "two_arenas"): 1.4943e9,
 }
 
 
@@ -173,6 +179,9 @@ def main() -> int:
                     "elements_on_candidate_path": n_cand,
                     "path_algorithmic_bytes": 12.0 * G + 8.0 * n_pairs,
                     "path_frac": (12.0 * G + 8.0 * n_pairs) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS}
+        path_traffic = MEASURED_PATH_TRAFFIC_BYTES.get((w.name, "in_place" if args.in_place else "two_arenas"))
+        roofline["path_traffic"] = path_traffic      # counted bytes of all kernels of one call (None = not measured)
+        roofline["path_moved_frac"] = (path_traffic / (dt / args.steps) / 1e9 / HBM_PEAK_GBS) if path_traffic else None
 
     out = {
         "metric": METRIC, "value": value, "unit": "elements/s", "n_gpus": 1, "steps": args.steps,
