@@ -154,6 +154,20 @@ def main() -> int:
         dt_events = time.perf_counter() - t1
         stages, n_rec = binding.rsdgc_profile_end(sess.plan)
 
+    # the inverse (Eq. 12, third line), outside the timed region: dense[idx] = val over a cleared
+    # arena, and dense[idx] += val (one call per peer message when several ranks' outputs are summed)
+    dense = torch.zeros_like(sess.grad)
+    decompress_ms = {}
+    for name, acc in (("overwrite", False), ("accumulate", True)):
+        sess.decompress(accumulate=acc, dense=dense)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(20):
+            sess.decompress(accumulate=acc, dense=dense)
+        torch.cuda.synchronize()
+        decompress_ms[name] = (time.perf_counter() - t2) / 20 * 1e3
+    del dense
+
     ms_per_step = dt / args.steps * 1e3
     value = G * args.steps / dt
     counts = sess.out_counts.cpu().numpy()
@@ -195,6 +209,7 @@ def main() -> int:
                    "residual_update": "in_place" if args.in_place else "two_arenas"},
         "roofline": roofline,
         "stages_ms": {k: round(v, 5) for k, v in stages.items()},
+        "decompress_ms": {k: round(v, 5) for k, v in decompress_ms.items()},
         "stages_recorded_calls": n_rec,
         "ms_per_step_with_stage_events": (dt_events / args.steps * 1e3) if dt_events else None,
     }
