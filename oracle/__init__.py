@@ -66,6 +66,15 @@ def _load():
     lib.rsdgc_oracle_compress_layer.argtypes = [fp, fp, i64, i64, c_int, f64, f64,
                                                 u32p, fp, u32p, i64p, fp, fp, fp]
     lib.rsdgc_oracle_compress_layer.restype = i64
+    c_float = ctypes.c_float
+    lib.rsdgc_oracle_momentum.argtypes = [fp, fp, fp, c_float, fp, fp, i64]
+    lib.rsdgc_oracle_momentum.restype = None
+    lib.rsdgc_oracle_mask_momentum.argtypes = [fp, u8p, i64, fp]
+    lib.rsdgc_oracle_mask_momentum.restype = None
+    lib.rsdgc_oracle_compress_layer_momentum.argtypes = [fp, fp, fp, c_float, i64, i64, c_int, f64, f64,
+                                                         u32p, fp, u32p, ctypes.POINTER(i64),
+                                                         ctypes.POINTER(c_float), fp, fp]
+    lib.rsdgc_oracle_compress_layer_momentum.restype = i64
     _lib = lib
     return lib
 
@@ -220,6 +229,64 @@ def compress_layer(g, r, p: int, alpha: float, rho: float) -> LayerResult:
     assert k_out.value == k
     return LayerResult(idx[:n].copy(), val[:n].copy(), centres[:k].copy(), k,
                        float(tau.value) if k > 0 else None, nsi_map, v, r_new)
+
+
+def momentum_accumulate(u, g, r, m: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 12, lines 1-2: (u_new, v) with u_new = m*u + g and v = r + u_new, in float32."""
+    u, g, r = _f32(u), _f32(g), _f32(r)
+    assert u.shape == g.shape == r.shape
+    u_new = np.empty_like(g)
+    v = np.empty_like(g)
+    _load().rsdgc_oracle_momentum(_p(u, ctypes.c_float), _p(g, ctypes.c_float), _p(r, ctypes.c_float),
+                                  float(m), _p(u_new, ctypes.c_float), _p(v, ctypes.c_float), g.size)
+    return u_new, v
+
+
+def mask_momentum(u_new, mask) -> np.ndarray:
+    """Momentum restarts from +0 where the accumulated gradient was sent."""
+    u_new = _f32(u_new)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    assert mask.size == u_new.size
+    out = np.empty_like(u_new)
+    _load().rsdgc_oracle_mask_momentum(_p(u_new, ctypes.c_float), _p(mask, ctypes.c_uint8), u_new.size,
+                                       _p(out, ctypes.c_float))
+    return out
+
+
+class MomentumLayerResult(NamedTuple):
+    layer: LayerResult    # as compress_layer (v is the momentum-corrected accumulation)
+    u_new: np.ndarray     # float32 R x C, momentum after masking
+
+
+def compress_layer_momentum(g, u, r, m: float, p: int, alpha: float, rho: float) -> MomentumLayerResult:
+    """Steps 1m, 2-7 for one layer (Eq. 12 in full).  g, u, r: R x C float32; none is modified."""
+    _check_p(p)
+    g = _f32(g)
+    u_new = _f32(u).copy()
+    r_new = _f32(r).copy()
+    assert g.ndim == 2 and g.shape == r_new.shape == u_new.shape
+    R, C = g.shape
+    G = R * C
+    k = keep_count(G, p, rho)
+    cap = min(k * p * p, G)
+    idx = np.empty(max(cap, 1), dtype=np.uint32)
+    val = np.empty(max(cap, 1), dtype=np.float32)
+    centres = np.empty(max(k, 1), dtype=np.uint32)
+    k_out = ctypes.c_int64(0)
+    tau = ctypes.c_float(0.0)
+    nsi_map = np.empty((R, C), dtype=np.float32)
+    v = np.empty((R, C), dtype=np.float32)
+    n = _load().rsdgc_oracle_compress_layer_momentum(
+        _p(g, ctypes.c_float), _p(u_new, ctypes.c_float), _p(r_new, ctypes.c_float), float(m), R, C, p,
+        float(alpha), float(rho), _p(idx, ctypes.c_uint32), _p(val, ctypes.c_float),
+        _p(centres, ctypes.c_uint32), ctypes.byref(k_out), ctypes.byref(tau),
+        _p(nsi_map, ctypes.c_float), _p(v, ctypes.c_float))
+    if n < 0:
+        raise MemoryError("oracle ran out of memory")
+    assert k_out.value == k
+    return MomentumLayerResult(
+        LayerResult(idx[:n].copy(), val[:n].copy(), centres[:k].copy(), k,
+                    float(tau.value) if k > 0 else None, nsi_map, v, r_new), u_new)
 
 
 def compress_model(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray], p: int,

@@ -17,6 +17,11 @@
  *   step 7  residual = what was not sent   Eq. 12 (v accumulates the unsent part)
  *   step 8  decompress (scatter)           Eq. 12, third line (sum of sparse(v))
  *
+ * With momentum correction (Eq. 12 in full) step 1 becomes
+ *   step 1m u = m*u + g,  v = r + u        Eq. 12, first and second line
+ * and step 7 also restarts u from zero where v was sent (the masking of the
+ * method Eq. 12 is taken from).
+ *
  * Readings taken where the paper is silent (each is also a parameter or a
  * documented convention of the GPU library):
  *   - every element is the centre of one neighbourhood (stride-1 window);
@@ -44,6 +49,21 @@ void rsdgc_oracle_accumulate(const float *r, const float *g, float *v, int64_t n
 {
     for (int64_t i = 0; i < n; ++i) {
         volatile float s = r[i] + g[i];
+        v[i] = s;
+    }
+}
+
+/* --------------------------------------------------------------- step 1m */
+/* Eq. 12, lines 1 and 2: u_new = m*u + g (one binary32 multiply, one
+ * binary32 add), v = r + u_new (one binary32 add).                         */
+void rsdgc_oracle_momentum(const float *u, const float *g, const float *r, float m,
+                           float *u_new, float *v, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float mu = m * u[i];
+        volatile float un = mu + g[i];
+        volatile float s = r[i] + un;
+        u_new[i] = un;
         v[i] = s;
     }
 }
@@ -200,6 +220,14 @@ void rsdgc_oracle_residual(const float *v, const uint8_t *mask, int64_t G,
         r_new[i] = mask[i] ? 0.0f : v[i];
 }
 
+/* Momentum masking: where v was sent the momentum restarts from +0.         */
+void rsdgc_oracle_mask_momentum(const float *u_new, const uint8_t *mask, int64_t G,
+                                float *u_out)
+{
+    for (int64_t i = 0; i < G; ++i)
+        u_out[i] = mask[i] ? 0.0f : u_new[i];
+}
+
 /* ---------------------------------------------------------------- step 8 */
 /* accumulate == 0: dense = 0 then dense[idx] = val;
  * accumulate != 0: dense[idx] += val (one binary32 add).                   */
@@ -254,5 +282,42 @@ int64_t rsdgc_oracle_compress_layer(const float *g, float *r, int64_t R, int64_t
     if (nsi_out) memcpy(nsi_out, nsi, (size_t)G * sizeof(float));
     if (v_out) memcpy(v_out, v, (size_t)G * sizeof(float));
     free(v); free(nsi); free(mask);
+    return n;
+}
+
+/* The same with momentum correction: steps 1m, 2-7; u and r are updated in
+ * place (u: m*u + g, then +0 where sent; r: as above).                      */
+int64_t rsdgc_oracle_compress_layer_momentum(const float *g, float *u, float *r, float m,
+                                             int64_t R, int64_t C, int p, double alpha,
+                                             double rho, uint32_t *idx, float *val,
+                                             uint32_t *centres, int64_t *k_out,
+                                             float *tau_out, float *nsi_out, float *v_out)
+{
+    const int64_t G = R * C;
+    float *v = (float *)malloc((size_t)G * sizeof(float));
+    float *un = (float *)malloc((size_t)G * sizeof(float));
+    float *nsi = (float *)malloc((size_t)G * sizeof(float));
+    uint8_t *mask = (uint8_t *)malloc((size_t)G);
+    if (!v || !un || !nsi || !mask) {
+        free(v); free(un); free(nsi); free(mask);
+        return -1;
+    }
+    rsdgc_oracle_momentum(u, g, r, m, un, v, G);              /* step 1m */
+    rsdgc_oracle_nsi(v, R, C, p, alpha, nsi);                 /* step 2 */
+    const int64_t k = rsdgc_oracle_k(G, p, rho);              /* step 3 */
+    float tau = 0.0f;
+    if (rsdgc_oracle_select(nsi, G, k, centres, &tau) != 0) { /* step 4 */
+        free(v); free(un); free(nsi); free(mask);
+        return -1;
+    }
+    rsdgc_oracle_dilate(centres, k, R, C, p, mask);           /* step 5 */
+    const int64_t n = rsdgc_oracle_emit(v, mask, G, idx, val);/* step 6 */
+    rsdgc_oracle_residual(v, mask, G, r);                     /* step 7 */
+    rsdgc_oracle_mask_momentum(un, mask, G, u);               /* step 7, momentum */
+    if (k_out) *k_out = k;
+    if (tau_out) *tau_out = tau;
+    if (nsi_out) memcpy(nsi_out, nsi, (size_t)G * sizeof(float));
+    if (v_out) memcpy(v_out, v, (size_t)G * sizeof(float));
+    free(v); free(un); free(nsi); free(mask);
     return n;
 }

@@ -102,6 +102,20 @@ def battery(orc):
     b = brute_compress(gg.tolist(), rr.tolist(), 3, 0.5, 0.3)
     check("brute", res.k == b["k"] and res.centres.tolist() == b["centres"] and res.idx.tolist() == b["idx"]
           and res.r_new.ravel().tolist() == b["r_new"])
+    # Eq. 12 in full: momentum, then the same steps; masking of the momentum
+    uu = (rng.standard_normal((13, 17)) * 1e-2).astype(np.float32)
+    mm = np.float32(0.9)
+    un = mm * uu + gg
+    mres = orc.compress_layer_momentum(gg, uu, rr, 0.9, 3, 0.5, 0.3)
+    check("momentum_v", np.array_equal(mres.layer.v, rr + un))
+    sent = np.zeros(gg.size, bool)
+    sent[mres.layer.idx] = True
+    want_u = un.ravel().copy()
+    want_u[sent] = 0.0
+    check("momentum_masked", np.array_equal(mres.u_new.ravel(), want_u))
+    plain = orc.compress_layer(un, rr, 3, 0.5, 0.3)
+    check("momentum_selection", np.array_equal(plain.idx, mres.layer.idx)
+          and np.array_equal(plain.r_new, mres.layer.r_new))
     d2 = np.ones(10, np.float32)
     orc.decompress(np.array([2, 5], np.uint32), np.array([0.5, -1.0], np.float32), 10, dense=d2, accumulate_into=True)
     check("decompress_acc", d2.tolist() == [1, 1, 1.5, 1, 1, 0, 1, 1, 1, 1])
@@ -132,6 +146,12 @@ MUTANTS = [
     ("emit_abs_value", "val[n] = v[i];", "val[n] = fabsf(v[i]);", 0),
     ("accumulate_subtracts", "volatile float s = r[i] + g[i];", "volatile float s = r[i] - g[i];", 0),
     ("decompress_overwrites", "volatile float s = dense[idx[j]] + val[j];", "volatile float s = val[j];", 0),
+    ("momentum_scales_gradient", "volatile float mu = m * u[i];", "volatile float mu = m * g[i];", 0),
+    ("momentum_not_added_to_v", "volatile float s = r[i] + un;", "volatile float s = r[i] + g[i];", 0),
+    ("momentum_fused", "volatile float mu = m * u[i];\n        volatile float un = mu + g[i];",
+     "volatile float mu = m * u[i];\n        volatile float un = (float)((double)m * (double)u[i] + (double)g[i]);", 0),
+    ("momentum_not_masked", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = u_new[i];", 0),
+    ("momentum_masked_where_kept_out", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = mask[i] ? u_new[i] : 0.0f;", 0),
 ]
 
 

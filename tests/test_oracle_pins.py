@@ -345,3 +345,79 @@ def test_oracle_against_pure_python_brute_force(R, C, p, alpha, rho, seed):
             assert o.tau == b["tau"]
     else:  # pragma: no cover - only if the two double evaluations round differently
         pytest.skip("score rounding differed between C and Python doubles")
+
+
+# ------------------------------------------------- momentum correction (Eq. 12 in full)
+def test_momentum_is_one_rounded_multiply_then_one_rounded_add():
+    rng = np.random.default_rng(21)
+    u = rng.standard_normal(20000).astype(np.float32)
+    g = rng.standard_normal(20000).astype(np.float32)
+    r = rng.standard_normal(20000).astype(np.float32)
+    m = np.float32(0.9)
+    u_new, v = oracle.momentum_accumulate(u, g, r, 0.9)
+    assert np.array_equal(u_new, m * u + g)                  # numpy rounds the product, then the sum
+    assert np.array_equal(v, r + u_new)
+    fused = (np.float64(m) * u.astype(np.float64) + g.astype(np.float64)).astype(np.float32)
+    assert np.any(fused != u_new), "the inputs must tell a fused multiply-add from two roundings"
+
+
+def test_momentum_closed_form_constant_gradient_nothing_sent():
+    # g = 1, m = 1/2, rho = 0: u_t = 2 - 2^(1-t), v_t = sum of u; every value is exact in float32
+    g = np.ones((6, 7), dtype=np.float32)
+    u = np.zeros_like(g)
+    r = np.zeros_like(g)
+    want_u, want_v = 0.0, 0.0
+    for t in range(1, 12):
+        res = oracle.compress_layer_momentum(g, u, r, 0.5, 3, 0.5, 0.0)
+        want_u = 0.5 * want_u + 1.0
+        want_v += want_u
+        assert want_u == 2.0 - 2.0 ** (1 - t)
+        assert len(res.layer.idx) == 0
+        assert np.all(res.u_new == np.float32(want_u)) and np.all(res.layer.r_new == np.float32(want_v))
+        u, r = res.u_new, res.layer.r_new
+
+
+def test_momentum_zero_is_the_plain_path_and_selection_runs_on_r_plus_u():
+    rng = np.random.default_rng(22)
+    g = (rng.standard_normal((19, 23)) * 1e-2).astype(np.float32)
+    u = (rng.standard_normal((19, 23)) * 1e-2).astype(np.float32)
+    r = (rng.standard_normal((19, 23)) * 1e-2).astype(np.float32)
+    a = oracle.compress_layer_momentum(g, u, r, 0.0, 3, 0.5, 0.2).layer
+    b = oracle.compress_layer(g, r, 3, 0.5, 0.2)
+    for x, y in zip(a[:3] + (a.nsi, a.v, a.r_new), b[:3] + (b.nsi, b.v, b.r_new)):
+        assert np.array_equal(x, y)
+    # general m: the same as the plain path fed with u_new = m*u + g (formed here in numpy)
+    m = np.float32(0.9)
+    un = m * u + g
+    c = oracle.compress_layer_momentum(g, u, r, 0.9, 3, 0.5, 0.2)
+    d = oracle.compress_layer(un, r, 3, 0.5, 0.2)
+    assert np.array_equal(c.layer.idx, d.idx) and np.array_equal(c.layer.val, d.val)
+    assert np.array_equal(c.layer.centres, d.centres) and np.array_equal(c.layer.r_new, d.r_new)
+    # masking: momentum and residual restart from +0 exactly where something was sent
+    sent = np.zeros(g.size, dtype=bool)
+    sent[c.layer.idx] = True
+    want_u = un.ravel().copy()
+    want_u[sent] = 0.0
+    assert np.array_equal(c.u_new.ravel().view(np.uint32), want_u.view(np.uint32))
+    assert np.array_equal(oracle.mask_momentum(un, sent).ravel(), want_u)
+    dense = oracle.decompress(c.layer.idx, c.layer.val, g.size)
+    assert np.array_equal(dense + c.layer.r_new.ravel(), c.layer.v.ravel())
+
+
+def test_momentum_against_pure_python_brute_force():
+    rng = np.random.default_rng(23)
+    for R, C, p, rho in ((9, 11, 3, 0.3), (7, 16, 5, 0.5)):
+        g = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        u = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        r = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        m = np.float32(0.9)
+        un = [[float(np.float32(np.float32(m * np.float32(u[x, y])) + np.float32(g[x, y]))) for y in range(C)]
+              for x in range(R)]
+        b = brute_compress(un, r.tolist(), p, 0.5, rho)        # Eq. 12: v = r + u_new
+        o = oracle.compress_layer_momentum(g, u, r, 0.9, p, 0.5, rho)
+        assert o.layer.v.ravel().tolist() == b["v"]
+        if np.array_equal(o.layer.nsi.ravel(), np.array(b["nsi"], dtype=np.float32)):
+            assert o.layer.idx.tolist() == b["idx"] and o.layer.r_new.ravel().tolist() == b["r_new"]
+            kept = set(b["idx"])
+            flat = [x for row in un for x in row]
+            assert o.u_new.ravel().tolist() == [0.0 if i in kept else flat[i] for i in range(R * C)]
