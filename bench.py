@@ -43,11 +43,13 @@ MEASURED_PATH_TRAFFIC_BYTES = {
 
 
 def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems: int,
-                            in_place: bool) -> float:
+                            in_place: bool, momentum: bool = False) -> float:
     """Bytes a stage has to move by its own contract (float32 data).  With two residual
     arenas the NSI passes also store v = r + g (4 more bytes per element) and the emit only
     touches the kept elements; in place the emit streams g and r again and rewrites r."""
     v_store = 0.0 if in_place else 4.0
+    if momentum:              # Eq. 12 in full: read u as well, write the new u beside v
+        v_store += 8.0
     if stage == "capture":    # read g, read r of the candidate-mode layers (candidates are < 1 %)
         return (8.0 + v_store) * n_cand_elems
     if stage == "first_pass":  # read g, read r, write the score map of the layers ranked on the full map
@@ -55,7 +57,7 @@ def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems
     if stage == "emit":
         if in_place:          # read g, read r, write r, write (index, value) pairs
             return 12.0 * n_elems + 8.0 * n_pairs
-        return n_elems / 8.0 + 16.0 * n_pairs   # mask bits; per pair: read v, write +0, index, value
+        return n_elems / 8.0 + (20.0 if momentum else 16.0) * n_pairs   # mask bits; per pair: read v, write +0 (also to u), index, value
     return 0.0
 
 
@@ -95,6 +97,9 @@ def main() -> int:
     ap.add_argument("--in-place", action="store_true",
                     help="update the residual in its own arena (one more streaming pass) instead of "
                          "writing the new residual to a second arena")
+    ap.add_argument("--momentum", type=float, default=None,
+                    help="momentum correction (Eq. 12 in full) with this factor: rsdgc_compress_momentum, "
+                         "20 bytes per element instead of 12")
     ap.add_argument("--full-map", action="store_true",
                     help="force the full-score-map ranking path for every layer")
     args = ap.parse_args()
@@ -116,7 +121,7 @@ def main() -> int:
     grads = synth.gradients(w, 0)
     sess = Session(w.shapes, w.p, w.alpha, w.ratios, want_centres=args.centres,
                    path=binding.RSDGC_PATH_FULL_MAP if args.full_map else binding.RSDGC_PATH_AUTO,
-                   in_place=args.in_place)
+                   in_place=args.in_place, momentum=args.momentum)
     sess.set_grad(grads)
     G = w.total_elems
     stream = torch.cuda.current_stream()
@@ -184,16 +189,20 @@ def main() -> int:
         n_cand = sum(r * c for (r, c), pth in zip(w.shapes, paths) if pth == 0)
         dom = max(("first_pass", "capture", "emit"), key=lambda s: stages.get(s, 0.0))
         dur_s = stages[dom] * 1e-3
-        alg = stage_algorithmic_bytes(dom, G, n_pairs, n_cand, args.in_place)
+        alg = stage_algorithmic_bytes(dom, G, n_pairs, n_cand, args.in_place, args.momentum is not None)
+        per_elem = 20.0 if args.momentum is not None else 12.0     # whole path: read g, (u,) r; write (u,) r
         achieved = alg / dur_s / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom, "in_place" if args.in_place else "two_arenas")),
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(
+                        (w.name, dom, "in_place" if args.in_place else
+                         "momentum" if args.momentum is not None else "two_arenas")),
                     "algorithmic_bytes": alg, "avg_ms": stages[dom],
                     "elements_on_candidate_path": n_cand,
-                    "path_algorithmic_bytes": 12.0 * G + 8.0 * n_pairs,
-                    "path_frac": (12.0 * G + 8.0 * n_pairs) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS}
-        path_traffic = MEASURED_PATH_TRAFFIC_BYTES.get((w.name, "in_place" if args.in_place else "two_arenas"))
+                    "path_algorithmic_bytes": per_elem * G + 8.0 * n_pairs,
+                    "path_frac": (per_elem * G + 8.0 * n_pairs) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS}
+        variant = "in_place" if args.in_place else "momentum" if args.momentum is not None else "two_arenas"
+        path_traffic = MEASURED_PATH_TRAFFIC_BYTES.get((w.name, variant))
         roofline["path_traffic"] = path_traffic      # counted bytes of all kernels of one call (None = not measured)
         roofline["path_moved_frac"] = (path_traffic / (dt / args.steps) / 1e9 / HBM_PEAK_GBS) if path_traffic else None
 
@@ -206,7 +215,8 @@ def main() -> int:
                    "pairs_emitted_last_step": n_pairs, "centre_lists": bool(args.centres),
                    "ranking_path": "full_map" if args.full_map else "auto",
                    "residual": "carried across steps",
-                   "residual_update": "in_place" if args.in_place else "two_arenas"},
+                   "residual_update": "in_place" if args.in_place else "two_arenas",
+                   "momentum": args.momentum},
         "roofline": roofline,
         "stages_ms": {k: round(v, 5) for k, v in stages.items()},
         "decompress_ms": {k: round(v, 5) for k, v in decompress_ms.items()},

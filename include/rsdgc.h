@@ -139,6 +139,24 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
                    uint32_t *out_centre_idx, int32_t *out_centre_counts,
                    void *workspace, void *stream);
 
+/* The same iteration with momentum correction (Eq. 12 in full; Section III-C's last
+ * paragraph adopts it):  u = m*u + g  (one float32 multiply, one float32 add),
+ * v = r + u, then everything as in rsdgc_compress on that v.  Where v was
+ * emitted the momentum restarts from +0 together with the residual (the masking
+ * of the method Eq. 12 is taken from).
+ *   momentum      [device, const] float32 arena: u of the previous iteration
+ *                 (all zeros before the first).
+ *   momentum_out  [device] float32 arena that receives the new u.
+ *   m             momentum factor in [0, 1]; m = 0 gives rsdgc_compress's result.
+ * grad, momentum, residual, momentum_out and residual_out must be five arenas that
+ * do not overlap (there is no in-place form); anything else is RSDGC_EINVAL.
+ * All other arguments as for rsdgc_compress.  HBM traffic: 20 bytes per element.  */
+int rsdgc_compress_momentum(rsdgc_plan_t *plan, const float *grad, const float *momentum,
+                            float *momentum_out, float m, const float *residual,
+                            float *residual_out, uint32_t *out_idx, float *out_val,
+                            int32_t *out_counts, uint32_t *out_centre_idx,
+                            int32_t *out_centre_counts, void *workspace, void *stream);
+
 /* NSI map only (Eqs. 8-10 at every element of every layer), for inspection:
  *   residual [device, nullable] NULL means an all-zero residual.
  *   nsi_out  [device] float32 arena; padding elements are not written.

@@ -21,7 +21,7 @@ EXPORTS = [
     "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
-    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_nsi", "rsdgc_decompress",
+    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_nsi", "rsdgc_decompress",
     "rsdgc_last_paths", "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
 ]
@@ -82,6 +82,8 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_workspace_bytes.restype = ctypes.c_size_t
     lib.rsdgc_compress.argtypes = [vp] * 11
     lib.rsdgc_compress.restype = ctypes.c_int
+    lib.rsdgc_compress_momentum.argtypes = [vp, vp, vp, vp, ctypes.c_float] + [vp] * 9
+    lib.rsdgc_compress_momentum.restype = ctypes.c_int
     lib.rsdgc_nsi.argtypes = [vp] * 6
     lib.rsdgc_nsi.restype = ctypes.c_int
     lib.rsdgc_decompress.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
@@ -208,6 +210,17 @@ def rsdgc_compress(plan: Plan, grad, residual, residual_out, out_idx, out_val, o
                                  _ptr(out_val), _ptr(out_counts), _ptr(out_centre_idx),
                                  _ptr(out_centre_counts), _ptr(workspace), _stream(stream)),
            "rsdgc_compress")
+
+
+def rsdgc_compress_momentum(plan: Plan, grad, momentum, momentum_out, m: float, residual, residual_out,
+                            out_idx, out_val, out_counts, workspace, out_centre_idx=None,
+                            out_centre_counts=None, stream=None) -> None:
+    """Eq. 12 in full; the five arenas must not overlap."""
+    _check(load().rsdgc_compress_momentum(plan.handle, _ptr(grad), _ptr(momentum), _ptr(momentum_out),
+                                          float(m), _ptr(residual), _ptr(residual_out), _ptr(out_idx),
+                                          _ptr(out_val), _ptr(out_counts), _ptr(out_centre_idx),
+                                          _ptr(out_centre_counts), _ptr(workspace), _stream(stream)),
+           "rsdgc_compress_momentum")
 
 
 def rsdgc_nsi(plan: Plan, grad, residual, nsi_out, workspace, stream=None) -> None:

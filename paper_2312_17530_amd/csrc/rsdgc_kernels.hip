@@ -187,6 +187,9 @@ struct NsiArgs {
     const float *resid;           // nullable: all-zero residual
     float *nsi_out;               // score map (kPassMapOnly, kPassFullMap)
     float *v_out;                 // nullable: second residual arena that receives v = r + g
+    const float *mom;             // nullable: momentum arena u (Eq. 12, first line); then v = r + (m*u + g)
+    float *mom_out;               // with mom: receives m*u + g wherever v_out receives v
+    float m;                      // momentum factor
     const uint32_t *flags;        // [0] != 0: some large layer fell back to the full map
     uint32_t *hist;               // [n_layers][kHistBins]
     const SelState *state;
@@ -207,7 +210,7 @@ struct NsiArgs {
 // one contiguous stretch of the launch: neighbouring tiles share halo rows in one L2).
 // Its LDS histogram is flushed to the layer's global histogram only when the layer
 // changes or the range ends, so a launch issues few same-address global atomics.
-template <int P, int PASS>
+template <int P, int PASS, bool MOM>   // MOM: with Eq. 12's momentum term (a.mom, a.mom_out, a.m)
 __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     constexpr int H = (P - 1) / 2;
     constexpr int ROWS = kTileRows + 2 * H;
@@ -320,6 +323,33 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                     if (r) rv[it] = *reinterpret_cast<const float4 *>(r + off);
                 }
             }
+            if (MOM) {                    // Eq. 12, first line: the gradient term becomes u = m*u + g
+                const float *__restrict__ u = a.mom + L.elem_off;
+                float4 uv[ITER];
+#pragma unroll
+                for (int it = 0; it < ITER; ++it) {
+                    const int s = tid + it * 256;
+                    const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
+                    const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
+                    uv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (s < NVEC && x >= 0 && x < R && y >= 0 && y < C)
+                        uv[it] = *reinterpret_cast<const float4 *>(u + static_cast<size_t>(x) * C + y);
+                }
+#pragma unroll
+                for (int it = 0; it < ITER; ++it) {
+                    gv[it].x = __fmul_rn(a.m, uv[it].x) + gv[it].x;
+                    gv[it].y = __fmul_rn(a.m, uv[it].y) + gv[it].y;
+                    gv[it].z = __fmul_rn(a.m, uv[it].z) + gv[it].z;
+                    gv[it].w = __fmul_rn(a.m, uv[it].w) + gv[it].w;
+                    if (STORE_V && a.mom_out && whole) {
+                        const int s = tid + it * 256;
+                        const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
+                        const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
+                        if (s < NVEC && rr >= H && rr < H + kTileRows && j4 >= 1 && j4 <= kTileCols / 4 && x < R && y < C)
+                            *reinterpret_cast<float4 *>(a.mom_out + L.elem_off + static_cast<size_t>(x) * C + y) = gv[it];
+                    }
+                }
+            }
 #pragma unroll
             for (int it = 0; it < ITER; ++it) {
                 const int s = tid + it * 256;
@@ -345,9 +375,14 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                 float v = 0.f;
                 if (x >= 0 && x < R && y >= 0 && y < C) {
                     const size_t off = static_cast<size_t>(x) * C + y;
-                    v = (r ? r[off] : 0.f) + g[off];
-                    if (STORE_V && a.v_out && whole && rr >= H && rr < H + kTileRows && j >= PADL && j < PADL + kTileCols)
-                        a.v_out[L.elem_off + off] = v;
+                    const bool own = rr >= H && rr < H + kTileRows && j >= PADL && j < PADL + kTileCols;
+                    float gu = g[off];
+                    if (MOM) {
+                        gu = __fmul_rn(a.m, a.mom[L.elem_off + off]) + gu;
+                        if (STORE_V && a.mom_out && whole && own) a.mom_out[L.elem_off + off] = gu;
+                    }
+                    v = (r ? r[off] : 0.f) + gu;
+                    if (STORE_V && a.v_out && whole && own) a.v_out[L.elem_off + off] = v;
                 }
                 tile[s] = v;
             }
@@ -1390,6 +1425,8 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict
                                                      const float *__restrict__ grad,
                                                      const float *__restrict__ resid_in,
                                                      float *__restrict__ v_arena,
+                                                     const float *__restrict__ mom_in,
+                                                     float *__restrict__ mom_arena, float m,
                                                      const uint32_t *__restrict__ mask,
                                                      const uint32_t *__restrict__ chunk_base,
                                                      uint32_t *__restrict__ out_idx,
@@ -1411,12 +1448,13 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict
         const float *__restrict__ g = grad + base;
         const float *__restrict__ r = resid_in + base;
         for (uint32_t e = 4 * tid; e < len; e += 1024) {
-            if (e + 3 < len) {
-                const float4 gv = *reinterpret_cast<const float4 *>(g + e);
-                const float4 rv = *reinterpret_cast<const float4 *>(r + e);
-                *reinterpret_cast<float4 *>(v + e) = make_float4(rv.x + gv.x, rv.y + gv.y, rv.z + gv.z, rv.w + gv.w);
-            } else {
-                for (uint32_t q = 0; q < 4 && e + q < len; ++q) v[e + q] = r[e + q] + g[e + q];
+            for (uint32_t q = 0; q < 4 && e + q < len; ++q) {
+                float gu = g[e + q];
+                if (mom_in) {
+                    gu = __fmul_rn(m, mom_in[base + e + q]) + gu;
+                    mom_arena[base + e + q] = gu;
+                }
+                v[e + q] = r[e + q] + gu;
             }
         }
         return;
@@ -1446,6 +1484,7 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict
             out_val[obase + i] = val;
         }
         v[e] = 0.f;
+        if (mom_arena) mom_arena[base + e] = 0.f;     // the momentum restarts where v was sent
     }
 }
 
@@ -1542,11 +1581,20 @@ uint32_t resident_workgroups(K kernel) {
 // One launch of the NSI kernel per neighbourhood side.  kPassSample runs over the sampled
 // tiles of the large layers, every other pass over all tiles (workgroups of layers that
 // are in another mode leave at once).
+struct Momentum {                 // Eq. 12's momentum term; all null / 0 without it
+    const float *in = nullptr;
+    float *out = nullptr;
+    float m = 0.f;
+};
+
 template <int PASS>
 int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const float *resid,
-               float *nsi_out, float *v_out, hipStream_t stream) {
+               float *nsi_out, float *v_out, const Momentum &mom, hipStream_t stream) {
     NsiArgs a;
     a.v_out = v_out;
+    a.mom = mom.in;
+    a.mom_out = mom.out;
+    a.m = mom.m;
     a.flags = reinterpret_cast<const uint32_t *>(ws + plan->ws.flags);
     a.layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
     a.grad = grad;
@@ -1573,9 +1621,15 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
         switch (g.p) {
 #define RSDGC_NSI_CASE(PP)                                                                  \
     case PP: {                                                                              \
-        static const uint32_t resident = resident_workgroups(k_nsi<PP, PASS>);              \
-        const dim3 grid(std::min<uint32_t>(items, resident));                               \
-        hipLaunchKernelGGL((k_nsi<PP, PASS>), grid, block, 0, stream, a);                    \
+        if (mom.in) {                                                                       \
+            static const uint32_t resident = resident_workgroups(k_nsi<PP, PASS, true>);    \
+            const dim3 grid(std::min<uint32_t>(items, resident));                           \
+            hipLaunchKernelGGL((k_nsi<PP, PASS, true>), grid, block, 0, stream, a);          \
+        } else {                                                                            \
+            static const uint32_t resident = resident_workgroups(k_nsi<PP, PASS, false>);   \
+            const dim3 grid(std::min<uint32_t>(items, resident));                           \
+            hipLaunchKernelGGL((k_nsi<PP, PASS, false>), grid, block, 0, stream, a);         \
+        }                                                                                   \
         break;                                                                              \
     }
             RSDGC_NSI_CASE(1)
@@ -1617,10 +1671,10 @@ extern "C" {
 
 const char *rsdgc_last_hip_error(void) { return g_hip_error; }
 
-int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
-                   float *residual_out, uint32_t *out_idx, float *out_val, int32_t *out_counts,
-                   uint32_t *out_centre_idx, int32_t *out_centre_counts, void *workspace,
-                   void *stream_) {
+static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &mom,
+                         const float *residual, float *residual_out, uint32_t *out_idx,
+                         float *out_val, int32_t *out_counts, uint32_t *out_centre_idx,
+                         int32_t *out_centre_counts, void *workspace, void *stream_) {
     if (!plan || !grad || !residual || !residual_out || !out_idx || !out_val || !out_counts || !workspace)
         return RSDGC_EINVAL;
     if (!aligned256(workspace) || !aligned16(grad) || !aligned16(residual) || !aligned16(residual_out))
@@ -1672,17 +1726,17 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
     const unsigned long long *slot_ent = reinterpret_cast<const unsigned long long *>(ws + w.slot_ent);
     // first pass: the sampled tiles of the large layers (histogram only) and every tile of the
     // other layers (scores, histogram, v) share one launch
-    rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, stream);
+    rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
     if (rc != RSDGC_OK) return rc;
     if (plan->any_large) {
         hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
         marks.close(1);
-        rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, v_out, stream);
+        rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, v_out, mom, stream);
         if (rc != RSDGC_OK) return rc;
         hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
         marks.close(2);
         // large layers whose candidate bound failed (rare): their workgroups find nothing to do otherwise
-        rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, stream);
+        rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, mom, stream);
         if (rc != RSDGC_OK) return rc;
     } else {
         marks.close(1);
@@ -1760,7 +1814,7 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
                            residual_out, mask, chunk_cnt, out_idx, out_val);
     else
         hipLaunchKernelGGL(k_emit_sparse, dim3(n_chunks), dim3(256), 0, stream, chunk_info, state, grad,
-                           residual, residual_out, mask, chunk_cnt, out_idx, out_val);
+                           residual, residual_out, mom.in, mom.out, mom.m, mask, chunk_cnt, out_idx, out_val);
     marks.close(7);
     if (out_centre_idx)
         hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer,
@@ -1768,6 +1822,38 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
     marks.close(8);
     HIP_TRY(hipGetLastError());
     return RSDGC_OK;
+}
+
+int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
+                   float *residual_out, uint32_t *out_idx, float *out_val, int32_t *out_counts,
+                   uint32_t *out_centre_idx, int32_t *out_centre_counts, void *workspace,
+                   void *stream) {
+    return compress_impl(plan, grad, Momentum{}, residual, residual_out, out_idx, out_val, out_counts,
+                         out_centre_idx, out_centre_counts, workspace, stream);
+}
+
+int rsdgc_compress_momentum(rsdgc_plan_t *plan, const float *grad, const float *momentum,
+                            float *momentum_out, float m, const float *residual,
+                            float *residual_out, uint32_t *out_idx, float *out_val,
+                            int32_t *out_counts, uint32_t *out_centre_idx,
+                            int32_t *out_centre_counts, void *workspace, void *stream) {
+    if (!plan || !grad || !momentum || !momentum_out || !residual || !residual_out) return RSDGC_EINVAL;
+    if (!(m >= 0.f && m <= 1.f)) return RSDGC_EINVAL;                       // false for NaN
+    if (!aligned16(momentum) || !aligned16(momentum_out)) return RSDGC_EINVAL;
+    // five arenas, pairwise disjoint: both new arenas are written while the three inputs are still read
+    const uintptr_t bytes = static_cast<uintptr_t>(plan->total_elems) * sizeof(float);
+    const uintptr_t p[5] = {reinterpret_cast<uintptr_t>(grad), reinterpret_cast<uintptr_t>(momentum),
+                            reinterpret_cast<uintptr_t>(residual), reinterpret_cast<uintptr_t>(momentum_out),
+                            reinterpret_cast<uintptr_t>(residual_out)};
+    for (int i = 0; i < 5; ++i)
+        for (int j = (i < 3 ? 3 : i + 1); j < 5; ++j)
+            if (p[i] < p[j] + bytes && p[j] < p[i] + bytes) return RSDGC_EINVAL;
+    Momentum mom;
+    mom.in = momentum;
+    mom.out = momentum_out;
+    mom.m = m;
+    return compress_impl(plan, grad, mom, residual, residual_out, out_idx, out_val, out_counts,
+                         out_centre_idx, out_centre_counts, workspace, stream);
 }
 
 int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream_) {
@@ -1854,7 +1940,7 @@ int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual, floa
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
     return launch_nsi<kPassMapOnly>(plan, static_cast<char *>(workspace), grad, residual, nsi_out,
-                                    nullptr, stream);
+                                    nullptr, Momentum{}, stream);
 }
 
 int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,

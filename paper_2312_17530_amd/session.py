@@ -15,7 +15,7 @@ class Session:
     def __init__(self, shapes, p: int, alpha: float, ratios: Sequence[float],
                  p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0",
                  want_centres: bool = True, path: int = binding.RSDGC_PATH_AUTO,
-                 in_place: bool = False):
+                 in_place: bool = False, momentum: Optional[float] = None):
         self.shapes = [(int(r), int(c)) for r, c in shapes]
         self.plan = binding.rsdgc_plan(self.shapes, p, alpha, ratios, p_per_layer)
         if path != binding.RSDGC_PATH_AUTO:
@@ -30,6 +30,12 @@ class Session:
         self.residual = torch.zeros(n, dtype=torch.float32, device=dev)
         self.in_place = in_place
         self.residual_next = None if in_place else torch.zeros(n, dtype=torch.float32, device=dev)
+        # Eq. 12's momentum term (optional): `momentum_buf` is the newest u, handled like the residual
+        self.m = momentum
+        if momentum is not None:
+            assert not in_place, "momentum correction needs the two-arena form"
+            self.momentum_buf = torch.zeros(n, dtype=torch.float32, device=dev)
+            self.momentum_next = torch.zeros(n, dtype=torch.float32, device=dev)
         self.out_idx = torch.zeros(max(1, self.plan.out_capacity), dtype=torch.int32, device=dev)
         self.out_val = torch.zeros(max(1, self.plan.out_capacity), dtype=torch.float32, device=dev)
         self.out_counts = torch.zeros(L, dtype=torch.int32, device=dev)
@@ -61,7 +67,19 @@ class Session:
         self.pack(arrays, self.residual)
 
     # ---- calls
+    def set_momentum(self, arrays):
+        self.pack(arrays, self.momentum_buf)
+
     def compress(self, stream=None) -> None:
+        if self.m is not None:
+            binding.rsdgc_compress_momentum(self.plan, self.grad, self.momentum_buf, self.momentum_next,
+                                            self.m, self.residual, self.residual_next, self.out_idx,
+                                            self.out_val, self.out_counts, self.workspace,
+                                            self.out_centre_idx,
+                                            self.out_centre_counts if self.want_centres else None, stream)
+            self.residual, self.residual_next = self.residual_next, self.residual
+            self.momentum_buf, self.momentum_next = self.momentum_next, self.momentum_buf
+            return
         target = self.residual if self.in_place else self.residual_next
         binding.rsdgc_compress(self.plan, self.grad, self.residual, target, self.out_idx, self.out_val,
                                self.out_counts, self.workspace, self.out_centre_idx,

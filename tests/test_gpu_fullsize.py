@@ -115,6 +115,39 @@ def test_vgg19_full_size_in_place_equals_two_arenas():
             assert torch.equal(a.out_centre_idx[co:co + k], b.out_centre_idx[co:co + k]), (t, l)
 
 
+def test_vgg19_full_size_with_momentum_against_oracle():
+    """Eq. 12 in full at the benchmark's size: one iteration from a random (u, r) state."""
+    import torch
+    from paper_2312_17530_amd.session import Session
+    w = synth.config(3)
+    m = 0.9
+    sess = Session(w.shapes, w.p, w.alpha, w.ratios, momentum=m)
+    grads = synth.gradients(w, 0)
+    u0 = synth.gradients(w, 7)
+    r0 = synth.gradients(w, 8)
+    sess.set_grad(grads)
+    sess.set_momentum(u0)
+    sess.set_residual(r0)
+    sess.compress()
+    torch.cuda.synchronize()
+    res = sess.results()
+    gpu_r = sess.unpack(sess.residual)
+    gpu_u = sess.unpack(sess.momentum_buf)
+    n_exact = 0
+    for l, sh in enumerate(w.shapes):
+        tag = f"{w.name}[momentum,l={l},{sh}]"
+        print("checking", tag, flush=True)
+        om = oracle.compress_layer_momentum(grads[l], u0[l], r0[l], m, w.p, w.alpha, w.ratios[l])
+        o = om.layer
+        gi, gv, gc, gn = res[l]
+        exact = parity.check_layer(tag, sh, w.p, o.k, o.tau, o.nsi, o.centres, o.idx, o.val, o.r_new, o.v,
+                                   gi, gv, gc, gn, gpu_r[l])
+        if exact:
+            assert np.array_equal(gpu_u[l].view(np.uint32), om.u_new.view(np.uint32)), f"{tag}: momentum"
+        n_exact += int(exact)
+    assert n_exact >= w.n_layers - 2
+
+
 def test_fc6_stress_p5_student_t_against_oracle_then_one_carried_iteration():
     w, n_exact = _run(4, extra_iterations=1)
     assert n_exact == 1

@@ -68,6 +68,102 @@ def run_and_check(shapes, p_list, alpha, ratios, grads_per_iter, name="case", ch
     return n_cmp, n_exact
 
 
+def run_and_check_momentum(shapes, p_list, alpha, ratios, m, grads_per_iter, name, u0=None, r0=None):
+    """Eq. 12 in full: every iteration on GPU and oracle from identical (u, r) state."""
+    import torch
+    from paper_2312_17530_amd.session import Session
+    sess = Session(shapes, p_list[0], alpha, ratios, p_list, momentum=m)
+    L = len(shapes)
+    mom = u0 if u0 is not None else [np.zeros(sh, dtype=np.float32) for sh in shapes]
+    resid = r0 if r0 is not None else [np.zeros(sh, dtype=np.float32) for sh in shapes]
+    n_cmp = n_exact = 0
+    for t, grads in enumerate(grads_per_iter):
+        sess.set_grad(grads)
+        sess.set_residual(resid)
+        sess.set_momentum(mom)
+        sess.compress()
+        torch.cuda.synchronize()
+        res = sess.results()
+        gpu_r = sess.unpack(sess.residual)
+        gpu_u = sess.unpack(sess.momentum_buf)
+        new_resid, new_mom = [], []
+        for l in range(L):
+            om = oracle.compress_layer_momentum(grads[l], mom[l], resid[l], m, p_list[l], alpha, ratios[l])
+            o = om.layer
+            tag = f"{name}[momentum,t={t},l={l},{shapes[l]},p={p_list[l]}]"
+            gi, gv, gc, gn = res[l]
+            exact = parity.check_layer(tag, shapes[l], p_list[l], o.k, o.tau, o.nsi, o.centres, o.idx,
+                                       o.val, o.r_new, o.v, gi, gv, gc, gn, gpu_r[l])
+            # the momentum: m*u + g where nothing was sent, +0 where something was (the GPU's own set)
+            un, _ = oracle.momentum_accumulate(mom[l], grads[l], resid[l], m)
+            want_u = un.reshape(-1).copy()
+            want_u[gi] = 0.0
+            assert np.array_equal(gpu_u[l].reshape(-1).view(np.uint32), want_u.view(np.uint32)), f"{tag}: momentum"
+            if exact:
+                assert np.array_equal(gpu_u[l].view(np.uint32), om.u_new.view(np.uint32)), f"{tag}: momentum vs oracle"
+            n_cmp += 1
+            n_exact += int(exact)
+            new_resid.append(o.r_new)
+            new_mom.append(om.u_new)
+        resid, mom = new_resid, new_mom
+    return n_cmp, n_exact
+
+
+def test_momentum_ragged_shapes_three_iterations():
+    shapes = RAGGED
+    p_list = [1, 3, 5, 7, 3, 5, 3, 3, 7, 5, 3, 1, 3, 5]
+    ratios = [1.0, 0.1, 0.1, 1.0, 0.02, 0.05, 0.02, 0.01, 0.3, 0.001, 0.5, 0.07, 0.0, 1.0]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 17, t, l) for l, sh in enumerate(shapes)] for t in range(3)]
+    n, ex = run_and_check_momentum(shapes, p_list, 0.5, ratios, 0.9, its, "ragged")
+    assert n == 3 * len(shapes) and ex >= n - 2
+
+
+@pytest.mark.parametrize("m", [0.9, 0.0, 1.0, 0.5])
+def test_momentum_resnet18_two_iterations(m):
+    w = synth.config(1)
+    its = [synth.gradients(w, t) for t in range(2)]
+    rng = np.random.default_rng(5)
+    u0 = [(rng.standard_normal(sh) * 1e-3).astype(np.float32) for sh in w.shapes]
+    r0 = [(rng.standard_normal(sh) * 1e-3).astype(np.float32) for sh in w.shapes]
+    n, ex = run_and_check_momentum(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, m, its, w.name, u0, r0)
+    assert n == 2 * w.n_layers and ex >= n - 2
+
+
+def test_momentum_zero_equals_the_plain_call():
+    import torch
+    from paper_2312_17530_amd.session import Session
+    w = synth.scaled_down(synth.config(2), 256, 512)
+    grads = synth.gradients(w, 0)
+    a = Session(w.shapes, w.p, w.alpha, w.ratios)
+    b = Session(w.shapes, w.p, w.alpha, w.ratios, momentum=0.0)
+    for sess in (a, b):
+        sess.set_grad(grads)
+        sess.compress()
+    torch.cuda.synchronize()
+    assert torch.equal(a.out_counts, b.out_counts)
+    assert torch.equal(a.residual.view(torch.int32), b.residual.view(torch.int32))
+    for (i1, v1, c1, n1), (i2, v2, c2, n2) in zip(a.results(), b.results()):
+        assert np.array_equal(i1, i2) and np.array_equal(v1.view(np.uint32), v2.view(np.uint32)) and np.array_equal(c1, c2)
+
+
+def test_momentum_refuses_overlapping_arenas():
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import Session
+    sess = Session([(64, 64)], 3, 0.5, [0.1], momentum=0.9)
+    args = dict(out_idx=sess.out_idx, out_val=sess.out_val, out_counts=sess.out_counts, workspace=sess.workspace)
+    for bad in ((sess.grad, sess.momentum_buf, sess.momentum_buf, sess.residual, sess.residual_next),
+                (sess.grad, sess.momentum_buf, sess.momentum_next, sess.residual, sess.residual),
+                (sess.grad, sess.momentum_buf, sess.residual_next, sess.residual, sess.residual_next),
+                (sess.grad, sess.momentum_buf, sess.grad, sess.residual, sess.residual_next)):
+        with pytest.raises(binding.RsdgcError):
+            binding.rsdgc_compress_momentum(sess.plan, bad[0], bad[1], bad[2], 0.9, bad[3], bad[4], **args)
+    with pytest.raises(binding.RsdgcError):
+        binding.rsdgc_compress_momentum(sess.plan, sess.grad, sess.momentum_buf, sess.momentum_next, 1.5,
+                                        sess.residual, sess.residual_next, **args)
+    torch.cuda.synchronize()
+
+
 def test_config0_single_layer_512(in_place):
     w = synth.config(0)
     n, ex = run_and_check(w.shapes, [w.p], w.alpha, w.ratios, [synth.gradients(w, 0)], w.name,
