@@ -75,6 +75,9 @@ def _load():
                                                          u32p, fp, u32p, ctypes.POINTER(i64),
                                                          ctypes.POINTER(c_float), fp, fp]
     lib.rsdgc_oracle_compress_layer_momentum.restype = i64
+    lib.rsdgc_oracle_dynamic_ratios.argtypes = [fp, ctypes.POINTER(i64), ctypes.c_int32, f64,
+                                                ctypes.POINTER(f64)]
+    lib.rsdgc_oracle_dynamic_ratios.restype = c_int
     _lib = lib
     return lib
 
@@ -287,6 +290,24 @@ def compress_layer_momentum(g, u, r, m: float, p: int, alpha: float, rho: float)
     return MomentumLayerResult(
         LayerResult(idx[:n].copy(), val[:n].copy(), centres[:k].copy(), k,
                     float(tau.value) if k > 0 else None, nsi_map, v, r_new), u_new)
+
+
+def dynamic_ratios(weights: Sequence[np.ndarray], rho: float) -> List[float]:
+    """Eqs. 3-5: per-layer keep ratios from one ranking of |w| over all layers; rho is the global
+    keep fraction, ceil(rho * G) weights survive, equal |w| rank by layer, then by index."""
+    flat = [_f32(w).reshape(-1) for w in weights]
+    off = np.zeros(len(flat) + 1, dtype=np.int64)
+    off[1:] = np.cumsum([f.size for f in flat])
+    w_all = np.concatenate(flat) if flat else np.zeros(0, dtype=np.float32)
+    if w_all.size == 0:
+        w_all = np.zeros(1, dtype=np.float32)
+    out = (ctypes.c_double * len(flat))()
+    rc = _load().rsdgc_oracle_dynamic_ratios(_p(w_all, ctypes.c_float),
+                                             off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                             len(flat), float(rho), out)
+    if rc != 0:
+        raise MemoryError("oracle ran out of memory")
+    return [float(x) for x in out]
 
 
 def compress_model(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray], p: int,

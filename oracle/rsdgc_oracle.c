@@ -22,6 +22,12 @@
  * and step 7 also restarts u from zero where v was sent (the masking of the
  * method Eq. 12 is taken from).
  *
+ * Once per epoch (Section III-B, Algorithm 1's outer loop) the per-layer keep
+ * ratios come from the weights:
+ *   step D  mu = |w| (Eq. 3); rank all weights of the network together; the
+ *           K = ceil(rho * G) top-ranked survive (Eq. 4); rho_l = survivors of
+ *           layer l / G_l (Eq. 5).  Equal |w| rank by layer, then by index.
+ *
  * Readings taken where the paper is silent (each is also a parameter or a
  * documented convention of the GPU library):
  *   - every element is the centre of one neighbourhood (stride-1 window);
@@ -320,4 +326,57 @@ int64_t rsdgc_oracle_compress_layer_momentum(const float *g, float *u, float *r,
     if (v_out) memcpy(v_out, v, (size_t)G * sizeof(float));
     free(v); free(un); free(nsi); free(mask);
     return n;
+}
+
+/* ---------------------------------------------------------------- step D */
+/* Eqs. 3-5: per-layer keep ratios from a cross-layer ranking of |w|.
+ * w_all holds the layers back to back; layer l is w_all[off[l] .. off[l+1]).
+ * rho is the global keep fraction.  Returns 0, or -1 on allocation failure. */
+typedef struct {
+    float mu;
+    int32_t layer;
+    int64_t index;
+} weight_item;
+
+static int weight_cmp(const void *a, const void *b)
+{
+    const weight_item *p = (const weight_item *)a, *q = (const weight_item *)b;
+    if (p->mu > q->mu) return -1;
+    if (p->mu < q->mu) return 1;
+    if (p->layer < q->layer) return -1;
+    if (p->layer > q->layer) return 1;
+    if (p->index < q->index) return -1;
+    if (p->index > q->index) return 1;
+    return 0;
+}
+
+int rsdgc_oracle_dynamic_ratios(const float *w_all, const int64_t *off, int32_t L, double rho,
+                                double *ratio_out)
+{
+    const int64_t N = off[L];
+    weight_item *it = (weight_item *)malloc((size_t)(N > 0 ? N : 1) * sizeof(weight_item));
+    int64_t *kept = (int64_t *)calloc((size_t)L, sizeof(int64_t));
+    if (!it || !kept) {
+        free(it); free(kept);
+        return -1;
+    }
+    for (int32_t l = 0; l < L; ++l)
+        for (int64_t i = off[l]; i < off[l + 1]; ++i) {
+            it[i].mu = fabsf(w_all[i]);                       /* Eq. 3 */
+            it[i].layer = l;
+            it[i].index = i - off[l];
+        }
+    qsort(it, (size_t)N, sizeof(weight_item), weight_cmp);    /* cross-layer ranking */
+    double kf = ceil(rho * (double)N);                        /* survivors (Eq. 4) */
+    if (kf < 0.0) kf = 0.0;
+    if (kf > (double)N) kf = (double)N;
+    const int64_t K = (int64_t)kf;
+    for (int64_t j = 0; j < K; ++j)
+        ++kept[it[j].layer];
+    for (int32_t l = 0; l < L; ++l) {                         /* Eq. 5 */
+        const int64_t Gl = off[l + 1] - off[l];
+        ratio_out[l] = Gl > 0 ? (double)kept[l] / (double)Gl : 0.0;
+    }
+    free(it); free(kept);
+    return 0;
 }

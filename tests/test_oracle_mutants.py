@@ -116,6 +116,15 @@ def battery(orc):
     plain = orc.compress_layer(un, rr, 3, 0.5, 0.3)
     check("momentum_selection", np.array_equal(plain.idx, mres.layer.idx)
           and np.array_equal(plain.r_new, mres.layer.r_new))
+    # Eqs. 3-5: dynamic per-layer ratios
+    ws = [(rng.standard_normal(sh) * sc).astype(np.float32) for sh, sc in (((9, 11), 1.0), ((40, 3), 0.2), ((5, 5), 4.0))]
+    mu = np.concatenate([np.abs(w).ravel() for w in ws])
+    lay = np.concatenate([np.full(w.size, l) for l, w in enumerate(ws)])
+    K = int(math.ceil(0.2 * mu.size))
+    kept = np.bincount(lay[np.argsort(-mu.astype(np.float64), kind="stable")[:K]], minlength=3)
+    check("dynamic_ratios", orc.dynamic_ratios(ws, 0.2) == [kept[l] / ws[l].size for l in range(3)])
+    ones = [np.ones((2, 5), np.float32), -np.ones((3, 4), np.float32)]
+    check("dynamic_ties", orc.dynamic_ratios(ones, 13 / 22) == [1.0, 3 / 12])
     d2 = np.ones(10, np.float32)
     orc.decompress(np.array([2, 5], np.uint32), np.array([0.5, -1.0], np.float32), 10, dense=d2, accumulate_into=True)
     check("decompress_acc", d2.tolist() == [1, 1, 1.5, 1, 1, 0, 1, 1, 1, 1])
@@ -150,6 +159,13 @@ MUTANTS = [
     ("momentum_not_added_to_v", "volatile float s = r[i] + un;", "volatile float s = r[i] + g[i];", 0),
     ("momentum_fused", "volatile float mu = m * u[i];\n        volatile float un = mu + g[i];",
      "volatile float mu = m * u[i];\n        volatile float un = (float)((double)m * (double)u[i] + (double)g[i]);", 0),
+    ("dynamic_signed_weights", "it[i].mu = fabsf(w_all[i]);", "it[i].mu = w_all[i];", 0),
+    ("dynamic_keeps_lowest", "if (p->mu > q->mu) return -1;\n    if (p->mu < q->mu) return 1;",
+     "if (p->mu > q->mu) return 1;\n    if (p->mu < q->mu) return -1;", 0),
+    ("dynamic_floor", "double kf = ceil(rho * (double)N);", "double kf = floor(rho * (double)N);", 0),
+    ("dynamic_ties_to_later_layer", "if (p->layer < q->layer) return -1;\n    if (p->layer > q->layer) return 1;",
+     "if (p->layer < q->layer) return 1;\n    if (p->layer > q->layer) return -1;", 0),
+    ("dynamic_ratio_of_network", "(double)kept[l] / (double)Gl", "(double)kept[l] / (double)N", 0),
     ("momentum_not_masked", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = u_new[i];", 0),
     ("momentum_masked_where_kept_out", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = mask[i] ? u_new[i] : 0.0f;", 0),
 ]

@@ -421,3 +421,43 @@ def test_momentum_against_pure_python_brute_force():
             kept = set(b["idx"])
             flat = [x for row in un for x in row]
             assert o.u_new.ravel().tolist() == [0.0 if i in kept else flat[i] for i in range(R * C)]
+
+
+# ------------------------------------------------- dynamic per-layer ratios (Eqs. 3-5)
+def test_dynamic_ratios_against_a_library_sort():
+    rng = np.random.default_rng(31)
+    shapes = [(9, 11), (40, 3), (1, 57), (16, 16)]
+    ws = [(rng.standard_normal(sh) * s).astype(np.float32) for sh, s in zip(shapes, (1.0, 0.2, 5.0, 1.0))]
+    for rho in (0.0, 0.001, 0.013, 0.25, 0.5, 0.999, 1.0):
+        got = oracle.dynamic_ratios(ws, rho)
+        mu = np.concatenate([np.abs(w).ravel() for w in ws])
+        layer = np.concatenate([np.full(w.size, l) for l, w in enumerate(ws)])
+        K = int(math.ceil(rho * mu.size))
+        order = np.argsort(-mu.astype(np.float64), kind="stable")        # stable: ties keep layer/index order
+        kept = np.bincount(layer[order[:K]], minlength=len(ws))
+        assert got == [kept[l] / ws[l].size for l in range(len(ws))]
+        assert sum(round(r * w.size) for r, w in zip(got, ws)) == K      # Eq. 5 over all layers: the survivors
+
+
+def test_dynamic_ratios_closed_forms_and_tie_order():
+    big = np.full((4, 5), -2.0, dtype=np.float32)         # |w| = 2 everywhere (sign must not matter)
+    small = np.full((10, 3), 1.0, dtype=np.float32)
+    assert oracle.dynamic_ratios([big, small], 20 / 50) == [1.0, 0.0]
+    assert oracle.dynamic_ratios([small, big], 20 / 50) == [0.0, 1.0]
+    assert oracle.dynamic_ratios([big, small], 35 / 50) == [1.0, 0.5]
+    # all weights equal: the ranking falls back to layer order, then index order
+    a = np.ones((2, 5), dtype=np.float32)
+    b = -np.ones((3, 4), dtype=np.float32)
+    assert oracle.dynamic_ratios([a, b], 13 / 22) == [1.0, 3 / 12]
+    assert oracle.dynamic_ratios([a, b], 1.0) == [1.0, 1.0]
+    assert oracle.dynamic_ratios([a, b], 0.0) == [0.0, 0.0]
+    # scaling one layer up moves the budget towards it (the paper's premise), monotonically
+    rng = np.random.default_rng(32)
+    x = rng.standard_normal((30, 30)).astype(np.float32)
+    y = rng.standard_normal((30, 30)).astype(np.float32)
+    prev = -1.0
+    for s in (0.25, 0.5, 1.0, 2.0, 4.0):
+        r0, r1 = oracle.dynamic_ratios([x * np.float32(s), y], 0.1)
+        assert r0 >= prev and abs(r0 * 900 + r1 * 900 - 180) < 1e-9
+        prev = r0
+    assert oracle.dynamic_ratios([x, y * np.float32(1.0)], 0.1)[0] == oracle.dynamic_ratios([x, y], 0.1)[0]
