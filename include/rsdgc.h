@@ -71,7 +71,10 @@ int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
 
 /* New per-layer keep ratios (the paper refreshes them once per epoch,
  * Section III-B / Algorithm 1).  Recomputes k_l, output offsets, capacities.
- * The workspace size does not change.                                       */
+ * The workspace size does not change, but rsdgc_out_capacity and
+ * rsdgc_centre_capacity may grow: the caller's out_idx / out_val / out_centre_idx
+ * buffers must be re-checked against them before the next rsdgc_compress (the
+ * library cannot see their sizes and writes up to the new capacities).      */
 int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio);
 
 /* How the per-layer ranking (Algorithm 1) is carried out; the result is the same.
@@ -156,6 +159,18 @@ int rsdgc_compress_momentum(rsdgc_plan_t *plan, const float *grad, const float *
                             float *residual_out, uint32_t *out_idx, float *out_val,
                             int32_t *out_counts, uint32_t *out_centre_idx,
                             int32_t *out_centre_counts, void *workspace, void *stream);
+
+/* Dynamic compression strategy (Section III-B, Eqs. 3-5; Algorithm 1's per-epoch part):
+ * mu = |w| of every weight of the network is ranked across all layers, the
+ * ceil(global_ratio * G) top-ranked weights survive (equal |w|: earlier layer
+ * first), and layer l's keep ratio is survivors_l / G_l.
+ *   weights     [device, const] float32 arena laid out like the gradient arena.
+ *   ratios_out  [host] double[n_layers]; feed it to rsdgc_plan_set_ratios.
+ * Runs four streaming passes on `stream` and waits for them (a per-epoch step,
+ * not part of the per-iteration path); uses the workspace's scratch only, so it
+ * must not overlap a compress call that uses the same workspace.             */
+int rsdgc_dynamic_ratios(rsdgc_plan_t *plan, const float *weights, double global_ratio,
+                         double *ratios_out, void *workspace, void *stream);
 
 /* NSI map only (Eqs. 8-10 at every element of every layer), for inspection:
  *   residual [device, nullable] NULL means an all-zero residual.

@@ -9,7 +9,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from typing import Optional, Sequence, Tuple
+from typing import List, Optional, Sequence, Tuple
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librsdgc.so")
@@ -21,7 +21,7 @@ EXPORTS = [
     "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
-    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_nsi", "rsdgc_decompress",
+    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_nsi", "rsdgc_decompress",
     "rsdgc_last_paths", "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
 ]
@@ -84,6 +84,8 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_compress.restype = ctypes.c_int
     lib.rsdgc_compress_momentum.argtypes = [vp, vp, vp, vp, ctypes.c_float] + [vp] * 9
     lib.rsdgc_compress_momentum.restype = ctypes.c_int
+    lib.rsdgc_dynamic_ratios.argtypes = [vp, vp, f64, ctypes.POINTER(f64), vp, vp]
+    lib.rsdgc_dynamic_ratios.restype = ctypes.c_int
     lib.rsdgc_nsi.argtypes = [vp] * 6
     lib.rsdgc_nsi.restype = ctypes.c_int
     lib.rsdgc_decompress.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
@@ -221,6 +223,14 @@ def rsdgc_compress_momentum(plan: Plan, grad, momentum, momentum_out, m: float, 
                                           _ptr(out_val), _ptr(out_counts), _ptr(out_centre_idx),
                                           _ptr(out_centre_counts), _ptr(workspace), _stream(stream)),
            "rsdgc_compress_momentum")
+
+
+def rsdgc_dynamic_ratios(plan: Plan, weights, global_ratio: float, workspace, stream=None) -> List[float]:
+    """Eqs. 3-5: per-layer keep ratios from the weights arena (waits for the GPU)."""
+    out = (ctypes.c_double * plan.n_layers)()
+    _check(load().rsdgc_dynamic_ratios(plan.handle, _ptr(weights), float(global_ratio), out,
+                                       _ptr(workspace), _stream(stream)), "rsdgc_dynamic_ratios")
+    return [float(x) for x in out]
 
 
 def rsdgc_nsi(plan: Plan, grad, residual, nsi_out, workspace, stream=None) -> None:

@@ -75,6 +75,13 @@ struct SelState {
 };
 static_assert(sizeof(SelState) == 40, "SelState layout");
 
+// State of the cross-layer ranking of |w| (rsdgc_dynamic_ratios).
+struct DynState {
+    unsigned long long k_rem;   // weights still to take inside the current bucket
+    uint32_t prefix;            // resolved high bits of the 31-bit key |w|
+    uint32_t pad_;
+};
+
 // Directory entry used to map a workgroup id to a layer by binary search.
 struct DirEntry {
     uint32_t begin;   // first tile / chunk / slot group of the layer
@@ -148,6 +155,7 @@ struct WsLayout {
     size_t list_ent = 0;     // uint64[sum list_cap]  composite keys of each layer's threshold bucket
     size_t list2_ent = 0;    // uint64[n_layers][kList2Cap]  keys sharing the first two digits
     size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
+    size_t dyn = 0;          // scratch of rsdgc_dynamic_ratios: DynState, uint64[kHistBins], uint32[2 * n_layers]
     size_t total = 0;
 };
 

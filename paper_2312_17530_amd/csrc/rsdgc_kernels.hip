@@ -1558,6 +1558,149 @@ __global__ __launch_bounds__(256) void k_scatter(const LayerDev *__restrict__ la
     if (accumulate) *d = *d + val[j]; else *d = val[j];
 }
 
+// ------------------------------------------------------- dynamic ratios --
+// Section III-B, Eqs. 3-5: one ranking of mu = |w| over all layers; the K top-ranked weights
+// survive and a layer's keep ratio is its share of survivors.  The K-th largest 31-bit key
+// (the bit pattern of |w|) is found by a radix select over three streaming passes
+// (12 + 10 + 9 bits), a fourth pass counts per layer the keys above and at the threshold.
+__global__ __launch_bounds__(256) void k_dyn_init(DynState *__restrict__ state,
+                                                  unsigned long long *__restrict__ hist,
+                                                  uint32_t *__restrict__ cnt, uint32_t n_cnt,
+                                                  unsigned long long K) {
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        DynState s;
+        s.k_rem = K;
+        s.prefix = 0;
+        s.pad_ = 0;
+        *state = s;
+    }
+    for (int b = tid; b < kHistBins; b += 256) hist[b] = 0ull;
+    for (uint32_t i = tid; i < n_cnt; i += 256) cnt[i] = 0u;
+}
+
+// Histogram of the digit (key >> shift) & (2^bits - 1) over the keys whose higher bits
+// (key >> prev_shift) equal the resolved prefix.  Persistent workgroups stride over the
+// 8192-element chunks (padding between layers is never read).
+__global__ __launch_bounds__(256) void k_dyn_hist(const ChunkInfo *__restrict__ chunk_info,
+                                                  uint32_t n_chunks, const uint32_t *__restrict__ w,
+                                                  const DynState *__restrict__ state, int shift,
+                                                  int bits, int prev_shift,
+                                                  unsigned long long *__restrict__ hist) {
+    __shared__ uint32_t lhist[kHistBins];
+    const int tid = threadIdx.x;
+    const int nb = 1 << bits;
+    for (int b = tid; b < nb; b += 256) lhist[b] = 0;
+    __syncthreads();
+    const uint32_t prefix = state->prefix;
+    const uint32_t dmask = static_cast<uint32_t>(nb - 1);
+    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const ChunkInfo ci = chunk_info[c];
+        const uint32_t *__restrict__ src = w + ci.arena_off;
+        for (uint32_t e = 4 * tid; e < ci.len; e += 1024) {
+            uint32_t kk[4] = {0, 0, 0, 0};
+            uint32_t nv = min(4u, ci.len - e);
+            if (nv == 4) {
+                const uint4 q = *reinterpret_cast<const uint4 *>(src + e);
+                kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
+            } else {
+                for (uint32_t q = 0; q < nv; ++q) kk[q] = src[e + q];
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint32_t key = kk[q] & 0x7fffffffu;
+                if (q < nv && (prev_shift >= 31 || (key >> prev_shift) == prefix))
+                    atomicAdd(&lhist[(key >> shift) & dmask], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    for (int b = tid; b < nb; b += 256) {
+        const uint32_t c = lhist[b];
+        if (c) atomicAdd(&hist[b], static_cast<unsigned long long>(c));
+    }
+}
+
+// One workgroup: the digit that holds the k_rem-th largest key; clears the histogram.
+__global__ __launch_bounds__(256) void k_dyn_find(DynState *__restrict__ state,
+                                                  unsigned long long *__restrict__ hist, int bits) {
+    __shared__ unsigned long long tot[256];
+    const int tid = threadIdx.x;
+    const int nb = 1 << bits, per = nb >> 8;   // bits >= 8
+    const DynState st = *state;
+    const int hi = nb - tid * per;             // thread t owns bins [hi - per, hi): t = 0 holds the top bins
+    unsigned long long own = 0;
+    for (int b = hi - 1; b >= hi - per; --b) own += hist[b];
+    tot[tid] = own;
+    __syncthreads();
+    if (tid == 0) {                            // 256 partial sums: a serial walk is short enough
+        unsigned long long acc = 0;
+        int t = 0;
+        while (t < 255 && acc + tot[t] < st.k_rem) acc += tot[t++];
+        const int h2 = nb - t * per;
+        int digit = h2 - per;
+        for (int b = h2 - 1; b >= h2 - per; --b) {
+            const unsigned long long c = hist[b];
+            if (acc + c >= st.k_rem) { digit = b; break; }
+            acc += c;
+        }
+        DynState ns = st;
+        ns.prefix = (st.prefix << bits) | static_cast<uint32_t>(digit);
+        ns.k_rem = st.k_rem - acc;
+        *state = ns;
+    }
+    __syncthreads();
+    for (int b = tid; b < nb; b += 256) hist[b] = 0ull;
+}
+
+// Per layer: keys above the threshold and keys equal to it.  Persistent workgroups; the
+// counts of a layer are added to its two counters once per workgroup.
+__global__ __launch_bounds__(256) void k_dyn_count(const ChunkInfo *__restrict__ chunk_info,
+                                                   uint32_t n_chunks, const uint32_t *__restrict__ w,
+                                                   const DynState *__restrict__ state,
+                                                   uint32_t *__restrict__ cnt /*[n_layers][2]*/) {
+    __shared__ uint32_t s_gt, s_eq;
+    const int tid = threadIdx.x;
+    const uint32_t T = state->prefix;          // all 31 bits are resolved
+    if (tid == 0) { s_gt = 0; s_eq = 0; }
+    __syncthreads();
+    uint32_t cur_l = 0xffffffffu;
+    uint32_t gt = 0, eq = 0;                   // this thread's counts for cur_l
+    for (uint32_t c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const ChunkInfo ci = chunk_info[c];
+        if (ci.layer != cur_l) {               // uniform
+            if (cur_l != 0xffffffffu) {
+                if (gt) atomicAdd(&s_gt, gt);
+                if (eq) atomicAdd(&s_eq, eq);
+                __syncthreads();
+                if (tid == 0) {
+                    if (s_gt) atomicAdd(&cnt[2 * cur_l], s_gt);
+                    if (s_eq) atomicAdd(&cnt[2 * cur_l + 1], s_eq);
+                    s_gt = 0; s_eq = 0;
+                }
+                __syncthreads();
+                gt = eq = 0;
+            }
+            cur_l = ci.layer;
+        }
+        const uint32_t *__restrict__ src = w + ci.arena_off;
+        for (uint32_t e = tid; e < ci.len; e += 256) {
+            const uint32_t key = src[e] & 0x7fffffffu;
+            gt += key > T ? 1u : 0u;
+            eq += key == T ? 1u : 0u;
+        }
+    }
+    if (cur_l != 0xffffffffu) {
+        if (gt) atomicAdd(&s_gt, gt);
+        if (eq) atomicAdd(&s_eq, eq);
+        __syncthreads();
+        if (tid == 0) {
+            if (s_gt) atomicAdd(&cnt[2 * cur_l], s_gt);
+            if (s_eq) atomicAdd(&cnt[2 * cur_l + 1], s_eq);
+        }
+    }
+}
+
 // ------------------------------------------------------------ host side --
 int upload_tables(rsdgc_plan_s *plan, void *workspace, hipStream_t stream) {
     if (plan->uploaded_ws == workspace && plan->uploaded_version == plan->version) return RSDGC_OK;
@@ -1854,6 +1997,69 @@ int rsdgc_compress_momentum(rsdgc_plan_t *plan, const float *grad, const float *
     mom.m = m;
     return compress_impl(plan, grad, mom, residual, residual_out, out_idx, out_val, out_counts,
                          out_centre_idx, out_centre_counts, workspace, stream);
+}
+
+int rsdgc_dynamic_ratios(rsdgc_plan_t *plan, const float *weights, double global_ratio,
+                         double *ratios_out, void *workspace, void *stream_) {
+    if (!plan || !weights || !ratios_out || !workspace) return RSDGC_EINVAL;
+    if (!(global_ratio >= 0.0 && global_ratio <= 1.0)) return RSDGC_EINVAL;     // false for NaN
+    if (!aligned256(workspace) || !aligned16(weights)) return RSDGC_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    const int L = plan->n_layers;
+    double n_real = 0.0;
+    for (int l = 0; l < L; ++l) n_real += static_cast<double>(plan->layers[l].G);
+    double kf = std::ceil(global_ratio * n_real);       // survivors of the ranking (Eq. 4)
+    kf = std::min(std::max(kf, 0.0), n_real);
+    const unsigned long long K = static_cast<unsigned long long>(kf);
+    if (K == 0ull || kf == n_real) {                    // nothing or everything survives
+        for (int l = 0; l < L; ++l) ratios_out[l] = K == 0ull ? 0.0 : 1.0;
+        return RSDGC_OK;
+    }
+    char *ws = static_cast<char *>(workspace);
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+    const WsLayout &w = plan->ws;
+    DynState *state = reinterpret_cast<DynState *>(ws + w.dyn);
+    unsigned long long *hist = reinterpret_cast<unsigned long long *>(ws + w.dyn + 256);
+    uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + w.dyn + 256 + sizeof(unsigned long long) * kHistBins);
+    const ChunkInfo *chunk_info = reinterpret_cast<const ChunkInfo *>(ws + w.chunk_info);
+    const uint32_t *keys = reinterpret_cast<const uint32_t *>(weights);
+    const uint32_t n_chunks = plan->n_chunks;
+    const uint32_t grid = std::min<uint32_t>(n_chunks, kNumCUs * 4u);
+    hipLaunchKernelGGL(k_dyn_init, dim3(1), dim3(256), 0, stream, state, hist, cnt,
+                       static_cast<uint32_t>(2 * L), K);
+    int prev_shift = 31;
+    for (int lv = 0; lv < 3; ++lv) {                    // 12 + 10 + 9 bits of the 31-bit key
+        const int bits = level_bits(lv), shift = level_shift(lv) - 32;
+        hipLaunchKernelGGL(k_dyn_hist, dim3(grid), dim3(256), 0, stream, chunk_info, n_chunks, keys,
+                           state, shift, bits, prev_shift, hist);
+        hipLaunchKernelGGL(k_dyn_find, dim3(1), dim3(256), 0, stream, state, hist, bits);
+        prev_shift = shift;
+    }
+    hipLaunchKernelGGL(k_dyn_count, dim3(grid), dim3(256), 0, stream, chunk_info, n_chunks, keys, state, cnt);
+    HIP_TRY(hipGetLastError());
+    std::vector<uint32_t> host;
+    try {
+        host.resize(2 * static_cast<size_t>(L));
+    } catch (const std::bad_alloc &) {
+        return RSDGC_ENOMEM;
+    }
+    HIP_TRY(hipMemcpyAsync(host.data(), cnt, sizeof(uint32_t) * host.size(), hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    // survivors per layer: everything above the threshold, then the keys equal to it in layer order
+    unsigned long long above = 0, equal = 0;
+    for (int l = 0; l < L; ++l) { above += host[2 * l]; equal += host[2 * l + 1]; }
+    if (above > K || above + equal < K) {
+        std::snprintf(g_hip_error, sizeof(g_hip_error), "rsdgc_dynamic_ratios: inconsistent counts");
+        return RSDGC_EHIP;
+    }
+    unsigned long long remaining = K - above;
+    for (int l = 0; l < L; ++l) {
+        const unsigned long long take = std::min<unsigned long long>(host[2 * l + 1], remaining);
+        remaining -= take;
+        ratios_out[l] = static_cast<double>(host[2 * l] + take) / static_cast<double>(plan->layers[l].G);   // Eq. 5
+    }
+    return RSDGC_OK;
 }
 
 int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream_) {

@@ -67,6 +67,16 @@ class Session:
         self.pack(arrays, self.residual)
 
     # ---- calls
+    def set_ratios(self, ratios: Sequence[float]) -> None:
+        """New per-layer keep ratios (the per-epoch refresh); output buffers grow if they have to."""
+        binding.rsdgc_plan_set_ratios(self.plan, ratios)
+        dev = self.device
+        if self.plan.out_capacity > self.out_idx.numel():
+            self.out_idx = torch.zeros(self.plan.out_capacity, dtype=torch.int32, device=dev)
+            self.out_val = torch.zeros(self.plan.out_capacity, dtype=torch.float32, device=dev)
+        if self.want_centres and self.plan.centre_capacity > self.out_centre_idx.numel():
+            self.out_centre_idx = torch.zeros(self.plan.centre_capacity, dtype=torch.int32, device=dev)
+
     def set_momentum(self, arrays):
         self.pack(arrays, self.momentum_buf)
 

@@ -148,6 +148,38 @@ def test_vgg19_full_size_with_momentum_against_oracle():
     assert n_exact >= w.n_layers - 2
 
 
+def test_dynamic_ratios_at_vgg19_size_against_a_library_partition():
+    """Eqs. 3-5 over 139.7 M weights: the oracle's full sort is too slow here, so the expected
+    survivors per layer come from numpy's partition (threshold) and plain counting."""
+    import math
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import Session
+    w = synth.config(3)
+    rng = np.random.default_rng(44)
+    weights = [(rng.standard_normal(sh, dtype=np.float32) * np.float32(np.sqrt(2.0 / sh[1]))) for sh in w.shapes]
+    weights[2][:] = weights[2][0, 0]                       # a layer of equal weights
+    sess = Session(w.shapes, w.p, w.alpha, w.ratios, want_centres=False)
+    arena = torch.empty_like(sess.grad)
+    host = np.full(sess.plan.total_elems, 1e30, dtype=np.float32)
+    for a, off, sz in zip(weights, sess.offsets, sess.sizes):
+        host[off:off + sz] = a.reshape(-1)
+    arena.copy_(torch.from_numpy(host))
+    for rho in (0.02, 0.001):
+        got = binding.rsdgc_dynamic_ratios(sess.plan, arena, rho, sess.workspace)
+        mu = np.concatenate([np.abs(x).ravel() for x in weights])
+        K = int(math.ceil(rho * mu.size))
+        T = np.partition(mu, mu.size - K)[mu.size - K]      # K-th largest |w|
+        remaining = K - int((mu > T).sum())
+        want = []
+        for x in weights:
+            a = np.abs(x)
+            take = min(int((a == T).sum()), remaining)
+            remaining -= take
+            want.append((int((a > T).sum()) + take) / x.size)
+        assert got == want, rho
+
+
 def test_fc6_stress_p5_student_t_against_oracle_then_one_carried_iteration():
     w, n_exact = _run(4, extra_iterations=1)
     assert n_exact == 1

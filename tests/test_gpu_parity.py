@@ -164,6 +164,66 @@ def test_momentum_refuses_overlapping_arenas():
     torch.cuda.synchronize()
 
 
+def _gpu_dynamic_ratios(shapes, weights, rho):
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import Session
+    sess = Session(shapes, 3, 0.5, [0.01] * len(shapes))
+    arena = torch.empty_like(sess.grad)
+    # the padding between layers holds huge values: it must not count
+    host = np.full(sess.plan.total_elems, 1e30, dtype=np.float32)
+    for a, off, sz in zip(weights, sess.offsets, sess.sizes):
+        host[off:off + sz] = np.asarray(a, dtype=np.float32).reshape(-1)
+    arena.copy_(torch.from_numpy(host))
+    return sess, binding.rsdgc_dynamic_ratios(sess.plan, arena, rho, sess.workspace)
+
+
+@pytest.mark.parametrize("rho", [0.0, 0.001, 0.02, 0.3, 0.97, 1.0])
+def test_dynamic_ratios_match_the_oracle(rho):
+    """Eqs. 3-5 on the GPU (radix select of |w| over all layers) against the oracle's full sort."""
+    rng = np.random.default_rng(41)
+    shapes = RAGGED + [(300, 700), (129, 64)]
+    weights = [(rng.standard_normal(sh) * 10.0 ** rng.uniform(-2, 0)).astype(np.float32) for sh in shapes]
+    weights[3][:] = 0.0                                # a dead layer
+    weights[5][:] = np.float32(-0.125)                 # a layer of equal weights (ties inside one layer)
+    weights[7][:] = np.float32(0.125)                  # ... and the same |w| in a later layer (ties across layers)
+    _, got = _gpu_dynamic_ratios(shapes, weights, rho)
+    want = oracle.dynamic_ratios(weights, rho)
+    assert got == want
+
+
+def test_dynamic_ratios_all_weights_equal_fall_back_to_layer_order():
+    shapes = [(40, 50), (30, 30), (64, 128)]
+    weights = [np.full(sh, 0.5 if l != 1 else -0.5, dtype=np.float32) for l, sh in enumerate(shapes)]
+    for rho in (0.1, 0.2, 0.5, 0.9):
+        _, got = _gpu_dynamic_ratios(shapes, weights, rho)
+        assert got == oracle.dynamic_ratios(weights, rho)
+
+
+def test_dynamic_ratios_feed_the_plan():
+    """The per-epoch step of Algorithm 1 end to end: ratios from the weights, then one iteration."""
+    import torch
+    from paper_2312_17530_amd import binding
+    w = synth.scaled_down(synth.config(2), 256, 512)
+    rng = np.random.default_rng(43)
+    weights = [(rng.standard_normal(sh) * np.sqrt(2.0 / sh[1])).astype(np.float32) for sh in w.shapes]
+    sess, ratios = _gpu_dynamic_ratios(w.shapes, weights, 0.02)
+    assert ratios == oracle.dynamic_ratios(weights, 0.02)
+    sess.set_ratios(ratios)                            # (output buffers grow with the new capacities)
+    grads = synth.gradients(w, 0)
+    sess.set_grad(grads)
+    sess.compress()
+    torch.cuda.synchronize()
+    res = sess.results()
+    gpu_r = sess.unpack(sess.residual)
+    for l, sh in enumerate(w.shapes):
+        o = oracle.compress_layer(grads[l], np.zeros(sh, np.float32), w.p, w.alpha, ratios[l])
+        gi, gv, gc, gn = res[l]
+        assert sess.plan.layer_k(l) == o.k
+        parity.check_layer(f"dynamic[l={l}]", sh, w.p, o.k, o.tau, o.nsi, o.centres, o.idx, o.val, o.r_new,
+                           o.v, gi, gv, gc, gn, gpu_r[l])
+
+
 def test_config0_single_layer_512(in_place):
     w = synth.config(0)
     n, ex = run_and_check(w.shapes, [w.p], w.alpha, w.ratios, [synth.gradients(w, 0)], w.name,
