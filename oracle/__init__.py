@@ -78,6 +78,9 @@ def _load():
     lib.rsdgc_oracle_dynamic_ratios.argtypes = [fp, ctypes.POINTER(i64), ctypes.c_int32, f64,
                                                 ctypes.POINTER(f64)]
     lib.rsdgc_oracle_dynamic_ratios.restype = c_int
+    lib.rsdgc_oracle_apply.argtypes = [fp, i64, ctypes.c_int32, ctypes.POINTER(u32p), ctypes.POINTER(fp),
+                                       ctypes.POINTER(i64), c_float]
+    lib.rsdgc_oracle_apply.restype = c_int
     _lib = lib
     return lib
 
@@ -308,6 +311,26 @@ def dynamic_ratios(weights: Sequence[np.ndarray], rho: float) -> List[float]:
     if rc != 0:
         raise MemoryError("oracle ran out of memory")
     return [float(x) for x in out]
+
+
+def apply_messages(w, messages: Sequence[Tuple[np.ndarray, np.ndarray]], eta: float) -> np.ndarray:
+    """Eq. 12, third line, for one layer: w - eta * (sum of the messages, first message first).
+    messages: (idx uint32, val float32) per node.  Returns the new weights; w is not modified."""
+    w_new = _f32(w).copy()
+    flat = w_new.reshape(-1)
+    n = len(messages)
+    idxs = [np.ascontiguousarray(m[0], dtype=np.uint32) for m in messages]
+    vals = [np.ascontiguousarray(m[1], dtype=np.float32) for m in messages]
+    for i, v in zip(idxs, vals):
+        assert i.size == v.size and (i.size == 0 or int(i.max()) < flat.size)
+    pad_i, pad_v = np.zeros(1, np.uint32), np.zeros(1, np.float32)
+    ip = (ctypes.POINTER(ctypes.c_uint32) * max(n, 1))(*[_p(i if i.size else pad_i, ctypes.c_uint32) for i in idxs])
+    vp = (ctypes.POINTER(ctypes.c_float) * max(n, 1))(*[_p(v if v.size else pad_v, ctypes.c_float) for v in vals])
+    cnt = (ctypes.c_int64 * max(n, 1))(*[i.size for i in idxs])
+    rc = _load().rsdgc_oracle_apply(_p(flat, ctypes.c_float), flat.size, n, ip, vp, cnt, float(eta))
+    if rc != 0:
+        raise MemoryError("oracle ran out of memory")
+    return w_new
 
 
 def compress_model(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray], p: int,

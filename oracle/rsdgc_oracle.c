@@ -22,6 +22,11 @@
  * and step 7 also restarts u from zero where v was sent (the masking of the
  * method Eq. 12 is taken from).
  *
+ * The receiving side of one iteration (Eq. 12, third line):
+ *   step 9  S = sum over the nodes' messages of sparse(v_k), accumulated in
+ *           message order with binary32 adds; w = w - eta * S (one binary32
+ *           multiply, one binary32 subtract).
+ *
  * Once per epoch (Section III-B, Algorithm 1's outer loop) the per-layer keep
  * ratios come from the weights:
  *   step D  mu = |w| (Eq. 3); rank all weights of the network together; the
@@ -378,5 +383,27 @@ int rsdgc_oracle_dynamic_ratios(const float *w_all, const int64_t *off, int32_t 
         ratio_out[l] = Gl > 0 ? (double)kept[l] / (double)Gl : 0.0;
     }
     free(it); free(kept);
+    return 0;
+}
+
+/* ---------------------------------------------------------------- step 9 */
+/* Eq. 12, third line, for one layer: the messages of n_msgs nodes are summed
+ * into a dense sum (message 0 first), then w <- w - eta * sum.              */
+int rsdgc_oracle_apply(float *w, int64_t G, int32_t n_msgs, const uint32_t *const *idx,
+                       const float *const *val, const int64_t *n, float eta)
+{
+    float *sum = (float *)malloc((size_t)(G > 0 ? G : 1) * sizeof(float));
+    if (!sum)
+        return -1;
+    for (int64_t i = 0; i < G; ++i)
+        sum[i] = 0.0f;
+    for (int32_t k = 0; k < n_msgs; ++k)
+        rsdgc_oracle_decompress(idx[k], val[k], n[k], sum, G, 1);
+    for (int64_t i = 0; i < G; ++i) {
+        volatile float step = eta * sum[i];
+        volatile float wn = w[i] - step;
+        w[i] = wn;
+    }
+    free(sum);
     return 0;
 }

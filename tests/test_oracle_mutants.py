@@ -125,6 +125,11 @@ def battery(orc):
     check("dynamic_ratios", orc.dynamic_ratios(ws, 0.2) == [kept[l] / ws[l].size for l in range(3)])
     ones = [np.ones((2, 5), np.float32), -np.ones((3, 4), np.float32)]
     check("dynamic_ties", orc.dynamic_ratios(ones, 13 / 22) == [1.0, 3 / 12])
+    # Eq. 12, third line
+    w10 = np.arange(10, dtype=np.float32)
+    m1 = (np.array([1, 3], np.uint32), np.array([1.0, 2.0], np.float32))
+    m2 = (np.array([3, 9], np.uint32), np.array([0.5, -4.0], np.float32))
+    check("apply", orc.apply_messages(w10, [m1, m2], 0.5).tolist() == [0, 0.5, 2, 1.75, 4, 5, 6, 7, 8, 11])
     d2 = np.ones(10, np.float32)
     orc.decompress(np.array([2, 5], np.uint32), np.array([0.5, -1.0], np.float32), 10, dense=d2, accumulate_into=True)
     check("decompress_acc", d2.tolist() == [1, 1, 1.5, 1, 1, 0, 1, 1, 1, 1])
@@ -166,6 +171,10 @@ MUTANTS = [
     ("dynamic_ties_to_later_layer", "if (p->layer < q->layer) return -1;\n    if (p->layer > q->layer) return 1;",
      "if (p->layer < q->layer) return 1;\n    if (p->layer > q->layer) return -1;", 0),
     ("dynamic_ratio_of_network", "(double)kept[l] / (double)Gl", "(double)kept[l] / (double)N", 0),
+    ("apply_adds_the_step", "volatile float wn = w[i] - step;", "volatile float wn = w[i] + step;", 0),
+    ("apply_scales_the_weight", "volatile float step = eta * sum[i];", "volatile float step = eta * w[i];", 0),
+    ("apply_keeps_last_message_only", "rsdgc_oracle_decompress(idx[k], val[k], n[k], sum, G, 1);",
+     "rsdgc_oracle_decompress(idx[k], val[k], n[k], sum, G, 0);", 0),
     ("momentum_not_masked", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = u_new[i];", 0),
     ("momentum_masked_where_kept_out", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = mask[i] ? u_new[i] : 0.0f;", 0),
 ]

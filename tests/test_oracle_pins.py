@@ -461,3 +461,54 @@ def test_dynamic_ratios_closed_forms_and_tie_order():
         assert r0 >= prev and abs(r0 * 900 + r1 * 900 - 180) < 1e-9
         prev = r0
     assert oracle.dynamic_ratios([x, y * np.float32(1.0)], 0.1)[0] == oracle.dynamic_ratios([x, y], 0.1)[0]
+
+
+# ------------------------------------------------- receiving side (Eq. 12, third line)
+def test_apply_messages_is_w_minus_eta_times_the_ordered_sum():
+    rng = np.random.default_rng(51)
+    G = 5000
+    w = rng.standard_normal(G).astype(np.float32)
+    msgs = []
+    for k in range(4):
+        idx = np.sort(rng.choice(G, size=700, replace=False)).astype(np.uint32)
+        msgs.append((idx, (rng.standard_normal(700) * 10.0 ** rng.uniform(-3, 1)).astype(np.float32)))
+    eta = np.float32(0.1)
+    got = oracle.apply_messages(w, msgs, 0.1)
+    total = np.zeros(G, dtype=np.float32)
+    for idx, val in msgs:                                  # numpy float32: one rounded add per message
+        total[idx] = total[idx] + val
+    assert np.array_equal(got, w - eta * total)            # one rounded product, one rounded difference
+    touched = np.zeros(G, dtype=bool)
+    for idx, _ in msgs:
+        touched[idx] = True
+    assert np.array_equal(got[~touched].view(np.uint32), w[~touched].view(np.uint32))   # untouched bits survive
+    # the order of the messages is the order of the float32 adds
+    rev = oracle.apply_messages(w, msgs[::-1], 0.1)
+    both = np.zeros(G, dtype=np.float32)
+    for idx, val in msgs[::-1]:
+        both[idx] = both[idx] + val
+    assert np.array_equal(rev, w - eta * both)
+    assert np.any(rev != got), "the data must tell the two summation orders apart"
+
+
+def test_apply_messages_small_cases():
+    w = np.arange(10, dtype=np.float32)
+    m1 = (np.array([1, 3], np.uint32), np.array([1.0, 2.0], np.float32))
+    m2 = (np.array([3, 9], np.uint32), np.array([0.5, -4.0], np.float32))
+    assert oracle.apply_messages(w, [m1, m2], 0.5).tolist() == [0, 0.5, 2, 1.75, 4, 5, 6, 7, 8, 11]
+    assert oracle.apply_messages(w, [], 0.5).tolist() == w.tolist()
+    assert oracle.apply_messages(w, [m1], 0.0).tolist() == w.tolist()
+    neg0 = np.array([-0.0, 1.0], np.float32)
+    out = oracle.apply_messages(neg0, [(np.array([1], np.uint32), np.array([0.0], np.float32))], 1.0)
+    assert np.array_equal(out.view(np.uint32), neg0.view(np.uint32))
+    # one iteration end to end on one layer, two nodes: what is applied is what the nodes sent
+    rng = np.random.default_rng(52)
+    ww = rng.standard_normal((20, 30)).astype(np.float32)
+    sent = []
+    dense = np.zeros(600, np.float32)
+    for k in range(2):
+        g = (rng.standard_normal((20, 30)) * 1e-2).astype(np.float32)
+        res = oracle.compress_layer(g, np.zeros_like(g), 3, 0.5, 0.1)
+        sent.append((res.idx, res.val))
+        dense = oracle.decompress(res.idx, res.val, 600, dense=dense, accumulate_into=True)
+    assert np.array_equal(oracle.apply_messages(ww, sent, 0.25).ravel(), ww.ravel() - np.float32(0.25) * dense)
