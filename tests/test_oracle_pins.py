@@ -470,8 +470,8 @@ def test_apply_messages_is_w_minus_eta_times_the_ordered_sum():
     w = rng.standard_normal(G).astype(np.float32)
     msgs = []
     for k in range(4):
-        idx = np.sort(rng.choice(G, size=700, replace=False)).astype(np.uint32)
-        msgs.append((idx, (rng.standard_normal(700) * 10.0 ** rng.uniform(-3, 1)).astype(np.float32)))
+        idx = np.sort(rng.choice(G, size=3000, replace=False)).astype(np.uint32)   # most positions get 2-3 messages
+        msgs.append((idx, (rng.standard_normal(3000) * 10.0 ** rng.uniform(-1, 1)).astype(np.float32)))
     eta = np.float32(0.1)
     got = oracle.apply_messages(w, msgs, 0.1)
     total = np.zeros(G, dtype=np.float32)
