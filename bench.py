@@ -174,6 +174,18 @@ def main() -> int:
         torch.cuda.synchronize()
         decompress_ms[name] = (time.perf_counter() - t2) / 20 * 1e3
     del dense
+    # the receiving side (Eq. 12, third line): eight nodes' messages (eight times this node's own)
+    # summed and applied to a weights arena
+    w_arena = torch.randn(sess.grad.numel(), dtype=torch.float32, device="cuda")
+    peers = [(sess.out_idx, sess.out_val, sess.out_counts)] * 8
+    binding.rsdgc_apply(sess.plan, peers, w_arena, 0.1, sess.workspace, stream)
+    torch.cuda.synchronize()
+    t4 = time.perf_counter()
+    for _ in range(20):
+        binding.rsdgc_apply(sess.plan, peers, w_arena, 0.1, sess.workspace, stream)
+    torch.cuda.synchronize()
+    apply_ms = (time.perf_counter() - t4) / 20 * 1e3
+    del w_arena
     # the per-epoch step (Eqs. 3-5): keep ratios from a weights arena (synthetic N(0, 0.05^2) weights)
     weights = torch.randn(sess.grad.numel(), dtype=torch.float32, device="cuda") * 0.05
     binding.rsdgc_dynamic_ratios(sess.plan, weights, 0.02, sess.workspace, stream)
@@ -230,6 +242,7 @@ def main() -> int:
         "roofline": roofline,
         "stages_ms": {k: round(v, 5) for k, v in stages.items()},
         "decompress_ms": {k: round(v, 5) for k, v in decompress_ms.items()},
+        "apply_8_messages_ms": round(apply_ms, 5),
         "dynamic_ratios_ms": round(dynamic_ratios_ms, 5),
         "stages_recorded_calls": n_rec,
         "ms_per_step_with_stage_events": (dt_events / args.steps * 1e3) if dt_events else None,

@@ -191,6 +191,25 @@ int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
                      const int32_t *counts, float *dense, int accumulate,
                      void *workspace, void *stream);
 
+/* The receiving side of an iteration (Eq. 12, third line):
+ *   w <- w - eta * sum_k sparse(v_k)
+ * for the messages of n_msgs nodes, each as produced by rsdgc_compress with a
+ * plan of the same shapes and ratios.  The messages are summed in the order
+ * given (float32 adds), the step is one float32 multiply and one float32
+ * subtract; weights at positions no message names are not touched.  Only the
+ * named positions are visited: the cost is proportional to the messages, not
+ * to the model.
+ *   idx, val, counts  [host] arrays of n_msgs device pointers (1 <= n_msgs <=
+ *                     RSDGC_MAX_MSGS); message k is idx[k], val[k], counts[k].
+ *   weights           [device, in/out] float32 arena laid out like the gradient.
+ * Uses an accumulator inside the workspace that is all zero between calls (it is
+ * cleared on the first call with a workspace); must not overlap another call
+ * that uses the same workspace.                                              */
+#define RSDGC_MAX_MSGS 64
+int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
+                const float *const *val, const int32_t *const *counts, float *weights,
+                float eta, void *workspace, void *stream);
+
 /* ------------------------------------------------------------ profiling --
  * Per-stage GPU time of rsdgc_compress, measured with HIP events recorded on the
  * caller's stream between the stages.  rsdgc_profile_begin creates the events for up

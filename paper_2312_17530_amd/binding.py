@@ -21,7 +21,7 @@ EXPORTS = [
     "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
-    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_nsi", "rsdgc_decompress",
+    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_nsi", "rsdgc_decompress",
     "rsdgc_last_paths", "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
 ]
@@ -86,6 +86,9 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_compress_momentum.restype = ctypes.c_int
     lib.rsdgc_dynamic_ratios.argtypes = [vp, vp, f64, ctypes.POINTER(f64), vp, vp]
     lib.rsdgc_dynamic_ratios.restype = ctypes.c_int
+    lib.rsdgc_apply.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+                                ctypes.c_float, vp, vp]
+    lib.rsdgc_apply.restype = ctypes.c_int
     lib.rsdgc_nsi.argtypes = [vp] * 6
     lib.rsdgc_nsi.restype = ctypes.c_int
     lib.rsdgc_decompress.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
@@ -231,6 +234,18 @@ def rsdgc_dynamic_ratios(plan: Plan, weights, global_ratio: float, workspace, st
     _check(load().rsdgc_dynamic_ratios(plan.handle, _ptr(weights), float(global_ratio), out,
                                        _ptr(workspace), _stream(stream)), "rsdgc_dynamic_ratios")
     return [float(x) for x in out]
+
+
+def rsdgc_apply(plan: Plan, messages, weights, eta: float, workspace, stream=None) -> None:
+    """Eq. 12, third line: weights -= eta * (sum of the messages, in order).
+    messages: sequence of (idx, val, counts) device tensors as written by rsdgc_compress."""
+    n = len(messages)
+    arr = ctypes.c_void_p * max(n, 1)
+    idx = arr(*[_ptr(m[0]) for m in messages])
+    val = arr(*[_ptr(m[1]) for m in messages])
+    cnt = arr(*[_ptr(m[2]) for m in messages])
+    _check(load().rsdgc_apply(plan.handle, n, idx, val, cnt, _ptr(weights), float(eta), _ptr(workspace),
+                              _stream(stream)), "rsdgc_apply")
 
 
 def rsdgc_nsi(plan: Plan, grad, residual, nsi_out, workspace, stream=None) -> None:

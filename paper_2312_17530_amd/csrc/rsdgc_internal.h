@@ -156,6 +156,7 @@ struct WsLayout {
     size_t list2_ent = 0;    // uint64[n_layers][kList2Cap]  keys sharing the first two digits
     size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
     size_t dyn = 0;          // scratch of rsdgc_dynamic_ratios: DynState, uint64[kHistBins], uint32[2 * n_layers]
+    size_t acc = 0;          // float[total_elems]  sum of the nodes' messages (rsdgc_apply); all zero between calls
     size_t total = 0;
 };
 
@@ -198,6 +199,7 @@ struct rsdgc_plan_s {
     uint64_t version = 1;               // bumped by set_ratios
     const void *uploaded_ws = nullptr;
     uint64_t uploaded_version = 0;
+    const void *acc_zero_ws = nullptr;  // workspace whose message accumulator is known to be all zero
     bool allow_candidates = true;       // false forces the full-map path for every layer
     // optional per-stage timing: (RSDGC_N_STAGES + 1) events per recorded call (hipEvent_t)
     std::vector<void *> prof_events;

@@ -1558,6 +1558,44 @@ __global__ __launch_bounds__(256) void k_scatter(const LayerDev *__restrict__ la
     if (accumulate) *d = *d + val[j]; else *d = val[j];
 }
 
+// ---------------------------------------------------------------- apply --
+// Eq. 12, third line.  The messages have been summed into the accumulator (k_scatter,
+// message by message).  One thread per pair of every message: whoever exchanges a non-zero
+// sum out of the accumulator applies it to the weight (the others find +0 there), so each
+// named position is updated exactly once and the accumulator is all zero again afterwards.
+struct ApplyMsgs {
+    const uint32_t *idx[RSDGC_MAX_MSGS];
+    const int32_t *counts[RSDGC_MAX_MSGS];
+};
+
+__global__ __launch_bounds__(256) void k_apply(const LayerDev *__restrict__ layers, int n_layers,
+                                               long long capacity, const ApplyMsgs msgs,
+                                               float *__restrict__ acc, float *__restrict__ weights,
+                                               float eta) {
+    const long long j = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+    if (j >= capacity) return;
+    const int k = blockIdx.y;
+    int lo = 0, hi = n_layers;            // last layer whose segment starts at or before j
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (layers[mid].out_off <= j) lo = mid; else hi = mid;
+    }
+    const LayerDev L = layers[lo];
+    const long long q = j - L.out_off;
+    if (q >= msgs.counts[k][lo] || q >= static_cast<long long>(L.cap)) return;
+    const uint32_t i = msgs.idx[k][j];
+    if (i >= L.G) return;                 // malformed message: ignore the pair (k_scatter did too)
+    const size_t pos = static_cast<size_t>(L.elem_off) + i;
+    const float s = atomicExch(&acc[pos], 0.f);
+    if (__float_as_uint(s) != 0u) weights[pos] = weights[pos] - __fmul_rn(eta, s);
+}
+
+__global__ __launch_bounds__(256) void k_fill_zero(uint4 *__restrict__ p, size_t n16) {
+    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride)
+        p[i] = make_uint4(0, 0, 0, 0);
+}
+
 // ------------------------------------------------------- dynamic ratios --
 // Section III-B, Eqs. 3-5: one ranking of mu = |w| over all layers; the K top-ranked weights
 // survive and a layer's keep ratio is its share of survivors.  The K-th largest 31-bit key
@@ -1997,6 +2035,44 @@ int rsdgc_compress_momentum(rsdgc_plan_t *plan, const float *grad, const float *
     mom.m = m;
     return compress_impl(plan, grad, mom, residual, residual_out, out_idx, out_val, out_counts,
                          out_centre_idx, out_centre_counts, workspace, stream);
+}
+
+int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
+                const float *const *val, const int32_t *const *counts, float *weights, float eta,
+                void *workspace, void *stream_) {
+    if (!plan || !idx || !val || !counts || !weights || !workspace) return RSDGC_EINVAL;
+    if (n_msgs < 1 || n_msgs > RSDGC_MAX_MSGS || !(eta == eta)) return RSDGC_EINVAL;
+    if (!aligned256(workspace) || !aligned16(weights)) return RSDGC_EINVAL;
+    for (int k = 0; k < n_msgs; ++k)
+        if (!idx[k] || !val[k] || !counts[k]) return RSDGC_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    char *ws = static_cast<char *>(workspace);
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+    const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
+    float *acc = reinterpret_cast<float *>(ws + plan->ws.acc);
+    if (plan->out_capacity == 0) return RSDGC_OK;      // no message can hold a pair
+    if (plan->acc_zero_ws != workspace) {              // first use of this workspace: clear the accumulator
+        const size_t n16 = static_cast<size_t>(plan->total_elems) * sizeof(float) / 16;
+        hipLaunchKernelGGL(k_fill_zero, dim3(kNumCUs * 8u), dim3(256), 0, stream,
+                           reinterpret_cast<uint4 *>(acc), n16);
+        HIP_TRY(hipGetLastError());
+    }
+    plan->acc_zero_ws = nullptr;                       // not known to be zero until the apply kernel is enqueued
+    const unsigned blocks = static_cast<unsigned>((plan->out_capacity + 255) / 256);
+    ApplyMsgs m;
+    std::memset(&m, 0, sizeof(m));
+    for (int k = 0; k < n_msgs; ++k) {                 // the sum, message by message, in the order given
+        hipLaunchKernelGGL(k_scatter, dim3(blocks), dim3(256), 0, stream, layers, plan->n_layers,
+                           static_cast<long long>(plan->out_capacity), idx[k], val[k], counts[k], acc, 1);
+        m.idx[k] = idx[k];
+        m.counts[k] = counts[k];
+    }
+    hipLaunchKernelGGL(k_apply, dim3(blocks, static_cast<unsigned>(n_msgs)), dim3(256), 0, stream, layers,
+                       plan->n_layers, static_cast<long long>(plan->out_capacity), m, acc, weights, eta);
+    HIP_TRY(hipGetLastError());
+    plan->acc_zero_ws = workspace;
+    return RSDGC_OK;
 }
 
 int rsdgc_dynamic_ratios(rsdgc_plan_t *plan, const float *weights, double global_ratio,

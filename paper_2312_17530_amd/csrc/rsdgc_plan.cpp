@@ -181,6 +181,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.list2_ent = off;    off = align_up(off + sizeof(uint64_t) * kList2Cap * size_t(L), A);
     w.nsi = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
     w.dyn = off;          off = align_up(off + 256 + sizeof(uint64_t) * kHistBins + sizeof(uint32_t) * 2 * size_t(L), A);
+    w.acc = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
     w.total = off;
 
     plan->table.assign(w.table_bytes, 0);

@@ -180,6 +180,33 @@ def test_dynamic_ratios_at_vgg19_size_against_a_library_partition():
         assert got == want, rho
 
 
+def test_apply_at_vgg19_size_four_equal_messages():
+    """Eq. 12, third line, at full size: four copies of one node's message sum to exactly 4 x val
+    (a power of two), so the expected weights are w - eta * (4 val) at the named positions and w
+    elsewhere, formed here with numpy."""
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import Session
+    w = synth.config(3)
+    sess = Session(w.shapes, w.p, w.alpha, w.ratios, want_centres=False)
+    sess.set_grad(synth.gradients(w, 0))
+    sess.compress()
+    torch.cuda.synchronize()
+    msg = (sess.out_idx, sess.out_val, sess.out_counts)
+    w_dev = torch.randn(sess.grad.numel(), dtype=torch.float32, device="cuda")
+    before = sess.unpack(w_dev)
+    eta = 0.125
+    for rnd in range(2):                                   # the second round meets the accumulator the first left
+        binding.rsdgc_apply(sess.plan, [msg] * 4, w_dev, eta, sess.workspace)
+    torch.cuda.synchronize()
+    after = sess.unpack(w_dev)
+    for l, (idx, val, _, _) in enumerate(sess.results()):
+        want = before[l].reshape(-1).copy()
+        step = np.float32(eta) * (np.float32(4.0) * val)
+        want[idx] = (want[idx] - step) - step
+        assert np.array_equal(after[l].reshape(-1).view(np.uint32), want.view(np.uint32)), l
+
+
 def test_fc6_stress_p5_student_t_against_oracle_then_one_carried_iteration():
     w, n_exact = _run(4, extra_iterations=1)
     assert n_exact == 1

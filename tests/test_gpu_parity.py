@@ -224,6 +224,41 @@ def test_dynamic_ratios_feed_the_plan():
                            o.v, gi, gv, gc, gn, gpu_r[l])
 
 
+def test_apply_messages_of_three_nodes_matches_the_oracle():
+    """Eq. 12, third line: three nodes compress their own gradients (one GPU plays all three in
+    turn); the receiving side sums their messages in order and steps the weights.  Two rounds, so
+    the second one runs on the accumulator the first one left behind."""
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import Session
+    shapes = [(1, 40), (33, 129), (200, 45), (64, 256), (300, 700), (7, 1000)]
+    p_list = [3, 3, 5, 3, 3, 7]
+    ratios = [0.5, 0.05, 0.1, 0.2, 0.02, 0.3]
+    sess = Session(shapes, 3, 0.5, ratios, p_list)
+    rng = np.random.default_rng(61)
+    weights = [rng.standard_normal(sh).astype(np.float32) for sh in shapes]
+    w_dev = torch.empty_like(sess.grad)
+    sess.pack(weights, w_dev)
+    eta = 0.05
+    for rnd in range(2):
+        msgs_dev, msgs_host = [], []
+        for node in range(3):
+            grads = [synth.layer_gradient(sh, 1e-2, 70 + node, rnd, l) for l, sh in enumerate(shapes)]
+            sess.set_grad(grads)
+            sess.residual.zero_()
+            sess.compress()
+            torch.cuda.synchronize()
+            msgs_dev.append((sess.out_idx.clone(), sess.out_val.clone(), sess.out_counts.clone()))
+            msgs_host.append([(i.copy(), v.copy()) for i, v, _, _ in sess.results()])
+        binding.rsdgc_apply(sess.plan, msgs_dev, w_dev, eta, sess.workspace)
+        torch.cuda.synchronize()
+        got = sess.unpack(w_dev)
+        for l, sh in enumerate(shapes):
+            want = oracle.apply_messages(weights[l], [m[l] for m in msgs_host], eta)
+            assert np.array_equal(got[l].view(np.uint32), want.view(np.uint32)), (rnd, l)
+        weights = got
+
+
 def test_config0_single_layer_512(in_place):
     w = synth.config(0)
     n, ex = run_and_check(w.shapes, [w.p], w.alpha, w.ratios, [synth.gradients(w, 0)], w.name,
