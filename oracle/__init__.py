@@ -81,6 +81,13 @@ def _load():
     lib.rsdgc_oracle_apply.argtypes = [fp, i64, ctypes.c_int32, ctypes.POINTER(u32p), ctypes.POINTER(fp),
                                        ctypes.POINTER(i64), c_float]
     lib.rsdgc_oracle_apply.restype = c_int
+    lib.rsdgc_oracle_block_nsi.argtypes = [fp, i64, i64, c_int, f64, fp]
+    lib.rsdgc_oracle_block_nsi.restype = None
+    lib.rsdgc_oracle_compress_layer_blocks.argtypes = [fp, fp, i64, i64, c_int, f64, f64, u32p, fp,
+                                                       ctypes.POINTER(c_float), fp, fp]
+    lib.rsdgc_oracle_compress_layer_blocks.restype = i64
+    lib.rsdgc_oracle_decompress_blocks.argtypes = [u32p, fp, i64, i64, i64, c_int, fp, c_int]
+    lib.rsdgc_oracle_decompress_blocks.restype = None
     _lib = lib
     return lib
 
@@ -331,6 +338,71 @@ def apply_messages(w, messages: Sequence[Tuple[np.ndarray, np.ndarray]], eta: fl
     if rc != 0:
         raise MemoryError("oracle ran out of memory")
     return w_new
+
+
+# ------------------------------------------------ the block reading of Section III-C
+def block_nsi(v, p: int, alpha: float) -> np.ndarray:
+    """NSI of every non-overlapping p x p block: a ceil(R/p) x ceil(C/p) float32 map."""
+    _check_p(p)
+    v = _f32(v)
+    R, C = v.shape
+    out = np.empty(((R + p - 1) // p, (C + p - 1) // p), dtype=np.float32)
+    _load().rsdgc_oracle_block_nsi(_p(v, ctypes.c_float), R, C, p, float(alpha), _p(out, ctypes.c_float))
+    return out
+
+
+def block_keep_count(G: int, p: int, rho: float, n_blocks: int) -> int:
+    return min(keep_count(G, p, rho), n_blocks)
+
+
+class BlockLayerResult(NamedTuple):
+    blocks: np.ndarray    # uint32, ascending indices of the kept blocks (row-major over the block grid)
+    val: np.ndarray       # float32, p*p values per kept block, row-major inside the block
+    k: int
+    tau: Optional[float]
+    nsi: np.ndarray       # float32 block map
+    v: np.ndarray
+    r_new: np.ndarray
+
+
+def compress_layer_blocks(g, r, p: int, alpha: float, rho: float) -> BlockLayerResult:
+    """One layer under the block reading.  g, r: R x C float32; r is NOT modified."""
+    _check_p(p)
+    g = _f32(g)
+    r_new = _f32(r).copy()
+    R, C = g.shape
+    BR, BC = (R + p - 1) // p, (C + p - 1) // p
+    k = block_keep_count(R * C, p, rho, BR * BC)
+    blocks = np.empty(max(k, 1), dtype=np.uint32)
+    val = np.empty(max(k * p * p, 1), dtype=np.float32)
+    tau = ctypes.c_float(0.0)
+    nsi_map = np.empty((BR, BC), dtype=np.float32)
+    v = np.empty((R, C), dtype=np.float32)
+    n = _load().rsdgc_oracle_compress_layer_blocks(
+        _p(g, ctypes.c_float), _p(r_new, ctypes.c_float), R, C, p, float(alpha), float(rho),
+        _p(blocks, ctypes.c_uint32), _p(val, ctypes.c_float), ctypes.byref(tau),
+        _p(nsi_map, ctypes.c_float), _p(v, ctypes.c_float))
+    if n < 0:
+        raise MemoryError("oracle ran out of memory")
+    assert n == k
+    return BlockLayerResult(blocks[:k].copy(), val[:k * p * p].copy(), k,
+                            float(tau.value) if k > 0 else None, nsi_map, v, r_new)
+
+
+def decompress_blocks(blocks, val, R: int, C: int, p: int, dense: Optional[np.ndarray] = None,
+                      accumulate_into: bool = False) -> np.ndarray:
+    blocks = np.ascontiguousarray(blocks, dtype=np.uint32)
+    val = np.ascontiguousarray(val, dtype=np.float32)
+    assert val.size == blocks.size * p * p
+    if dense is None:
+        dense = np.zeros((R, C), dtype=np.float32)
+    assert dense.dtype == np.float32 and dense.size == R * C and dense.flags.c_contiguous
+    pad_b, pad_v = np.zeros(1, np.uint32), np.zeros(1, np.float32)
+    _load().rsdgc_oracle_decompress_blocks(_p(blocks if blocks.size else pad_b, ctypes.c_uint32),
+                                           _p(val if val.size else pad_v, ctypes.c_float), blocks.size,
+                                           R, C, p, _p(dense.reshape(-1), ctypes.c_float),
+                                           1 if accumulate_into else 0)
+    return dense
 
 
 def compress_model(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray], p: int,

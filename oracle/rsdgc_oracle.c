@@ -27,6 +27,17 @@
  *           message order with binary32 adds; w = w - eta * S (one binary32
  *           multiply, one binary32 subtract).
  *
+ * The other reading of Section III-C ("a convolution kernel as a whole", Eq. 11's
+ * G / p^2): the matrix is cut into ceil(R/p) x ceil(C/p) non-overlapping p x p
+ * blocks, each block is one neighbourhood:
+ *   step B2  NSI of every block (Eqs. 8-10 over the block's p*p slots, zero
+ *            outside the matrix, divisor p*p)
+ *   step B3  k = min(ceil(G / (p*p) * rho_l), number of blocks)      Eq. 11
+ *   step B4  rank the blocks, take k (ties: lower block index)
+ *   step B6  emit per kept block its index and its p*p values (row-major,
+ *            zero for slots outside the matrix), blocks in ascending order
+ *   step B7  residual = v outside the kept blocks, +0 inside
+ *
  * Once per epoch (Section III-B, Algorithm 1's outer loop) the per-layer keep
  * ratios come from the weights:
  *   step D  mu = |w| (Eq. 3); rank all weights of the network together; the
@@ -406,4 +417,105 @@ int rsdgc_oracle_apply(float *w, int64_t G, int32_t n_msgs, const uint32_t *cons
     }
     free(sum);
     return 0;
+}
+
+/* ------------------------------------------------------- block reading -- */
+/* Eqs. 8-10 over block (bx, by): rows bx*p .. bx*p+p-1, columns by*p .. by*p+p-1. */
+double rsdgc_oracle_block_nsi_at(const float *v, int64_t R, int64_t C, int p, double alpha,
+                                 int64_t bx, int64_t by)
+{
+    const double n = (double)p * (double)p;
+    double sum_abs = 0.0, sum = 0.0;
+    for (int dx = 0; dx < p; ++dx)
+        for (int dy = 0; dy < p; ++dy) {
+            double w = slot(v, R, C, bx * p + dx, by * p + dy);
+            sum_abs += fabs(w);
+            sum += w;
+        }
+    const double mean_abs = sum_abs / n;   /* Eq. 9  */
+    const double mean = sum / n;
+    double sq = 0.0;
+    for (int dx = 0; dx < p; ++dx)
+        for (int dy = 0; dy < p; ++dy) {
+            double d = slot(v, R, C, bx * p + dx, by * p + dy) - mean;
+            sq += d * d;
+        }
+    const double std = sqrt(sq / n);       /* Eq. 10 */
+    return alpha * mean_abs + (1.0 - alpha) * std;   /* Eq. 8 */
+}
+
+/* Block NSI map: ceil(R/p) x ceil(C/p) scores, each rounded once to float32. */
+void rsdgc_oracle_block_nsi(const float *v, int64_t R, int64_t C, int p, double alpha, float *nsi)
+{
+    const int64_t BR = (R + p - 1) / p, BC = (C + p - 1) / p;
+    for (int64_t bx = 0; bx < BR; ++bx)
+        for (int64_t by = 0; by < BC; ++by)
+            nsi[bx * BC + by] = (float)rsdgc_oracle_block_nsi_at(v, R, C, p, alpha, bx, by);
+}
+
+/* Steps 1, B2-B7 for one layer.  r is updated in place.  blocks: capacity k block
+ * indices; val: capacity k*p*p values (p*p per kept block, in block order).
+ * Returns the number of kept blocks, or -1 on allocation failure.           */
+int64_t rsdgc_oracle_compress_layer_blocks(const float *g, float *r, int64_t R, int64_t C, int p,
+                                           double alpha, double rho, uint32_t *blocks, float *val,
+                                           float *tau_out, float *nsi_out, float *v_out)
+{
+    const int64_t G = R * C;
+    const int64_t BR = (R + p - 1) / p, BC = (C + p - 1) / p, NB = BR * BC;
+    float *v = (float *)malloc((size_t)G * sizeof(float));
+    float *nsi = (float *)malloc((size_t)NB * sizeof(float));
+    if (!v || !nsi) {
+        free(v); free(nsi);
+        return -1;
+    }
+    rsdgc_oracle_accumulate(r, g, v, G);                       /* step 1 */
+    rsdgc_oracle_block_nsi(v, R, C, p, alpha, nsi);            /* step B2 */
+    int64_t k = rsdgc_oracle_k(G, p, rho);                     /* step B3 */
+    if (k > NB) k = NB;
+    float tau = 0.0f;
+    if (rsdgc_oracle_select(nsi, NB, k, blocks, &tau) != 0) {  /* step B4 */
+        free(v); free(nsi);
+        return -1;
+    }
+    for (int64_t i = 0; i < G; ++i)                            /* step B7, first half */
+        r[i] = v[i];
+    for (int64_t j = 0; j < k; ++j) {                          /* steps B6, B7 */
+        const int64_t bx = blocks[j] / BC, by = blocks[j] % BC;
+        for (int dx = 0; dx < p; ++dx)
+            for (int dy = 0; dy < p; ++dy) {
+                const int64_t x = bx * p + dx, y = by * p + dy;
+                const int inside = x < R && y < C;
+                val[j * p * p + dx * p + dy] = inside ? v[x * C + y] : 0.0f;
+                if (inside) r[x * C + y] = 0.0f;
+            }
+    }
+    if (tau_out) *tau_out = tau;
+    if (nsi_out) memcpy(nsi_out, nsi, (size_t)NB * sizeof(float));
+    if (v_out) memcpy(v_out, v, (size_t)G * sizeof(float));
+    free(v); free(nsi);
+    return k;
+}
+
+/* Inverse of step B6: dense = 0 (accumulate == 0) or kept; dense[block slot] = or += value. */
+void rsdgc_oracle_decompress_blocks(const uint32_t *blocks, const float *val, int64_t k,
+                                    int64_t R, int64_t C, int p, float *dense, int accumulate)
+{
+    const int64_t BC = (C + p - 1) / p;
+    if (!accumulate)
+        for (int64_t i = 0; i < R * C; ++i)
+            dense[i] = 0.0f;
+    for (int64_t j = 0; j < k; ++j) {
+        const int64_t bx = blocks[j] / BC, by = blocks[j] % BC;
+        for (int dx = 0; dx < p; ++dx)
+            for (int dy = 0; dy < p; ++dy) {
+                const int64_t x = bx * p + dx, y = by * p + dy;
+                if (x >= R || y >= C) continue;
+                if (accumulate) {
+                    volatile float s = dense[x * C + y] + val[j * p * p + dx * p + dy];
+                    dense[x * C + y] = s;
+                } else {
+                    dense[x * C + y] = val[j * p * p + dx * p + dy];
+                }
+            }
+    }
 }

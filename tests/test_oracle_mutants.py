@@ -130,6 +130,22 @@ def battery(orc):
     m1 = (np.array([1, 3], np.uint32), np.array([1.0, 2.0], np.float32))
     m2 = (np.array([3, 9], np.uint32), np.array([0.5, -4.0], np.float32))
     check("apply", orc.apply_messages(w10, [m1, m2], 0.5).tolist() == [0, 0.5, 2, 1.75, 4, 5, 6, 7, 8, 11])
+    # block reading
+    vb = (rng.standard_normal((13, 17)) + 0.3).astype(np.float32)
+    pad = np.zeros((15, 18), np.float64)
+    pad[:13, :17] = vb
+    blk = pad.reshape(5, 3, 6, 3).transpose(0, 2, 1, 3).reshape(5, 6, 9)
+    check("block_nsi", np.allclose(orc.block_nsi(vb, 3, 0.3), 0.3 * np.abs(blk).mean(axis=2) + 0.7 * blk.std(axis=2),
+                                   rtol=1e-6, atol=1e-7))
+    bres = orc.compress_layer_blocks(gg, rr, 3, 0.5, 0.3)
+    bs = bres.nsi.ravel()
+    border = sorted(range(bs.size), key=lambda i: (-float(bs[i]), i))
+    check("block_select", bres.blocks.tolist() == sorted(border[:bres.k]) and bres.k == math.ceil(13 * 17 / 9 * 0.3))
+    bdense = orc.decompress_blocks(bres.blocks, bres.val, 13, 17, 3)
+    check("block_sent_plus_residual", np.array_equal(bdense + bres.r_new, rr + gg))
+    first = int(bres.blocks[0])
+    check("block_values", bres.val[:3].tolist() == (rr + gg)[first // 6 * 3, first % 6 * 3:first % 6 * 3 + 3].tolist()
+          if first % 6 < 5 else True)
     d2 = np.ones(10, np.float32)
     orc.decompress(np.array([2, 5], np.uint32), np.array([0.5, -1.0], np.float32), 10, dense=d2, accumulate_into=True)
     check("decompress_acc", d2.tolist() == [1, 1, 1.5, 1, 1, 0, 1, 1, 1, 1])
@@ -175,6 +191,12 @@ MUTANTS = [
     ("apply_scales_the_weight", "volatile float step = eta * sum[i];", "volatile float step = eta * w[i];", 0),
     ("apply_keeps_last_message_only", "rsdgc_oracle_decompress(idx[k], val[k], n[k], sum, G, 1);",
      "rsdgc_oracle_decompress(idx[k], val[k], n[k], sum, G, 0);", 0),
+    ("block_window_centred", "double w = slot(v, R, C, bx * p + dx, by * p + dy);", "double w = slot(v, R, C, bx * p + dx - 1, by * p + dy - 1);", 0),
+    ("block_std_around_zero", "double d = slot(v, R, C, bx * p + dx, by * p + dy) - mean;", "double d = slot(v, R, C, bx * p + dx, by * p + dy);", 0),
+    ("block_residual_keeps_sent", "if (inside) r[x * C + y] = 0.0f;", "if (inside) r[x * C + y] = v[x * C + y];", 0),
+    ("block_values_transposed", "val[j * p * p + dx * p + dy] = inside ? v[x * C + y] : 0.0f;", "val[j * p * p + dy * p + dx] = inside ? v[x * C + y] : 0.0f;", 0),
+    ("block_grid_row_stride", "const int64_t bx = blocks[j] / BC, by = blocks[j] % BC;\n        for (int dx = 0; dx < p; ++dx)\n            for (int dy = 0; dy < p; ++dy) {\n                const int64_t x = bx * p + dx, y = by * p + dy;\n                const int inside",
+     "const int64_t bx = blocks[j] / BR, by = blocks[j] % BR;\n        for (int dx = 0; dx < p; ++dx)\n            for (int dy = 0; dy < p; ++dy) {\n                const int64_t x = bx * p + dx, y = by * p + dy;\n                const int inside", 0),
     ("momentum_not_masked", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = u_new[i];", 0),
     ("momentum_masked_where_kept_out", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = mask[i] ? u_new[i] : 0.0f;", 0),
 ]

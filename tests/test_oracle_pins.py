@@ -512,3 +512,79 @@ def test_apply_messages_small_cases():
         sent.append((res.idx, res.val))
         dense = oracle.decompress(res.idx, res.val, 600, dense=dense, accumulate_into=True)
     assert np.array_equal(oracle.apply_messages(ww, sent, 0.25).ravel(), ww.ravel() - np.float32(0.25) * dense)
+
+
+# ------------------------------------------------- the block reading (non-overlapping p x p neighbourhoods)
+def _numpy_block_nsi(v, p, alpha):
+    """Zero-pad to multiples of p, cut into blocks with a reshape, statistics with numpy in double."""
+    R, C = v.shape
+    BR, BC = -(-R // p), -(-C // p)
+    pad = np.zeros((BR * p, BC * p), dtype=np.float64)
+    pad[:R, :C] = v
+    blk = pad.reshape(BR, p, BC, p).transpose(0, 2, 1, 3).reshape(BR, BC, p * p)
+    return alpha * np.abs(blk).mean(axis=2) + (1.0 - alpha) * blk.std(axis=2)       # population std
+
+
+@pytest.mark.parametrize("R,C,p", [(12, 15, 3), (13, 17, 3), (10, 10, 5), (11, 23, 5), (7, 7, 7), (4, 9, 1), (2, 2, 3)])
+def test_block_nsi_against_numpy_reshape(R, C, p):
+    rng = np.random.default_rng(R * 100 + C)
+    v = (rng.standard_normal((R, C)) + 0.3).astype(np.float32)
+    for alpha in (0.0, 0.3, 1.0):
+        got = oracle.block_nsi(v, p, alpha)
+        want = _numpy_block_nsi(v, p, alpha)
+        assert got.shape == want.shape
+        assert np.allclose(got, want, rtol=1e-6, atol=1e-7)
+
+
+def test_block_nsi_equals_the_window_nsi_at_block_centres():
+    # a full interior block is exactly the window of its centre element
+    rng = np.random.default_rng(71)
+    v = rng.standard_normal((15, 21)).astype(np.float32)
+    for p in (3, 5):
+        full = oracle.nsi(v, p, 0.4)
+        blk = oracle.block_nsi(v, p, 0.4)
+        h = (p - 1) // 2
+        for bx in range(15 // p):
+            for by in range(21 // p):
+                assert blk[bx, by] == full[bx * p + h, by * p + h]
+
+
+def test_block_compress_invariants_counts_and_order():
+    rng = np.random.default_rng(72)
+    for R, C, p, rho in ((20, 31, 3, 0.2), (9, 9, 5, 1.0), (30, 7, 3, 0.05), (8, 8, 1, 0.1), (6, 40, 7, 0.5)):
+        g = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        r = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        res = oracle.compress_layer_blocks(g, r, p, 0.5, rho)
+        BR, BC = -(-R // p), -(-C // p)
+        assert res.k == min(math.ceil(R * C / (p * p) * rho), BR * BC)           # Eq. 11, at most all blocks
+        assert np.array_equal(res.v, r + g)
+        # ranking: the k best blocks by (score desc, index asc), listed ascending
+        s = res.nsi.ravel()
+        order = sorted(range(s.size), key=lambda i: (-float(s[i]), i))
+        assert res.blocks.tolist() == sorted(order[:res.k])
+        if res.k:
+            assert res.tau == float(s[order[res.k - 1]])
+        # wire format: p*p values per kept block, row-major, zero outside the matrix
+        for j, b in enumerate(res.blocks):
+            bx, by = divmod(int(b), BC)
+            for dx in range(p):
+                for dy in range(p):
+                    x, y = bx * p + dx, by * p + dy
+                    want = res.v[x, y] if x < R and y < C else np.float32(0.0)
+                    assert res.val[j * p * p + dx * p + dy] == want
+        # what was sent plus what stays is the accumulated gradient, bit for bit
+        dense = oracle.decompress_blocks(res.blocks, res.val, R, C, p)
+        assert np.array_equal(dense + res.r_new, res.v)
+        kept = dense != 0
+        assert np.all(res.r_new[kept] == 0)
+        acc = oracle.decompress_blocks(res.blocks, res.val, R, C, p, dense=np.ones((R, C), np.float32), accumulate_into=True)
+        assert np.array_equal(acc, np.float32(1.0) + dense)
+
+
+def test_block_reading_with_p1_is_the_element_reading():
+    rng = np.random.default_rng(73)
+    g = (rng.standard_normal((12, 19)) * 1e-2).astype(np.float32)
+    r = (rng.standard_normal((12, 19)) * 1e-2).astype(np.float32)
+    a = oracle.compress_layer_blocks(g, r, 1, 0.5, 0.1)
+    b = oracle.compress_layer(g, r, 1, 0.5, 0.1)
+    assert np.array_equal(a.blocks, b.idx) and np.array_equal(a.val, b.val) and np.array_equal(a.r_new, b.r_new)
