@@ -84,6 +84,44 @@ def cpu_baseline(workload, grads, budget_elems: int = 150_000_000):
                       f"({total} elements, one iteration, zero residual), {dt:.1f} s single thread"}
 
 
+def bench_blocks(args, w, grads) -> int:
+    """Same contract for the block reading: K timed rsdgc_compress_blocks calls, one JSON line."""
+    import torch
+    from paper_2312_17530_amd.session import BlockSession
+    sess = BlockSession(w.shapes, w.p, w.alpha, w.ratios, in_place=args.in_place)
+    sess.set_grad(grads)
+    stream = torch.cuda.current_stream()
+    G = w.total_elems
+    for _ in range(args.warmup):
+        sess.compress(stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sess.compress(stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # the dominant kernel (block scores + v) alone, with events on the same stream
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    counts = sess.out_counts.cpu().numpy()
+    n_blocks = int(counts.sum())
+    alg = 12.0 * G + 4.0 * G / (w.p * w.p)          # read g, read r, write v; one score per block
+    out = {
+        "metric": METRIC, "value": G * args.steps / dt, "unit": "elements/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "reading": "non-overlapping blocks", "layers": w.n_layers, "elements": G,
+                   "p": w.p, "alpha": w.alpha, "blocks_kept_last_step": n_blocks,
+                   "residual_update": "in_place" if args.in_place else "two_arenas"},
+        "roofline": {"bound": "hbm", "kernel": "whole call (k_block_nsi dominates)",
+                     "achieved": alg / (dt / args.steps) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": alg / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": alg},
+    }
+    del ev
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +140,9 @@ def main() -> int:
     ap.add_argument("--momentum", type=float, default=None,
                     help="momentum correction (Eq. 12 in full) with this factor: rsdgc_compress_momentum, "
                          "20 bytes per element instead of 12")
+    ap.add_argument("--blocks", action="store_true",
+                    help="the block reading (non-overlapping p x p neighbourhoods, rsdgc_compress_blocks): "
+                         "prints its own JSON line and nothing else")
     ap.add_argument("--full-map", action="store_true",
                     help="force the full-score-map ranking path for every layer")
     args = ap.parse_args()
@@ -121,6 +162,8 @@ def main() -> int:
 
     w = synth.config(args.config)
     grads = synth.gradients(w, 0)
+    if args.blocks:
+        return bench_blocks(args, w, grads)
     sess = Session(w.shapes, w.p, w.alpha, w.ratios, want_centres=args.centres,
                    path=binding.RSDGC_PATH_FULL_MAP if args.full_map else binding.RSDGC_PATH_AUTO,
                    in_place=args.in_place, momentum=args.momentum)

@@ -191,6 +191,40 @@ int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
                      const int32_t *counts, float *dense, int accumulate,
                      void *workspace, void *stream);
 
+/* ---------------------------------------------------------- block reading --
+ * The other reading of Section III-C ("a convolution kernel as a whole", the
+ * G / p^2 of Eq. 11): the matrix is cut into ceil(R/p) x ceil(C/p)
+ * non-overlapping p x p blocks and each block is one neighbourhood.  Its NSI is
+ * Eqs. 8-10 over the block's p*p slots (zero outside the matrix, divisor p*p);
+ * the k_l = ceil(G_l / p^2 * rho_l) best blocks are kept (ties: lower block
+ * index) and a kept block goes out as its index plus its p*p values.
+ *
+ * rsdgc_plan_blocks has rsdgc_plan's arguments.  For such a plan
+ *   rsdgc_layer_k(l)            kept blocks of layer l,
+ *   rsdgc_centre_offset(l) / rsdgc_centre_capacity   layout of the block index list,
+ *   rsdgc_out_offset(l) / rsdgc_out_capacity         layout of the value list
+ *                               (k_l * p_l^2 floats per layer),
+ * and only rsdgc_compress_blocks / rsdgc_decompress_blocks (and the plan calls)
+ * accept it; a plan from rsdgc_plan is refused by these two (RSDGC_EINVAL).
+ *   out_block_idx [device] uint32: per layer, from rsdgc_centre_offset(l), the kept
+ *                 blocks' indices bx * ceil(C/p) + by, ascending.
+ *   out_val       [device] float32: per layer, from rsdgc_out_offset(l), p*p values
+ *                 per kept block in the same order, row-major inside the block,
+ *                 +0 for slots outside the matrix.
+ *   out_counts    [device] int32[n_layers]: kept blocks per layer (= k_l).
+ *   residual_out  a second arena, or residual itself (blocks share no element, so
+ *                 the update in place costs nothing extra here).
+ * Everything else as for rsdgc_compress / rsdgc_decompress.                  */
+int rsdgc_plan_blocks(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
+                      const int32_t *p_per_layer, double alpha,
+                      const double *keep_ratio, rsdgc_plan_t **out_plan);
+int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *residual,
+                          float *residual_out, uint32_t *out_block_idx, float *out_val,
+                          int32_t *out_counts, void *workspace, void *stream);
+int rsdgc_decompress_blocks(rsdgc_plan_t *plan, const uint32_t *block_idx, const float *val,
+                            const int32_t *counts, float *dense, int accumulate,
+                            void *workspace, void *stream);
+
 /* The receiving side of an iteration (Eq. 12, third line):
  *   w <- w - eta * sum_k sparse(v_k)
  * for the messages of n_msgs nodes, each as produced by rsdgc_compress with a

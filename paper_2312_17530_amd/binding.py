@@ -21,7 +21,8 @@ EXPORTS = [
     "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
-    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_nsi", "rsdgc_decompress",
+    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_plan_blocks", "rsdgc_compress_blocks",
+    "rsdgc_decompress_blocks", "rsdgc_nsi", "rsdgc_decompress",
     "rsdgc_last_paths", "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
 ]
@@ -89,6 +90,12 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_apply.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
                                 ctypes.c_float, vp, vp]
     lib.rsdgc_apply.restype = ctypes.c_int
+    lib.rsdgc_plan_blocks.argtypes = lib.rsdgc_plan.argtypes
+    lib.rsdgc_plan_blocks.restype = ctypes.c_int
+    lib.rsdgc_compress_blocks.argtypes = [vp] * 9
+    lib.rsdgc_compress_blocks.restype = ctypes.c_int
+    lib.rsdgc_decompress_blocks.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
+    lib.rsdgc_decompress_blocks.restype = ctypes.c_int
     lib.rsdgc_nsi.argtypes = [vp] * 6
     lib.rsdgc_nsi.restype = ctypes.c_int
     lib.rsdgc_decompress.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
@@ -182,7 +189,9 @@ class Plan:
 
 
 def rsdgc_plan(shapes: Sequence[Tuple[int, int]], p: int, alpha: float,
-               keep_ratio: Sequence[float], p_per_layer: Optional[Sequence[int]] = None) -> Plan:
+               keep_ratio: Sequence[float], p_per_layer: Optional[Sequence[int]] = None,
+               blocks: bool = False) -> Plan:
+    """blocks=True: rsdgc_plan_blocks (non-overlapping p x p neighbourhoods)."""
     lib = load()
     n = len(shapes)
     if len(keep_ratio) != n or (p_per_layer is not None and len(p_per_layer) != n):
@@ -193,8 +202,28 @@ def rsdgc_plan(shapes: Sequence[Tuple[int, int]], p: int, alpha: float,
     if p_per_layer is not None:
         pp = (ctypes.c_int32 * max(n, 1))(*[int(x) for x in p_per_layer])
     out = ctypes.c_void_p()
-    _check(lib.rsdgc_plan(arr, n, int(p), pp, float(alpha), ratios, ctypes.byref(out)), "rsdgc_plan")
+    fn = lib.rsdgc_plan_blocks if blocks else lib.rsdgc_plan
+    _check(fn(arr, n, int(p), pp, float(alpha), ratios, ctypes.byref(out)),
+           "rsdgc_plan_blocks" if blocks else "rsdgc_plan")
     return Plan(out.value)
+
+
+def rsdgc_plan_blocks(shapes, p: int, alpha: float, keep_ratio, p_per_layer=None) -> Plan:
+    return rsdgc_plan(shapes, p, alpha, keep_ratio, p_per_layer, blocks=True)
+
+
+def rsdgc_compress_blocks(plan: Plan, grad, residual, residual_out, out_block_idx, out_val, out_counts,
+                          workspace, stream=None) -> None:
+    _check(load().rsdgc_compress_blocks(plan.handle, _ptr(grad), _ptr(residual), _ptr(residual_out),
+                                        _ptr(out_block_idx), _ptr(out_val), _ptr(out_counts),
+                                        _ptr(workspace), _stream(stream)), "rsdgc_compress_blocks")
+
+
+def rsdgc_decompress_blocks(plan: Plan, block_idx, val, counts, dense, accumulate: bool, workspace,
+                            stream=None) -> None:
+    _check(load().rsdgc_decompress_blocks(plan.handle, _ptr(block_idx), _ptr(val), _ptr(counts), _ptr(dense),
+                                          1 if accumulate else 0, _ptr(workspace), _stream(stream)),
+           "rsdgc_decompress_blocks")
 
 
 def rsdgc_plan_set_ratios(plan: Plan, keep_ratio: Sequence[float]) -> None:

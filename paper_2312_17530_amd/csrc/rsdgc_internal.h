@@ -22,6 +22,14 @@ constexpr int kList2Cap = 2048;      // keys sharing the first two digits that a
 constexpr int kListDiv = 32;         // ... or 1/32 of the layer, whichever is larger
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 
+// Tile of the block-score kernel (block reading): kBlockTileRows block rows by
+// block_tile_cols(p) block columns, i.e. 8p x (8 .. 256)p elements.
+constexpr int kBlockTileRows = 8;
+#if defined(__HIPCC__)
+__host__ __device__
+#endif
+constexpr int block_tile_cols(int p) { return p == 1 ? 256 : p == 3 ? 64 : 32; }
+
 // How the k_l-th largest score of a layer is found (per layer, decided on the device).
 enum LayerMode : uint32_t {
     kModeCandidates = 0,  // scores above a sampled bound are recorded per tile; exact select on them
@@ -200,6 +208,14 @@ struct rsdgc_plan_s {
     const void *uploaded_ws = nullptr;
     uint64_t uploaded_version = 0;
     const void *acc_zero_ws = nullptr;  // workspace whose message accumulator is known to be all zero
+    // block reading (non-overlapping p x p neighbourhoods): this plan describes the element
+    // matrices; `inner` describes the block grids as layers with p = 1 and the same k_l, and
+    // the selection machinery runs on it.  The workspace is this plan's tables followed by
+    // inner's whole workspace.
+    bool blocks = false;
+    rsdgc_plan_s *inner = nullptr;
+    std::vector<int64_t> k_override;    // inner plan only: k_l taken from the outer plan
+    ~rsdgc_plan_s() { delete inner; }
     bool allow_candidates = true;       // false forces the full-map path for every layer
     // optional per-stage timing: (RSDGC_N_STAGES + 1) events per recorded call (hipEvent_t)
     std::vector<void *> prof_events;

@@ -1558,6 +1558,241 @@ __global__ __launch_bounds__(256) void k_scatter(const LayerDev *__restrict__ la
     if (accumulate) *d = *d + val[j]; else *d = val[j];
 }
 
+// --------------------------------------------------------- block reading --
+// Non-overlapping p x p neighbourhoods (the other reading of Section III-C): one score per
+// block.  `outer` are the element matrices, `inner` the block grids (one "element" per block).
+// Work unit: a tile of 8 block rows by block_tile_cols(P) block columns of one layer.  Its
+// elements are loaded with 16-byte loads (rows that are a multiple of 4 floats long), v = r + g
+// goes to LDS and to the new residual arena (which may be r's own: no element is read by two
+// tiles), then every thread takes blocks of the tile: Eqs. 8-10 in double over the p*p slots
+// (zero outside the matrix, divisor p*p), score to the inner score map, 12-bit histogram.
+// Persistent workgroups stride over the tiles; the histogram is flushed on layer change.
+template <int P>
+__global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ outer,
+                                                   const DirEntry *__restrict__ tile_dir,
+                                                   uint32_t n_layers, uint32_t n_tiles,
+                                                   const LayerDev *__restrict__ inner,
+                                                   const float *__restrict__ grad,
+                                                   const float *resid, float *v_out,
+                                                   float *__restrict__ score_map,
+                                                   uint32_t *__restrict__ hist, double alpha) {
+    constexpr int BCT = block_tile_cols(P);
+    constexpr int TR = kBlockTileRows * P, TC = BCT * P;      // tile in elements; TC is a multiple of 4
+    constexpr int VEC_PER_ROW = TC / 4;
+    constexpr int NVEC = TR * VEC_PER_ROW;
+    constexpr int ITER = (NVEC + 255) / 256;
+    constexpr int NBLK = kBlockTileRows * BCT;
+    static_assert(TC % 4 == 0, "tile rows are whole 16-byte groups");
+    __shared__ __attribute__((aligned(16))) float tile[TR * TC];
+    __shared__ uint32_t lhist[kHistBins];
+    const int tid = threadIdx.x;
+    const uint32_t first = blockIdx.x, stride = gridDim.x;
+    if (first >= n_tiles) return;
+    for (int b = tid; b < kHistBins; b += 256) lhist[b] = 0;
+    __syncthreads();
+    const double n = static_cast<double>(P * P);
+    const double ca = alpha / n, cb = (1.0 - alpha) / n;
+    uint32_t e = dir_lookup(tile_dir, n_layers, first);
+    uint32_t cur_l = 0xffffffffu;
+    bool active = false;
+    LayerDev O, I;
+    for (uint32_t t = first; t < n_tiles; t += stride) {
+        while (t >= tile_dir[e + 1].begin) ++e;
+        const uint32_t l = tile_dir[e].layer;
+        if (l != cur_l) {
+            if (active) {                              // flush the finished layer's counts
+                uint32_t *__restrict__ gh = hist + static_cast<size_t>(cur_l) * kHistBins;
+                for (int b = tid; b < kHistBins; b += 256) {
+                    const uint32_t c = lhist[b];
+                    if (c) { atomicAdd(&gh[b], c); lhist[b] = 0; }
+                }
+                __syncthreads();
+            }
+            cur_l = l;
+            O = outer[l];
+            I = inner[l];
+            active = static_cast<int>(O.p) == P;       // another launch takes the other neighbourhood sides
+        }
+        if (!active) {
+            const uint32_t nb = tile_dir[e + 1].begin;
+            t += (nb - t + stride - 1) / stride * stride - stride;
+            continue;
+        }
+        const uint32_t local = t - tile_dir[e].begin;
+        const int trow = static_cast<int>(local / O.tiles_x);
+        const int tcol = static_cast<int>(local - static_cast<uint32_t>(trow) * O.tiles_x);
+        const int R = static_cast<int>(O.R), C = static_cast<int>(O.C);
+        const int x0 = trow * TR, y0 = tcol * TC;
+        const float *__restrict__ g = grad + O.elem_off;
+        const float *r = resid + O.elem_off;           // may be the same arena as vo
+        float *vo = v_out + O.elem_off;
+        if ((C & 3) == 0) {
+            float4 gv[ITER], rv[ITER];
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                const int s = tid + it * 256;
+                const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
+                const int x = x0 + rr, y = y0 + 4 * j4;
+                gv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                rv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (s < NVEC && x < R && y < C) {
+                    const size_t off = static_cast<size_t>(x) * C + y;
+                    gv[it] = *reinterpret_cast<const float4 *>(g + off);
+                    rv[it] = *reinterpret_cast<const float4 *>(r + off);
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < ITER; ++it) {
+                const int s = tid + it * 256;
+                if (s < NVEC) {
+                    const float4 v = make_float4(rv[it].x + gv[it].x, rv[it].y + gv[it].y,
+                                                 rv[it].z + gv[it].z, rv[it].w + gv[it].w);
+                    *reinterpret_cast<float4 *>(&tile[s * 4]) = v;          // s*4 == rr*TC + 4*j4
+                    const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
+                    const int x = x0 + rr, y = y0 + 4 * j4;
+                    if (x < R && y < C) *reinterpret_cast<float4 *>(vo + static_cast<size_t>(x) * C + y) = v;
+                }
+            }
+        } else {
+            for (int s = tid; s < TR * TC; s += 256) {
+                const int rr = s / TC, j = s - rr * TC;
+                const int x = x0 + rr, y = y0 + j;
+                float v = 0.f;
+                if (x < R && y < C) {
+                    const size_t off = static_cast<size_t>(x) * C + y;
+                    v = r[off] + g[off];
+                    vo[off] = v;
+                }
+                tile[s] = v;
+            }
+        }
+        __syncthreads();
+        const uint32_t BR = I.R, BC = I.C;
+#pragma unroll
+        for (int q = tid; q < NBLK; q += 256) {
+            const int br = q / BCT, bc = q - br * BCT;
+            const uint32_t bx = static_cast<uint32_t>(trow * kBlockTileRows + br);
+            const uint32_t by = static_cast<uint32_t>(tcol * BCT + bc);
+            if (bx < BR && by < BC) {
+                double sa = 0.0, ss = 0.0, sq = 0.0;
+#pragma unroll
+                for (int dx = 0; dx < P; ++dx)
+#pragma unroll
+                    for (int dy = 0; dy < P; ++dy) {
+                        const double w = static_cast<double>(tile[(br * P + dx) * TC + bc * P + dy]);
+                        sa += fabs(w);
+                        ss += w;
+                        sq = fma(w, w, sq);
+                    }
+                const float score = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
+                score_map[I.elem_off + static_cast<size_t>(bx) * BC + by] = score;
+                atomicAdd(&lhist[(__float_as_uint(score) & 0x7fffffffu) >> 19], 1u);
+            }
+        }
+        __syncthreads();                               // the tile is reused by the next item
+    }
+    if (active) {
+        uint32_t *__restrict__ gh = hist + static_cast<size_t>(cur_l) * kHistBins;
+        for (int b = tid; b < kHistBins; b += 256) {
+            const uint32_t c = lhist[b];
+            if (c) atomicAdd(&gh[b], c);
+        }
+    }
+}
+
+// Kept blocks of one chunk of a layer's grid, in ascending order: block index to the index
+// list, the block's p*p values (row-major, +0 for slots outside the matrix) to the value
+// list, +0 into the new residual.
+__global__ __launch_bounds__(256) void k_emit_blocks(const LayerDev *__restrict__ outer,
+                                                     const ChunkInfo *__restrict__ inner_chunks,
+                                                     const uint32_t *__restrict__ mask,
+                                                     const uint32_t *__restrict__ chunk_base,
+                                                     const LayerDev *__restrict__ inner,
+                                                     float *__restrict__ v_arena,
+                                                     uint32_t *__restrict__ out_blocks,
+                                                     float *__restrict__ out_val) {
+    __shared__ uint32_t wave_tot[4];
+    __shared__ uint16_t s_list[kChunk];
+    __shared__ uint32_t s_total;
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const ChunkInfo ci = inner_chunks[c];
+    const uint32_t nwords = (ci.len + 31) >> 5;
+    uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(ci.arena_off >> 5) + tid] : 0;
+    const uint32_t cbase = chunk_base[c];
+    if (!__syncthreads_or(word != 0u)) return;
+    const uint32_t cnt = __popc(word);
+    const uint32_t incl = block_scan_incl(cnt, wave_tot);
+    uint32_t pos = incl - cnt;
+    while (word) {
+        const uint32_t b = static_cast<uint32_t>(__ffs(word)) - 1u;
+        word &= word - 1u;
+        s_list[pos++] = static_cast<uint16_t>(32u * static_cast<uint32_t>(tid) + b);
+    }
+    if (tid == 255) s_total = incl;
+    __syncthreads();
+    const uint32_t total = s_total;
+    const LayerDev O = outer[ci.layer];
+    const int P = static_cast<int>(O.p), R = static_cast<int>(O.R), C = static_cast<int>(O.C);
+    const uint32_t BC = inner[ci.layer].C;
+    float *__restrict__ v = v_arena + O.elem_off;
+    for (uint32_t i = tid; i < total; i += 256) {
+        const uint32_t q = s_list[i];
+        if (q >= ci.len) break;             // (mask bits exist only for blocks of the grid)
+        const uint32_t rank = cbase + i;    // position among the layer's kept blocks
+        if (rank >= O.k) continue;          // never write past the layer's segment
+        const uint32_t b = ci.start + q;
+        const int bx = static_cast<int>(b / BC), by = static_cast<int>(b - static_cast<uint32_t>(bx) * BC);
+        out_blocks[static_cast<size_t>(O.centre_off) + rank] = b;
+        float *__restrict__ dst = out_val + static_cast<size_t>(O.out_off) + static_cast<size_t>(rank) * (P * P);
+        for (int dx = 0; dx < P; ++dx)
+            for (int dy = 0; dy < P; ++dy) {
+                const int x = bx * P + dx, y = by * P + dy;
+                float val = 0.f;
+                if (x < R && y < C) {
+                    const size_t off = static_cast<size_t>(x) * C + y;
+                    val = v[off];
+                    v[off] = 0.f;
+                }
+                dst[dx * P + dy] = val;
+            }
+    }
+}
+
+// Inverse: one thread per kept block of a message.
+__global__ __launch_bounds__(256) void k_scatter_blocks(const LayerDev *__restrict__ outer, int n_layers,
+                                                        long long capacity,
+                                                        const uint32_t *__restrict__ blocks,
+                                                        const float *__restrict__ val,
+                                                        const int32_t *__restrict__ counts,
+                                                        float *__restrict__ dense, int accumulate) {
+    const long long j = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+    if (j >= capacity) return;
+    int lo = 0, hi = n_layers;            // last layer whose block segment starts at or before j
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (outer[mid].centre_off <= j) lo = mid; else hi = mid;
+    }
+    const LayerDev O = outer[lo];
+    const long long q = j - O.centre_off;
+    if (q >= counts[lo] || q >= static_cast<long long>(O.k)) return;
+    const int P = static_cast<int>(O.p), R = static_cast<int>(O.R), C = static_cast<int>(O.C);
+    const uint32_t BC = (O.C + O.p - 1) / O.p, BR = (O.R + O.p - 1) / O.p;
+    const uint32_t b = blocks[j];
+    if (b >= BR * BC) return;             // malformed message: ignore the block
+    const int bx = static_cast<int>(b / BC), by = static_cast<int>(b - static_cast<uint32_t>(bx) * BC);
+    const float *__restrict__ src = val + static_cast<size_t>(O.out_off) + static_cast<size_t>(q) * (P * P);
+    float *__restrict__ d = dense + O.elem_off;
+    for (int dx = 0; dx < P; ++dx)
+        for (int dy = 0; dy < P; ++dy) {
+            const int x = bx * P + dx, y = by * P + dy;
+            if (x < R && y < C) {
+                const size_t off = static_cast<size_t>(x) * C + y;
+                if (accumulate) d[off] = d[off] + src[dx * P + dy]; else d[off] = src[dx * P + dy];
+            }
+        }
+}
+
 // ---------------------------------------------------------------- apply --
 // Eq. 12, third line.  The messages have been summed into the accumulator (k_scatter,
 // message by message).  One thread per pair of every message: whoever exchanges a non-zero
@@ -1852,30 +2087,13 @@ extern "C" {
 
 const char *rsdgc_last_hip_error(void) { return g_hip_error; }
 
-static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &mom,
-                         const float *residual, float *residual_out, uint32_t *out_idx,
-                         float *out_val, int32_t *out_counts, uint32_t *out_centre_idx,
-                         int32_t *out_centre_counts, void *workspace, void *stream_) {
-    if (!plan || !grad || !residual || !residual_out || !out_idx || !out_val || !out_counts || !workspace)
-        return RSDGC_EINVAL;
-    if (!aligned256(workspace) || !aligned16(grad) || !aligned16(residual) || !aligned16(residual_out))
-        return RSDGC_EINVAL;
-    const bool in_place = residual_out == residual;
-    if (!in_place) {    // two arenas: they must not overlap, and the new one must not be the gradient
-        const uintptr_t bytes = static_cast<uintptr_t>(plan->total_elems) * sizeof(float);
-        const uintptr_t o = reinterpret_cast<uintptr_t>(residual_out);
-        const uintptr_t r = reinterpret_cast<uintptr_t>(residual), g = reinterpret_cast<uintptr_t>(grad);
-        if ((o < r + bytes && r < o + bytes) || (o < g + bytes && g < o + bytes)) return RSDGC_EINVAL;
-    }
-    float *v_out = in_place ? nullptr : residual_out;
-    hipStream_t stream = static_cast<hipStream_t>(stream_);
-    char *ws = static_cast<char *>(workspace);
+// The part of a compress call between the NSI passes and the emit: radix select of every
+// layer's threshold, marking of the kept elements, kept counts per chunk and their prefix.
+static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, int32_t *out_counts,
+                             int32_t *out_centre_counts, StageMarks &marks, hipStream_t stream) {
     const WsLayout &w = plan->ws;
     const int L = plan->n_layers;
     const uint32_t n_chunks = plan->n_chunks;
-    int rc = upload_tables(plan, workspace, stream);
-    if (rc != RSDGC_OK) return rc;
-
     const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + w.layers);
     const DirEntry *chunk_dir = reinterpret_cast<const DirEntry *>(ws + w.chunk_dir);
     SelState *state = reinterpret_cast<SelState *>(ws + w.state);
@@ -1884,47 +2102,12 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
     uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
     uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
-    const bool want_centres = out_centre_idx || out_centre_counts;
     uint32_t *cmask = want_centres ? reinterpret_cast<uint32_t *>(ws + w.cmask) : nullptr;
     float *nsi = reinterpret_cast<float *>(ws + w.nsi);
-
-    StageMarks marks(plan, stream);
-    // clear: state .. mask (and the centre mask only when it is used)
-    {
-        const size_t end = want_centres ? w.zero_end : w.cmask;
-        const size_t n16 = (end - w.zero_begin) / 16;
-        const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
-        hipLaunchKernelGGL(k_begin, dim3(blocks + 1), dim3(256), 0, stream,
-                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, layers, state, L);
-        HIP_TRY(hipGetLastError());
-    }
-    marks.close(0);
-
-    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + w.chunk_layer);
     const GroupEntry *cand_groups = reinterpret_cast<const GroupEntry *>(ws + w.cand_groups);
     const uint32_t n_cand_groups = static_cast<uint32_t>(plan->cand_groups.size());
     const uint32_t *slot_cnt = reinterpret_cast<const uint32_t *>(ws + w.slot_cnt);
     const unsigned long long *slot_ent = reinterpret_cast<const unsigned long long *>(ws + w.slot_ent);
-    // first pass: the sampled tiles of the large layers (histogram only) and every tile of the
-    // other layers (scores, histogram, v) share one launch
-    rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
-    if (rc != RSDGC_OK) return rc;
-    if (plan->any_large) {
-        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
-        marks.close(1);
-        rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, v_out, mom, stream);
-        if (rc != RSDGC_OK) return rc;
-        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
-        marks.close(2);
-        // large layers whose candidate bound failed (rare): their workgroups find nothing to do otherwise
-        rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, mom, stream);
-        if (rc != RSDGC_OK) return rc;
-    } else {
-        marks.close(1);
-        marks.close(2);
-    }
-    marks.close(3);
-
     // radix select: first digit from the histograms of the NSI passes, then the keys of each
     // layer's threshold bucket are gathered and one workgroup per layer finishes on them
     {
@@ -1990,6 +2173,81 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     hipLaunchKernelGGL(k_scan, dim3(L), dim3(kScanThreads), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
                        out_counts, out_centre_counts, cmask ? 1 : 0);
     marks.close(6);
+    return RSDGC_OK;
+}
+
+static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &mom,
+                         const float *residual, float *residual_out, uint32_t *out_idx,
+                         float *out_val, int32_t *out_counts, uint32_t *out_centre_idx,
+                         int32_t *out_centre_counts, void *workspace, void *stream_) {
+    if (!plan || !grad || !residual || !residual_out || !out_idx || !out_val || !out_counts || !workspace)
+        return RSDGC_EINVAL;
+    if (plan->blocks) return RSDGC_EINVAL;              // a block plan goes with rsdgc_compress_blocks
+    if (!aligned256(workspace) || !aligned16(grad) || !aligned16(residual) || !aligned16(residual_out))
+        return RSDGC_EINVAL;
+    const bool in_place = residual_out == residual;
+    if (!in_place) {    // two arenas: they must not overlap, and the new one must not be the gradient
+        const uintptr_t bytes = static_cast<uintptr_t>(plan->total_elems) * sizeof(float);
+        const uintptr_t o = reinterpret_cast<uintptr_t>(residual_out);
+        const uintptr_t r = reinterpret_cast<uintptr_t>(residual), g = reinterpret_cast<uintptr_t>(grad);
+        if ((o < r + bytes && r < o + bytes) || (o < g + bytes && g < o + bytes)) return RSDGC_EINVAL;
+    }
+    float *v_out = in_place ? nullptr : residual_out;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    char *ws = static_cast<char *>(workspace);
+    const WsLayout &w = plan->ws;
+    const int L = plan->n_layers;
+    const uint32_t n_chunks = plan->n_chunks;
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+
+    const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + w.layers);
+    SelState *state = reinterpret_cast<SelState *>(ws + w.state);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(ws + w.hist);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(ws + w.flags);
+    uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
+    uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
+    uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
+    const bool want_centres = out_centre_idx || out_centre_counts;
+    uint32_t *cmask = want_centres ? reinterpret_cast<uint32_t *>(ws + w.cmask) : nullptr;
+    float *nsi = reinterpret_cast<float *>(ws + w.nsi);
+
+    StageMarks marks(plan, stream);
+    // clear: state .. mask (and the centre mask only when it is used)
+    {
+        const size_t end = want_centres ? w.zero_end : w.cmask;
+        const size_t n16 = (end - w.zero_begin) / 16;
+        const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
+        hipLaunchKernelGGL(k_begin, dim3(blocks + 1), dim3(256), 0, stream,
+                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, layers, state, L);
+        HIP_TRY(hipGetLastError());
+    }
+    marks.close(0);
+
+    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + w.chunk_layer);
+    // first pass: the sampled tiles of the large layers (histogram only) and every tile of the
+    // other layers (scores, histogram, v) share one launch
+    rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
+    if (rc != RSDGC_OK) return rc;
+    if (plan->any_large) {
+        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
+        marks.close(1);
+        rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, v_out, mom, stream);
+        if (rc != RSDGC_OK) return rc;
+        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
+        marks.close(2);
+        // large layers whose candidate bound failed (rare): their workgroups find nothing to do otherwise
+        rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, mom, stream);
+        if (rc != RSDGC_OK) return rc;
+    } else {
+        marks.close(1);
+        marks.close(2);
+    }
+    marks.close(3);
+
+    rc = select_mark_count(plan, ws, want_centres, out_counts, out_centre_counts, marks, stream);
+    if (rc != RSDGC_OK) return rc;
+    const ChunkInfo *chunk_info = reinterpret_cast<const ChunkInfo *>(ws + w.chunk_info);
     if (in_place)
         hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, grad,
                            residual_out, mask, chunk_cnt, out_idx, out_val);
@@ -2037,10 +2295,107 @@ int rsdgc_compress_momentum(rsdgc_plan_t *plan, const float *grad, const float *
                          out_centre_idx, out_centre_counts, workspace, stream);
 }
 
+int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *residual,
+                          float *residual_out, uint32_t *out_block_idx, float *out_val,
+                          int32_t *out_counts, void *workspace, void *stream_) {
+    if (!plan || !plan->blocks || !grad || !residual || !residual_out || !out_block_idx || !out_val ||
+        !out_counts || !workspace)
+        return RSDGC_EINVAL;
+    if (!aligned256(workspace) || !aligned16(grad) || !aligned16(residual) || !aligned16(residual_out))
+        return RSDGC_EINVAL;
+    if (residual_out != residual) {     // a second arena must overlap neither input
+        const uintptr_t bytes = static_cast<uintptr_t>(plan->total_elems) * sizeof(float);
+        const uintptr_t o = reinterpret_cast<uintptr_t>(residual_out);
+        const uintptr_t r = reinterpret_cast<uintptr_t>(residual), g = reinterpret_cast<uintptr_t>(grad);
+        if ((o < r + bytes && r < o + bytes) || (o < g + bytes && g < o + bytes)) return RSDGC_EINVAL;
+    } else {
+        const uintptr_t bytes = static_cast<uintptr_t>(plan->total_elems) * sizeof(float);
+        const uintptr_t o = reinterpret_cast<uintptr_t>(residual_out), g = reinterpret_cast<uintptr_t>(grad);
+        if (o < g + bytes && g < o + bytes) return RSDGC_EINVAL;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    char *ws_outer = static_cast<char *>(workspace);
+    rsdgc_plan_s *in = plan->inner;
+    char *ws = ws_outer + plan->ws.table_bytes;        // the inner plan's workspace
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+    rc = upload_tables(in, ws, stream);
+    if (rc != RSDGC_OK) return rc;
+    const WsLayout &w = in->ws;
+    const int L = in->n_layers;
+    const LayerDev *outer = reinterpret_cast<const LayerDev *>(ws_outer + plan->ws.layers);
+    const LayerDev *inner = reinterpret_cast<const LayerDev *>(ws + w.layers);
+    const ChunkInfo *inner_chunks = reinterpret_cast<const ChunkInfo *>(ws + w.chunk_info);
+    SelState *state = reinterpret_cast<SelState *>(ws + w.state);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(ws + w.hist);
+    uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
+    uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
+    float *score_map = reinterpret_cast<float *>(ws + w.nsi);
+    StageMarks marks(in, stream);                      // (the inner plan never records events)
+    {
+        const size_t n16 = (w.cmask - w.zero_begin) / 16;
+        const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
+        hipLaunchKernelGGL(k_begin, dim3(blocks + 1), dim3(256), 0, stream,
+                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, inner, state, L);
+    }
+    bool have[RSDGC_MAX_P + 1] = {};
+    for (int l = 0; l < L; ++l) have[plan->p[l]] = true;
+    for (int pp = 1; pp <= RSDGC_MAX_P; pp += 2) {
+        if (!have[pp]) continue;
+        switch (pp) {
+#define RSDGC_BLOCK_CASE(PP)                                                                     \
+    case PP: {                                                                                   \
+        static const uint32_t resident = resident_workgroups(k_block_nsi<PP>);                   \
+        hipLaunchKernelGGL((k_block_nsi<PP>), dim3(std::min<uint32_t>(plan->n_tiles_all, resident)), \
+                           dim3(256), 0, stream, outer,                                          \
+                           reinterpret_cast<const DirEntry *>(ws_outer + plan->ws.all_tile_dir), \
+                           static_cast<uint32_t>(L), plan->n_tiles_all, inner, grad, residual,   \
+                           residual_out, score_map, hist, plan->alpha);                          \
+        break;                                                                                   \
+    }
+            RSDGC_BLOCK_CASE(1)
+            RSDGC_BLOCK_CASE(3)
+            RSDGC_BLOCK_CASE(5)
+            RSDGC_BLOCK_CASE(7)
+#undef RSDGC_BLOCK_CASE
+        }
+    }
+    HIP_TRY(hipGetLastError());
+    rc = select_mark_count(in, ws, false, out_counts, nullptr, marks, stream);
+    if (rc != RSDGC_OK) return rc;
+    hipLaunchKernelGGL(k_emit_blocks, dim3(in->n_chunks), dim3(256), 0, stream, outer, inner_chunks, mask,
+                       chunk_cnt, inner, residual_out, out_block_idx, out_val);
+    HIP_TRY(hipGetLastError());
+    return RSDGC_OK;
+}
+
+int rsdgc_decompress_blocks(rsdgc_plan_t *plan, const uint32_t *block_idx, const float *val,
+                            const int32_t *counts, float *dense, int accumulate, void *workspace,
+                            void *stream_) {
+    if (!plan || !plan->blocks || !block_idx || !val || !counts || !dense || !workspace) return RSDGC_EINVAL;
+    if (!aligned256(workspace) || !aligned16(dense)) return RSDGC_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    char *ws = static_cast<char *>(workspace);
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+    const LayerDev *outer = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
+    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + plan->ws.chunk_layer);
+    if (!accumulate)
+        hipLaunchKernelGGL(k_zero_layers, dim3(plan->n_chunks), dim3(256), 0, stream, outer, chunk_layer, dense);
+    if (plan->centre_capacity > 0) {
+        const unsigned blocks = static_cast<unsigned>((plan->centre_capacity + 255) / 256);
+        hipLaunchKernelGGL(k_scatter_blocks, dim3(blocks), dim3(256), 0, stream, outer, plan->n_layers,
+                           static_cast<long long>(plan->centre_capacity), block_idx, val, counts, dense,
+                           accumulate);
+    }
+    HIP_TRY(hipGetLastError());
+    return RSDGC_OK;
+}
+
 int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
                 const float *const *val, const int32_t *const *counts, float *weights, float eta,
                 void *workspace, void *stream_) {
-    if (!plan || !idx || !val || !counts || !weights || !workspace) return RSDGC_EINVAL;
+    if (!plan || plan->blocks || !idx || !val || !counts || !weights || !workspace) return RSDGC_EINVAL;
     if (n_msgs < 1 || n_msgs > RSDGC_MAX_MSGS || !(eta == eta)) return RSDGC_EINVAL;
     if (!aligned256(workspace) || !aligned16(weights)) return RSDGC_EINVAL;
     for (int k = 0; k < n_msgs; ++k)
@@ -2077,7 +2432,7 @@ int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
 
 int rsdgc_dynamic_ratios(rsdgc_plan_t *plan, const float *weights, double global_ratio,
                          double *ratios_out, void *workspace, void *stream_) {
-    if (!plan || !weights || !ratios_out || !workspace) return RSDGC_EINVAL;
+    if (!plan || plan->blocks || !weights || !ratios_out || !workspace) return RSDGC_EINVAL;
     if (!(global_ratio >= 0.0 && global_ratio <= 1.0)) return RSDGC_EINVAL;     // false for NaN
     if (!aligned256(workspace) || !aligned16(weights)) return RSDGC_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
@@ -2139,7 +2494,7 @@ int rsdgc_dynamic_ratios(rsdgc_plan_t *plan, const float *weights, double global
 }
 
 int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream_) {
-    if (!plan || !workspace || !paths) return RSDGC_EINVAL;
+    if (!plan || plan->blocks || !workspace || !paths) return RSDGC_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     std::vector<SelState> host;
     try {
@@ -2214,7 +2569,7 @@ const char *rsdgc_stage_name(int32_t stage) {
 
 int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual, float *nsi_out,
               void *workspace, void *stream_) {
-    if (!plan || !grad || !nsi_out || !workspace) return RSDGC_EINVAL;
+    if (!plan || plan->blocks || !grad || !nsi_out || !workspace) return RSDGC_EINVAL;
     if (!aligned256(workspace) || !aligned16(grad) || !aligned16(nsi_out) ||
         (residual && !aligned16(residual)))
         return RSDGC_EINVAL;
@@ -2228,7 +2583,7 @@ int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual, floa
 int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
                      const int32_t *counts, float *dense, int accumulate, void *workspace,
                      void *stream_) {
-    if (!plan || !idx || !val || !counts || !dense || !workspace) return RSDGC_EINVAL;
+    if (!plan || plan->blocks || !idx || !val || !counts || !dense || !workspace) return RSDGC_EINVAL;
     if (!aligned256(workspace) || !aligned16(dense)) return RSDGC_EINVAL;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     char *ws = static_cast<char *>(workspace);

@@ -42,9 +42,9 @@ int build_tables(rsdgc_plan_s *plan) {
         LayerDev &d = plan->layers[l];
         const int64_t R = plan->shapes[l].rows, C = plan->shapes[l].cols, G = R * C;
         const int p = plan->p[l];
-        const int64_t k = keep_count(G, p, plan->ratio[l]);
+        const int64_t k = plan->k_override.empty() ? keep_count(G, p, plan->ratio[l]) : plan->k_override[l];
         int64_t cap = k * p * p;
-        if (cap > G) cap = G;
+        if (cap > G && !plan->blocks) cap = G;   // (a kept block always sends p*p values, padding included)
         d.elem_off = elem_off;
         d.out_off = out_off;
         d.centre_off = centre_off;
@@ -55,6 +55,11 @@ int build_tables(rsdgc_plan_s *plan) {
         d.p = static_cast<uint32_t>(p);
         d.tiles_x = static_cast<uint32_t>((C + kTileCols - 1) / kTileCols);
         d.n_tiles = d.tiles_x * static_cast<uint32_t>((R + kTileRows - 1) / kTileRows);
+        if (plan->blocks) {   // tiles of the block-score kernel instead: 8 x block_tile_cols(p) blocks
+            const int64_t BR = (R + p - 1) / p, BC = (C + p - 1) / p;
+            d.tiles_x = static_cast<uint32_t>((BC + block_tile_cols(p) - 1) / block_tile_cols(p));
+            d.n_tiles = d.tiles_x * static_cast<uint32_t>((BR + kBlockTileRows - 1) / kBlockTileRows);
+        }
         d.chunk_begin = chunk_begin;
         d.n_chunks = static_cast<uint32_t>((G + kChunk - 1) / kChunk);
         d.cap = static_cast<uint32_t>(cap);
@@ -62,7 +67,11 @@ int build_tables(rsdgc_plan_s *plan) {
         d.group_begin = group_begin;
         d.n_groups = (d.n_tiles + kSlotGroup - 1) / kSlotGroup;
         d.list_off = static_cast<uint32_t>(list_off);
-        d.list_cap = static_cast<uint32_t>(std::min<int64_t>(G, std::max<int64_t>(kListMin, G / kListDiv)));
+        // a block grid is ranked on its full score map whatever its size: its threshold bucket may hold
+        // a large part of a large layer, so the list takes all of it (else 1/32, see kListDiv)
+        d.list_cap = plan->k_override.empty()
+                         ? static_cast<uint32_t>(std::min<int64_t>(G, std::max<int64_t>(kListMin, G / kListDiv)))
+                         : static_cast<uint32_t>(G);
         list_off += d.list_cap;
 
         // Candidate path: the bound comes from the scores of a sample of the layer's tiles.
@@ -219,6 +228,25 @@ int build_tables(rsdgc_plan_s *plan) {
         std::memcpy(plan->table.data() + w.map_tiles, plan->map_tiles.data(),
                     sizeof(SampleEntry) * plan->map_tiles.size());
     ++plan->version;
+
+    if (plan->blocks) {       // the block grids as a plan of their own: p = 1, the same k_l, full-map ranking
+        if (!plan->inner) plan->inner = new rsdgc_plan_s;
+        rsdgc_plan_s *in = plan->inner;
+        in->n_layers = L;
+        in->alpha = plan->alpha;
+        in->shapes.resize(L);
+        in->p.assign(L, 1);
+        in->ratio.assign(L, 0.0);
+        in->k_override.resize(L);
+        in->allow_candidates = false;
+        for (int l = 0; l < L; ++l) {
+            const int64_t p = plan->p[l];
+            in->shapes[l].rows = (plan->shapes[l].rows + p - 1) / p;
+            in->shapes[l].cols = (plan->shapes[l].cols + p - 1) / p;
+            in->k_override[l] = plan->layers[l].k;     // Eq. 11; never more than the number of blocks
+        }
+        build_tables(in);
+    }
     return RSDGC_OK;
 }
 
@@ -230,9 +258,9 @@ using namespace rsdgc;
 
 extern "C" {
 
-int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
-               const int32_t *p_per_layer, double alpha, const double *keep_ratio,
-               rsdgc_plan_t **out_plan) {
+static int make_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
+                     const int32_t *p_per_layer, double alpha, const double *keep_ratio,
+                     bool blocks, rsdgc_plan_t **out_plan) {
     if (!shapes || !keep_ratio || !out_plan || n_layers < 1 || n_layers > 65536) return RSDGC_EINVAL;
     *out_plan = nullptr;
     if (!(alpha >= 0.0 && alpha <= 1.0)) return RSDGC_EINVAL;
@@ -257,6 +285,7 @@ int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
         plan->p.resize(n_layers);
         for (int l = 0; l < n_layers; ++l) plan->p[l] = p_per_layer ? p_per_layer[l] : p;
         plan->ratio.assign(keep_ratio, keep_ratio + n_layers);
+        plan->blocks = blocks;
         build_tables(plan);
     } catch (const std::bad_alloc &) {
         delete plan;
@@ -264,6 +293,18 @@ int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
     }
     *out_plan = plan;
     return RSDGC_OK;
+}
+
+int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
+               const int32_t *p_per_layer, double alpha, const double *keep_ratio,
+               rsdgc_plan_t **out_plan) {
+    return make_plan(shapes, n_layers, p, p_per_layer, alpha, keep_ratio, false, out_plan);
+}
+
+int rsdgc_plan_blocks(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
+                      const int32_t *p_per_layer, double alpha, const double *keep_ratio,
+                      rsdgc_plan_t **out_plan) {
+    return make_plan(shapes, n_layers, p, p_per_layer, alpha, keep_ratio, true, out_plan);
 }
 
 int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio) {
@@ -324,7 +365,11 @@ int64_t rsdgc_centre_offset(const rsdgc_plan_t *plan, int32_t l) {
 int64_t rsdgc_centre_capacity(const rsdgc_plan_t *plan) {
     return plan ? plan->centre_capacity : -1;
 }
-size_t rsdgc_workspace_bytes(const rsdgc_plan_t *plan) { return plan ? plan->ws.total : 0; }
+size_t rsdgc_workspace_bytes(const rsdgc_plan_t *plan) {
+    if (!plan) return 0;
+    if (plan->blocks) return plan->ws.table_bytes + plan->inner->ws.total;   // table_bytes is a multiple of 256
+    return plan->ws.total;
+}
 
 const char *rsdgc_strerror(int code) {
     switch (code) {

@@ -127,3 +127,63 @@ class Session:
             out.append((idx[o:o + n].copy(), val[o:o + n].copy(),
                         cidx[co:co + k].copy() if cidx is not None else None, int(ccounts[l])))
         return out
+
+
+class BlockSession:
+    """The same plumbing for the block reading (rsdgc_plan_blocks / rsdgc_compress_blocks)."""
+
+    def __init__(self, shapes, p: int, alpha: float, ratios: Sequence[float],
+                 p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0", in_place: bool = False):
+        self.shapes = [(int(r), int(c)) for r, c in shapes]
+        self.p_list = [int(x) for x in p_per_layer] if p_per_layer is not None else [int(p)] * len(self.shapes)
+        self.plan = binding.rsdgc_plan_blocks(self.shapes, p, alpha, ratios, p_per_layer)
+        self.device = torch.device(device)
+        dev = self.device
+        n, L = self.plan.total_elems, self.plan.n_layers
+        self.grad = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.residual = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.in_place = in_place
+        self.residual_next = None if in_place else torch.zeros(n, dtype=torch.float32, device=dev)
+        self.out_blocks = torch.zeros(max(1, self.plan.centre_capacity), dtype=torch.int32, device=dev)
+        self.out_val = torch.zeros(max(1, self.plan.out_capacity), dtype=torch.float32, device=dev)
+        self.out_counts = torch.zeros(L, dtype=torch.int32, device=dev)
+        self.workspace = torch.zeros(self.plan.workspace_bytes, dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.offsets = [self.plan.layer_offset(l) for l in range(L)]
+        self.sizes = [self.plan.layer_elems(l) for l in range(L)]
+
+    pack = Session.pack
+    unpack = Session.unpack
+
+    def set_grad(self, arrays):
+        self.pack(arrays, self.grad)
+
+    def set_residual(self, arrays):
+        self.pack(arrays, self.residual)
+
+    def compress(self, stream=None) -> None:
+        target = self.residual if self.in_place else self.residual_next
+        binding.rsdgc_compress_blocks(self.plan, self.grad, self.residual, target, self.out_blocks,
+                                      self.out_val, self.out_counts, self.workspace, stream)
+        if not self.in_place:
+            self.residual, self.residual_next = self.residual_next, self.residual
+
+    def decompress(self, accumulate: bool = False, dense: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if dense is None:
+            dense = torch.full_like(self.grad, 7.0)
+        binding.rsdgc_decompress_blocks(self.plan, self.out_blocks, self.out_val, self.out_counts, dense,
+                                        accumulate, self.workspace)
+        return dense
+
+    def results(self):
+        """Per layer: (kept block indices uint32, values float32 with p*p per block)."""
+        torch.cuda.synchronize()
+        counts = self.out_counts.cpu().numpy()
+        blocks = self.out_blocks.cpu().numpy().view(np.uint32)
+        val = self.out_val.cpu().numpy()
+        out = []
+        for l in range(self.plan.n_layers):
+            n, pp = int(counts[l]), self.p_list[l] ** 2
+            bo, vo = self.plan.centre_offset(l), self.plan.out_offset(l)
+            out.append((blocks[bo:bo + n].copy(), val[vo:vo + n * pp].copy()))
+        return out

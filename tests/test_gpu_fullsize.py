@@ -207,6 +207,40 @@ def test_apply_at_vgg19_size_four_equal_messages():
         assert np.array_equal(after[l].reshape(-1).view(np.uint32), want.view(np.uint32)), l
 
 
+def test_vgg19_full_size_block_reading_against_oracle():
+    """Non-overlapping 3 x 3 neighbourhoods on the VGG-19-shaped gradient: kept blocks, values and
+    residual against the complete oracle, layer by layer."""
+    import torch
+    from paper_2312_17530_amd.session import BlockSession
+    w = synth.config(3)
+    sess = BlockSession(w.shapes, w.p, w.alpha, w.ratios)
+    grads = synth.gradients(w, 0)
+    resid = synth.gradients(w, 9)
+    sess.set_grad(grads)
+    sess.set_residual(resid)
+    sess.compress()
+    torch.cuda.synchronize()
+    res = sess.results()
+    gpu_r = sess.unpack(sess.residual)
+    n_exact = 0
+    for l, sh in enumerate(w.shapes):
+        print("checking blocks", l, sh, flush=True)
+        o = oracle.compress_layer_blocks(grads[l], resid[l], w.p, w.alpha, w.ratios[l])
+        gb, gv = res[l]
+        assert len(gb) == o.k == sess.plan.layer_k(l)
+        if np.array_equal(gb, o.blocks):
+            assert np.array_equal(gv.view(np.uint32), o.val.view(np.uint32)), l
+            assert np.array_equal(gpu_r[l].view(np.uint32), o.r_new.view(np.uint32)), l
+            n_exact += 1
+        else:                                   # only scores within the tolerance band may differ
+            s = o.nsi.ravel().astype(np.float64)
+            kept = np.zeros(s.size, dtype=bool)
+            kept[gb] = True
+            tau = float(o.tau)
+            assert not np.any(~kept & (s > tau * (1 + parity.EPS))) and not np.any(kept & (s < tau * (1 - parity.EPS))), l
+    assert n_exact >= w.n_layers - 2
+
+
 def test_fc6_stress_p5_student_t_against_oracle_then_one_carried_iteration():
     w, n_exact = _run(4, extra_iterations=1)
     assert n_exact == 1

@@ -259,6 +259,109 @@ def test_apply_messages_of_three_nodes_matches_the_oracle():
         weights = got
 
 
+def run_and_check_blocks(shapes, p_list, alpha, ratios, grads_per_iter, name, in_place=False):
+    """The block reading on GPU and oracle from identical state; returns (compared, exact)."""
+    import torch
+    from paper_2312_17530_amd.session import BlockSession
+    sess = BlockSession(shapes, p_list[0], alpha, ratios, p_list, in_place=in_place)
+    resid = [np.zeros(sh, dtype=np.float32) for sh in shapes]
+    n_cmp = n_exact = 0
+    for t, grads in enumerate(grads_per_iter):
+        sess.set_grad(grads)
+        sess.set_residual(resid)
+        sess.compress()
+        torch.cuda.synchronize()
+        res = sess.results()
+        gpu_r = sess.unpack(sess.residual)
+        dense = sess.unpack(sess.decompress(accumulate=False))
+        new_resid = []
+        for l, sh in enumerate(shapes):
+            p = p_list[l]
+            o = oracle.compress_layer_blocks(grads[l], resid[l], p, alpha, ratios[l])
+            tag = f"{name}[blocks,t={t},l={l},{sh},p={p}]"
+            gb, gv = res[l]
+            assert sess.plan.layer_k(l) == o.k and len(gb) == o.k, tag
+            assert np.all(np.diff(gb.astype(np.int64)) > 0), tag
+            # ranking: every block clearly above the threshold is kept, none clearly below
+            s = o.nsi.ravel().astype(np.float64)
+            kept = np.zeros(s.size, dtype=bool)
+            kept[gb] = True
+            if 0 < o.k < s.size:
+                tau = float(o.tau)
+                assert not np.any(~kept & (s > tau * (1 + parity.EPS))), tag
+                assert not np.any(kept & (s < tau * (1 - parity.EPS))), tag
+            # wire format and residual follow from the GPU's own kept set, bit for bit
+            R, C = sh
+            BC = -(-C // p)
+            v = o.v
+            want_r = v.copy()
+            want_val = np.zeros(len(gb) * p * p, dtype=np.float32)
+            for j, b in enumerate(gb):
+                bx, by = divmod(int(b), BC)
+                x1, y1 = min(R, bx * p + p), min(C, by * p + p)
+                blk = np.zeros((p, p), dtype=np.float32)
+                blk[:x1 - bx * p, :y1 - by * p] = v[bx * p:x1, by * p:y1]
+                want_val[j * p * p:(j + 1) * p * p] = blk.ravel()
+                want_r[bx * p:x1, by * p:y1] = 0.0
+            assert np.array_equal(gv.view(np.uint32), want_val.view(np.uint32)), f"{tag}: values"
+            assert np.array_equal(gpu_r[l].view(np.uint32), want_r.view(np.uint32)), f"{tag}: residual"
+            assert np.array_equal((dense[l] + gpu_r[l]).view(np.uint32), v.view(np.uint32)) or \
+                np.array_equal(dense[l] + gpu_r[l], v), f"{tag}: decompress"
+            exact = np.array_equal(gb, o.blocks)
+            if exact:
+                assert np.array_equal(gv.view(np.uint32), o.val.view(np.uint32)), tag
+                assert np.array_equal(gpu_r[l].view(np.uint32), o.r_new.view(np.uint32)), tag
+            n_cmp += 1
+            n_exact += int(exact)
+            new_resid.append(o.r_new)
+        resid = new_resid
+    return n_cmp, n_exact
+
+
+def test_blocks_ragged_shapes_mixed_p_two_iterations(in_place):
+    shapes = RAGGED + [(300, 700), (512, 1152)]
+    p_list = [1, 3, 5, 7, 3, 5, 3, 3, 7, 5, 3, 1, 3, 5, 3, 3]
+    ratios = [1.0, 0.1, 0.1, 1.0, 0.02, 0.05, 0.02, 0.01, 0.3, 0.001, 0.5, 0.07, 0.0, 1.0, 0.02, 0.01]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 19, t, l) for l, sh in enumerate(shapes)] for t in range(2)]
+    n, ex = run_and_check_blocks(shapes, p_list, 0.5, ratios, its, "ragged", in_place=in_place)
+    assert n == 2 * len(shapes) and ex >= n - 2
+
+
+def test_blocks_degenerate_inputs_follow_index_tie_break():
+    shapes = [(40, 70), (64, 128), (33, 40), (16, 300)]
+    zeros = np.zeros(shapes[0], dtype=np.float32)
+    const = np.full(shapes[1], -0.375, dtype=np.float32)
+    xs, ys = np.meshgrid(np.arange(33), np.arange(40), indexing="ij")
+    checker = np.where((xs + ys) % 2 == 0, 0.5, -0.5).astype(np.float32)
+    ints = np.random.default_rng(98).integers(-3, 4, size=shapes[3]).astype(np.float32)
+    grads = [zeros, const, checker, ints]
+    for p in (3, 5, 1):
+        n, ex = run_and_check_blocks(shapes, [p] * 4, 0.5, [0.3, 0.2, 0.1, 0.15], [grads, grads], f"degenerate(p={p})")
+        assert ex == n, "exact ties must resolve exactly like the oracle (lower block index wins)"
+
+
+def test_blocks_resnet18_shapes():
+    w = synth.config(1)
+    its = [synth.gradients(w, t) for t in range(2)]
+    n, ex = run_and_check_blocks(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name)
+    assert n == 2 * w.n_layers and ex >= n - 2
+
+
+def test_block_plan_and_element_plan_do_not_mix():
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import BlockSession, Session
+    b = BlockSession([(64, 64)], 3, 0.5, [0.1])
+    e = Session([(64, 64)], 3, 0.5, [0.1])
+    with pytest.raises(binding.RsdgcError):
+        binding.rsdgc_compress(b.plan, b.grad, b.residual, b.residual_next, b.out_blocks, b.out_val,
+                               b.out_counts, b.workspace)
+    with pytest.raises(binding.RsdgcError):
+        binding.rsdgc_compress_blocks(e.plan, e.grad, e.residual, e.residual_next, e.out_idx, e.out_val,
+                                      e.out_counts, e.workspace)
+    torch.cuda.synchronize()
+
+
 def test_config0_single_layer_512(in_place):
     w = synth.config(0)
     n, ex = run_and_check(w.shapes, [w.p], w.alpha, w.ratios, [synth.gradients(w, 0)], w.name,
