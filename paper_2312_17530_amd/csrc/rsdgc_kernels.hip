@@ -1736,26 +1736,26 @@ __global__ __launch_bounds__(256) void k_emit_blocks(const LayerDev *__restrict_
     const int P = static_cast<int>(O.p), R = static_cast<int>(O.R), C = static_cast<int>(O.C);
     const uint32_t BC = inner[ci.layer].C;
     float *__restrict__ v = v_arena + O.elem_off;
-    for (uint32_t i = tid; i < total; i += 256) {
-        const uint32_t q = s_list[i];
-        if (q >= ci.len) break;             // (mask bits exist only for blocks of the grid)
-        const uint32_t rank = cbase + i;    // position among the layer's kept blocks
+    // one thread per (kept block, slot): independent loads, contiguous value stores
+    const uint32_t PP = static_cast<uint32_t>(P * P);
+    for (uint32_t i = tid; i < total * PP; i += 256) {
+        const uint32_t kb = i / PP, sl = i - kb * PP;
+        const uint32_t q = s_list[kb];
+        if (q >= ci.len) continue;          // (mask bits exist only for blocks of the grid)
+        const uint32_t rank = cbase + kb;   // position among the layer's kept blocks
         if (rank >= O.k) continue;          // never write past the layer's segment
         const uint32_t b = ci.start + q;
         const int bx = static_cast<int>(b / BC), by = static_cast<int>(b - static_cast<uint32_t>(bx) * BC);
-        out_blocks[static_cast<size_t>(O.centre_off) + rank] = b;
-        float *__restrict__ dst = out_val + static_cast<size_t>(O.out_off) + static_cast<size_t>(rank) * (P * P);
-        for (int dx = 0; dx < P; ++dx)
-            for (int dy = 0; dy < P; ++dy) {
-                const int x = bx * P + dx, y = by * P + dy;
-                float val = 0.f;
-                if (x < R && y < C) {
-                    const size_t off = static_cast<size_t>(x) * C + y;
-                    val = v[off];
-                    v[off] = 0.f;
-                }
-                dst[dx * P + dy] = val;
-            }
+        if (sl == 0) out_blocks[static_cast<size_t>(O.centre_off) + rank] = b;
+        const int dx = static_cast<int>(sl) / P, dy = static_cast<int>(sl) - dx * P;
+        const int x = bx * P + dx, y = by * P + dy;
+        float val = 0.f;
+        if (x < R && y < C) {
+            const size_t off = static_cast<size_t>(x) * C + y;
+            val = v[off];
+            v[off] = 0.f;
+        }
+        out_val[static_cast<size_t>(O.out_off) + static_cast<size_t>(rank) * PP + sl] = val;
     }
 }
 
