@@ -2,6 +2,7 @@
 declares, validates its arguments, and does the host arithmetic of the plan (Eq. 11 counts,
 arena offsets, output capacities) correctly.  No kernel is launched."""
 import ctypes
+import math
 import os
 import re
 from fractions import Fraction
@@ -146,3 +147,59 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "librsdgc.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.load()
+
+
+def test_block_plan_layout_on_the_host():
+    """rsdgc_plan_blocks: k_l from Eq. 11, one index per kept block, p*p values per kept block
+    (padding slots of partial blocks included), workspace = the plan's tables + the block grid's."""
+    shapes, p_list, ratios = [(90, 90), (10, 10), (64, 27), (7, 1000)], [3, 3, 5, 7], [0.1, 1.0, 0.5, 0.3]
+    plan = binding.rsdgc_plan_blocks(shapes, 3, 0.5, ratios, p_list)
+    ks = [math.ceil(r * c / (p * p) * rho) for (r, c), p, rho in zip(shapes, p_list, ratios)]
+    assert [plan.layer_k(l) for l in range(4)] == ks
+    n_blocks = [-(-r // p) * -(-c // p) for (r, c), p in zip(shapes, p_list)]
+    assert all(k <= nb for k, nb in zip(ks, n_blocks))           # Eq. 11 never asks for more blocks than exist
+    assert plan.centre_capacity == sum(ks)
+    assert plan.out_capacity == sum(k * p * p for k, p in zip(ks, p_list))
+    assert plan.out_capacity > sum(min(k * p * p, r * c) for k, p, (r, c) in zip(ks, p_list, shapes))  # (10,10): 16 blocks x 9 > 100
+    assert [plan.centre_offset(l) for l in range(4)] == [0, ks[0], ks[0] + ks[1], ks[0] + ks[1] + ks[2]]
+    assert plan.out_offset(2) == ks[0] * 9 + ks[1] * 9
+    element_plan = binding.rsdgc_plan(shapes, 3, 0.5, ratios, p_list)
+    assert plan.total_elems == element_plan.total_elems           # the arenas are laid out alike
+    assert plan.workspace_bytes % 256 == 0 and 0 < plan.workspace_bytes < element_plan.workspace_bytes
+    binding.rsdgc_plan_set_ratios(plan, [0.0, 0.5, 0.5, 0.3])
+    assert [plan.layer_k(l) for l in range(4)] == [0, 6, ks[2], ks[3]]
+    with pytest.raises(binding.RsdgcError):
+        binding.rsdgc_plan_blocks([(8, 8)], 4, 0.5, [0.1])
+
+
+def test_newer_entry_points_validate_before_touching_the_gpu():
+    lib = binding.load()
+    plan = binding.rsdgc_plan([(8, 8)], 3, 0.5, [0.1])
+    bplan = binding.rsdgc_plan_blocks([(8, 8)], 3, 0.5, [0.1])
+    E, null, a = binding.RSDGC_EINVAL, None, 4096
+    # momentum: null arenas, factor outside [0, 1], overlapping arenas (the arena is 64 floats = 256 bytes)
+    assert lib.rsdgc_compress_momentum(plan.handle, a, null, a, 0.9, a, a, a, a, a, null, null, a, null) == E
+    assert lib.rsdgc_compress_momentum(plan.handle, a, 2 * a, 3 * a, 1.5, 4 * a, 5 * a, a, a, a, null, null, 6 * a, null) == E
+    assert lib.rsdgc_compress_momentum(plan.handle, a, 2 * a, 3 * a, float("nan"), 4 * a, 5 * a, a, a, a, null, null, 6 * a, null) == E
+    assert lib.rsdgc_compress_momentum(plan.handle, a, 2 * a, 2 * a + 128, 0.9, 4 * a, 5 * a, a, a, a, null, null, 6 * a, null) == E
+    assert lib.rsdgc_compress_momentum(plan.handle, a, 2 * a, 3 * a, 0.9, 4 * a, 3 * a, a, a, a, null, null, 6 * a, null) == E
+    # dynamic ratios: bad fraction; nothing / everything kept needs no GPU at all
+    out = (ctypes.c_double * 1)()
+    assert lib.rsdgc_dynamic_ratios(plan.handle, a, 1.5, out, a, null) == E
+    assert lib.rsdgc_dynamic_ratios(plan.handle, null, 0.5, out, a, null) == E
+    assert lib.rsdgc_dynamic_ratios(plan.handle, a, 0.0, out, a, null) == binding.RSDGC_OK and out[0] == 0.0
+    assert lib.rsdgc_dynamic_ratios(plan.handle, a, 1.0, out, a, null) == binding.RSDGC_OK and out[0] == 1.0
+    # apply: message count out of range, null tables
+    ptrs = (ctypes.c_void_p * 1)(a)
+    assert lib.rsdgc_apply(plan.handle, 0, ptrs, ptrs, ptrs, a, 0.1, a, null) == E
+    assert lib.rsdgc_apply(plan.handle, 65, ptrs, ptrs, ptrs, a, 0.1, a, null) == E
+    assert lib.rsdgc_apply(plan.handle, 1, null, ptrs, ptrs, a, 0.1, a, null) == E
+    assert lib.rsdgc_apply(plan.handle, 1, (ctypes.c_void_p * 1)(None), ptrs, ptrs, a, 0.1, a, null) == E
+    # plans of the two readings do not mix
+    assert lib.rsdgc_compress(bplan.handle, a, 2 * a, 3 * a, a, a, a, null, null, 4 * a, null) == E
+    assert lib.rsdgc_compress_blocks(plan.handle, a, 2 * a, 3 * a, a, a, a, 4 * a, null) == E
+    assert lib.rsdgc_decompress_blocks(plan.handle, a, a, a, a, 0, 4 * a, null) == E
+    assert lib.rsdgc_decompress(bplan.handle, a, a, a, a, 0, 4 * a, null) == E
+    assert lib.rsdgc_nsi(bplan.handle, a, a, a, 4 * a, null) == E
+    assert lib.rsdgc_compress_blocks(bplan.handle, a, 2 * a, 2 * a + 128, a, a, a, 4 * a, null) == E    # overlapping arenas
+    assert lib.rsdgc_compress_blocks(bplan.handle, a, a, a, a, a, a, 4 * a, null) == E                    # new residual on the gradient
