@@ -20,6 +20,8 @@ constexpr int kCandBins = 256;       // 12-bit score buckets above the bound tha
 constexpr int kListMin = 8192;       // smallest threshold-bucket list of a layer (entries)
 constexpr int kList2Cap = 2048;      // keys sharing the first two digits that a layer can stage
 constexpr int kListDiv = 32;         // ... or 1/32 of the layer, whichever is larger
+constexpr int kListShards = 16;      // a layer's threshold-bucket list is filled through this many counters
+constexpr int kListCntStride = 32;   // uint32 between two of them (one 128-byte line each)
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 
 // Tile of the block-score kernel (block reading): kBlockTileRows block rows by
@@ -65,7 +67,7 @@ struct LayerDev {
     uint32_t n_sampled;     // sampled tiles of the layer
     uint32_t list_off;      // first entry of the layer's threshold-bucket list
     uint32_t list_cap;      // its capacity
-    uint32_t pad_;
+    uint32_t list_shards;   // shards the list is split into (each list_cap / list_shards entries, own counter)
 };
 static_assert(sizeof(LayerDev) == 104, "LayerDev layout");
 
@@ -151,7 +153,7 @@ struct WsLayout {
     size_t hist = 0;         // uint32[n_layers][kHistBins]
     size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk, then their prefix
     size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk, then prefix
-    size_t list_cnt = 0;     // uint32[n_layers]  keys gathered from the threshold bucket
+    size_t list_cnt = 0;     // uint32[n_layers][kListShards][kListCntStride]  keys gathered per list shard
     size_t list2_cnt = 0;    // uint32[n_layers]  of those, keys that also share the second digit
     size_t flags = 0;        // uint32[64]  [0]: some large layer fell back to the full map
     size_t mask = 0;         // uint32[total_elems / 32]  kept-element bitmask

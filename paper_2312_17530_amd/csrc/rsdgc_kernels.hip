@@ -651,11 +651,15 @@ __device__ __forceinline__ void gather_flush(GatherStage &st, const LayerDev &L,
     __syncthreads();
     const uint32_t n = st.n;
     if (n != 0) {                          // uniform
-        if (threadIdx.x == 0) st.base = atomicAdd(&list_cnt[l], n);
+        // the workgroup's shard of the layer's list: its own counter (own cache line) and region
+        const uint32_t shard = blockIdx.x % L.list_shards, cap = L.list_cap / L.list_shards;
+        if (threadIdx.x == 0)
+            st.base = atomicAdd(&list_cnt[(static_cast<size_t>(l) * kListShards + shard) * kListCntStride], n);
         __syncthreads();
         const uint32_t base = st.base;
+        unsigned long long *__restrict__ dst = list_ent + static_cast<size_t>(L.list_off) + static_cast<size_t>(shard) * cap;
         for (uint32_t i = threadIdx.x; i < n; i += 256)
-            if (base + i < L.list_cap) list_ent[static_cast<size_t>(L.list_off) + base + i] = st.ent[i];
+            if (base + i < cap) dst[base + i] = st.ent[i];
         __syncthreads();
         if (threadIdx.x == 0) st.n = 0;
     }
@@ -880,17 +884,23 @@ __global__ __launch_bounds__(kFinishThreads) void k_filter(const LayerDev *__res
     __shared__ unsigned long long stage[kList2Cap];
     __shared__ uint32_t nstage, base;
     const int l = blockIdx.x / kFilterSplit, part = blockIdx.x % kFilterSplit, tid = threadIdx.x;
+    // lane s of every wave reads shard s's counter (unused shards stay 0); issued with the other loads
+    const uint32_t *__restrict__ cnt = list_cnt + static_cast<size_t>(l) * kListShards * kListCntStride;
+    const uint32_t c = (tid & 63) < kListShards ? cnt[(tid & 63) * kListCntStride] : 0u;
     const SelState st = state[l];
-    if (st.done || st.mode == kModeSkip) return;
     const LayerDev L = layers[l];
-    const uint32_t n = list_cnt[l];
-    if (n > L.list_cap) return;            // the bucket did not fit: the finish streams the layer
-    const unsigned long long *__restrict__ list = list_ent + L.list_off;
+    if (st.done || st.mode == kModeSkip) return;
+    const uint32_t shards = L.list_shards, cap = L.list_cap / shards;
+    if (__ballot(c > cap)) return;         // the bucket did not fit: the finish streams the layer
+    // this workgroup's shard, and its share of that shard
+    const uint32_t shard = part % shards, sub = part / shards, nsub = (kFilterSplit + shards - 1 - shard) / shards;
+    const uint32_t n = __shfl(c, static_cast<int>(shard));
+    const unsigned long long *__restrict__ list = list_ent + L.list_off + static_cast<size_t>(shard) * cap;
     if (tid == 0) nstage = 0;
     __syncthreads();
     const unsigned long long want = st.T >> level_shift(1);
     constexpr uint32_t U = 4;              // independent loads in flight per thread
-    for (uint32_t i0 = part * U * kFinishThreads; i0 < n; i0 += kFilterSplit * U * kFinishThreads) {
+    for (uint32_t i0 = sub * U * kFinishThreads; i0 < n; i0 += nsub * U * kFinishThreads) {
         unsigned long long K[U];
 #pragma unroll
         for (uint32_t u = 0; u < U; ++u) {
@@ -939,17 +949,20 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
     __shared__ DigitResult res;
     constexpr int NW = kFinishThreads / 64;
     const int l = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *__restrict__ cnt = list_cnt + static_cast<size_t>(l) * kListShards * kListCntStride;
+    const uint32_t c = (tid & 63) < kListShards ? cnt[(tid & 63) * kListCntStride] : 0u;   // as in k_filter
+    const uint32_t n2 = list2_cnt[l];
     const SelState st = state[l];          // first two digits are fixed
-    if (st.done || st.mode == kModeSkip) return;
     const LayerDev L = layers[l];
-    const uint32_t n = list_cnt[l];
-    const bool use_list = n <= L.list_cap;
+    if (st.done || st.mode == kModeSkip) return;
+    const uint32_t shards = L.list_shards, cap = L.list_cap / shards;
+    const bool use_list = __ballot(c > cap) == 0;      // every shard of the threshold-bucket list fits
     const unsigned long long *__restrict__ list = list_ent + L.list_off;
     unsigned long long T = st.T;
     uint32_t k_rem = st.k_rem;
     bool done = false;
     int lv = 2;
-    const uint32_t nsel = use_list ? list2_cnt[l] : 0xffffffffu;
+    const uint32_t nsel = use_list ? n2 : 0xffffffffu;
     const bool staged = nsel <= static_cast<uint32_t>(kFinishStage);
     if (staged) {
         for (uint32_t i = tid; i < nsel; i += kFinishThreads)
@@ -968,9 +981,13 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
                 if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
             }
         } else if (use_list) {
-            for (uint32_t i = tid; i < n; i += kFinishThreads) {
-                const unsigned long long K = list[i];
-                if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
+            for (uint32_t s = 0; s < shards; ++s) {
+                const uint32_t n = cnt[s * kListCntStride];
+                const unsigned long long *__restrict__ part = list + static_cast<size_t>(s) * cap;
+                for (uint32_t i = tid; i < n; i += kFinishThreads) {
+                    const unsigned long long K = part[i];
+                    if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
+                }
             }
         } else if (st.mode == kModeFullMap) {
             const uint32_t *__restrict__ src = keys + L.elem_off;

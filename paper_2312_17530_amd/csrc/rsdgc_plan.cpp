@@ -72,6 +72,9 @@ int build_tables(rsdgc_plan_s *plan) {
         d.list_cap = plan->k_override.empty()
                          ? static_cast<uint32_t>(std::min<int64_t>(G, std::max<int64_t>(kListMin, G / kListDiv)))
                          : static_cast<uint32_t>(G);
+        // workgroups append through kListShards counters so that few atomics meet on one address; a
+        // block grid keeps one shard, which can take the whole layer
+        d.list_shards = plan->k_override.empty() ? kListShards : 1;
         list_off += d.list_cap;
 
         // Candidate path: the bound comes from the scores of a sample of the layer's tiles.
@@ -178,7 +181,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.hist = off;         off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
     w.chunk_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
-    w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * L, A);
+    w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * kListShards * kListCntStride * size_t(L), A);
     w.list2_cnt = off;    off = align_up(off + sizeof(uint32_t) * L, A);
     w.flags = off;        off = align_up(off + sizeof(uint32_t) * 64, A);
     w.mask = off;         off = align_up(off + sizeof(uint32_t) * words, A);
