@@ -9,8 +9,8 @@
 namespace rsdgc {
 
 // ---- geometry constants (device and host agree on these) -----------------
-constexpr int kTileRows = 32;        // NSI tile: output rows per workgroup
-constexpr int kTileCols = 128;       // NSI tile: output columns per workgroup
+constexpr int kTileRows = 16;        // NSI tile: output rows per workgroup
+constexpr int kTileCols = 256;       // NSI tile: output columns per workgroup
 constexpr int kChunk = 8192;         // elements per workgroup in the 1-D passes
 constexpr int kHistBins = 4096;      // widest radix digit (12 bits)
 constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements

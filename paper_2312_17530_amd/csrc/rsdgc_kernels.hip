@@ -199,7 +199,7 @@ struct NsiArgs {
     double alpha;
 };
 
-// Work unit: one 32 x 128 tile of one layer.  The tile of v = r + g plus a halo of
+// Work unit: one 16 x 256 tile of one layer.  The tile of v = r + g plus a halo of
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
 // down 8 rows of 2 adjacent columns, keeping per-row horizontal sums of |w|, w and w^2
 // (double) for the last P rows in registers.  The variance is formed as
@@ -237,6 +237,14 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     if (first >= last) return;
     if (PASS == kPassFullMap && a.flags[0] == 0u) return;   // no layer fell back: nothing to do
 
+#if defined(RSDGC_EXP) && RSDGC_EXP == 8
+    if (CAPTURE) {   // experiment: phase offset between the workgroups that share a CU
+        const uint32_t slot = (blockIdx.x / RSDGC_STAG_DIV) & 3u;
+        const unsigned long long t0 = wall_clock64();
+        const unsigned long long ticks = static_cast<unsigned long long>(slot) * RSDGC_STAG;
+        for (int it = 0; it < 4096 && wall_clock64() - t0 < ticks; ++it) __builtin_amdgcn_s_sleep(8);
+    }
+#endif
     if (NBINS > 1)
         for (int b = tid; b < NBINS; b += 256) lhist[b] = 0;
     if (CAPTURE && tid == 0) ncand = 0;
@@ -253,7 +261,8 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     const double n = static_cast<double>(P * P);
     const double ca = a.alpha / n;        // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
     const double cb = (1.0 - a.alpha) / n;
-    const int tx = tid & 63, ty = tid >> 6;
+    static_assert(kTileCols / 2 * (kTileRows / RPT) == 256, "one thread per 8 rows x 2 columns");
+    const int tx = tid % (kTileCols / 2), ty = tid / (kTileCols / 2);
     const int c0 = 2 * tx;
     const int row_base = ty * RPT;
 
@@ -1112,7 +1121,7 @@ __device__ __forceinline__ void mark_candidates(const LayerDev *__restrict__ lay
     }
 }
 
-// Full-map layers: workgroups stride over the 32 x 128 tiles (the NSI tiling).  Every centre
+// Full-map layers: workgroups stride over the 16 x 256 tiles (the NSI tiling).  Every centre
 // of a tile and of a halo of h rows / columns is compared with the layer's threshold; the
 // per-row results become 64-bit ballot words in LDS, the p x p box dilation (Section III-C:
 // whole neighbourhoods are kept) is done on those words with shifts and ORs, and the tile's
@@ -1140,7 +1149,9 @@ struct MarkArgs {
 
 __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
     constexpr int MAXH = (RSDGC_MAX_P - 1) / 2;
-    __shared__ unsigned long long bits[kTileRows + 2 * MAXH][4];   // [row][left, seg0, seg1, right]
+    constexpr int NSEG = kTileCols / 64;       // 64-column segments of a tile row
+    static_assert(kTileRows * NSEG == 64, "one lane of wave 0 per row segment");
+    __shared__ unsigned long long bits[kTileRows + 2 * MAXH][NSEG + 2];   // [row][left, segments, right]
     if (blockIdx.x < m.n_cand_wgs) {
         mark_candidates(m.layers, m.cand_groups, m.n_cand_groups, blockIdx.x, m.n_cand_wgs, m.state,
                         m.slot_cnt, m.slot_ent, m.mask, m.cmask);
@@ -1200,8 +1211,8 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
         const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
         const uint32_t *__restrict__ src = keys + L.elem_off;
 
-        for (int it = wave; it < rows_ext * 2; it += 4) {
-            const int rr = it >> 1, seg = it & 1;
+        for (int it = wave; it < rows_ext * NSEG; it += 4) {
+            const int rr = it / NSEG, seg = it % NSEG;
             const int x = x0 - h + rr, y = y0 + 64 * seg + lane;
             bool flag = false;
             if (x >= 0 && x < R && y < C) {
@@ -1224,11 +1235,11 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
                     }
                 }
             }
-            bits[lane][wave == 0 ? 0 : 3] = hw;
+            bits[lane][wave == 0 ? 0 : NSEG + 1] = hw;
         }
         __syncthreads();
 
-        const int r = lane >> 1, seg = lane & 1;    // wave 0: 32 rows x 2 segments = 64 items
+        const int r = lane / NSEG, seg = lane % NSEG;    // wave 0: rows x segments = 64 items
         const int x = x0 + r, yb = y0 + 64 * seg;
         if (wave == 0 && x < R && yb < C) {
             unsigned long long acc = 0;

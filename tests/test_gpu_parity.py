@@ -454,21 +454,22 @@ def _tile_is_sampled(t):
 def test_candidate_path_falls_back_when_its_bound_fails(in_place):
     """Large layers rank only the centres above a bound estimated from sampled tiles.  Inputs
     built to defeat that estimate must still give the oracle's result (through the full map)."""
-    R, C = 512, 4608                      # 16 x 36 tiles of 32 x 128
+    R, C = 512, 4608                      # 32 x 18 tiles of 16 x 256
+    TR, TC = 16, 256                      # the library's NSI tile
     rng = np.random.default_rng(123)
     base = (rng.standard_normal((R, C)) * 1e-3).astype(np.float32)
-    tiles_x = C // 128
+    tiles_x = C // TC
     # (a) the sampled tiles carry far larger values than the rest: the bound comes out too high
     hot_sampled = base.copy()
-    # (b) one tile holds thousands of top-ranked centres: its candidate slot overflows
+    # (b) one region holds thousands of top-ranked centres: candidate slots overflow
     hot_tile = base.copy()
     hot_tile[64:96, 256:384] *= np.float32(50.0)
     n_sampled = 0
-    for t in range((R // 32) * tiles_x):
+    for t in range((R // TR) * tiles_x):
         if _tile_is_sampled(t):
             n_sampled += 1
             tr, tc = divmod(t, tiles_x)
-            hot_sampled[tr * 32:(tr + 1) * 32, tc * 128:(tc + 1) * 128] *= np.float32(30.0)
+            hot_sampled[tr * TR:(tr + 1) * TR, tc * TC:(tc + 1) * TC] *= np.float32(30.0)
     assert n_sampled >= 8, "the layer must be large enough to take the candidate path"
     # (c) a well-behaved layer next to them keeps using the candidate path
     shapes = [(R, C), (R, C), (R, C)]
