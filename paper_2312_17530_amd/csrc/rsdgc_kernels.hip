@@ -1398,7 +1398,7 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
                         v[q] = 0.f;
                     }
             }
-            *reinterpret_cast<float4 *>(r + e) = make_float4(v[0], v[1], v[2], v[3]);
+            store_streaming(r + e, make_float4(v[0], v[1], v[2], v[3]));
         }
         return;
     }
@@ -1679,7 +1679,7 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
                     *reinterpret_cast<float4 *>(&tile[s * 4]) = v;          // s*4 == rr*TC + 4*j4
                     const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
                     const int x = x0 + rr, y = y0 + 4 * j4;
-                    if (x < R && y < C) *reinterpret_cast<float4 *>(vo + static_cast<size_t>(x) * C + y) = v;
+                    if (x < R && y < C) store_streaming(vo + static_cast<size_t>(x) * C + y, v);
                 }
             }
         } else {
