@@ -20,6 +20,7 @@ constexpr int kCandBins = 256;       // 12-bit score buckets above the bound tha
 constexpr int kListMin = 8192;       // smallest threshold-bucket list of a layer (entries)
 constexpr int kList2Cap = 2048;      // keys sharing the first two digits that a layer can stage
 constexpr int kListDiv = 32;         // ... or 1/32 of the layer, whichever is larger
+constexpr int kChunkGroup = 64;      // chunks per group in the two-level chunk prefix
 constexpr int kListShards = 16;      // a layer's threshold-bucket list is filled through this many counters
 constexpr int kListCntStride = 32;   // uint32 between two of them (one 128-byte line each)
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
@@ -121,6 +122,16 @@ struct ChunkEntry {
     uint64_t arena_off;  // elem_off + start
 };
 
+// Work item of the count pass: one group of up to kChunkGroup consecutive chunks of a layer.
+struct CountGroup {
+    uint64_t word0;        // first 32-bit word of the group's mask bits
+    uint32_t first_chunk;
+    uint32_t n_chunks;
+    uint32_t n_words;      // mask words of the group (a layer's last chunk may be short)
+    uint32_t pad_;
+};
+static_assert(sizeof(CountGroup) == 24, "CountGroup layout");
+
 // Everything the 1-D passes need to know about one 8192-element chunk (one load instead of a
 // chain chunk -> layer -> layer table).
 struct ChunkInfo {
@@ -130,8 +141,14 @@ struct ChunkInfo {
     uint32_t start;      // first element of the chunk inside the layer
     uint32_t len;        // elements in the chunk
     uint32_t cap;        // capacity of the layer's output segment
+    // for the chunk's prefix (kept elements of the layer before the chunk), which is the sum
+    // of the totals of the layer's earlier chunk groups and of the earlier chunks of its own
+    uint32_t group;              // chunk group (kChunkGroup chunks of one layer), numbered over all layers
+    uint32_t group_first_chunk;  // first chunk of that group
+    uint32_t layer_first_group;  // first group of the layer
+    uint32_t last;               // 1: the layer's last chunk (it reports the layer's total)
 };
-static_assert(sizeof(ChunkInfo) == 32, "ChunkInfo layout");
+static_assert(sizeof(ChunkInfo) == 48, "ChunkInfo layout");
 
 // Byte offsets of the workspace sections (all multiples of 256).
 struct WsLayout {
@@ -146,13 +163,16 @@ struct WsLayout {
     size_t cand_groups = 0;  // GroupEntry[]: slot groups of the large layers (work list of the candidate passes)
     size_t map_chunks = 0;   // ChunkEntry[]: chunks of the other layers that select something
     size_t map_tiles = 0;    // SampleEntry[]: tiles of those layers
+    size_t count_groups = 0; // CountGroup[n_chunk_groups]
     size_t table_bytes = 0;  // bytes uploaded from the host
     size_t state = 0;        // SelState[n_layers], rewritten at the start of every compress
     // cleared at the start of every compress
     size_t zero_begin = 0;
     size_t hist = 0;         // uint32[n_layers][kHistBins]
-    size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk, then their prefix
-    size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk, then prefix
+    size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk
+    size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk
+    size_t group_cnt = 0;    // uint32[n_chunk_groups]  kept elements per chunk group
+    size_t group_ccnt = 0;   // uint32[n_chunk_groups]  selected centres per chunk group
     size_t list_cnt = 0;     // uint32[n_layers][kListShards][kListCntStride]  keys gathered per list shard
     size_t list2_cnt = 0;    // uint32[n_layers]  of those, keys that also share the second digit
     size_t flags = 0;        // uint32[64]  [0]: some large layer fell back to the full map
@@ -203,6 +223,7 @@ struct rsdgc_plan_s {
     int64_t out_capacity = 0;
     int64_t centre_capacity = 0;
     uint32_t n_chunks = 0;
+    uint32_t n_chunk_groups = 0;  // chunk groups over all layers
     rsdgc::WsLayout ws;
     std::vector<unsigned char> table;   // host image of the uploaded tables
     // device-side bookkeeping

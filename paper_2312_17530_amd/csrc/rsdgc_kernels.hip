@@ -1274,63 +1274,98 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
 }
 
 // ---------------------------------------------------------------- count --
-__global__ __launch_bounds__(256) void k_count(const ChunkInfo *__restrict__ chunk_info,
-                                               const uint32_t *__restrict__ mask,
-                                               const uint32_t *__restrict__ cmask,
-                                               uint32_t *__restrict__ chunk_cnt,
-                                               uint32_t *__restrict__ chunk_ccnt) {
-    __shared__ uint32_t wave_tot[4];
+// Kept elements (and selected centres) per chunk and per group of kChunkGroup chunks: one
+// 1024-thread workgroup per group; 16 adjacent threads read the 256 mask words of one chunk
+// (16 consecutive words each, as independent 8-byte loads) and add their popcounts with
+// four shuffles.  Plain stores only: the group totals need no global atomics (which all fell
+// on a few cache lines when every chunk added its own count).
+constexpr int kCountThreads = 1024;
+
+__global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__restrict__ groups,
+                                                         const uint32_t *__restrict__ mask,
+                                                         const uint32_t *__restrict__ cmask,
+                                                         uint32_t *__restrict__ chunk_cnt,
+                                                         uint32_t *__restrict__ chunk_ccnt,
+                                                         uint32_t *__restrict__ group_cnt,
+                                                         uint32_t *__restrict__ group_ccnt) {
+    constexpr int kPerThread = kChunk / 32 / 16;    // 16 words
+    static_assert(kCountThreads / 16 == kChunkGroup && kChunkGroup == 64, "16 threads per chunk, one lane per chunk");
+    __shared__ uint32_t lcnt[2][kChunkGroup];
     const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x;
-    const ChunkInfo ci = chunk_info[c];
-    const size_t w0 = ci.arena_off >> 5;
-    const uint32_t nwords = (ci.len + 31) >> 5;
-    const uint32_t a = static_cast<uint32_t>(tid) < nwords ? __popc(mask[w0 + tid]) : 0;
-    const uint32_t sa = block_scan_incl(a, wave_tot);
-    if (tid == 255) chunk_cnt[c] = sa;
-    if (cmask) {
-        const uint32_t b = static_cast<uint32_t>(tid) < nwords ? __popc(cmask[w0 + tid]) : 0;
-        const uint32_t sb = block_scan_incl(b, wave_tot);
-        if (tid == 255) chunk_ccnt[c] = sb;
+    const CountGroup gr = groups[blockIdx.x];
+    const uint32_t i0 = static_cast<uint32_t>(tid) * kPerThread;
+    // (a layer starts at a multiple of 64 elements, so word0 and i0 are even: 8-byte loads)
+    uint2 wa[kPerThread / 2], wb[kPerThread / 2];
+#pragma unroll
+    for (int j = 0; j < kPerThread / 2; ++j) {
+        const uint32_t i = i0 + 2 * j;
+        wa[j] = make_uint2(0u, 0u);
+        wb[j] = make_uint2(0u, 0u);
+        if (i + 1 < gr.n_words) {
+            wa[j] = *reinterpret_cast<const uint2 *>(mask + gr.word0 + i);
+            if (cmask) wb[j] = *reinterpret_cast<const uint2 *>(cmask + gr.word0 + i);
+        } else if (i < gr.n_words) {
+            wa[j].x = mask[gr.word0 + i];
+            if (cmask) wb[j].x = cmask[gr.word0 + i];
+        }
+    }
+    uint32_t a = 0, b = 0;
+#pragma unroll
+    for (int j = 0; j < kPerThread / 2; ++j) {
+        a += __popc(wa[j].x) + __popc(wa[j].y);
+        b += __popc(wb[j].x) + __popc(wb[j].y);
+    }
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) {
+        a += __shfl_xor(a, d, 64);
+        b += __shfl_xor(b, d, 64);
+    }
+    if ((tid & 15) == 0) {
+        lcnt[0][tid >> 4] = a;
+        lcnt[1][tid >> 4] = b;
+    }
+    __syncthreads();
+    if (tid < 64) {                        // the first wave: one lane per chunk of the group
+        a = lcnt[0][tid];
+        b = lcnt[1][tid];
+        if (static_cast<uint32_t>(tid) < gr.n_chunks) {
+            chunk_cnt[gr.first_chunk + tid] = a;
+            if (cmask) chunk_ccnt[gr.first_chunk + tid] = b;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            a += __shfl_xor(a, d, 64);
+            b += __shfl_xor(b, d, 64);
+        }
+        if (tid == 0) {
+            group_cnt[blockIdx.x] = a;
+            if (cmask) group_ccnt[blockIdx.x] = b;
+        }
     }
 }
 
-// ----------------------------------------------------------------- scan --
-// One workgroup (1024 threads) per layer: exclusive prefix of the per-chunk counts, totals out.
-constexpr int kScanThreads = 1024;
-
-__global__ __launch_bounds__(kScanThreads) void k_scan(const LayerDev *__restrict__ layers,
-                                                       SelState *__restrict__ state,
-                                                       uint32_t *__restrict__ chunk_cnt,
-                                                       uint32_t *__restrict__ chunk_ccnt,
-                                                       int32_t *__restrict__ out_counts,
-                                                       int32_t *__restrict__ out_centre_counts,
-                                                       int with_centres) {
-    __shared__ uint32_t wave_tot[kScanThreads / 64];
-    const int l = blockIdx.x, tid = threadIdx.x;
-    const LayerDev L = layers[l];
-    const uint32_t n = L.n_chunks, per = (n + kScanThreads - 1) / kScanThreads;
-    const uint32_t lo = min(n, tid * per), hi = min(n, lo + per);
-    for (int pass = 0; pass < (with_centres ? 2 : 1); ++pass) {
-        uint32_t *__restrict__ a = (pass == 0 ? chunk_cnt : chunk_ccnt) + L.chunk_begin;
-        uint32_t own = 0;
-        for (uint32_t i = lo; i < hi; ++i) own += a[i];
-        const uint32_t incl = block_scan_incl_n<kScanThreads / 64>(own, wave_tot);
-        uint32_t run = incl - own;
-        for (uint32_t i = lo; i < hi; ++i) {
-            const uint32_t v = a[i];
-            a[i] = run;
-            run += v;
-        }
-        if (tid == kScanThreads - 1 && pass == 0) {
-            out_counts[l] = static_cast<int32_t>(incl);
-            state[l].n_pairs = incl;
-        }
-        if (tid == kScanThreads - 1 && pass == 1) {
-            state[l].n_centres = incl;
-            if (out_centre_counts) out_centre_counts[l] = static_cast<int32_t>(incl);
-        }
-    }
+// The chunk's prefix -- kept elements of its layer before it -- is the sum of the totals of
+// the layer's earlier chunk groups and of the earlier chunks of its own group: at most a few
+// hundred values, so every consumer adds them up itself instead of waiting for a scan
+// kernel.  The first wave does it (independent loads issued with the workgroup's other loads,
+// one wave reduction) and leaves the sum in *s_prefix; the caller reads it after its next
+// barrier.
+__device__ __forceinline__ void chunk_prefix_wave0(const ChunkInfo &ci, uint32_t c,
+                                                   const uint32_t *__restrict__ chunk_cnt,
+                                                   const uint32_t *__restrict__ group_cnt,
+                                                   uint32_t *s_prefix) {
+    if (threadIdx.x >= 64) return;
+    const uint32_t g0 = ci.layer_first_group + threadIdx.x, g1 = ci.group;
+    const uint32_t cc = ci.group_first_chunk + threadIdx.x;     // at most kChunkGroup - 1 = 63 of them
+    uint32_t v[5];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = g0 + 64 * j < g1 ? group_cnt[g0 + 64 * j] : 0u;
+    v[4] = cc < c ? chunk_cnt[cc] : 0u;
+    uint32_t own = v[0] + v[1] + v[2] + v[3] + v[4];
+    for (uint32_t g = g0 + 256; g < g1; g += 64) own += group_cnt[g];     // layers beyond 2^27 elements
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) own += __shfl_xor(own, d, 64);
+    if (threadIdx.x == 0) *s_prefix = own;
 }
 
 // ----------------------------------------------------------------- emit --
@@ -1338,29 +1373,28 @@ __global__ __launch_bounds__(kScanThreads) void k_scan(const LayerDev *__restric
 // the position given by the chunk prefix plus the popcount of the mask bits before them;
 // the residual becomes +0 where kept and v elsewhere.
 __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layers,
-                                              const uint32_t *__restrict__ chunk_layer, const float *__restrict__ grad,
+                                              const ChunkInfo *__restrict__ chunk_info, const float *__restrict__ grad,
                                               float *__restrict__ resid,
                                               const uint32_t *__restrict__ mask,
-                                              const uint32_t *__restrict__ chunk_base,
+                                              const uint32_t *__restrict__ chunk_cnt,
+                                              const uint32_t *__restrict__ group_cnt,
                                               uint32_t *__restrict__ out_idx,
-                                              float *__restrict__ out_val) {
+                                              float *__restrict__ out_val,
+                                              int32_t *__restrict__ out_counts) {
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t s_word[256];
     __shared__ uint32_t s_pref[256];
+    __shared__ uint32_t s_cbase;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_layer[c];
-    const LayerDev L = layers[l];
-    const uint32_t start = (c - L.chunk_begin) * kChunk;
-    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-    const size_t base = static_cast<size_t>(L.elem_off) + start;
+    const ChunkInfo ci = chunk_info[c];
+    const LayerDev L = layers[ci.layer];
+    const uint32_t start = ci.start, len = ci.len;
+    const size_t base = ci.arena_off;
     const uint32_t nwords = (len + 31) >> 5;
     const uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(base >> 5) + tid] : 0;
     const float *__restrict__ g = grad + base;
     float *__restrict__ r = resid + base;
-    const uint32_t cbase = chunk_base[c];
-    const size_t obase = static_cast<size_t>(L.out_off) + cbase;
-    const uint32_t room = L.cap > cbase ? L.cap - cbase : 0u;   // never write past the segment
     const bool whole = len == static_cast<uint32_t>(kChunk);
     // A whole chunk: every load is issued before the mask scan, so the scan's latency and the
     // loads overlap and each thread keeps 16 wide loads in flight.
@@ -1372,10 +1406,15 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
             rq[j] = *reinterpret_cast<const float4 *>(r + j * 1024 + 4 * tid);
         }
     }
+    chunk_prefix_wave0(ci, c, chunk_cnt, group_cnt, &s_cbase);
     const uint32_t cnt = __popc(word);
     s_word[tid] = word;
     const uint32_t incl = block_scan_incl(cnt, wave_tot);
+    const uint32_t cbase = s_cbase;
+    const size_t obase = static_cast<size_t>(L.out_off) + cbase;
+    const uint32_t room = L.cap > cbase ? L.cap - cbase : 0u;   // never write past the segment
     s_pref[tid] = incl - cnt;
+    if (ci.last && tid == 255) out_counts[ci.layer] = static_cast<int32_t>(cbase + incl);
     __syncthreads();
     if (whole) {
 #pragma unroll
@@ -1457,12 +1496,14 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict
                                                      const float *__restrict__ mom_in,
                                                      float *__restrict__ mom_arena, float m,
                                                      const uint32_t *__restrict__ mask,
-                                                     const uint32_t *__restrict__ chunk_base,
+                                                     const uint32_t *__restrict__ chunk_cnt,
+                                                     const uint32_t *__restrict__ group_cnt,
                                                      uint32_t *__restrict__ out_idx,
-                                                     float *__restrict__ out_val) {
+                                                     float *__restrict__ out_val,
+                                                     int32_t *__restrict__ out_counts) {
     __shared__ uint32_t wave_tot[4];
     __shared__ uint16_t s_list[kChunk];
-    __shared__ uint32_t s_total;
+    __shared__ uint32_t s_total, s_cbase;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
     const ChunkInfo ci = chunk_info[c];
@@ -1472,8 +1513,10 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict
     // the three loads that depend only on the chunk's entry go out together
     const uint32_t nwords = (len + 31) >> 5;
     uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(base >> 5) + tid] : 0;
-    const uint32_t cbase = chunk_base[c];
-    if (state[ci.layer].mode == kModeSkip) {
+    const uint32_t mode = state[ci.layer].mode;
+    chunk_prefix_wave0(ci, c, chunk_cnt, group_cnt, &s_cbase);
+    if (mode == kModeSkip) {
+        if (ci.last && tid == 0) out_counts[ci.layer] = 0;
         const float *__restrict__ g = grad + base;
         const float *__restrict__ r = resid_in + base;
         for (uint32_t e = 4 * tid; e < len; e += 1024) {
@@ -1488,7 +1531,8 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict
         }
         return;
     }
-    if (!__syncthreads_or(word != 0u)) return;
+    if (!__syncthreads_or(word != 0u) && !ci.last) return;      // uniform
+    const uint32_t cbase = s_cbase;
     const uint32_t cnt = __popc(word);
     const uint32_t incl = block_scan_incl(cnt, wave_tot);
     // the chunk's kept elements, in ascending order, as offsets inside the chunk
@@ -1498,7 +1542,10 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict
         word &= word - 1u;
         s_list[pos++] = static_cast<uint16_t>(32u * static_cast<uint32_t>(tid) + b);
     }
-    if (tid == 255) s_total = incl;
+    if (tid == 255) {
+        s_total = incl;
+        if (ci.last) out_counts[ci.layer] = static_cast<int32_t>(cbase + incl);
+    }
     __syncthreads();
     const uint32_t total = s_total;
     const size_t obase = static_cast<size_t>(ci.out_off) + cbase;
@@ -1519,23 +1566,28 @@ __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict
 
 // Ascending list of the selected centres of every layer.
 __global__ __launch_bounds__(256) void k_emit_centres(const LayerDev *__restrict__ layers,
-                                                      const uint32_t *__restrict__ chunk_layer,
+                                                      const ChunkInfo *__restrict__ chunk_info,
                                                       const uint32_t *__restrict__ cmask,
-                                                      const uint32_t *__restrict__ chunk_cbase,
-                                                      uint32_t *__restrict__ out_centre_idx) {
+                                                      const uint32_t *__restrict__ chunk_ccnt,
+                                                      const uint32_t *__restrict__ group_ccnt,
+                                                      uint32_t *__restrict__ out_centre_idx,
+                                                      int32_t *__restrict__ out_centre_counts) {
     __shared__ uint32_t wave_tot[4];
+    __shared__ uint32_t s_cbase;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_layer[c];
-    const LayerDev L = layers[l];
-    const uint32_t start = (c - L.chunk_begin) * kChunk;
-    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-    const size_t base = static_cast<size_t>(L.elem_off) + start;
-    const uint32_t nwords = (len + 31) >> 5;
+    const ChunkInfo ci = chunk_info[c];
+    const LayerDev L = layers[ci.layer];
+    const uint32_t start = ci.start;
+    const size_t base = ci.arena_off;
+    const uint32_t nwords = (ci.len + 31) >> 5;
     uint32_t word = static_cast<uint32_t>(tid) < nwords ? cmask[(base >> 5) + tid] : 0;
+    chunk_prefix_wave0(ci, c, chunk_ccnt, group_ccnt, &s_cbase);
     const uint32_t cnt = __popc(word);
     const uint32_t incl = block_scan_incl(cnt, wave_tot);
-    uint32_t rank = chunk_cbase[c] + (incl - cnt);
+    const uint32_t cbase = s_cbase;
+    if (ci.last && tid == 255 && out_centre_counts) out_centre_counts[ci.layer] = static_cast<int32_t>(cbase + incl);
+    uint32_t rank = cbase + (incl - cnt);
     while (word) {
         const int b = __ffs(word) - 1;
         word &= word - 1;
@@ -1735,21 +1787,24 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
 __global__ __launch_bounds__(256) void k_emit_blocks(const LayerDev *__restrict__ outer,
                                                      const ChunkInfo *__restrict__ inner_chunks,
                                                      const uint32_t *__restrict__ mask,
-                                                     const uint32_t *__restrict__ chunk_base,
+                                                     const uint32_t *__restrict__ chunk_cnt,
+                                                     const uint32_t *__restrict__ group_cnt,
                                                      const LayerDev *__restrict__ inner,
                                                      float *__restrict__ v_arena,
                                                      uint32_t *__restrict__ out_blocks,
-                                                     float *__restrict__ out_val) {
+                                                     float *__restrict__ out_val,
+                                                     int32_t *__restrict__ out_counts) {
     __shared__ uint32_t wave_tot[4];
     __shared__ uint16_t s_list[kChunk];
-    __shared__ uint32_t s_total;
+    __shared__ uint32_t s_total, s_cbase;
     const int tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
     const ChunkInfo ci = inner_chunks[c];
     const uint32_t nwords = (ci.len + 31) >> 5;
     uint32_t word = static_cast<uint32_t>(tid) < nwords ? mask[(ci.arena_off >> 5) + tid] : 0;
-    const uint32_t cbase = chunk_base[c];
-    if (!__syncthreads_or(word != 0u)) return;
+    chunk_prefix_wave0(ci, c, chunk_cnt, group_cnt, &s_cbase);
+    if (!__syncthreads_or(word != 0u) && !ci.last) return;      // uniform
+    const uint32_t cbase = s_cbase;
     const uint32_t cnt = __popc(word);
     const uint32_t incl = block_scan_incl(cnt, wave_tot);
     uint32_t pos = incl - cnt;
@@ -1758,7 +1813,10 @@ __global__ __launch_bounds__(256) void k_emit_blocks(const LayerDev *__restrict_
         word &= word - 1u;
         s_list[pos++] = static_cast<uint16_t>(32u * static_cast<uint32_t>(tid) + b);
     }
-    if (tid == 255) s_total = incl;
+    if (tid == 255) {
+        s_total = incl;
+        if (ci.last) out_counts[ci.layer] = static_cast<int32_t>(cbase + incl);
+    }
     __syncthreads();
     const uint32_t total = s_total;
     const LayerDev O = outer[ci.layer];
@@ -2117,9 +2175,9 @@ extern "C" {
 const char *rsdgc_last_hip_error(void) { return g_hip_error; }
 
 // The part of a compress call between the NSI passes and the emit: radix select of every
-// layer's threshold, marking of the kept elements, kept counts per chunk and their prefix.
-static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, int32_t *out_counts,
-                             int32_t *out_centre_counts, StageMarks &marks, hipStream_t stream) {
+// layer's threshold, marking of the kept elements, kept counts per chunk and chunk group.
+static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, StageMarks &marks,
+                             hipStream_t stream) {
     const WsLayout &w = plan->ws;
     const int L = plan->n_layers;
     const uint32_t n_chunks = plan->n_chunks;
@@ -2197,10 +2255,9 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, in
         if (n_wgs > 0) hipLaunchKernelGGL(k_mark, dim3(n_wgs), dim3(256), 0, stream, m);
     }
     marks.close(5);
-    const ChunkInfo *chunk_info = reinterpret_cast<const ChunkInfo *>(ws + w.chunk_info);
-    hipLaunchKernelGGL(k_count, dim3(n_chunks), dim3(256), 0, stream, chunk_info, mask, cmask, chunk_cnt, chunk_ccnt);
-    hipLaunchKernelGGL(k_scan, dim3(L), dim3(kScanThreads), 0, stream, layers, state, chunk_cnt, chunk_ccnt,
-                       out_counts, out_centre_counts, cmask ? 1 : 0);
+    hipLaunchKernelGGL(k_count, dim3(plan->n_chunk_groups), dim3(kCountThreads), 0, stream,
+                       reinterpret_cast<const CountGroup *>(ws + w.count_groups), mask, cmask, chunk_cnt, chunk_ccnt,
+                       reinterpret_cast<uint32_t *>(ws + w.group_cnt), reinterpret_cast<uint32_t *>(ws + w.group_ccnt));
     marks.close(6);
     return RSDGC_OK;
 }
@@ -2236,6 +2293,7 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     uint32_t *flags = reinterpret_cast<uint32_t *>(ws + w.flags);
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
     uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
+    const uint32_t *group_cnt = reinterpret_cast<const uint32_t *>(ws + w.group_cnt);
     uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
     const bool want_centres = out_centre_idx || out_centre_counts;
     uint32_t *cmask = want_centres ? reinterpret_cast<uint32_t *>(ws + w.cmask) : nullptr;
@@ -2253,7 +2311,6 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     }
     marks.close(0);
 
-    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + w.chunk_layer);
     // first pass: the sampled tiles of the large layers (histogram only) and every tile of the
     // other layers (scores, histogram, v) share one launch
     rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
@@ -2274,19 +2331,21 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     }
     marks.close(3);
 
-    rc = select_mark_count(plan, ws, want_centres, out_counts, out_centre_counts, marks, stream);
+    rc = select_mark_count(plan, ws, want_centres, marks, stream);
     if (rc != RSDGC_OK) return rc;
     const ChunkInfo *chunk_info = reinterpret_cast<const ChunkInfo *>(ws + w.chunk_info);
     if (in_place)
-        hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer, grad,
-                           residual_out, mask, chunk_cnt, out_idx, out_val);
+        hipLaunchKernelGGL(k_emit, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_info, grad,
+                           residual_out, mask, chunk_cnt, group_cnt, out_idx, out_val, out_counts);
     else
         hipLaunchKernelGGL(k_emit_sparse, dim3(n_chunks), dim3(256), 0, stream, chunk_info, state, grad,
-                           residual, residual_out, mom.in, mom.out, mom.m, mask, chunk_cnt, out_idx, out_val);
+                           residual, residual_out, mom.in, mom.out, mom.m, mask, chunk_cnt, group_cnt, out_idx,
+                           out_val, out_counts);
     marks.close(7);
     if (out_centre_idx)
-        hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_layer,
-                           cmask, chunk_ccnt, out_centre_idx);
+        hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_info,
+                           cmask, chunk_ccnt, reinterpret_cast<const uint32_t *>(ws + w.group_ccnt), out_centre_idx,
+                           out_centre_counts);
     marks.close(8);
     HIP_TRY(hipGetLastError());
     return RSDGC_OK;
@@ -2359,6 +2418,7 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
     uint32_t *hist = reinterpret_cast<uint32_t *>(ws + w.hist);
     uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
+    const uint32_t *group_cnt = reinterpret_cast<const uint32_t *>(ws + w.group_cnt);
     float *score_map = reinterpret_cast<float *>(ws + w.nsi);
     StageMarks marks(in, stream);                      // (the inner plan never records events)
     {
@@ -2390,10 +2450,10 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
         }
     }
     HIP_TRY(hipGetLastError());
-    rc = select_mark_count(in, ws, false, out_counts, nullptr, marks, stream);
+    rc = select_mark_count(in, ws, false, marks, stream);
     if (rc != RSDGC_OK) return rc;
     hipLaunchKernelGGL(k_emit_blocks, dim3(in->n_chunks), dim3(256), 0, stream, outer, inner_chunks, mask,
-                       chunk_cnt, inner, residual_out, out_block_idx, out_val);
+                       chunk_cnt, group_cnt, inner, residual_out, out_block_idx, out_val, out_counts);
     HIP_TRY(hipGetLastError());
     return RSDGC_OK;
 }

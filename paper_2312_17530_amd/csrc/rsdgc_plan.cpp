@@ -105,6 +105,8 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(L)});
     plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(L)});
     plan->n_chunks = chunk_begin;
+    plan->n_chunk_groups = 0;
+    for (const LayerDev &d : plan->layers) plan->n_chunk_groups += (d.n_chunks + kChunkGroup - 1) / kChunkGroup;
     plan->n_tiles_all = tile_begin_all;
     plan->n_slot_groups = group_begin;
     plan->total_elems = elem_off;
@@ -175,12 +177,15 @@ int build_tables(rsdgc_plan_s *plan) {
     w.cand_groups = off;  off = align_up(off + sizeof(GroupEntry) * plan->n_slot_groups, A);
     w.map_chunks = off;   off = align_up(off + sizeof(ChunkEntry) * plan->n_chunks, A);
     w.map_tiles = off;    off = align_up(off + sizeof(SampleEntry) * (size_t(plan->n_tiles_all) + 1), A);
+    w.count_groups = off; off = align_up(off + sizeof(CountGroup) * plan->n_chunk_groups, A);
     w.table_bytes = off;
     w.state = off;        off = align_up(off + sizeof(SelState) * L, A);   // written in full each call
     w.zero_begin = off;
     w.hist = off;         off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
     w.chunk_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
+    w.group_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
+    w.group_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
     w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * kListShards * kListCntStride * size_t(L), A);
     w.list2_cnt = off;    off = align_up(off + sizeof(uint32_t) * L, A);
     w.flags = off;        off = align_up(off + sizeof(uint32_t) * 64, A);
@@ -210,15 +215,29 @@ int build_tables(rsdgc_plan_s *plan) {
     {
         uint32_t *cl = reinterpret_cast<uint32_t *>(plan->table.data() + w.chunk_layer);
         ChunkInfo *ci = reinterpret_cast<ChunkInfo *>(plan->table.data() + w.chunk_info);
+        CountGroup *cg = reinterpret_cast<CountGroup *>(plan->table.data() + w.count_groups);
+        uint32_t first_group = 0;
         for (int l = 0; l < L; ++l) {
             const LayerDev &d = plan->layers[l];
+            for (uint32_t c = 0; c < d.n_chunks; c += kChunkGroup) {
+                const uint32_t n = std::min<uint32_t>(kChunkGroup, d.n_chunks - c);
+                const uint64_t first_elem = static_cast<uint64_t>(c) * kChunk;
+                const uint64_t end_elem = std::min<uint64_t>(first_elem + static_cast<uint64_t>(n) * kChunk, d.G);
+                cg[first_group + c / kChunkGroup] =
+                    CountGroup{(static_cast<uint64_t>(d.elem_off) + first_elem) >> 5, d.chunk_begin + c, n,
+                               static_cast<uint32_t>((end_elem - first_elem + 31) / 32), 0u};
+            }
             for (uint32_t c = 0; c < d.n_chunks; ++c) {
                 cl[d.chunk_begin + c] = static_cast<uint32_t>(l);
                 const uint32_t start = c * kChunk;
                 ci[d.chunk_begin + c] = ChunkInfo{static_cast<uint64_t>(d.elem_off) + start,
                                                   static_cast<uint64_t>(d.out_off), static_cast<uint32_t>(l),
-                                                  start, std::min<uint32_t>(kChunk, d.G - start), d.cap};
+                                                  start, std::min<uint32_t>(kChunk, d.G - start), d.cap,
+                                                  first_group + c / kChunkGroup,
+                                                  d.chunk_begin + c / kChunkGroup * kChunkGroup, first_group,
+                                                  c + 1 == d.n_chunks ? 1u : 0u};
             }
+            first_group += (d.n_chunks + kChunkGroup - 1) / kChunkGroup;
         }
     }
     if (!plan->cand_groups.empty())
