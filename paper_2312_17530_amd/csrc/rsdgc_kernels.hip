@@ -596,28 +596,39 @@ __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
     const SelState st = state[l];
     if (tid == 0) found = 0;
     if (!st.done) {
-        // thread t owns bins [hi - per, hi), hi = nb - t * per  (t = 0 holds the top bins)
+        // thread t owns bins [hi - per, hi), hi = nb - t * per  (t = 0 holds the top bins); their
+        // counts (added over the copies) stay in registers for the walk below
         const int hi = nb - tid * per;
+        constexpr int kMaxPer = kHistBins / 256, kMaxCopies = kHistBins >> level_bits(1);
+        uint32_t v[kMaxPer];
         uint32_t own = 0;
-        for (int cp = 0; cp < copies; ++cp)
-            for (int b = hi - 1; b >= hi - per; --b) own += h[cp * nb + b];
+#pragma unroll
+        for (int j = 0; j < kMaxPer; ++j) {
+            v[j] = 0;
+            if (j < per) {
+#pragma unroll
+                for (int cp = 0; cp < kMaxCopies; ++cp)
+                    if (cp < copies) v[j] += h[cp * nb + hi - 1 - j];
+            }
+            own += v[j];
+        }
         const uint32_t incl = block_scan_incl(own, wave_tot);
         const uint32_t excl = incl - own;
         if (excl < st.k_rem && st.k_rem <= incl) {
             uint32_t acc = excl;
-            for (int b = hi - 1; b >= hi - per; --b) {
-                uint32_t c = 0;
-                for (int cp = 0; cp < copies; ++cp) c += h[cp * nb + b];
-                if (acc + c >= st.k_rem) {
+            bool hit = false;
+#pragma unroll
+            for (int j = 0; j < kMaxPer; ++j) {
+                if (!hit && j < per && acc + v[j] >= st.k_rem) {
                     SelState ns = st;
-                    ns.T = st.T | (static_cast<unsigned long long>(b) << shift);
+                    ns.T = st.T | (static_cast<unsigned long long>(hi - 1 - j) << shift);
                     ns.k_rem = st.k_rem - acc;
-                    ns.done = (c == ns.k_rem) ? 1u : 0u;   // whole bucket taken: lower digits stay 0
+                    ns.done = (v[j] == ns.k_rem) ? 1u : 0u;   // whole bucket taken: lower digits stay 0
                     state[l] = ns;
                     found = 1;
-                    break;
+                    hit = true;
                 }
-                acc += c;
+                if (!hit) acc += v[j];
             }
         }
         __syncthreads();
