@@ -88,6 +88,18 @@ int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio);
 #define RSDGC_PATH_FULL_MAP  1
 int rsdgc_plan_set_path(rsdgc_plan_t *plan, int32_t path);
 
+/* How the main pass hands its tiles to the workgroups; the result is the same.
+ *   RSDGC_FEED_AUTO  from per-XCD work counters when a launch has many tiles per
+ *                    workgroup (where it is faster), else a fixed strided share (default).
+ *   RSDGC_FEED_OFF   always the fixed share.
+ *   RSDGC_FEED_ON    the counters whenever the kernel variant has them (p <= 3), also for
+ *                    small launches (meant for tests).
+ * Returns RSDGC_EINVAL for a null plan or an unknown mode.                          */
+#define RSDGC_FEED_AUTO  0
+#define RSDGC_FEED_OFF   1
+#define RSDGC_FEED_ON    2
+int rsdgc_plan_set_work_feed(rsdgc_plan_t *plan, int32_t mode);
+
 void rsdgc_plan_destroy(rsdgc_plan_t *plan);
 
 /* Host queries; l in [0, n_layers).  Invalid arguments give -1 (0 for size_t). */

@@ -175,6 +175,7 @@ struct WsLayout {
     size_t group_ccnt = 0;   // uint32[n_chunk_groups]  selected centres per chunk group
     size_t list_cnt = 0;     // uint32[n_layers][kListShards][kListCntStride]  keys gathered per list shard
     size_t list2_cnt = 0;    // uint32[n_layers]  of those, keys that also share the second digit
+    size_t feed = 0;         // uint32[16][8][32]  work-feed counters of the NSI launches
     size_t flags = 0;        // uint32[64]  [0]: some large layer fell back to the full map
     size_t mask = 0;         // uint32[total_elems / 32]  kept-element bitmask
     size_t cmask = 0;        // uint32[total_elems / 32]  selected-centre bitmask
@@ -224,6 +225,7 @@ struct rsdgc_plan_s {
     int64_t centre_capacity = 0;
     uint32_t n_chunks = 0;
     uint32_t n_chunk_groups = 0;  // chunk groups over all layers
+    int work_feed = 0;            // RSDGC_FEED_*
     rsdgc::WsLayout ws;
     std::vector<unsigned char> table;   // host image of the uploaded tables
     // device-side bookkeeping

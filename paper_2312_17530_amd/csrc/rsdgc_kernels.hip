@@ -176,6 +176,72 @@ __device__ __forceinline__ double nsi_from_sums(double sa, double ss, double sq,
     return fma(cb, g, ca * sa);
 }
 
+// ----------------------------------------------------------- work feed --
+// Hands the items of a launch (tiles) to its persistent workgroups.  With a fixed strided
+// share per workgroup the workgroups drift apart (measured on the VGG-19 main pass: the first
+// leaves at 240 us, the mean at 310, the last at 390); here every workgroup takes its next item
+// from a counter when it is ready.
+//
+// Locality is kept: the items are cut into stretches of 8 * S consecutive items, part d of
+// every stretch belongs to domain d (one per XCD: workgroups are handed to the XCDs
+// round-robin by id), and a domain's counter walks its parts in order -- so at any moment an
+// XCD's workgroups hold consecutive items (neighbouring tiles share halo rows in that XCD's
+// L2), and a counter's cache line stays in that XCD's L2.  A workgroup leaves when its own
+// domain is used up: taking from other domains was measured too (in ring order, or from the
+// fullest), and the tickets it costs on other XCDs' counters outweigh the better balance.
+//
+// The ticket for the item after the current one is requested (one atomic by thread 0) when the
+// current item starts and read when it ends, so its latency is hidden.
+constexpr uint32_t kNoItem = 0xffffffffu;
+constexpr int kFeedDomains = 8;
+constexpr int kFeedStride = 32;          // uint32 between two counters (one 128-byte line each)
+constexpr int kFeedSets = 16;            // counter sets per call: (pass, p-group) pairs
+
+// Items of domain d: part d of every full stretch, and its share of the last, partial one.
+__device__ __forceinline__ uint32_t feed_domain_items(uint32_t n_items, uint32_t shift, uint32_t d) {
+    const uint32_t S = 1u << shift;
+    const uint32_t full = n_items >> (shift + 3), rem = n_items & ((S << 3) - 1u);
+    const uint32_t lo = d << shift;
+    return (full << shift) + (rem > lo ? min(rem - lo, S) : 0u);
+}
+
+struct WorkFeed {
+    uint32_t st;          // bit 0: LDS slot of the next hand-over, bit 1: the requested ticket is in it
+    uint32_t pending;     // thread 0: the ticket requested last
+
+    // Thread 0 puts the requested ticket into LDS.  Reading it waits for the wave's memory
+    // operations up to the request, and the compiler may make that a wait for everything
+    // issued since.  So the item's code calls this after its loads have arrived and before
+    // its first store; next() does it for items that never got there.
+    __device__ __forceinline__ void stash(uint32_t *slot /*[2], LDS*/) {
+        if (st & 2u) return;                           // uniform
+        if (threadIdx.x == 0) slot[st & 1u] = pending;
+        st |= 2u;
+    }
+    // Called by all threads of the workgroup (it contains a barrier); returns the next item or
+    // kNoItem.  ctr: the launch's kFeedDomains counters, zero at launch.
+    __device__ __forceinline__ uint32_t next(uint32_t *__restrict__ ctr, uint32_t n_items, uint32_t shift,
+                                             uint32_t *slot) {
+        stash(slot);
+        const uint32_t par = st & 1u, dom = blockIdx.x % kFeedDomains;
+        __syncthreads();
+        const uint32_t t = __builtin_amdgcn_readfirstlane(slot[par]);   // the same in every lane: keep it scalar
+        st = par ^ 1u;
+        if (t >= feed_domain_items(n_items, shift, dom)) return kNoItem;   // uniform: the domain is used up
+        if (threadIdx.x == 0) pending = atomicAdd(&ctr[dom * kFeedStride], 1u);
+        return ((t >> shift) * kFeedDomains + dom) * (1u << shift) + (t & ((1u << shift) - 1u));
+    }
+    __device__ __forceinline__ uint32_t first(uint32_t *__restrict__ ctr, uint32_t n_items, uint32_t shift,
+                                              uint32_t *slot) {
+        const uint32_t dom = blockIdx.x % kFeedDomains;    // workgroups go to the XCDs round-robin by id
+        st = 0;
+        pending = kNoItem;                                  // an empty domain never touches its counter
+        if (threadIdx.x == 0 && feed_domain_items(n_items, shift, dom) != 0u)
+            pending = atomicAdd(&ctr[dom * kFeedStride], 1u);
+        return next(ctr, n_items, shift, slot);
+    }
+};
+
 // ------------------------------------------------------------------ nsi --
 // What one launch of the NSI kernel produces.
 enum NsiPass : int {
@@ -206,6 +272,8 @@ struct NsiArgs {
     uint32_t *slot_cnt;           // [n_tiles_all]
     unsigned long long *slot_ent; // [n_tiles_all][kSlotCap]
     double alpha;
+    uint32_t *feed;               // work-feed counters of this launch (all but kPassMapOnly)
+    uint32_t feed_shift;          // log2 of the items per domain and stretch
 };
 
 // Work unit: one 16 x 256 tile of one layer.  The tile of v = r + g plus a halo of
@@ -219,8 +287,11 @@ struct NsiArgs {
 // one contiguous stretch of the launch: neighbouring tiles share halo rows in one L2).
 // Its LDS histogram is flushed to the layer's global histogram only when the layer
 // changes or the range ends, so a launch issues few same-address global atomics.
-template <int P, int PASS, bool MOM>   // MOM: with Eq. 12's momentum term (a.mom, a.mom_out, a.m)
-__global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
+// MOM: with Eq. 12's momentum term (a.mom, a.mom_out, a.m).  FEED: the workgroups take their
+// tiles from the launch's work feed instead of a fixed strided share.
+template <int P, int PASS, bool MOM, bool FEED>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FEED && !MOM ? 4 : 1, 8)))
+void k_nsi(const NsiArgs a) {
     constexpr int H = (P - 1) / 2;
     constexpr int ROWS = kTileRows + 2 * H;
     constexpr int PADL = 4;
@@ -236,15 +307,24 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     __shared__ uint32_t lhist[NBINS];
     __shared__ unsigned long long cand[CAPTURE ? kSlotCap : 1];
     __shared__ uint32_t ncand;
+    __shared__ uint32_t feed_slot[2];
 
     const int tid = threadIdx.x;
-    // grid-stride share of the launch's work items (tiles, or sampled tiles): at any moment
-    // the resident workgroups work on one compact stretch of tiles, so neighbouring tiles'
-    // halo rows are still in cache; inside a stretch each XCD takes one contiguous part
+    // the launch's work items (tiles, or sampled tiles): at any moment the resident workgroups
+    // work on one compact stretch of tiles, so neighbouring tiles' halo rows are still in
+    // cache; inside a stretch each XCD takes one contiguous part
     const uint32_t n_items = a.n_tiles;
-    const uint32_t first = xcd_contiguous(blockIdx.x, gridDim.x), stride = gridDim.x, last = n_items;
-    if (first >= last) return;
+    const uint32_t stride = gridDim.x;
     if (PASS == kPassFullMap && a.flags[0] == 0u) return;   // no layer fell back: nothing to do
+    WorkFeed feed;
+    uint32_t first;
+    if (FEED) {
+        first = feed.first(a.feed, n_items, a.feed_shift, feed_slot);
+        if (first == kNoItem) return;      // uniform
+    } else {
+        first = xcd_contiguous(blockIdx.x, gridDim.x);
+        if (first >= n_items) return;
+    }
 
     if (NBINS > 1)
         for (int b = tid; b < NBINS; b += 256) lhist[b] = 0;
@@ -267,7 +347,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
     const int c0 = 2 * tx;
     const int row_base = ty * RPT;
 
-    for (uint32_t t = first; t < last; t += stride) {
+    for (uint32_t t = first; FEED ? t != kNoItem : t < n_items; t = FEED ? feed.next(a.feed, n_items, a.feed_shift, feed_slot) : t + stride) {
         uint32_t l, local;
         if (PASS == kPassSample) {
             const SampleEntry se = a.samples[t];
@@ -301,7 +381,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
             }
         }
         if (!active) {                    // skip the rest of this layer
-            if (PASS != kPassSample) {
+            if (!FEED && PASS != kPassSample) {
                 const uint32_t nb = a.dir[e + 1].begin;          // first tile of the next layer
                 t += (nb - t + stride - 1) / stride * stride - stride;   // loop increment adds the last stride
             }
@@ -345,6 +425,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                     if (s < NVEC && x >= 0 && x < R && y >= 0 && y < C)
                         uv[it] = *reinterpret_cast<const float4 *>(u + static_cast<size_t>(x) * C + y);
                 }
+                if (FEED) feed.stash(feed_slot);   // the loads are out, no store of this tile yet
 #pragma unroll
                 for (int it = 0; it < ITER; ++it) {
                     gv[it].x = __fmul_rn(a.m, uv[it].x) + gv[it].x;
@@ -360,6 +441,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                     }
                 }
             }
+            if (FEED) feed.stash(feed_slot);       // the loads are out, no store of this tile yet
 #pragma unroll
             for (int it = 0; it < ITER; ++it) {
                 const int s = tid + it * 256;
@@ -379,6 +461,7 @@ __global__ __launch_bounds__(256) void k_nsi(const NsiArgs a) {
                 }
             }
         } else {
+            if (FEED) feed.stash(feed_slot);
             for (int s = tid; s < ROWS * PITCH; s += 256) {
                 const int rr = s / PITCH, j = s - rr * PITCH;
                 const int x = x0 - H + rr, y = y0 - PADL + j;
@@ -2122,7 +2205,12 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
     a.alpha = plan->alpha;
     const DirEntry *tile_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.tile_dir);
     const SampleEntry *samples = reinterpret_cast<const SampleEntry *>(ws + plan->ws.samples);
+    uint32_t *feed = reinterpret_cast<uint32_t *>(ws + plan->ws.feed);
+    int group_index = 0;
     for (const PGroup &g : plan->groups) {
+        // this launch's work-feed counters (cleared at the start of the call)
+        const int pass_index = PASS == kPassSample ? 0 : PASS == kPassCapture ? 1 : 2;
+        a.feed = feed + static_cast<size_t>((pass_index * 4 + group_index++) % kFeedSets) * kFeedDomains * kFeedStride;
         a.dir = tile_dir + g.dir_begin;
         a.n_dir = g.dir_count;
         a.n_tiles = g.n_tiles;
@@ -2131,18 +2219,29 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
         const uint32_t items = PASS == kPassSample ? g.n_samples : g.n_tiles;
         if (items == 0) continue;
         a.n_tiles = items;
+        a.feed_shift = 7;                  // 128 items per domain and stretch: one per resident workgroup of an XCD
+        while (a.feed_shift > 0 && (static_cast<uint32_t>(kFeedDomains) << a.feed_shift) > items) --a.feed_shift;
         const dim3 block(256);
         switch (g.p) {
+#define RSDGC_NSI_LAUNCH(PP, MM, FF)                                                        \
+    {                                                                                       \
+        static const uint32_t resident = resident_workgroups(k_nsi<PP, PASS, MM, FF>);      \
+        const dim3 grid(std::min<uint32_t>(items, resident));                               \
+        hipLaunchKernelGGL((k_nsi<PP, PASS, MM, FF>), grid, block, 0, stream, a);           \
+    }
 #define RSDGC_NSI_CASE(PP)                                                                  \
     case PP: {                                                                              \
+        /* the work feed pays when a workgroup gets many tiles (its start and its end cost  \
+           a few round trips to the counters); built for the main pass of p <= 3 */         \
+        constexpr bool kFeedBuilt = PP <= 3 && PASS == kPassCapture;                        \
+        const bool fed = kFeedBuilt && plan->work_feed != RSDGC_FEED_OFF &&                 \
+                         (plan->work_feed == RSDGC_FEED_ON || items >= 16u * kNumCUs * 4u); \
         if (mom.in) {                                                                       \
-            static const uint32_t resident = resident_workgroups(k_nsi<PP, PASS, true>);    \
-            const dim3 grid(std::min<uint32_t>(items, resident));                           \
-            hipLaunchKernelGGL((k_nsi<PP, PASS, true>), grid, block, 0, stream, a);          \
+            if (fed) RSDGC_NSI_LAUNCH(PP, true, kFeedBuilt)                                 \
+            else RSDGC_NSI_LAUNCH(PP, true, false)                                          \
         } else {                                                                            \
-            static const uint32_t resident = resident_workgroups(k_nsi<PP, PASS, false>);   \
-            const dim3 grid(std::min<uint32_t>(items, resident));                           \
-            hipLaunchKernelGGL((k_nsi<PP, PASS, false>), grid, block, 0, stream, a);         \
+            if (fed) RSDGC_NSI_LAUNCH(PP, false, kFeedBuilt)                                \
+            else RSDGC_NSI_LAUNCH(PP, false, false)                                         \
         }                                                                                   \
         break;                                                                              \
     }
@@ -2151,6 +2250,7 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
             RSDGC_NSI_CASE(5)
             RSDGC_NSI_CASE(7)
 #undef RSDGC_NSI_CASE
+#undef RSDGC_NSI_LAUNCH
             default: return RSDGC_EINVAL;
         }
         HIP_TRY(hipGetLastError());

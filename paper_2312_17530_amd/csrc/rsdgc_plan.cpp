@@ -188,6 +188,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.group_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
     w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * kListShards * kListCntStride * size_t(L), A);
     w.list2_cnt = off;    off = align_up(off + sizeof(uint32_t) * L, A);
+    w.feed = off;         off = align_up(off + sizeof(uint32_t) * 16 * 8 * 32, A);
     w.flags = off;        off = align_up(off + sizeof(uint32_t) * 64, A);
     w.mask = off;         off = align_up(off + sizeof(uint32_t) * words, A);
     w.cmask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
@@ -350,6 +351,13 @@ int rsdgc_plan_set_path(rsdgc_plan_t *plan, int32_t path) {
     } catch (const std::bad_alloc &) {
         return RSDGC_ENOMEM;
     }
+    return RSDGC_OK;
+}
+
+int rsdgc_plan_set_work_feed(rsdgc_plan_t *plan, int32_t mode) {
+    if (!plan || mode < RSDGC_FEED_AUTO || mode > RSDGC_FEED_ON) return RSDGC_EINVAL;
+    plan->work_feed = mode;
+    if (plan->inner) plan->inner->work_feed = mode;
     return RSDGC_OK;
 }
 

@@ -15,11 +15,14 @@ class Session:
     def __init__(self, shapes, p: int, alpha: float, ratios: Sequence[float],
                  p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0",
                  want_centres: bool = True, path: int = binding.RSDGC_PATH_AUTO,
-                 in_place: bool = False, momentum: Optional[float] = None):
+                 in_place: bool = False, momentum: Optional[float] = None,
+                 work_feed: int = binding.FEED_AUTO):
         self.shapes = [(int(r), int(c)) for r, c in shapes]
         self.plan = binding.rsdgc_plan(self.shapes, p, alpha, ratios, p_per_layer)
         if path != binding.RSDGC_PATH_AUTO:
             binding.rsdgc_plan_set_path(self.plan, path)
+        if work_feed != binding.FEED_AUTO:
+            binding.rsdgc_plan_set_work_feed(self.plan, work_feed)
         self.device = torch.device(device)
         n = self.plan.total_elems
         L = self.plan.n_layers

@@ -101,6 +101,18 @@ def test_set_ratios_recomputes_counts_and_validates():
     assert [plan.layer_k(0), plan.layer_k(1)] == [0, 192]      # unchanged after the error
 
 
+def test_work_feed_mode_is_validated():
+    plan = binding.rsdgc_plan([(64, 64)], 3, 0.5, [0.1])
+    ws = plan.workspace_bytes
+    for mode in (binding.FEED_ON, binding.FEED_OFF, binding.FEED_AUTO):
+        binding.rsdgc_plan_set_work_feed(plan, mode)
+    assert plan.workspace_bytes == ws
+    for bad in (-1, 3):
+        with pytest.raises(binding.RsdgcError):
+            binding.rsdgc_plan_set_work_feed(plan, bad)
+    assert binding.load().rsdgc_plan_set_work_feed(None, 0) == binding.RSDGC_EINVAL
+
+
 def test_per_layer_neighbourhood_side():
     plan = binding.rsdgc_plan([(90, 90), (90, 90), (90, 90)], 3, 0.5, [0.1, 0.1, 0.1], [1, 3, 5])
     assert [plan.layer_k(l) for l in range(3)] == [810, 90, 33]

@@ -19,17 +19,20 @@ def in_place(request):
     return request.param
 
 
-def _session(shapes, p, alpha, ratios, p_per_layer=None, path=AUTO, in_place=False):
+def _session(shapes, p, alpha, ratios, p_per_layer=None, path=AUTO, in_place=False, work_feed=0):
     from paper_2312_17530_amd.session import Session
-    return Session(shapes, p, alpha, ratios, p_per_layer, path=path, in_place=in_place)
+    return Session(shapes, p, alpha, ratios, p_per_layer, path=path, in_place=in_place, work_feed=work_feed)
+
+
+FEED_AUTO, FEED_OFF, FEED_ON = 0, 1, 2
 
 
 def run_and_check(shapes, p_list, alpha, ratios, grads_per_iter, name="case", check_nsi=True,
-                  path=AUTO, in_place=False):
+                  path=AUTO, in_place=False, work_feed=FEED_AUTO):
     """Runs every iteration on GPU and oracle from identical state and applies the parity rule.
     Returns (number of layer-iterations compared, number that matched the oracle exactly)."""
     import torch
-    sess = _session(shapes, p_list[0], alpha, ratios, p_list, path, in_place)
+    sess = _session(shapes, p_list[0], alpha, ratios, p_list, path, in_place, work_feed)
     name = f"{name}/{'in_place' if in_place else 'two_arenas'}"
     L = len(shapes)
     resid = [np.zeros(sh, dtype=np.float32) for sh in shapes]
@@ -68,11 +71,12 @@ def run_and_check(shapes, p_list, alpha, ratios, grads_per_iter, name="case", ch
     return n_cmp, n_exact
 
 
-def run_and_check_momentum(shapes, p_list, alpha, ratios, m, grads_per_iter, name, u0=None, r0=None):
+def run_and_check_momentum(shapes, p_list, alpha, ratios, m, grads_per_iter, name, u0=None, r0=None,
+                           work_feed=FEED_AUTO):
     """Eq. 12 in full: every iteration on GPU and oracle from identical (u, r) state."""
     import torch
     from paper_2312_17530_amd.session import Session
-    sess = Session(shapes, p_list[0], alpha, ratios, p_list, momentum=m)
+    sess = Session(shapes, p_list[0], alpha, ratios, p_list, momentum=m, work_feed=work_feed)
     L = len(shapes)
     mom = u0 if u0 is not None else [np.zeros(sh, dtype=np.float32) for sh in shapes]
     resid = r0 if r0 is not None else [np.zeros(sh, dtype=np.float32) for sh in shapes]
@@ -445,6 +449,34 @@ def test_large_layers_with_rows_that_are_not_whole_mask_words(in_place):
     assert paths[0] == 0 and paths[3] == 0, "expected the candidate path"
 
 
+@pytest.mark.parametrize("in_place", [False, True], ids=["two_arenas", "in_place"])
+def test_work_feed_on_small_launches(in_place):
+    """The main pass can hand out its tiles through per-XCD work counters; by default it does so
+    only for launches of many thousand tiles.  Forced on here, so that the small cases meet it
+    too: ragged shapes with mixed p (launches of a few tiles, most domains empty), large layers
+    with unaligned rows, ResNet-18, the fallback inputs, and the momentum form."""
+    shapes = RAGGED
+    p_list = [1, 3, 5, 7, 3, 5, 3, 3, 7, 5, 3, 1, 3, 5]
+    ratios = [1.0, 0.1, 0.1, 1.0, 0.02, 0.05, 0.02, 0.01, 0.3, 0.001, 0.5, 0.07, 0.0, 1.0]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 19, t, l) for l, sh in enumerate(shapes)] for t in range(2)]
+    n, ex = run_and_check(shapes, p_list, 0.5, ratios, its, "feed/ragged", in_place=in_place, work_feed=FEED_ON)
+    assert n == 2 * len(shapes) and ex >= n - 2
+    shapes = [(700, 1100), (1000, 2570), (640, 1536), (2100, 333)]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 31, t, l) for l, sh in enumerate(shapes)] for t in range(2)]
+    n, ex = run_and_check(shapes, [3, 1, 3, 3], 0.5, [0.02, 0.01, 0.03, 0.05], its, "feed/large_unaligned",
+                          in_place=in_place, work_feed=FEED_ON)
+    assert n == 2 * len(shapes) and ex >= n - 1
+    w = synth.config(1)
+    its = [synth.gradients(w, t) for t in range(2)]
+    n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, "feed/" + w.name,
+                          in_place=in_place, work_feed=FEED_ON)
+    assert n == 2 * w.n_layers and ex >= n - 2
+    if not in_place:
+        n, ex = run_and_check_momentum(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, 0.9, its,
+                                       "feed/momentum/" + w.name, work_feed=FEED_ON)
+        assert n == 2 * w.n_layers and ex >= n - 2
+
+
 def _tile_is_sampled(t):
     """The library samples one tile in 16 (layers below 4096 tiles) by this hash of the tile's
     index inside its layer."""
@@ -475,9 +507,10 @@ def test_candidate_path_falls_back_when_its_bound_fails(in_place):
     shapes = [(R, C), (R, C), (R, C)]
     grads = [hot_sampled, hot_tile, base]
     for ratios in ([0.3, 0.02, 0.02], [0.02, 0.2, 0.01]):
-        n, ex = run_and_check(shapes, [3, 3, 3], 0.5, ratios, [grads, grads], "fallback",
-                              in_place=in_place)
-        assert n == 6 and ex >= 5
+        for feed in (FEED_AUTO, FEED_ON):
+            n, ex = run_and_check(shapes, [3, 3, 3], 0.5, ratios, [grads, grads], "fallback",
+                                  in_place=in_place, work_feed=feed)
+            assert n == 6 and ex >= 5
 
 
 def test_set_ratios_and_determinism():
