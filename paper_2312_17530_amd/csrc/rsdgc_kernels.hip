@@ -1742,7 +1742,9 @@ __global__ __launch_bounds__(256) void k_scatter(const LayerDev *__restrict__ la
 // tiles), then every thread takes blocks of the tile: Eqs. 8-10 in double over the p*p slots
 // (zero outside the matrix, divisor p*p), score to the inner score map, 12-bit histogram.
 // Persistent workgroups stride over the tiles; the histogram is flushed on layer change.
-template <int P>
+// FEED: tiles come from the launch's work feed (many tiles per workgroup) instead of a
+// fixed strided share.
+template <int P, bool FEED>
 __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ outer,
                                                    const DirEntry *__restrict__ tile_dir,
                                                    uint32_t n_layers, uint32_t n_tiles,
@@ -1750,7 +1752,8 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
                                                    const float *__restrict__ grad,
                                                    const float *resid, float *v_out,
                                                    float *__restrict__ score_map,
-                                                   uint32_t *__restrict__ hist, double alpha) {
+                                                   uint32_t *__restrict__ hist, double alpha,
+                                                   uint32_t *__restrict__ feed_ctr, uint32_t feed_shift) {
     constexpr int BCT = block_tile_cols(P);
     constexpr int TR = kBlockTileRows * P, TC = BCT * P;      // tile in elements; TC is a multiple of 4
     constexpr int VEC_PER_ROW = TC / 4;
@@ -1760,9 +1763,18 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
     static_assert(TC % 4 == 0, "tile rows are whole 16-byte groups");
     __shared__ __attribute__((aligned(16))) float tile[TR * TC];
     __shared__ uint32_t lhist[kHistBins];
+    __shared__ uint32_t feed_slot[2];
     const int tid = threadIdx.x;
-    const uint32_t first = blockIdx.x, stride = gridDim.x;
-    if (first >= n_tiles) return;
+    const uint32_t stride = gridDim.x;
+    WorkFeed feed;
+    uint32_t first;
+    if (FEED) {
+        first = feed.first(feed_ctr, n_tiles, feed_shift, feed_slot);
+        if (first == kNoItem) return;      // uniform
+    } else {
+        first = blockIdx.x;
+        if (first >= n_tiles) return;
+    }
     for (int b = tid; b < kHistBins; b += 256) lhist[b] = 0;
     __syncthreads();
     const double n = static_cast<double>(P * P);
@@ -1771,7 +1783,8 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
     uint32_t cur_l = 0xffffffffu;
     bool active = false;
     LayerDev O, I;
-    for (uint32_t t = first; t < n_tiles; t += stride) {
+    for (uint32_t t = first; FEED ? t != kNoItem : t < n_tiles;
+         t = FEED ? feed.next(feed_ctr, n_tiles, feed_shift, feed_slot) : t + stride) {
         while (t >= tile_dir[e + 1].begin) ++e;
         const uint32_t l = tile_dir[e].layer;
         if (l != cur_l) {
@@ -1789,8 +1802,10 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
             active = static_cast<int>(O.p) == P;       // another launch takes the other neighbourhood sides
         }
         if (!active) {
-            const uint32_t nb = tile_dir[e + 1].begin;
-            t += (nb - t + stride - 1) / stride * stride - stride;
+            if (!FEED) {
+                const uint32_t nb = tile_dir[e + 1].begin;
+                t += (nb - t + stride - 1) / stride * stride - stride;
+            }
             continue;
         }
         const uint32_t local = t - tile_dir[e].begin;
@@ -1816,6 +1831,7 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
                     rv[it] = *reinterpret_cast<const float4 *>(r + off);
                 }
             }
+            if (FEED) feed.stash(feed_slot);      // the loads are out, no store of this tile yet
 #pragma unroll
             for (int it = 0; it < ITER; ++it) {
                 const int s = tid + it * 256;
@@ -2540,17 +2556,31 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
     }
     bool have[RSDGC_MAX_P + 1] = {};
     for (int l = 0; l < L; ++l) have[plan->p[l]] = true;
+    // the work feed (counters in the inner plan's workspace, cleared above) pays when a
+    // workgroup gets many tiles
+    uint32_t *feed = reinterpret_cast<uint32_t *>(ws + w.feed);
+    const bool fed = plan->work_feed != RSDGC_FEED_OFF &&
+                     (plan->work_feed == RSDGC_FEED_ON || plan->n_tiles_all >= 16u * kNumCUs * 4u);
+    uint32_t feed_shift = 7;
+    while (feed_shift > 0 && (static_cast<uint32_t>(kFeedDomains) << feed_shift) > plan->n_tiles_all) --feed_shift;
     for (int pp = 1; pp <= RSDGC_MAX_P; pp += 2) {
         if (!have[pp]) continue;
         switch (pp) {
-#define RSDGC_BLOCK_CASE(PP)                                                                     \
-    case PP: {                                                                                   \
-        static const uint32_t resident = resident_workgroups(k_block_nsi<PP>);                   \
-        hipLaunchKernelGGL((k_block_nsi<PP>), dim3(std::min<uint32_t>(plan->n_tiles_all, resident)), \
+#define RSDGC_BLOCK_LAUNCH(PP, FF)                                                               \
+    {                                                                                            \
+        static const uint32_t resident = resident_workgroups(k_block_nsi<PP, FF>);               \
+        hipLaunchKernelGGL((k_block_nsi<PP, FF>), dim3(std::min<uint32_t>(plan->n_tiles_all, resident)), \
                            dim3(256), 0, stream, outer,                                          \
                            reinterpret_cast<const DirEntry *>(ws_outer + plan->ws.all_tile_dir), \
                            static_cast<uint32_t>(L), plan->n_tiles_all, inner, grad, residual,   \
-                           residual_out, score_map, hist, plan->alpha);                          \
+                           residual_out, score_map, hist, plan->alpha,                           \
+                           feed + static_cast<size_t>(PP / 2) * kFeedDomains * kFeedStride,      \
+                           feed_shift);                                                          \
+    }
+#define RSDGC_BLOCK_CASE(PP)                                                                     \
+    case PP: {                                                                                   \
+        if (fed) RSDGC_BLOCK_LAUNCH(PP, true)                                                    \
+        else RSDGC_BLOCK_LAUNCH(PP, false)                                                       \
         break;                                                                                   \
     }
             RSDGC_BLOCK_CASE(1)
@@ -2558,6 +2588,7 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
             RSDGC_BLOCK_CASE(5)
             RSDGC_BLOCK_CASE(7)
 #undef RSDGC_BLOCK_CASE
+#undef RSDGC_BLOCK_LAUNCH
         }
     }
     HIP_TRY(hipGetLastError());

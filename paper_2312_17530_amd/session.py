@@ -136,10 +136,13 @@ class BlockSession:
     """The same plumbing for the block reading (rsdgc_plan_blocks / rsdgc_compress_blocks)."""
 
     def __init__(self, shapes, p: int, alpha: float, ratios: Sequence[float],
-                 p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0", in_place: bool = False):
+                 p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0", in_place: bool = False,
+                 work_feed: int = binding.FEED_AUTO):
         self.shapes = [(int(r), int(c)) for r, c in shapes]
         self.p_list = [int(x) for x in p_per_layer] if p_per_layer is not None else [int(p)] * len(self.shapes)
         self.plan = binding.rsdgc_plan_blocks(self.shapes, p, alpha, ratios, p_per_layer)
+        if work_feed != binding.FEED_AUTO:
+            binding.rsdgc_plan_set_work_feed(self.plan, work_feed)
         self.device = torch.device(device)
         dev = self.device
         n, L = self.plan.total_elems, self.plan.n_layers

@@ -263,11 +263,11 @@ def test_apply_messages_of_three_nodes_matches_the_oracle():
         weights = got
 
 
-def run_and_check_blocks(shapes, p_list, alpha, ratios, grads_per_iter, name, in_place=False):
+def run_and_check_blocks(shapes, p_list, alpha, ratios, grads_per_iter, name, in_place=False, work_feed=0):
     """The block reading on GPU and oracle from identical state; returns (compared, exact)."""
     import torch
     from paper_2312_17530_amd.session import BlockSession
-    sess = BlockSession(shapes, p_list[0], alpha, ratios, p_list, in_place=in_place)
+    sess = BlockSession(shapes, p_list[0], alpha, ratios, p_list, in_place=in_place, work_feed=work_feed)
     resid = [np.zeros(sh, dtype=np.float32) for sh in shapes]
     n_cmp = n_exact = 0
     for t, grads in enumerate(grads_per_iter):
@@ -348,6 +348,23 @@ def test_blocks_resnet18_shapes():
     w = synth.config(1)
     its = [synth.gradients(w, t) for t in range(2)]
     n, ex = run_and_check_blocks(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, w.name)
+    assert n == 2 * w.n_layers and ex >= n - 2
+
+
+@pytest.mark.parametrize("in_place", [False, True], ids=["two_arenas", "in_place"])
+def test_blocks_with_the_work_feed_forced_on(in_place):
+    """The block-score pass with its tiles handed out through the work counters (by default only
+    for launches of many thousand tiles): ragged shapes with mixed p, and ResNet-18."""
+    shapes = RAGGED
+    p_list = [1, 3, 5, 7, 3, 5, 3, 3, 7, 5, 3, 1, 3, 5]
+    ratios = [1.0, 0.1, 0.1, 1.0, 0.02, 0.05, 0.02, 0.01, 0.3, 0.001, 0.5, 0.07, 0.0, 1.0]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 23, t, l) for l, sh in enumerate(shapes)] for t in range(2)]
+    n, ex = run_and_check_blocks(shapes, p_list, 0.5, ratios, its, "blocks/feed/ragged", in_place=in_place, work_feed=2)
+    assert n == 2 * len(shapes) and ex >= n - 2
+    w = synth.config(1)
+    its = [synth.gradients(w, t) for t in range(2)]
+    n, ex = run_and_check_blocks(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, "blocks/feed/" + w.name,
+                                 in_place=in_place, work_feed=2)
     assert n == 2 * w.n_layers and ex >= n - 2
 
 
