@@ -156,6 +156,7 @@ struct WsLayout {
     size_t layers = 0;       // LayerDev[n_layers]
     size_t tile_dir = 0;     // DirEntry[] per p-group, each closed by a sentinel
     size_t chunk_dir = 0;    // DirEntry[n_layers + 1]
+    size_t large_dir = 0;    // DirEntry[] per p-group over its large layers, each closed by a sentinel
     size_t all_tile_dir = 0; // DirEntry[n_layers + 1]: tiles of all layers in layer order
     size_t samples = 0;      // SampleEntry[] per p-group
     size_t chunk_layer = 0;  // uint32[n_chunks]: layer of every 8192-element chunk
@@ -198,6 +199,11 @@ struct PGroup {           // layers sharing one neighbourhood side: one launch p
     uint32_t dir_count = 0;     // entries excluding the sentinel
     uint32_t sample_begin = 0;  // index of the group's first SampleEntry
     uint32_t n_samples = 0;
+    // the group's large layers only (the main pass and its fallback walk no other tiles, so
+    // that equal shares of the walk are equal shares of the work)
+    uint32_t large_dir_begin = 0;   // index of the first DirEntry in large_dir
+    uint32_t large_dir_count = 0;   // entries excluding the sentinel
+    uint32_t n_large_tiles = 0;
 };
 
 }  // namespace rsdgc
@@ -213,6 +219,7 @@ struct rsdgc_plan_s {
     std::vector<rsdgc::DirEntry> tile_dir;
     std::vector<rsdgc::DirEntry> chunk_dir;
     std::vector<rsdgc::DirEntry> all_tile_dir;
+    std::vector<rsdgc::DirEntry> large_dir;
     std::vector<rsdgc::SampleEntry> samples;
     std::vector<rsdgc::GroupEntry> cand_groups;
     std::vector<rsdgc::ChunkEntry> map_chunks;

@@ -2220,6 +2220,9 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
     a.slot_ent = reinterpret_cast<unsigned long long *>(ws + plan->ws.slot_ent);
     a.alpha = plan->alpha;
     const DirEntry *tile_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.tile_dir);
+    const DirEntry *large_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.large_dir);
+    // the main pass and its fallback concern the large layers only: they walk those layers' tiles
+    constexpr bool kLargeOnly = PASS == kPassCapture || PASS == kPassFullMap;
     const SampleEntry *samples = reinterpret_cast<const SampleEntry *>(ws + plan->ws.samples);
     uint32_t *feed = reinterpret_cast<uint32_t *>(ws + plan->ws.feed);
     int group_index = 0;
@@ -2227,12 +2230,12 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
         // this launch's work-feed counters (cleared at the start of the call)
         const int pass_index = PASS == kPassSample ? 0 : PASS == kPassCapture ? 1 : 2;
         a.feed = feed + static_cast<size_t>((pass_index * 4 + group_index++) % kFeedSets) * kFeedDomains * kFeedStride;
-        a.dir = tile_dir + g.dir_begin;
-        a.n_dir = g.dir_count;
+        a.dir = kLargeOnly ? large_dir + g.large_dir_begin : tile_dir + g.dir_begin;
+        a.n_dir = kLargeOnly ? g.large_dir_count : g.dir_count;
         a.n_tiles = g.n_tiles;
         a.samples = samples + g.sample_begin;
         // work items of this launch and the number of workgroups that share them
-        const uint32_t items = PASS == kPassSample ? g.n_samples : g.n_tiles;
+        const uint32_t items = PASS == kPassSample ? g.n_samples : kLargeOnly ? g.n_large_tiles : g.n_tiles;
         if (items == 0) continue;
         a.n_tiles = items;
         a.feed_shift = 7;                  // 128 items per domain and stretch: one per resident workgroup of an XCD

@@ -29,6 +29,7 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->tile_dir.clear();
     plan->chunk_dir.clear();
     plan->all_tile_dir.clear();
+    plan->large_dir.clear();
     plan->samples.clear();
     plan->cand_groups.clear();
     plan->map_chunks.clear();
@@ -140,6 +141,7 @@ int build_tables(rsdgc_plan_s *plan) {
         PGroup g;
         g.p = p;
         g.dir_begin = static_cast<uint32_t>(plan->tile_dir.size());
+        g.large_dir_begin = static_cast<uint32_t>(plan->large_dir.size());
         g.sample_begin = static_cast<uint32_t>(plan->samples.size());
         for (int l = 0; l < L; ++l) {
             if (plan->p[l] != p) continue;
@@ -148,6 +150,11 @@ int build_tables(rsdgc_plan_s *plan) {
             plan->tile_dir.push_back(DirEntry{g.n_tiles, static_cast<uint32_t>(l)});
             g.n_tiles += d.n_tiles;
             ++g.dir_count;
+            if (d.large) {
+                plan->large_dir.push_back(DirEntry{g.n_large_tiles, static_cast<uint32_t>(l)});
+                g.n_large_tiles += d.n_tiles;
+                ++g.large_dir_count;
+            }
             // tile list of the first NSI pass: the sampled tiles of a large layer, every tile
             // of any other layer that selects something
             for (uint32_t t = 0; t < d.n_tiles; ++t)
@@ -157,6 +164,7 @@ int build_tables(rsdgc_plan_s *plan) {
         if (g.dir_count == 0) continue;
         g.n_samples = static_cast<uint32_t>(plan->samples.size()) - g.sample_begin;
         plan->tile_dir.push_back(DirEntry{g.n_tiles, static_cast<uint32_t>(L)});  // sentinel
+        plan->large_dir.push_back(DirEntry{g.n_large_tiles, static_cast<uint32_t>(L)});
         plan->groups.push_back(g);
     }
 
@@ -170,6 +178,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.layers = off;       off = align_up(off + sizeof(LayerDev) * L, A);
     w.tile_dir = off;     off = align_up(off + sizeof(DirEntry) * (L + (RSDGC_MAX_P + 1) / 2), A);
     w.chunk_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + 1), A);
+    w.large_dir = off;    off = align_up(off + sizeof(DirEntry) * (L + (RSDGC_MAX_P + 1) / 2), A);
     w.all_tile_dir = off; off = align_up(off + sizeof(DirEntry) * (L + 1), A);
     w.samples = off;      off = align_up(off + sizeof(SampleEntry) * (max_samples + 1), A);
     w.chunk_layer = off;  off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
@@ -210,6 +219,9 @@ int build_tables(rsdgc_plan_s *plan) {
                 sizeof(DirEntry) * plan->chunk_dir.size());
     std::memcpy(plan->table.data() + w.all_tile_dir, plan->all_tile_dir.data(),
                 sizeof(DirEntry) * plan->all_tile_dir.size());
+    if (!plan->large_dir.empty())
+        std::memcpy(plan->table.data() + w.large_dir, plan->large_dir.data(),
+                    sizeof(DirEntry) * plan->large_dir.size());
     if (!plan->samples.empty())
         std::memcpy(plan->table.data() + w.samples, plan->samples.data(),
                     sizeof(SampleEntry) * plan->samples.size());
