@@ -278,7 +278,7 @@ struct NsiArgs {
 
 // Work unit: one 16 x 256 tile of one layer.  The tile of v = r + g plus a halo of
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
-// down 8 rows of 2 adjacent columns, keeping per-row horizontal sums of |w|, w and w^2
+// down the 16 rows of one column, keeping per-row horizontal sums of |w|, w and w^2
 // (double) for the last P rows in registers.  The variance is formed as
 // (P^2 * sum w^2 - (sum w)^2) / P^4 in double, which is exactly 0 for a constant window
 // and keeps equal windows at equal scores wherever they lie.
@@ -297,7 +297,11 @@ void k_nsi(const NsiArgs a) {
     constexpr int PADL = 4;
     constexpr int PITCH = kTileCols + 2 * PADL;   // 136 floats
     constexpr int VEC_PER_ROW = PITCH / 4;        // 34
-    constexpr int RPT = 8;                        // output rows per thread
+    // One column per thread: two adjacent columns share LDS reads, but the second set of row
+    // sums costs 18 registers, and at one column the main pass fits 5 waves per SIMD (p = 3) and
+    // the p = 7 variants 4 instead of 3.
+    constexpr int CPT = 1;                        // adjacent output columns per thread
+    constexpr int RPT = kTileRows * kTileCols / (256 * CPT);   // output rows per thread
     constexpr bool MAP = PASS == kPassMapOnly || PASS == kPassFullMap;
     constexpr bool CAPTURE = PASS == kPassCapture;
     constexpr bool FULLHIST = PASS == kPassFullMap || PASS == kPassSample;
@@ -342,9 +346,9 @@ void k_nsi(const NsiArgs a) {
     const double n = static_cast<double>(P * P);
     const double ca = a.alpha / n;        // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
     const double cb = (1.0 - a.alpha) / n;
-    static_assert(kTileCols / 2 * (kTileRows / RPT) == 256, "one thread per 8 rows x 2 columns");
-    const int tx = tid % (kTileCols / 2), ty = tid / (kTileCols / 2);
-    const int c0 = 2 * tx;
+    static_assert(kTileCols / CPT * (kTileRows / RPT) == 256, "one thread per RPT rows x CPT columns");
+    const int tx = tid % (kTileCols / CPT), ty = tid / (kTileCols / CPT);
+    const int c0 = CPT * tx;
     const int row_base = ty * RPT;
 
     for (uint32_t t = first; FEED ? t != kNoItem : t < n_items; t = FEED ? feed.next(a.feed, n_items, a.feed_shift, feed_slot) : t + stride) {
@@ -484,16 +488,16 @@ void k_nsi(const NsiArgs a) {
 
         // ---- window statistics
         const bool pair_store = (C & 1) == 0;
-        double hs_a[P][2], hs_s[P][2], hs_q[P][2];
+        double hs_a[P][CPT], hs_s[P][CPT], hs_q[P][CPT];
 #pragma unroll
         for (int i = 0; i < RPT + 2 * H; ++i) {
             const float *row = &tile[(row_base + i) * PITCH + PADL + c0 - H];
-            double w[2 * H + 2];
+            double w[2 * H + CPT];
 #pragma unroll
-            for (int j = 0; j < 2 * H + 2; ++j) w[j] = static_cast<double>(row[j]);
+            for (int j = 0; j < 2 * H + CPT; ++j) w[j] = static_cast<double>(row[j]);
             const int slot = i % P;
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
+            for (int c = 0; c < CPT; ++c) {
                 double sa = fabs(w[c]), ss = w[c], sq = w[c] * w[c];
 #pragma unroll
                 for (int j = 1; j < P; ++j) {
@@ -507,9 +511,11 @@ void k_nsi(const NsiArgs a) {
             }
             if (i >= 2 * H) {
                 const int o = i - 2 * H;   // output row inside the thread's strip
-                float out[2];
+                float out[CPT];
+                uint32_t key[CPT];
+                bool reaches = false;      // capture: some centre of the thread reaches the bound
 #pragma unroll
-                for (int c = 0; c < 2; ++c) {
+                for (int c = 0; c < CPT; ++c) {
                     double sa = hs_a[o % P][c], ss = hs_s[o % P][c], sq = hs_q[o % P][c];
 #pragma unroll
                     for (int j = 1; j < P; ++j) {
@@ -518,45 +524,40 @@ void k_nsi(const NsiArgs a) {
                         sq += hs_q[(o + j) % P][c];
                     }
                     out[c] = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
+                    key[c] = __float_as_uint(out[c]) & 0x7fffffffu;
+                    reaches = reaches || key[c] >= hint_key;
                 }
-                const uint32_t key0 = __float_as_uint(out[0]) & 0x7fffffffu;
-                const uint32_t key1 = __float_as_uint(out[1]) & 0x7fffffffu;
+                const int x = x0 + row_base + o, y = y0 + c0;
                 if (CAPTURE) {
-                    // common case: neither centre reaches the bound -- nothing else to do
-                    if (key0 >= hint_key || key1 >= hint_key) {
-                        const int x = x0 + row_base + o, y = y0 + c0;
-                        if (x < R && y < C) {
-                            const uint32_t i0 = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+                    // common case: no centre reaches the bound -- nothing else to do
+                    if (reaches && x < R && y < C) {
+                        const uint32_t i0 = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
 #pragma unroll
-                            for (int c = 0; c < 2; ++c) {
-                                const uint32_t key = c == 0 ? key0 : key1;
-                                if (key >= hint_key && y + c < C) {
-                                    const uint32_t pos = atomicAdd(&ncand, 1u);
-                                    if (pos < kSlotCap) cand[pos] = composite_key(key, i0 + c);
-                                    const uint32_t rel = (key >> 19) - hint_bin;
-                                    atomicAdd(&lhist[min(rel, static_cast<uint32_t>(kCandBins - 1))], 1u);
-                                    if (rel >= static_cast<uint32_t>(kCandBins - 1)) a.state_rw[l].overflow = 1u;
-                                }
+                        for (int c = 0; c < CPT; ++c) {
+                            if (key[c] >= hint_key && y + c < C) {
+                                const uint32_t pos = atomicAdd(&ncand, 1u);
+                                if (pos < kSlotCap) cand[pos] = composite_key(key[c], i0 + c);
+                                const uint32_t rel = (key[c] >> 19) - hint_bin;
+                                atomicAdd(&lhist[min(rel, static_cast<uint32_t>(kCandBins - 1))], 1u);
+                                if (rel >= static_cast<uint32_t>(kCandBins - 1)) a.state_rw[l].overflow = 1u;
                             }
                         }
                     }
-                } else {
-                    const int x = x0 + row_base + o, y = y0 + c0;
-                    if (x < R && y < C) {
-                        const bool two = y + 1 < C;
-                        if (MAP || (PASS == kPassSample && whole)) {
-                            const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
-                            if (two && pair_store) {
-                                *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[1]);
-                            } else {
-                                a.nsi_out[off] = out[0];
-                                if (two) a.nsi_out[off + 1] = out[1];
-                            }
+                } else if (x < R && y < C) {
+                    if (MAP || (PASS == kPassSample && whole)) {
+                        const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
+                        if (CPT == 2 && y + 1 < C && pair_store) {
+                            *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[CPT - 1]);
+                        } else {
+#pragma unroll
+                            for (int c = 0; c < CPT; ++c)
+                                if (y + c < C) a.nsi_out[off + c] = out[c];
                         }
-                        if (FULLHIST) {
-                            atomicAdd(&lhist[key0 >> 19], 1u);
-                            if (two) atomicAdd(&lhist[key1 >> 19], 1u);
-                        }
+                    }
+                    if (FULLHIST) {
+#pragma unroll
+                        for (int c = 0; c < CPT; ++c)
+                            if (y + c < C) atomicAdd(&lhist[key[c] >> 19], 1u);
                     }
                 }
             }
