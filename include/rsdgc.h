@@ -92,8 +92,7 @@ int rsdgc_plan_set_path(rsdgc_plan_t *plan, int32_t path);
  *   RSDGC_FEED_AUTO  from per-XCD work counters when a launch has many tiles per
  *                    workgroup (where it is faster), else a fixed strided share (default).
  *   RSDGC_FEED_OFF   always the fixed share.
- *   RSDGC_FEED_ON    the counters whenever the kernel variant has them (p <= 3), also for
- *                    small launches (meant for tests).
+ *   RSDGC_FEED_ON    always the counters, also for small launches (meant for tests).
  * Returns RSDGC_EINVAL for a null plan or an unknown mode.                          */
 #define RSDGC_FEED_AUTO  0
 #define RSDGC_FEED_OFF   1

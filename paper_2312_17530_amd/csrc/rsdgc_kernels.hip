@@ -283,10 +283,11 @@ struct NsiArgs {
 // (P^2 * sum w^2 - (sum w)^2) / P^4 in double, which is exactly 0 for a constant window
 // and keeps equal windows at equal scores wherever they lie.
 //
-// A workgroup walks a contiguous range of tiles (ranges are laid out so that each XCD gets
-// one contiguous stretch of the launch: neighbouring tiles share halo rows in one L2).
-// Its LDS histogram is flushed to the layer's global histogram only when the layer
-// changes or the range ends, so a launch issues few same-address global atomics.
+// A workgroup takes tiles b, b + W, ... of the launch (W workgroups, laid out so that each XCD
+// gets one contiguous part of every stretch of W tiles: neighbouring tiles share halo rows in
+// one L2), or -- FEED -- whatever the launch's work feed hands it next.  Its LDS histogram is
+// flushed to the layer's global histogram only when the layer changes or its tiles end, so
+// a launch issues few same-address global atomics.
 // MOM: with Eq. 12's momentum term (a.mom, a.mom_out, a.m).  FEED: the workgroups take their
 // tiles from the launch's work feed instead of a fixed strided share.
 template <int P, int PASS, bool MOM, bool FEED>
@@ -2252,8 +2253,8 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
 #define RSDGC_NSI_CASE(PP)                                                                  \
     case PP: {                                                                              \
         /* the work feed pays when a workgroup gets many tiles (its start and its end cost  \
-           a few round trips to the counters); built for the main pass of p <= 3 */         \
-        constexpr bool kFeedBuilt = PP <= 3 && PASS == kPassCapture;                        \
+           a few round trips to the counters); built for the main pass */                   \
+        constexpr bool kFeedBuilt = PASS == kPassCapture;                                   \
         const bool fed = kFeedBuilt && plan->work_feed != RSDGC_FEED_OFF &&                 \
                          (plan->work_feed == RSDGC_FEED_ON || items >= 16u * kNumCUs * 4u); \
         if (mom.in) {                                                                       \
