@@ -206,39 +206,47 @@ __device__ __forceinline__ uint32_t feed_domain_items(uint32_t n_items, uint32_t
 }
 
 struct WorkFeed {
-    uint32_t st;          // bit 0: LDS slot of the next hand-over, bit 1: the requested ticket is in it
+    uint32_t *ctr;        // the workgroup's domain counter (zero at launch)
+    uint32_t items;       // items of that domain
+    uint32_t shift, dom;
+    uint32_t par;         // LDS slot of the next hand-over
+    bool stashed;         // the requested ticket is already in that slot
     uint32_t pending;     // thread 0: the ticket requested last
+    // (plain members whose values the compiler can follow through the loop: with the flags
+    // packed into one word the main pass needed 15 more registers)
 
     // Thread 0 puts the requested ticket into LDS.  Reading it waits for the wave's memory
     // operations up to the request, and the compiler may make that a wait for everything
     // issued since.  So the item's code calls this after its loads have arrived and before
     // its first store; next() does it for items that never got there.
     __device__ __forceinline__ void stash(uint32_t *slot /*[2], LDS*/) {
-        if (st & 2u) return;                           // uniform
-        if (threadIdx.x == 0) slot[st & 1u] = pending;
-        st |= 2u;
+        if (!stashed && threadIdx.x == 0) slot[par] = pending;
+        stashed = true;
     }
     // Called by all threads of the workgroup (it contains a barrier); returns the next item or
-    // kNoItem.  ctr: the launch's kFeedDomains counters, zero at launch.
-    __device__ __forceinline__ uint32_t next(uint32_t *__restrict__ ctr, uint32_t n_items, uint32_t shift,
-                                             uint32_t *slot) {
-        stash(slot);
-        const uint32_t par = st & 1u, dom = blockIdx.x % kFeedDomains;
+    // kNoItem.
+    __device__ __forceinline__ uint32_t next(uint32_t *slot) {
+        if (!stashed && threadIdx.x == 0) slot[par] = pending;
+        stashed = false;
         __syncthreads();
         const uint32_t t = __builtin_amdgcn_readfirstlane(slot[par]);   // the same in every lane: keep it scalar
-        st = par ^ 1u;
-        if (t >= feed_domain_items(n_items, shift, dom)) return kNoItem;   // uniform: the domain is used up
-        if (threadIdx.x == 0) pending = atomicAdd(&ctr[dom * kFeedStride], 1u);
+        par ^= 1u;
+        if (t >= items) return kNoItem;                 // uniform: the domain is used up
+        if (threadIdx.x == 0) pending = atomicAdd(ctr, 1u);
         return ((t >> shift) * kFeedDomains + dom) * (1u << shift) + (t & ((1u << shift) - 1u));
     }
-    __device__ __forceinline__ uint32_t first(uint32_t *__restrict__ ctr, uint32_t n_items, uint32_t shift,
+    // counters: the launch's kFeedDomains counters; log2_part: log2 S.
+    __device__ __forceinline__ uint32_t first(uint32_t *__restrict__ counters, uint32_t n_items, uint32_t log2_part,
                                               uint32_t *slot) {
-        const uint32_t dom = blockIdx.x % kFeedDomains;    // workgroups go to the XCDs round-robin by id
-        st = 0;
-        pending = kNoItem;                                  // an empty domain never touches its counter
-        if (threadIdx.x == 0 && feed_domain_items(n_items, shift, dom) != 0u)
-            pending = atomicAdd(&ctr[dom * kFeedStride], 1u);
-        return next(ctr, n_items, shift, slot);
+        dom = blockIdx.x % kFeedDomains;                // workgroups go to the XCDs round-robin by id
+        shift = log2_part;
+        items = feed_domain_items(n_items, shift, dom);
+        ctr = counters + dom * kFeedStride;
+        par = 0;
+        stashed = false;
+        pending = kNoItem;                              // an empty domain never touches its counter
+        if (threadIdx.x == 0 && items != 0u) pending = atomicAdd(ctr, 1u);
+        return next(slot);
     }
 };
 
@@ -291,7 +299,7 @@ struct NsiArgs {
 // MOM: with Eq. 12's momentum term (a.mom, a.mom_out, a.m).  FEED: the workgroups take their
 // tiles from the launch's work feed instead of a fixed strided share.
 template <int P, int PASS, bool MOM, bool FEED>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FEED && !MOM ? 4 : 1, 8)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FEED && !MOM ? (P <= 3 ? 5 : 4) : 1, 8)))
 void k_nsi(const NsiArgs a) {
     constexpr int H = (P - 1) / 2;
     constexpr int ROWS = kTileRows + 2 * H;
@@ -352,7 +360,7 @@ void k_nsi(const NsiArgs a) {
     const int c0 = CPT * tx;
     const int row_base = ty * RPT;
 
-    for (uint32_t t = first; FEED ? t != kNoItem : t < n_items; t = FEED ? feed.next(a.feed, n_items, a.feed_shift, feed_slot) : t + stride) {
+    for (uint32_t t = first; FEED ? t != kNoItem : t < n_items; t = FEED ? feed.next(feed_slot) : t + stride) {
         uint32_t l, local;
         if (PASS == kPassSample) {
             const SampleEntry se = a.samples[t];
@@ -1786,7 +1794,7 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
     bool active = false;
     LayerDev O, I;
     for (uint32_t t = first; FEED ? t != kNoItem : t < n_tiles;
-         t = FEED ? feed.next(feed_ctr, n_tiles, feed_shift, feed_slot) : t + stride) {
+         t = FEED ? feed.next(feed_slot) : t + stride) {
         while (t >= tile_dir[e + 1].begin) ++e;
         const uint32_t l = tile_dir[e].layer;
         if (l != cur_l) {
