@@ -581,14 +581,16 @@ def test_decompress_accumulate_sums_messages():
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
-def test_compress_can_be_captured_in_a_hip_graph_and_replayed(in_place):
+@pytest.mark.parametrize("work_feed", [FEED_AUTO, FEED_ON], ids=["feed_auto", "feed_on"])
+def test_compress_can_be_captured_in_a_hip_graph_and_replayed(in_place, work_feed):
     """rsdgc_compress enqueues kernels only (no allocation, no synchronisation, no memset node),
     so a caller may capture it.  Every replay must reproduce the eager result, with eager work
-    and synchronisations between the replays."""
+    and synchronisations between the replays.  With the work feed forced on, every replay also
+    has to find the feed's counters cleared by the call's own first kernel."""
     import torch
     w = synth.config(1)
     grads = synth.gradients(w, 0)
-    sess = _session(w.shapes, w.p, w.alpha, w.ratios, in_place=in_place)
+    sess = _session(w.shapes, w.p, w.alpha, w.ratios, in_place=in_place, work_feed=work_feed)
     sess.set_grad(grads)
     sess.compress()                                  # first call uploads the plan's tables
     torch.cuda.synchronize()
