@@ -1701,20 +1701,19 @@ __global__ __launch_bounds__(256) void k_emit_centres(const LayerDev *__restrict
 }
 
 // ----------------------------------------------------------- decompress --
-__global__ __launch_bounds__(256) void k_zero_layers(const LayerDev *__restrict__ layers,
-                                                     const uint32_t *__restrict__ chunk_layer, float *__restrict__ dense) {
+// +0 into every element of every layer (the padding between layers is left alone): one chunk
+// per workgroup, streaming 16-byte stores.
+__global__ __launch_bounds__(256) void k_zero_layers(const ChunkInfo *__restrict__ chunk_info, float *__restrict__ dense) {
     const int tid = threadIdx.x;
-    const uint32_t c = blockIdx.x;
-    const uint32_t l = chunk_layer[c];
-    const LayerDev L = layers[l];
-    const uint32_t start = (c - L.chunk_begin) * kChunk;
-    const uint32_t len = min(static_cast<uint32_t>(kChunk), L.G - start);
-    float *__restrict__ d = dense + L.elem_off + start;
+    const ChunkInfo ci = chunk_info[blockIdx.x];
+    const uint32_t len = ci.len;
+    float *__restrict__ d = dense + ci.arena_off;
+#pragma unroll
     for (int j = 0; j < kChunk / 1024; ++j) {
         const uint32_t e = j * 1024 + 4 * tid;
         if (e >= len) break;
         if (e + 3 < len) {
-            *reinterpret_cast<float4 *>(d + e) = make_float4(0.f, 0.f, 0.f, 0.f);
+            store_streaming(d + e, make_float4(0.f, 0.f, 0.f, 0.f));
         } else {
             for (uint32_t q = 0; q < 4 && e + q < len; ++q) d[e + q] = 0.f;
         }
@@ -2623,9 +2622,9 @@ int rsdgc_decompress_blocks(rsdgc_plan_t *plan, const uint32_t *block_idx, const
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
     const LayerDev *outer = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
-    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + plan->ws.chunk_layer);
     if (!accumulate)
-        hipLaunchKernelGGL(k_zero_layers, dim3(plan->n_chunks), dim3(256), 0, stream, outer, chunk_layer, dense);
+        hipLaunchKernelGGL(k_zero_layers, dim3(plan->n_chunks), dim3(256), 0, stream,
+                           reinterpret_cast<const ChunkInfo *>(ws + plan->ws.chunk_info), dense);
     if (plan->centre_capacity > 0) {
         const unsigned blocks = static_cast<unsigned>((plan->centre_capacity + 255) / 256);
         hipLaunchKernelGGL(k_scatter_blocks, dim3(blocks), dim3(256), 0, stream, outer, plan->n_layers,
@@ -2834,10 +2833,9 @@ int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
     const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
-    const uint32_t *chunk_layer = reinterpret_cast<const uint32_t *>(ws + plan->ws.chunk_layer);
     if (!accumulate)
-        hipLaunchKernelGGL(k_zero_layers, dim3(plan->n_chunks), dim3(256), 0, stream, layers,
-                           chunk_layer, dense);
+        hipLaunchKernelGGL(k_zero_layers, dim3(plan->n_chunks), dim3(256), 0, stream,
+                           reinterpret_cast<const ChunkInfo *>(ws + plan->ws.chunk_info), dense);
     if (plan->out_capacity > 0) {
         const unsigned blocks = static_cast<unsigned>((plan->out_capacity + 255) / 256);
         hipLaunchKernelGGL(k_scatter, dim3(blocks), dim3(256), 0, stream, layers, plan->n_layers,
