@@ -1514,8 +1514,8 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
     if (whole) {
 #pragma unroll
         for (int j = 0; j < kChunk / 1024; ++j) {
-            gq[j] = *reinterpret_cast<const float4 *>(g + j * 1024 + 4 * tid);
-            rq[j] = *reinterpret_cast<const float4 *>(r + j * 1024 + 4 * tid);
+            gq[j] = load_streaming(g + j * 1024 + 4 * tid);
+            rq[j] = load_streaming(r + j * 1024 + 4 * tid);
         }
     }
     chunk_prefix_wave0(ci, c, chunk_cnt, group_cnt, &s_cbase);
@@ -2088,7 +2088,9 @@ __global__ __launch_bounds__(256) void k_dyn_hist(const ChunkInfo *__restrict__ 
             uint32_t kk[4] = {0, 0, 0, 0};
             uint32_t nv = min(4u, ci.len - e);
             if (nv == 4) {
-                const uint4 q = *reinterpret_cast<const uint4 *>(src + e);
+                typedef uint32_t vu4 __attribute__((ext_vector_type(4)));   // read once per pass: streamed
+                const vu4 qq = __builtin_nontemporal_load(reinterpret_cast<const vu4 *>(src + e));
+                const uint4 q = make_uint4(qq.x, qq.y, qq.z, qq.w);
                 kk[0] = q.x; kk[1] = q.y; kk[2] = q.z; kk[3] = q.w;
             } else {
                 for (uint32_t q = 0; q < nv; ++q) kk[q] = src[e + q];
