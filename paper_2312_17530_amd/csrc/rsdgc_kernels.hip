@@ -16,10 +16,26 @@
 //              threshold bucket, find, filter, finish
 //   mark       selected centres set the bits of their p x p window (Section III-C: whole
 //              neighbourhoods are kept)
-//   count/scan kept elements per chunk and their prefix sums
+//   count      kept elements per chunk and per group of chunks (no scan kernel: each consumer
+//              adds up its own prefix from those)
 //   emit       ordered (index, value) pairs and the residual update (Eq. 12): either only the
 //              kept elements are touched (second arena), or g and r are streamed again
 //              (update in place)
+//
+// Sections of this file, in order (each starts with a "// ---- name --" line):
+//   begin            k_begin
+//   work feed        WorkFeed: tiles handed to persistent workgroups through per-XCD counters
+//   nsi              k_nsi<P, PASS, MOM, FEED>: the four NSI passes, with or without Eq. 12's momentum
+//   hint, validate   k_hint, k_validate: the candidate bound and whether it held
+//   find .. filter   k_find, k_gather, k_finish, k_filter: the radix select
+//   mark             k_mark: p x p windows into the bitmask
+//   count            k_count, chunk_prefix_wave0
+//   emit             k_emit, k_emit_sparse, k_emit_centres
+//   decompress       k_zero_layers, k_scatter
+//   block reading    k_block_nsi, k_emit_blocks, k_scatter_blocks
+//   apply            k_apply (receiving side)
+//   dynamic ratios   k_dyn_*
+//   host side        launch helpers and the extern "C" entry points
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
