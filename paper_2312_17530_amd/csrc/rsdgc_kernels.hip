@@ -337,6 +337,10 @@ void k_nsi(const NsiArgs a) {
     constexpr int RPT = kTileRows * kTileCols / (256 * CPT);   // output rows per thread
     constexpr bool MAP = PASS == kPassMapOnly || PASS == kPassFullMap;
     constexpr bool CAPTURE = PASS == kPassCapture;
+    // the main pass of the wide neighbourhoods tests a centre against the bound before it takes
+    // the square root (p = 5: 262 -> 254 us on 25088 x 4096; at p <= 3 the few registers it
+    // needs cost the fifth wave per SIMD, and the pass is not faster with it)
+    constexpr bool PRETEST = CAPTURE && FEED && !MOM && P >= 5;
     constexpr bool FULLHIST = PASS == kPassFullMap || PASS == kPassSample;
     constexpr bool STORE_V = PASS != kPassMapOnly;
     constexpr int NBINS = FULLHIST ? kHistBins : (CAPTURE ? kCandBins : 1);
@@ -372,6 +376,7 @@ void k_nsi(const NsiArgs a) {
     if (PASS != kPassSample) e = dir_lookup(a.dir, a.n_dir, first);
     uint32_t cur_l = 0xffffffffu;         // layer whose counts sit in lhist
     uint32_t hint_key = 0, hint_bin = 0;
+    double bound_lo = 0.0;                // capture: a conservative form of the candidate bound
     bool active = true;
     bool whole = true;                    // every tile of the layer is visited: v and the scores go out
     LayerDev L;
@@ -379,6 +384,7 @@ void k_nsi(const NsiArgs a) {
     const double n = static_cast<double>(P * P);
     const double ca = a.alpha / n;        // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
     const double cb = (1.0 - a.alpha) / n;
+    const double cb2 = cb * cb;
     static_assert(kTileCols / CPT * (kTileRows / RPT) == 256, "one thread per RPT rows x CPT columns");
     const int tx = tid % (kTileCols / CPT), ty = tid / (kTileCols / CPT);
     const int c0 = CPT * tx;
@@ -414,7 +420,12 @@ void k_nsi(const NsiArgs a) {
                 const SelState st = a.state[l];
                 if (PASS == kPassFullMap) active = st.mode == kModeFullMap && L.large != 0u;
                 else active = st.mode == kModeCandidates;
-                if (CAPTURE) { hint_key = st.hint_key; hint_bin = hint_key >> 19; }
+                if (CAPTURE) {
+                    hint_key = st.hint_key;
+                    hint_bin = hint_key >> 19;
+                    // below every double that rounds to a float32 at or above the bound
+                    bound_lo = static_cast<double>(__uint_as_float(hint_key)) * (1.0 - 1.0 / 4194304.0);
+                }
             }
         }
         if (!active) {                    // skip the rest of this layer
@@ -556,9 +567,21 @@ void k_nsi(const NsiArgs a) {
                         ss += hs_s[(o + j) % P][c];
                         sq += hs_q[(o + j) % P][c];
                     }
-                    out[c] = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
+                    bool exact = true;
+                    if (PRETEST) {
+                        // Only the centres that reach the bound are wanted, and 99.5 % do not.  A test
+                        // without the square root, with slack far beyond the double rounding errors
+                        // and the last float32 bit of the bound, rules most of them out (a wave skips
+                        // the rest when all its lanes are ruled out):
+                        //   NSI >= B  <=>  cb*sqrt(d) >= B - ca*sa  <=>  rest <= 0  or  cb^2 * d >= rest^2
+                        const double d = __dsub_rn(__dmul_rn(n, sq), __dmul_rn(ss, ss));
+                        const double rest = bound_lo - ca * sa;
+                        exact = rest <= 0.0 || cb2 * d >= rest * rest * (1.0 - 1e-9);
+                    }
+                    out[c] = 0.f;
+                    if (exact) out[c] = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
                     key[c] = __float_as_uint(out[c]) & 0x7fffffffu;
-                    reaches = reaches || key[c] >= hint_key;
+                    reaches = reaches || (exact && key[c] >= hint_key);
                 }
                 const int x = x0 + row_base + o, y = y0 + c0;
                 if (CAPTURE) {
