@@ -483,6 +483,16 @@ def test_work_feed_on_small_launches(in_place):
     n, ex = run_and_check(shapes, [3, 1, 3, 3], 0.5, [0.02, 0.01, 0.03, 0.05], its, "feed/large_unaligned",
                           in_place=in_place, work_feed=FEED_ON)
     assert n == 2 * len(shapes) and ex >= n - 1
+    # large layers with the wide neighbourhoods: their main pass rules centres out before the square root
+    shapes = [(1500, 2100), (1200, 1800), (900, 2048)]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 37, t, l) for l, sh in enumerate(shapes)] for t in range(2)]
+    n, ex = run_and_check(shapes, [7, 5, 5], 0.5, [0.01, 0.02, 0.003], its, "feed/wide", in_place=in_place,
+                          work_feed=FEED_ON)
+    assert n == 2 * len(shapes) and ex >= n - 1
+    for alpha in (0.0, 1.0):
+        n, ex = run_and_check(shapes[1:], [5, 7], alpha, [0.02, 0.01], its[:1] and [[g for g in its[0][1:]]],
+                              f"feed/wide/alpha{alpha}", in_place=in_place, work_feed=FEED_ON)
+        assert n == 2 and ex >= 1
     w = synth.config(1)
     its = [synth.gradients(w, t) for t in range(2)]
     n, ex = run_and_check(w.shapes, [w.p] * w.n_layers, w.alpha, w.ratios, its, "feed/" + w.name,
