@@ -180,6 +180,14 @@ __device__ __forceinline__ float4 load_streaming(const float *__restrict__ src) 
     return make_float4(t.x, t.y, t.z, t.w);
 }
 
+// A double that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ double uniform_f64(double x) {
+    const unsigned long long b = static_cast<unsigned long long>(__double_as_longlong(x));
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b >> 32));
+    return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
+}
+
 // Eqs. 8-10 from the window sums sa = sum|w|, ss = sum w, sq = sum w^2 (n = p*p slots):
 //   mean = sa / n,  std = sqrt(n*sq - ss^2) / n,  NSI = alpha*mean + (1-alpha)*std.
 // n*sq - ss^2 is formed from two separately rounded products so that it is exactly 0 for a
@@ -303,7 +311,7 @@ struct NsiArgs {
     SelState *state_rw;           // same array; only the overflow flag is written (capture)
     uint32_t *slot_cnt;           // [n_tiles_all]
     unsigned long long *slot_ent; // [n_tiles_all][kSlotCap]
-    double alpha;
+    double ca, cb;                // alpha / p^2, (1 - alpha) / p^2: NSI = ca * sum|w| + cb * sqrt(p^2 * sum w^2 - (sum w)^2)
     uint32_t *feed;               // work-feed counters of this launch (all but kPassMapOnly)
     uint32_t feed_shift;          // log2 of the items per domain and stretch
 };
@@ -382,9 +390,10 @@ void k_nsi(const NsiArgs a) {
     LayerDev L;
 
     const double n = static_cast<double>(P * P);
-    const double ca = a.alpha / n;        // NSI = ca * sum|w| + cb * sqrt(n*sum w^2 - (sum w)^2)
-    const double cb = (1.0 - a.alpha) / n;
-    const double cb2 = cb * cb;
+    // (kernel arguments: the same in every lane, so they stay in scalar registers -- the scalar unit
+    // has no floating point, a uniform value computed here would occupy vector registers)
+    const double ca = a.ca, cb = a.cb;
+    const double cb2 = uniform_f64(cb * cb);
     static_assert(kTileCols / CPT * (kTileRows / RPT) == 256, "one thread per RPT rows x CPT columns");
     const int tx = tid % (kTileCols / CPT), ty = tid / (kTileCols / CPT);
     const int c0 = CPT * tx;
@@ -424,7 +433,7 @@ void k_nsi(const NsiArgs a) {
                     hint_key = st.hint_key;
                     hint_bin = hint_key >> 19;
                     // below every double that rounds to a float32 at or above the bound
-                    bound_lo = static_cast<double>(__uint_as_float(hint_key)) * (1.0 - 1.0 / 4194304.0);
+                    bound_lo = uniform_f64(static_cast<double>(__uint_as_float(hint_key)) * (1.0 - 1.0 / 4194304.0));
                 }
             }
         }
@@ -2276,7 +2285,7 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
     a.state_rw = reinterpret_cast<SelState *>(ws + plan->ws.state);
     a.slot_cnt = reinterpret_cast<uint32_t *>(ws + plan->ws.slot_cnt);
     a.slot_ent = reinterpret_cast<unsigned long long *>(ws + plan->ws.slot_ent);
-    a.alpha = plan->alpha;
+    a.ca = a.cb = 0.0;                 // set per neighbourhood side below
     const DirEntry *tile_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.tile_dir);
     const DirEntry *large_dir = reinterpret_cast<const DirEntry *>(ws + plan->ws.large_dir);
     // the main pass and its fallback concern the large layers only: they walk those layers' tiles
@@ -2288,6 +2297,8 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
         // this launch's work-feed counters (cleared at the start of the call)
         const int pass_index = PASS == kPassSample ? 0 : PASS == kPassCapture ? 1 : 2;
         a.feed = feed + static_cast<size_t>((pass_index * 4 + group_index++) % kFeedSets) * kFeedDomains * kFeedStride;
+        a.ca = plan->alpha / static_cast<double>(g.p * g.p);
+        a.cb = (1.0 - plan->alpha) / static_cast<double>(g.p * g.p);
         a.dir = kLargeOnly ? large_dir + g.large_dir_begin : tile_dir + g.dir_begin;
         a.n_dir = kLargeOnly ? g.large_dir_count : g.dir_count;
         a.n_tiles = g.n_tiles;
