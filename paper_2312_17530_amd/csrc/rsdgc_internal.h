@@ -20,6 +20,7 @@ constexpr int kCandBins = 256;       // 12-bit score buckets above the bound tha
 constexpr int kListMin = 8192;       // smallest threshold-bucket list of a layer (entries)
 constexpr int kList2Cap = 2048;      // keys sharing the first two digits that a layer can stage
 constexpr int kListDiv = 32;         // ... or 1/32 of the layer, whichever is larger
+constexpr int kCountChunks = 16;     // chunks per workgroup of the count pass
 constexpr int kChunkGroup = 64;      // chunks per group in the two-level chunk prefix
 constexpr int kListShards = 16;      // a layer's threshold-bucket list is filled through this many counters
 constexpr int kListCntStride = 32;   // uint32 between two of them (one 128-byte line each)
@@ -122,13 +123,14 @@ struct ChunkEntry {
     uint64_t arena_off;  // elem_off + start
 };
 
-// Work item of the count pass: one group of up to kChunkGroup consecutive chunks of a layer.
+// Work item of the count pass: up to kCountChunks consecutive chunks of a layer (a quarter of a
+// chunk group).
 struct CountGroup {
     uint64_t word0;        // first 32-bit word of the group's mask bits
     uint32_t first_chunk;
     uint32_t n_chunks;
-    uint32_t n_words;      // mask words of the group (a layer's last chunk may be short)
-    uint32_t pad_;
+    uint32_t n_words;      // mask words of these chunks (a layer's last chunk may be short)
+    uint32_t group;        // the chunk group (kChunkGroup chunks) they belong to
 };
 static_assert(sizeof(CountGroup) == 24, "CountGroup layout");
 
@@ -164,7 +166,7 @@ struct WsLayout {
     size_t cand_groups = 0;  // GroupEntry[]: slot groups of the large layers (work list of the candidate passes)
     size_t map_chunks = 0;   // ChunkEntry[]: chunks of the other layers that select something
     size_t map_tiles = 0;    // SampleEntry[]: tiles of those layers
-    size_t count_groups = 0; // CountGroup[n_chunk_groups]
+    size_t count_groups = 0; // CountGroup[n_count_groups]
     size_t table_bytes = 0;  // bytes uploaded from the host
     size_t state = 0;        // SelState[n_layers], rewritten at the start of every compress
     // cleared at the start of every compress
@@ -232,6 +234,7 @@ struct rsdgc_plan_s {
     int64_t centre_capacity = 0;
     uint32_t n_chunks = 0;
     uint32_t n_chunk_groups = 0;  // chunk groups over all layers
+    uint32_t n_count_groups = 0;  // work items of the count pass
     int work_feed = 0;            // RSDGC_FEED_*
     rsdgc::WsLayout ws;
     std::vector<unsigned char> table;   // host image of the uploaded tables

@@ -1435,11 +1435,11 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
 
 // ---------------------------------------------------------------- count --
 // Kept elements (and selected centres) per chunk and per group of kChunkGroup chunks: one
-// 1024-thread workgroup per group; 16 adjacent threads read the 256 mask words of one chunk
-// (16 consecutive words each, as independent 8-byte loads) and add their popcounts with
-// four shuffles.  Plain stores only: the group totals need no global atomics (which all fell
-// on a few cache lines when every chunk added its own count).
-constexpr int kCountThreads = 1024;
+// workgroup per kCountChunks = 16 chunks; 16 adjacent threads read the 256 mask words of one
+// chunk (16 consecutive words each, as independent 8-byte loads) and add their popcounts with
+// four shuffles.  A workgroup adds its total to its chunk group's with one atomic -- four per
+// group (one atomic per chunk put 17 k of them on 9 cache lines and cost 18 us).
+constexpr int kCountThreads = 16 * kCountChunks;
 
 __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__restrict__ groups,
                                                          const uint32_t *__restrict__ mask,
@@ -1449,8 +1449,8 @@ __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__res
                                                          uint32_t *__restrict__ group_cnt,
                                                          uint32_t *__restrict__ group_ccnt) {
     constexpr int kPerThread = kChunk / 32 / 16;    // 16 words
-    static_assert(kCountThreads / 16 == kChunkGroup && kChunkGroup == 64, "16 threads per chunk, one lane per chunk");
-    __shared__ uint32_t lcnt[2][kChunkGroup];
+    static_assert(kCountChunks <= 64, "one lane of the first wave per chunk");
+    __shared__ uint32_t lcnt[2][kCountChunks];
     const int tid = threadIdx.x;
     const CountGroup gr = groups[blockIdx.x];
     const uint32_t i0 = static_cast<uint32_t>(tid) * kPerThread;
@@ -1485,9 +1485,9 @@ __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__res
         lcnt[1][tid >> 4] = b;
     }
     __syncthreads();
-    if (tid < 64) {                        // the first wave: one lane per chunk of the group
-        a = lcnt[0][tid];
-        b = lcnt[1][tid];
+    if (tid < 64) {                        // the first wave: one lane per chunk
+        a = tid < kCountChunks ? lcnt[0][tid] : 0u;
+        b = tid < kCountChunks ? lcnt[1][tid] : 0u;
         if (static_cast<uint32_t>(tid) < gr.n_chunks) {
             chunk_cnt[gr.first_chunk + tid] = a;
             if (cmask) chunk_ccnt[gr.first_chunk + tid] = b;
@@ -1497,9 +1497,9 @@ __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__res
             a += __shfl_xor(a, d, 64);
             b += __shfl_xor(b, d, 64);
         }
-        if (tid == 0) {
-            group_cnt[blockIdx.x] = a;
-            if (cmask) group_ccnt[blockIdx.x] = b;
+        if (tid == 0) {                    // (the group totals are cleared at the start of the call)
+            if (a) atomicAdd(&group_cnt[gr.group], a);
+            if (cmask && b) atomicAdd(&group_ccnt[gr.group], b);
         }
     }
 }
@@ -2454,7 +2454,7 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         if (n_wgs > 0) hipLaunchKernelGGL(k_mark, dim3(n_wgs), dim3(256), 0, stream, m);
     }
     marks.close(5);
-    hipLaunchKernelGGL(k_count, dim3(plan->n_chunk_groups), dim3(kCountThreads), 0, stream,
+    hipLaunchKernelGGL(k_count, dim3(plan->n_count_groups), dim3(kCountThreads), 0, stream,
                        reinterpret_cast<const CountGroup *>(ws + w.count_groups), mask, cmask, chunk_cnt, chunk_ccnt,
                        reinterpret_cast<uint32_t *>(ws + w.group_cnt), reinterpret_cast<uint32_t *>(ws + w.group_ccnt));
     marks.close(6);

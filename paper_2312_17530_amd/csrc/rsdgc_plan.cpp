@@ -107,7 +107,11 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(L)});
     plan->n_chunks = chunk_begin;
     plan->n_chunk_groups = 0;
-    for (const LayerDev &d : plan->layers) plan->n_chunk_groups += (d.n_chunks + kChunkGroup - 1) / kChunkGroup;
+    plan->n_count_groups = 0;
+    for (const LayerDev &d : plan->layers) {
+        plan->n_chunk_groups += (d.n_chunks + kChunkGroup - 1) / kChunkGroup;
+        plan->n_count_groups += (d.n_chunks + kCountChunks - 1) / kCountChunks;
+    }
     plan->n_tiles_all = tile_begin_all;
     plan->n_slot_groups = group_begin;
     plan->total_elems = elem_off;
@@ -186,7 +190,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.cand_groups = off;  off = align_up(off + sizeof(GroupEntry) * plan->n_slot_groups, A);
     w.map_chunks = off;   off = align_up(off + sizeof(ChunkEntry) * plan->n_chunks, A);
     w.map_tiles = off;    off = align_up(off + sizeof(SampleEntry) * (size_t(plan->n_tiles_all) + 1), A);
-    w.count_groups = off; off = align_up(off + sizeof(CountGroup) * plan->n_chunk_groups, A);
+    w.count_groups = off; off = align_up(off + sizeof(CountGroup) * plan->n_count_groups, A);
     w.table_bytes = off;
     w.state = off;        off = align_up(off + sizeof(SelState) * L, A);   // written in full each call
     w.zero_begin = off;
@@ -229,16 +233,18 @@ int build_tables(rsdgc_plan_s *plan) {
         uint32_t *cl = reinterpret_cast<uint32_t *>(plan->table.data() + w.chunk_layer);
         ChunkInfo *ci = reinterpret_cast<ChunkInfo *>(plan->table.data() + w.chunk_info);
         CountGroup *cg = reinterpret_cast<CountGroup *>(plan->table.data() + w.count_groups);
-        uint32_t first_group = 0;
+        static_assert(kChunkGroup % kCountChunks == 0, "a count item lies inside one chunk group");
+        uint32_t first_group = 0, n_cg = 0;
         for (int l = 0; l < L; ++l) {
             const LayerDev &d = plan->layers[l];
-            for (uint32_t c = 0; c < d.n_chunks; c += kChunkGroup) {
-                const uint32_t n = std::min<uint32_t>(kChunkGroup, d.n_chunks - c);
+            for (uint32_t c = 0; c < d.n_chunks; c += kCountChunks) {
+                const uint32_t n = std::min<uint32_t>(kCountChunks, d.n_chunks - c);
                 const uint64_t first_elem = static_cast<uint64_t>(c) * kChunk;
                 const uint64_t end_elem = std::min<uint64_t>(first_elem + static_cast<uint64_t>(n) * kChunk, d.G);
-                cg[first_group + c / kChunkGroup] =
+                cg[n_cg++] =
                     CountGroup{(static_cast<uint64_t>(d.elem_off) + first_elem) >> 5, d.chunk_begin + c, n,
-                               static_cast<uint32_t>((end_elem - first_elem + 31) / 32), 0u};
+                               static_cast<uint32_t>((end_elem - first_elem + 31) / 32),
+                               first_group + c / kChunkGroup};
             }
             for (uint32_t c = 0; c < d.n_chunks; ++c) {
                 cl[d.chunk_begin + c] = static_cast<uint32_t>(l);
