@@ -1372,16 +1372,30 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
         const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
         const uint32_t *__restrict__ src = keys + L.elem_off;
 
-        for (int it = wave; it < rows_ext * NSEG; it += 4) {
-            const int rr = it / NSEG, seg = it % NSEG;
-            const int x = x0 - h + rr, y = y0 + 64 * seg + lane;
-            bool flag = false;
-            if (x >= 0 && x < R && y < C) {
-                const uint32_t i = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
-                flag = composite_key(src[i], i) >= T;
+        // wave w takes segment w of every row: all its keys are requested before any is compared
+        static_assert(NSEG == 4, "one wave per 64-column segment");
+        constexpr int kMaxRowsExt = kTileRows + 2 * MAXH;
+        {
+            const int y = y0 + 64 * wave + lane;
+            uint32_t key[kMaxRowsExt];
+#pragma unroll
+            for (int rr = 0; rr < kMaxRowsExt; ++rr) {
+                const int x = x0 - h + rr;
+                key[rr] = 0;
+                if (rr < rows_ext && x >= 0 && x < R && y < C)
+                    key[rr] = src[static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y)];
             }
-            const unsigned long long w = __ballot(flag);
-            if (lane == 0) bits[rr][1 + seg] = w;
+#pragma unroll
+            for (int rr = 0; rr < kMaxRowsExt; ++rr) {
+                const int x = x0 - h + rr;
+                bool flag = false;
+                if (rr < rows_ext && x >= 0 && x < R && y < C) {
+                    const uint32_t i = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
+                    flag = composite_key(key[rr], i) >= T;
+                }
+                const unsigned long long w = __ballot(flag);
+                if (lane == 0 && rr < rows_ext) bits[rr][1 + wave] = w;
+            }
         }
         if (wave < 2 && lane < rows_ext) {      // halo columns: lane = row; wave 0 left, wave 1 right
             unsigned long long hw = 0;
