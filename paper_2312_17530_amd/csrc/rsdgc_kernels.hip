@@ -664,15 +664,17 @@ __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layer
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t found;
     const int l = blockIdx.x, tid = threadIdx.x;
+    // state, target and counts are requested together (see k_validate)
     const SelState st = state[l];
-    if (st.mode != kModeCandidates) return;      // its histogram is untouched (still zero)
     const uint32_t target = layers[l].hint_target;
     uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
     constexpr int per = kHistBins / 256;
-    if (tid == 0) found = 0;
     const int hi = kHistBins - tid * per;
     uint32_t own = 0;
+#pragma unroll
     for (int b = hi - 1; b >= hi - per; --b) own += h[b];
+    if (st.mode != kModeCandidates) return;      // its histogram is untouched (still zero)
+    if (tid == 0) found = 0;
     const uint32_t incl = block_scan_incl(own, wave_tot);
     const uint32_t excl = incl - own;
     if (excl < target && target <= incl) {
@@ -709,14 +711,18 @@ __global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ l
                                                   uint32_t *__restrict__ flags) {
     __shared__ uint32_t wave_tot[4];
     const int l = blockIdx.x, tid = threadIdx.x;
+    // state, k_l and the counts are requested together: one round trip to memory instead of
+    // three (each costs this one-workgroup-per-layer kernel about 2 us)
     const SelState st = state[l];
-    if (st.mode != kModeCandidates) return;
+    const uint32_t k = layers[l].k;
     uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
     uint32_t own = 0;
-    for (int b = tid; b < kHistBins; b += 256) own += h[b];
+#pragma unroll
+    for (int j = 0; j < kHistBins / 256; ++j) own += h[tid + 256 * j];
+    if (st.mode != kModeCandidates) return;
     const uint32_t total = block_scan_incl(own, wave_tot);
     __shared__ uint32_t fail;
-    if (tid == 255) fail = (st.overflow || total < layers[l].k) ? 1u : 0u;
+    if (tid == 255) fail = (st.overflow || total < k) ? 1u : 0u;
     __syncthreads();
     if (fail) {
         for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
@@ -744,23 +750,24 @@ __global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
     const int nb = 1 << bits, per = nb >> 8;
     const SelState st = state[l];
     if (tid == 0) found = 0;
-    if (!st.done) {
-        // thread t owns bins [hi - per, hi), hi = nb - t * per  (t = 0 holds the top bins); their
-        // counts (added over the copies) stay in registers for the walk below
-        const int hi = nb - tid * per;
-        constexpr int kMaxPer = kHistBins / 256, kMaxCopies = kHistBins >> level_bits(1);
-        uint32_t v[kMaxPer];
-        uint32_t own = 0;
+    // thread t owns bins [hi - per, hi), hi = nb - t * per  (t = 0 holds the top bins); their
+    // counts (added over the copies) stay in registers for the walk below.  They are requested
+    // with the state, before it is known whether the layer still needs them.
+    const int hi = nb - tid * per;
+    constexpr int kMaxPer = kHistBins / 256, kMaxCopies = kHistBins >> level_bits(1);
+    uint32_t v[kMaxPer];
+    uint32_t own = 0;
 #pragma unroll
-        for (int j = 0; j < kMaxPer; ++j) {
-            v[j] = 0;
-            if (j < per) {
+    for (int j = 0; j < kMaxPer; ++j) {
+        v[j] = 0;
+        if (j < per) {
 #pragma unroll
-                for (int cp = 0; cp < kMaxCopies; ++cp)
-                    if (cp < copies) v[j] += h[cp * nb + hi - 1 - j];
-            }
-            own += v[j];
+            for (int cp = 0; cp < kMaxCopies; ++cp)
+                if (cp < copies) v[j] += h[cp * nb + hi - 1 - j];
         }
+        own += v[j];
+    }
+    if (!st.done) {
         const uint32_t incl = block_scan_incl(own, wave_tot);
         const uint32_t excl = incl - own;
         if (excl < st.k_rem && st.k_rem <= incl) {
