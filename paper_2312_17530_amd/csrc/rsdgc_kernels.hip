@@ -366,19 +366,10 @@ void k_nsi(const NsiArgs a) {
     const uint32_t stride = gridDim.x;
     if (PASS == kPassFullMap && a.flags[0] == 0u) return;   // no layer fell back: nothing to do
     WorkFeed feed;
-    uint32_t first, step = stride, t_end = n_items;
+    uint32_t first;
     if (FEED) {
         first = feed.first(a.feed, n_items, a.feed_shift, feed_slot);
         if (first == kNoItem) return;      // uniform
-    } else if (PASS == kPassSample) {
-        // consecutive items: mostly one layer per workgroup, so one histogram flush instead of
-        // one per tile (VGG-19: 53.6 -> 50.2 us; giving the workgroups of an XCD neighbouring
-        // runs on top of that was slower again)
-        const uint32_t per = n_items / gridDim.x, rem = n_items % gridDim.x;
-        first = blockIdx.x * per + min(blockIdx.x, rem);
-        t_end = first + per + (blockIdx.x < rem ? 1u : 0u);
-        step = 1;
-        if (first >= t_end) return;
     } else {
         first = xcd_contiguous(blockIdx.x, gridDim.x);
         if (first >= n_items) return;
@@ -408,7 +399,7 @@ void k_nsi(const NsiArgs a) {
     const int c0 = CPT * tx;
     const int row_base = ty * RPT;
 
-    for (uint32_t t = first; FEED ? t != kNoItem : t < t_end; t = FEED ? feed.next(feed_slot) : t + step) {
+    for (uint32_t t = first; FEED ? t != kNoItem : t < n_items; t = FEED ? feed.next(feed_slot) : t + stride) {
         uint32_t l, local;
         if (PASS == kPassSample) {
             const SampleEntry se = a.samples[t];
