@@ -7,6 +7,8 @@ Later iterations, which carry the residual, are checked through properties that 
 size: Eq. 11 counts, ascending indices, values and residual bit-equal to v = r + g, kept set
 == dilation of the centres, and the centres being exactly the k best composite keys of the
 library's own score map."""
+import functools
+
 import numpy as np
 import pytest
 
@@ -244,3 +246,45 @@ def test_vgg19_full_size_block_reading_against_oracle():
 def test_fc6_stress_p5_student_t_against_oracle_then_one_carried_iteration():
     w, n_exact = _run(4, extra_iterations=1)
     assert n_exact == 1
+
+
+_HUGE = ((16512, 8192), 3, 0.5, 0.01)      # shape, p, alpha, keep ratio
+
+
+@functools.lru_cache(maxsize=1)
+def _huge_layer_and_oracle():
+    """Seeded normal noise (std 1e-3) and the oracle's result for it, computed once for both forms."""
+    shape, p, alpha, rho = _HUGE
+    rng = np.random.default_rng(727)
+    g = rng.standard_normal(shape, dtype=np.float32) * np.float32(1e-3)
+    r0 = np.zeros(shape, dtype=np.float32)
+    return g, r0, oracle.compress_layer(g, r0, p, alpha, rho)
+
+
+@pytest.mark.parametrize("in_place", [False, True], ids=["two_arenas", "in_place"])
+def test_one_layer_beyond_2_pow_27_elements_against_oracle(in_place):
+    """A layer of 258 chunk groups (16512 x 8192 = 135,266,304 elements): the kept count before
+    a chunk of the last groups adds up more group totals than the one wave-wide request of the
+    prefix covers, which no workload of the benchmark reaches."""
+    import torch
+    from paper_2312_17530_amd.session import Session
+    shape, p, alpha, rho = _HUGE
+    assert shape[0] * shape[1] > 257 * 64 * 8192
+    tag = f"beyond_2^27[{'in_place' if in_place else 'two_arenas'}]"
+    print("oracle", tag, flush=True)
+    g, r0, o = _huge_layer_and_oracle()
+    print("gpu", tag, flush=True)
+    sess = Session([shape], p, alpha, [rho], in_place=in_place)
+    sess.set_grad([g])
+    sess.set_residual([r0])
+    sess.compress()
+    torch.cuda.synchronize()
+    gi, gv, gc, gn = sess.results()[0]
+    gpu_r = sess.unpack(sess.residual)[0]
+    assert sess.plan.layer_k(0) == o.k, tag
+    parity.check_layer(tag, shape, p, o.k, o.tau, o.nsi, o.centres, o.idx, o.val, o.r_new, o.v,
+                       gi, gv, gc, gn, gpu_r)
+    dense = sess.unpack(sess.decompress(accumulate=False))[0].reshape(-1)
+    want = np.zeros(dense.size, dtype=np.float32)
+    want[gi] = gv
+    assert np.array_equal(dense.view(np.uint32), want.view(np.uint32)), f"{tag}: decompress"
