@@ -428,6 +428,25 @@ def test_degenerate_inputs_follow_index_tie_break():
         assert ex == n, "exact ties must resolve exactly like the oracle (lower index wins)"
 
 
+def test_large_layers_with_masses_of_exact_ties(in_place):
+    """Layers large enough for the candidate path whose scores are all equal, or take a handful
+    of values (a frozen layer's all-zero gradient is the everyday case): the candidate bound
+    cannot separate anything, the layer falls back to the full map, its threshold bucket holds
+    far more keys than the bucket list, and the last radix digits -- those of the index -- are
+    found by streaming the score map.  The lower index must win exactly as in the oracle."""
+    shapes = [(1024, 1024), (768, 1536), (1000, 1100), (600, 2048)]
+    rng = np.random.default_rng(4242)
+    zeros = np.zeros(shapes[0], dtype=np.float32)
+    const = np.full(shapes[1], 0.0625, dtype=np.float32)
+    ints = rng.integers(-2, 3, size=shapes[2]).astype(np.float32)
+    noise = (rng.standard_normal(shapes[3]) * 1e-3).astype(np.float32)     # an ordinary layer beside them
+    grads = [zeros, const, ints, noise]
+    for p, ratios in [(3, [0.05, 0.02, 0.03, 0.02]), (5, [0.3, 0.01, 0.2, 0.05])]:
+        n, ex = run_and_check(shapes, [p] * 4, 0.5, ratios, [grads, grads], f"large_ties(p={p})",
+                              in_place=in_place)
+        assert n == 8 and ex >= 7, "exact ties must resolve exactly like the oracle"
+
+
 @pytest.mark.parametrize("path", [AUTO, FULL_MAP])
 def test_config1_resnet18_two_iterations(path, in_place):
     w = synth.config(1)
