@@ -445,6 +445,10 @@ def test_large_layers_with_masses_of_exact_ties(in_place):
         n, ex = run_and_check(shapes, [p] * 4, 0.5, ratios, [grads, grads], f"large_ties(p={p})",
                               in_place=in_place)
         assert n == 8 and ex >= 7, "exact ties must resolve exactly like the oracle"
+    if not in_place:        # the same fallback with Eq. 12's momentum: the full-map pass forms m*u + g again
+        n, ex = run_and_check_momentum(shapes, [3] * 4, 0.5, [0.05, 0.02, 0.03, 0.02], 0.9, [grads, grads],
+                                       "large_ties")
+        assert n == 8 and ex >= 7
 
 
 @pytest.mark.parametrize("path", [AUTO, FULL_MAP])
