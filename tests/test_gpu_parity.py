@@ -344,6 +344,23 @@ def test_blocks_degenerate_inputs_follow_index_tie_break():
         assert ex == n, "exact ties must resolve exactly like the oracle (lower block index wins)"
 
 
+def test_blocks_large_layers_with_masses_of_exact_ties():
+    """The block reading on layers of about a million elements whose block scores are all equal
+    or take few values: the threshold bucket holds most of the grid, far more than the small
+    second list, so the last digits come from the bucket list itself."""
+    shapes = [(1024, 1024), (768, 1536), (1000, 1100), (600, 2048)]
+    rng = np.random.default_rng(4243)
+    zeros = np.zeros(shapes[0], dtype=np.float32)
+    const = np.full(shapes[1], 0.0625, dtype=np.float32)
+    ints = rng.integers(-2, 3, size=shapes[2]).astype(np.float32)
+    noise = (rng.standard_normal(shapes[3]) * 1e-3).astype(np.float32)
+    grads = [zeros, const, ints, noise]
+    for p in (3, 1):
+        n, ex = run_and_check_blocks(shapes, [p] * 4, 0.5, [0.05, 0.02, 0.03, 0.02], [grads, grads],
+                                     f"large_ties(p={p})")
+        assert n == 8 and ex >= 7
+
+
 def test_blocks_resnet18_shapes():
     w = synth.config(1)
     its = [synth.gradients(w, t) for t in range(2)]
