@@ -468,6 +468,17 @@ def test_large_layers_with_masses_of_exact_ties(in_place):
         assert n == 8 and ex >= 7
 
 
+def test_large_layers_with_high_keep_ratios(in_place):
+    """Keep ratios far above the benchmark's (up to 1, where Eq. 11 selects G/p^2 centres, and
+    with p = 1 every element): the layers are ranked on the full map and the threshold bucket of
+    an ordinary noise layer outgrows the bucket list."""
+    shapes = [(1000, 1100), (600, 2048), (900, 1000)]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 43, t, l) for l, sh in enumerate(shapes)] for t in range(2)]
+    for p_list, ratios in [([3, 3, 3], [1.0, 0.5, 0.25]), ([1, 1, 5], [1.0, 0.4, 1.0])]:
+        n, ex = run_and_check(shapes, p_list, 0.5, ratios, its, f"high_ratio{p_list}", in_place=in_place)
+        assert n == 6 and ex >= 5
+
+
 @pytest.mark.parametrize("path", [AUTO, FULL_MAP])
 def test_config1_resnet18_two_iterations(path, in_place):
     w = synth.config(1)
