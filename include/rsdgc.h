@@ -197,7 +197,15 @@ int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual,
  *   idx, val, counts  [device] as produced by rsdgc_compress with this plan.
  *   dense             [device] float32 arena.
  *   accumulate = 0: every layer element of dense is overwritten (zeros where
- *                   nothing was sent);  != 0: dense[idx] += val.            */
+ *                   nothing was sent);  != 0: dense[idx] += val.
+ * A message is taken as it comes (it may have crossed a network): a pair
+ * whose index is not below G_l is skipped, counts[l] is read as clamped to
+ * [0, the layer's segment capacity], and nothing outside dense's layer
+ * elements is ever written; none of this is reported as an error.  A message
+ * that names an element twice (rsdgc_compress never does) leaves an
+ * unspecified one of its values, or sums, there.  The same holds for
+ * rsdgc_decompress_blocks (block index not below the layer's block count) and
+ * for the messages given to rsdgc_apply.                                    */
 int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
                      const int32_t *counts, float *dense, int accumulate,
                      void *workspace, void *stream);

@@ -642,6 +642,73 @@ def test_decompress_accumulate_sums_messages():
     assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
+def test_receiving_side_skips_what_a_malformed_message_names():
+    """A message that crossed a network is not trusted: indices at or beyond the layer's size are
+    skipped, a count beyond the layer's segment is read as the segment's capacity, a negative
+    count as zero -- and nothing outside the layers' elements is written (the arena's padding
+    keeps its values).  Checked for rsdgc_decompress (overwrite) and rsdgc_apply."""
+    import torch
+    from paper_2312_17530_amd import binding
+    shapes, ratios = [(64, 100), (40, 50), (30, 30)], [0.1, 0.2, 0.1]
+    G = [r * c for r, c in shapes]
+    sess = _session(shapes, 3, 0.5, ratios)
+    sess.set_grad([synth.layer_gradient(sh, 1e-2, 83, 0, l) for l, sh in enumerate(shapes)])
+    sess.compress()
+    torch.cuda.synchronize()
+    plan = sess.plan
+    offs = [plan.out_offset(l) for l in range(3)] + [plan.out_capacity]
+    caps = [offs[l + 1] - offs[l] for l in range(3)]
+    counts = sess.out_counts.cpu().numpy().copy()
+    idx = sess.out_idx.cpu().numpy().view(np.uint32).copy()
+    val = sess.out_val.cpu().numpy().copy()
+    rng = np.random.default_rng(84)
+    # layer 0: three pairs name elements that do not exist
+    n0 = int(counts[0])
+    assert n0 >= 3
+    picks = np.array([0, n0 // 2, n0 - 1])
+    idx[offs[0] + picks] = np.array([G[0], 0xffffffff, G[0] + 12345], dtype=np.uint32)
+    # layer 1: the whole segment holds valid pairs, the count claims far more
+    assert caps[1] <= G[1]
+    idx[offs[1]:offs[1] + caps[1]] = rng.permutation(G[1])[:caps[1]].astype(np.uint32)
+    val[offs[1]:offs[1] + caps[1]] = rng.standard_normal(caps[1]).astype(np.float32)
+    counts[1] = caps[1] + 100000
+    # layer 2: a negative count
+    counts[2] = -5
+    dev = sess.grad.device
+    idx_t = torch.from_numpy(idx.view(np.int32)).to(dev)
+    val_t = torch.from_numpy(val).to(dev)
+    cnt_t = torch.from_numpy(counts.astype(np.int32)).to(dev)
+    # what a careful reader of the message keeps
+    kept = []
+    for l in range(3):
+        n = min(max(int(counts[l]), 0), caps[l])
+        i, v = idx[offs[l]:offs[l] + n], val[offs[l]:offs[l] + n]
+        ok = i < G[l]
+        kept.append((i[ok], v[ok]))
+    assert len(kept[0][0]) == n0 - 3 and len(kept[1][0]) == caps[1] and len(kept[2][0]) == 0
+
+    dense = torch.full_like(sess.grad, 7.0)
+    binding.rsdgc_decompress(plan, idx_t, val_t, cnt_t, dense, False, sess.workspace)
+    torch.cuda.synchronize()
+    want = np.full(dense.numel(), 7.0, dtype=np.float32)          # padding keeps its 7.0
+    for l in range(3):
+        o = plan.layer_offset(l)
+        want[o:o + G[l]] = oracle.decompress(kept[l][0], kept[l][1], G[l])
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+    weights = [rng.standard_normal(sh).astype(np.float32) for sh in shapes]
+    w_dev = torch.full_like(sess.grad, 3.0)
+    sess.pack(weights, w_dev)
+    before = w_dev.cpu().numpy().copy()
+    binding.rsdgc_apply(plan, [(idx_t, val_t, cnt_t)], w_dev, 0.5, sess.workspace)
+    torch.cuda.synchronize()
+    want_w = before.copy()
+    for l in range(3):
+        o = plan.layer_offset(l)
+        want_w[o:o + G[l]] = oracle.apply_messages(weights[l], [kept[l]], 0.5).reshape(-1)
+    assert np.array_equal(w_dev.cpu().numpy().view(np.uint32), want_w.view(np.uint32))
+
+
 @pytest.mark.parametrize("work_feed", [FEED_AUTO, FEED_ON], ids=["feed_auto", "feed_on"])
 def test_compress_can_be_captured_in_a_hip_graph_and_replayed(in_place, work_feed):
     """rsdgc_compress enqueues kernels only (no allocation, no synchronisation, no memset node),
