@@ -361,6 +361,47 @@ def test_blocks_large_layers_with_masses_of_exact_ties():
         assert n == 8 and ex >= 7
 
 
+def test_blocks_receiving_side_skips_what_a_malformed_message_names():
+    """As for element messages: a block index at or beyond the layer's block count is skipped,
+    a count beyond k_l is read as k_l, a negative one as zero; the arena's padding is not written."""
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import BlockSession
+    shapes, ratios, p = [(64, 100), (40, 50), (31, 29)], [0.1, 0.2, 0.1], 3
+    sess = BlockSession(shapes, p, 0.5, ratios)
+    sess.set_grad([synth.layer_gradient(sh, 1e-2, 85, 0, l) for l, sh in enumerate(shapes)])
+    sess.compress()
+    torch.cuda.synchronize()
+    plan = sess.plan
+    n_blocks = [-(-r // p) * -(-c // p) for r, c in shapes]
+    ks = [plan.layer_k(l) for l in range(3)]
+    counts = sess.out_counts.cpu().numpy().copy()
+    blocks = sess.out_blocks.cpu().numpy().view(np.uint32).copy()
+    val = sess.out_val.cpu().numpy().copy()
+    assert list(counts) == ks and ks[0] >= 3
+    b0 = plan.centre_offset(0)
+    picks = np.array([0, ks[0] // 2, ks[0] - 1])
+    blocks[b0 + picks] = np.array([n_blocks[0], 0xffffffff, n_blocks[0] + 77], dtype=np.uint32)
+    counts[1] = ks[1] + 100000
+    counts[2] = -1
+    dev = sess.grad.device
+    dense = torch.full_like(sess.grad, 7.0)
+    binding.rsdgc_decompress_blocks(plan, torch.from_numpy(blocks.view(np.int32)).to(dev),
+                                    torch.from_numpy(val).to(dev), torch.from_numpy(counts.astype(np.int32)).to(dev),
+                                    dense, False, sess.workspace)
+    torch.cuda.synchronize()
+    want = np.full(dense.numel(), 7.0, dtype=np.float32)
+    for l, (R, C) in enumerate(shapes):
+        n = min(max(int(counts[l]), 0), ks[l])
+        bo, vo = plan.centre_offset(l), plan.out_offset(l)
+        b = blocks[bo:bo + n]
+        v = val[vo:vo + n * p * p].reshape(n, p * p)
+        ok = b < n_blocks[l]
+        o = plan.layer_offset(l)
+        want[o:o + R * C] = oracle.decompress_blocks(b[ok], v[ok].reshape(-1), R, C, p).reshape(-1)
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
 def test_blocks_resnet18_shapes():
     w = synth.config(1)
     its = [synth.gradients(w, t) for t in range(2)]
