@@ -81,6 +81,9 @@ def _load():
     lib.rsdgc_oracle_apply.argtypes = [fp, i64, ctypes.c_int32, ctypes.POINTER(u32p), ctypes.POINTER(fp),
                                        ctypes.POINTER(i64), c_float]
     lib.rsdgc_oracle_apply.restype = c_int
+    lib.rsdgc_oracle_apply_blocks.argtypes = [fp, i64, i64, c_int, ctypes.c_int32, ctypes.POINTER(u32p),
+                                              ctypes.POINTER(fp), ctypes.POINTER(i64), c_float]
+    lib.rsdgc_oracle_apply_blocks.restype = c_int
     lib.rsdgc_oracle_block_nsi.argtypes = [fp, i64, i64, c_int, f64, fp]
     lib.rsdgc_oracle_block_nsi.restype = None
     lib.rsdgc_oracle_compress_layer_blocks.argtypes = [fp, fp, i64, i64, c_int, f64, f64, u32p, fp,
@@ -410,3 +413,27 @@ def compress_model(grads: Sequence[np.ndarray], residuals: Sequence[np.ndarray],
     """All layers of one iteration, each independently (per-layer selection)."""
     assert len(grads) == len(residuals) == len(ratios)
     return [compress_layer(g, r, p, alpha, rho) for g, r, rho in zip(grads, residuals, ratios)]
+
+
+def apply_block_messages(w, messages: Sequence[Tuple[np.ndarray, np.ndarray]], p: int, eta: float) -> np.ndarray:
+    """Eq. 12, third line, for one layer and block messages: w - eta * (sum of the messages,
+    first message first).  messages: (block indices uint32, p*p float32 values per block) per
+    node.  Returns the new weights; w is not modified."""
+    _check_p(p)
+    w_new = _f32(w).copy()
+    R, C = w_new.shape
+    n_blocks = ((R + p - 1) // p) * ((C + p - 1) // p)
+    n = len(messages)
+    bs = [np.ascontiguousarray(m[0], dtype=np.uint32) for m in messages]
+    vs = [np.ascontiguousarray(m[1], dtype=np.float32) for m in messages]
+    for b, v in zip(bs, vs):
+        assert v.size == b.size * p * p and (b.size == 0 or int(b.max()) < n_blocks)
+    pad_b, pad_v = np.zeros(1, np.uint32), np.zeros(1, np.float32)
+    bp = (ctypes.POINTER(ctypes.c_uint32) * max(n, 1))(*[_p(b if b.size else pad_b, ctypes.c_uint32) for b in bs])
+    vp = (ctypes.POINTER(ctypes.c_float) * max(n, 1))(*[_p(v if v.size else pad_v, ctypes.c_float) for v in vs])
+    cnt = (ctypes.c_int64 * max(n, 1))(*[b.size for b in bs])
+    rc = _load().rsdgc_oracle_apply_blocks(_p(w_new.reshape(-1), ctypes.c_float), R, C, p, n, bp, vp, cnt,
+                                           float(eta))
+    if rc != 0:
+        raise MemoryError("oracle ran out of memory")
+    return w_new

@@ -519,3 +519,27 @@ void rsdgc_oracle_decompress_blocks(const uint32_t *blocks, const float *val, in
             }
     }
 }
+
+/* Eq. 12, third line, with block messages (the block reading of Section III-C): the messages
+ * are summed in the order given (float32 adds, each block slot inside the matrix once per
+ * message), then w <- w - eta * sum with one float32 multiply and one float32 subtract.     */
+int rsdgc_oracle_apply_blocks(float *w, int64_t R, int64_t C, int p, int32_t n_msgs,
+                              const uint32_t *const *blocks, const float *const *val,
+                              const int64_t *n, float eta)
+{
+    const int64_t G = R * C;
+    float *sum = (float *)malloc((size_t)(G > 0 ? G : 1) * sizeof(float));
+    if (!sum)
+        return -1;
+    for (int64_t i = 0; i < G; ++i)
+        sum[i] = 0.0f;
+    for (int32_t k = 0; k < n_msgs; ++k)
+        rsdgc_oracle_decompress_blocks(blocks[k], val[k], n[k], R, C, p, sum, 1);
+    for (int64_t i = 0; i < G; ++i) {
+        volatile float step = eta * sum[i];
+        volatile float wn = w[i] - step;
+        w[i] = wn;
+    }
+    free(sum);
+    return 0;
+}

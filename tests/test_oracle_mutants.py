@@ -130,6 +130,14 @@ def battery(orc):
     m1 = (np.array([1, 3], np.uint32), np.array([1.0, 2.0], np.float32))
     m2 = (np.array([3, 9], np.uint32), np.array([0.5, -4.0], np.float32))
     check("apply", orc.apply_messages(w10, [m1, m2], 0.5).tolist() == [0, 0.5, 2, 1.75, 4, 5, 6, 7, 8, 11])
+    w45 = np.arange(20, dtype=np.float32).reshape(4, 5)
+    b1 = (np.array([0, 3], np.uint32),
+          np.array([1, 2, 3, 4, 5, 6, 7, 8, 9] + [10, 20, 99, 99, 99, 99, 99, 99, 99], np.float32))
+    b2 = (np.array([0], np.uint32), np.array([0.5, 0, 0, 0, -4, 0, 0, 0, 0], np.float32))
+    want45 = w45.copy()
+    want45[0:3, 0:3] -= np.float32(0.5) * np.array([[1.5, 2, 3], [4, 1, 6], [7, 8, 9]], np.float32)
+    want45[3, 3:5] -= np.float32(0.5) * np.array([10, 20], np.float32)
+    check("apply_blocks", orc.apply_block_messages(w45, [b1, b2], 3, 0.5).tolist() == want45.tolist())
     # block reading
     vb = (rng.standard_normal((13, 17)) + 0.3).astype(np.float32)
     pad = np.zeros((15, 18), np.float64)
@@ -191,6 +199,9 @@ MUTANTS = [
     ("apply_scales_the_weight", "volatile float step = eta * sum[i];", "volatile float step = eta * w[i];", 0),
     ("apply_keeps_last_message_only", "rsdgc_oracle_decompress(idx[k], val[k], n[k], sum, G, 1);",
      "rsdgc_oracle_decompress(idx[k], val[k], n[k], sum, G, 0);", 0),
+    ("apply_blocks_adds_the_step", "volatile float wn = w[i] - step;", "volatile float wn = w[i] + step;", 1),
+    ("apply_blocks_keeps_last_message_only", "rsdgc_oracle_decompress_blocks(blocks[k], val[k], n[k], R, C, p, sum, 1);",
+     "rsdgc_oracle_decompress_blocks(blocks[k], val[k], n[k], R, C, p, sum, 0);", 0),
     ("block_window_centred", "double w = slot(v, R, C, bx * p + dx, by * p + dy);", "double w = slot(v, R, C, bx * p + dx - 1, by * p + dy - 1);", 0),
     ("block_std_around_zero", "double d = slot(v, R, C, bx * p + dx, by * p + dy) - mean;", "double d = slot(v, R, C, bx * p + dx, by * p + dy);", 0),
     ("block_residual_keeps_sent", "if (inside) r[x * C + y] = 0.0f;", "if (inside) r[x * C + y] = v[x * C + y];", 0),

@@ -588,3 +588,70 @@ def test_block_reading_with_p1_is_the_element_reading():
     a = oracle.compress_layer_blocks(g, r, 1, 0.5, 0.1)
     b = oracle.compress_layer(g, r, 1, 0.5, 0.1)
     assert np.array_equal(a.blocks, b.idx) and np.array_equal(a.val, b.val) and np.array_equal(a.r_new, b.r_new)
+
+
+def _blocks_as_pairs(blocks, val, R, C, p):
+    """A block message written out as (flat index, value) pairs of the slots inside the matrix."""
+    BC = (C + p - 1) // p
+    idx, out = [], []
+    for j, b in enumerate(blocks.tolist()):
+        bx, by = divmod(b, BC)
+        for dx in range(p):
+            for dy in range(p):
+                x, y = bx * p + dx, by * p + dy
+                if x < R and y < C:
+                    idx.append(x * C + y)
+                    out.append(val[j * p * p + dx * p + dy])
+    return np.array(idx, np.uint32), np.array(out, np.float32)
+
+
+def test_apply_block_messages_small_case_by_hand():
+    # 4 x 5 matrix, p = 3: blocks 0 1 / 2 3; blocks 1 and 3 are cut by the right edge, 2 and 3 by the lower one
+    w = np.arange(20, dtype=np.float32).reshape(4, 5)
+    m1 = (np.array([0, 3], np.uint32),
+          np.array([1, 2, 3, 4, 5, 6, 7, 8, 9] + [10, 20, 99, 99, 99, 99, 99, 99, 99], np.float32))
+    m2 = (np.array([0], np.uint32), np.array([0.5, 0, 0, 0, -4, 0, 0, 0, 0], np.float32))
+    got = oracle.apply_block_messages(w, [m1, m2], 3, 0.5)
+    want = w.copy()
+    want[0:3, 0:3] -= np.float32(0.5) * np.array([[1.5, 2, 3], [4, 1, 6], [7, 8, 9]], np.float32)
+    want[3, 3] -= 0.5 * 10
+    want[3, 4] -= 0.5 * 20
+    assert got.tolist() == want.tolist()
+    assert oracle.apply_block_messages(w, [], 3, 0.5).tolist() == w.tolist()
+    assert oracle.apply_block_messages(w, [m1], 3, 0.0).tolist() == w.tolist()
+
+
+def test_apply_block_messages_is_the_element_form_on_the_blocks_slots():
+    rng = np.random.default_rng(53)
+    order_seen = False
+    for (R, C), p in [((20, 31), 3), ((17, 17), 5), ((9, 40), 1), ((14, 10), 7)]:
+        BR, BC = (R + p - 1) // p, (C + p - 1) // p
+        w = rng.standard_normal((R, C)).astype(np.float32)
+        msgs = []
+        for k in range(3):
+            blocks = np.sort(rng.choice(BR * BC, size=max(1, 3 * BR * BC // 4), replace=False)).astype(np.uint32)
+            msgs.append((blocks, (rng.standard_normal(blocks.size * p * p) * 10.0 ** rng.uniform(-1, 1)).astype(np.float32)))
+        got = oracle.apply_block_messages(w, msgs, p, 0.3)
+        pairs = [_blocks_as_pairs(b, v, R, C, p) for b, v in msgs]
+        assert np.array_equal(got.view(np.uint32), oracle.apply_messages(w, pairs, 0.3).view(np.uint32)), (R, C, p)
+        # and numpy's float32 arithmetic: one rounded add per message, one product, one difference
+        total = np.zeros(R * C, dtype=np.float32)
+        for idx, val in pairs:
+            total[idx] = total[idx] + val
+        assert np.array_equal(got.ravel(), w.ravel() - np.float32(0.3) * total)
+        order_seen = order_seen or bool(np.any(oracle.apply_block_messages(w, msgs[::-1], p, 0.3) != got))
+    assert order_seen, "the data must tell the two summation orders apart"
+
+
+def test_apply_block_messages_applies_what_the_nodes_sent():
+    rng = np.random.default_rng(54)
+    R, C, p = 26, 35, 3
+    w = rng.standard_normal((R, C)).astype(np.float32)
+    dense = np.zeros((R, C), np.float32)
+    sent = []
+    for k in range(2):
+        g = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        res = oracle.compress_layer_blocks(g, np.zeros_like(g), p, 0.5, 0.2)
+        sent.append((res.blocks, res.val))
+        dense = oracle.decompress_blocks(res.blocks, res.val, R, C, p, dense=dense, accumulate_into=True)
+    assert np.array_equal(oracle.apply_block_messages(w, sent, p, 0.25), w - np.float32(0.25) * dense)
