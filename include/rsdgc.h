@@ -205,7 +205,7 @@ int rsdgc_nsi(rsdgc_plan_t *plan, const float *grad, const float *residual,
  * that names an element twice (rsdgc_compress never does) leaves an
  * unspecified one of its values, or sums, there.  The same holds for
  * rsdgc_decompress_blocks (block index not below the layer's block count) and
- * for the messages given to rsdgc_apply.                                    */
+ * for the messages given to rsdgc_apply and rsdgc_apply_blocks.             */
 int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
                      const int32_t *counts, float *dense, int accumulate,
                      void *workspace, void *stream);
@@ -223,8 +223,8 @@ int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
  *   rsdgc_centre_offset(l) / rsdgc_centre_capacity   layout of the block index list,
  *   rsdgc_out_offset(l) / rsdgc_out_capacity         layout of the value list
  *                               (k_l * p_l^2 floats per layer),
- * and only rsdgc_compress_blocks / rsdgc_decompress_blocks (and the plan calls)
- * accept it; a plan from rsdgc_plan is refused by these two (RSDGC_EINVAL).
+ * and only rsdgc_compress_blocks / rsdgc_decompress_blocks / rsdgc_apply_blocks (and
+ * the plan calls) accept it; a plan from rsdgc_plan is refused by these (RSDGC_EINVAL).
  *   out_block_idx [device] uint32: per layer, from rsdgc_centre_offset(l), the kept
  *                 blocks' indices bx * ceil(C/p) + by, ascending.
  *   out_val       [device] float32: per layer, from rsdgc_out_offset(l), p*p values
@@ -262,6 +262,14 @@ int rsdgc_decompress_blocks(rsdgc_plan_t *plan, const uint32_t *block_idx, const
 int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
                 const float *const *val, const int32_t *const *counts, float *weights,
                 float eta, void *workspace, void *stream);
+
+/* The same for a plan from rsdgc_plan_blocks and messages as produced by
+ * rsdgc_compress_blocks: block_idx[k], val[k] (p*p values per block) and
+ * counts[k] of node k.  rsdgc_apply refuses a block plan and this call an
+ * element plan (RSDGC_EINVAL).                                               */
+int rsdgc_apply_blocks(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *block_idx,
+                       const float *const *val, const int32_t *const *counts, float *weights,
+                       float eta, void *workspace, void *stream);
 
 /* ------------------------------------------------------------ profiling --
  * Per-stage GPU time of rsdgc_compress, measured with HIP events recorded on the

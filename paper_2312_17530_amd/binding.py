@@ -21,7 +21,7 @@ EXPORTS = [
     "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_set_work_feed", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
-    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_plan_blocks", "rsdgc_compress_blocks",
+    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_apply_blocks", "rsdgc_plan_blocks", "rsdgc_compress_blocks",
     "rsdgc_decompress_blocks", "rsdgc_nsi", "rsdgc_decompress",
     "rsdgc_last_paths", "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
@@ -92,6 +92,9 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_apply.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
                                 ctypes.c_float, vp, vp]
     lib.rsdgc_apply.restype = ctypes.c_int
+    lib.rsdgc_apply_blocks.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp,
+                                ctypes.c_float, vp, vp]
+    lib.rsdgc_apply_blocks.restype = ctypes.c_int
     lib.rsdgc_plan_blocks.argtypes = lib.rsdgc_plan.argtypes
     lib.rsdgc_plan_blocks.restype = ctypes.c_int
     lib.rsdgc_compress_blocks.argtypes = [vp] * 9
@@ -284,6 +287,18 @@ def rsdgc_apply(plan: Plan, messages, weights, eta: float, workspace, stream=Non
     cnt = arr(*[_ptr(m[2]) for m in messages])
     _check(load().rsdgc_apply(plan.handle, n, idx, val, cnt, _ptr(weights), float(eta), _ptr(workspace),
                               _stream(stream)), "rsdgc_apply")
+
+
+def rsdgc_apply_blocks(plan: Plan, messages, weights, eta: float, workspace, stream=None) -> None:
+    """rsdgc_apply for a block plan.  messages: sequence of (block_idx, val, counts) device
+    tensors as written by rsdgc_compress_blocks."""
+    n = len(messages)
+    arr = ctypes.c_void_p * max(n, 1)
+    idx = arr(*[_ptr(m[0]) for m in messages])
+    val = arr(*[_ptr(m[1]) for m in messages])
+    cnt = arr(*[_ptr(m[2]) for m in messages])
+    _check(load().rsdgc_apply_blocks(plan.handle, n, idx, val, cnt, _ptr(weights), float(eta), _ptr(workspace),
+                                     _stream(stream)), "rsdgc_apply_blocks")
 
 
 def rsdgc_nsi(plan: Plan, grad, residual, nsi_out, workspace, stream=None) -> None:

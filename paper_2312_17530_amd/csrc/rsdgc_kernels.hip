@@ -33,7 +33,7 @@
 //   emit             k_emit, k_emit_sparse, k_emit_centres
 //   decompress       k_zero_layers, k_scatter
 //   block reading    k_block_nsi, k_emit_blocks, k_scatter_blocks
-//   apply            k_apply (receiving side)
+//   apply            k_apply, k_apply_blocks (receiving side)
 //   dynamic ratios   k_dyn_*
 //   host side        launch helpers and the extern "C" entry points
 #include <hip/hip_runtime.h>
@@ -2108,6 +2108,39 @@ __global__ __launch_bounds__(256) void k_apply(const LayerDev *__restrict__ laye
     if (__float_as_uint(s) != 0u) weights[pos] = weights[pos] - __fmul_rn(eta, s);
 }
 
+// The same for block messages (the block reading): one thread per kept block of every message
+// walks the block's slots inside the matrix.
+__global__ __launch_bounds__(256) void k_apply_blocks(const LayerDev *__restrict__ outer, int n_layers,
+                                                      long long capacity, const ApplyMsgs msgs,
+                                                      float *__restrict__ acc, float *__restrict__ weights,
+                                                      float eta) {
+    const long long j = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+    if (j >= capacity) return;
+    const int k = blockIdx.y;
+    int lo = 0, hi = n_layers;            // last layer whose block segment starts at or before j
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (outer[mid].centre_off <= j) lo = mid; else hi = mid;
+    }
+    const LayerDev O = outer[lo];
+    const long long q = j - O.centre_off;
+    if (q >= msgs.counts[k][lo] || q >= static_cast<long long>(O.k)) return;
+    const int P = static_cast<int>(O.p), R = static_cast<int>(O.R), C = static_cast<int>(O.C);
+    const uint32_t BC = (O.C + O.p - 1) / O.p, BR = (O.R + O.p - 1) / O.p;
+    const uint32_t b = msgs.idx[k][j];
+    if (b >= BR * BC) return;             // malformed message: ignore the block (k_scatter_blocks did too)
+    const int bx = static_cast<int>(b / BC), by = static_cast<int>(b - static_cast<uint32_t>(bx) * BC);
+    for (int dx = 0; dx < P; ++dx)
+        for (int dy = 0; dy < P; ++dy) {
+            const int x = bx * P + dx, y = by * P + dy;
+            if (x < R && y < C) {
+                const size_t pos = static_cast<size_t>(O.elem_off) + static_cast<size_t>(x) * C + y;
+                const float sum = atomicExch(&acc[pos], 0.f);
+                if (__float_as_uint(sum) != 0u) weights[pos] = weights[pos] - __fmul_rn(eta, sum);
+            }
+        }
+}
+
 __global__ __launch_bounds__(256) void k_fill_zero(uint4 *__restrict__ p, size_t n16) {
     const size_t stride = static_cast<size_t>(gridDim.x) * 256;
     for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride)
@@ -2749,6 +2782,45 @@ int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
     }
     hipLaunchKernelGGL(k_apply, dim3(blocks, static_cast<unsigned>(n_msgs)), dim3(256), 0, stream, layers,
                        plan->n_layers, static_cast<long long>(plan->out_capacity), m, acc, weights, eta);
+    HIP_TRY(hipGetLastError());
+    plan->acc_zero_ws = workspace;
+    return RSDGC_OK;
+}
+
+int rsdgc_apply_blocks(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *block_idx,
+                       const float *const *val, const int32_t *const *counts, float *weights, float eta,
+                       void *workspace, void *stream_) {
+    if (!plan || !plan->blocks || !block_idx || !val || !counts || !weights || !workspace) return RSDGC_EINVAL;
+    if (n_msgs < 1 || n_msgs > RSDGC_MAX_MSGS || !(eta == eta)) return RSDGC_EINVAL;
+    if (!aligned256(workspace) || !aligned16(weights)) return RSDGC_EINVAL;
+    for (int k = 0; k < n_msgs; ++k)
+        if (!block_idx[k] || !val[k] || !counts[k]) return RSDGC_EINVAL;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    char *ws = static_cast<char *>(workspace);
+    int rc = upload_tables(plan, workspace, stream);
+    if (rc != RSDGC_OK) return rc;
+    const LayerDev *outer = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
+    // a block plan's workspace: its tables, the inner plan's workspace, then the accumulator
+    float *acc = reinterpret_cast<float *>(ws + plan->ws.table_bytes + plan->inner->ws.total);
+    if (plan->centre_capacity == 0) return RSDGC_OK;   // no message can hold a block
+    if (plan->acc_zero_ws != workspace) {              // first use of this workspace: clear the accumulator
+        const size_t n16 = static_cast<size_t>(plan->total_elems) * sizeof(float) / 16;
+        hipLaunchKernelGGL(k_fill_zero, dim3(kNumCUs * 8u), dim3(256), 0, stream,
+                           reinterpret_cast<uint4 *>(acc), n16);
+        HIP_TRY(hipGetLastError());
+    }
+    plan->acc_zero_ws = nullptr;                       // not known to be zero until the apply kernel is enqueued
+    const unsigned blocks = static_cast<unsigned>((plan->centre_capacity + 255) / 256);
+    ApplyMsgs m;
+    std::memset(&m, 0, sizeof(m));
+    for (int k = 0; k < n_msgs; ++k) {                 // the sum, message by message, in the order given
+        hipLaunchKernelGGL(k_scatter_blocks, dim3(blocks), dim3(256), 0, stream, outer, plan->n_layers,
+                           static_cast<long long>(plan->centre_capacity), block_idx[k], val[k], counts[k], acc, 1);
+        m.idx[k] = block_idx[k];
+        m.counts[k] = counts[k];
+    }
+    hipLaunchKernelGGL(k_apply_blocks, dim3(blocks, static_cast<unsigned>(n_msgs)), dim3(256), 0, stream, outer,
+                       plan->n_layers, static_cast<long long>(plan->centre_capacity), m, acc, weights, eta);
     HIP_TRY(hipGetLastError());
     plan->acc_zero_ws = workspace;
     return RSDGC_OK;

@@ -415,7 +415,11 @@ int64_t rsdgc_centre_capacity(const rsdgc_plan_t *plan) {
 }
 size_t rsdgc_workspace_bytes(const rsdgc_plan_t *plan) {
     if (!plan) return 0;
-    if (plan->blocks) return plan->ws.table_bytes + plan->inner->ws.total;   // table_bytes is a multiple of 256
+    // a block plan: its own tables, the workspace of the plan that ranks the block grids, and the
+    // message accumulator of rsdgc_apply_blocks (float[total_elems]); all multiples of 256
+    if (plan->blocks)
+        return plan->ws.table_bytes + plan->inner->ws.total +
+               align_up(sizeof(float) * static_cast<size_t>(plan->total_elems), 256);
     return plan->ws.total;
 }
 

@@ -213,5 +213,13 @@ def test_newer_entry_points_validate_before_touching_the_gpu():
     assert lib.rsdgc_decompress_blocks(plan.handle, a, a, a, a, 0, 4 * a, null) == E
     assert lib.rsdgc_decompress(bplan.handle, a, a, a, a, 0, 4 * a, null) == E
     assert lib.rsdgc_nsi(bplan.handle, a, a, a, 4 * a, null) == E
+    assert lib.rsdgc_apply(bplan.handle, 1, ptrs, ptrs, ptrs, a, 0.1, a, null) == E
+    assert lib.rsdgc_apply_blocks(plan.handle, 1, ptrs, ptrs, ptrs, a, 0.1, a, null) == E
+    # apply for block messages: the same argument checks
+    assert lib.rsdgc_apply_blocks(bplan.handle, 0, ptrs, ptrs, ptrs, a, 0.1, a, null) == E
+    assert lib.rsdgc_apply_blocks(bplan.handle, 65, ptrs, ptrs, ptrs, a, 0.1, a, null) == E
+    assert lib.rsdgc_apply_blocks(bplan.handle, 1, ptrs, null, ptrs, a, 0.1, a, null) == E
+    assert lib.rsdgc_apply_blocks(bplan.handle, 1, ptrs, ptrs, ptrs, a + 4, 0.1, a, null) == E
+    assert lib.rsdgc_apply_blocks(bplan.handle, 1, ptrs, ptrs, ptrs, a, float("nan"), a, null) == E
     assert lib.rsdgc_compress_blocks(bplan.handle, a, 2 * a, 2 * a + 128, a, a, a, 4 * a, null) == E    # overlapping arenas
     assert lib.rsdgc_compress_blocks(bplan.handle, a, a, a, a, a, a, 4 * a, null) == E                    # new residual on the gradient

@@ -402,6 +402,74 @@ def test_blocks_receiving_side_skips_what_a_malformed_message_names():
     assert np.array_equal(dense.cpu().numpy().view(np.uint32), want.view(np.uint32))
 
 
+def test_blocks_apply_messages_of_three_nodes_matches_the_oracle():
+    """Eq. 12, third line, with block messages: three nodes compress their own gradients in the
+    block reading; the receiving side sums the messages in order and steps the weights.  Two
+    rounds, so the second runs on the accumulator the first left behind; a tampered message at
+    the end (block index beyond the grid, counts beyond k_l and negative) must be skipped."""
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import BlockSession
+    shapes = [(1, 40), (33, 129), (200, 45), (64, 256), (300, 700), (7, 1000)]
+    p_list = [3, 3, 5, 3, 1, 7]
+    ratios = [0.5, 0.05, 0.1, 0.2, 0.02, 0.3]
+    sess = BlockSession(shapes, 3, 0.5, ratios, p_list)
+    rng = np.random.default_rng(62)
+    weights = [rng.standard_normal(sh).astype(np.float32) for sh in shapes]
+    w_dev = torch.full_like(sess.grad, 3.0)
+    for l, w in enumerate(weights):
+        o = sess.plan.layer_offset(l)
+        w_dev[o:o + w.size] = torch.from_numpy(w.reshape(-1)).to(w_dev.device)
+    eta = 0.05
+    for rnd in range(2):
+        msgs_dev, msgs_host = [], []
+        for node in range(3):
+            sess.set_grad([synth.layer_gradient(sh, 1e-2, 90 + node, rnd, l) for l, sh in enumerate(shapes)])
+            sess.residual.zero_()
+            sess.compress()
+            torch.cuda.synchronize()
+            msgs_dev.append((sess.out_blocks.clone(), sess.out_val.clone(), sess.out_counts.clone()))
+            msgs_host.append(sess.results())
+        binding.rsdgc_apply_blocks(sess.plan, msgs_dev, w_dev, eta, sess.workspace)
+        torch.cuda.synchronize()
+        arena = w_dev.cpu().numpy()
+        got = []
+        for l, (R, C) in enumerate(shapes):
+            o = sess.plan.layer_offset(l)
+            got.append(arena[o:o + R * C].reshape(R, C).copy())
+            want = oracle.apply_block_messages(weights[l], [m[l] for m in msgs_host], p_list[l], eta)
+            assert np.array_equal(got[l].view(np.uint32), want.view(np.uint32)), (rnd, l)
+        weights = got
+    # a tampered copy of the last message: nothing it names wrongly is followed
+    blocks, val, counts = (t.clone() for t in msgs_dev[-1])
+    n_blocks = [-(-r // p) * -(-c // p) for (r, c), p in zip(shapes, p_list)]
+    ks = [sess.plan.layer_k(l) for l in range(len(shapes))]
+    host_blocks = blocks.cpu().numpy().view(np.uint32).copy()
+    host_counts = counts.cpu().numpy().copy()
+    l_bad = 4
+    host_blocks[sess.plan.centre_offset(l_bad)] = n_blocks[l_bad] + 3
+    host_counts[1] = ks[1] + 1000
+    host_counts[2] = -7
+    blocks.copy_(torch.from_numpy(host_blocks.view(np.int32)))
+    counts.copy_(torch.from_numpy(host_counts))
+    before = w_dev.cpu().numpy().copy()
+    binding.rsdgc_apply_blocks(sess.plan, [(blocks, val, counts)], w_dev, eta, sess.workspace)
+    torch.cuda.synchronize()
+    arena = w_dev.cpu().numpy()
+    last = msgs_host[-1]
+    want_arena = before.copy()
+    for l, (R, C) in enumerate(shapes):
+        b, v = last[l]
+        pp = p_list[l] ** 2
+        if l == 2:
+            b, v = b[:0], v[:0]
+        if l == l_bad:
+            b, v = b[1:], v[pp:]
+        o = sess.plan.layer_offset(l)
+        want_arena[o:o + R * C] = oracle.apply_block_messages(weights[l], [(b, v)], p_list[l], eta).reshape(-1)
+    assert np.array_equal(arena.view(np.uint32), want_arena.view(np.uint32))     # padding (3.0) included
+
+
 def test_blocks_resnet18_shapes():
     w = synth.config(1)
     its = [synth.gradients(w, t) for t in range(2)]
