@@ -8,6 +8,8 @@ import math
 import os
 from fractions import Fraction
 
+import hypothesis
+import hypothesis.strategies as st
 import numpy as np
 import pytest
 from scipy import ndimage
@@ -345,6 +347,32 @@ def test_oracle_against_pure_python_brute_force(R, C, p, alpha, rho, seed):
             assert o.tau == b["tau"]
     else:  # pragma: no cover - only if the two double evaluations round differently
         pytest.skip("score rounding differed between C and Python doubles")
+
+
+@hypothesis.settings(max_examples=60, deadline=None, derandomize=True)
+@hypothesis.given(R=st.integers(1, 12), C=st.integers(1, 12), p=st.sampled_from([1, 3, 5, 7]),
+                  alpha=st.sampled_from([0.0, 0.25, 0.5, 1.0]), rho=st.sampled_from([0.0, 0.01, 0.1, 0.3, 0.7, 1.0]),
+                  few_values=st.booleans(), seed=st.integers(0, 2 ** 16))
+def test_oracle_against_brute_force_on_drawn_cases(R, C, p, alpha, rho, few_values, seed):
+    """The same comparison on drawn shapes, neighbourhood sides, mixes and ratios; half of the
+    inputs take only five distinct values, so equal scores (and the index tie rule) are common."""
+    rng = np.random.default_rng(seed)
+    if few_values:
+        g = rng.integers(-2, 3, size=(R, C)).astype(np.float32) * np.float32(0.125)
+        r = rng.integers(-1, 2, size=(R, C)).astype(np.float32) * np.float32(0.25)
+    else:
+        g = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        r = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+    b = brute_compress(g.tolist(), r.tolist(), p, alpha, rho)
+    o = oracle.compress_layer(g, r, p, alpha, rho)
+    assert o.k == b["k"]
+    assert o.v.ravel().tolist() == b["v"]
+    assert np.allclose(o.nsi.ravel(), np.array(b["nsi"], dtype=np.float32), rtol=2e-7, atol=1e-30)
+    hypothesis.assume(np.array_equal(o.nsi.ravel(), np.array(b["nsi"], dtype=np.float32)))
+    assert o.centres.tolist() == b["centres"]
+    assert o.idx.tolist() == b["idx"]
+    assert o.val.tolist() == b["val"]
+    assert o.r_new.ravel().tolist() == b["r_new"]
 
 
 # ------------------------------------------------- momentum correction (Eq. 12 in full)
