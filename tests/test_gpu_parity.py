@@ -534,6 +534,33 @@ def test_ragged_shapes_mixed_p_two_iterations(alpha, in_place):
     assert ex >= n - 2          # the tolerance band is allowed, but should hardly ever be needed
 
 
+def test_drawn_small_configurations(in_place):
+    """Twenty seeded draws of a small plan: 1-5 layers of up to 90 x 400 elements, a
+    neighbourhood side per layer, keep ratios from 0 to 1, mixes from 0 to 1, ordinary noise or
+    inputs of five distinct values (scores tie in masses); two iterations carrying the residual."""
+    n_total = ex_total = 0
+    for seed in range(20):
+        rng = np.random.default_rng(1000 + seed)
+        L = int(rng.integers(1, 6))
+        shapes = [(int(rng.integers(1, 91)), int(rng.integers(1, 401))) for _ in range(L)]
+        p_list = [int(rng.choice([1, 3, 5, 7])) for _ in range(L)]
+        ratios = [float(rng.choice([0.0, 0.003, 0.02, 0.1, 0.3, 0.8, 1.0])) for _ in range(L)]
+        alpha = float(rng.choice([0.0, 0.25, 0.5, 1.0]))
+        its = []
+        for t in range(2):
+            grads = []
+            for sh in shapes:
+                if rng.random() < 0.3:
+                    grads.append(rng.integers(-2, 3, size=sh).astype(np.float32) * np.float32(0.125))
+                else:
+                    grads.append((rng.standard_normal(sh) * 10.0 ** rng.uniform(-4, 0)).astype(np.float32))
+            its.append(grads)
+        n, ex = run_and_check(shapes, p_list, alpha, ratios, its, f"drawn{seed}", in_place=in_place)
+        n_total += n
+        ex_total += ex
+    assert ex_total >= n_total - 2
+
+
 def test_degenerate_inputs_follow_index_tie_break():
     shapes = [(40, 70), (64, 128), (50, 50), (33, 40), (16, 300), (90, 45)]
     zeros = np.zeros(shapes[0], dtype=np.float32)
