@@ -561,6 +561,28 @@ def test_drawn_small_configurations(in_place):
     assert ex_total >= n_total - 2
 
 
+def test_drawn_large_configurations(in_place):
+    """Six seeded draws of 2-3 layers of 0.1 to 4 million elements with odd row lengths: most take
+    the candidate path (with and without the work feed), some the full map; sides, ratios, mixes
+    and the noise scale (down to 1e-6, up to 1e3) are drawn per layer."""
+    n_total = ex_total = 0
+    for seed in range(6):
+        rng = np.random.default_rng(2000 + seed)
+        L = int(rng.integers(2, 4))
+        shapes = [(int(rng.integers(300, 1501)), int(rng.integers(300, 3001))) for _ in range(L)]
+        p_list = [int(rng.choice([1, 3, 3, 5, 7])) for _ in range(L)]
+        ratios = [float(rng.choice([0.003, 0.02, 0.05, 0.2])) for _ in range(L)]
+        alpha = float(rng.choice([0.0, 0.25, 0.5, 0.5, 1.0]))
+        its = [[synth.layer_gradient(sh, 10.0 ** rng.uniform(-6, 3), 2000 + seed, t, l) for l, sh in enumerate(shapes)]
+               for t in range(2)]
+        feed = FEED_ON if seed % 2 else FEED_AUTO
+        n, ex = run_and_check(shapes, p_list, alpha, ratios, its, f"drawn_large{seed}", in_place=in_place,
+                              work_feed=feed)
+        n_total += n
+        ex_total += ex
+    assert ex_total >= n_total - 2
+
+
 def test_degenerate_inputs_follow_index_tie_break():
     shapes = [(40, 70), (64, 128), (50, 50), (33, 40), (16, 300), (90, 45)]
     zeros = np.zeros(shapes[0], dtype=np.float32)
