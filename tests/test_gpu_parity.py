@@ -534,31 +534,52 @@ def test_ragged_shapes_mixed_p_two_iterations(alpha, in_place):
     assert ex >= n - 2          # the tolerance band is allowed, but should hardly ever be needed
 
 
+def _draw_small(seed):
+    """A seeded small plan: 1-5 layers of up to 90 x 400 elements, a neighbourhood side per
+    layer, keep ratios from 0 to 1, a mix from 0 to 1, two iterations of ordinary noise or of
+    inputs with five distinct values (scores tie in masses)."""
+    rng = np.random.default_rng(1000 + seed)
+    L = int(rng.integers(1, 6))
+    shapes = [(int(rng.integers(1, 91)), int(rng.integers(1, 401))) for _ in range(L)]
+    p_list = [int(rng.choice([1, 3, 5, 7])) for _ in range(L)]
+    ratios = [float(rng.choice([0.0, 0.003, 0.02, 0.1, 0.3, 0.8, 1.0])) for _ in range(L)]
+    alpha = float(rng.choice([0.0, 0.25, 0.5, 1.0]))
+    its = []
+    for t in range(2):
+        grads = []
+        for sh in shapes:
+            if rng.random() < 0.3:
+                grads.append(rng.integers(-2, 3, size=sh).astype(np.float32) * np.float32(0.125))
+            else:
+                grads.append((rng.standard_normal(sh) * 10.0 ** rng.uniform(-4, 0)).astype(np.float32))
+        its.append(grads)
+    return shapes, p_list, ratios, alpha, its
+
+
 def test_drawn_small_configurations(in_place):
-    """Twenty seeded draws of a small plan: 1-5 layers of up to 90 x 400 elements, a
-    neighbourhood side per layer, keep ratios from 0 to 1, mixes from 0 to 1, ordinary noise or
-    inputs of five distinct values (scores tie in masses); two iterations carrying the residual."""
+    """Twenty seeded draws (see _draw_small), two iterations carrying the residual."""
     n_total = ex_total = 0
     for seed in range(20):
-        rng = np.random.default_rng(1000 + seed)
-        L = int(rng.integers(1, 6))
-        shapes = [(int(rng.integers(1, 91)), int(rng.integers(1, 401))) for _ in range(L)]
-        p_list = [int(rng.choice([1, 3, 5, 7])) for _ in range(L)]
-        ratios = [float(rng.choice([0.0, 0.003, 0.02, 0.1, 0.3, 0.8, 1.0])) for _ in range(L)]
-        alpha = float(rng.choice([0.0, 0.25, 0.5, 1.0]))
-        its = []
-        for t in range(2):
-            grads = []
-            for sh in shapes:
-                if rng.random() < 0.3:
-                    grads.append(rng.integers(-2, 3, size=sh).astype(np.float32) * np.float32(0.125))
-                else:
-                    grads.append((rng.standard_normal(sh) * 10.0 ** rng.uniform(-4, 0)).astype(np.float32))
-            its.append(grads)
+        shapes, p_list, ratios, alpha, its = _draw_small(seed)
         n, ex = run_and_check(shapes, p_list, alpha, ratios, its, f"drawn{seed}", in_place=in_place)
         n_total += n
         ex_total += ex
     assert ex_total >= n_total - 2
+
+
+def test_drawn_small_configurations_with_momentum_and_in_the_block_reading():
+    """The same draws through rsdgc_compress_momentum (m drawn too) and rsdgc_compress_blocks."""
+    n_total = ex_total = 0
+    for seed in range(20, 32):
+        shapes, p_list, ratios, alpha, its = _draw_small(seed)
+        m = [0.9, 0.5, 0.0, 1.0][seed % 4]
+        n, ex = run_and_check_momentum(shapes, p_list, alpha, ratios, m, its, f"drawn{seed}")
+        n_total += n
+        ex_total += ex
+        n, ex = run_and_check_blocks(shapes, p_list, alpha, ratios, its, f"drawn{seed}", in_place=bool(seed % 2))
+        n_total += n
+        ex_total += ex
+    assert ex_total >= n_total - 3
 
 
 def test_drawn_large_configurations(in_place):
