@@ -604,6 +604,19 @@ def test_drawn_large_configurations(in_place):
     assert ex_total >= n_total - 2
 
 
+def test_subnormal_and_huge_magnitudes(in_place):
+    """Gradients in float32's subnormal range (their scores are subnormal floats too, and must
+    not be flushed to zero: the ranking would collapse into index order) and near its upper end
+    (squares far beyond float32, within double)."""
+    shapes = [(40, 300), (64, 129), (700, 1100)]
+    rng = np.random.default_rng(77)
+    for scale in (1e-41, 3e-39, 1e18):
+        its = [[(rng.standard_normal(sh) * scale).astype(np.float32) for sh in shapes] for _ in range(2)]
+        assert all(np.isfinite(g).all() and np.count_nonzero(g) > g.size // 2 for g in its[0])
+        n, ex = run_and_check(shapes, [3, 5, 3], 0.5, [0.05, 0.1, 0.02], its, f"magnitude{scale}", in_place=in_place)
+        assert n == 6 and ex >= 5
+
+
 def test_degenerate_inputs_follow_index_tie_break():
     shapes = [(40, 70), (64, 128), (50, 50), (33, 40), (16, 300), (90, 45)]
     zeros = np.zeros(shapes[0], dtype=np.float32)
