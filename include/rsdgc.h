@@ -99,6 +99,13 @@ int rsdgc_plan_set_path(rsdgc_plan_t *plan, int32_t path);
 #define RSDGC_FEED_ON    2
 int rsdgc_plan_set_work_feed(rsdgc_plan_t *plan, int32_t mode);
 
+/* A plan remembers the address of the workspace it last prepared (tables
+ * uploaded, message accumulator cleared) and skips that work while the address
+ * stays the same.  Call this when the memory at that address has been freed,
+ * reused or overwritten in the meantime: the next call with any workspace
+ * prepares it afresh.  Host side only; no GPU work.                          */
+int rsdgc_plan_forget_workspace(rsdgc_plan_t *plan);
+
 void rsdgc_plan_destroy(rsdgc_plan_t *plan);
 
 /* Host queries; l in [0, n_layers).  Invalid arguments give -1 (0 for size_t). */
@@ -144,7 +151,8 @@ size_t  rsdgc_workspace_bytes(const rsdgc_plan_t *plan);
  *   workspace [device] rsdgc_workspace_bytes bytes, 256-byte aligned.  It is
  *             the plan's device-side state: keep the same buffer, unmodified,
  *             between calls that use this plan (switching to another buffer is
- *             allowed at any time and is detected by its address).
+ *             allowed at any time and is detected by its address; after the
+ *             buffer's memory was recycled, see rsdgc_plan_forget_workspace).
  * Ranking ties are resolved towards the lower flat index; exactly k_l centres
  * are selected.  Scores are float32 roundings of double-precision window
  * statistics.                                                               */

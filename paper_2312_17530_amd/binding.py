@@ -18,7 +18,7 @@ RSDGC_OK, RSDGC_EINVAL, RSDGC_ENOMEM, RSDGC_EHIP = 0, -1, -2, -3
 RSDGC_MAX_P = 7
 
 EXPORTS = [
-    "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_set_work_feed", "rsdgc_plan_destroy", "rsdgc_n_layers",
+    "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_set_work_feed", "rsdgc_plan_forget_workspace", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
     "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_apply_blocks", "rsdgc_plan_blocks", "rsdgc_compress_blocks",
@@ -70,6 +70,8 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_plan_set_path.restype = ctypes.c_int
     lib.rsdgc_plan_set_work_feed.argtypes = [vp, i32]
     lib.rsdgc_plan_set_work_feed.restype = ctypes.c_int
+    lib.rsdgc_plan_forget_workspace.argtypes = [vp]
+    lib.rsdgc_plan_forget_workspace.restype = ctypes.c_int
     lib.rsdgc_plan_destroy.argtypes = [vp]
     lib.rsdgc_plan_destroy.restype = None
     lib.rsdgc_n_layers.argtypes = [vp]
@@ -239,6 +241,10 @@ def rsdgc_plan_set_ratios(plan: Plan, keep_ratio: Sequence[float]) -> None:
 
 
 FEED_AUTO, FEED_OFF, FEED_ON = 0, 1, 2
+
+
+def rsdgc_plan_forget_workspace(plan: "Plan") -> None:
+    _check(load().rsdgc_plan_forget_workspace(plan.handle), "rsdgc_plan_forget_workspace")
 
 
 def rsdgc_plan_set_work_feed(plan: "Plan", mode: int) -> None:

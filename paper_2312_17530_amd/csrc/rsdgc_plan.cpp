@@ -379,6 +379,14 @@ int rsdgc_plan_set_work_feed(rsdgc_plan_t *plan, int32_t mode) {
     return RSDGC_OK;
 }
 
+int rsdgc_plan_forget_workspace(rsdgc_plan_t *plan) {
+    if (!plan) return RSDGC_EINVAL;
+    plan->uploaded_ws = nullptr;       // the next call uploads the tables again ...
+    plan->acc_zero_ws = nullptr;       // ... and clears the message accumulator before it is used
+    if (plan->inner) plan->inner->uploaded_ws = nullptr;
+    return RSDGC_OK;
+}
+
 void rsdgc_plan_destroy(rsdgc_plan_t *plan) {
     if (plan) {
         int32_t n = 0;

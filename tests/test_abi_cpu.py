@@ -111,6 +111,8 @@ def test_work_feed_mode_is_validated():
         with pytest.raises(binding.RsdgcError):
             binding.rsdgc_plan_set_work_feed(plan, bad)
     assert binding.load().rsdgc_plan_set_work_feed(None, 0) == binding.RSDGC_EINVAL
+    binding.rsdgc_plan_forget_workspace(plan)
+    assert binding.load().rsdgc_plan_forget_workspace(None) == binding.RSDGC_EINVAL
 
 
 def test_per_layer_neighbourhood_side():

@@ -815,6 +815,31 @@ def test_set_ratios_and_determinism():
         assert np.array_equal(c1, c2)
 
 
+def test_a_recycled_workspace_is_prepared_again_when_the_plan_is_told():
+    """The workspace is wiped between two calls (as when its memory was freed and handed out
+    again); after rsdgc_plan_forget_workspace the next call uploads the tables afresh and gives
+    the same result -- for an element plan and a block plan."""
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import BlockSession
+    w = synth.scaled_down(synth.config(1), 256, 512)
+    grads = synth.gradients(w, 0)
+    for make in (lambda: _session(w.shapes, w.p, w.alpha, w.ratios),
+                 lambda: BlockSession(w.shapes, w.p, w.alpha, w.ratios)):
+        sess = make()
+        sess.set_grad(grads)
+        sess.compress()
+        torch.cuda.synchronize()
+        first = [tuple(np.copy(a) if isinstance(a, np.ndarray) else a for a in r) for r in sess.results()]
+        sess.workspace.zero_()                       # tables gone
+        binding.rsdgc_plan_forget_workspace(sess.plan)
+        sess.residual.zero_()
+        sess.compress()
+        torch.cuda.synchronize()
+        for a, b in zip(first, sess.results()):
+            assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+
+
 def test_decompress_accumulate_sums_messages():
     import torch
     w = synth.config(0)
