@@ -165,7 +165,8 @@ def test_binding_fails_loudly_without_the_library(monkeypatch):
 
 def test_block_plan_layout_on_the_host():
     """rsdgc_plan_blocks: k_l from Eq. 11, one index per kept block, p*p values per kept block
-    (padding slots of partial blocks included), workspace = the plan's tables + the block grid's."""
+    (padding slots of partial blocks included), workspace = the plan's tables + the block grid's
+    + the message accumulator."""
     shapes, p_list, ratios = [(90, 90), (10, 10), (64, 27), (7, 1000)], [3, 3, 5, 7], [0.1, 1.0, 0.5, 0.3]
     plan = binding.rsdgc_plan_blocks(shapes, 3, 0.5, ratios, p_list)
     ks = [math.ceil(r * c / (p * p) * rho) for (r, c), p, rho in zip(shapes, p_list, ratios)]
@@ -180,6 +181,8 @@ def test_block_plan_layout_on_the_host():
     element_plan = binding.rsdgc_plan(shapes, 3, 0.5, ratios, p_list)
     assert plan.total_elems == element_plan.total_elems           # the arenas are laid out alike
     assert plan.workspace_bytes % 256 == 0 and 0 < plan.workspace_bytes < element_plan.workspace_bytes
+    # ... + the message accumulator of rsdgc_apply_blocks (one float per arena element)
+    assert plan.workspace_bytes > 4 * plan.total_elems
     binding.rsdgc_plan_set_ratios(plan, [0.0, 0.5, 0.5, 0.3])
     assert [plan.layer_k(l) for l in range(4)] == [0, 6, ks[2], ks[3]]
     with pytest.raises(binding.RsdgcError):
