@@ -81,7 +81,8 @@ int build_tables(rsdgc_plan_s *plan) {
         // Candidate path: the bound comes from the scores of a sample of the layer's tiles.
         // It is taken where about twice k_l centres are expected above the bound; a layer is
         // eligible when it has enough sampled tiles for that estimate and when the expected
-        // number of candidates per tile leaves ample room in a tile's slot.
+        // number of candidates per tile (2 k_l / tiles, at most 57) leaves a factor 4.5 of room
+        // in a tile's slot (kSlotCap); a tile that still overflows sends the layer to the full map.
         uint32_t n_sampled = 0;
         const uint32_t sshift = sample_shift(d.n_tiles);
         for (uint32_t t = 0; t < d.n_tiles; ++t) n_sampled += tile_is_sampled(t, sshift) ? 1u : 0u;
@@ -90,7 +91,7 @@ int build_tables(rsdgc_plan_s *plan) {
         const double want = 2.0 * double(k) * frac;
         const double per_tile = d.n_tiles ? 3.0 * double(k) / double(d.n_tiles) : 0.0;
         d.large = (plan->allow_candidates && k > 0 && n_sampled >= uint32_t(kMinSampledTiles) &&
-                   per_tile <= kSlotCap / 4.0) ? 1u : 0u;
+                   per_tile <= kSlotCap / 3.0) ? 1u : 0u;
         d.hint_target = d.large ? static_cast<uint32_t>(std::ceil(want + 4.0 * std::sqrt(want) + 8.0)) : 0u;
         plan->any_large = plan->any_large || d.large;
 
