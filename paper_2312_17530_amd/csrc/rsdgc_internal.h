@@ -24,6 +24,7 @@ constexpr int kCountChunks = 16;     // chunks per workgroup of the count pass
 constexpr int kChunkGroup = 64;      // chunks per group in the two-level chunk prefix
 constexpr int kListShards = 16;      // a layer's threshold-bucket list is filled through this many counters
 constexpr int kListCntStride = 32;   // uint32 between two of them (one 128-byte line each)
+constexpr uint32_t kPenaltyCalls = 8;  // calls a large layer spends on the full map after its candidate bound failed
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 
 // Tile of the block-score kernel (block reading): kBlockTileRows block rows by
@@ -167,6 +168,7 @@ struct WsLayout {
     size_t map_chunks = 0;   // ChunkEntry[]: chunks of the other layers that select something
     size_t map_tiles = 0;    // SampleEntry[]: tiles of those layers
     size_t count_groups = 0; // CountGroup[n_count_groups]
+    size_t penalty = 0;      // uint32[n_layers]  uploaded as zeros, then kept by the kernels: calls left on the full map
     size_t table_bytes = 0;  // bytes uploaded from the host
     size_t state = 0;        // SelState[n_layers], rewritten at the start of every compress
     // cleared at the start of every compress

@@ -137,10 +137,13 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_t
 
 // ---------------------------------------------------------------- begin --
 // Start of a compress call: all workgroups but the last clear the histograms, counters and
-// bitmasks; the last one writes every layer's initial selection state.
+// bitmasks; the last one writes every layer's initial selection state.  A large layer whose
+// candidate bound failed in a recent call (penalty[l] > 0, see k_hint and k_validate) starts on
+// the full map: it would most likely fail again, and the main pass over it would be wasted.
 __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16,
                                                const LayerDev *__restrict__ layers,
-                                               SelState *__restrict__ state, int n_layers) {
+                                               SelState *__restrict__ state, int n_layers,
+                                               uint32_t *__restrict__ penalty /* nullable */) {
     if (blockIdx.x + 1 == gridDim.x) {
         for (int l = threadIdx.x; l < n_layers; l += 256) {
             SelState s;
@@ -149,6 +152,13 @@ __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16
             s.k_rem = L.k;
             s.done = L.k == 0 ? 1u : 0u;
             s.mode = L.k == 0 ? kModeSkip : (L.large ? kModeCandidates : kModeFullMap);
+            if (penalty && s.mode == kModeCandidates) {
+                const uint32_t left = penalty[l];
+                if (left > 0) {
+                    s.mode = kModeFullMap;
+                    penalty[l] = left - 1;
+                }
+            }
             s.hint_key = 0;
             s.overflow = 0;
             s.n_centres = 0;
@@ -660,7 +670,8 @@ void k_nsi(const NsiArgs a) {
 __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layers,
                                               SelState *__restrict__ state,
                                               uint32_t *__restrict__ hist,
-                                              uint32_t *__restrict__ flags) {
+                                              uint32_t *__restrict__ flags,
+                                              uint32_t *__restrict__ penalty) {
     __shared__ uint32_t wave_tot[4];
     __shared__ uint32_t found;
     const int l = blockIdx.x, tid = threadIdx.x;
@@ -673,7 +684,15 @@ __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layer
     uint32_t own = 0;
 #pragma unroll
     for (int b = hi - 1; b >= hi - per; --b) own += h[b];
-    if (st.mode != kModeCandidates) return;      // its histogram is untouched (still zero)
+    if (st.mode != kModeCandidates) {
+        // a large layer that k_begin kept off the candidate path: the sampled counts go, and the
+        // fallback pass has work; any other layer's histogram is either still zero or complete
+        if (st.mode == kModeFullMap && layers[l].large != 0u) {
+            for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
+            if (tid == 0) flags[0] = 1u;
+        }
+        return;
+    }
     if (tid == 0) found = 0;
     const uint32_t incl = block_scan_incl(own, wave_tot);
     const uint32_t excl = incl - own;
@@ -696,6 +715,7 @@ __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layer
         ns.mode = kModeFullMap;
         state[l] = ns;
         flags[0] = 1u;                     // the fallback pass has work
+        penalty[l] = kPenaltyCalls;
     }
     for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
 }
@@ -708,7 +728,8 @@ __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layer
 __global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ layers,
                                                   SelState *__restrict__ state,
                                                   uint32_t *__restrict__ hist,
-                                                  uint32_t *__restrict__ flags) {
+                                                  uint32_t *__restrict__ flags,
+                                                  uint32_t *__restrict__ penalty) {
     __shared__ uint32_t wave_tot[4];
     const int l = blockIdx.x, tid = threadIdx.x;
     // state, k_l and the counts are requested together: one round trip to memory instead of
@@ -731,6 +752,7 @@ __global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ l
             ns.mode = kModeFullMap;
             state[l] = ns;
             flags[0] = 1u;                 // the fallback pass has work
+            penalty[l] = kPenaltyCalls;
         }
     }
 }
@@ -2544,6 +2566,7 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     SelState *state = reinterpret_cast<SelState *>(ws + w.state);
     uint32_t *hist = reinterpret_cast<uint32_t *>(ws + w.hist);
     uint32_t *flags = reinterpret_cast<uint32_t *>(ws + w.flags);
+    uint32_t *penalty = reinterpret_cast<uint32_t *>(ws + w.penalty);
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
     uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
     const uint32_t *group_cnt = reinterpret_cast<const uint32_t *>(ws + w.group_cnt);
@@ -2559,7 +2582,7 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
         const size_t n16 = (end - w.zero_begin) / 16;
         const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
         hipLaunchKernelGGL(k_begin, dim3(blocks + 1), dim3(256), 0, stream,
-                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, layers, state, L);
+                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, layers, state, L, penalty);
         HIP_TRY(hipGetLastError());
     }
     marks.close(0);
@@ -2569,11 +2592,11 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
     if (rc != RSDGC_OK) return rc;
     if (plan->any_large) {
-        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
+        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist, flags, penalty);
         marks.close(1);
         rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, v_out, mom, stream);
         if (rc != RSDGC_OK) return rc;
-        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist, flags);
+        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist, flags, penalty);
         marks.close(2);
         // large layers whose candidate bound failed (rare): their workgroups find nothing to do otherwise
         rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, mom, stream);
@@ -2678,7 +2701,8 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
         const size_t n16 = (w.cmask - w.zero_begin) / 16;
         const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
         hipLaunchKernelGGL(k_begin, dim3(blocks + 1), dim3(256), 0, stream,
-                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, inner, state, L);
+                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, inner, state, L,
+                           static_cast<uint32_t *>(nullptr));   // a block grid is always ranked on its full map
     }
     bool have[RSDGC_MAX_P + 1] = {};
     for (int l = 0; l < L; ++l) have[plan->p[l]] = true;

@@ -192,6 +192,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.map_chunks = off;   off = align_up(off + sizeof(ChunkEntry) * plan->n_chunks, A);
     w.map_tiles = off;    off = align_up(off + sizeof(SampleEntry) * (size_t(plan->n_tiles_all) + 1), A);
     w.count_groups = off; off = align_up(off + sizeof(CountGroup) * plan->n_count_groups, A);
+    w.penalty = off;      off = align_up(off + sizeof(uint32_t) * L, A);
     w.table_bytes = off;
     w.state = off;        off = align_up(off + sizeof(SelState) * L, A);   // written in full each call
     w.zero_begin = off;

@@ -783,6 +783,47 @@ def test_candidate_path_falls_back_when_its_bound_fails(in_place):
             assert n == 6 and ex >= 5
 
 
+def test_a_layer_whose_bound_failed_stays_on_the_full_map_for_eight_calls():
+    """After a call in which a large layer's candidate bound failed, the library starts that
+    layer on the full map for the next eight calls with the same workspace (no wasted main pass
+    over it) and tries the candidate path again in the ninth.  Every call gives the oracle's result."""
+    import torch
+    from paper_2312_17530_amd import binding
+    R, C = 512, 4608
+    rng = np.random.default_rng(124)
+    base = (rng.standard_normal((R, C)) * 1e-3).astype(np.float32)
+    hot_tile = base.copy()
+    hot_tile[64:96, 256:384] *= np.float32(50.0)          # thousands of winners in one tile: slots overflow
+    other = (rng.standard_normal((R, C)) * 1e-3).astype(np.float32)
+    shapes, ratios = [(R, C), (R, C)], [0.02, 0.02]
+    sess = _session(shapes, 3, 0.5, ratios)
+
+    def call(grads, check):
+        sess.set_grad(grads)
+        sess.set_residual([np.zeros((R, C), np.float32)] * 2)
+        sess.compress()
+        torch.cuda.synchronize()
+        paths = binding.rsdgc_last_paths(sess.plan, sess.workspace)
+        if check:
+            res = sess.results()
+            gpu_r = sess.unpack(sess.residual)
+            for l in range(2):
+                o = oracle.compress_layer(grads[l], np.zeros((R, C), np.float32), 3, 0.5, ratios[l])
+                gi, gv, gc, gn = res[l]
+                assert parity.check_layer(f"penalty[l={l}]", shapes[l], 3, o.k, o.tau, o.nsi, o.centres, o.idx,
+                                          o.val, o.r_new, o.v, gi, gv, gc, gn, gpu_r[l])
+        return list(paths)
+
+    assert call([hot_tile, other], True) == [1, 0]         # fails, redone through the full map
+    for i in range(8):                                     # benign input now, but the layer sits out
+        assert call([base, other], i in (0, 7)) == [1, 0], i
+    assert call([base, other], True) == [0, 0]             # the ninth call tries the bound again
+    binding.rsdgc_plan_forget_workspace(sess.plan)         # a prepared-again workspace starts afresh
+    assert call([hot_tile, other], False) == [1, 0]
+    binding.rsdgc_plan_forget_workspace(sess.plan)
+    assert call([base, other], True) == [0, 0]
+
+
 def test_set_ratios_and_determinism():
     import torch
     w = synth.scaled_down(synth.config(2), 256, 512)
