@@ -293,7 +293,11 @@ const char *rsdgc_stage_name(int32_t stage);
 
 /* Which ranking path each layer took in the last rsdgc_compress that used `workspace`:
  * paths[l] [host, n_layers] = 0 candidates above a sampled bound, 1 full score map,
- * 2 nothing to select (k_l = 0).  Waits for `stream`, then copies from the device.   */
+ * 2 nothing to select (k_l = 0).  Waits for `stream`, then copies from the device.
+ * The path never changes a result.  A layer that would take path 0 shows 1 when its
+ * bound failed in this call (too few centres above it, or too many in one tile) or in
+ * one of the eight calls before it with the same workspace: after a failure the layer
+ * starts on the full map for eight calls before the bound is tried again.            */
 int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream);
 
 /* ----------------------------------------------------------- diagnostics */
