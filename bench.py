@@ -32,15 +32,15 @@ METRIC = "gradient elements compressed/sec (full-model, 1 GPU) and % of HBM peak
 # (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); the summaries are
 # in profiles/.  Keyed by (workload name, stage, residual update).  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("vgg19_45c", "capture", "two_arenas"): 1.7360e9,          # profiles/hbm_traffic_vgg19.md, k_nsi<3, 2, false, true>
+    ("vgg19_45c", "capture", "two_arenas"): 1.7378e9,          # profiles/hbm_traffic_vgg19.md, k_nsi<3, 2, false, true>
     ("fc6_25088x4096_t3", "capture", "two_arenas"): 1.2933e9,  # profiles/hbm_traffic_fc6_p5.md, k_nsi<5, 2, false, true>
-    ("vgg19_45c", "capture", "momentum"): 2.8194e9,            # profiles/hbm_traffic_vgg19_momentum.md, k_nsi<3, 2, true, true>
+    ("vgg19_45c", "capture", "momentum"): 2.8207e9,            # profiles/hbm_traffic_vgg19_momentum.md, k_nsi<3, 2, true, true>
 }
 # the same counters summed over all kernels of one rsdgc_compress call
 MEASURED_PATH_TRAFFIC_BYTES = {
-    ("vgg19_45c", "two_arenas"): 2.1010e9,
+    ("vgg19_45c", "two_arenas"): 2.1384e9,
     ("fc6_25088x4096_t3", "two_arenas"): 1.3583e9,
-    ("vgg19_45c", "momentum"): 3.2757e9,
+    ("vgg19_45c", "momentum"): 3.2850e9,
 }
 
 
