@@ -43,6 +43,7 @@ extern "C" {
 #define RSDGC_EINVAL   (-1)  /* bad argument (null pointer, shape, p, alpha, ratio) */
 #define RSDGC_ENOMEM   (-2)  /* host allocation failed */
 #define RSDGC_EHIP     (-3)  /* a HIP call failed; see rsdgc_last_hip_error() */
+#define RSDGC_ETOOBIG  (-4)  /* rsdgc_compress_static: the plan needs more workspace than the built-in one */
 
 #define RSDGC_MAX_P     7    /* largest supported neighbourhood side */
 
@@ -160,6 +161,30 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
                    float *residual_out, uint32_t *out_idx, float *out_val, int32_t *out_counts,
                    uint32_t *out_centre_idx, int32_t *out_centre_counts,
                    void *workspace, void *stream);
+
+/* rsdgc_compress for callers that cannot allocate device memory (code that runs under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * workspace is an array inside the library, RSDGC_STATIC_WORKSPACE_BYTES long, one copy
+ * per GPU, held from the moment the library is loaded until the process ends.  The call
+ * allocates and frees nothing, on the device or through any library that would.
+ *   - Arguments and results as for rsdgc_compress (same kernels), without `workspace`.
+ *     The caller still owns inputs and outputs.
+ *   - A plan with rsdgc_workspace_bytes(plan) > RSDGC_STATIC_WORKSPACE_BYTES is refused
+ *     with RSDGC_ETOOBIG before anything is enqueued (rsdgc_last_hip_error() then holds
+ *     both sizes); a block plan with RSDGC_EINVAL.
+ *   - All calls on one GPU share that GPU's array: two of them (from any plans, streams
+ *     or threads) must not overlap in time -- the later one would overwrite tables and
+ *     counters the earlier one still reads.  Calls that follow each other on one stream
+ *     are fine.  When the array last served another plan (or this plan with other ratios),
+ *     the plan's tables are copied into it again (one host-to-device copy on `stream`)
+ *     and a state the plan keeps between calls starts afresh; everything else that must
+ *     start at zero is cleared by every call.
+ *   - The device current at the time of the call is the one whose array is used.      */
+#define RSDGC_STATIC_WORKSPACE_BYTES (64u << 20)
+int rsdgc_compress_static(rsdgc_plan_t *plan, const float *grad, const float *residual,
+                          float *residual_out, uint32_t *out_idx, float *out_val,
+                          int32_t *out_counts, uint32_t *out_centre_idx,
+                          int32_t *out_centre_counts, void *stream);
 
 /* The same iteration with momentum correction (Eq. 12 in full; Section III-C's last
  * paragraph adopts it):  u = m*u + g  (one float32 multiply, one float32 add),

@@ -14,14 +14,15 @@ from typing import List, Optional, Sequence, Tuple
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librsdgc.so")
 
-RSDGC_OK, RSDGC_EINVAL, RSDGC_ENOMEM, RSDGC_EHIP = 0, -1, -2, -3
+RSDGC_OK, RSDGC_EINVAL, RSDGC_ENOMEM, RSDGC_EHIP, RSDGC_ETOOBIG = 0, -1, -2, -3, -4
+RSDGC_STATIC_WORKSPACE_BYTES = 64 << 20
 RSDGC_MAX_P = 7
 
 EXPORTS = [
     "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_set_work_feed", "rsdgc_plan_forget_workspace", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
-    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_apply_blocks", "rsdgc_plan_blocks", "rsdgc_compress_blocks",
+    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_static", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_apply_blocks", "rsdgc_plan_blocks", "rsdgc_compress_blocks",
     "rsdgc_decompress_blocks", "rsdgc_nsi", "rsdgc_decompress",
     "rsdgc_last_paths", "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
@@ -39,7 +40,8 @@ class RsdgcError(RuntimeError):
         lib = load()
         msg = lib.rsdgc_strerror(code).decode()
         hip = lib.rsdgc_last_hip_error().decode()
-        super().__init__(f"{where}: {msg} ({code})" + (f" [{hip}]" if code == RSDGC_EHIP and hip else ""))
+        super().__init__(f"{where}: {msg} ({code})" +
+                         (f" [{hip}]" if code in (RSDGC_EHIP, RSDGC_ETOOBIG) and hip else ""))
         self.code = code
 
 
@@ -87,6 +89,8 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_workspace_bytes.restype = ctypes.c_size_t
     lib.rsdgc_compress.argtypes = [vp] * 11
     lib.rsdgc_compress.restype = ctypes.c_int
+    lib.rsdgc_compress_static.argtypes = [vp] * 10
+    lib.rsdgc_compress_static.restype = ctypes.c_int
     lib.rsdgc_compress_momentum.argtypes = [vp, vp, vp, vp, ctypes.c_float] + [vp] * 9
     lib.rsdgc_compress_momentum.restype = ctypes.c_int
     lib.rsdgc_dynamic_ratios.argtypes = [vp, vp, f64, ctypes.POINTER(f64), vp, vp]
@@ -262,6 +266,14 @@ def rsdgc_compress(plan: Plan, grad, residual, residual_out, out_idx, out_val, o
                                  _ptr(out_val), _ptr(out_counts), _ptr(out_centre_idx),
                                  _ptr(out_centre_counts), _ptr(workspace), _stream(stream)),
            "rsdgc_compress")
+
+
+def rsdgc_compress_static(plan: Plan, grad, residual, residual_out, out_idx, out_val, out_counts,
+                          out_centre_idx=None, out_centre_counts=None, stream=None) -> None:
+    """rsdgc_compress with the library's built-in workspace (no device allocation)."""
+    _check(load().rsdgc_compress_static(plan.handle, _ptr(grad), _ptr(residual), _ptr(residual_out),
+                                        _ptr(out_idx), _ptr(out_val), _ptr(out_counts), _ptr(out_centre_idx),
+                                        _ptr(out_centre_counts), _stream(stream)), "rsdgc_compress_static")
 
 
 def rsdgc_compress_momentum(plan: Plan, grad, momentum, momentum_out, m: float, residual, residual_out,

@@ -242,6 +242,7 @@ struct rsdgc_plan_s {
     std::vector<unsigned char> table;   // host image of the uploaded tables
     // device-side bookkeeping
     uint64_t version = 1;               // bumped by set_ratios
+    uint64_t serial = 0;                // unique per plan of this process (never reused, unlike its address)
     const void *uploaded_ws = nullptr;
     uint64_t uploaded_version = 0;
     const void *acc_zero_ws = nullptr;  // workspace whose message accumulator is known to be all zero

@@ -41,6 +41,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "rsdgc_internal.h"
 
@@ -2633,6 +2634,61 @@ int rsdgc_compress(rsdgc_plan_t *plan, const float *grad, const float *residual,
                    void *stream) {
     return compress_impl(plan, grad, Momentum{}, residual, residual_out, out_idx, out_val, out_counts,
                          out_centre_idx, out_centre_counts, workspace, stream);
+}
+
+// Workspace of rsdgc_compress_static: one array per GPU, part of the library's code object, so
+// that the call needs no device allocation.  It lives as long as the process; every
+// rsdgc_compress_static call on a GPU uses that GPU's copy, so two of them must not overlap in
+// time on one GPU.  In host code the array's name is not a device address: the address is
+// asked for once per device (hipGetSymbolAddress) and only that pointer is handed to kernels
+// and copies.
+static __device__ __align__(256) unsigned char scratch[RSDGC_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct ScratchSlot {
+    void *ptr = nullptr;            // device address of `scratch` on this device
+    uint64_t owner_serial = 0;      // plan (and its version) whose tables the array holds now
+    uint64_t owner_version = 0;
+};
+ScratchSlot g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
+}  // namespace
+
+int rsdgc_compress_static(rsdgc_plan_t *plan, const float *grad, const float *residual,
+                          float *residual_out, uint32_t *out_idx, float *out_val, int32_t *out_counts,
+                          uint32_t *out_centre_idx, int32_t *out_centre_counts, void *stream) {
+    if (!plan || plan->blocks) return RSDGC_EINVAL;
+    if (plan->ws.total > static_cast<size_t>(RSDGC_STATIC_WORKSPACE_BYTES)) {
+        std::snprintf(g_hip_error, sizeof(g_hip_error),
+                      "rsdgc_compress_static: the plan needs %zu bytes of workspace, the built-in one has %zu",
+                      plan->ws.total, static_cast<size_t>(RSDGC_STATIC_WORKSPACE_BYTES));
+        return RSDGC_ETOOBIG;
+    }
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return RSDGC_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    ScratchSlot &slot = g_scratch[dev];
+    if (!slot.ptr) {                       // once per device, with that device current
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || !aligned256(p)) return hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+        slot.ptr = p;
+    }
+    // the array keeps what the last call left: when that was another plan (or other ratios), this
+    // plan's tables and its state between calls are laid down again; the per-call clears of
+    // rsdgc_compress take care of everything else
+    if (slot.owner_serial != plan->serial || slot.owner_version != plan->version) plan->uploaded_ws = nullptr;
+    const int rc = compress_impl(plan, grad, Momentum{}, residual, residual_out, out_idx, out_val,
+                                 out_counts, out_centre_idx, out_centre_counts, slot.ptr, stream);
+    if (rc == RSDGC_OK) {
+        slot.owner_serial = plan->serial;
+        slot.owner_version = plan->version;
+    } else {
+        slot.owner_serial = 0;
+    }
+    return rc;
 }
 
 int rsdgc_compress_momentum(rsdgc_plan_t *plan, const float *grad, const float *momentum,

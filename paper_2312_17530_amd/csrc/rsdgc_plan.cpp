@@ -2,6 +2,7 @@
 // No HIP call is made from this file (destroying a plan that still holds profiling
 // events releases them through rsdgc_profile_end).
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -321,6 +322,8 @@ static int make_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
     if ((total + kChunk - 1) / kChunk + n_layers > 0x7fffffffLL) return RSDGC_EINVAL;
     rsdgc_plan_s *plan = new (std::nothrow) rsdgc_plan_s;
     if (!plan) return RSDGC_ENOMEM;
+    static std::atomic<uint64_t> next_serial{1};
+    plan->serial = next_serial.fetch_add(1);
     try {
         plan->n_layers = n_layers;
         plan->alpha = alpha;
@@ -439,6 +442,7 @@ const char *rsdgc_strerror(int code) {
         case RSDGC_EINVAL: return "invalid argument";
         case RSDGC_ENOMEM: return "host allocation failed";
         case RSDGC_EHIP: return "HIP call failed";
+        case RSDGC_ETOOBIG: return "the plan's workspace exceeds the library's built-in one";
         default: return "unknown error code";
     }
 }
