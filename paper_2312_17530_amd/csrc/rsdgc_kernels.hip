@@ -200,14 +200,43 @@ __device__ __forceinline__ double uniform_f64(double x) {
 }
 
 // Eqs. 8-10 from the window sums sa = sum|w|, ss = sum w, sq = sum w^2 (n = p*p slots):
-//   mean = sa / n,  std = sqrt(n*sq - ss^2) / n,  NSI = alpha*mean + (1-alpha)*std.
-// n*sq - ss^2 is formed from two separately rounded products so that it is exactly 0 for a
-// constant window.  The square root is one v_rsq_f64 seed, one coupled Newton step and one
-// residual correction (about 1 ulp in double); the floor 1e-300 stands in for 0 and
-// vanishes when the score is rounded to float32.
-__device__ __forceinline__ double nsi_from_sums(double sa, double ss, double sq, double n,
-                                                double ca, double cb) {
-    double d = __dsub_rn(__dmul_rn(n, sq), __dmul_rn(ss, ss));
+//   mean = sa / n,  std = sqrt(d) / n  with  d = n*sq - ss^2 = n^2 * variance,
+//   NSI = alpha*mean + (1-alpha)*std = ca*sa + cb*sqrt(d).
+// d is formed from two separately rounded products.  That form cancels: its absolute error
+// is a few 1e-16 of n*sq, so the relative error of the standard deviation grows like
+// 1e-16 * (1 + mean^2 / variance).  A window whose d falls below kCancelFrac * n*sq
+// (|mean| beyond a thousand standard deviations: near-constant values on a large offset)
+// is therefore evaluated again the way Eq. 10 is printed -- window_ssd below -- and only the
+// others (relative error of the one-pass form below 3e-9) keep the one-pass value.
+constexpr double kCancelFrac = 1.0 / 1048576.0;
+
+__device__ __forceinline__ double var_n2_one_pass(double ss, double nsq) {
+    return __dsub_rn(nsq, __dmul_rn(ss, ss));
+}
+
+// Eq. 10 as printed, for the rare window where the one-pass form cancels: the sum over the
+// P x P window at `win` (LDS, row pitch `pitch`) of (w - m)^2, rows top to bottom, left to right.
+// Equal windows give equal bits wherever they lie, and a constant window gives exactly 0
+// (m = P*P*c / (P*P) is exact), which the ranking's tie rule relies on.  Loops are kept rolled:
+// this is cold code inside an unrolled loop.
+template <int P>
+__device__ __forceinline__ double window_ssd(const float *win, int pitch, double m) {
+    double acc = 0.0;
+#pragma unroll 1
+    for (int dx = 0; dx < P; ++dx) {
+#pragma unroll 1
+        for (int dy = 0; dy < P; ++dy) {
+            const double e = static_cast<double>(win[dx * pitch + dy]) - m;
+            acc += __dmul_rn(e, e);
+        }
+    }
+    return acc;
+}
+
+// ca*sa + cb*sqrt(d).  The square root is one v_rsq_f64 seed, one coupled Newton step and one
+// residual correction (about 1 ulp in double); the floor 1e-300 stands in for 0 and vanishes
+// when the score is rounded to float32.
+__device__ __forceinline__ double nsi_from_var(double sa, double d, double ca, double cb) {
     d = fmax(d, 1e-300);
     const double y = __builtin_amdgcn_rsq(d);
     double g = d * y, h = 0.5 * y;
@@ -331,8 +360,9 @@ struct NsiArgs {
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
 // down the 16 rows of one column, keeping per-row horizontal sums of |w|, w and w^2
 // (double) for the last P rows in registers.  The variance is formed as
-// (P^2 * sum w^2 - (sum w)^2) / P^4 in double, which is exactly 0 for a constant window
-// and keeps equal windows at equal scores wherever they lie.
+// (P^2 * sum w^2 - (sum w)^2) / P^4 in double, or -- where that form cancels -- from the
+// tile again as Eq. 10 prints it; either way equal windows get equal scores wherever they
+// lie and a constant window gets a variance of exactly 0.
 //
 // A workgroup takes tiles b, b + W, ... of the launch (W workgroups, laid out so that each XCD
 // gets one contiguous part of every stretch of W tiles: neighbouring tiles share halo rows in
@@ -587,6 +617,10 @@ void k_nsi(const NsiArgs a) {
                         ss += hs_s[(o + j) % P][c];
                         sq += hs_q[(o + j) % P][c];
                     }
+                    const double nsq = __dmul_rn(n, sq);
+                    double d = var_n2_one_pass(ss, nsq);
+                    // the one-pass variance cancelled (rare; never for P = 1, where it is 0 by definition)
+                    const bool cancels = P > 1 && d < kCancelFrac * nsq;
                     bool exact = true;
                     if (PRETEST) {
                         // Only the centres that reach the bound are wanted, and 99.5 % do not.  A test
@@ -594,12 +628,16 @@ void k_nsi(const NsiArgs a) {
                         // and the last float32 bit of the bound, rules most of them out (a wave skips
                         // the rest when all its lanes are ruled out):
                         //   NSI >= B  <=>  cb*sqrt(d) >= B - ca*sa  <=>  rest <= 0  or  cb^2 * d >= rest^2
-                        const double d = __dsub_rn(__dmul_rn(n, sq), __dmul_rn(ss, ss));
                         const double rest = bound_lo - ca * sa;
-                        exact = rest <= 0.0 || cb2 * d >= rest * rest * (1.0 - 1e-9);
+                        exact = cancels || rest <= 0.0 || cb2 * d >= rest * rest * (1.0 - 1e-9);
                     }
                     out[c] = 0.f;
-                    if (exact) out[c] = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
+                    if (exact) {
+                        if (cancels)
+                            d = __dmul_rn(n, window_ssd<P>(&tile[(row_base + o) * PITCH + PADL + c0 + c - H],
+                                                           PITCH, ss / n));
+                        out[c] = static_cast<float>(nsi_from_var(sa, d, ca, cb));
+                    }
                     key[c] = __float_as_uint(out[c]) & 0x7fffffffu;
                     reaches = reaches || (exact && key[c] >= hint_key);
                 }
@@ -1984,7 +2022,11 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
                         ss += w;
                         sq = fma(w, w, sq);
                     }
-                const float score = static_cast<float>(nsi_from_sums(sa, ss, sq, n, ca, cb));
+                const double nsq = __dmul_rn(n, sq);
+                double d = var_n2_one_pass(ss, nsq);
+                if (P > 1 && d < kCancelFrac * nsq)          // the one-pass variance cancelled (rare)
+                    d = __dmul_rn(n, window_ssd<P>(&tile[(br * P) * TC + bc * P], TC, ss / n));
+                const float score = static_cast<float>(nsi_from_var(sa, d, ca, cb));
                 score_map[I.elem_off + static_cast<size_t>(bx) * BC + by] = score;
                 atomicAdd(&lhist[(__float_as_uint(score) & 0x7fffffffu) >> 19], 1u);
             }

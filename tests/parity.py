@@ -1,10 +1,8 @@
 """GPU-versus-oracle comparison rule for one layer of one iteration.
 
 Scores: the GPU evaluates the window statistics in double like the oracle but in a
-different order and with (P^2*sum w^2 - (sum w)^2)/P^4 for the variance, so float32
-scores may differ in the last place.  The tolerance is EPS = 1e-5 relative plus the
-rounding floor of the inputs (a window of values known to 2^-24 relative cannot
-resolve a standard deviation below that fraction of their magnitude).
+different order, so float32 scores may differ in the last place.  The tolerance is
+EPS = 1e-5 relative and nothing else (two zeros count as equal).
 
 Selection: let tau be the oracle's k-th largest score, BAND the centres whose oracle
 score is within EPS*tau of tau and HIGH the centres above the band.  The GPU must
@@ -19,19 +17,13 @@ import numpy as np
 from scipy import ndimage
 
 EPS = 1e-5
-FLOOR = 4.0 * 2.0 ** -24
 
 
-def nsi_close(gpu: np.ndarray, ref: np.ndarray, v: np.ndarray, p: int):
-    """Boolean map of scores within tolerance."""
+def nsi_close(gpu: np.ndarray, ref: np.ndarray):
+    """Boolean map of scores within EPS relative of each other."""
     a = gpu.astype(np.float64)
     b = ref.astype(np.float64)
-    mean_abs = ndimage.uniform_filter(np.abs(v.astype(np.float64)), size=p, mode="constant", cval=0.0)
-    # the library's box filter keeps running sums: over an all-zero window behind non-zero values it
-    # can return -1e-19 instead of 0, and a negative tolerance would reject 0 == 0
-    mean_abs = np.maximum(mean_abs, 0.0)
-    tol = EPS * np.maximum(np.abs(a), np.abs(b)) + FLOOR * mean_abs
-    return np.abs(a - b) <= tol
+    return np.abs(a - b) <= EPS * np.maximum(np.abs(a), np.abs(b))
 
 
 def dilate_np(centres: np.ndarray, R: int, C: int, p: int) -> np.ndarray:

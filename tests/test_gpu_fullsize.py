@@ -2,12 +2,15 @@
 the VGG-19-shaped gradient (139,740,864 elements, 19 layers, p = 3, dynamic ratios) and the
 25088 x 4096 stress layer (p = 5, Student-t noise, 0.1 % kept).
 
-Iteration 0 is compared with the complete CPU oracle (full sort included), layer by layer.
-Later iterations, which carry the residual, are checked through properties that hold at any
-size: Eq. 11 counts, ascending indices, values and residual bit-equal to v = r + g, kept set
-== dilation of the centres, and the centres being exactly the k best composite keys of the
-library's own score map."""
+Every iteration -- the first from a zero residual and the carried ones (Eq. 12) -- is compared
+with the complete CPU oracle (two-pass statistics, full sort), layer by layer, from identical
+state: scores to 1e-5 relative, then the whole parity rule of tests/parity.py.  The oracle takes
+about 20 s per iteration at these sizes (its layers run in a few threads here; it is the same
+single-threaded C code per layer), which is what bounds the number of iterations: three of the
+VGG-19 workload's ten, all five of the stress layer's.  All ten iterations of the VGG-19 recipe
+run against the oracle on matrices clipped to 256 x 1152."""
 import functools
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -19,42 +22,26 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 
-def _check_properties(tag, shape, p, k, v, nsi_gpu, idx, val, centres, n_centres, r_new):
-    R, C = shape
-    G = R * C
-    v = v.reshape(-1)
-    assert n_centres == k and len(centres) == k, tag
-    assert np.all(np.diff(centres.astype(np.int64)) > 0), tag
-    # the selected centres are the k largest (score, lower index first) of the library's own map
-    s = nsi_gpu.reshape(-1)
-    sel = np.zeros(G, dtype=bool)
-    sel[centres] = True
-    if 0 < k < G:
-        lo_sel = s[sel].min()
-        hi_unsel = s[~sel].max()
-        assert lo_sel >= hi_unsel, f"{tag}: an unselected centre outranks a selected one"
-        if lo_sel == hi_unsel:      # ties at the threshold: lower indices must have won
-            tie_sel = np.flatnonzero(sel & (s == lo_sel))
-            tie_unsel = np.flatnonzero(~sel & (s == lo_sel))
-            assert tie_sel.max() < tie_unsel.min(), f"{tag}: tie not resolved towards the lower index"
-    mask = parity.dilate_np(centres, R, C, p) if k else np.zeros(G, dtype=bool)
-    want_idx = np.flatnonzero(mask).astype(np.uint32)
-    assert np.array_equal(idx, want_idx), f"{tag}: kept set is not the dilation of the centres"
-    assert np.array_equal(val.view(np.uint32), v[want_idx].view(np.uint32)), tag
-    want_r = v.copy()
-    want_r[want_idx] = 0.0
-    assert np.array_equal(r_new.reshape(-1).view(np.uint32), want_r.view(np.uint32)), f"{tag}: residual"
+def _oracle_layers(w, grads, resid):
+    """oracle.compress_layer for every layer; large layers first, a few at a time (the C code
+    releases the interpreter lock)."""
+    order = sorted(range(w.n_layers), key=lambda l: -grads[l].size)
+    with ThreadPoolExecutor(max_workers=6) as pool:
+        futs = {l: pool.submit(oracle.compress_layer, grads[l], resid[l], w.p, w.alpha, w.ratios[l])
+                for l in order}
+        return [futs[l].result() for l in range(w.n_layers)]
 
 
-def _run(config_index, extra_iterations):
+def _run(w, iterations, expect_candidate_path=True):
+    """Runs `iterations` carried iterations on the GPU and on the oracle from identical state;
+    returns the number of layer-iterations whose output equals the oracle's byte for byte."""
     import torch
     from paper_2312_17530_amd import binding
     from paper_2312_17530_amd.session import Session
-    w = synth.config(config_index)
     sess = Session(w.shapes, w.p, w.alpha, w.ratios)
     resid = [np.zeros(sh, dtype=np.float32) for sh in w.shapes]
     n_exact = 0
-    for t in range(1 + extra_iterations):
+    for t in range(iterations):
         grads = synth.gradients(w, t)
         sess.set_grad(grads)
         sess.set_residual(resid)
@@ -64,30 +51,36 @@ def _run(config_index, extra_iterations):
         res = sess.results()
         gpu_r = sess.unpack(sess.residual)
         paths = binding.rsdgc_last_paths(sess.plan, sess.workspace)
+        print(f"oracle {w.name} t={t}", flush=True)          # progress for long runs
+        ref = _oracle_layers(w, grads, resid)
         for l, sh in enumerate(w.shapes):
             tag = f"{w.name}[t={t},l={l},{sh},path={paths[l]}]"
-            print("checking", tag, flush=True)      # progress for long runs
+            print("checking", tag, flush=True)
             gi, gv, gc, gn = res[l]
-            k = sess.plan.layer_k(l)
-            if t == 0:
-                o = oracle.compress_layer(grads[l], resid[l], w.p, w.alpha, w.ratios[l])
-                assert o.k == k, tag
-                assert parity.nsi_close(gpu_nsi[l], o.nsi, o.v, w.p).all(), f"{tag}: scores"
-                n_exact += int(parity.check_layer(tag, sh, w.p, o.k, o.tau, o.nsi, o.centres, o.idx,
-                                                  o.val, o.r_new, o.v, gi, gv, gc, gn, gpu_r[l]))
-            else:
-                v = resid[l] + grads[l]                     # float32 add (numpy)
-                _check_properties(tag, sh, w.p, k, v, gpu_nsi[l], gi, gv, gc, gn, gpu_r[l])
-        resid = gpu_r                                        # carry the residual
-        if t == 0:
-            # the large layers really went through the candidate path
-            assert 0 in paths or w.n_layers == 1 and paths[0] in (0, 1)
-    return w, n_exact
+            o = ref[l]
+            assert o.k == sess.plan.layer_k(l), tag
+            assert parity.nsi_close(gpu_nsi[l], o.nsi).all(), f"{tag}: scores"
+            n_exact += int(parity.check_layer(tag, sh, w.p, o.k, o.tau, o.nsi, o.centres, o.idx,
+                                              o.val, o.r_new, o.v, gi, gv, gc, gn, gpu_r[l]))
+        # carry the oracle's residual (identical to the GPU's unless a tolerance band was used)
+        resid = [o.r_new for o in ref]
+        del ref, gpu_nsi, res, gpu_r
+        if t == 0 and expect_candidate_path:
+            assert 0 in paths, "the large layers should have taken the candidate path"
+    return n_exact
 
 
-def test_vgg19_full_size_against_oracle_then_two_carried_iterations():
-    w, n_exact = _run(3, extra_iterations=2)
-    assert n_exact >= w.n_layers - 2
+def test_vgg19_full_size_three_carried_iterations_against_oracle():
+    w = synth.config(3)
+    n_exact = _run(w, iterations=3)
+    assert n_exact >= 3 * w.n_layers - 2
+
+
+def test_vgg19_recipe_clipped_all_ten_carried_iterations_against_oracle():
+    w = synth.scaled_down(synth.config(3), 256, 1152)
+    assert w.iterations == 10
+    n_exact = _run(w, iterations=w.iterations, expect_candidate_path=False)
+    assert n_exact >= 10 * w.n_layers - 2
 
 
 def test_vgg19_full_size_in_place_equals_two_arenas():
@@ -243,9 +236,11 @@ def test_vgg19_full_size_block_reading_against_oracle():
     assert n_exact >= w.n_layers - 2
 
 
-def test_fc6_stress_p5_student_t_against_oracle_then_one_carried_iteration():
-    w, n_exact = _run(4, extra_iterations=1)
-    assert n_exact == 1
+def test_fc6_stress_p5_student_t_all_five_carried_iterations_against_oracle():
+    w = synth.config(4)
+    assert w.iterations == 5
+    n_exact = _run(w, iterations=w.iterations)
+    assert n_exact >= 4
 
 
 _HUGE = ((16512, 8192), 3, 0.5, 0.01)      # shape, p, alpha, keep ratio
