@@ -28,20 +28,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 METRIC = "gradient elements compressed/sec (full-model, 1 GPU) and % of HBM peak"
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); the summaries are
-# in profiles/.  Keyed by (workload name, stage, residual update).  None = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    ("vgg19_45c", "capture", "two_arenas"): 1.7378e9,          # profiles/hbm_traffic_vgg19.md, k_nsi<3, 2, false, true>
-    ("fc6_25088x4096_t3", "capture", "two_arenas"): 1.2933e9,  # profiles/hbm_traffic_fc6_p5.md, k_nsi<5, 2, false, true>
-    ("vgg19_45c", "capture", "momentum"): 2.8207e9,            # profiles/hbm_traffic_vgg19_momentum.md, k_nsi<3, 2, true, true>
-}
-# the same counters summed over all kernels of one rsdgc_compress call
-MEASURED_PATH_TRAFFIC_BYTES = {
-    ("vgg19_45c", "two_arenas"): 2.1384e9,
-    ("fc6_25088x4096_t3", "two_arenas"): 1.3583e9,
-    ("vgg19_45c", "momentum"): 3.2850e9,
-}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, scaled by a copy
+# kernel of known size) are not typed in here: they are read from the summaries under profiles/,
+# which carry them on lines of the form
+#     bench-traffic: workload=<name> variant=<two_arenas|in_place|momentum> scope=<stage name|path> bytes=<float>
+# so that a summary that was not refreshed after a kernel changed can be seen (and replaced) in
+# one place.  No matching line = null in the JSON.
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def measured_traffic(workload: str, variant: str, scope: str):
+    import glob
+    import re
+    pat = re.compile(r"bench-traffic:\s+workload=(\S+)\s+variant=(\S+)\s+scope=(\S+)\s+bytes=(\S+)")
+    for path in sorted(glob.glob(os.path.join(PROFILES, "hbm_traffic_*.md"))):
+        for line in open(path):
+            m = pat.search(line)
+            if m and (m.group(1), m.group(2), m.group(3)) == (workload, variant, scope):
+                return float(m.group(4)), os.path.relpath(path, ROOT)
+    return None, None
 
 
 def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems: int,
@@ -63,9 +68,44 @@ def stage_algorithmic_bytes(stage: str, n_elems: int, n_pairs: int, n_cand_elems
     return 0.0
 
 
-def cpu_baseline(workload, grads, budget_elems: int = 150_000_000):
-    """Times the CPU oracle as it stands on a bounded sample of the same workload."""
+def _cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def _oracle_layer_all_cores(pool, workers, g, r, p, alpha, rho):
+    """One layer through the oracle's own step functions, its score map cut into row bands that
+    run side by side (a band plus a halo of (p-1)/2 rows gives the same windows, hence the same
+    arithmetic, as the whole matrix); ranking, dilation, emit and residual as they stand."""
     import oracle
+    R, C = g.shape
+    h = (p - 1) // 2
+    v = oracle.accumulate(r, g)
+    bands = max(1, min(workers, R // 64))
+    edges = [R * b // bands for b in range(bands + 1)]
+
+    def band(b):
+        a0, a1 = edges[b], edges[b + 1]
+        lo, hi = max(0, a0 - h), min(R, a1 + h)
+        return oracle.nsi(v[lo:hi], p, alpha)[a0 - lo:a0 - lo + (a1 - a0)]
+    nsi_map = np.concatenate(list(pool.map(band, range(bands))), axis=0)
+    k = oracle.keep_count(R * C, p, rho)
+    centres, _ = oracle.select(nsi_map, k)
+    mask = oracle.dilate(centres, R, C, p)
+    idx, val = oracle.emit(v, mask)
+    return idx, val, oracle.residual(v, mask)
+
+
+def cpu_baseline(workload, grads, budget_elems: int = 150_000_000):
+    """Times the CPU oracle as it stands on a bounded sample of the same workload: once on one
+    thread (`value`), once with its step functions spread over the host's cores (`all_cores`)."""
+    import oracle
+    from concurrent.futures import ThreadPoolExecutor
     order = sorted(range(workload.n_layers), key=lambda l: grads[l].size)
     chosen, total = [], 0
     for l in order:                      # smallest layers first, until the budget is reached
@@ -79,9 +119,25 @@ def cpu_baseline(workload, grads, budget_elems: int = 150_000_000):
         g = grads[l]
         oracle.compress_layer(g, np.zeros_like(g), workload.p, workload.alpha, workload.ratios[l])
     dt = time.perf_counter() - t0
+    # all cores: layers side by side (largest first), each layer's score map in row bands; a GPU machine
+    # gives one GPU's job 16 cores whatever os.cpu_count() says
+    host_cpus = os.cpu_count() or 1
+    workers = max(1, min(host_cpus, 16))
+    t1 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=workers) as bands, ThreadPoolExecutor(max_workers=workers) as layers:
+        futs = [layers.submit(_oracle_layer_all_cores, bands, workers, grads[l], np.zeros_like(grads[l]),
+                              workload.p, workload.alpha, workload.ratios[l]) for l in reversed(chosen)]
+        for f in futs:
+            f.result()
+    dt_all = time.perf_counter() - t1
+    sample = (f"{len(chosen)} of {workload.n_layers} layers of {workload.name} "
+              f"({total} elements, one iteration, zero residual)")
     return {"value": total / dt, "unit": "elements/s", "cores": 1, "kind": "oracle",
-            "sample": f"{len(chosen)} of {workload.n_layers} layers of {workload.name} "
-                      f"({total} elements, one iteration, zero residual), {dt:.1f} s single thread"}
+            "sample": f"{sample}, {dt:.1f} s single thread",
+            "all_cores": {"value": total / dt_all, "unit": "elements/s", "cores": workers,
+                          "sample": f"{sample}, {dt_all:.1f} s; layers side by side, score maps in row bands, "
+                                    "ranking (full sort) one thread per layer"},
+            "host_cpu_count": host_cpus, "cpu_model": _cpu_model()}
 
 
 def bench_blocks(args, w, grads) -> int:
@@ -100,8 +156,6 @@ def bench_blocks(args, w, grads) -> int:
         sess.compress(stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    # the dominant kernel (block scores + v) alone, with events on the same stream
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     counts = sess.out_counts.cpu().numpy()
     n_blocks = int(counts.sum())
     alg = 12.0 * G + 4.0 * G / (w.p * w.p)          # read g, read r, write v; one score per block
@@ -117,7 +171,17 @@ def bench_blocks(args, w, grads) -> int:
                      "frac": alg / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes": alg},
     }
-    del ev
+    if not args.no_cpu_baseline:
+        import oracle
+        l = max(range(w.n_layers), key=lambda i: 0 if grads[i].size > 20_000_000 else grads[i].size)
+        oracle.build()
+        t0 = time.perf_counter()
+        oracle.compress_layer_blocks(grads[l], np.zeros_like(grads[l]), w.p, w.alpha, w.ratios[l])
+        dtc = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": grads[l].size / dtc, "unit": "elements/s", "cores": 1, "kind": "oracle",
+                               "sample": f"layer {l} of {w.name} ({grads[l].size} elements, block reading, one "
+                                         f"iteration, zero residual), {dtc:.1f} s single thread",
+                               "host_cpu_count": os.cpu_count(), "cpu_model": _cpu_model()}
     print(json.dumps(out), flush=True)
     return 0
 
@@ -145,6 +209,9 @@ def main() -> int:
                          "prints its own JSON line and nothing else")
     ap.add_argument("--full-map", action="store_true",
                     help="force the full-score-map ranking path for every layer")
+    ap.add_argument("--grad-cycle", type=int, default=4,
+                    help="number of different seeded gradients (iterations 0 .. N-1 of the workload's recipe) "
+                         "kept in HBM and fed in turn, one per step; 1 = the same gradient every step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the compressor is per-rank and has no "
@@ -168,6 +235,20 @@ def main() -> int:
                    path=binding.RSDGC_PATH_FULL_MAP if args.full_map else binding.RSDGC_PATH_AUTO,
                    in_place=args.in_place, momentum=args.momentum)
     sess.set_grad(grads)
+    # the gradients of the following iterations, resident in HBM like the first: a training step
+    # brings a new gradient every time, and the residual (Eq. 12) then grows like a random walk
+    # instead of in proportion to the step count
+    arenas = [sess.grad]
+    for t in range(1, max(1, args.grad_cycle)):
+        arenas.append(torch.empty_like(sess.grad))
+        sess.pack(synth.gradients(w, t), arenas[-1])
+    n_calls = 0
+
+    def step():
+        nonlocal n_calls
+        sess.grad = arenas[n_calls % len(arenas)]
+        n_calls += 1
+        sess.compress(stream)
     G = w.total_elems
     stream = torch.cuda.current_stream()
 
@@ -180,14 +261,14 @@ def main() -> int:
         del src, dst
 
     for _ in range(args.warmup):
-        sess.compress(stream)
+        step()
     torch.cuda.synchronize()
 
     # timed region: exactly K steps, nothing but the compress calls between the two syncs
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        sess.compress(stream)
+        step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -199,7 +280,7 @@ def main() -> int:
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         for _ in range(args.steps):
-            sess.compress(stream)
+            step()
         torch.cuda.synchronize()
         dt_events = time.perf_counter() - t1
         stages, n_rec = binding.rsdgc_profile_end(sess.plan)
@@ -251,23 +332,22 @@ def main() -> int:
     roofline = None
     if stages:
         paths = binding.rsdgc_last_paths(sess.plan, sess.workspace)
-        n_cand = sum(r * c for (r, c), pth in zip(w.shapes, paths) if pth == 0)
+        n_cand = sum(r * c for (r, c), pth in zip(w.shapes, paths) if pth in (0, 3))   # candidate path
         dom = max(("first_pass", "capture", "emit"), key=lambda s: stages.get(s, 0.0))
         dur_s = stages[dom] * 1e-3
+        variant = "in_place" if args.in_place else "momentum" if args.momentum is not None else "two_arenas"
+        traffic, traffic_src = measured_traffic(w.name, variant, dom)
         alg = stage_algorithmic_bytes(dom, G, n_pairs, n_cand, args.in_place, args.momentum is not None)
         per_elem = 20.0 if args.momentum is not None else 12.0     # whole path: read g, (u,) r; write (u,) r
         achieved = alg / dur_s / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(
-                        (w.name, dom, "in_place" if args.in_place else
-                         "momentum" if args.momentum is not None else "two_arenas")),
+                    "traffic": traffic, "traffic_source": traffic_src,
                     "algorithmic_bytes": alg, "avg_ms": stages[dom],
                     "elements_on_candidate_path": n_cand,
                     "path_algorithmic_bytes": per_elem * G + 8.0 * n_pairs,
                     "path_frac": (per_elem * G + 8.0 * n_pairs) / (dt / args.steps) / 1e9 / HBM_PEAK_GBS}
-        variant = "in_place" if args.in_place else "momentum" if args.momentum is not None else "two_arenas"
-        path_traffic = MEASURED_PATH_TRAFFIC_BYTES.get((w.name, variant))
+        path_traffic, _ = measured_traffic(w.name, variant, "path")
         roofline["path_traffic"] = path_traffic      # counted bytes of all kernels of one call (None = not measured)
         roofline["path_moved_frac"] = (path_traffic / (dt / args.steps) / 1e9 / HBM_PEAK_GBS) if path_traffic else None
 
@@ -279,7 +359,8 @@ def main() -> int:
                    "alpha": w.alpha, "mean_keep_ratio": float(np.average(w.ratios, weights=[r * c for r, c in w.shapes])),
                    "pairs_emitted_last_step": n_pairs, "centre_lists": bool(args.centres),
                    "ranking_path": "full_map" if args.full_map else "auto",
-                   "residual": "carried across steps",
+                   "residual": "carried across steps", "gradients_cycled": len(arenas),
+                   "bounds_predicted_last_step": sum(1 for pth in paths if pth == 3) if stages else None,
                    "residual_update": "in_place" if args.in_place else "two_arenas",
                    "momentum": args.momentum},
         "roofline": roofline,

@@ -14,18 +14,29 @@ constexpr int kTileCols = 256;       // NSI tile: output columns per workgroup
 constexpr int kChunk = 8192;         // elements per workgroup in the 1-D passes
 constexpr int kHistBins = 4096;      // widest radix digit (12 bits)
 constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements
-constexpr int kSlotCap = 256;        // candidate centres one tile can record
-constexpr int kSlotGroup = 16;       // tile slots per work item of the candidate passes (4 per wave)
-constexpr int kCandBins = 256;       // 12-bit score buckets above the bound that a capture workgroup counts
+constexpr int kSlotCap = 256;        // candidate centres one tile of a large layer can record ...
+constexpr int kSlotCapMax = 512;     // ... or twice that where the layer's keep ratio asks for it
+constexpr int kSlotGroup = 16;       // tile slots per work item of the candidate passes (one per wave)
+constexpr int kFineShift = 13;       // candidate path: the first ranking digit counts score bits in steps of 2^13
+constexpr int kFineBins = 1024;      // ... relative to the candidate bound: 1024 bins = one binade above it
+constexpr int kLevel1Bits = 11;      // second ranking digit (both paths)
+constexpr int kLevel1Bins = 1 << kLevel1Bits;
+constexpr int kCoarseShift = 19;     // full-map path: the first digit is the top 12 bits of the 31-bit score
 constexpr int kListMin = 8192;       // smallest threshold-bucket list of a layer (entries)
-constexpr int kList2Cap = 2048;      // keys sharing the first two digits that a layer can stage
 constexpr int kListDiv = 32;         // ... or 1/32 of the layer, whichever is larger
 constexpr int kCountChunks = 16;     // chunks per workgroup of the count pass
 constexpr int kChunkGroup = 64;      // chunks per group in the two-level chunk prefix
 constexpr int kListShards = 16;      // a layer's threshold-bucket list is filled through this many counters
 constexpr int kListCntStride = 32;   // uint32 between two of them (one 128-byte line each)
-constexpr uint32_t kPenaltyCalls = 8;  // calls a large layer spends on the full map after its candidate bound failed
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
+// Candidate bound predicted from the thresholds of the two calls before, on a log2 scale: used
+// while the threshold moved by at most kTrendMaxLog2 between those calls.
+constexpr float kTrendMaxLog2 = 0.14f;         // a factor of 1.10 per call
+constexpr float kMarginInitLog2 = 0.02f;       // safety margin below the lowest threshold expected (1.4 %)
+constexpr float kMarginMaxLog2 = 0.25f;        // it doubles after every failed bound, up to this
+constexpr uint32_t kCooldownCalls = 4;         // calls without a predicted bound after a failed one
+constexpr int kSamplingCalls = 16;             // first calls with a workspace: a layer without a predicted bound
+                                               // takes one sampled from the call's own scores (later: the full map)
 
 // Tile of the block-score kernel (block reading): kBlockTileRows block rows by
 // block_tile_cols(p) block columns, i.e. 8p x (8 .. 256)p elements.
@@ -60,6 +71,8 @@ struct LayerDev {
     int64_t elem_off;    // offset of the layer in the g / r / NSI arenas (elements)
     int64_t out_off;     // first pair of the layer in out_idx / out_val
     int64_t centre_off;  // first entry of the layer in out_centre_idx
+    uint64_t list_off;   // first entry of the layer's threshold-bucket list
+    uint64_t slot_off;   // first entry of the layer's tile slots (large layers)
     uint32_t R, C, G, k;
     uint32_t p, tiles_x, tile_begin, n_tiles;   // tile_begin: first tile inside its p-group launch
     uint32_t chunk_begin, n_chunks, cap, tile_begin_all;  // tile_begin_all: first tile over all layers
@@ -68,25 +81,34 @@ struct LayerDev {
     uint32_t n_groups;      // ceil(n_tiles / kSlotGroup)
     uint32_t hint_target;   // sampled scores wanted at or above the candidate bound
     uint32_t n_sampled;     // sampled tiles of the layer
-    uint32_t list_off;      // first entry of the layer's threshold-bucket list
-    uint32_t list_cap;      // its capacity
+    uint32_t list_cap;      // capacity of the threshold-bucket list
     uint32_t list_shards;   // shards the list is split into (each list_cap / list_shards entries, own counter)
+    uint32_t slot_cap;      // entries per tile slot (kSlotCap or kSlotCapMax)
 };
-static_assert(sizeof(LayerDev) == 104, "LayerDev layout");
+static_assert(sizeof(LayerDev) == 120, "LayerDev layout");
 
-// Per-layer selection state (40 bytes), lives in the workspace.
+// Per-layer selection state (40 bytes), lives in the workspace, rewritten by every call.
 struct SelState {
     unsigned long long T;   // threshold on the composite key (score bits << 32 | ~index)
     uint32_t k_rem;         // centres still to take inside the current bucket
     uint32_t done;          // threshold is final
     uint32_t mode;          // LayerMode
-    uint32_t hint_key;      // candidate bound (score bits), candidate path only
-    uint32_t overflow;      // candidate path: a tile slot or the histogram window overflowed
-    uint32_t n_centres;     // centres selected (only counted when centre lists are requested)
-    uint32_t n_pairs;       // pairs emitted
-    uint32_t pad_;
+    uint32_t hint_key;      // candidate bound (score bits), candidate path only; 0: still to come from the sample
+    uint32_t overflow;      // candidate path: a tile slot overflowed
+    uint32_t lo;            // first ranking digit resolved: the k-th score lies in [lo, lo + 2^span)
+    uint32_t span;
+    uint32_t predicted;     // 1: the candidate bound was predicted from earlier calls, not sampled
 };
 static_assert(sizeof(SelState) == 40, "SelState layout");
+
+// What a large layer remembers from one call to the next (uploaded as zeros with the tables).
+struct PredState {
+    uint32_t tau1;          // score bits of the last call's threshold (0: none yet)
+    uint32_t tau2;          // ... and of the call before it
+    float margin;           // safety margin below the predicted threshold, in log2 units (0: kMarginInitLog2)
+    uint32_t cooldown;      // calls left that take the sampled bound (after a failed bound)
+};
+static_assert(sizeof(PredState) == 16, "PredState layout");
 
 // State of the cross-layer ranking of |w| (rsdgc_dynamic_ratios).
 struct DynState {
@@ -168,28 +190,29 @@ struct WsLayout {
     size_t map_chunks = 0;   // ChunkEntry[]: chunks of the other layers that select something
     size_t map_tiles = 0;    // SampleEntry[]: tiles of those layers
     size_t count_groups = 0; // CountGroup[n_count_groups]
-    size_t penalty = 0;      // uint32[n_layers]  uploaded as zeros, then kept by the kernels: calls left on the full map
+    size_t pred = 0;         // PredState[n_layers]  uploaded as zeros, then kept by the kernels from call to call
     size_t table_bytes = 0;  // bytes uploaded from the host
     size_t state = 0;        // SelState[n_layers], rewritten at the start of every compress
+    size_t flags = 0;        // uint32[64]  [0]: some large layer is ranked on the full map in this call (set at the
+                             //             start of every compress, raised by the kernels that send a layer there)
     // cleared at the start of every compress
     size_t zero_begin = 0;
-    size_t hist = 0;         // uint32[n_layers][kHistBins]
+    size_t hist = 0;         // uint32[n_layers][kHistBins]  first ranking digit
+    size_t hist_s = 0;       // uint32[n_layers][kHistBins]  sampled scores of the large layers (coarse digit)
+    size_t hist1 = 0;        // uint32[n_layers][kLevel1Bins]  second ranking digit
     size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk
     size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk
     size_t group_cnt = 0;    // uint32[n_chunk_groups]  kept elements per chunk group
     size_t group_ccnt = 0;   // uint32[n_chunk_groups]  selected centres per chunk group
     size_t list_cnt = 0;     // uint32[n_layers][kListShards][kListCntStride]  keys gathered per list shard
-    size_t list2_cnt = 0;    // uint32[n_layers]  of those, keys that also share the second digit
     size_t feed = 0;         // uint32[16][8][32]  work-feed counters of the NSI launches
-    size_t flags = 0;        // uint32[64]  [0]: some large layer fell back to the full map
     size_t mask = 0;         // uint32[total_elems / 32]  kept-element bitmask
     size_t cmask = 0;        // uint32[total_elems / 32]  selected-centre bitmask
     size_t zero_end = 0;
     // not cleared
     size_t slot_cnt = 0;     // uint32[n_tiles_all]  candidates recorded per tile
-    size_t slot_ent = 0;     // uint64[n_tiles_all][kSlotCap]  their composite keys
+    size_t slot_ent = 0;     // uint64[sum over large layers of n_tiles * slot_cap]  their composite keys
     size_t list_ent = 0;     // uint64[sum list_cap]  composite keys of each layer's threshold bucket
-    size_t list2_ent = 0;    // uint64[n_layers][kList2Cap]  keys sharing the first two digits
     size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
     size_t dyn = 0;          // scratch of rsdgc_dynamic_ratios: DynState, uint64[kHistBins], uint32[2 * n_layers]
     size_t acc = 0;          // float[total_elems]  sum of the nodes' messages (rsdgc_apply); all zero between calls
@@ -244,6 +267,7 @@ struct rsdgc_plan_s {
     uint64_t version = 1;               // bumped by set_ratios
     uint64_t serial = 0;                // unique per plan of this process (never reused, unlike its address)
     const void *uploaded_ws = nullptr;
+    int calls_since_upload = 0;         // compress calls since the tables went to uploaded_ws (counted up to kSamplingCalls)
     uint64_t uploaded_version = 0;
     const void *acc_zero_ws = nullptr;  // workspace whose message accumulator is known to be all zero
     // block reading (non-overlapping p x p neighbourhoods): this plan describes the element

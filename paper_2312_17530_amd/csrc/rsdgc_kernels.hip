@@ -1,19 +1,25 @@
 // HIP kernels (gfx950, wave64) and the device-facing entry points of the C ABI.
 //
 // Pipeline of one rsdgc_compress call, all layers per launch:
-//   clear      zero histograms, bitmasks, counters, flags; per-layer state
-//   first pass NSI (Eqs. 6-10) on one tile in 16 .. 64 of the large layers -> score histogram;
-//              in the same launch every tile of the other layers: v = r + g (Eq. 12), NSI
-//              map and exact 12-bit histogram
-//   hint       per large layer: a score bound with about 2 k_l centres expected above it
-//   capture    v = r + g and NSI for every element of the large layers; centres whose score
-//              reaches the bound are recorded per tile (no score map); with a second
-//              residual arena v is stored there as it is formed
-//   validate   a layer whose bound caught fewer than k_l centres, or overfilled a tile,
-//              falls back to the full map (a flag tells the fallback kernels there is work)
-//   select     radix select of the k_l-th largest composite key per layer (Algorithm 1's
-//              ranking; Eq. 11's k_l), most significant digit first: find, gather the
-//              threshold bucket, find, filter, finish
+//   begin      zero histograms, bitmasks, counters, flags; per-layer state; for every large layer
+//              the candidate bound predicted from the thresholds of the two calls before, if
+//              they moved little
+//   first pass every tile of the layers that are ranked on the full score map: v = r + g (Eq. 12),
+//              NSI (Eqs. 6-10), score map, exact 12-bit histogram; in the same launch one tile in
+//              16 .. 64 of the large layers that have no predicted bound (first calls, after a
+//              failure): their score histogram gives a bound with about 2 k_l centres expected
+//              above it (computed by the workgroup that finishes last)
+//   capture    the main pass: v = r + g and NSI for every element of the large layers; centres
+//              whose score reaches the bound are recorded per tile (no score map) and counted in
+//              fine bins above the bound; with a second residual arena v is stored there as it
+//              is formed
+//   find0      first ranking digit of every layer; a large layer whose bound caught fewer than
+//              k_l centres, or overfilled a tile, falls back to the full map (a flag tells the
+//              fallback kernels there is work)
+//   fallback   score map + histogram of such layers (rare)
+//   select     gather: the keys of each layer's threshold bucket are copied to a list and their
+//              next digit counted; finish: one workgroup per layer resolves the remaining digits
+//              (Algorithm 1's ranking; Eq. 11's k_l)
 //   mark       selected centres set the bits of their p x p window (Section III-C: whole
 //              neighbourhoods are kept)
 //   count      kept elements per chunk and per group of chunks (no scan kernel: each consumer
@@ -26,8 +32,8 @@
 //   begin            k_begin
 //   work feed        WorkFeed: tiles handed to persistent workgroups through per-XCD counters
 //   nsi              k_nsi<P, PASS, MOM, FEED>: the four NSI passes, with or without Eq. 12's momentum
-//   hint, validate   k_hint, k_validate: the candidate bound and whether it held
-//   find .. filter   k_find, k_gather, k_finish, k_filter: the radix select
+//   ranking digits   block_find_digit, publish_threshold
+//   find0 .. finish  k_find0, k_gather, k_finish: the radix select
 //   mark             k_mark: p x p windows into the bitmask
 //   count            k_count, chunk_prefix_wave0
 //   emit             k_emit, k_emit_sparse, k_emit_centres
@@ -61,18 +67,10 @@ int hip_fail(hipError_t e, const char *what) {
         if (e_ != hipSuccess) return hip_fail(e_, #expr);    \
     } while (0)
 
-// Radix digits of the 63-bit composite key  K = (score bits << 32) | ~index,
-// most significant first.  Scores are non-negative floats, so their bit pattern
-// orders like the value; ~index makes the lower index the larger key.
-constexpr int kLevels = 6;
+// Composite ranking key  K = (score bits << 32) | ~index.  Scores are non-negative floats, so
+// their bit pattern orders like the value; ~index makes the lower index the larger key; all
+// keys of a layer are distinct.
 constexpr uint32_t kNumCUs = 256;   // MI355X
-__host__ __device__ constexpr int level_shift(int lv) {
-    return lv == 0 ? 51 : lv == 1 ? 41 : lv == 2 ? 32 : lv == 3 ? 21 : lv == 4 ? 10 : 0;
-}
-__host__ __device__ constexpr int level_bits(int lv) {
-    return lv == 0 ? 12 : lv == 1 ? 10 : lv == 2 ? 9 : lv == 3 ? 11 : lv == 4 ? 11 : 10;
-}
-
 __device__ __forceinline__ unsigned long long composite_key(uint32_t score_bits, uint32_t index) {
     return (static_cast<unsigned long long>(score_bits & 0x7fffffffu) << 32) |
            static_cast<unsigned long long>(~index);
@@ -138,14 +136,25 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_t
 
 // ---------------------------------------------------------------- begin --
 // Start of a compress call: all workgroups but the last clear the histograms, counters and
-// bitmasks; the last one writes every layer's initial selection state.  A large layer whose
-// candidate bound failed in a recent call (penalty[l] > 0, see k_hint and k_validate) starts on
-// the full map: it would most likely fail again, and the main pass over it would be wasted.
+// bitmasks; the last one writes every layer's initial selection state.  A large layer gets its
+// candidate bound here when the thresholds of its last two calls (kept in `pred`) lie close
+// together.  While a residual builds up, the threshold keeps moving in one direction by steps
+// that, on a logarithmic scale, shrink smoothly from call to call; so after a step d of
+// log2(threshold) the next one is taken to lie between 0.6 d and 1.15 d, and the bound sits a
+// margin below the lowest threshold that allows.  The margin doubles after every failed bound.
+// The result of the call never depends on the bound -- only whether the layer has to be redone
+// through the full map.  Without a usable history (first calls, after a failure, a threshold
+// that jumps) the bound comes from a sample of this call's scores (k_hint) during the first
+// calls with a workspace (`sampling`); later such a layer is ranked on the full map until its
+// threshold has settled, and the call needs neither the sampled tiles nor k_hint.
+// flags[0] tells the fallback kernels whether any large layer is on the full map.
 __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16,
                                                const LayerDev *__restrict__ layers,
                                                SelState *__restrict__ state, int n_layers,
-                                               uint32_t *__restrict__ penalty /* nullable */) {
+                                               PredState *__restrict__ pred /* nullable */,
+                                               uint32_t *__restrict__ flags, int sampling) {
     if (blockIdx.x + 1 == gridDim.x) {
+        bool fallback_work = false;
         for (int l = threadIdx.x; l < n_layers; l += 256) {
             SelState s;
             const LayerDev L = layers[l];
@@ -153,20 +162,37 @@ __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16
             s.k_rem = L.k;
             s.done = L.k == 0 ? 1u : 0u;
             s.mode = L.k == 0 ? kModeSkip : (L.large ? kModeCandidates : kModeFullMap);
-            if (penalty && s.mode == kModeCandidates) {
-                const uint32_t left = penalty[l];
-                if (left > 0) {
-                    s.mode = kModeFullMap;
-                    penalty[l] = left - 1;
-                }
-            }
             s.hint_key = 0;
             s.overflow = 0;
-            s.n_centres = 0;
-            s.n_pairs = 0;
-            s.pad_ = 0;
+            s.lo = 0;
+            s.span = 0;
+            s.predicted = 0;
+            if (pred && s.mode == kModeCandidates) {
+                const PredState ps = pred[l];
+                if (ps.cooldown > 0) {
+                    pred[l].cooldown = ps.cooldown - 1;
+                } else if (ps.tau1 >= (1u << 23) && ps.tau2 >= (1u << 23)) {   // (both in the normal float32 range)
+                    const float l1 = __log2f(__uint_as_float(ps.tau1)), l2 = __log2f(__uint_as_float(ps.tau2));
+                    const float d = l1 - l2;
+                    if (fabsf(d) <= kTrendMaxLog2) {
+                        const float margin = ps.margin > 0.f ? ps.margin : kMarginInitLog2;
+                        const float bound = exp2f(l1 + (d > 0.f ? 0.6f * d : 1.15f * d) - margin);
+                        const uint32_t key = __float_as_uint(bound);
+                        if (key >= (1u << 23) && key < 0x7f800000u) {
+                            s.hint_key = key;
+                            s.predicted = 1;
+                        }
+                    }
+                }
+                if (!s.predicted && !sampling) {
+                    s.mode = kModeFullMap;
+                    fallback_work = true;
+                }
+            }
             state[l] = s;
         }
+        const int any = __syncthreads_or(fallback_work ? 1 : 0);
+        if (threadIdx.x == 0) flags[0] = any ? 1u : 0u;
         return;
     }
     const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
@@ -209,6 +235,10 @@ __device__ __forceinline__ double uniform_f64(double x) {
 // is therefore evaluated again the way Eq. 10 is printed -- window_ssd below -- and only the
 // others (relative error of the one-pass form below 3e-9) keep the one-pass value.
 constexpr double kCancelFrac = 1.0 / 1048576.0;
+// More than the absolute error of the one-pass d, as a fraction of n*sq (a product, a square and
+// the p*p roundings of sum w^2: below 52 * 2^-53 for p <= 7).
+constexpr double kOnePassErr = 1e-13;
+constexpr int kQueueCap = 1024;      // centres one tile can queue for full evaluation (twice the largest slot)
 
 __device__ __forceinline__ double var_n2_one_pass(double ss, double nsq) {
     return __dsub_rn(nsq, __dmul_rn(ss, ss));
@@ -347,14 +377,70 @@ struct NsiArgs {
     float m;                      // momentum factor
     const uint32_t *flags;        // [0] != 0: some large layer fell back to the full map
     uint32_t *hist;               // [n_layers][kHistBins]
+    uint32_t *hist_s;             // [n_layers][kHistBins]  scores of the sampled tiles of the large layers
     const SelState *state;
-    SelState *state_rw;           // same array; only the overflow flag is written (capture)
+    SelState *state_rw;           // same array; the main pass sets the overflow flag
     uint32_t *slot_cnt;           // [n_tiles_all]
-    unsigned long long *slot_ent; // [n_tiles_all][kSlotCap]
+    unsigned long long *slot_ent; // per large layer n_tiles slots of slot_cap entries, from the layer's slot_off
     double ca, cb;                // alpha / p^2, (1 - alpha) / p^2: NSI = ca * sum|w| + cb * sqrt(p^2 * sum w^2 - (sum w)^2)
     uint32_t *feed;               // work-feed counters of this launch (all but kPassMapOnly)
     uint32_t feed_shift;          // log2 of the items per domain and stretch
 };
+
+// Bucket that holds the k-th largest entry of a 4096-bucket histogram h (completed by an earlier
+// launch), walking down from the top bucket.  One wave; every lane returns the same result
+// (found = 0 when the histogram holds fewer than k entries).  Cold code inside hot kernels: its
+// loops stay rolled so that it needs next to no registers.
+struct WaveBucket {
+    uint32_t bucket, above, count, found;
+};
+__device__ __forceinline__ WaveBucket wave_find_bucket(const uint32_t *__restrict__ h, uint32_t k) {
+    const int lane = threadIdx.x & 63;
+    constexpr int per = kHistBins / 64;
+    const int hi = kHistBins - lane * per;              // lane 0 holds the top buckets
+    uint32_t own = 0;
+#pragma unroll 1
+    for (int b = hi - 1; b >= hi - per; --b) own += h[b];
+    uint32_t incl = own;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+    }
+    const uint32_t excl = incl - own;
+    WaveBucket r = {0u, 0u, 0u, 0u};
+    const bool mine = excl < k && k <= incl;
+    if (mine) {
+        uint32_t acc = excl;
+#pragma unroll 1
+        for (int b = hi - 1; b >= hi - per; --b) {
+            const uint32_t c = h[b];
+            if (acc + c >= k) {
+                r.bucket = static_cast<uint32_t>(b);
+                r.above = acc;
+                r.count = c;
+                break;
+            }
+            acc += c;
+        }
+    }
+    const unsigned long long who = __ballot(mine);
+    if (who == 0ull) return r;
+    const int src = __ffsll(static_cast<long long>(who)) - 1;
+    r.bucket = __shfl(r.bucket, src, 64);
+    r.above = __shfl(r.above, src, 64);
+    r.count = __shfl(r.count, src, 64);
+    r.found = 1u;
+    return r;
+}
+
+// Candidate bound of a large layer from the scores of its sampled tiles (12-bit histogram hs):
+// the lower edge of the bucket at which `target` sampled scores are reached from the top; 0 when
+// the sample cannot supply the target or supplies it only from bucket 0.
+__device__ __forceinline__ uint32_t wave_bound_from_sample(const uint32_t *__restrict__ hs, uint32_t target) {
+    const WaveBucket r = wave_find_bucket(hs, target);
+    return r.found ? r.bucket << kCoarseShift : 0u;
+}
 
 // Work unit: one 16 x 256 tile of one layer.  The tile of v = r + g plus a halo of
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
@@ -372,31 +458,25 @@ struct NsiArgs {
 // MOM: with Eq. 12's momentum term (a.mom, a.mom_out, a.m).  FEED: the workgroups take their
 // tiles from the launch's work feed instead of a fixed strided share.
 template <int P, int PASS, bool MOM, bool FEED>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FEED && !MOM ? (P <= 3 ? 5 : 4) : 1, 8)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FEED && !MOM ? (P <= 3 ? 5 : P == 5 ? 4 : 3) : 1, 8)))
 void k_nsi(const NsiArgs a) {
     constexpr int H = (P - 1) / 2;
     constexpr int ROWS = kTileRows + 2 * H;
     constexpr int PADL = 4;
-    constexpr int PITCH = kTileCols + 2 * PADL;   // 136 floats
-    constexpr int VEC_PER_ROW = PITCH / 4;        // 34
-    // One column per thread: two adjacent columns share LDS reads, but the second set of row
-    // sums costs 18 registers, and at one column the main pass fits 5 waves per SIMD (p = 3) and
-    // the p = 7 variants 4 instead of 3.
-    constexpr int CPT = 1;                        // adjacent output columns per thread
-    constexpr int RPT = kTileRows * kTileCols / (256 * CPT);   // output rows per thread
+    constexpr int PITCH = kTileCols + 2 * PADL;   // 264 floats
+    // One column per thread (two adjacent columns would share LDS reads, but the second set of row
+    // sums costs 18 registers and a wave per SIMD).
+    constexpr int RPT = kTileRows * kTileCols / 256;           // output rows per thread
     constexpr bool MAP = PASS == kPassMapOnly || PASS == kPassFullMap;
     constexpr bool CAPTURE = PASS == kPassCapture;
-    // the main pass of the wide neighbourhoods tests a centre against the bound before it takes
-    // the square root (p = 5: 262 -> 254 us on 25088 x 4096; at p <= 3 the few registers it
-    // needs cost the fifth wave per SIMD, and the pass is not faster with it)
-    constexpr bool PRETEST = CAPTURE && FEED && !MOM && P >= 5;
     constexpr bool FULLHIST = PASS == kPassFullMap || PASS == kPassSample;
     constexpr bool STORE_V = PASS != kPassMapOnly;
-    constexpr int NBINS = FULLHIST ? kHistBins : (CAPTURE ? kCandBins : 1);
+    constexpr int NBINS = FULLHIST ? kHistBins : (CAPTURE ? kFineBins : 1);
     __shared__ __attribute__((aligned(16))) float tile[ROWS * PITCH];
     __shared__ uint32_t lhist[NBINS];
-    __shared__ unsigned long long cand[CAPTURE ? kSlotCap : 1];
-    __shared__ uint32_t ncand;
+    __shared__ unsigned long long cand[CAPTURE ? kSlotCapMax : 1];
+    __shared__ uint16_t queue[CAPTURE ? kQueueCap : 1];
+    __shared__ uint32_t ncand, nqueue;
     __shared__ uint32_t feed_slot[2];
 
     const int tid = threadIdx.x;
@@ -418,13 +498,14 @@ void k_nsi(const NsiArgs a) {
 
     if (NBINS > 1)
         for (int b = tid; b < NBINS; b += 256) lhist[b] = 0;
-    if (CAPTURE && tid == 0) ncand = 0;
+    if (CAPTURE && tid == 0) { ncand = 0; nqueue = 0; }
     __syncthreads();
 
     uint32_t e = 0;                       // directory entry of the current layer
     if (PASS != kPassSample) e = dir_lookup(a.dir, a.n_dir, first);
     uint32_t cur_l = 0xffffffffu;         // layer whose counts sit in lhist
-    uint32_t hint_key = 0, hint_bin = 0;
+    uint32_t hint_key = 0;
+    uint32_t *hist_base = a.hist;         // first pass: a.hist_s for the sampled tiles of a large layer
     double bound_lo = 0.0;                // capture: a conservative form of the candidate bound
     bool active = true;
     bool whole = true;                    // every tile of the layer is visited: v and the scores go out
@@ -435,9 +516,8 @@ void k_nsi(const NsiArgs a) {
     // has no floating point, a uniform value computed here would occupy vector registers)
     const double ca = a.ca, cb = a.cb;
     const double cb2 = uniform_f64(cb * cb);
-    static_assert(kTileCols / CPT * (kTileRows / RPT) == 256, "one thread per RPT rows x CPT columns");
-    const int tx = tid % (kTileCols / CPT), ty = tid / (kTileCols / CPT);
-    const int c0 = CPT * tx;
+    static_assert(kTileCols * (kTileRows / RPT) == 256, "one thread per RPT rows of one column");
+    const int c0 = tid % kTileCols, ty = tid / kTileCols;
     const int row_base = ty * RPT;
 
     for (uint32_t t = first; FEED ? t != kNoItem : t < n_items; t = FEED ? feed.next(feed_slot) : t + stride) {
@@ -453,7 +533,7 @@ void k_nsi(const NsiArgs a) {
         }
         if (l != cur_l) {
             if (NBINS > 1 && cur_l != 0xffffffffu && active) {   // flush the finished layer's counts
-                uint32_t *__restrict__ gh = a.hist + static_cast<size_t>(cur_l) * kHistBins + hint_bin;
+                uint32_t *__restrict__ gh = hist_base + static_cast<size_t>(cur_l) * kHistBins;
                 for (int b = tid; b < NBINS; b += 256) {
                     const uint32_t c = lhist[b];
                     if (c) { atomicAdd(&gh[b], c); lhist[b] = 0; }
@@ -464,19 +544,19 @@ void k_nsi(const NsiArgs a) {
             L = a.layers[l];
             active = true;
             hint_key = 0;
-            hint_bin = 0;
             whole = PASS != kPassSample || L.large == 0u;
-            if (PASS == kPassFullMap || PASS == kPassCapture) {
+            if (PASS == kPassFullMap || PASS == kPassCapture || (PASS == kPassSample && !whole)) {
                 const SelState st = a.state[l];
                 if (PASS == kPassFullMap) active = st.mode == kModeFullMap && L.large != 0u;
+                else if (PASS == kPassSample) active = st.mode == kModeCandidates && st.hint_key == 0u;   // no predicted bound
                 else active = st.mode == kModeCandidates;
                 if (CAPTURE) {
                     hint_key = st.hint_key;
-                    hint_bin = hint_key >> 19;
                     // below every double that rounds to a float32 at or above the bound
                     bound_lo = uniform_f64(static_cast<double>(__uint_as_float(hint_key)) * (1.0 - 1.0 / 4194304.0));
                 }
             }
+            if (PASS == kPassSample) hist_base = whole ? a.hist : a.hist_s;
         }
         if (!active) {                    // skip the rest of this layer
             if (!FEED && PASS != kPassSample) {
@@ -495,69 +575,88 @@ void k_nsi(const NsiArgs a) {
 
         // ---- load v = r + g for the tile and its halo; zero outside the matrix
         if ((C & 3) == 0) {
-            constexpr int NVEC = ROWS * VEC_PER_ROW;
-            constexpr int ITER = (NVEC + 255) / 256;
+            // The tile's own 256 columns: wave w takes rows w, w + 4, ... of the tile and its row
+            // halo, lane j the 16 bytes at column 4 j -- 1 KB per wave and row, and next to no
+            // index arithmetic (a flat split of the tile into 16-byte pieces needs a division per
+            // piece, which the compiler computes once and then keeps in a dozen registers).  The
+            // column halo, H floats on either side of every row, is loaded as single floats by the
+            // first 2 H ROWS threads.
+            constexpr int ITER = (ROWS + 3) / 4;
+            const int wave = tid >> 6, lane = tid & 63;
+            const int ym = y0 + 4 * lane;
+            const int hrow = H > 0 ? tid / (2 * H > 0 ? 2 * H : 1) : 0;
+            const int hc = H > 0 ? tid - hrow * 2 * H : 0;              // 0 .. H-1 left of the tile, H .. 2H-1 right of it
+            const int hy = hc < H ? y0 - 1 - hc : y0 + kTileCols + (hc - H);
+            const int hx = x0 - H + hrow;
+            const bool halo_thread = H > 0 && tid < 2 * H * ROWS;
+            const bool halo_in = halo_thread && hx >= 0 && hx < R && hy >= 0 && hy < C;
+            const size_t hoff = halo_in ? static_cast<size_t>(hx) * C + hy : 0;
             float4 gv[ITER], rv[ITER];
+            float gh = 0.f, rh = 0.f;
 #pragma unroll
             for (int it = 0; it < ITER; ++it) {
-                const int s = tid + it * 256;
-                const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
-                const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
+                const int rr = 4 * it + wave;
+                const int x = x0 - H + rr;
                 gv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
                 rv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (s < NVEC && x >= 0 && x < R && y >= 0 && y < C) {
-                    const size_t off = static_cast<size_t>(x) * C + y;
+                if (rr < ROWS && x >= 0 && x < R && ym < C) {
+                    const size_t off = static_cast<size_t>(x) * C + ym;
                     gv[it] = *reinterpret_cast<const float4 *>(g + off);
                     if (r) rv[it] = *reinterpret_cast<const float4 *>(r + off);
                 }
             }
+            if (halo_in) {
+                gh = g[hoff];
+                if (r) rh = r[hoff];
+            }
             if (MOM) {                    // Eq. 12, first line: the gradient term becomes u = m*u + g
                 const float *__restrict__ u = a.mom + L.elem_off;
                 float4 uv[ITER];
+                float uh = 0.f;
 #pragma unroll
                 for (int it = 0; it < ITER; ++it) {
-                    const int s = tid + it * 256;
-                    const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
-                    const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
+                    const int rr = 4 * it + wave;
+                    const int x = x0 - H + rr;
                     uv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (s < NVEC && x >= 0 && x < R && y >= 0 && y < C)
-                        uv[it] = *reinterpret_cast<const float4 *>(u + static_cast<size_t>(x) * C + y);
+                    if (rr < ROWS && x >= 0 && x < R && ym < C)
+                        uv[it] = *reinterpret_cast<const float4 *>(u + static_cast<size_t>(x) * C + ym);
                 }
+                if (halo_in) uh = u[hoff];
                 if (FEED) feed.stash(feed_slot);   // the loads are out, no store of this tile yet
+                gh = __fmul_rn(a.m, uh) + gh;
 #pragma unroll
                 for (int it = 0; it < ITER; ++it) {
                     gv[it].x = __fmul_rn(a.m, uv[it].x) + gv[it].x;
                     gv[it].y = __fmul_rn(a.m, uv[it].y) + gv[it].y;
                     gv[it].z = __fmul_rn(a.m, uv[it].z) + gv[it].z;
                     gv[it].w = __fmul_rn(a.m, uv[it].w) + gv[it].w;
-                    if (STORE_V && a.mom_out && whole) {
-                        const int s = tid + it * 256;
-                        const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
-                        const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
-                        if (s < NVEC && rr >= H && rr < H + kTileRows && j4 >= 1 && j4 <= kTileCols / 4 && x < R && y < C)
-                            store_streaming(a.mom_out + L.elem_off + static_cast<size_t>(x) * C + y, gv[it]);
+                    if (STORE_V && a.mom_out && whole) {   // the tile's own elements (not the halo) go out once
+                        const int rr = 4 * it + wave;
+                        const int x = x0 - H + rr;
+                        if (rr >= H && rr < H + kTileRows && x < R && ym < C)
+                            store_streaming(a.mom_out + L.elem_off + static_cast<size_t>(x) * C + ym, gv[it]);
                     }
                 }
             }
             if (FEED) feed.stash(feed_slot);       // the loads are out, no store of this tile yet
 #pragma unroll
             for (int it = 0; it < ITER; ++it) {
-                const int s = tid + it * 256;
-                if (s < NVEC) {
+                const int rr = 4 * it + wave;
+                if (rr < ROWS) {
                     float4 v;
                     v.x = rv[it].x + gv[it].x;
                     v.y = rv[it].y + gv[it].y;
                     v.z = rv[it].z + gv[it].z;
                     v.w = rv[it].w + gv[it].w;
-                    *reinterpret_cast<float4 *>(&tile[s * 4]) = v;   // s*4 == rr*PITCH + 4*j4
-                    if (STORE_V && a.v_out && whole) {   // the tile's own elements (not the halo) go out once
-                        const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
-                        const int x = x0 - H + rr, y = y0 - PADL + 4 * j4;
-                        if (rr >= H && rr < H + kTileRows && j4 >= 1 && j4 <= kTileCols / 4 && x < R && y < C)
-                            store_streaming(a.v_out + L.elem_off + static_cast<size_t>(x) * C + y, v);
+                    *reinterpret_cast<float4 *>(&tile[rr * PITCH + PADL + 4 * lane]) = v;
+                    if (STORE_V && a.v_out && whole) {     // the tile's own elements (not the halo) go out once
+                        const int x = x0 - H + rr;
+                        if (rr >= H && rr < H + kTileRows && x < R && ym < C)
+                            store_streaming(a.v_out + L.elem_off + static_cast<size_t>(x) * C + ym, v);
                     }
                 }
             }
+            if (halo_thread) tile[hrow * PITCH + (hc < H ? PADL - 1 - hc : PADL + kTileCols + (hc - H))] = rh + gh;
         } else {
             if (FEED) feed.stash(feed_slot);
             for (int s = tid; s < ROWS * PITCH; s += 256) {
@@ -581,120 +680,129 @@ void k_nsi(const NsiArgs a) {
         __syncthreads();
 
         // ---- window statistics
-        const bool pair_store = (C & 1) == 0;
-        double hs_a[P][CPT], hs_s[P][CPT], hs_q[P][CPT];
+        // (the column as the compiler cannot see through it: otherwise it forms the 16 queue
+        // entries of the thread once, outside the loop over the tiles, and keeps them in registers)
+        int c0q = c0;
+        asm volatile("" : "+v"(c0q));
+        double hs_a[P], hs_s[P], hs_q[P];
 #pragma unroll
         for (int i = 0; i < RPT + 2 * H; ++i) {
             const float *row = &tile[(row_base + i) * PITCH + PADL + c0 - H];
-            double w[2 * H + CPT];
+            double w[P];
 #pragma unroll
-            for (int j = 0; j < 2 * H + CPT; ++j) w[j] = static_cast<double>(row[j]);
-            const int slot = i % P;
-#pragma unroll
-            for (int c = 0; c < CPT; ++c) {
-                double sa = fabs(w[c]), ss = w[c], sq = w[c] * w[c];
+            for (int j = 0; j < P; ++j) w[j] = static_cast<double>(row[j]);
+            {
+                double sa = fabs(w[0]), ss = w[0], sq = w[0] * w[0];
 #pragma unroll
                 for (int j = 1; j < P; ++j) {
-                    sa += fabs(w[c + j]);
-                    ss += w[c + j];
-                    sq = fma(w[c + j], w[c + j], sq);
+                    sa += fabs(w[j]);
+                    ss += w[j];
+                    sq = fma(w[j], w[j], sq);
                 }
-                hs_a[slot][c] = sa;
-                hs_s[slot][c] = ss;
-                hs_q[slot][c] = sq;
+                hs_a[i % P] = sa;
+                hs_s[i % P] = ss;
+                hs_q[i % P] = sq;
             }
             if (i >= 2 * H) {
                 const int o = i - 2 * H;   // output row inside the thread's strip
-                float out[CPT];
-                uint32_t key[CPT];
-                bool reaches = false;      // capture: some centre of the thread reaches the bound
+                double sa = hs_a[o % P], ss = hs_s[o % P], sq = hs_q[o % P];
 #pragma unroll
-                for (int c = 0; c < CPT; ++c) {
-                    double sa = hs_a[o % P][c], ss = hs_s[o % P][c], sq = hs_q[o % P][c];
-#pragma unroll
-                    for (int j = 1; j < P; ++j) {
-                        sa += hs_a[(o + j) % P][c];
-                        ss += hs_s[(o + j) % P][c];
-                        sq += hs_q[(o + j) % P][c];
-                    }
-                    const double nsq = __dmul_rn(n, sq);
-                    double d = var_n2_one_pass(ss, nsq);
-                    // the one-pass variance cancelled (rare; never for P = 1, where it is 0 by definition)
-                    const bool cancels = P > 1 && d < kCancelFrac * nsq;
-                    bool exact = true;
-                    if (PRETEST) {
-                        // Only the centres that reach the bound are wanted, and 99.5 % do not.  A test
-                        // without the square root, with slack far beyond the double rounding errors
-                        // and the last float32 bit of the bound, rules most of them out (a wave skips
-                        // the rest when all its lanes are ruled out):
-                        //   NSI >= B  <=>  cb*sqrt(d) >= B - ca*sa  <=>  rest <= 0  or  cb^2 * d >= rest^2
-                        const double rest = bound_lo - ca * sa;
-                        exact = cancels || rest <= 0.0 || cb2 * d >= rest * rest * (1.0 - 1e-9);
-                    }
-                    out[c] = 0.f;
-                    if (exact) {
-                        if (cancels)
-                            d = __dmul_rn(n, window_ssd<P>(&tile[(row_base + o) * PITCH + PADL + c0 + c - H],
-                                                           PITCH, ss / n));
-                        out[c] = static_cast<float>(nsi_from_var(sa, d, ca, cb));
-                    }
-                    key[c] = __float_as_uint(out[c]) & 0x7fffffffu;
-                    reaches = reaches || (exact && key[c] >= hint_key);
+                for (int j = 1; j < P; ++j) {
+                    sa += hs_a[(o + j) % P];
+                    ss += hs_s[(o + j) % P];
+                    sq += hs_q[(o + j) % P];
                 }
+                const double nsq = __dmul_rn(n, sq);
+                double d = var_n2_one_pass(ss, nsq);
                 const int x = x0 + row_base + o, y = y0 + c0;
                 if (CAPTURE) {
-                    // common case: no centre reaches the bound -- nothing else to do
-                    if (reaches && x < R && y < C) {
-                        const uint32_t i0 = static_cast<uint32_t>(x) * L.C + static_cast<uint32_t>(y);
-#pragma unroll
-                        for (int c = 0; c < CPT; ++c) {
-                            if (key[c] >= hint_key && y + c < C) {
-                                const uint32_t pos = atomicAdd(&ncand, 1u);
-                                if (pos < kSlotCap) cand[pos] = composite_key(key[c], i0 + c);
-                                const uint32_t rel = (key[c] >> 19) - hint_bin;
-                                atomicAdd(&lhist[min(rel, static_cast<uint32_t>(kCandBins - 1))], 1u);
-                                if (rel >= static_cast<uint32_t>(kCandBins - 1)) a.state_rw[l].overflow = 1u;
-                            }
-                        }
+                    // Only the centres that reach the bound are wanted, and about 99.5 % do not.  A
+                    // test without the square root rules those out:
+                    //   NSI >= B  <=>  cb*sqrt(d) >= B - ca*sa  <=>  rest <= 0  or  cb^2 * d >= rest^2
+                    // with slack far beyond the rounding errors of the double arithmetic and the last
+                    // float32 bit of the bound, and with d raised by more than the error the one-pass
+                    // form can have (so that a window whose variance cancels is never ruled out on a
+                    // value that is too small).  The few that remain are queued and evaluated in
+                    // full after the sweep, one per thread.
+                    const double rest = bound_lo - ca * sa;
+                    const double d_hi = fma(kOnePassErr, nsq, d);
+                    if ((rest <= 0.0 || cb2 * d_hi >= rest * rest * (1.0 - 1e-9)) && x < R && y < C) {
+                        const uint32_t pos = atomicAdd(&nqueue, 1u);
+                        if (pos < static_cast<uint32_t>(kQueueCap))
+                            queue[pos] = static_cast<uint16_t>((row_base + o) * kTileCols + c0q);
                     }
-                } else if (x < R && y < C) {
-                    if (MAP || (PASS == kPassSample && whole)) {
-                        const size_t off = static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y;
-                        if (CPT == 2 && y + 1 < C && pair_store) {
-                            *reinterpret_cast<float2 *>(a.nsi_out + off) = make_float2(out[0], out[CPT - 1]);
-                        } else {
-#pragma unroll
-                            for (int c = 0; c < CPT; ++c)
-                                if (y + c < C) a.nsi_out[off + c] = out[c];
-                        }
-                    }
-                    if (FULLHIST) {
-#pragma unroll
-                        for (int c = 0; c < CPT; ++c)
-                            if (y + c < C) atomicAdd(&lhist[key[c] >> 19], 1u);
+                } else {
+                    // the one-pass variance cancelled (rare; never for P = 1, where it is 0 by definition)
+                    if (P > 1 && d < kCancelFrac * nsq)
+                        d = __dmul_rn(n, window_ssd<P>(&tile[(row_base + o) * PITCH + PADL + c0 - H], PITCH, ss / n));
+                    const float out = static_cast<float>(nsi_from_var(sa, d, ca, cb));
+                    if (x < R && y < C) {
+                        if (MAP || (PASS == kPassSample && whole))
+                            a.nsi_out[static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + y] = out;
+                        if (FULLHIST) atomicAdd(&lhist[(__float_as_uint(out) & 0x7fffffffu) >> kCoarseShift], 1u);
                     }
                 }
             }
         }
-        __syncthreads();                  // all reads of the tile (and of cand) are complete
+        __syncthreads();                  // the sweep is complete (the tile is still needed by the queue)
 
         if (CAPTURE) {
-            const uint32_t slot = L.tile_begin_all + local;
-            const uint32_t nc = ncand;
-            unsigned long long *__restrict__ dst = a.slot_ent + static_cast<size_t>(slot) * kSlotCap;
-            for (uint32_t i = tid; i < min(nc, static_cast<uint32_t>(kSlotCap)); i += 256) dst[i] = cand[i];
+            // ---- the queued centres in full: the same sums in the same order as above, Eq. 10 again
+            // from the tile where the one-pass variance cancels, score, and the record if it reaches
+            // the bound
+            const uint32_t nq = nqueue;
+            if (nq > static_cast<uint32_t>(kQueueCap) && tid == 0) a.state_rw[l].overflow = 1u;   // (more than any slot holds)
+            for (uint32_t qi = tid; qi < min(nq, static_cast<uint32_t>(kQueueCap)); qi += 256) {
+                const int pos = queue[qi];
+                const int orow = pos / kTileCols, ocol = pos - orow * kTileCols;
+                const float *win = &tile[orow * PITCH + PADL + ocol - H];
+                double sa = 0.0, ss = 0.0, sq = 0.0;
+#pragma unroll 1
+                for (int dx = 0; dx < P; ++dx) {       // (cold code: kept rolled, it needs few registers that way)
+                    const double w0 = static_cast<double>(win[dx * PITCH]);
+                    double ra = fabs(w0), rs = w0, rq = w0 * w0;
+#pragma unroll
+                    for (int j = 1; j < P; ++j) {
+                        const double wj = static_cast<double>(win[dx * PITCH + j]);
+                        ra += fabs(wj);
+                        rs += wj;
+                        rq = fma(wj, wj, rq);
+                    }
+                    if (dx == 0) { sa = ra; ss = rs; sq = rq; }
+                    else { sa += ra; ss += rs; sq += rq; }
+                }
+                const double nsq = __dmul_rn(n, sq);
+                double d = var_n2_one_pass(ss, nsq);
+                if (P > 1 && d < kCancelFrac * nsq) d = __dmul_rn(n, window_ssd<P>(win, PITCH, ss / n));
+                const uint32_t key = __float_as_uint(static_cast<float>(nsi_from_var(sa, d, ca, cb))) & 0x7fffffffu;
+                if (key >= hint_key) {
+                    const uint32_t x = static_cast<uint32_t>(x0 + orow), y = static_cast<uint32_t>(y0 + ocol);
+                    const uint32_t cp = atomicAdd(&ncand, 1u);
+                    if (cp < static_cast<uint32_t>(kSlotCapMax)) cand[cp] = composite_key(key, x * L.C + y);
+                    // fine bins upwards from the bound; the last one is open-ended
+                    const uint32_t rel = (key - hint_key) >> kFineShift;
+                    atomicAdd(&lhist[min(rel, static_cast<uint32_t>(kFineBins - 1))], 1u);
+                }
+            }
+            __syncthreads();              // all reads of the tile are complete, all records made
+        }
+
+        if (CAPTURE) {
+            const uint32_t nc = ncand, cap = L.slot_cap;
+            unsigned long long *__restrict__ dst = a.slot_ent + L.slot_off + static_cast<size_t>(local) * cap;
+            for (uint32_t i = tid; i < min(nc, cap); i += 256) dst[i] = cand[i];
             if (tid == 0) {
-                a.slot_cnt[slot] = min(nc, static_cast<uint32_t>(kSlotCap));
-                if (nc > static_cast<uint32_t>(kSlotCap)) a.state_rw[l].overflow = 1u;
+                a.slot_cnt[L.tile_begin_all + local] = min(nc, cap);
+                if (nc > cap) a.state_rw[l].overflow = 1u;
             }
             __syncthreads();
-            if (tid == 0) ncand = 0;
+            if (tid == 0) { ncand = 0; nqueue = 0; }
             // the next tile's first barrier orders this reset before any new append
         }
     }
 
     if (NBINS > 1 && cur_l != 0xffffffffu && active) {
-        uint32_t *__restrict__ gh = a.hist + static_cast<size_t>(cur_l) * kHistBins + hint_bin;
+        uint32_t *__restrict__ gh = hist_base + static_cast<size_t>(cur_l) * kHistBins;
         for (int b = tid; b < NBINS; b += 256) {
             const uint32_t c = lhist[b];
             if (c) atomicAdd(&gh[b], c);
@@ -702,393 +810,40 @@ void k_nsi(const NsiArgs a) {
     }
 }
 
-// ----------------------------------------------------------------- hint --
-// One workgroup per large layer: walk the sampled-score histogram from the top until
-// hint_target scores lie at or above a bucket; that bucket's lower edge is the candidate
-// bound.  A layer whose sample cannot supply the target goes to the full map.
-__global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layers,
-                                              SelState *__restrict__ state,
-                                              uint32_t *__restrict__ hist,
-                                              uint32_t *__restrict__ flags,
-                                              uint32_t *__restrict__ penalty) {
-    __shared__ uint32_t wave_tot[4];
-    __shared__ uint32_t found;
-    const int l = blockIdx.x, tid = threadIdx.x;
-    // state, target and counts are requested together (see k_validate)
-    const SelState st = state[l];
-    const uint32_t target = layers[l].hint_target;
-    uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
-    constexpr int per = kHistBins / 256;
-    const int hi = kHistBins - tid * per;
-    uint32_t own = 0;
-#pragma unroll
-    for (int b = hi - 1; b >= hi - per; --b) own += h[b];
-    if (st.mode != kModeCandidates) {
-        // a large layer that k_begin kept off the candidate path: the sampled counts go, and the
-        // fallback pass has work; any other layer's histogram is either still zero or complete
-        if (st.mode == kModeFullMap && layers[l].large != 0u) {
-            for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
-            if (tid == 0) flags[0] = 1u;
-        }
-        return;
-    }
-    if (tid == 0) found = 0;
-    const uint32_t incl = block_scan_incl(own, wave_tot);
-    const uint32_t excl = incl - own;
-    if (excl < target && target <= incl) {
-        uint32_t acc = excl;
-        for (int b = hi - 1; b >= hi - per; --b) {
-            acc += h[b];
-            if (acc >= target) {
-                SelState ns = st;
-                ns.hint_key = static_cast<uint32_t>(b) << 19;
-                state[l] = ns;
-                found = 1;
-                break;
-            }
-        }
-    }
-    __syncthreads();
-    if (tid == 0 && !found) {
-        SelState ns = st;
-        ns.mode = kModeFullMap;
-        state[l] = ns;
-        flags[0] = 1u;                     // the fallback pass has work
-        penalty[l] = kPenaltyCalls;
-    }
-    for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
-}
-
-// ------------------------------------------------------------- validate --
-// One workgroup per candidate-mode layer: the recorded candidates are usable only if no
-// tile slot and no histogram window overflowed and at least k_l centres were recorded
-// (then the k_l best of the layer are all among them).  Otherwise the layer falls back to
-// the full map, and its histogram is cleared for that pass.
-__global__ __launch_bounds__(256) void k_validate(const LayerDev *__restrict__ layers,
-                                                  SelState *__restrict__ state,
-                                                  uint32_t *__restrict__ hist,
-                                                  uint32_t *__restrict__ flags,
-                                                  uint32_t *__restrict__ penalty) {
-    __shared__ uint32_t wave_tot[4];
-    const int l = blockIdx.x, tid = threadIdx.x;
-    // state, k_l and the counts are requested together: one round trip to memory instead of
-    // three (each costs this one-workgroup-per-layer kernel about 2 us)
-    const SelState st = state[l];
-    const uint32_t k = layers[l].k;
-    uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
-    uint32_t own = 0;
-#pragma unroll
-    for (int j = 0; j < kHistBins / 256; ++j) own += h[tid + 256 * j];
-    if (st.mode != kModeCandidates) return;
-    const uint32_t total = block_scan_incl(own, wave_tot);
-    __shared__ uint32_t fail;
-    if (tid == 255) fail = (st.overflow || total < k) ? 1u : 0u;
-    __syncthreads();
-    if (fail) {
-        for (int b = tid; b < kHistBins; b += 256) h[b] = 0;
-        if (tid == 0) {
-            SelState ns = st;
-            ns.mode = kModeFullMap;
-            state[l] = ns;
-            flags[0] = 1u;                 // the fallback pass has work
-            penalty[l] = kPenaltyCalls;
-        }
-    }
-}
-
-// ----------------------------------------------------------------- find --
-// One workgroup per layer: walk the digit histogram from the top, fix the digit that
-// holds the k_rem-th largest key, clear the histogram for the next level.
-// The layer's counts may be spread over `copies` histograms of 2^bits bins laid end to end
-// (writers pick a copy by workgroup id so that fewer atomics meet in one cache line).
-__global__ __launch_bounds__(256) void k_find(SelState *__restrict__ state,
-                                              uint32_t *__restrict__ hist, int shift, int bits,
-                                              int copies) {
-    __shared__ uint32_t wave_tot[4];
-    __shared__ uint32_t found;
-    const int l = blockIdx.x, tid = threadIdx.x;
-    uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
-    const int nb = 1 << bits, per = nb >> 8;
-    const SelState st = state[l];
-    if (tid == 0) found = 0;
-    // thread t owns bins [hi - per, hi), hi = nb - t * per  (t = 0 holds the top bins); their
-    // counts (added over the copies) stay in registers for the walk below.  They are requested
-    // with the state, before it is known whether the layer still needs them.
-    const int hi = nb - tid * per;
-    constexpr int kMaxPer = kHistBins / 256, kMaxCopies = kHistBins >> level_bits(1);
-    uint32_t v[kMaxPer];
-    uint32_t own = 0;
-#pragma unroll
-    for (int j = 0; j < kMaxPer; ++j) {
-        v[j] = 0;
-        if (j < per) {
-#pragma unroll
-            for (int cp = 0; cp < kMaxCopies; ++cp)
-                if (cp < copies) v[j] += h[cp * nb + hi - 1 - j];
-        }
-        own += v[j];
-    }
-    if (!st.done) {
-        const uint32_t incl = block_scan_incl(own, wave_tot);
-        const uint32_t excl = incl - own;
-        if (excl < st.k_rem && st.k_rem <= incl) {
-            uint32_t acc = excl;
-            bool hit = false;
-#pragma unroll
-            for (int j = 0; j < kMaxPer; ++j) {
-                if (!hit && j < per && acc + v[j] >= st.k_rem) {
-                    SelState ns = st;
-                    ns.T = st.T | (static_cast<unsigned long long>(hi - 1 - j) << shift);
-                    ns.k_rem = st.k_rem - acc;
-                    ns.done = (v[j] == ns.k_rem) ? 1u : 0u;   // whole bucket taken: lower digits stay 0
-                    state[l] = ns;
-                    found = 1;
-                    hit = true;
-                }
-                if (!hit) acc += v[j];
-            }
-        }
-        __syncthreads();
-        if (tid == 0 && !found) {          // fewer keys than k_rem (cannot happen for finite input)
-            SelState ns = st;
-            ns.done = 1;
-            state[l] = ns;
-        }
-    }
-    __syncthreads();
-    for (int b = tid; b < nb * copies; b += 256) h[b] = 0;
-}
-
-// --------------------------------------------------------------- gather --
-// After the first digit: the keys of each layer's threshold bucket (those whose top
-// 12 score bits equal the chosen digit) are copied into the layer's list, and their next
-// digit is histogrammed.  Three kinds of workgroups share the launch:
-//   [0, n_map_wgs)              stride over the plan's list of 8192-element score-map chunks
-//                               (layers that are always ranked on the full map);
-//   [n_map_wgs, +n_slot_wgs)    stride over the plan's list of slot groups (large layers,
-//                               where they are still in candidate mode);
-//   the last n_fb_wgs           only when some large layer fell back to the full map: they
-//                               walk all chunks and take those of such layers.
-// Matches are staged in LDS and appended with one atomic per flush.
-constexpr int kStage = 2048;            // staged keys per workgroup (a round adds at most 1024)
-constexpr int kHist1Copies = kHistBins >> level_bits(1);   // second-digit histograms per layer (4)
-
-struct GatherStage {
-    unsigned long long ent[kStage];
-    uint32_t hist1[1 << level_bits(1)];
-    uint32_t n;
-    uint32_t base;
-};
-
-// Appends the staged keys to the layer's list; with_hist also adds the staged second-digit
-// counts to the layer's global histogram (done once per layer per workgroup).
-__device__ __forceinline__ void gather_flush(GatherStage &st, const LayerDev &L,
-                                             uint32_t *__restrict__ list_cnt, uint32_t l,
-                                             unsigned long long *__restrict__ list_ent,
-                                             uint32_t *__restrict__ hist, bool with_hist) {
-    __syncthreads();
-    const uint32_t n = st.n;
-    if (n != 0) {                          // uniform
-        // the workgroup's shard of the layer's list: its own counter (own cache line) and region
-        const uint32_t shard = blockIdx.x % L.list_shards, cap = L.list_cap / L.list_shards;
-        if (threadIdx.x == 0)
-            st.base = atomicAdd(&list_cnt[(static_cast<size_t>(l) * kListShards + shard) * kListCntStride], n);
-        __syncthreads();
-        const uint32_t base = st.base;
-        unsigned long long *__restrict__ dst = list_ent + static_cast<size_t>(L.list_off) + static_cast<size_t>(shard) * cap;
-        for (uint32_t i = threadIdx.x; i < n; i += 256)
-            if (base + i < cap) dst[base + i] = st.ent[i];
-        __syncthreads();
-        if (threadIdx.x == 0) st.n = 0;
-    }
-    if (with_hist) {
-        uint32_t *__restrict__ gh = hist + static_cast<size_t>(l) * kHistBins +
-                                    (blockIdx.x % kHist1Copies) * (1u << level_bits(1));
-        for (int b = threadIdx.x; b < (1 << level_bits(1)); b += 256) {
-            const uint32_t c = st.hist1[b];
-            if (c) { atomicAdd(&gh[b], c); st.hist1[b] = 0; }
-        }
-    }
-    __syncthreads();
-}
-
-// One round of at most 1024 appends (4 per thread) is about to start: make room for it.
-__device__ __forceinline__ void gather_make_room(GatherStage &st, const LayerDev &L,
-                                                 uint32_t *__restrict__ list_cnt, uint32_t l,
-                                                 unsigned long long *__restrict__ list_ent,
-                                                 uint32_t *__restrict__ hist) {
-    __syncthreads();                       // appends of the previous round are counted
-    if (st.n + 1024u > static_cast<uint32_t>(kStage))          // uniform
-        gather_flush(st, L, list_cnt, l, list_ent, hist, false);
-}
-
-// Stages key K (of a flagged lane) and counts its second digit.  Called by whole waves.
-__device__ __forceinline__ void gather_stage_key(GatherStage &st, bool hit, unsigned long long K) {
-    const uint32_t pos = wave_append(&st.n, hit);
-    if (hit) {
-        st.ent[pos] = K;
-        atomicAdd(&st.hist1[static_cast<uint32_t>(K >> level_shift(1)) & ((1u << level_bits(1)) - 1u)], 1u);
-    }
-}
-
-struct GatherLists {
-    const DirEntry *chunk_dir;       // all chunks by layer (fallback walk)
-    const ChunkEntry *map_chunks;    // [n_map_chunks]
-    const GroupEntry *cand_groups;   // [n_cand_groups]
-    const uint32_t *flags;
-    uint32_t n_layers, n_chunks, n_map_chunks, n_cand_groups;
-    uint32_t n_map_wgs, n_slot_wgs;  // the remaining workgroups are fallback walkers
-};
-
-__global__ __launch_bounds__(256) void k_gather(const LayerDev *__restrict__ layers,
-                                                const GatherLists gl,
-                                                const SelState *__restrict__ state,
-                                                const uint32_t *__restrict__ keys,
-                                                const uint32_t *__restrict__ slot_cnt,
-                                                const unsigned long long *__restrict__ slot_ent,
-                                                uint32_t *__restrict__ list_cnt,
-                                                unsigned long long *__restrict__ list_ent,
-                                                uint32_t *__restrict__ hist) {
-    __shared__ GatherStage stage;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // role 0: listed score-map chunks, 1: listed slot groups, 2: fallback walk over all chunks
-    const int role = blockIdx.x < gl.n_map_wgs ? 0 : blockIdx.x < gl.n_map_wgs + gl.n_slot_wgs ? 1 : 2;
-    const uint32_t first = role == 0 ? blockIdx.x : role == 1 ? blockIdx.x - gl.n_map_wgs
-                                                              : blockIdx.x - gl.n_map_wgs - gl.n_slot_wgs;
-    const uint32_t stride = role == 0 ? gl.n_map_wgs : role == 1 ? gl.n_slot_wgs
-                                                                 : gridDim.x - gl.n_map_wgs - gl.n_slot_wgs;
-    const uint32_t n_items = role == 0 ? gl.n_map_chunks : role == 1 ? gl.n_cand_groups : gl.n_chunks;
-    const DirEntry *__restrict__ dir = gl.chunk_dir;
-    if (first >= n_items) return;
-    if (role == 2 && gl.flags[0] == 0u) return;
-    if (tid == 0) stage.n = 0;
-    for (int b = tid; b < (1 << level_bits(1)); b += 256) stage.hist1[b] = 0;
-    __syncthreads();
-
-    uint32_t e = role == 2 ? dir_lookup(dir, gl.n_layers, first) : 0u;
-    uint32_t cur_l = 0xffffffffu;
-    bool active = false;
-    uint32_t digit0 = 0;
-    LayerDev L;
-    for (uint32_t it = first; it < n_items; it += stride) {
-        uint32_t l;
-        ChunkEntry ce = {};
-        GroupEntry ge = {};
-        if (role == 0) {
-            ce = gl.map_chunks[it];
-            l = ce.layer;
-        } else if (role == 1) {
-            ge = gl.cand_groups[it];
-            l = ge.layer;
-        } else {
-            while (it >= dir[e + 1].begin) ++e;
-            l = dir[e].layer;
-        }
-        if (l != cur_l) {
-            if (active) gather_flush(stage, L, list_cnt, cur_l, list_ent, hist, true);
-            cur_l = l;
-            L = layers[l];
-            const SelState st = state[l];
-            active = !st.done && st.mode == (role == 1 ? kModeCandidates : kModeFullMap);
-            if (role == 2) active = active && L.large != 0u;      // the others are on the list
-            digit0 = static_cast<uint32_t>(st.T >> level_shift(0));
-        }
-        if (!active) {
-            if (role == 2) {               // on to this workgroup's first chunk of the next layer
-                const uint32_t nb = dir[e + 1].begin;
-                it += (nb - it + stride - 1) / stride * stride - stride;
-            }
-            continue;
-        }
-        if (role != 1) {
-            if (role == 2) {
-                ce.start = (it - L.chunk_begin) * kChunk;
-                ce.len = min(static_cast<uint32_t>(kChunk), L.G - ce.start);
-                ce.arena_off = static_cast<uint64_t>(L.elem_off) + ce.start;
-            }
-            const uint32_t start = ce.start, len = ce.len;
-            const uint32_t *__restrict__ src = keys + ce.arena_off;
-            // the whole chunk is requested before any of it is used
-            uint4 q[kChunk / 1024];
-#pragma unroll
-            for (int j = 0; j < kChunk / 1024; ++j) {
-                const uint32_t e4 = j * 1024 + 4 * tid;
-                q[j] = make_uint4(0, 0, 0, 0);
-                if (e4 + 3 < len) {
-                    q[j] = *reinterpret_cast<const uint4 *>(src + e4);
-                } else if (e4 < len) {
-                    q[j].x = src[e4];
-                    if (e4 + 1 < len) q[j].y = src[e4 + 1];
-                    if (e4 + 2 < len) q[j].z = src[e4 + 2];
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < kChunk / 1024; ++j) {
-                if (static_cast<uint32_t>(j) * 1024u >= len) break;       // uniform
-                gather_make_room(stage, L, list_cnt, l, list_ent, hist);
-                const uint32_t e4 = j * 1024 + 4 * tid;
-                const uint32_t kk[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
-#pragma unroll
-                for (uint32_t c = 0; c < 4; ++c) {
-                    const bool hit = e4 + c < len && ((kk[c] & 0x7fffffffu) >> 19) == digit0;
-                    gather_stage_key(stage, hit, composite_key(kk[c], start + e4 + c));
-                }
-            }
-        } else {
-            // each wave takes 4 of the group's tile slots; a round covers 64 entries of each
-            uint32_t cnt[kSlotGroup / 4];
-#pragma unroll
-            for (int c = 0; c < kSlotGroup / 4; ++c) {
-                const uint32_t sl = wave + 4 * c;
-                cnt[c] = sl < ge.ntile ? min(slot_cnt[ge.slot0 + sl], static_cast<uint32_t>(kSlotCap)) : 0u;
-            }
-            uint32_t longest = 0;
-#pragma unroll
-            for (int c = 0; c < kSlotGroup / 4; ++c) longest = max(longest, cnt[c]);
-            const int rounds = __syncthreads_or(longest > 64u) ? kSlotCap / 64 : 1;   // uniform
-            for (int rd = 0; rd < rounds; ++rd) {
-                unsigned long long K[kSlotGroup / 4];
-                const uint32_t j = 64u * rd + lane;
-#pragma unroll
-                for (int c = 0; c < kSlotGroup / 4; ++c) {
-                    K[c] = 0;
-                    if (j < cnt[c])
-                        K[c] = slot_ent[static_cast<size_t>(ge.slot0 + wave + 4 * c) * kSlotCap + j];
-                }
-                gather_make_room(stage, L, list_cnt, l, list_ent, hist);
-#pragma unroll
-                for (int c = 0; c < kSlotGroup / 4; ++c) {
-                    const bool hit = j < cnt[c] && static_cast<uint32_t>(K[c] >> level_shift(0)) == digit0;
-                    gather_stage_key(stage, hit, K[c]);
-                }
-            }
-        }
-    }
-    if (active) gather_flush(stage, L, list_cnt, cur_l, list_ent, hist, true);
-}
-
-// --------------------------------------------------------------- finish --
-// Digit that holds the k_rem-th largest key of a histogram in LDS (counted from the top);
-// every thread of the workgroup returns the same result.
+// ------------------------------------------------------- ranking digits --
+// The k_l-th largest composite key of a layer (Algorithm 1's ranking, Eq. 11's k_l) is found
+// digit by digit, most significant first:
+//   first digit   where the k_l-th score lies, from a histogram over all scores of the layer:
+//                 candidate path: kFineBins bins of 2^kFineShift score-bit values each, counted
+//                 upwards from the candidate bound by the main pass; full-map path: the top 12
+//                 bits of the score, counted by the pass that writes the map (k_find0);
+//   second digit  the next kLevel1Bits bits inside that bucket; the bucket's keys are gathered
+//                 into the layer's list on the way (k_gather, many workgroups per layer);
+//   the rest      remaining score bits, then -- only if equal scores straddle the k_l-th rank --
+//                 the bits of ~index, so that the lower index wins: one workgroup per layer, on
+//                 the gathered keys (k_finish).
 struct DigitResult {
     uint32_t digit, above, count, found;
 };
 
+// Digit that holds the k_rem-th largest key of a histogram of nb <= 4096 bins (LDS or global),
+// counted from the top; every thread of the workgroup (NW waves) returns the same result.
+// `found` is 0 when the histogram holds fewer than k_rem keys.
 template <int NW>
 __device__ __forceinline__ DigitResult block_find_digit(const uint32_t *h, int nb, uint32_t k_rem,
                                                         uint32_t *wave_tot /*[NW]*/, DigitResult *res) {
     const int tid = threadIdx.x;
-    const int per = nb >> 8;               // the first 256 threads own the bins, top bins first
+    const int per = nb >= 256 ? nb >> 8 : 1;    // the first 256 threads own `per` bins each, top bins first
     if (tid == 0) res->found = 0;
-    const int hi = nb - tid * per;
+    const int hi = nb - tid * per;              // bins [hi - per, hi), as far as they exist
     uint32_t own = 0;
     if (tid < 256)
-        for (int b = hi - 1; b >= hi - per; --b) own += h[b];
+        for (int b = hi - 1; b >= hi - per && b >= 0; --b) own += h[b];
     const uint32_t incl = block_scan_incl_n<NW>(own, wave_tot);
     const uint32_t excl = incl - own;
     if (tid < 256 && excl < k_rem && k_rem <= incl) {
         uint32_t acc = excl;
-        for (int b = hi - 1; b >= hi - per; --b) {
+        for (int b = hi - 1; b >= hi - per && b >= 0; --b) {
             const uint32_t c = h[b];
             if (acc + c >= k_rem) {
                 res->digit = static_cast<uint32_t>(b);
@@ -1106,157 +861,526 @@ __device__ __forceinline__ DigitResult block_find_digit(const uint32_t *h, int n
     return r;
 }
 
-// --------------------------------------------------------------- filter --
-// After the second digit: kFilterSplit workgroups per layer go through the layer's
-// threshold-bucket list and keep the keys that share both digits (typically a few dozen) in
-// the layer's second, small list.
-constexpr int kFilterSplit = 32;
-constexpr int kFinishThreads = 1024;
+// A large layer's threshold of this call, kept for the next call's candidate bound.
+__device__ __forceinline__ void publish_threshold(PredState *__restrict__ pred, uint32_t l, uint32_t large,
+                                                  unsigned long long T) {
+    if (pred == nullptr || large == 0u) return;
+    PredState ps = pred[l];
+    ps.tau2 = ps.tau1;
+    ps.tau1 = static_cast<uint32_t>(T >> 32);
+    pred[l] = ps;
+}
 
-__global__ __launch_bounds__(kFinishThreads) void k_filter(const LayerDev *__restrict__ layers,
-                                                           const SelState *__restrict__ state,
+// ----------------------------------------------------------------- hint --
+// First calls with a workspace only: one wave per large layer that has no predicted bound turns
+// the layer's sampled scores into its candidate bound.  A layer whose sample gives none goes to
+// the full map.
+__global__ __launch_bounds__(64) void k_hint(const LayerDev *__restrict__ layers,
+                                             SelState *__restrict__ state,
+                                             const uint32_t *__restrict__ hist_s,
+                                             uint32_t *__restrict__ flags) {
+    const int l = blockIdx.x;
+    const SelState st = state[l];
+    const uint32_t target = layers[l].hint_target;
+    if (st.mode != kModeCandidates || st.hint_key != 0u) return;
+    const uint32_t key = wave_bound_from_sample(hist_s + static_cast<size_t>(l) * kHistBins, target);
+    if (threadIdx.x == 0) {
+        if (key != 0u) {
+            state[l].hint_key = key;
+        } else {
+            state[l].mode = kModeFullMap;
+            flags[0] = 1u;                 // the fallback pass has work
+        }
+    }
+}
+
+// ---------------------------------------------------------------- find0 --
+// One workgroup per layer, after the NSI passes: the first ranking digit.  For a layer on the
+// candidate path this is also the check of its bound: the recorded centres are usable only if
+// no tile slot overflowed, at least k_l were recorded (then the k_l best of the layer are all
+// among them) and the k_l-th does not lie in the open-ended top bin.  Otherwise the layer falls
+// back to the full map in this call (a flag tells the fallback kernels that there is work), goes
+// back to sampled bounds for the next few calls and widens the margin of its predictions.
+__global__ __launch_bounds__(256) void k_find0(const LayerDev *__restrict__ layers,
+                                               SelState *__restrict__ state,
+                                               uint32_t *__restrict__ hist,
+                                               uint32_t *__restrict__ flags,
+                                               PredState *__restrict__ pred /* nullable */) {
+    __shared__ uint32_t wave_tot[4];
+    __shared__ DigitResult res;
+    const int l = blockIdx.x, tid = threadIdx.x;
+    // state, layer constants and counts are requested together: one round trip to memory
+    // instead of three (each costs this one-workgroup-per-layer kernel about 2 us)
+    const SelState st = state[l];
+    const uint32_t large = layers[l].large;
+    uint32_t *__restrict__ h = hist + static_cast<size_t>(l) * kHistBins;
+    const bool cand = st.mode == kModeCandidates;                  // uniform
+    const int nb = cand ? kFineBins : kHistBins, per = nb >> 8;
+    const int hi = nb - tid * per;              // thread t owns bins [hi - per, hi): t = 0 holds the top bins
+    constexpr int kMaxPer = kHistBins / 256;
+    uint32_t v[kMaxPer];
+    uint32_t own = 0;
+#pragma unroll
+    for (int j = 0; j < kMaxPer; ++j) {
+        v[j] = j < per ? h[hi - 1 - j] : 0u;
+        own += v[j];
+    }
+    if (st.done || st.mode == kModeSkip) return;
+    // a large layer that is already on the full map (its sample gave no bound): its histogram
+    // comes with the fallback pass, and the select pass finds its first digit
+    if (st.mode == kModeFullMap && large != 0u) return;
+    if (tid == 0) res.found = 0;
+    const uint32_t incl = block_scan_incl(own, wave_tot);
+    const uint32_t excl = incl - own;
+    if (excl < st.k_rem && st.k_rem <= incl) {
+        uint32_t acc = excl;
+        bool hit = false;
+#pragma unroll
+        for (int j = 0; j < kMaxPer; ++j) {
+            if (!hit && j < per && acc + v[j] >= st.k_rem) {
+                res.digit = static_cast<uint32_t>(hi - 1 - j);
+                res.above = acc;
+                res.count = v[j];
+                res.found = 1;
+                hit = true;
+            }
+            if (!hit) acc += v[j];
+        }
+    }
+    __syncthreads();
+    const DigitResult r = res;
+    if (cand && (!r.found || st.overflow != 0u || r.digit == static_cast<uint32_t>(kFineBins - 1) ||
+                 st.hint_key == 0u)) {
+        for (int b = tid; b < kFineBins; b += 256) h[b] = 0;       // the fallback pass counts afresh
+        if (tid == 0) {
+            SelState ns = st;
+            ns.mode = kModeFullMap;
+            state[l] = ns;
+            flags[0] = 1u;                 // the fallback pass has work
+            PredState ps = pred[l];
+            ps.cooldown = kCooldownCalls;
+            ps.margin = fminf(2.f * (ps.margin > 0.f ? ps.margin : kMarginInitLog2), kMarginMaxLog2);
+            pred[l] = ps;
+        }
+        return;
+    }
+    if (tid == 0) {
+        SelState ns = st;
+        if (!r.found) {                    // fewer keys than k_l (cannot happen for finite input)
+            ns.done = 1;
+        } else {
+            const uint32_t shift = cand ? kFineShift : kCoarseShift;
+            ns.lo = (cand ? st.hint_key : 0u) + (r.digit << shift);
+            ns.span = shift;
+            ns.k_rem = st.k_rem - r.above;
+            ns.T = static_cast<unsigned long long>(ns.lo) << 32;
+            if (r.count == ns.k_rem) {     // whole bucket taken: the threshold is its lower edge
+                ns.done = 1;
+                publish_threshold(pred, l, large, ns.T);
+            }
+        }
+        state[l] = ns;
+    }
+}
+
+// --------------------------------------------------------------- gather --
+// After the first digit: the keys of each layer's threshold bucket (score bits in
+// [lo, lo + 2^span)) are copied into the layer's list and their next digit is histogrammed.
+// Three kinds of workgroups share the launch:
+//   [0, n_map_wgs)              stride over the plan's list of 8192-element score-map chunks
+//                               (layers that are always ranked on the full map);
+//   [n_map_wgs, +n_slot_wgs)    stride over the plan's list of slot groups (large layers,
+//                               where they are still in candidate mode);
+//   the last n_fb_wgs           only when some large layer fell back to the full map: they
+//                               walk all chunks and take those of such layers (and find the
+//                               first digit of such a layer themselves, from the histogram the
+//                               fallback pass has counted).
+// Matches are staged in LDS and appended with one atomic per flush.
+// (In-kernel hand-over of a finished layer to "the last workgroup" was measured and dropped:
+// the device-scope fences it needs write back the whole L2 of an XCD each time and cost more
+// than the launch they save.)
+constexpr int kStage = 2048;            // staged keys per workgroup (a round adds at most 1024)
+constexpr int kSlotsPerWave = kSlotGroup / 4;   // tile slots of a group that one wave of a gather workgroup takes
+
+struct GatherShared {
+    unsigned long long ent[kStage];     // staged keys
+    uint32_t hist[kLevel1Bins];         // second-digit counts
+    DigitResult res;
+    uint32_t n;                         // staged keys
+    uint32_t base;
+};
+
+struct GatherLists {
+    const DirEntry *chunk_dir;       // all chunks by layer (fallback walk)
+    const ChunkEntry *map_chunks;    // [n_map_chunks]
+    const GroupEntry *cand_groups;   // [n_cand_groups]
+    uint32_t n_layers, n_chunks, n_map_chunks, n_cand_groups;
+    uint32_t n_map_wgs, n_slot_wgs;  // the remaining workgroups are fallback walkers
+};
+
+struct GatherArgs {
+    const LayerDev *layers;
+    const SelState *state;
+    const uint32_t *keys;                 // score map
+    const uint32_t *slot_cnt;
+    const unsigned long long *slot_ent;
+    uint32_t *list_cnt;
+    unsigned long long *list_ent;
+    const uint32_t *hist;                 // first-digit counts (fallback layers)
+    uint32_t *hist1;                      // [n_layers][kLevel1Bins]
+    const uint32_t *flags;
+};
+
+// The list of the layer the workgroup is working on.
+struct GatherList {
+    uint32_t *cnt;                        // this workgroup's shard counter
+    unsigned long long *ent;              // ... and region
+    uint32_t cap;
+};
+
+// Appends the staged keys to the current layer's list.
+__device__ __forceinline__ void gather_flush_keys(GatherShared &sh, const GatherList &gl) {
+    __syncthreads();
+    const uint32_t n = sh.n;
+    if (n != 0) {                          // uniform
+        if (threadIdx.x == 0) sh.base = atomicAdd(gl.cnt, n);
+        __syncthreads();
+        const uint32_t base = sh.base;
+        for (uint32_t i = threadIdx.x; i < n; i += 256)
+            if (base + i < gl.cap) gl.ent[base + i] = sh.ent[i];
+        __syncthreads();
+        if (threadIdx.x == 0) sh.n = 0;
+    }
+    __syncthreads();
+}
+
+// One round of at most 1024 appends (4 per thread) is about to start: make room for it.
+__device__ __forceinline__ void gather_make_room(GatherShared &sh, const GatherList &gl) {
+    __syncthreads();                       // appends of the previous round are counted
+    if (sh.n + 1024u > static_cast<uint32_t>(kStage))            // uniform
+        gather_flush_keys(sh, gl);
+}
+
+// Stages key K (of a flagged lane) and counts its second digit.  Called by whole waves.
+__device__ __forceinline__ void gather_stage_key(GatherShared &sh, bool hit, unsigned long long K,
+                                                 uint32_t lo, uint32_t shift1) {
+    const uint32_t pos = wave_append(&sh.n, hit);
+    if (hit) {
+        sh.ent[pos] = K;
+        atomicAdd(&sh.hist[(static_cast<uint32_t>(K >> 32) - lo) >> shift1], 1u);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const GatherLists gl) {
+    __shared__ GatherShared sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // role 0: listed score-map chunks, 1: listed slot groups, 2: fallback walk over all chunks
+    const int role = blockIdx.x < gl.n_map_wgs ? 0 : blockIdx.x < gl.n_map_wgs + gl.n_slot_wgs ? 1 : 2;
+    const uint32_t first = role == 0 ? blockIdx.x : role == 1 ? blockIdx.x - gl.n_map_wgs
+                                                              : blockIdx.x - gl.n_map_wgs - gl.n_slot_wgs;
+    const uint32_t stride = role == 0 ? gl.n_map_wgs : role == 1 ? gl.n_slot_wgs
+                                                                 : gridDim.x - gl.n_map_wgs - gl.n_slot_wgs;
+    const uint32_t n_items = role == 0 ? gl.n_map_chunks : role == 1 ? gl.n_cand_groups : gl.n_chunks;
+    const DirEntry *__restrict__ dir = gl.chunk_dir;
+    if (first >= n_items) return;
+    if (role == 2 && a.flags[0] == 0u) return;
+    if (tid == 0) sh.n = 0;
+    for (int b = tid; b < kLevel1Bins; b += 256) sh.hist[b] = 0;
+    __syncthreads();
+
+    uint32_t e = role == 2 ? dir_lookup(dir, gl.n_layers, first) : 0u;
+    uint32_t cur_l = 0xffffffffu;
+    bool active = false;
+    uint32_t lo = 0, width = 0, shift1 = 0;   // the current layer's bucket [lo, lo + width) and its second digit's shift
+    LayerDev L;
+    GatherList list = {nullptr, nullptr, 0u};
+
+    for (uint32_t it = first; it < n_items; it += stride) {
+        uint32_t l;
+        ChunkEntry ce = {};
+        GroupEntry ge = {};
+        if (role == 0) {
+            ce = gl.map_chunks[it];
+            l = ce.layer;
+        } else if (role == 1) {
+            ge = gl.cand_groups[it];
+            l = ge.layer;
+        } else {
+            while (it >= dir[e + 1].begin) ++e;
+            l = dir[e].layer;
+        }
+        if (l != cur_l) {
+            if (active) {                  // uniform: the finished layer's keys and counts go out
+                gather_flush_keys(sh, list);
+                uint32_t *__restrict__ gh = a.hist1 + static_cast<size_t>(cur_l) * kLevel1Bins;
+                for (int b = tid; b < kLevel1Bins; b += 256) {
+                    const uint32_t cc = sh.hist[b];
+                    if (cc) { atomicAdd(&gh[b], cc); sh.hist[b] = 0; }
+                }
+                __syncthreads();
+            }
+            cur_l = l;
+            L = a.layers[l];
+            const SelState st = a.state[l];
+            active = !st.done && st.mode == (role == 1 ? kModeCandidates : kModeFullMap);
+            lo = st.lo;
+            width = 1u << st.span;
+            shift1 = st.span - kLevel1Bits;
+            if (role == 2) {
+                active = st.mode == kModeFullMap && L.large != 0u;      // the others are on the list
+                if (active) {              // uniform: first digit from the histogram of the fallback pass
+                    if (tid < 64) {
+                        const WaveBucket wb = wave_find_bucket(a.hist + static_cast<size_t>(l) * kHistBins, L.k);
+                        if (tid == 0) sh.res = DigitResult{wb.bucket, wb.above, wb.count, wb.found};
+                    }
+                    __syncthreads();
+                    const DigitResult r = sh.res;
+                    __syncthreads();
+                    lo = r.found ? r.digit << kCoarseShift : 0u;
+                    width = 1u << kCoarseShift;
+                    shift1 = kCoarseShift - kLevel1Bits;
+                    if (!r.found || r.count == L.k - r.above) active = false;   // nothing left to rank
+                }
+            }
+            // the workgroup's shard of the layer's list: its own counter (own cache line) and region
+            const uint32_t shard = blockIdx.x % L.list_shards;
+            list.cap = L.list_cap / L.list_shards;
+            list.cnt = a.list_cnt + (static_cast<size_t>(l) * kListShards + shard) * kListCntStride;
+            list.ent = a.list_ent + L.list_off + static_cast<size_t>(shard) * list.cap;
+        }
+        if (!active) {
+            if (role == 2) {               // on to this workgroup's first chunk of the next layer
+                const uint32_t nb = dir[e + 1].begin;
+                it += (nb - it + stride - 1) / stride * stride - stride;
+            }
+            continue;
+        }
+        if (role != 1) {
+            if (role == 2) {
+                ce.start = (it - L.chunk_begin) * kChunk;
+                ce.len = min(static_cast<uint32_t>(kChunk), L.G - ce.start);
+                ce.arena_off = static_cast<uint64_t>(L.elem_off) + ce.start;
+            }
+            const uint32_t start = ce.start, len = ce.len;
+            const uint32_t *__restrict__ src = a.keys + ce.arena_off;
+            // the whole chunk is requested before any of it is used
+            uint4 q[kChunk / 1024];
+#pragma unroll
+            for (int j = 0; j < kChunk / 1024; ++j) {
+                const uint32_t e4 = j * 1024 + 4 * tid;
+                q[j] = make_uint4(0, 0, 0, 0);
+                if (e4 + 3 < len) {
+                    q[j] = *reinterpret_cast<const uint4 *>(src + e4);
+                } else if (e4 < len) {
+                    q[j].x = src[e4];
+                    if (e4 + 1 < len) q[j].y = src[e4 + 1];
+                    if (e4 + 2 < len) q[j].z = src[e4 + 2];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kChunk / 1024; ++j) {
+                if (static_cast<uint32_t>(j) * 1024u >= len) break;       // uniform
+                gather_make_room(sh, list);
+                const uint32_t e4 = j * 1024 + 4 * tid;
+                const uint32_t kk[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
+#pragma unroll
+                for (uint32_t c = 0; c < 4; ++c) {
+                    const bool hit = e4 + c < len && (kk[c] & 0x7fffffffu) - lo < width;
+                    gather_stage_key(sh, hit, composite_key(kk[c], start + e4 + c), lo, shift1);
+                }
+            }
+        } else {
+            // each wave takes 4 of the group's tile slots; a round covers 64 entries of each
+            const uint32_t slot_cap = L.slot_cap;
+            const unsigned long long *__restrict__ ent0 =
+                a.slot_ent + L.slot_off + static_cast<size_t>(ge.slot0 - L.tile_begin_all) * slot_cap;
+            uint32_t cnt[kSlotsPerWave];
+            uint32_t longest = 0;
+#pragma unroll
+            for (int c = 0; c < kSlotsPerWave; ++c) {
+                const uint32_t s = static_cast<uint32_t>(wave) + 4u * c;
+                cnt[c] = s < ge.ntile ? min(a.slot_cnt[ge.slot0 + s], slot_cap) : 0u;
+                longest = max(longest, cnt[c]);
+            }
+            const int rounds = __syncthreads_or(longest > 64u) ? static_cast<int>(slot_cap / 64u) : 1;   // uniform
+            for (int rd = 0; rd < rounds; ++rd) {
+                const uint32_t j = 64u * rd + lane;
+                unsigned long long K[kSlotsPerWave];
+#pragma unroll
+                for (int c = 0; c < kSlotsPerWave; ++c)
+                    K[c] = j < cnt[c] ? ent0[static_cast<size_t>(wave + 4 * c) * slot_cap + j] : 0ull;
+                gather_make_room(sh, list);
+#pragma unroll
+                for (int c = 0; c < kSlotsPerWave; ++c) {
+                    const bool hit = j < cnt[c] && static_cast<uint32_t>(K[c] >> 32) - lo < width;
+                    gather_stage_key(sh, hit, K[c], lo, shift1);
+                }
+            }
+        }
+    }
+    if (active) {
+        gather_flush_keys(sh, list);
+        uint32_t *__restrict__ gh = a.hist1 + static_cast<size_t>(cur_l) * kLevel1Bins;
+        for (int b = tid; b < kLevel1Bins; b += 256) {
+            const uint32_t cc = sh.hist[b];
+            if (cc) atomicAdd(&gh[b], cc);
+        }
+    }
+}
+
+// --------------------------------------------------------------- finish --
+// One workgroup (1024 threads) per layer finishes the ranking: second digit from the layer's
+// histogram; if the k-th rank is still inside a bucket of several keys, the bucket's keys are
+// staged in LDS from the layer's list and the remaining score bits and -- only if equal
+// scores straddle the k-th rank -- the bits of ~index are resolved there, so that the lower
+// index wins.  Slow but exact routes: if the bucket's keys do not fit the stage, each further
+// digit streams the list again; if the list itself overflowed (a huge number of nearly equal
+// scores, e.g. an all-zero layer), each digit streams the layer's keys from the score map or
+// the tile slots.
+constexpr int kFinishThreads = 1024;
+constexpr int kFinishWaves = kFinishThreads / 64;
+
+__global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__restrict__ layers,
+                                                           SelState *__restrict__ state,
+                                                           const uint32_t *__restrict__ hist,
+                                                           const uint32_t *__restrict__ hist1,
                                                            const uint32_t *__restrict__ list_cnt,
                                                            const unsigned long long *__restrict__ list_ent,
-                                                           uint32_t *__restrict__ list2_cnt,
-                                                           unsigned long long *__restrict__ list2_ent) {
-    __shared__ unsigned long long stage[kList2Cap];
-    __shared__ uint32_t nstage, base;
-    const int l = blockIdx.x / kFilterSplit, part = blockIdx.x % kFilterSplit, tid = threadIdx.x;
+                                                           const uint32_t *__restrict__ keys,
+                                                           const uint32_t *__restrict__ slot_cnt,
+                                                           const unsigned long long *__restrict__ slot_ent,
+                                                           PredState *__restrict__ pred /* nullable */) {
+    __shared__ uint32_t lh[kLevel1Bins];
+    __shared__ unsigned long long sel[kStage];
+    __shared__ uint32_t wave_tot[kFinishWaves];
+    __shared__ DigitResult res;
+    __shared__ uint32_t nstage;
+    const int l = blockIdx.x, tid = threadIdx.x;
     // lane s of every wave reads shard s's counter (unused shards stay 0); issued with the other loads
     const uint32_t *__restrict__ cnt = list_cnt + static_cast<size_t>(l) * kListShards * kListCntStride;
     const uint32_t c = (tid & 63) < kListShards ? cnt[(tid & 63) * kListCntStride] : 0u;
     const SelState st = state[l];
     const LayerDev L = layers[l];
+    for (int b = tid; b < kLevel1Bins; b += kFinishThreads) lh[b] = hist1[static_cast<size_t>(l) * kLevel1Bins + b];
     if (st.done || st.mode == kModeSkip) return;
-    const uint32_t shards = L.list_shards, cap = L.list_cap / shards;
-    if (__ballot(c > cap)) return;         // the bucket did not fit: the finish streams the layer
-    // this workgroup's shard, and its share of that shard
-    const uint32_t shard = part % shards, sub = part / shards, nsub = (kFilterSplit + shards - 1 - shard) / shards;
-    const uint32_t n = __shfl(c, static_cast<int>(shard));
-    const unsigned long long *__restrict__ list = list_ent + L.list_off + static_cast<size_t>(shard) * cap;
-    if (tid == 0) nstage = 0;
     __syncthreads();
-    const unsigned long long want = st.T >> level_shift(1);
-    constexpr uint32_t U = 4;              // independent loads in flight per thread
-    for (uint32_t i0 = sub * U * kFinishThreads; i0 < n; i0 += nsub * U * kFinishThreads) {
-        unsigned long long K[U];
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u) {
-            const uint32_t i = i0 + u * kFinishThreads + tid;
-            K[u] = i < n ? list[i] : ~0ull;                    // ~0 never matches a prefix
+    uint32_t lo = st.lo, span = st.span, k_rem = st.k_rem;
+    if (st.mode == kModeFullMap && L.large != 0u) {
+        // a large layer that fell back to the full map: its first digit, as the gather pass found it
+        __shared__ uint32_t lh0[kHistBins];
+        for (int b = tid; b < kHistBins; b += kFinishThreads) lh0[b] = hist[static_cast<size_t>(l) * kHistBins + b];
+        __syncthreads();
+        const DigitResult r0 = block_find_digit<kFinishWaves>(lh0, kHistBins, L.k, wave_tot, &res);
+        lo = r0.found ? r0.digit << kCoarseShift : 0u;
+        span = kCoarseShift;
+        k_rem = r0.found ? L.k - r0.above : 0u;
+        if (!r0.found || r0.count == k_rem) {      // nothing left to rank
+            if (tid == 0) {
+                SelState ns = st;
+                ns.T = static_cast<unsigned long long>(lo) << 32;
+                ns.lo = lo;
+                ns.span = span;
+                ns.k_rem = k_rem;
+                ns.done = 1;
+                state[l] = ns;
+                publish_threshold(pred, l, L.large, ns.T);
+            }
+            return;
         }
-#pragma unroll
-        for (uint32_t u = 0; u < U; ++u)
-            if ((K[u] >> level_shift(1)) == want) {
-                const uint32_t pos = atomicAdd(&nstage, 1u);
-                if (pos < static_cast<uint32_t>(kList2Cap)) stage[pos] = K[u];
-            }
     }
-    __syncthreads();
-    const uint32_t m = nstage;
-    if (m == 0) return;                    // uniform
-    if (tid == 0) base = atomicAdd(&list2_cnt[l], m);          // counts past the capacity too
-    __syncthreads();
-    const uint32_t b0 = base;
-    for (uint32_t i = tid; i < min(m, static_cast<uint32_t>(kList2Cap)); i += kFinishThreads)
-        if (b0 + i < static_cast<uint32_t>(kList2Cap))
-            list2_ent[static_cast<size_t>(l) * kList2Cap + b0 + i] = stage[i];
-}
-
-// One workgroup (1024 threads) per layer finishes the radix select on the layer's second list
-// (staged in LDS): the remaining score digits and -- only if equal scores straddle the k-th
-// rank -- the digits of ~index, so that the lower index wins.
-// Slow but exact routes: if the second list overflowed, the later digits are histogrammed
-// from the threshold-bucket list; if that did not fit either (a huge number of nearly equal
-// scores, e.g. an all-zero layer), they are histogrammed by streaming the layer's keys from
-// the score map or the tile slots.
-constexpr int kFinishStage = kList2Cap;
-
-__global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__restrict__ layers,
-                                                           SelState *__restrict__ state,
-                                                           const uint32_t *__restrict__ list_cnt,
-                                                           const unsigned long long *__restrict__ list_ent,
-                                                           const uint32_t *__restrict__ list2_cnt,
-                                                           const unsigned long long *__restrict__ list2_ent,
-                                                           const uint32_t *__restrict__ keys,
-                                                           const uint32_t *__restrict__ slot_cnt,
-                                                           const unsigned long long *__restrict__ slot_ent) {
-    __shared__ uint32_t lh[2048];
-    __shared__ unsigned long long sel[kFinishStage];
-    __shared__ uint32_t wave_tot[kFinishThreads / 64];
-    __shared__ DigitResult res;
-    constexpr int NW = kFinishThreads / 64;
-    const int l = blockIdx.x, tid = threadIdx.x;
-    const uint32_t *__restrict__ cnt = list_cnt + static_cast<size_t>(l) * kListShards * kListCntStride;
-    const uint32_t c = (tid & 63) < kListShards ? cnt[(tid & 63) * kListCntStride] : 0u;   // as in k_filter
-    const uint32_t n2 = list2_cnt[l];
-    const SelState st = state[l];          // first two digits are fixed
-    const LayerDev L = layers[l];
-    if (st.done || st.mode == kModeSkip) return;
     const uint32_t shards = L.list_shards, cap = L.list_cap / shards;
-    const bool use_list = __ballot(c > cap) == 0;      // every shard of the threshold-bucket list fits
-    const unsigned long long *__restrict__ list = list_ent + L.list_off;
-    unsigned long long T = st.T;
-    uint32_t k_rem = st.k_rem;
-    bool done = false;
-    int lv = 2;
-    const uint32_t nsel = use_list ? n2 : 0xffffffffu;
-    const bool staged = nsel <= static_cast<uint32_t>(kFinishStage);
-    if (staged) {
-        for (uint32_t i = tid; i < nsel; i += kFinishThreads)
-            sel[i] = list2_ent[static_cast<size_t>(l) * kList2Cap + i];
-        __syncthreads();
+    const bool use_list = __syncthreads_and(c <= cap) != 0;      // every shard of the list fits
+    DigitResult r = block_find_digit<kFinishWaves>(lh, kLevel1Bins, k_rem, wave_tot, &res);
+    const uint32_t sh1 = span - kLevel1Bits;                     // score bits still open after this digit
+    unsigned long long T = static_cast<unsigned long long>(lo) << 32;
+    bool done = !r.found;                  // fewer keys than k_rem (cannot happen for finite input)
+    if (r.found) {
+        T += static_cast<unsigned long long>(r.digit) << (32 + sh1);
+        k_rem -= r.above;
+        done = r.count == k_rem;           // whole bucket taken: the threshold is its lower edge
     }
-    for (; lv < kLevels && !done; ++lv) {
-        const int shift = level_shift(lv), nb = 1 << level_bits(lv), shift_prev = level_shift(lv - 1);
-        for (int b = tid; b < nb; b += kFinishThreads) lh[b] = 0;
-        __syncthreads();
-        const unsigned long long want = T >> shift_prev;
-        if (staged) {
-            const uint32_t m = nsel;
-            for (uint32_t i = tid; i < m; i += kFinishThreads) {
-                const unsigned long long K = sel[i];
-                if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
-            }
-        } else if (use_list) {
+    if (!done) {
+        // Keys still in question: K - T < 2^(32 + sh1).  Their remaining bits are ranked as the
+        // number rel = K - T, most significant digit first.
+        const unsigned long long base = T;
+        const int top = 32 + static_cast<int>(sh1);
+        const unsigned long long *__restrict__ list = list_ent + L.list_off;
+        uint32_t nsel = 0xffffffffu;
+        if (use_list) {                    // stage the bucket's keys
+            if (tid == 0) nstage = 0;
+            __syncthreads();
             for (uint32_t s = 0; s < shards; ++s) {
-                const uint32_t n = cnt[s * kListCntStride];
+                const uint32_t n = __shfl(c, static_cast<int>(s));
                 const unsigned long long *__restrict__ part = list + static_cast<size_t>(s) * cap;
                 for (uint32_t i = tid; i < n; i += kFinishThreads) {
                     const unsigned long long K = part[i];
-                    if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
+                    if (K >= base && ((K - base) >> top) == 0ull) {
+                        const uint32_t pos = atomicAdd(&nstage, 1u);
+                        if (pos < static_cast<uint32_t>(kStage)) sel[pos] = K - base;
+                    }
                 }
             }
-        } else if (st.mode == kModeFullMap) {
-            const uint32_t *__restrict__ src = keys + L.elem_off;
-            for (uint32_t i = tid; i < L.G; i += kFinishThreads) {
-                const unsigned long long K = composite_key(src[i], i);
-                if ((K >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
-            }
-        } else {
-            for (uint32_t t = tid >> 8; t < L.n_tiles; t += kFinishThreads / 256) {
-                const uint32_t slot = L.tile_begin_all + t;
-                const uint32_t i = tid & 255;
-                if (i < slot_cnt[slot]) {
-                    const unsigned long long K = slot_ent[static_cast<size_t>(slot) * kSlotCap + i];
-                    if ((K >> shift_prev) == want)
-                        atomicAdd(&lh[static_cast<uint32_t>(K >> shift) & (nb - 1)], 1u);
-                }
-            }
+            __syncthreads();
+            nsel = nstage;
         }
-        __syncthreads();
-        const DigitResult r = block_find_digit<NW>(lh, nb, k_rem, wave_tot, &res);
-        if (!r.found) break;               // fewer keys than k_rem (cannot happen for finite input)
-        T |= static_cast<unsigned long long>(r.digit) << shift;
-        k_rem -= r.above;
-        done = r.count == k_rem;           // whole bucket taken: lower digits stay 0
+        const bool staged = nsel <= static_cast<uint32_t>(kStage);
+        unsigned long long Trel = 0;
+        int shift_prev = top;
+#pragma unroll 1
+        for (int lv = 0; lv < 4 && !done; ++lv) {
+            const int shift = lv == 0 ? 32 : lv == 1 ? 21 : lv == 2 ? 10 : 0;
+            const int nb = 1 << (shift_prev - shift);            // 2^sh1 (4 or 256), 2048, 2048, 1024
+            __syncthreads();
+            for (int b = tid; b < nb; b += kFinishThreads) lh[b] = 0;
+            __syncthreads();
+            const unsigned long long want = Trel >> shift_prev;
+#define RSDGC_COUNT_KEY(K_)                                                                         \
+    {                                                                                               \
+        const unsigned long long k_ = (K_);                                                         \
+        if (k_ >= base && ((k_ - base) >> shift_prev) == want)                                      \
+            atomicAdd(&lh[static_cast<uint32_t>((k_ - base) >> shift) & (nb - 1)], 1u);             \
+    }
+            if (staged) {
+                for (uint32_t i = tid; i < nsel; i += kFinishThreads) {
+                    const unsigned long long rel = sel[i];
+                    if ((rel >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(rel >> shift) & (nb - 1)], 1u);
+                }
+            } else if (use_list) {
+                for (uint32_t s = 0; s < shards; ++s) {
+                    const uint32_t n = __shfl(c, static_cast<int>(s));
+                    const unsigned long long *__restrict__ part = list + static_cast<size_t>(s) * cap;
+                    for (uint32_t i = tid; i < n; i += kFinishThreads) RSDGC_COUNT_KEY(part[i])
+                }
+            } else if (st.mode == kModeFullMap) {
+                const uint32_t *__restrict__ src = keys + L.elem_off;
+                for (uint32_t i = tid; i < L.G; i += kFinishThreads) RSDGC_COUNT_KEY(composite_key(src[i], i))
+            } else {
+                for (uint32_t t = tid >> 8; t < L.n_tiles; t += kFinishThreads / 256) {
+                    const uint32_t n = min(slot_cnt[L.tile_begin_all + t], L.slot_cap);
+                    const unsigned long long *__restrict__ ent = slot_ent + L.slot_off + static_cast<size_t>(t) * L.slot_cap;
+                    for (uint32_t i = tid & 255; i < n; i += 256) RSDGC_COUNT_KEY(ent[i])
+                }
+            }
+#undef RSDGC_COUNT_KEY
+            __syncthreads();
+            r = block_find_digit<kFinishWaves>(lh, nb, k_rem, wave_tot, &res);
+            if (!r.found) break;           // fewer keys than k_rem (cannot happen for finite input)
+            Trel |= static_cast<unsigned long long>(r.digit) << shift;
+            k_rem -= r.above;
+            done = r.count == k_rem;       // whole bucket taken: lower digits stay 0
+            shift_prev = shift;
+        }
+        T = base + Trel;
     }
     if (tid == 0) {
         SelState ns = st;
         ns.T = T;
         ns.k_rem = k_rem;
         ns.done = 1;
+        ns.lo = lo;
+        ns.span = span;
         state[l] = ns;
+        publish_threshold(pred, l, L.large, T);
     }
 }
 
@@ -1317,18 +1441,21 @@ __device__ __forceinline__ void mark_candidates(const LayerDev *__restrict__ lay
 #pragma unroll
         for (int c = 0; c < kSlotGroup / 4; ++c) {
             const uint32_t sl = wave + 4 * c;
-            cnt[c] = sl < ge.ntile ? min(slot_cnt[ge.slot0 + sl], static_cast<uint32_t>(kSlotCap)) : 0u;
+            cnt[c] = sl < ge.ntile ? min(slot_cnt[ge.slot0 + sl], L.slot_cap) : 0u;
         }
         uint32_t longest = 0;
 #pragma unroll
         for (int c = 0; c < kSlotGroup / 4; ++c) longest = max(longest, cnt[c]);   // wave-uniform
+        // the group's first slot inside the layer's slot array
+        const unsigned long long *__restrict__ ent0 =
+            slot_ent + L.slot_off + static_cast<size_t>(ge.slot0 - L.tile_begin_all) * L.slot_cap;
         for (uint32_t j0 = 0; j0 < longest; j0 += 64) {
             const uint32_t j = j0 + lane;
             unsigned long long K[kSlotGroup / 4];
 #pragma unroll
             for (int c = 0; c < kSlotGroup / 4; ++c) {
                 K[c] = 0;
-                if (j < cnt[c]) K[c] = slot_ent[static_cast<size_t>(ge.slot0 + wave + 4 * c) * kSlotCap + j];
+                if (j < cnt[c]) K[c] = ent0[static_cast<size_t>(wave + 4 * c) * L.slot_cap + j];
             }
 #pragma unroll
             for (int c = 0; c < kSlotGroup / 4; ++c) {
@@ -2362,6 +2489,7 @@ int upload_tables(rsdgc_plan_s *plan, void *workspace, hipStream_t stream) {
     if (plan->uploaded_ws == workspace && plan->uploaded_version == plan->version) return RSDGC_OK;
     HIP_TRY(hipMemcpyAsync(workspace, plan->table.data(), plan->ws.table_bytes,
                            hipMemcpyHostToDevice, stream));
+    plan->calls_since_upload = 0;
     plan->uploaded_ws = workspace;
     plan->uploaded_version = plan->version;
     return RSDGC_OK;
@@ -2395,6 +2523,7 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
     a.mom_out = mom.out;
     a.m = mom.m;
     a.flags = reinterpret_cast<const uint32_t *>(ws + plan->ws.flags);
+    a.hist_s = reinterpret_cast<uint32_t *>(ws + plan->ws.hist_s);
     a.layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
     a.grad = grad;
     a.resid = resid;
@@ -2495,14 +2624,14 @@ const char *rsdgc_last_hip_error(void) { return g_hip_error; }
 // The part of a compress call between the NSI passes and the emit: radix select of every
 // layer's threshold, marking of the kept elements, kept counts per chunk and chunk group.
 static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, StageMarks &marks,
-                             hipStream_t stream) {
+                             PredState *pred, hipStream_t stream) {
     const WsLayout &w = plan->ws;
     const int L = plan->n_layers;
     const uint32_t n_chunks = plan->n_chunks;
     const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + w.layers);
     const DirEntry *chunk_dir = reinterpret_cast<const DirEntry *>(ws + w.chunk_dir);
     SelState *state = reinterpret_cast<SelState *>(ws + w.state);
-    uint32_t *hist = reinterpret_cast<uint32_t *>(ws + w.hist);
+    const uint32_t *hist = reinterpret_cast<const uint32_t *>(ws + w.hist);
     uint32_t *flags = reinterpret_cast<uint32_t *>(ws + w.flags);
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
     uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
@@ -2513,18 +2642,24 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
     const uint32_t n_cand_groups = static_cast<uint32_t>(plan->cand_groups.size());
     const uint32_t *slot_cnt = reinterpret_cast<const uint32_t *>(ws + w.slot_cnt);
     const unsigned long long *slot_ent = reinterpret_cast<const unsigned long long *>(ws + w.slot_ent);
-    // radix select: first digit from the histograms of the NSI passes, then the keys of each
-    // layer's threshold bucket are gathered and one workgroup per layer finishes on them
+    // the keys of each layer's threshold bucket are gathered, then one workgroup per layer finishes
+    // the ranking on them
     {
-        uint32_t *list_cnt = reinterpret_cast<uint32_t *>(ws + w.list_cnt);
-        unsigned long long *list_ent = reinterpret_cast<unsigned long long *>(ws + w.list_ent);
-        hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(0),
-                           level_bits(0), 1);
+        GatherArgs a;
+        a.layers = layers;
+        a.state = state;
+        a.keys = reinterpret_cast<const uint32_t *>(nsi);
+        a.slot_cnt = slot_cnt;
+        a.slot_ent = slot_ent;
+        a.list_cnt = reinterpret_cast<uint32_t *>(ws + w.list_cnt);
+        a.list_ent = reinterpret_cast<unsigned long long *>(ws + w.list_ent);
+        a.hist = hist;
+        a.hist1 = reinterpret_cast<uint32_t *>(ws + w.hist1);
+        a.flags = flags;
         GatherLists gl;
         gl.chunk_dir = chunk_dir;
         gl.map_chunks = reinterpret_cast<const ChunkEntry *>(ws + w.map_chunks);
         gl.cand_groups = cand_groups;
-        gl.flags = flags;
         gl.n_layers = static_cast<uint32_t>(L);
         gl.n_chunks = n_chunks;
         gl.n_map_chunks = static_cast<uint32_t>(plan->map_chunks.size());
@@ -2533,18 +2668,9 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         gl.n_slot_wgs = std::min<uint32_t>(n_cand_groups, kNumCUs * 4u);
         const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(n_chunks, kNumCUs * 2u) : 0u;
         if (gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs > 0)
-            hipLaunchKernelGGL(k_gather, dim3(gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs), dim3(256), 0,
-                               stream, layers, gl, state, reinterpret_cast<const uint32_t *>(nsi),
-                               slot_cnt, slot_ent, list_cnt, list_ent, hist);
-        uint32_t *list2_cnt = reinterpret_cast<uint32_t *>(ws + w.list2_cnt);
-        unsigned long long *list2_ent = reinterpret_cast<unsigned long long *>(ws + w.list2_ent);
-        hipLaunchKernelGGL(k_find, dim3(L), dim3(256), 0, stream, state, hist, level_shift(1),
-                           level_bits(1), kHist1Copies);
-        hipLaunchKernelGGL(k_filter, dim3(L * kFilterSplit), dim3(kFinishThreads), 0, stream, layers,
-                           state, list_cnt, list_ent, list2_cnt, list2_ent);
-        hipLaunchKernelGGL(k_finish, dim3(L), dim3(kFinishThreads), 0, stream, layers, state, list_cnt,
-                           list_ent, list2_cnt, list2_ent, reinterpret_cast<const uint32_t *>(nsi),
-                           slot_cnt, slot_ent);
+            hipLaunchKernelGGL(k_gather, dim3(gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs), dim3(256), 0, stream, a, gl);
+        hipLaunchKernelGGL(k_finish, dim3(L), dim3(kFinishThreads), 0, stream, layers, state, hist, a.hist1,
+                           a.list_cnt, a.list_ent, a.keys, slot_cnt, slot_ent, pred);
     }
     HIP_TRY(hipGetLastError());
     marks.close(4);
@@ -2604,12 +2730,16 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     const uint32_t n_chunks = plan->n_chunks;
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
+    // the first calls with a workspace (the thresholds have no history yet, or still move fast) may
+    // take candidate bounds from a sample of the call's own scores
+    const bool sampling = plan->any_large && plan->calls_since_upload < kSamplingCalls;
+    if (plan->calls_since_upload < kSamplingCalls) ++plan->calls_since_upload;
 
     const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + w.layers);
     SelState *state = reinterpret_cast<SelState *>(ws + w.state);
     uint32_t *hist = reinterpret_cast<uint32_t *>(ws + w.hist);
     uint32_t *flags = reinterpret_cast<uint32_t *>(ws + w.flags);
-    uint32_t *penalty = reinterpret_cast<uint32_t *>(ws + w.penalty);
+    PredState *pred = reinterpret_cast<PredState *>(ws + w.pred);
     uint32_t *chunk_cnt = reinterpret_cast<uint32_t *>(ws + w.chunk_cnt);
     uint32_t *chunk_ccnt = reinterpret_cast<uint32_t *>(ws + w.chunk_ccnt);
     const uint32_t *group_cnt = reinterpret_cast<const uint32_t *>(ws + w.group_cnt);
@@ -2625,32 +2755,35 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
         const size_t n16 = (end - w.zero_begin) / 16;
         const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
         hipLaunchKernelGGL(k_begin, dim3(blocks + 1), dim3(256), 0, stream,
-                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, layers, state, L, penalty);
+                           reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, layers, state, L, pred, flags,
+                           sampling ? 1 : 0);
         HIP_TRY(hipGetLastError());
     }
     marks.close(0);
 
-    // first pass: the sampled tiles of the large layers (histogram only) and every tile of the
-    // other layers (scores, histogram, v) share one launch
+    // first pass: every tile of the layers ranked on the full map (scores, histogram, v) and, where a
+    // large layer has no predicted bound, its sampled tiles (histogram only) share one launch
     rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
     if (rc != RSDGC_OK) return rc;
+    if (sampling)
+        hipLaunchKernelGGL(k_hint, dim3(L), dim3(64), 0, stream, layers, state,
+                           reinterpret_cast<const uint32_t *>(ws + w.hist_s), flags);
+    marks.close(1);
     if (plan->any_large) {
-        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state, hist, flags, penalty);
-        marks.close(1);
         rc = launch_nsi<kPassCapture>(plan, ws, grad, residual, nsi, v_out, mom, stream);
         if (rc != RSDGC_OK) return rc;
-        hipLaunchKernelGGL(k_validate, dim3(L), dim3(256), 0, stream, layers, state, hist, flags, penalty);
-        marks.close(2);
-        // large layers whose candidate bound failed (rare): their workgroups find nothing to do otherwise
+    }
+    marks.close(2);
+    // first ranking digit of every layer, and whether the candidate bounds held
+    hipLaunchKernelGGL(k_find0, dim3(L), dim3(256), 0, stream, layers, state, hist, flags, pred);
+    if (plan->any_large) {
+        // large layers whose candidate bound failed (rare): the workgroups find nothing to do otherwise
         rc = launch_nsi<kPassFullMap>(plan, ws, grad, residual, nsi, v_out, mom, stream);
         if (rc != RSDGC_OK) return rc;
-    } else {
-        marks.close(1);
-        marks.close(2);
     }
     marks.close(3);
 
-    rc = select_mark_count(plan, ws, want_centres, marks, stream);
+    rc = select_mark_count(plan, ws, want_centres, marks, pred, stream);
     if (rc != RSDGC_OK) return rc;
     const ChunkInfo *chunk_info = reinterpret_cast<const ChunkInfo *>(ws + w.chunk_info);
     if (in_place)
@@ -2800,7 +2933,8 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
         const unsigned blocks = static_cast<unsigned>(std::min<size_t>((n16 + 255) / 256, 4096));
         hipLaunchKernelGGL(k_begin, dim3(blocks + 1), dim3(256), 0, stream,
                            reinterpret_cast<uint4 *>(ws + w.zero_begin), n16, inner, state, L,
-                           static_cast<uint32_t *>(nullptr));   // a block grid is always ranked on its full map
+                           static_cast<PredState *>(nullptr),    // a block grid is always ranked on its full map
+                           reinterpret_cast<uint32_t *>(ws + w.flags), 0);
     }
     bool have[RSDGC_MAX_P + 1] = {};
     for (int l = 0; l < L; ++l) have[plan->p[l]] = true;
@@ -2840,7 +2974,9 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
         }
     }
     HIP_TRY(hipGetLastError());
-    rc = select_mark_count(in, ws, false, marks, stream);
+    hipLaunchKernelGGL(k_find0, dim3(L), dim3(256), 0, stream, inner, state, hist,
+                       reinterpret_cast<uint32_t *>(ws + w.flags), static_cast<PredState *>(nullptr));
+    rc = select_mark_count(in, ws, false, marks, nullptr, stream);
     if (rc != RSDGC_OK) return rc;
     hipLaunchKernelGGL(k_emit_blocks, dim3(in->n_chunks), dim3(256), 0, stream, outer, inner_chunks, mask,
                        chunk_cnt, group_cnt, inner, residual_out, out_block_idx, out_val, out_counts);
@@ -2979,7 +3115,7 @@ int rsdgc_dynamic_ratios(rsdgc_plan_t *plan, const float *weights, double global
                        static_cast<uint32_t>(2 * L), K);
     int prev_shift = 31;
     for (int lv = 0; lv < 3; ++lv) {                    // 12 + 10 + 9 bits of the 31-bit key
-        const int bits = level_bits(lv), shift = level_shift(lv) - 32;
+        const int bits = lv == 0 ? 12 : lv == 1 ? 10 : 9, shift = lv == 0 ? 19 : lv == 1 ? 9 : 0;
         hipLaunchKernelGGL(k_dyn_hist, dim3(grid), dim3(256), 0, stream, chunk_info, n_chunks, keys,
                            state, shift, bits, prev_shift, hist);
         hipLaunchKernelGGL(k_dyn_find, dim3(1), dim3(256), 0, stream, state, hist, bits);
@@ -3023,7 +3159,8 @@ int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, 
     HIP_TRY(hipStreamSynchronize(stream));
     HIP_TRY(hipMemcpy(host.data(), static_cast<const char *>(workspace) + plan->ws.state,
                       sizeof(SelState) * plan->n_layers, hipMemcpyDeviceToHost));
-    for (int l = 0; l < plan->n_layers; ++l) paths[l] = static_cast<int32_t>(host[l].mode);
+    for (int l = 0; l < plan->n_layers; ++l)
+        paths[l] = host[l].mode == kModeCandidates && host[l].predicted ? 3 : static_cast<int32_t>(host[l].mode);
     return RSDGC_OK;
 }
 
@@ -3080,7 +3217,7 @@ int rsdgc_profile_end(rsdgc_plan_t *plan, double *stage_ms, int32_t *n_calls) {
 }
 
 const char *rsdgc_stage_name(int32_t stage) {
-    static const char *names[RSDGC_N_STAGES] = {"clear", "first_pass", "capture", "fallback_map", "select",
+    static const char *names[RSDGC_N_STAGES] = {"clear", "first_pass", "capture", "find0_fallback", "select",
                                                 "mark", "count_scan", "emit", "centres"};
     return (stage >= 0 && stage < RSDGC_N_STAGES) ? names[stage] : "";
 }

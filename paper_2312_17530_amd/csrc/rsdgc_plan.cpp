@@ -68,7 +68,7 @@ int build_tables(rsdgc_plan_s *plan) {
         d.tile_begin_all = tile_begin_all;
         d.group_begin = group_begin;
         d.n_groups = (d.n_tiles + kSlotGroup - 1) / kSlotGroup;
-        d.list_off = static_cast<uint32_t>(list_off);
+        d.list_off = list_off;
         // a block grid is ranked on its full score map whatever its size: its threshold bucket may hold
         // a large part of a large layer, so the list takes all of it (else 1/32, see kListDiv)
         d.list_cap = plan->k_override.empty()
@@ -79,20 +79,24 @@ int build_tables(rsdgc_plan_s *plan) {
         d.list_shards = plan->k_override.empty() ? kListShards : 1;
         list_off += d.list_cap;
 
-        // Candidate path: the bound comes from the scores of a sample of the layer's tiles.
-        // It is taken where about twice k_l centres are expected above the bound; a layer is
-        // eligible when it has enough sampled tiles for that estimate and when the expected
-        // number of candidates per tile (2 k_l / tiles, at most 57) leaves a factor 4.5 of room
-        // in a tile's slot (kSlotCap); a tile that still overflows sends the layer to the full map.
+        // Candidate path: only the centres whose score reaches a bound are recorded, per tile, and
+        // ranked.  The bound aims at a few times k_l centres; a layer is eligible when a sample of
+        // its tiles can estimate such a bound (first calls) and when 16 k_l / tiles -- eight times
+        // the aim of 2 k_l, for tiles that hold more than their share -- fits a tile's slot, which
+        // has kSlotCap entries, or kSlotCapMax where the keep ratio asks for it.  A tile that
+        // still overflows sends the layer to the full map for that call.
         uint32_t n_sampled = 0;
         const uint32_t sshift = sample_shift(d.n_tiles);
         for (uint32_t t = 0; t < d.n_tiles; ++t) n_sampled += tile_is_sampled(t, sshift) ? 1u : 0u;
         d.n_sampled = n_sampled;
         const double frac = d.n_tiles ? double(n_sampled) / double(d.n_tiles) : 0.0;
         const double want = 2.0 * double(k) * frac;
-        const double per_tile = d.n_tiles ? 3.0 * double(k) / double(d.n_tiles) : 0.0;
+        const double per_tile = d.n_tiles ? 16.0 * double(k) / double(d.n_tiles) : 0.0;
         d.large = (plan->allow_candidates && k > 0 && n_sampled >= uint32_t(kMinSampledTiles) &&
-                   per_tile <= kSlotCap / 3.0) ? 1u : 0u;
+                   per_tile <= double(kSlotCapMax)) ? 1u : 0u;
+        d.slot_cap = per_tile <= double(kSlotCap) ? kSlotCap : kSlotCapMax;
+        d.slot_off = static_cast<uint64_t>(tile_begin_all) * kSlotCapMax;   // (room for either size: the
+                                                                            // layout does not move with the ratios)
         d.hint_target = d.large ? static_cast<uint32_t>(std::ceil(want + 4.0 * std::sqrt(want) + 8.0)) : 0u;
         plan->any_large = plan->any_large || d.large;
 
@@ -193,26 +197,30 @@ int build_tables(rsdgc_plan_s *plan) {
     w.map_chunks = off;   off = align_up(off + sizeof(ChunkEntry) * plan->n_chunks, A);
     w.map_tiles = off;    off = align_up(off + sizeof(SampleEntry) * (size_t(plan->n_tiles_all) + 1), A);
     w.count_groups = off; off = align_up(off + sizeof(CountGroup) * plan->n_count_groups, A);
-    w.penalty = off;      off = align_up(off + sizeof(uint32_t) * L, A);
+    w.pred = off;         off = align_up(off + sizeof(PredState) * L, A);
     w.table_bytes = off;
     w.state = off;        off = align_up(off + sizeof(SelState) * L, A);   // written in full each call
+    w.flags = off;        off = align_up(off + sizeof(uint32_t) * 64, A);
     w.zero_begin = off;
     w.hist = off;         off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
+    w.hist_s = off;       off = align_up(off + sizeof(uint32_t) * kHistBins * L, A);
+    w.hist1 = off;        off = align_up(off + sizeof(uint32_t) * kLevel1Bins * L, A);
     w.chunk_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.group_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
     w.group_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
     w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * kListShards * kListCntStride * size_t(L), A);
-    w.list2_cnt = off;    off = align_up(off + sizeof(uint32_t) * L, A);
     w.feed = off;         off = align_up(off + sizeof(uint32_t) * 16 * 8 * 32, A);
-    w.flags = off;        off = align_up(off + sizeof(uint32_t) * 64, A);
     w.mask = off;         off = align_up(off + sizeof(uint32_t) * words, A);
     w.cmask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
     w.zero_end = off;
     w.slot_cnt = off;     off = align_up(off + sizeof(uint32_t) * plan->n_tiles_all, A);
-    w.slot_ent = off;     off = align_up(off + sizeof(uint64_t) * kSlotCap * size_t(plan->n_tiles_all), A);
+    // (the plan of a block grid never takes the candidate path and has no tile slots)
+    w.slot_ent = off;     off = align_up(off + (plan->k_override.empty() ? sizeof(uint64_t) * kSlotCapMax * size_t(plan->n_tiles_all) : 0), A);
     w.list_ent = off;     off = align_up(off + sizeof(uint64_t) * static_cast<size_t>(list_off), A);
-    w.list2_ent = off;    off = align_up(off + sizeof(uint64_t) * kList2Cap * size_t(L), A);
+    // the score map covers every layer: which layers are ranked on it depends on the keep ratios
+    // (set_ratios must not change the workspace size), and any large layer may fall back to it in
+    // any call, several of them in the same one
     w.nsi = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
     w.dyn = off;          off = align_up(off + 256 + sizeof(uint64_t) * kHistBins + sizeof(uint32_t) * 2 * size_t(L), A);
     w.acc = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);

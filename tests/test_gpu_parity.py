@@ -836,10 +836,13 @@ def test_candidate_path_falls_back_when_its_bound_fails(in_place):
             assert n == 6 and ex >= 5
 
 
-def test_a_layer_whose_bound_failed_stays_on_the_full_map_for_eight_calls():
-    """After a call in which a large layer's candidate bound failed, the library starts that
-    layer on the full map for the next eight calls with the same workspace (no wasted main pass
-    over it) and tries the candidate path again in the ninth.  Every call gives the oracle's result."""
+def test_candidate_bound_is_predicted_from_earlier_calls_and_recovers_from_failures():
+    """The first calls of a large layer take a bound sampled from that call's scores (path 0); once
+    two thresholds lie close together the bound is predicted from them (path 3) and no tile is
+    sampled.  A call whose bound fails -- here an input with thousands of winners in one tile, and
+    a gradient that suddenly shrinks so that the predicted bound lies above everything -- is redone
+    through the full map within the call (path 1) and the layer goes back to sampled bounds for a
+    few calls; it is never parked on the full map.  Every call gives the oracle's result."""
     import torch
     from paper_2312_17530_amd import binding
     R, C = 512, 4608
@@ -850,31 +853,73 @@ def test_a_layer_whose_bound_failed_stays_on_the_full_map_for_eight_calls():
     other = (rng.standard_normal((R, C)) * 1e-3).astype(np.float32)
     shapes, ratios = [(R, C), (R, C)], [0.02, 0.02]
     sess = _session(shapes, 3, 0.5, ratios)
+    zero = [np.zeros((R, C), np.float32)] * 2
 
-    def call(grads, check):
+    def call(grads, tag):
         sess.set_grad(grads)
-        sess.set_residual([np.zeros((R, C), np.float32)] * 2)
+        sess.set_residual(zero)
         sess.compress()
         torch.cuda.synchronize()
         paths = binding.rsdgc_last_paths(sess.plan, sess.workspace)
-        if check:
-            res = sess.results()
-            gpu_r = sess.unpack(sess.residual)
-            for l in range(2):
-                o = oracle.compress_layer(grads[l], np.zeros((R, C), np.float32), 3, 0.5, ratios[l])
-                gi, gv, gc, gn = res[l]
-                assert parity.check_layer(f"penalty[l={l}]", shapes[l], 3, o.k, o.tau, o.nsi, o.centres, o.idx,
-                                          o.val, o.r_new, o.v, gi, gv, gc, gn, gpu_r[l])
+        res = sess.results()
+        gpu_r = sess.unpack(sess.residual)
+        for l in range(2):
+            o = oracle.compress_layer(grads[l], zero[l], 3, 0.5, ratios[l])
+            gi, gv, gc, gn = res[l]
+            assert parity.check_layer(f"{tag}[l={l},path={paths[l]}]", shapes[l], 3, o.k, o.tau, o.nsi, o.centres,
+                                      o.idx, o.val, o.r_new, o.v, gi, gv, gc, gn, gpu_r[l])
         return list(paths)
 
-    assert call([hot_tile, other], True) == [1, 0]         # fails, redone through the full map
-    for i in range(8):                                     # benign input now, but the layer sits out
-        assert call([base, other], i in (0, 7)) == [1, 0], i
-    assert call([base, other], True) == [0, 0]             # the ninth call tries the bound again
+    assert call([base, other], "first") == [0, 0]          # no history: sampled bounds
+    assert call([base, other], "second") == [0, 0]         # one threshold is not a trend
+    assert call([base, other], "third") == [3, 3]          # two equal thresholds: predicted
+    assert call([hot_tile, other], "hot tile") == [1, 3]   # slots overflow: redone through the full map
+    seen = [call([base, other], f"after failure {i}") for i in range(6)]
+    assert all(p[1] == 3 for p in seen)
+    assert all(p[0] in (0, 3) for p in seen), "a layer whose bound failed is not parked on the full map"
+    assert seen[0][0] == 0 and seen[-1][0] == 3            # sampled for a few calls, then predicted again
+    # the gradient shrinks tenfold from one call to the next: the predicted bound lies far too high
+    small = [g * np.float32(0.1) for g in (base, other)]
+    assert call(small, "shrunk") == [1, 1]
+    assert call(small, "shrunk again") == [0, 0]
+    # and grows a hundredfold: the bound is far too low, every tile overflows -- or the sample decides
+    big = [g * np.float32(10.0) for g in (base, other)]
+    for i in range(8):
+        paths = call(big if i % 2 == 0 else small, f"alternating {i}")
+        assert all(p in (0, 1, 3) for p in paths)
     binding.rsdgc_plan_forget_workspace(sess.plan)         # a prepared-again workspace starts afresh
-    assert call([hot_tile, other], False) == [1, 0]
-    binding.rsdgc_plan_forget_workspace(sess.plan)
-    assert call([base, other], True) == [0, 0]
+    assert call([base, other], "fresh workspace") == [0, 0]
+
+
+def test_thirty_calls_from_a_zero_residual_hardly_ever_fall_back():
+    """The benchmark's situation: the same workspace over many calls while the residual builds up
+    from zero (the VGG-19 recipe on matrices clipped to 1024 x 4608, so that every large layer
+    keeps its tile structure).  With the same gradient every call the threshold grows fast at
+    first and ever more slowly later; with a fresh gradient every call it grows like a random
+    walk.  At most one call of one layer may need the full map in either run."""
+    import torch
+    from paper_2312_17530_amd import binding
+    w = synth.scaled_down(synth.config(3), 1024, 4608)
+    for fresh in (False, True):
+        sess = _session(w.shapes, w.p, w.alpha, w.ratios)
+        g0 = synth.gradients(w, 0)
+        sess.set_grad(g0)
+        history = []
+        for t in range(30):
+            if fresh and t > 0:
+                sess.set_grad(synth.gradients(w, t))
+            sess.compress()
+            torch.cuda.synchronize()
+            history.append(binding.rsdgc_last_paths(sess.plan, sess.workspace))
+        large = [l for l in range(w.n_layers) if any(h[l] in (0, 3) for h in history)]
+        assert len(large) >= 8
+        fallbacks = [(t, l) for t, h in enumerate(history) for l in large if h[l] == 1]
+        assert len(fallbacks) <= 1, f"fresh={fresh}: {fallbacks}"
+        # (with the same gradient every call the threshold still moves by more than the prediction
+        # accepts until about the thirteenth call)
+        predicted = sum(1 for h in history[10:] for l in large if h[l] == 3)
+        assert predicted >= 0.7 * 20 * len(large), f"fresh={fresh}: bounds are still sampled late in the run"
+        assert all(h[l] == 3 for h in history[20:] for l in large), f"fresh={fresh}"
 
 
 def test_set_ratios_and_determinism():
