@@ -871,6 +871,36 @@ __device__ __forceinline__ void publish_threshold(PredState *__restrict__ pred, 
     pred[l] = ps;
 }
 
+// Set nbits (<= RSDGC_MAX_P) consecutive mask bits starting at bit position pos.
+__device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos, uint32_t nbits) {
+    const size_t w = pos >> 5;
+    const uint32_t b = static_cast<uint32_t>(pos & 31);
+    const uint32_t bits = (1u << nbits) - 1u;
+    atomicOr(&mask[w], bits << b);
+    if (b + nbits > 32) atomicOr(&mask[w + 1], bits >> (32 - b));
+}
+
+// A selected centre (flat index i inside its layer) ORs the bits of its p x p window into the
+// (cleared) mask -- Section III-C: whole neighbourhoods are kept -- and its own bit into the
+// centre mask when centre lists are wanted.  The words touched by different centres are nearly
+// all distinct, which is the case global atomics handle well.
+struct WindowGeom {
+    size_t elem_off;
+    int R, C, h;
+};
+__device__ __forceinline__ void mark_window(const WindowGeom &g, uint32_t i, uint32_t *__restrict__ mask,
+                                            uint32_t *__restrict__ cmask) {
+    const int xc = static_cast<int>(i / static_cast<uint32_t>(g.C));
+    const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * static_cast<uint32_t>(g.C));
+    const int ylo = max(0, yc - g.h), yhi = min(g.C - 1, yc + g.h);
+    for (int x = max(0, xc - g.h); x <= min(g.R - 1, xc + g.h); ++x)
+        set_bits(mask, g.elem_off + static_cast<size_t>(x) * g.C + ylo, static_cast<uint32_t>(yhi - ylo + 1));
+    if (cmask) {
+        const size_t pos = g.elem_off + i;
+        atomicOr(&cmask[pos >> 5], 1u << (pos & 31));
+    }
+}
+
 // ----------------------------------------------------------------- hint --
 // First calls with a workspace only: one wave per large layer that has no predicted bound turns
 // the layer's sampled scores into its candidate bound.  A layer whose sample gives none goes to
@@ -995,7 +1025,12 @@ __global__ __launch_bounds__(256) void k_find0(const LayerDev *__restrict__ laye
 //                               walk all chunks and take those of such layers (and find the
 //                               first digit of such a layer themselves, from the histogram the
 //                               fallback pass has counted).
-// Matches are staged in LDS and appended with one atomic per flush.
+// Matches from the score map are staged in LDS and appended with one atomic per flush.
+// The recorded candidates of a large layer are nearly all decided by the first digit already
+// (its bins are fine: the threshold bucket holds a per cent or two of them): a candidate above
+// the bucket is selected whatever the later digits say, so its window is marked here and now
+// (k_mark marks the few that the bucket contributes); one in the bucket is appended to the
+// list straight away, one atomic per wave, without staging or barriers.
 // (In-kernel hand-over of a finished layer to "the last workgroup" was measured and dropped:
 // the device-scope fences it needs write back the whole L2 of an XCD each time and cost more
 // than the launch they save.)
@@ -1029,6 +1064,7 @@ struct GatherArgs {
     const uint32_t *hist;                 // first-digit counts (fallback layers)
     uint32_t *hist1;                      // [n_layers][kLevel1Bins]
     const uint32_t *flags;
+    uint32_t *mask, *cmask;               // kept-element bitmask; selected-centre bitmask (nullable)
 };
 
 // The list of the layer the workgroup is working on.
@@ -1092,6 +1128,7 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
     uint32_t cur_l = 0xffffffffu;
     bool active = false;
     uint32_t lo = 0, width = 0, shift1 = 0;   // the current layer's bucket [lo, lo + width) and its second digit's shift
+    uint32_t above = 0;                       // candidate layers: scores from here on are selected for certain
     LayerDev L;
     GatherList list = {nullptr, nullptr, 0u};
 
@@ -1126,6 +1163,13 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
             lo = st.lo;
             width = 1u << st.span;
             shift1 = st.span - kLevel1Bits;
+            if (role == 1) {
+                // candidates: everything at or above `above` is selected for certain.  A layer whose
+                // first digit already settled the ranking (done) has its threshold at lo.
+                active = st.mode == kModeCandidates;
+                above = st.done ? static_cast<uint32_t>(st.T >> 32) : lo + width;
+                if (st.done) width = 0;
+            }
             if (role == 2) {
                 active = st.mode == kModeFullMap && L.large != 0u;      // the others are on the list
                 if (active) {              // uniform: first digit from the histogram of the fallback pass
@@ -1163,30 +1207,34 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
             }
             const uint32_t start = ce.start, len = ce.len;
             const uint32_t *__restrict__ src = a.keys + ce.arena_off;
-            // the whole chunk is requested before any of it is used
-            uint4 q[kChunk / 1024];
+            // half a chunk is requested before any of it is used
+            constexpr int NQ = kChunk / 2048;
+#pragma unroll 1
+            for (uint32_t half = 0; half < 2u && half * (kChunk / 2) < len; ++half) {
+                uint4 q[NQ];
 #pragma unroll
-            for (int j = 0; j < kChunk / 1024; ++j) {
-                const uint32_t e4 = j * 1024 + 4 * tid;
-                q[j] = make_uint4(0, 0, 0, 0);
-                if (e4 + 3 < len) {
-                    q[j] = *reinterpret_cast<const uint4 *>(src + e4);
-                } else if (e4 < len) {
-                    q[j].x = src[e4];
-                    if (e4 + 1 < len) q[j].y = src[e4 + 1];
-                    if (e4 + 2 < len) q[j].z = src[e4 + 2];
+                for (int j = 0; j < NQ; ++j) {
+                    const uint32_t e4 = half * (kChunk / 2) + j * 1024 + 4 * tid;
+                    q[j] = make_uint4(0, 0, 0, 0);
+                    if (e4 + 3 < len) {
+                        q[j] = *reinterpret_cast<const uint4 *>(src + e4);
+                    } else if (e4 < len) {
+                        q[j].x = src[e4];
+                        if (e4 + 1 < len) q[j].y = src[e4 + 1];
+                        if (e4 + 2 < len) q[j].z = src[e4 + 2];
+                    }
                 }
-            }
 #pragma unroll
-            for (int j = 0; j < kChunk / 1024; ++j) {
-                if (static_cast<uint32_t>(j) * 1024u >= len) break;       // uniform
-                gather_make_room(sh, list);
-                const uint32_t e4 = j * 1024 + 4 * tid;
-                const uint32_t kk[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
+                for (int j = 0; j < NQ; ++j) {
+                    const uint32_t e4 = half * (kChunk / 2) + j * 1024 + 4 * tid;
+                    if (half * (kChunk / 2) + static_cast<uint32_t>(j) * 1024u >= len) break;       // uniform
+                    gather_make_room(sh, list);
+                    const uint32_t kk[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
 #pragma unroll
-                for (uint32_t c = 0; c < 4; ++c) {
-                    const bool hit = e4 + c < len && (kk[c] & 0x7fffffffu) - lo < width;
-                    gather_stage_key(sh, hit, composite_key(kk[c], start + e4 + c), lo, shift1);
+                    for (uint32_t c = 0; c < 4; ++c) {
+                        const bool hit = e4 + c < len && (kk[c] & 0x7fffffffu) - lo < width;
+                        gather_stage_key(sh, hit, composite_key(kk[c], start + e4 + c), lo, shift1);
+                    }
                 }
             }
         } else {
@@ -1200,20 +1248,34 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
             for (int c = 0; c < kSlotsPerWave; ++c) {
                 const uint32_t s = static_cast<uint32_t>(wave) + 4u * c;
                 cnt[c] = s < ge.ntile ? min(a.slot_cnt[ge.slot0 + s], slot_cap) : 0u;
-                longest = max(longest, cnt[c]);
+                longest = max(longest, cnt[c]);                     // wave-uniform
             }
-            const int rounds = __syncthreads_or(longest > 64u) ? static_cast<int>(slot_cap / 64u) : 1;   // uniform
-            for (int rd = 0; rd < rounds; ++rd) {
-                const uint32_t j = 64u * rd + lane;
+            const WindowGeom geom = {static_cast<size_t>(L.elem_off), static_cast<int>(L.R), static_cast<int>(L.C),
+                                     (static_cast<int>(L.p) - 1) / 2};
+            for (uint32_t j0 = 0; j0 < longest; j0 += 64) {
+                const uint32_t j = j0 + lane;
                 unsigned long long K[kSlotsPerWave];
 #pragma unroll
                 for (int c = 0; c < kSlotsPerWave; ++c)
                     K[c] = j < cnt[c] ? ent0[static_cast<size_t>(wave + 4 * c) * slot_cap + j] : 0ull;
-                gather_make_room(sh, list);
 #pragma unroll
                 for (int c = 0; c < kSlotsPerWave; ++c) {
-                    const bool hit = j < cnt[c] && static_cast<uint32_t>(K[c] >> 32) - lo < width;
-                    gather_stage_key(sh, hit, K[c], lo, shift1);
+                    const uint32_t score = static_cast<uint32_t>(K[c] >> 32);
+                    const bool valid = j < cnt[c];
+                    if (valid && score >= above) mark_window(geom, ~static_cast<uint32_t>(K[c]), a.mask, a.cmask);
+                    const bool hit = valid && score < above && score - lo < width;    // (never when the layer is done)
+                    const unsigned long long m = __ballot(hit);
+                    if (m != 0ull) {       // wave-uniform
+                        const uint32_t leader = static_cast<uint32_t>(__ffsll(static_cast<long long>(m))) - 1u;
+                        uint32_t base = 0;
+                        if (static_cast<uint32_t>(lane) == leader) base = atomicAdd(list.cnt, static_cast<uint32_t>(__popcll(m)));
+                        base = __shfl(base, static_cast<int>(leader), 64);
+                        if (hit) {
+                            const uint32_t pos = base + static_cast<uint32_t>(__popcll(m & ((1ull << lane) - 1ull)));
+                            if (pos < list.cap) list.ent[pos] = K[c];
+                            atomicAdd(&sh.hist[(score - lo) >> shift1], 1u);
+                        }
+                    }
                 }
             }
         }
@@ -1239,6 +1301,31 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
 // the tile slots.
 constexpr int kFinishThreads = 1024;
 constexpr int kFinishWaves = kFinishThreads / 64;
+
+// Calls f(K) for every key of a layer's list.  `c` holds, in lane s of every wave, the number of
+// keys in shard s.  The shards are walked side by side -- one load per shard in flight per
+// thread -- rather than one after the other: a shard of a few hundred keys is one round trip to
+// memory, and sixteen of them in a row were most of this kernel's time.
+template <typename F>
+__device__ __forceinline__ void for_each_list_key(const unsigned long long *__restrict__ list, uint32_t shards,
+                                                  uint32_t cap, uint32_t c, F f) {
+    uint32_t longest = c;
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) longest = max(longest, __shfl_xor(longest, d, 64));
+    longest = __shfl(longest, 0, 64);
+    for (uint32_t i = threadIdx.x; i < longest + threadIdx.x; i += kFinishThreads) {   // (the same trip count in every thread)
+        unsigned long long K[kListShards];
+        bool have[kListShards];
+#pragma unroll
+        for (int s = 0; s < kListShards; ++s) {
+            have[s] = static_cast<uint32_t>(s) < shards && i < __shfl(c, s, 64);
+            K[s] = have[s] ? list[static_cast<size_t>(s) * cap + i] : 0ull;
+        }
+#pragma unroll
+        for (int s = 0; s < kListShards; ++s)
+            if (have[s]) f(K[s]);
+    }
+}
 
 __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__restrict__ layers,
                                                            SelState *__restrict__ state,
@@ -1309,17 +1396,12 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
         if (use_list) {                    // stage the bucket's keys
             if (tid == 0) nstage = 0;
             __syncthreads();
-            for (uint32_t s = 0; s < shards; ++s) {
-                const uint32_t n = __shfl(c, static_cast<int>(s));
-                const unsigned long long *__restrict__ part = list + static_cast<size_t>(s) * cap;
-                for (uint32_t i = tid; i < n; i += kFinishThreads) {
-                    const unsigned long long K = part[i];
-                    if (K >= base && ((K - base) >> top) == 0ull) {
-                        const uint32_t pos = atomicAdd(&nstage, 1u);
-                        if (pos < static_cast<uint32_t>(kStage)) sel[pos] = K - base;
-                    }
+            for_each_list_key(list, shards, cap, c, [&](unsigned long long K) {
+                if (K >= base && ((K - base) >> top) == 0ull) {
+                    const uint32_t pos = atomicAdd(&nstage, 1u);
+                    if (pos < static_cast<uint32_t>(kStage)) sel[pos] = K - base;
                 }
-            }
+            });
             __syncthreads();
             nsel = nstage;
         }
@@ -1346,11 +1428,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
                     if ((rel >> shift_prev) == want) atomicAdd(&lh[static_cast<uint32_t>(rel >> shift) & (nb - 1)], 1u);
                 }
             } else if (use_list) {
-                for (uint32_t s = 0; s < shards; ++s) {
-                    const uint32_t n = __shfl(c, static_cast<int>(s));
-                    const unsigned long long *__restrict__ part = list + static_cast<size_t>(s) * cap;
-                    for (uint32_t i = tid; i < n; i += kFinishThreads) RSDGC_COUNT_KEY(part[i])
-                }
+                for_each_list_key(list, shards, cap, c, [&](unsigned long long K) { RSDGC_COUNT_KEY(K) });
             } else if (st.mode == kModeFullMap) {
                 const uint32_t *__restrict__ src = keys + L.elem_off;
                 for (uint32_t i = tid; i < L.G; i += kFinishThreads) RSDGC_COUNT_KEY(composite_key(src[i], i))
@@ -1400,98 +1478,26 @@ __device__ __forceinline__ void or_bits_shared(uint32_t *__restrict__ mask, size
     if (p2) atomicOr(&mask[w + 2], p2);
 }
 
-// Set nbits (<= RSDGC_MAX_P) consecutive mask bits starting at bit position pos.
-__device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos, uint32_t nbits) {
-    const size_t w = pos >> 5;
-    const uint32_t b = static_cast<uint32_t>(pos & 31);
-    const uint32_t bits = (1u << nbits) - 1u;
-    atomicOr(&mask[w], bits << b);
-    if (b + nbits > 32) atomicOr(&mask[w + 1], bits >> (32 - b));
-}
-
-// Candidate-mode layers: workgroups stride over the plan's list of slot groups of the large
-// layers, each wave taking 4 tile slots of a group; every recorded candidate that reaches its
-// layer's threshold ORs the bits of its window into the (cleared) mask.  The words touched
-// are nearly all distinct, which is the case global atomics handle well.
-__device__ __forceinline__ void mark_candidates(const LayerDev *__restrict__ layers,
-                                                const GroupEntry *__restrict__ groups, uint32_t n_groups,
-                                                uint32_t first, uint32_t stride,
-                                                const SelState *__restrict__ state,
-                                                const uint32_t *__restrict__ slot_cnt,
-                                                const unsigned long long *__restrict__ slot_ent,
-                                                uint32_t *__restrict__ mask, uint32_t *__restrict__ cmask) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t cur_l = 0xffffffffu;
-    bool active = false;
-    unsigned long long T = 0;
-    LayerDev L;
-    for (uint32_t it = first; it < n_groups; it += stride) {
-        const GroupEntry ge = groups[it];
-        if (ge.layer != cur_l) {
-            cur_l = ge.layer;
-            L = layers[cur_l];
-            const SelState st = state[cur_l];
-            active = st.mode == kModeCandidates;
-            T = st.T;
-        }
-        if (!active) continue;
-        const int h = (static_cast<int>(L.p) - 1) / 2;
-        const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
-        uint32_t cnt[kSlotGroup / 4];
-#pragma unroll
-        for (int c = 0; c < kSlotGroup / 4; ++c) {
-            const uint32_t sl = wave + 4 * c;
-            cnt[c] = sl < ge.ntile ? min(slot_cnt[ge.slot0 + sl], L.slot_cap) : 0u;
-        }
-        uint32_t longest = 0;
-#pragma unroll
-        for (int c = 0; c < kSlotGroup / 4; ++c) longest = max(longest, cnt[c]);   // wave-uniform
-        // the group's first slot inside the layer's slot array
-        const unsigned long long *__restrict__ ent0 =
-            slot_ent + L.slot_off + static_cast<size_t>(ge.slot0 - L.tile_begin_all) * L.slot_cap;
-        for (uint32_t j0 = 0; j0 < longest; j0 += 64) {
-            const uint32_t j = j0 + lane;
-            unsigned long long K[kSlotGroup / 4];
-#pragma unroll
-            for (int c = 0; c < kSlotGroup / 4; ++c) {
-                K[c] = 0;
-                if (j < cnt[c]) K[c] = ent0[static_cast<size_t>(wave + 4 * c) * L.slot_cap + j];
-            }
-#pragma unroll
-            for (int c = 0; c < kSlotGroup / 4; ++c) {
-                if (j < cnt[c] && K[c] >= T) {
-                    const uint32_t i = ~static_cast<uint32_t>(K[c]);
-                    const int xc = static_cast<int>(i / L.C);
-                    const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * L.C);
-                    const int ylo = max(0, yc - h), yhi = min(C - 1, yc + h);
-                    for (int x = max(0, xc - h); x <= min(R - 1, xc + h); ++x)
-                        set_bits(mask, static_cast<size_t>(L.elem_off) + static_cast<size_t>(x) * C + ylo,
-                                 static_cast<uint32_t>(yhi - ylo + 1));
-                    if (cmask) {
-                        const size_t pos = static_cast<size_t>(L.elem_off) + i;
-                        atomicOr(&cmask[pos >> 5], 1u << (pos & 31));
-                    }
-                }
-            }
-        }
-    }
-}
-
 // Full-map layers: workgroups stride over the 16 x 256 tiles (the NSI tiling).  Every centre
 // of a tile and of a halo of h rows / columns is compared with the layer's threshold; the
 // per-row results become 64-bit ballot words in LDS, the p x p box dilation (Section III-C:
 // whole neighbourhoods are kept) is done on those words with shifts and ORs, and the tile's
 // mask words are written with plain stores (rows that are a multiple of 32 long) -- no
 // global atomics on that path.
-// One launch marks everything.  Workgroups [0, n_cand_wgs) take the candidate-mode layers (see
-// mark_candidates); the next n_list_wgs stride over the plan's list of tiles of the layers
-// that are always ranked on the full map; the others run only when some large layer fell back
-// to it, walk all tiles and take those of such layers.
+// The first n_bucket_wgs workgroups take the layers on the candidate path, one workgroup per
+// layer and shard of the layer's threshold-bucket list: the recorded candidates above the bucket
+// were marked by the gather pass, those of the bucket that reach the threshold are marked here,
+// each ORing the bits of its window into the mask.  (One workgroup per layer doing this at the
+// end of k_finish took 20 .. 75 us: the marks of a large layer are too many for one CU.)  The
+// next n_list_wgs workgroups stride over the plan's list of tiles of the layers that are
+// always ranked on the full map; the others run only when some large layer fell back to it,
+// walk all tiles and take those of such layers.
 struct MarkArgs {
     const LayerDev *layers;
     const SelState *state;
-    const GroupEntry *cand_groups;
-    uint32_t n_cand_groups, n_cand_wgs;
+    uint32_t n_bucket_wgs;           // n_layers * kListShards
+    const uint32_t *list_cnt;
+    const unsigned long long *list_ent;
     const uint32_t *slot_cnt;
     const unsigned long long *slot_ent;
     const DirEntry *dir;             // tiles of all layers in layer order (fallback walk)
@@ -1508,11 +1514,6 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
     constexpr int NSEG = kTileCols / 64;       // 64-column segments of a tile row
     static_assert(kTileRows * NSEG == 64, "one lane of wave 0 per row segment");
     __shared__ unsigned long long bits[kTileRows + 2 * MAXH][NSEG + 2];   // [row][left, segments, right]
-    if (blockIdx.x < m.n_cand_wgs) {
-        mark_candidates(m.layers, m.cand_groups, m.n_cand_groups, blockIdx.x, m.n_cand_wgs, m.state,
-                        m.slot_cnt, m.slot_ent, m.mask, m.cmask);
-        return;
-    }
     const LayerDev *__restrict__ layers = m.layers;
     const DirEntry *__restrict__ dir = m.dir;
     const SampleEntry *__restrict__ map_tiles = m.map_tiles;
@@ -1522,10 +1523,42 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
     uint32_t *__restrict__ cmask = m.cmask;
     const uint32_t n_layers = m.n_layers;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t bid = blockIdx.x - m.n_cand_wgs;
+    if (blockIdx.x < m.n_bucket_wgs) {
+        const uint32_t l = blockIdx.x / kListShards, shard = blockIdx.x % kListShards;
+        const uint32_t *__restrict__ cnt = m.list_cnt + static_cast<size_t>(l) * kListShards * kListCntStride;
+        const uint32_t c = static_cast<uint32_t>(lane) < kListShards ? cnt[lane * kListCntStride] : 0u;
+        const SelState st = state[l];
+        if (st.mode != kModeCandidates || st.span == 0u) return;      // (no bucket: nothing was ranked)
+        const LayerDev Lc = layers[l];
+        const unsigned long long Tc = st.T;
+        const WindowGeom geom = {static_cast<size_t>(Lc.elem_off), static_cast<int>(Lc.R), static_cast<int>(Lc.C),
+                                 (static_cast<int>(Lc.p) - 1) / 2};
+        const uint32_t shards = Lc.list_shards, cap = Lc.list_cap / shards;
+        if (shard >= shards) return;
+        if (__ballot(c > cap) == 0ull) {       // every shard fits: this workgroup takes its shard
+            const uint32_t n = __shfl(c, static_cast<int>(shard), 64);
+            const unsigned long long *__restrict__ part = m.list_ent + Lc.list_off + static_cast<size_t>(shard) * cap;
+            for (uint32_t i = tid; i < n; i += 256) {
+                const unsigned long long K = part[i];
+                if (K >= Tc) mark_window(geom, ~static_cast<uint32_t>(K), mask, cmask);
+            }
+        } else {                               // the list overflowed: the bucket's keys are still in the tile slots
+            const unsigned long long bucket_end = (static_cast<unsigned long long>(st.lo) + (1ull << st.span)) << 32;
+            for (uint32_t t = shard; t < Lc.n_tiles; t += shards) {
+                const uint32_t n = min(m.slot_cnt[Lc.tile_begin_all + t], Lc.slot_cap);
+                const unsigned long long *__restrict__ ent = m.slot_ent + Lc.slot_off + static_cast<size_t>(t) * Lc.slot_cap;
+                for (uint32_t i = tid; i < n; i += 256) {
+                    const unsigned long long K = ent[i];
+                    if (K >= Tc && K < bucket_end) mark_window(geom, ~static_cast<uint32_t>(K), mask, cmask);
+                }
+            }
+        }
+        return;
+    }
+    const uint32_t bid = blockIdx.x - m.n_bucket_wgs;
     const bool listed = bid < m.n_list_wgs;
     const uint32_t first = listed ? bid : bid - m.n_list_wgs;
-    const uint32_t stride = listed ? m.n_list_wgs : gridDim.x - m.n_cand_wgs - m.n_list_wgs;
+    const uint32_t stride = listed ? m.n_list_wgs : gridDim.x - m.n_bucket_wgs - m.n_list_wgs;
     const uint32_t n_items = listed ? m.n_map_tiles : m.n_tiles;
     if (first >= n_items) return;
     if (!listed && m.flags[0] == 0u) return;
@@ -2656,6 +2689,8 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         a.hist = hist;
         a.hist1 = reinterpret_cast<uint32_t *>(ws + w.hist1);
         a.flags = flags;
+        a.mask = mask;
+        a.cmask = cmask;
         GatherLists gl;
         gl.chunk_dir = chunk_dir;
         gl.map_chunks = reinterpret_cast<const ChunkEntry *>(ws + w.map_chunks);
@@ -2665,7 +2700,7 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         gl.n_map_chunks = static_cast<uint32_t>(plan->map_chunks.size());
         gl.n_cand_groups = n_cand_groups;
         gl.n_map_wgs = std::min<uint32_t>(gl.n_map_chunks, kNumCUs * 4u);
-        gl.n_slot_wgs = std::min<uint32_t>(n_cand_groups, kNumCUs * 4u);
+        gl.n_slot_wgs = std::min<uint32_t>(n_cand_groups, kNumCUs * 8u);
         const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(n_chunks, kNumCUs * 2u) : 0u;
         if (gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs > 0)
             hipLaunchKernelGGL(k_gather, dim3(gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs), dim3(256), 0, stream, a, gl);
@@ -2679,11 +2714,6 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         MarkArgs m;
         m.layers = layers;
         m.state = state;
-        m.cand_groups = cand_groups;
-        m.n_cand_groups = n_cand_groups;
-        m.n_cand_wgs = std::min<uint32_t>(n_cand_groups, kNumCUs * 8u);
-        m.slot_cnt = slot_cnt;
-        m.slot_ent = slot_ent;
         m.dir = reinterpret_cast<const DirEntry *>(ws + w.all_tile_dir);
         m.n_layers = static_cast<uint32_t>(L);
         m.n_tiles = plan->n_tiles_all;
@@ -2695,7 +2725,12 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         m.mask = mask;
         m.cmask = cmask;
         const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(plan->n_tiles_all, kNumCUs * 4u) : 0u;
-        const uint32_t n_wgs = m.n_cand_wgs + m.n_list_wgs + n_fb_wgs;
+        m.n_bucket_wgs = plan->any_large ? static_cast<uint32_t>(L) * kListShards : 0u;
+        m.list_cnt = reinterpret_cast<const uint32_t *>(ws + w.list_cnt);
+        m.list_ent = reinterpret_cast<const unsigned long long *>(ws + w.list_ent);
+        m.slot_cnt = slot_cnt;
+        m.slot_ent = slot_ent;
+        const uint32_t n_wgs = m.n_bucket_wgs + m.n_list_wgs + n_fb_wgs;
         if (n_wgs > 0) hipLaunchKernelGGL(k_mark, dim3(n_wgs), dim3(256), 0, stream, m);
     }
     marks.close(5);
