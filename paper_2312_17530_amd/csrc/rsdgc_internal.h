@@ -28,6 +28,7 @@ constexpr int kCountChunks = 16;     // chunks per workgroup of the count pass
 constexpr int kChunkGroup = 64;      // chunks per group in the two-level chunk prefix
 constexpr int kListShards = 16;      // a layer's threshold-bucket list is filled through this many counters
 constexpr int kListCntStride = 32;   // uint32 between two of them (one 128-byte line each)
+constexpr int kBigMapLayer = 1 << 20; // elements from which a full-map layer's bucket list goes through k_filter
 constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 // Candidate bound predicted from the thresholds of the two calls before, on a log2 scale: used
 // while the threshold moved by at most kTrendMaxLog2 between those calls.
@@ -205,6 +206,7 @@ struct WsLayout {
     size_t group_cnt = 0;    // uint32[n_chunk_groups]  kept elements per chunk group
     size_t group_ccnt = 0;   // uint32[n_chunk_groups]  selected centres per chunk group
     size_t list_cnt = 0;     // uint32[n_layers][kListShards][kListCntStride]  keys gathered per list shard
+    size_t list2_cnt = 0;    // uint32[n_layers]  of those, keys that k_filter picked for k_finish
     size_t feed = 0;         // uint32[16][8][32]  work-feed counters of the NSI launches
     size_t mask = 0;         // uint32[total_elems / 32]  kept-element bitmask
     size_t cmask = 0;        // uint32[total_elems / 32]  selected-centre bitmask
@@ -213,6 +215,7 @@ struct WsLayout {
     size_t slot_cnt = 0;     // uint32[n_tiles_all]  candidates recorded per tile
     size_t slot_ent = 0;     // uint64[sum over large layers of n_tiles * slot_cap]  their composite keys
     size_t list_ent = 0;     // uint64[sum list_cap]  composite keys of each layer's threshold bucket
+    size_t list2_ent = 0;    // uint64[n_layers][2048]  keys sharing the first two digits (plans with big_map_layers)
     size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
     size_t dyn = 0;          // scratch of rsdgc_dynamic_ratios: DynState, uint64[kHistBins], uint32[2 * n_layers]
     size_t acc = 0;          // float[total_elems]  sum of the nodes' messages (rsdgc_apply); all zero between calls
@@ -254,6 +257,7 @@ struct rsdgc_plan_s {
     uint32_t n_tiles_all = 0;
     uint32_t n_slot_groups = 0;
     bool any_large = false;
+    bool big_map_layers = false;        // some layer of a million elements or more is ranked on the full map
     int64_t total_elems = 0;
     int64_t out_capacity = 0;
     int64_t centre_capacity = 0;

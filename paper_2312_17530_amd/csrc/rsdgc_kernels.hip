@@ -1290,6 +1290,83 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
     }
 }
 
+// --------------------------------------------------------------- filter --
+// Only for plans with large layers that are ranked on the full map (a block grid, a keep ratio
+// too high for the candidate path): the threshold bucket of such a layer holds hundreds of
+// thousands of keys, too many for the one workgroup of k_finish to go through.  kFilterSplit
+// workgroups per layer find the second digit (each for itself, from the layer's complete
+// histogram) and copy the keys of the list that share it -- a few hundred -- to the layer's
+// second, small list, from which k_finish then works.
+constexpr int kFilterSplit = 32;
+constexpr int kFilterThreads = 1024;
+constexpr int kList2Cap = 2048;          // == kStage: what k_finish can hold in LDS
+
+__global__ __launch_bounds__(kFilterThreads) void k_filter(const LayerDev *__restrict__ layers,
+                                                           const SelState *__restrict__ state,
+                                                           const uint32_t *__restrict__ hist1,
+                                                           const uint32_t *__restrict__ list_cnt,
+                                                           const unsigned long long *__restrict__ list_ent,
+                                                           uint32_t *__restrict__ list2_cnt,
+                                                           unsigned long long *__restrict__ list2_ent) {
+    __shared__ uint32_t lh[kLevel1Bins];
+    __shared__ unsigned long long stage[kList2Cap];
+    __shared__ uint32_t wave_tot[kFilterThreads / 64];
+    __shared__ DigitResult res;
+    __shared__ uint32_t nstage, base_pos;
+    const int l = blockIdx.x / kFilterSplit, part = blockIdx.x % kFilterSplit, tid = threadIdx.x;
+    // lane s of every wave reads shard s's counter (unused shards stay 0); issued with the other loads
+    const uint32_t *__restrict__ cnt = list_cnt + static_cast<size_t>(l) * kListShards * kListCntStride;
+    const uint32_t c = (tid & 63) < kListShards ? cnt[(tid & 63) * kListCntStride] : 0u;
+    const SelState st = state[l];
+    const LayerDev L = layers[l];
+    for (int b = tid; b < kLevel1Bins; b += kFilterThreads) lh[b] = hist1[static_cast<size_t>(l) * kLevel1Bins + b];
+    // (a large layer that fell back to the full map has its first digit found in the gather pass only:
+    // k_finish goes through its list alone -- rare)
+    if (st.done || st.mode != kModeFullMap || L.large != 0u) return;
+    uint32_t total = c;
+#pragma unroll
+    for (int d = 8; d >= 1; d >>= 1) total += __shfl_xor(total, d, 64);
+    total = __shfl(total, 0, 64);
+    const uint32_t shards = L.list_shards, cap = L.list_cap / shards;
+    if (total <= static_cast<uint32_t>(kList2Cap) || __syncthreads_or(c > cap)) return;   // small enough, or overflowed
+    const DigitResult r = block_find_digit<kFilterThreads / 64>(lh, kLevel1Bins, st.k_rem, wave_tot, &res);
+    if (!r.found || r.count == st.k_rem - r.above) return;       // nothing left to rank below this digit
+    const uint32_t sh1 = st.span - kLevel1Bits;
+    const unsigned long long base = (static_cast<unsigned long long>(st.lo) << 32) +
+                                    (static_cast<unsigned long long>(r.digit) << (32 + sh1));
+    const int top = 32 + static_cast<int>(sh1);
+    // this workgroup's shard, and its share of that shard
+    const uint32_t shard = part % shards, sub = part / shards, nsub = (kFilterSplit + shards - 1 - shard) / shards;
+    const uint32_t n = __shfl(c, static_cast<int>(shard), 64);
+    const unsigned long long *__restrict__ list = list_ent + L.list_off + static_cast<size_t>(shard) * cap;
+    if (tid == 0) nstage = 0;
+    __syncthreads();
+    constexpr uint32_t U = 4;              // independent loads in flight per thread
+    for (uint32_t i0 = sub * U * kFilterThreads; i0 < n; i0 += nsub * U * kFilterThreads) {
+        unsigned long long K[U];
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u) {
+            const uint32_t i = i0 + u * kFilterThreads + tid;
+            K[u] = i < n ? list[i] : 0ull;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < U; ++u)
+            if (i0 + u * kFilterThreads + tid < n && K[u] >= base && ((K[u] - base) >> top) == 0ull) {
+                const uint32_t pos = atomicAdd(&nstage, 1u);
+                if (pos < static_cast<uint32_t>(kList2Cap)) stage[pos] = K[u];
+            }
+    }
+    __syncthreads();
+    const uint32_t m = nstage;
+    if (m == 0) return;                    // uniform
+    if (tid == 0) base_pos = atomicAdd(&list2_cnt[l], m);        // counts past the capacity too
+    __syncthreads();
+    const uint32_t b0 = base_pos;
+    for (uint32_t i = tid; i < min(m, static_cast<uint32_t>(kList2Cap)); i += kFilterThreads)
+        if (b0 + i < static_cast<uint32_t>(kList2Cap))
+            list2_ent[static_cast<size_t>(l) * kList2Cap + b0 + i] = stage[i];
+}
+
 // --------------------------------------------------------------- finish --
 // One workgroup (1024 threads) per layer finishes the ranking: second digit from the layer's
 // histogram; if the k-th rank is still inside a bucket of several keys, the bucket's keys are
@@ -1336,6 +1413,8 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
                                                            const uint32_t *__restrict__ keys,
                                                            const uint32_t *__restrict__ slot_cnt,
                                                            const unsigned long long *__restrict__ slot_ent,
+                                                           const uint32_t *__restrict__ list2_cnt,
+                                                           const unsigned long long *__restrict__ list2_ent,
                                                            PredState *__restrict__ pred /* nullable */) {
     __shared__ uint32_t lh[kLevel1Bins];
     __shared__ unsigned long long sel[kStage];
@@ -1346,6 +1425,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
     // lane s of every wave reads shard s's counter (unused shards stay 0); issued with the other loads
     const uint32_t *__restrict__ cnt = list_cnt + static_cast<size_t>(l) * kListShards * kListCntStride;
     const uint32_t c = (tid & 63) < kListShards ? cnt[(tid & 63) * kListCntStride] : 0u;
+    const uint32_t n2 = list2_cnt[l];     // keys that k_filter has already picked from a long list (0: none)
     const SelState st = state[l];
     const LayerDev L = layers[l];
     for (int b = tid; b < kLevel1Bins; b += kFinishThreads) lh[b] = hist1[static_cast<size_t>(l) * kLevel1Bins + b];
@@ -1393,7 +1473,12 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
         const int top = 32 + static_cast<int>(sh1);
         const unsigned long long *__restrict__ list = list_ent + L.list_off;
         uint32_t nsel = 0xffffffffu;
-        if (use_list) {                    // stage the bucket's keys
+        if (use_list && n2 != 0u && n2 <= static_cast<uint32_t>(kStage)) {   // already picked by k_filter
+            for (uint32_t i = tid; i < n2; i += kFinishThreads)
+                sel[i] = list2_ent[static_cast<size_t>(l) * kList2Cap + i] - base;
+            __syncthreads();
+            nsel = n2;
+        } else if (use_list) {             // stage the bucket's keys
             if (tid == 0) nstage = 0;
             __syncthreads();
             for_each_list_key(list, shards, cap, c, [&](unsigned long long K) {
@@ -2704,8 +2789,13 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(n_chunks, kNumCUs * 2u) : 0u;
         if (gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs > 0)
             hipLaunchKernelGGL(k_gather, dim3(gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs), dim3(256), 0, stream, a, gl);
+        uint32_t *list2_cnt = reinterpret_cast<uint32_t *>(ws + w.list2_cnt);
+        unsigned long long *list2_ent = reinterpret_cast<unsigned long long *>(ws + w.list2_ent);
+        if (plan->big_map_layers)          // long threshold-bucket lists: many workgroups pick the keys k_finish needs
+            hipLaunchKernelGGL(k_filter, dim3(L * kFilterSplit), dim3(kFilterThreads), 0, stream, layers, state,
+                               a.hist1, a.list_cnt, a.list_ent, list2_cnt, list2_ent);
         hipLaunchKernelGGL(k_finish, dim3(L), dim3(kFinishThreads), 0, stream, layers, state, hist, a.hist1,
-                           a.list_cnt, a.list_ent, a.keys, slot_cnt, slot_ent, pred);
+                           a.list_cnt, a.list_ent, a.keys, slot_cnt, slot_ent, list2_cnt, list2_ent, pred);
     }
     HIP_TRY(hipGetLastError());
     marks.close(4);

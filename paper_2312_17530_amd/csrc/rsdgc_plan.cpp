@@ -36,6 +36,7 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->map_chunks.clear();
     plan->map_tiles.clear();
     plan->any_large = false;
+    plan->big_map_layers = false;
 
     int64_t elem_off = 0, out_off = 0, centre_off = 0;
     uint32_t chunk_begin = 0, tile_begin_all = 0, group_begin = 0;
@@ -74,9 +75,10 @@ int build_tables(rsdgc_plan_s *plan) {
         d.list_cap = plan->k_override.empty()
                          ? static_cast<uint32_t>(std::min<int64_t>(G, std::max<int64_t>(kListMin, G / kListDiv)))
                          : static_cast<uint32_t>(G);
-        // workgroups append through kListShards counters so that few atomics meet on one address; a
-        // block grid keeps one shard, which can take the whole layer
-        d.list_shards = plan->k_override.empty() ? kListShards : 1;
+        // workgroups append through kListShards counters so that few atomics meet on one address
+        // (each takes the shard of its id modulo kListShards: an even split unless nearly the whole
+        // layer lies in the bucket, in which case the ranking streams the score map instead)
+        d.list_shards = kListShards;
         list_off += d.list_cap;
 
         // Candidate path: only the centres whose score reaches a bound are recorded, per tile, and
@@ -99,6 +101,7 @@ int build_tables(rsdgc_plan_s *plan) {
                                                                             // layout does not move with the ratios)
         d.hint_target = d.large ? static_cast<uint32_t>(std::ceil(want + 4.0 * std::sqrt(want) + 8.0)) : 0u;
         plan->any_large = plan->any_large || d.large;
+        plan->big_map_layers = plan->big_map_layers || (!d.large && k > 0 && G >= kBigMapLayer);
 
         plan->chunk_dir.push_back(DirEntry{chunk_begin, static_cast<uint32_t>(l)});
         plan->all_tile_dir.push_back(DirEntry{tile_begin_all, static_cast<uint32_t>(l)});
@@ -210,6 +213,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.group_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
     w.group_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
     w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * kListShards * kListCntStride * size_t(L), A);
+    w.list2_cnt = off;    off = align_up(off + sizeof(uint32_t) * L, A);
     w.feed = off;         off = align_up(off + sizeof(uint32_t) * 16 * 8 * 32, A);
     w.mask = off;         off = align_up(off + sizeof(uint32_t) * words, A);
     w.cmask = off;        off = align_up(off + sizeof(uint32_t) * words, A);
@@ -218,6 +222,7 @@ int build_tables(rsdgc_plan_s *plan) {
     // (the plan of a block grid never takes the candidate path and has no tile slots)
     w.slot_ent = off;     off = align_up(off + (plan->k_override.empty() ? sizeof(uint64_t) * kSlotCapMax * size_t(plan->n_tiles_all) : 0), A);
     w.list_ent = off;     off = align_up(off + sizeof(uint64_t) * static_cast<size_t>(list_off), A);
+    w.list2_ent = off;    off = align_up(off + sizeof(uint64_t) * 2048 * size_t(L), A);
     // the score map covers every layer: which layers are ranked on it depends on the keep ratios
     // (set_ratios must not change the workspace size), and any large layer may fall back to it in
     // any call, several of them in the same one
