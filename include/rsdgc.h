@@ -80,9 +80,13 @@ int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio);
 
 /* How the per-layer ranking (Algorithm 1) is carried out; the result is the same.
  *   RSDGC_PATH_AUTO      large layers record only the centres whose score reaches a
- *                        bound estimated from a sample of the layer and rank those;
- *                        a layer falls back to the full map when the bound turns out
- *                        too high or a tile holds too many such centres (default).
+ *                        bound and rank those.  The bound comes from the thresholds
+ *                        the same layer ended on in the two calls before (kept in the
+ *                        workspace), or, in the first sixteen calls with a workspace,
+ *                        from a sample of the layer's tiles.
+ *                        A layer falls back to the full map within the call when the
+ *                        bound turns out too high or a tile holds too many such
+ *                        centres (default).
  *   RSDGC_PATH_FULL_MAP  every layer writes its full score map and ranks it with
  *                        histogram passes over all elements.                       */
 #define RSDGC_PATH_AUTO      0
@@ -148,12 +152,19 @@ size_t  rsdgc_workspace_bytes(const rsdgc_plan_t *plan);
  *                     from rsdgc_centre_offset(l) -- the "neighbourhood index"
  *                     of Section III-C.
  *   out_centre_counts [device, nullable] int32[n_layers]: selected centres per
- *                     layer; always equals k_l.
+ *                     layer; always equals k_l.  Either of the two may be given
+ *                     without the other.
  *   workspace [device] rsdgc_workspace_bytes bytes, 256-byte aligned.  It is
  *             the plan's device-side state: keep the same buffer, unmodified,
  *             between calls that use this plan (switching to another buffer is
  *             allowed at any time and is detected by its address; after the
  *             buffer's memory was recycled, see rsdgc_plan_forget_workspace).
+ *             The first call with a workspace, and the first after
+ *             rsdgc_plan_set_ratios, rsdgc_plan_set_path or
+ *             rsdgc_plan_forget_workspace, copies the plan's tables from host
+ *             memory into it (one hipMemcpyAsync on `stream`): that call must
+ *             not be made under HIP graph capture; every later one enqueues
+ *             kernels only and may be captured.
  * Ranking ties are resolved towards the lower flat index; exactly k_l centres
  * are selected.  Scores are float32 roundings of double-precision window
  * statistics.                                                               */
@@ -281,16 +292,20 @@ int rsdgc_decompress_blocks(rsdgc_plan_t *plan, const uint32_t *block_idx, const
  *   w <- w - eta * sum_k sparse(v_k)
  * for the messages of n_msgs nodes, each as produced by rsdgc_compress with a
  * plan of the same shapes and ratios.  The messages are summed in the order
- * given (float32 adds), the step is one float32 multiply and one float32
- * subtract; weights at positions no message names are not touched.  Only the
- * named positions are visited: the cost is proportional to the messages, not
- * to the model.
+ * given (float32 adds, starting from +0), the step is one float32 multiply and
+ * one float32 subtract; weights at positions no message names, or whose sum is
+ * +0, are not touched.  Only the named positions are visited: the cost is
+ * proportional to the messages, not to the model, and no dense accumulator is
+ * kept.
  *   idx, val, counts  [host] arrays of n_msgs device pointers (1 <= n_msgs <=
  *                     RSDGC_MAX_MSGS); message k is idx[k], val[k], counts[k].
  *   weights           [device, in/out] float32 arena laid out like the gradient.
- * Uses an accumulator inside the workspace that is all zero between calls (it is
- * cleared on the first call with a workspace); must not overlap another call
- * that uses the same workspace.                                              */
+ * With more than one message every layer's indices must be ascending, as
+ * rsdgc_compress writes them (the pairs of one stretch of a layer are found by
+ * binary search); a segment that is not leaves an unspecified part of the sum at
+ * its positions, but nothing outside the layers' elements is ever written.  A
+ * single message is applied pair by pair, in any order.  Uses scratch inside the
+ * workspace: must not overlap another call that uses the same workspace.       */
 #define RSDGC_MAX_MSGS 64
 int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
                 const float *const *val, const int32_t *const *counts, float *weights,
@@ -317,12 +332,16 @@ int rsdgc_profile_end(rsdgc_plan_t *plan, double *stage_ms, int32_t *n_calls);
 const char *rsdgc_stage_name(int32_t stage);
 
 /* Which ranking path each layer took in the last rsdgc_compress that used `workspace`:
- * paths[l] [host, n_layers] = 0 candidates above a sampled bound, 1 full score map,
- * 2 nothing to select (k_l = 0).  Waits for `stream`, then copies from the device.
- * The path never changes a result.  A layer that would take path 0 shows 1 when its
- * bound failed in this call (too few centres above it, or too many in one tile) or in
- * one of the eight calls before it with the same workspace: after a failure the layer
- * starts on the full map for eight calls before the bound is tried again.            */
+ * paths[l] [host, n_layers] = 0 candidates above a bound taken from a sample of the layer,
+ * 1 full score map, 2 nothing to select (k_l = 0), 3 candidates above a bound predicted
+ * from the layer's earlier thresholds.  Waits for `stream`, then copies from the device.
+ * The path never changes a result.  A layer that would take path 0 or 3 shows 1 when
+ *   - its bound failed in this call (too few centres above it, or too many in one tile):
+ *     the call then ranked the full map, the layer's safety margin is doubled and the
+ *     prediction pauses for four calls;
+ *   - no bound could be predicted (prediction paused, or the last two thresholds lie more
+ *     than about 10 % apart) and the workspace is past its first sixteen calls, the only
+ *     ones that sample tiles for a bound.                                              */
 int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream);
 
 /* ----------------------------------------------------------- diagnostics */

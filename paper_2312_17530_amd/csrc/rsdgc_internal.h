@@ -218,7 +218,7 @@ struct WsLayout {
     size_t list2_ent = 0;    // uint64[n_layers][2048]  keys sharing the first two digits (plans with big_map_layers)
     size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
     size_t dyn = 0;          // scratch of rsdgc_dynamic_ratios: DynState, uint64[kHistBins], uint32[2 * n_layers]
-    size_t acc = 0;          // float[total_elems]  sum of the nodes' messages (rsdgc_apply); all zero between calls
+    size_t apply_ranges = 0; // uint32[RSDGC_MAX_MSGS][n_chunks][2]  rsdgc_apply: each message's pairs per chunk
     size_t total = 0;
 };
 

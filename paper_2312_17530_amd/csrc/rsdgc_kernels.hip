@@ -2078,7 +2078,7 @@ __global__ __launch_bounds__(256) void k_emit_centres(const LayerDev *__restrict
     while (word) {
         const int b = __ffs(word) - 1;
         word &= word - 1;
-        if (rank < L.k) out_centre_idx[static_cast<size_t>(L.centre_off) + rank] = start + 32u * tid + b;
+        if (out_centre_idx && rank < L.k) out_centre_idx[static_cast<size_t>(L.centre_off) + rank] = start + 32u * tid + b;
         ++rank;
     }
 }
@@ -2387,22 +2387,103 @@ __global__ __launch_bounds__(256) void k_scatter_blocks(const LayerDev *__restri
 }
 
 // ---------------------------------------------------------------- apply --
-// Eq. 12, third line.  The messages have been summed into the accumulator (k_scatter,
-// message by message).  One thread per pair of every message: whoever exchanges a non-zero
-// sum out of the accumulator applies it to the weight (the others find +0 there), so each
-// named position is updated exactly once and the accumulator is all zero again afterwards.
+// Eq. 12, third line: w <- w - eta * (sum over the nodes' messages).  No dense accumulator: the
+// messages are index-sorted per layer (rsdgc_compress writes them so), so the pairs that fall into
+// one 8192-element chunk of a layer are one contiguous stretch of every message.  A first
+// kernel finds those stretches (two binary searches per message and chunk, all in parallel); the
+// second takes one chunk per workgroup, sums the messages' values in an LDS array in the order
+// given -- message after message, a barrier between them, plain float32 adds starting from +0 --
+// and updates the weights at the positions that were named.  One message needs none of this:
+// every pair is applied on its own.
 struct ApplyMsgs {
     const uint32_t *idx[RSDGC_MAX_MSGS];
+    const float *val[RSDGC_MAX_MSGS];
     const int32_t *counts[RSDGC_MAX_MSGS];
 };
 
-__global__ __launch_bounds__(256) void k_apply(const LayerDev *__restrict__ layers, int n_layers,
-                                               long long capacity, const ApplyMsgs msgs,
-                                               float *__restrict__ acc, float *__restrict__ weights,
-                                               float eta) {
+// First position in a[0, n) whose value is not below x (a ascending).
+__device__ __forceinline__ uint32_t lower_bound_u32(const uint32_t *__restrict__ a, uint32_t n, uint32_t x) {
+    uint32_t lo = 0, hi = n;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (a[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// ranges[(k * n_chunks + c) * 2 + {0, 1}]: first and one-past-last pair of message k (positions
+// in the message's arrays) that fall into chunk c.
+__global__ __launch_bounds__(256) void k_apply_ranges(const LayerDev *__restrict__ layers,
+                                                      const ChunkInfo *__restrict__ chunk_info,
+                                                      uint32_t n_chunks, int n_msgs, const ApplyMsgs msgs,
+                                                      uint32_t *__restrict__ ranges) {
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= n_chunks * static_cast<uint32_t>(n_msgs)) return;
+    const uint32_t k = t / n_chunks, c = t - k * n_chunks;
+    const ChunkInfo ci = chunk_info[c];
+    const int32_t raw = msgs.counts[k][ci.layer];
+    const uint32_t n = static_cast<uint32_t>(min(max(raw, 0), static_cast<int32_t>(min(ci.cap, 0x7fffffffu))));
+    const uint32_t *__restrict__ seg = msgs.idx[k] + ci.out_off;
+    const uint32_t a = lower_bound_u32(seg, n, ci.start);
+    const uint32_t b = ci.last ? n : lower_bound_u32(seg, n, ci.start + ci.len);
+    ranges[2 * t] = a;
+    ranges[2 * t + 1] = max(a, b);
+}
+
+__global__ __launch_bounds__(256) void k_apply_chunks(const ChunkInfo *__restrict__ chunk_info, uint32_t n_chunks,
+                                                      int n_msgs, const ApplyMsgs msgs,
+                                                      const uint32_t *__restrict__ ranges,
+                                                      float *__restrict__ weights, float eta) {
+    __shared__ float acc[kChunk];
+    __shared__ uint32_t touched[kChunk / 32];
+    __shared__ uint32_t s_rng[RSDGC_MAX_MSGS][2];
+    const int tid = threadIdx.x;
+    const uint32_t c = blockIdx.x;
+    const ChunkInfo ci = chunk_info[c];
+    uint32_t mine = 0;
+    if (tid < n_msgs) {
+        const uint32_t a = ranges[2 * (static_cast<uint32_t>(tid) * n_chunks + c)];
+        const uint32_t b = ranges[2 * (static_cast<uint32_t>(tid) * n_chunks + c) + 1];
+        s_rng[tid][0] = a;
+        s_rng[tid][1] = b;
+        mine = b - a;
+    }
+    if (!__syncthreads_or(mine != 0u)) return;         // no message names an element of this chunk
+#pragma unroll
+    for (int j = 0; j < kChunk / 256; ++j) acc[tid + 256 * j] = 0.f;
+    touched[tid] = 0u;
+    __syncthreads();
+    for (int k = 0; k < n_msgs; ++k) {                 // the sum, message by message, in the order given
+        const uint32_t a = s_rng[k][0], b = s_rng[k][1];
+        const uint32_t *__restrict__ idx = msgs.idx[k] + ci.out_off;
+        const float *__restrict__ val = msgs.val[k] + ci.out_off;
+        for (uint32_t j = a + tid; j < b; j += 256) {
+            const uint32_t rel = idx[j] - ci.start;
+            if (rel < ci.len) {                        // (always, for a sorted message)
+                acc[rel] = acc[rel] + val[j];
+                atomicOr(&touched[rel >> 5], 1u << (rel & 31));
+            }
+        }
+        __syncthreads();
+    }
+    uint32_t word = touched[tid];
+    float *__restrict__ w = weights + ci.arena_off;
+    while (word) {
+        const uint32_t rel = 32u * static_cast<uint32_t>(tid) + static_cast<uint32_t>(__ffs(word)) - 1u;
+        word &= word - 1u;
+        const float sum = acc[rel];
+        if (__float_as_uint(sum) != 0u) w[rel] = w[rel] - __fmul_rn(eta, sum);
+    }
+}
+
+// One message: every pair on its own.
+__global__ __launch_bounds__(256) void k_apply_single(const LayerDev *__restrict__ layers, int n_layers,
+                                                      long long capacity, const uint32_t *__restrict__ idx,
+                                                      const float *__restrict__ val,
+                                                      const int32_t *__restrict__ counts,
+                                                      float *__restrict__ weights, float eta) {
     const long long j = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
     if (j >= capacity) return;
-    const int k = blockIdx.y;
     int lo = 0, hi = n_layers;            // last layer whose segment starts at or before j
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -2410,18 +2491,26 @@ __global__ __launch_bounds__(256) void k_apply(const LayerDev *__restrict__ laye
     }
     const LayerDev L = layers[lo];
     const long long q = j - L.out_off;
-    if (q >= msgs.counts[k][lo] || q >= static_cast<long long>(L.cap)) return;
-    const uint32_t i = msgs.idx[k][j];
-    if (i >= L.G) return;                 // malformed message: ignore the pair (k_scatter did too)
+    if (q >= counts[lo] || q >= static_cast<long long>(L.cap)) return;
+    const uint32_t i = idx[j];
+    if (i >= L.G) return;                 // malformed message: ignore the pair
+    const float sum = 0.f + val[j];       // (the sum of one message, formed like any other: +0 + val)
     const size_t pos = static_cast<size_t>(L.elem_off) + i;
-    const float s = atomicExch(&acc[pos], 0.f);
-    if (__float_as_uint(s) != 0u) weights[pos] = weights[pos] - __fmul_rn(eta, s);
+    if (__float_as_uint(sum) != 0u) weights[pos] = weights[pos] - __fmul_rn(eta, sum);
 }
+
+// Block messages keep the accumulator form: the messages are summed into an arena that is all zero
+// between calls (k_scatter_blocks, message by message), then one thread per kept block of every
+// message exchanges each slot's sum with +0 and whoever gets a non-zero sum applies it.
+struct ApplyBlockMsgs {
+    const uint32_t *idx[RSDGC_MAX_MSGS];
+    const int32_t *counts[RSDGC_MAX_MSGS];
+};
 
 // The same for block messages (the block reading): one thread per kept block of every message
 // walks the block's slots inside the matrix.
 __global__ __launch_bounds__(256) void k_apply_blocks(const LayerDev *__restrict__ outer, int n_layers,
-                                                      long long capacity, const ApplyMsgs msgs,
+                                                      long long capacity, const ApplyBlockMsgs msgs,
                                                       float *__restrict__ acc, float *__restrict__ weights,
                                                       float eta) {
     const long long j = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
@@ -2919,7 +3008,7 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
                            residual, residual_out, mom.in, mom.out, mom.m, mask, chunk_cnt, group_cnt, out_idx,
                            out_val, out_counts);
     marks.close(7);
-    if (out_centre_idx)
+    if (want_centres)                      // the list, the counts, or both
         hipLaunchKernelGGL(k_emit_centres, dim3(n_chunks), dim3(256), 0, stream, layers, chunk_info,
                            cmask, chunk_ccnt, reinterpret_cast<const uint32_t *>(ws + w.group_ccnt), out_centre_idx,
                            out_centre_counts);
@@ -3145,28 +3234,30 @@ int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
     const LayerDev *layers = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
-    float *acc = reinterpret_cast<float *>(ws + plan->ws.acc);
     if (plan->out_capacity == 0) return RSDGC_OK;      // no message can hold a pair
-    if (plan->acc_zero_ws != workspace) {              // first use of this workspace: clear the accumulator
-        const size_t n16 = static_cast<size_t>(plan->total_elems) * sizeof(float) / 16;
-        hipLaunchKernelGGL(k_fill_zero, dim3(kNumCUs * 8u), dim3(256), 0, stream,
-                           reinterpret_cast<uint4 *>(acc), n16);
+    if (n_msgs == 1) {
+        const unsigned blocks = static_cast<unsigned>((plan->out_capacity + 255) / 256);
+        hipLaunchKernelGGL(k_apply_single, dim3(blocks), dim3(256), 0, stream, layers, plan->n_layers,
+                           static_cast<long long>(plan->out_capacity), idx[0], val[0], counts[0], weights, eta);
         HIP_TRY(hipGetLastError());
+        return RSDGC_OK;
     }
-    plan->acc_zero_ws = nullptr;                       // not known to be zero until the apply kernel is enqueued
-    const unsigned blocks = static_cast<unsigned>((plan->out_capacity + 255) / 256);
     ApplyMsgs m;
     std::memset(&m, 0, sizeof(m));
-    for (int k = 0; k < n_msgs; ++k) {                 // the sum, message by message, in the order given
-        hipLaunchKernelGGL(k_scatter, dim3(blocks), dim3(256), 0, stream, layers, plan->n_layers,
-                           static_cast<long long>(plan->out_capacity), idx[k], val[k], counts[k], acc, 1);
+    for (int k = 0; k < n_msgs; ++k) {
         m.idx[k] = idx[k];
+        m.val[k] = val[k];
         m.counts[k] = counts[k];
     }
-    hipLaunchKernelGGL(k_apply, dim3(blocks, static_cast<unsigned>(n_msgs)), dim3(256), 0, stream, layers,
-                       plan->n_layers, static_cast<long long>(plan->out_capacity), m, acc, weights, eta);
+    const ChunkInfo *chunk_info = reinterpret_cast<const ChunkInfo *>(ws + plan->ws.chunk_info);
+    uint32_t *ranges = reinterpret_cast<uint32_t *>(ws + plan->ws.apply_ranges);
+    const uint32_t n_chunks = plan->n_chunks;
+    const unsigned range_blocks = static_cast<unsigned>((static_cast<uint64_t>(n_chunks) * n_msgs + 255) / 256);
+    hipLaunchKernelGGL(k_apply_ranges, dim3(range_blocks), dim3(256), 0, stream, layers, chunk_info, n_chunks,
+                       n_msgs, m, ranges);
+    hipLaunchKernelGGL(k_apply_chunks, dim3(n_chunks), dim3(256), 0, stream, chunk_info, n_chunks, n_msgs, m,
+                       ranges, weights, eta);
     HIP_TRY(hipGetLastError());
-    plan->acc_zero_ws = workspace;
     return RSDGC_OK;
 }
 
@@ -3194,7 +3285,7 @@ int rsdgc_apply_blocks(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const
     }
     plan->acc_zero_ws = nullptr;                       // not known to be zero until the apply kernel is enqueued
     const unsigned blocks = static_cast<unsigned>((plan->centre_capacity + 255) / 256);
-    ApplyMsgs m;
+    ApplyBlockMsgs m;
     std::memset(&m, 0, sizeof(m));
     for (int k = 0; k < n_msgs; ++k) {                 // the sum, message by message, in the order given
         hipLaunchKernelGGL(k_scatter_blocks, dim3(blocks), dim3(256), 0, stream, outer, plan->n_layers,

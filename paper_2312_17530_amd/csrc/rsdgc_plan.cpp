@@ -228,7 +228,7 @@ int build_tables(rsdgc_plan_s *plan) {
     // any call, several of them in the same one
     w.nsi = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
     w.dyn = off;          off = align_up(off + 256 + sizeof(uint64_t) * kHistBins + sizeof(uint32_t) * 2 * size_t(L), A);
-    w.acc = off;          off = align_up(off + sizeof(float) * static_cast<size_t>(plan->total_elems), A);
+    w.apply_ranges = off; off = align_up(off + sizeof(uint32_t) * 2 * RSDGC_MAX_MSGS * static_cast<size_t>(plan->n_chunks), A);
     w.total = off;
 
     plan->table.assign(w.table_bytes, 0);
@@ -331,6 +331,9 @@ static int make_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
         if (!ratio_ok(keep_ratio[l])) return RSDGC_EINVAL;
         total += R * C + kLayerAlign;
         if (total > (int64_t(1) << 34)) return RSDGC_EINVAL;         // 64 GiB per float32 arena
+        // a kept block always sends p*p values: the layer's value segment, k_l * p^2 floats, is
+        // counted in 32 bits like every other per-layer quantity
+        if (blocks && keep_count(R * C, pl, keep_ratio[l]) * pl * pl > 0xffffffffLL) return RSDGC_EINVAL;
     }
     if ((total + kChunk - 1) / kChunk + n_layers > 0x7fffffffLL) return RSDGC_EINVAL;
     rsdgc_plan_s *plan = new (std::nothrow) rsdgc_plan_s;
@@ -368,8 +371,11 @@ int rsdgc_plan_blocks(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
 
 int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio) {
     if (!plan || !keep_ratio) return RSDGC_EINVAL;
-    for (int l = 0; l < plan->n_layers; ++l)
+    for (int l = 0; l < plan->n_layers; ++l) {
         if (!ratio_ok(keep_ratio[l])) return RSDGC_EINVAL;
+        const int64_t G = plan->shapes[l].rows * plan->shapes[l].cols, pl = plan->p[l];
+        if (plan->blocks && keep_count(G, static_cast<int>(pl), keep_ratio[l]) * pl * pl > 0xffffffffLL) return RSDGC_EINVAL;
+    }
     try {
         plan->ratio.assign(keep_ratio, keep_ratio + plan->n_layers);
         build_tables(plan);

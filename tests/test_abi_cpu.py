@@ -228,3 +228,43 @@ def test_newer_entry_points_validate_before_touching_the_gpu():
     assert lib.rsdgc_apply_blocks(bplan.handle, 1, ptrs, ptrs, ptrs, a, float("nan"), a, null) == E
     assert lib.rsdgc_compress_blocks(bplan.handle, a, 2 * a, 2 * a + 128, a, a, a, 4 * a, null) == E    # overlapping arenas
     assert lib.rsdgc_compress_blocks(bplan.handle, a, a, a, a, a, a, 4 * a, null) == E                    # new residual on the gradient
+
+
+def test_plans_near_the_32_bit_limits():
+    """Per-layer quantities are 32-bit, offsets into the lists and slots 64-bit.  A block plan whose
+    value segment k_l p^2 would not fit 32 bits is refused; block grids whose threshold-bucket lists
+    add up to more than 2^32 entries are accepted and laid out without wrapping."""
+    lib = binding.load()
+    G = 65535 * 65537                    # 2^32 - 1 elements in one layer
+    assert G == 2 ** 32 - 1
+    for rho, ok in ((1.0, False), (0.5, True)):
+        try:
+            plan = binding.rsdgc_plan_blocks([(65535, 65537)], 3, 0.5, [rho])
+            assert ok, "k_l * 9 exceeds 32 bits: must be refused"
+            assert plan.layer_k(0) * 9 <= 0xffffffff and plan.out_capacity == plan.layer_k(0) * 9
+            with pytest.raises(binding.RsdgcError):
+                binding.rsdgc_plan_set_ratios(plan, [1.0])
+        except binding.RsdgcError as e:
+            assert not ok and e.code == binding.RSDGC_EINVAL
+    # five block grids of 2^30 blocks each (p = 1): the lists of the grids hold a layer each
+    shapes = [(32768, 32768)] * 5
+    plan = binding.rsdgc_plan_blocks(shapes, 1, 0.5, [0.001] * 5)
+    total = sum(r * c for r, c in shapes)
+    assert total > 2 ** 32
+    assert plan.workspace_bytes > 8 * total          # the lists alone: 8 bytes per entry
+    del plan, lib
+
+
+def test_static_workspace_entry_point_validates_on_the_host():
+    """rsdgc_compress_static refuses a null or block plan and a plan beyond its built-in workspace
+    before it touches the GPU (this box may have none)."""
+    lib = binding.load()
+    null, a = None, 4096
+    assert lib.rsdgc_compress_static(null, a, a, a, a, a, a, null, null, null) == binding.RSDGC_EINVAL
+    bplan = binding.rsdgc_plan_blocks([(8, 8)], 3, 0.5, [0.1])
+    assert lib.rsdgc_compress_static(bplan.handle, a, a, a, a, a, a, null, null, null) == binding.RSDGC_EINVAL
+    big = binding.rsdgc_plan([(8192, 4096)], 3, 0.5, [0.01])
+    assert big.workspace_bytes > binding.RSDGC_STATIC_WORKSPACE_BYTES
+    assert lib.rsdgc_compress_static(big.handle, a, 2 * a, 3 * a, a, a, a, null, null, null) == binding.RSDGC_ETOOBIG
+    assert str(big.workspace_bytes).encode() in lib.rsdgc_last_hip_error()
+    assert b"built-in" in lib.rsdgc_strerror(binding.RSDGC_ETOOBIG)

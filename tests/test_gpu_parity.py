@@ -954,6 +954,46 @@ def test_set_ratios_and_determinism():
         assert np.array_equal(c1, c2)
 
 
+def test_either_centre_output_may_be_given_alone():
+    """out_centre_counts without out_centre_idx (and the other way round) gives what the call
+    with both gives; with neither, the message is unchanged."""
+    import torch
+    from paper_2312_17530_amd import binding
+    w = synth.scaled_down(synth.config(1), 256, 512)
+    grads = synth.gradients(w, 0)
+    sess = _session(w.shapes, w.p, w.alpha, w.ratios)
+    sess.set_grad(grads)
+    sess.compress()
+    torch.cuda.synchronize()
+    both_idx, both_cnt = sess.out_centre_idx.clone(), sess.out_centre_counts.clone()
+    msg = (sess.out_idx.clone(), sess.out_val.clone(), sess.out_counts.clone())
+    assert int(both_cnt.sum()) == sum(sess.plan.layer_k(l) for l in range(len(w.shapes)))
+    for give_idx, give_cnt in [(False, True), (True, False), (False, False)]:
+        ci = torch.full_like(both_idx, -7)
+        cc = torch.full_like(both_cnt, -7)
+        sess.residual.zero_()
+        if sess.residual_next is not None:
+            sess.residual_next.zero_()
+        binding.rsdgc_compress(sess.plan, sess.grad, sess.residual, sess.residual_next, sess.out_idx,
+                               sess.out_val, sess.out_counts, sess.workspace,
+                               out_centre_idx=ci if give_idx else None,
+                               out_centre_counts=cc if give_cnt else None)
+        torch.cuda.synchronize()
+        tag = f"idx={give_idx} counts={give_cnt}"
+        if give_cnt:
+            assert torch.equal(cc, both_cnt), tag
+        else:
+            assert bool((cc == -7).all()), tag
+        if give_idx:
+            for l in range(len(w.shapes)):
+                o, k = sess.plan.centre_offset(l), sess.plan.layer_k(l)
+                assert torch.equal(ci[o:o + k], both_idx[o:o + k]), f"{tag} layer {l}"
+        else:
+            assert bool((ci == -7).all()), tag
+        assert torch.equal(sess.out_idx, msg[0]) and torch.equal(sess.out_val, msg[1]), tag
+        assert torch.equal(sess.out_counts, msg[2]), tag
+
+
 def test_a_recycled_workspace_is_prepared_again_when_the_plan_is_told():
     """The workspace is wiped between two calls (as when its memory was freed and handed out
     again); after rsdgc_plan_forget_workspace the next call uploads the tables afresh and gives
