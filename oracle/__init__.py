@@ -89,6 +89,9 @@ def _load():
     lib.rsdgc_oracle_compress_layer_blocks.argtypes = [fp, fp, i64, i64, c_int, f64, f64, u32p, fp,
                                                        ctypes.POINTER(c_float), fp, fp]
     lib.rsdgc_oracle_compress_layer_blocks.restype = i64
+    lib.rsdgc_oracle_compress_layer_blocks_momentum.argtypes = [fp, fp, fp, c_float, i64, i64, c_int, f64, f64,
+                                                                u32p, fp, ctypes.POINTER(c_float), fp, fp]
+    lib.rsdgc_oracle_compress_layer_blocks_momentum.restype = i64
     lib.rsdgc_oracle_decompress_blocks.argtypes = [u32p, fp, i64, i64, i64, c_int, fp, c_int]
     lib.rsdgc_oracle_decompress_blocks.restype = None
     _lib = lib
@@ -390,6 +393,37 @@ def compress_layer_blocks(g, r, p: int, alpha: float, rho: float) -> BlockLayerR
     assert n == k
     return BlockLayerResult(blocks[:k].copy(), val[:k * p * p].copy(), k,
                             float(tau.value) if k > 0 else None, nsi_map, v, r_new)
+
+
+class MomentumBlockLayerResult(NamedTuple):
+    layer: BlockLayerResult   # v = r + u_new; everything else as in the plain block reading
+    u_new: np.ndarray         # m*u + g, then +0 on every slot of a kept block
+
+
+def compress_layer_blocks_momentum(g, u, r, m: float, p: int, alpha: float, rho: float) -> MomentumBlockLayerResult:
+    """One layer under the block reading with Eq. 12's momentum.  g, u, r: R x C float32; none is modified."""
+    _check_p(p)
+    g = _f32(g)
+    u_new = _f32(u).copy()
+    r_new = _f32(r).copy()
+    R, C = g.shape
+    BR, BC = (R + p - 1) // p, (C + p - 1) // p
+    k = block_keep_count(R * C, p, rho, BR * BC)
+    blocks = np.empty(max(k, 1), dtype=np.uint32)
+    val = np.empty(max(k * p * p, 1), dtype=np.float32)
+    tau = ctypes.c_float(0.0)
+    nsi_map = np.empty((BR, BC), dtype=np.float32)
+    v = np.empty((R, C), dtype=np.float32)
+    n = _load().rsdgc_oracle_compress_layer_blocks_momentum(
+        _p(g, ctypes.c_float), _p(u_new, ctypes.c_float), _p(r_new, ctypes.c_float), ctypes.c_float(m),
+        R, C, p, float(alpha), float(rho), _p(blocks, ctypes.c_uint32), _p(val, ctypes.c_float),
+        ctypes.byref(tau), _p(nsi_map, ctypes.c_float), _p(v, ctypes.c_float))
+    if n < 0:
+        raise MemoryError("oracle ran out of memory")
+    assert n == k
+    return MomentumBlockLayerResult(
+        BlockLayerResult(blocks[:k].copy(), val[:k * p * p].copy(), k, float(tau.value) if k > 0 else None,
+                         nsi_map, v, r_new), u_new)
 
 
 def decompress_blocks(blocks, val, R: int, C: int, p: int, dense: Optional[np.ndarray] = None,

@@ -496,6 +496,57 @@ int64_t rsdgc_oracle_compress_layer_blocks(const float *g, float *r, int64_t R, 
     return k;
 }
 
+/* The block reading with momentum correction: Eq. 12's first two lines (step 1m), then steps
+ * B2-B7 on v = r + u_new; u and r are updated in place and both restart from +0 on every slot
+ * of a kept block (what Eq. 12's line 1 accumulates for a sent position must not be sent again).
+ * Arguments and return value as above.                                                         */
+int64_t rsdgc_oracle_compress_layer_blocks_momentum(const float *g, float *u, float *r, float m,
+                                                    int64_t R, int64_t C, int p, double alpha,
+                                                    double rho, uint32_t *blocks, float *val,
+                                                    float *tau_out, float *nsi_out, float *v_out)
+{
+    const int64_t G = R * C;
+    const int64_t BR = (R + p - 1) / p, BC = (C + p - 1) / p, NB = BR * BC;
+    float *v = (float *)malloc((size_t)G * sizeof(float));
+    float *un = (float *)malloc((size_t)G * sizeof(float));
+    float *nsi = (float *)malloc((size_t)NB * sizeof(float));
+    if (!v || !un || !nsi) {
+        free(v); free(un); free(nsi);
+        return -1;
+    }
+    rsdgc_oracle_momentum(u, g, r, m, un, v, G);               /* step 1m */
+    rsdgc_oracle_block_nsi(v, R, C, p, alpha, nsi);            /* step B2 */
+    int64_t k = rsdgc_oracle_k(G, p, rho);                     /* step B3 */
+    if (k > NB) k = NB;
+    float tau = 0.0f;
+    if (rsdgc_oracle_select(nsi, NB, k, blocks, &tau) != 0) {  /* step B4 */
+        free(v); free(un); free(nsi);
+        return -1;
+    }
+    for (int64_t i = 0; i < G; ++i) {                          /* step B7, first half */
+        r[i] = v[i];
+        u[i] = un[i];
+    }
+    for (int64_t j = 0; j < k; ++j) {                          /* steps B6, B7 */
+        const int64_t kx = blocks[j] / BC, ky = blocks[j] % BC;
+        for (int dx = 0; dx < p; ++dx)
+            for (int dy = 0; dy < p; ++dy) {
+                const int64_t x = kx * p + dx, y = ky * p + dy;
+                const int within = x < R && y < C;
+                val[j * p * p + dx * p + dy] = within ? v[x * C + y] : 0.0f;
+                if (within) {
+                    r[x * C + y] = 0.0f;
+                    u[x * C + y] = 0.0f;
+                }
+            }
+    }
+    if (tau_out) *tau_out = tau;
+    if (nsi_out) memcpy(nsi_out, nsi, (size_t)NB * sizeof(float));
+    if (v_out) memcpy(v_out, v, (size_t)G * sizeof(float));
+    free(v); free(un); free(nsi);
+    return k;
+}
+
 /* Inverse of step B6: dense = 0 (accumulate == 0) or kept; dense[block slot] = or += value. */
 void rsdgc_oracle_decompress_blocks(const uint32_t *blocks, const float *val, int64_t k,
                                     int64_t R, int64_t C, int p, float *dense, int accumulate)

@@ -25,6 +25,10 @@ int64_t rsdgc_oracle_compress_layer_momentum(const float *g, float *u, float *r,
 int64_t rsdgc_oracle_compress_layer_blocks(const float *g, float *r, int64_t R, int64_t C, int p,
                                            double alpha, double rho, uint32_t *blocks, float *val,
                                            float *tau_out, float *nsi_out, float *v_out);
+int64_t rsdgc_oracle_compress_layer_blocks_momentum(const float *g, float *u, float *r, float m, int64_t R,
+                                                    int64_t C, int p, double alpha, double rho,
+                                                    uint32_t *blocks, float *val, float *tau_out,
+                                                    float *nsi_out, float *v_out);
 void rsdgc_oracle_decompress(const uint32_t *idx, const float *val, int64_t n, float *dense, int64_t G,
                              int accumulate);
 void rsdgc_oracle_decompress_blocks(const uint32_t *blocks, const float *val, int64_t k, int64_t R,
@@ -97,6 +101,10 @@ static void oracle_cases() {
                 CHECK(rsdgc_oracle_compress_layer_blocks(g.data(), r3.data(), R, C, p, 0.5, rho, blocks.data(),
                                                          bval.data(), &tau, bnsi.data(), v.data()) == kb);
                 rsdgc_oracle_decompress_blocks(blocks.data(), bval.data(), kb, R, C, p, dense.data(), 0);
+                std::vector<float> r4 = r0, u4 = u;
+                CHECK(rsdgc_oracle_compress_layer_blocks_momentum(g.data(), u4.data(), r4.data(), 0.9f, R, C, p, 0.5,
+                                                                  rho, blocks.data(), bval.data(), &tau,
+                                                                  bnsi.data(), v.data()) == kb);
                 // receiving side: the plain call's message from two nodes
                 std::vector<float> w(G, 1.f);
                 const uint32_t *ip[2] = {idx0.data(), idx0.data()};

@@ -154,6 +154,14 @@ def battery(orc):
     first = int(bres.blocks[0])
     check("block_values", bres.val[:3].tolist() == (rr + gg)[first // 6 * 3, first % 6 * 3:first % 6 * 3 + 3].tolist()
           if first % 6 < 5 else True)
+    # block reading with Eq. 12's momentum
+    bm = orc.compress_layer_blocks_momentum(gg, uu, rr, 0.9, 3, 0.5, 0.3)
+    bplain = orc.compress_layer_blocks(un, rr, 3, 0.5, 0.3)
+    check("block_momentum_selection", np.array_equal(bm.layer.blocks, bplain.blocks)
+          and np.array_equal(bm.layer.val, bplain.val) and np.array_equal(bm.layer.r_new, bplain.r_new))
+    bkept = orc.decompress_blocks(bm.layer.blocks, np.ones(bm.layer.k * 9, np.float32), 13, 17, 3) != 0
+    check("block_momentum_masked", np.array_equal(bm.u_new, np.where(bkept, np.float32(0), un)))
+    check("block_momentum_v", np.array_equal(bm.layer.v, rr + un))
     d2 = np.ones(10, np.float32)
     orc.decompress(np.array([2, 5], np.uint32), np.array([0.5, -1.0], np.float32), 10, dense=d2, accumulate_into=True)
     check("decompress_acc", d2.tolist() == [1, 1, 1.5, 1, 1, 0, 1, 1, 1, 1])
@@ -208,6 +216,13 @@ MUTANTS = [
     ("block_values_transposed", "val[j * p * p + dx * p + dy] = inside ? v[x * C + y] : 0.0f;", "val[j * p * p + dy * p + dx] = inside ? v[x * C + y] : 0.0f;", 0),
     ("block_grid_row_stride", "const int64_t bx = blocks[j] / BC, by = blocks[j] % BC;\n        for (int dx = 0; dx < p; ++dx)\n            for (int dy = 0; dy < p; ++dy) {\n                const int64_t x = bx * p + dx, y = by * p + dy;\n                const int inside",
      "const int64_t bx = blocks[j] / BR, by = blocks[j] % BR;\n        for (int dx = 0; dx < p; ++dx)\n            for (int dy = 0; dy < p; ++dy) {\n                const int64_t x = bx * p + dx, y = by * p + dy;\n                const int inside", 0),
+    ("block_momentum_not_masked", "                    u[x * C + y] = 0.0f;\n", "", 0),
+    ("block_momentum_keeps_old_momentum", "        u[i] = un[i];", "        u[i] = u[i];", 0),
+    ("block_momentum_scores_without_residual", "rsdgc_oracle_block_nsi(v, R, C, p, alpha, nsi);            /* step B2 */",
+     "rsdgc_oracle_block_nsi(un, R, C, p, alpha, nsi);            /* step B2 */", 1),
+    ("block_momentum_sends_momentum_only", "val[j * p * p + dx * p + dy] = within ? v[x * C + y] : 0.0f;",
+     "val[j * p * p + dx * p + dy] = within ? un[x * C + y] : 0.0f;", 0),
+    ("block_momentum_residual_keeps_sent", "                    r[x * C + y] = 0.0f;\n", "", 0),
     ("momentum_not_masked", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = u_new[i];", 0),
     ("momentum_masked_where_kept_out", "u_out[i] = mask[i] ? 0.0f : u_new[i];", "u_out[i] = mask[i] ? u_new[i] : 0.0f;", 0),
 ]

@@ -618,6 +618,113 @@ def test_block_reading_with_p1_is_the_element_reading():
     assert np.array_equal(a.blocks, b.idx) and np.array_equal(a.val, b.val) and np.array_equal(a.r_new, b.r_new)
 
 
+# ------------------------------------------------- block reading with momentum (Eq. 12 in full)
+def test_block_momentum_zero_is_the_plain_block_reading():
+    rng = np.random.default_rng(74)
+    g = (rng.standard_normal((19, 23)) * 1e-2).astype(np.float32)
+    u = (rng.standard_normal((19, 23)) * 1e-2).astype(np.float32)
+    r = (rng.standard_normal((19, 23)) * 1e-2).astype(np.float32)
+    a = oracle.compress_layer_blocks_momentum(g, u, r, 0.0, 3, 0.5, 0.2)
+    b = oracle.compress_layer_blocks(g, r, 3, 0.5, 0.2)
+    for x, y in zip(a.layer, b):
+        assert np.array_equal(x, y)
+    kept = oracle.decompress_blocks(b.blocks, np.ones(b.k * 9, np.float32), 19, 23, 3) != 0
+    assert np.array_equal(a.u_new, np.where(kept, np.float32(0), g))
+
+
+def test_block_momentum_is_the_plain_block_reading_fed_with_m_u_plus_g():
+    rng = np.random.default_rng(75)
+    for (R, C), p, rho in (((19, 23), 3, 0.2), ((10, 31), 5, 0.6), ((7, 7), 7, 1.0), ((9, 40), 1, 0.1)):
+        g = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        u = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        r = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        un = np.float32(0.9) * u + g                         # one rounded multiply, one rounded add (numpy)
+        c = oracle.compress_layer_blocks_momentum(g, u, r, 0.9, p, 0.5, rho)
+        d = oracle.compress_layer_blocks(un, r, p, 0.5, rho)
+        assert np.array_equal(c.layer.v, r + un)
+        assert np.array_equal(c.layer.blocks, d.blocks) and np.array_equal(c.layer.val, d.val)
+        assert np.array_equal(c.layer.nsi, d.nsi) and np.array_equal(c.layer.r_new, d.r_new)
+        # momentum and residual restart from +0 on exactly the slots of the kept blocks
+        kept = np.zeros((R, C), bool)
+        BC = -(-C // p)
+        for b in c.layer.blocks.tolist():
+            bx, by = divmod(b, BC)
+            kept[bx * p:bx * p + p, by * p:by * p + p] = True
+        want_u = np.where(kept, np.float32(0), un)
+        assert np.array_equal(c.u_new.view(np.uint32), want_u.view(np.uint32))
+        assert np.array_equal(c.layer.r_new.view(np.uint32), np.where(kept, np.float32(0), r + un).view(np.uint32))
+        dense = oracle.decompress_blocks(c.layer.blocks, c.layer.val, R, C, p)
+        assert np.array_equal(dense + c.layer.r_new, c.layer.v)
+
+
+def test_block_momentum_closed_form_constant_gradient_nothing_sent_then_all_sent():
+    # g = 1, m = 1/2, rho = 0: u_t = 2 - 2^(1-t), v_t = sum of u (all exact in float32); then one
+    # call with rho = 1 sends every block and both u and r restart from zero
+    g = np.ones((6, 7), dtype=np.float32)
+    u = np.zeros_like(g)
+    r = np.zeros_like(g)
+    want_u, want_v = 0.0, 0.0
+    for t in range(1, 10):
+        res = oracle.compress_layer_blocks_momentum(g, u, r, 0.5, 3, 0.5, 0.0)
+        want_u = 0.5 * want_u + 1.0
+        want_v += want_u
+        assert res.layer.k == 0 and res.layer.blocks.size == 0
+        assert np.all(res.u_new == np.float32(want_u)) and np.all(res.layer.r_new == np.float32(want_v))
+        u, r = res.u_new, res.layer.r_new
+    res = oracle.compress_layer_blocks_momentum(g, u, r, 0.5, 3, 0.5, 1.0)
+    assert res.layer.k == 5 and res.layer.blocks.tolist() == [0, 1, 2, 3, 4]     # ceil(42/9) of 6 blocks
+    sent = np.float32(want_v + 0.5 * want_u + 1.0)
+    # the block not sent is one with the lowest score: the right-hand blocks are cut by the edge
+    # (one column of three inside), equal scores tie towards the lower index
+    assert res.layer.nsi[0, 2] == res.layer.nsi[1, 2] < res.layer.nsi[0, 0]
+    assert np.all(res.layer.val.reshape(5, 3, 3)[[0, 1, 3, 4]] == sent)
+    assert np.all(res.u_new[:, :6] == 0) and np.all(res.layer.r_new[:, :6] == 0)
+    assert np.all(res.u_new[0:3, 6] == 0) and np.all(res.u_new[3:6, 6] == np.float32(0.5 * want_u + 1.0))
+    assert np.all(res.layer.r_new[3:6, 6] == sent)
+
+
+def test_block_momentum_with_p1_is_the_element_reading_with_momentum():
+    rng = np.random.default_rng(76)
+    g = (rng.standard_normal((12, 19)) * 1e-2).astype(np.float32)
+    u = (rng.standard_normal((12, 19)) * 1e-2).astype(np.float32)
+    r = (rng.standard_normal((12, 19)) * 1e-2).astype(np.float32)
+    a = oracle.compress_layer_blocks_momentum(g, u, r, 0.7, 1, 0.5, 0.1)
+    b = oracle.compress_layer_momentum(g, u, r, 0.7, 1, 0.5, 0.1)
+    assert np.array_equal(a.layer.blocks, b.layer.idx) and np.array_equal(a.layer.val, b.layer.val)
+    assert np.array_equal(a.layer.r_new, b.layer.r_new) and np.array_equal(a.u_new, b.u_new)
+
+
+def test_block_momentum_against_pure_python_brute_force():
+    rng = np.random.default_rng(77)
+    for R, C, p, rho in ((9, 11, 3, 0.3), (7, 16, 5, 0.5)):
+        g = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        u = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        r = (rng.standard_normal((R, C)) * 1e-2).astype(np.float32)
+        m = np.float32(0.9)
+        un = [[float(np.float32(np.float32(m * u[x, y]) + g[x, y])) for y in range(C)] for x in range(R)]
+        v = [[float(np.float32(np.float32(r[x, y]) + np.float32(un[x][y]))) for y in range(C)] for x in range(R)]
+        BR, BC = -(-R // p), -(-C // p)
+        score = []
+        for bx in range(BR):
+            for by in range(BC):
+                w = [v[x][y] if x < R and y < C else 0.0
+                     for x in range(bx * p, bx * p + p) for y in range(by * p, by * p + p)]
+                mean = sum(w) / (p * p)
+                std = math.sqrt(sum((t - mean) ** 2 for t in w) / (p * p))               # Eq. 10
+                score.append(float(np.float32(0.5 * sum(abs(t) for t in w) / (p * p) + 0.5 * std)))   # Eqs. 8, 9
+        k = min(math.ceil(R * C / (p * p) * rho), BR * BC)                                # Eq. 11
+        kept_blocks = sorted(sorted(range(BR * BC), key=lambda i: (-score[i], i))[:k])
+        o = oracle.compress_layer_blocks_momentum(g, u, r, 0.9, p, 0.5, rho)
+        assert o.layer.v.tolist() == v
+        if o.layer.nsi.ravel().tolist() == score:
+            assert o.layer.blocks.tolist() == kept_blocks
+            for x in range(R):
+                for y in range(C):
+                    kept = (x // p) * BC + y // p in kept_blocks
+                    assert o.u_new[x, y] == (0.0 if kept else un[x][y])
+                    assert o.layer.r_new[x, y] == (0.0 if kept else v[x][y])
+
+
 def _blocks_as_pairs(blocks, val, R, C, p):
     """A block message written out as (flat index, value) pairs of the slots inside the matrix."""
     BC = (C + p - 1) // p
