@@ -144,7 +144,7 @@ def bench_blocks(args, w, grads) -> int:
     """Same contract for the block reading: K timed rsdgc_compress_blocks calls, one JSON line."""
     import torch
     from paper_2312_17530_amd.session import BlockSession
-    sess = BlockSession(w.shapes, w.p, w.alpha, w.ratios, in_place=args.in_place)
+    sess = BlockSession(w.shapes, w.p, w.alpha, w.ratios, in_place=args.in_place, momentum=args.momentum)
     sess.set_grad(grads)
     stream = torch.cuda.current_stream()
     G = w.total_elems
@@ -158,14 +158,15 @@ def bench_blocks(args, w, grads) -> int:
     dt = time.perf_counter() - t0
     counts = sess.out_counts.cpu().numpy()
     n_blocks = int(counts.sum())
-    alg = 12.0 * G + 4.0 * G / (w.p * w.p)          # read g, read r, write v; one score per block
+    # read g, read r, write v (with momentum also read u, write u); one score per block
+    alg = (20.0 if args.momentum is not None else 12.0) * G + 4.0 * G / (w.p * w.p)
     out = {
         "metric": METRIC, "value": G * args.steps / dt, "unit": "elements/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "reading": "non-overlapping blocks", "layers": w.n_layers, "elements": G,
                    "p": w.p, "alpha": w.alpha, "blocks_kept_last_step": n_blocks,
-                   "residual_update": "in_place" if args.in_place else "two_arenas"},
+                   "residual_update": "in_place" if args.in_place else "two_arenas", "momentum": args.momentum},
         "roofline": {"bound": "hbm", "kernel": "whole call (k_block_nsi dominates)",
                      "achieved": alg / (dt / args.steps) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": alg / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, "traffic": None,

@@ -267,7 +267,7 @@ int rsdgc_decompress(rsdgc_plan_t *plan, const uint32_t *idx, const float *val,
  *   rsdgc_centre_offset(l) / rsdgc_centre_capacity   layout of the block index list,
  *   rsdgc_out_offset(l) / rsdgc_out_capacity         layout of the value list
  *                               (k_l * p_l^2 floats per layer),
- * and only rsdgc_compress_blocks / rsdgc_decompress_blocks / rsdgc_apply_blocks (and
+ * and only rsdgc_compress_blocks(_momentum) / rsdgc_decompress_blocks / rsdgc_apply_blocks (and
  * the plan calls) accept it; a plan from rsdgc_plan is refused by these (RSDGC_EINVAL).
  *   out_block_idx [device] uint32: per layer, from rsdgc_centre_offset(l), the kept
  *                 blocks' indices bx * ceil(C/p) + by, ascending.
@@ -284,6 +284,19 @@ int rsdgc_plan_blocks(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
 int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *residual,
                           float *residual_out, uint32_t *out_block_idx, float *out_val,
                           int32_t *out_counts, void *workspace, void *stream);
+/* The block reading with momentum correction (Eq. 12 in full, Section III-C's last paragraph):
+ * u = m*u + g (one float32 multiply, one float32 add), v = r + u, then the blocks are scored,
+ * ranked and sent as in rsdgc_compress_blocks on that v; momentum and residual both restart
+ * from +0 on every slot of a kept block.
+ *   momentum      [device, const] float32 arena: u of the previous iteration.
+ *   momentum_out  [device] float32 arena for the new u: a further arena, or momentum itself.
+ *   m             momentum factor in [0, 1]; m = 0 gives rsdgc_compress_blocks's message.
+ * Apart from momentum_out == momentum and residual_out == residual no two arenas may overlap
+ * (RSDGC_EINVAL).  HBM traffic: 20 bytes per element.                                        */
+int rsdgc_compress_blocks_momentum(rsdgc_plan_t *plan, const float *grad, const float *momentum,
+                                   float *momentum_out, float m, const float *residual,
+                                   float *residual_out, uint32_t *out_block_idx, float *out_val,
+                                   int32_t *out_counts, void *workspace, void *stream);
 int rsdgc_decompress_blocks(rsdgc_plan_t *plan, const uint32_t *block_idx, const float *val,
                             const int32_t *counts, float *dense, int accumulate,
                             void *workspace, void *stream);

@@ -22,7 +22,7 @@ EXPORTS = [
     "rsdgc_plan", "rsdgc_plan_set_ratios", "rsdgc_plan_set_path", "rsdgc_plan_set_work_feed", "rsdgc_plan_forget_workspace", "rsdgc_plan_destroy", "rsdgc_n_layers",
     "rsdgc_total_elems", "rsdgc_layer_offset", "rsdgc_layer_elems", "rsdgc_layer_k",
     "rsdgc_out_offset", "rsdgc_out_capacity", "rsdgc_centre_offset", "rsdgc_centre_capacity",
-    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_static", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_apply_blocks", "rsdgc_plan_blocks", "rsdgc_compress_blocks",
+    "rsdgc_workspace_bytes", "rsdgc_compress", "rsdgc_compress_static", "rsdgc_compress_momentum", "rsdgc_dynamic_ratios", "rsdgc_apply", "rsdgc_apply_blocks", "rsdgc_plan_blocks", "rsdgc_compress_blocks", "rsdgc_compress_blocks_momentum",
     "rsdgc_decompress_blocks", "rsdgc_nsi", "rsdgc_decompress",
     "rsdgc_last_paths", "rsdgc_profile_begin", "rsdgc_profile_end", "rsdgc_stage_name",
     "rsdgc_strerror", "rsdgc_last_hip_error",
@@ -105,6 +105,8 @@ def load() -> ctypes.CDLL:
     lib.rsdgc_plan_blocks.restype = ctypes.c_int
     lib.rsdgc_compress_blocks.argtypes = [vp] * 9
     lib.rsdgc_compress_blocks.restype = ctypes.c_int
+    lib.rsdgc_compress_blocks_momentum.argtypes = [vp, vp, vp, vp, ctypes.c_float] + [vp] * 7
+    lib.rsdgc_compress_blocks_momentum.restype = ctypes.c_int
     lib.rsdgc_decompress_blocks.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, vp]
     lib.rsdgc_decompress_blocks.restype = ctypes.c_int
     lib.rsdgc_nsi.argtypes = [vp] * 6
@@ -228,6 +230,15 @@ def rsdgc_compress_blocks(plan: Plan, grad, residual, residual_out, out_block_id
     _check(load().rsdgc_compress_blocks(plan.handle, _ptr(grad), _ptr(residual), _ptr(residual_out),
                                         _ptr(out_block_idx), _ptr(out_val), _ptr(out_counts),
                                         _ptr(workspace), _stream(stream)), "rsdgc_compress_blocks")
+
+
+def rsdgc_compress_blocks_momentum(plan: Plan, grad, momentum, momentum_out, m: float, residual, residual_out,
+                                   out_block_idx, out_val, out_counts, workspace, stream=None) -> None:
+    _check(load().rsdgc_compress_blocks_momentum(plan.handle, _ptr(grad), _ptr(momentum), _ptr(momentum_out),
+                                                 float(m), _ptr(residual), _ptr(residual_out),
+                                                 _ptr(out_block_idx), _ptr(out_val), _ptr(out_counts),
+                                                 _ptr(workspace), _stream(stream)),
+           "rsdgc_compress_blocks_momentum")
 
 
 def rsdgc_decompress_blocks(plan: Plan, block_idx, val, counts, dense, accumulate: bool, workspace,

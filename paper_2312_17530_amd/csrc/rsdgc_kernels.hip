@@ -2135,8 +2135,10 @@ __global__ __launch_bounds__(256) void k_scatter(const LayerDev *__restrict__ la
 // (zero outside the matrix, divisor p*p), score to the inner score map, 12-bit histogram.
 // Persistent workgroups stride over the tiles; the histogram is flushed on layer change.
 // FEED: tiles come from the launch's work feed (many tiles per workgroup) instead of a
-// fixed strided share.
-template <int P, bool FEED>
+// fixed strided share.  MOM: Eq. 12's first line on the way in -- u_new = m*u + g (one rounded
+// multiply, one rounded add) takes g's place and goes to the new momentum arena (which, like
+// the residual's, may be the old one).
+template <int P, bool FEED, bool MOM>
 __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ outer,
                                                    const DirEntry *__restrict__ tile_dir,
                                                    uint32_t n_layers, uint32_t n_tiles,
@@ -2145,7 +2147,8 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
                                                    const float *resid, float *v_out,
                                                    float *__restrict__ score_map,
                                                    uint32_t *__restrict__ hist, double alpha,
-                                                   uint32_t *__restrict__ feed_ctr, uint32_t feed_shift) {
+                                                   uint32_t *__restrict__ feed_ctr, uint32_t feed_shift,
+                                                   const float *mom_in, float *mom_out, float m) {
     constexpr int BCT = block_tile_cols(P);
     constexpr int TR = kBlockTileRows * P, TC = BCT * P;      // tile in elements; TC is a multiple of 4
     constexpr int VEC_PER_ROW = TC / 4;
@@ -2208,8 +2211,10 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
         const float *__restrict__ g = grad + O.elem_off;
         const float *r = resid + O.elem_off;           // may be the same arena as vo
         float *vo = v_out + O.elem_off;
+        const float *ui = MOM ? mom_in + O.elem_off : nullptr;     // may be the same arena as uo
+        float *uo = MOM ? mom_out + O.elem_off : nullptr;
         if ((C & 3) == 0) {
-            float4 gv[ITER], rv[ITER];
+            float4 gv[ITER], rv[ITER], uv[MOM ? ITER : 1];
 #pragma unroll
             for (int it = 0; it < ITER; ++it) {
                 const int s = tid + it * 256;
@@ -2217,10 +2222,12 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
                 const int x = x0 + rr, y = y0 + 4 * j4;
                 gv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
                 rv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (MOM) uv[it] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (s < NVEC && x < R && y < C) {
                     const size_t off = static_cast<size_t>(x) * C + y;
                     gv[it] = load_streaming(g + off);       // blocks share no element
                     rv[it] = load_streaming(r + off);
+                    if (MOM) uv[it] = load_streaming(ui + off);
                 }
             }
             if (FEED) feed.stash(feed_slot);      // the loads are out, no store of this tile yet
@@ -2228,12 +2235,20 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
             for (int it = 0; it < ITER; ++it) {
                 const int s = tid + it * 256;
                 if (s < NVEC) {
+                    const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
+                    const int x = x0 + rr, y = y0 + 4 * j4;
+                    const bool inside = x < R && y < C;
+                    if (MOM) {
+                        gv[it].x = __fmul_rn(m, uv[it].x) + gv[it].x;
+                        gv[it].y = __fmul_rn(m, uv[it].y) + gv[it].y;
+                        gv[it].z = __fmul_rn(m, uv[it].z) + gv[it].z;
+                        gv[it].w = __fmul_rn(m, uv[it].w) + gv[it].w;
+                        if (inside) store_streaming(uo + static_cast<size_t>(x) * C + y, gv[it]);
+                    }
                     const float4 v = make_float4(rv[it].x + gv[it].x, rv[it].y + gv[it].y,
                                                  rv[it].z + gv[it].z, rv[it].w + gv[it].w);
                     *reinterpret_cast<float4 *>(&tile[s * 4]) = v;          // s*4 == rr*TC + 4*j4
-                    const int rr = s / VEC_PER_ROW, j4 = s - rr * VEC_PER_ROW;
-                    const int x = x0 + rr, y = y0 + 4 * j4;
-                    if (x < R && y < C) store_streaming(vo + static_cast<size_t>(x) * C + y, v);
+                    if (inside) store_streaming(vo + static_cast<size_t>(x) * C + y, v);
                 }
             }
         } else {
@@ -2243,7 +2258,12 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
                 float v = 0.f;
                 if (x < R && y < C) {
                     const size_t off = static_cast<size_t>(x) * C + y;
-                    v = r[off] + g[off];
+                    float gu = g[off];
+                    if (MOM) {
+                        gu = __fmul_rn(m, ui[off]) + gu;
+                        uo[off] = gu;
+                    }
+                    v = r[off] + gu;
                     vo[off] = v;
                 }
                 tile[s] = v;
@@ -2289,7 +2309,7 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
 
 // Kept blocks of one chunk of a layer's grid, in ascending order: block index to the index
 // list, the block's p*p values (row-major, +0 for slots outside the matrix) to the value
-// list, +0 into the new residual.
+// list, +0 into the new residual (and into the new momentum, when the call carries one).
 __global__ __launch_bounds__(256) void k_emit_blocks(const LayerDev *__restrict__ outer,
                                                      const ChunkInfo *__restrict__ inner_chunks,
                                                      const uint32_t *__restrict__ mask,
@@ -2297,6 +2317,7 @@ __global__ __launch_bounds__(256) void k_emit_blocks(const LayerDev *__restrict_
                                                      const uint32_t *__restrict__ group_cnt,
                                                      const LayerDev *__restrict__ inner,
                                                      float *__restrict__ v_arena,
+                                                     float *__restrict__ u_arena /* nullable */,
                                                      uint32_t *__restrict__ out_blocks,
                                                      float *__restrict__ out_val,
                                                      int32_t *__restrict__ out_counts) {
@@ -2347,6 +2368,7 @@ __global__ __launch_bounds__(256) void k_emit_blocks(const LayerDev *__restrict_
             const size_t off = static_cast<size_t>(x) * C + y;
             val = v[off];
             v[off] = 0.f;
+            if (u_arena) u_arena[O.elem_off + off] = 0.f;
         }
         out_val[static_cast<size_t>(O.out_off) + static_cast<size_t>(rank) * PP + sl] = val;
     }
@@ -3104,23 +3126,33 @@ int rsdgc_compress_momentum(rsdgc_plan_t *plan, const float *grad, const float *
                          out_centre_idx, out_centre_counts, workspace, stream);
 }
 
-int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *residual,
-                          float *residual_out, uint32_t *out_block_idx, float *out_val,
-                          int32_t *out_counts, void *workspace, void *stream_) {
+// Two arenas of the plan's size overlap unless they are the same one.
+static bool arenas_clash(const void *a, const void *b, uintptr_t bytes, bool same_allowed) {
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    if (x == y) return !same_allowed;
+    return x < y + bytes && y < x + bytes;
+}
+
+static int compress_blocks_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &mom,
+                                const float *residual, float *residual_out, uint32_t *out_block_idx,
+                                float *out_val, int32_t *out_counts, void *workspace, void *stream_) {
     if (!plan || !plan->blocks || !grad || !residual || !residual_out || !out_block_idx || !out_val ||
         !out_counts || !workspace)
         return RSDGC_EINVAL;
     if (!aligned256(workspace) || !aligned16(grad) || !aligned16(residual) || !aligned16(residual_out))
         return RSDGC_EINVAL;
-    if (residual_out != residual) {     // a second arena must overlap neither input
+    {
+        // an output arena may be its own input (no element is read by two tiles) and nothing else
         const uintptr_t bytes = static_cast<uintptr_t>(plan->total_elems) * sizeof(float);
-        const uintptr_t o = reinterpret_cast<uintptr_t>(residual_out);
-        const uintptr_t r = reinterpret_cast<uintptr_t>(residual), g = reinterpret_cast<uintptr_t>(grad);
-        if ((o < r + bytes && r < o + bytes) || (o < g + bytes && g < o + bytes)) return RSDGC_EINVAL;
-    } else {
-        const uintptr_t bytes = static_cast<uintptr_t>(plan->total_elems) * sizeof(float);
-        const uintptr_t o = reinterpret_cast<uintptr_t>(residual_out), g = reinterpret_cast<uintptr_t>(grad);
-        if (o < g + bytes && g < o + bytes) return RSDGC_EINVAL;
+        if (arenas_clash(residual_out, residual, bytes, true) || arenas_clash(residual_out, grad, bytes, false))
+            return RSDGC_EINVAL;
+        if (mom.in) {
+            if (!mom.out || !aligned16(mom.in) || !aligned16(mom.out)) return RSDGC_EINVAL;
+            if (arenas_clash(mom.out, mom.in, bytes, true) || arenas_clash(mom.out, grad, bytes, false) ||
+                arenas_clash(mom.out, residual, bytes, false) || arenas_clash(mom.out, residual_out, bytes, false) ||
+                arenas_clash(mom.in, residual_out, bytes, false))
+                return RSDGC_EINVAL;
+        }
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     char *ws_outer = static_cast<char *>(workspace);
@@ -3162,21 +3194,26 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
     for (int pp = 1; pp <= RSDGC_MAX_P; pp += 2) {
         if (!have[pp]) continue;
         switch (pp) {
-#define RSDGC_BLOCK_LAUNCH(PP, FF)                                                               \
+#define RSDGC_BLOCK_LAUNCH(PP, FF, MM)                                                           \
     {                                                                                            \
-        static const uint32_t resident = resident_workgroups(k_block_nsi<PP, FF>);               \
-        hipLaunchKernelGGL((k_block_nsi<PP, FF>), dim3(std::min<uint32_t>(plan->n_tiles_all, resident)), \
+        static const uint32_t resident = resident_workgroups(k_block_nsi<PP, FF, MM>);           \
+        hipLaunchKernelGGL((k_block_nsi<PP, FF, MM>), dim3(std::min<uint32_t>(plan->n_tiles_all, resident)), \
                            dim3(256), 0, stream, outer,                                          \
                            reinterpret_cast<const DirEntry *>(ws_outer + plan->ws.all_tile_dir), \
                            static_cast<uint32_t>(L), plan->n_tiles_all, inner, grad, residual,   \
                            residual_out, score_map, hist, plan->alpha,                           \
                            feed + static_cast<size_t>(PP / 2) * kFeedDomains * kFeedStride,      \
-                           feed_shift);                                                          \
+                           feed_shift, mom.in, mom.out, mom.m);                                  \
     }
 #define RSDGC_BLOCK_CASE(PP)                                                                     \
     case PP: {                                                                                   \
-        if (fed) RSDGC_BLOCK_LAUNCH(PP, true)                                                    \
-        else RSDGC_BLOCK_LAUNCH(PP, false)                                                       \
+        if (mom.in) {                                                                            \
+            if (fed) RSDGC_BLOCK_LAUNCH(PP, true, true)                                          \
+            else RSDGC_BLOCK_LAUNCH(PP, false, true)                                             \
+        } else {                                                                                 \
+            if (fed) RSDGC_BLOCK_LAUNCH(PP, true, false)                                         \
+            else RSDGC_BLOCK_LAUNCH(PP, false, false)                                            \
+        }                                                                                        \
         break;                                                                                   \
     }
             RSDGC_BLOCK_CASE(1)
@@ -3193,9 +3230,29 @@ int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *re
     rc = select_mark_count(in, ws, false, marks, nullptr, stream);
     if (rc != RSDGC_OK) return rc;
     hipLaunchKernelGGL(k_emit_blocks, dim3(in->n_chunks), dim3(256), 0, stream, outer, inner_chunks, mask,
-                       chunk_cnt, group_cnt, inner, residual_out, out_block_idx, out_val, out_counts);
+                       chunk_cnt, group_cnt, inner, residual_out, mom.out, out_block_idx, out_val, out_counts);
     HIP_TRY(hipGetLastError());
     return RSDGC_OK;
+}
+
+int rsdgc_compress_blocks(rsdgc_plan_t *plan, const float *grad, const float *residual,
+                          float *residual_out, uint32_t *out_block_idx, float *out_val,
+                          int32_t *out_counts, void *workspace, void *stream) {
+    return compress_blocks_impl(plan, grad, Momentum(), residual, residual_out, out_block_idx, out_val,
+                                out_counts, workspace, stream);
+}
+
+int rsdgc_compress_blocks_momentum(rsdgc_plan_t *plan, const float *grad, const float *momentum,
+                                   float *momentum_out, float m, const float *residual,
+                                   float *residual_out, uint32_t *out_block_idx, float *out_val,
+                                   int32_t *out_counts, void *workspace, void *stream) {
+    if (!momentum || !momentum_out || !(m >= 0.f && m <= 1.f)) return RSDGC_EINVAL;
+    Momentum mom;
+    mom.in = momentum;
+    mom.out = momentum_out;
+    mom.m = m;
+    return compress_blocks_impl(plan, grad, mom, residual, residual_out, out_block_idx, out_val,
+                                out_counts, workspace, stream);
 }
 
 int rsdgc_decompress_blocks(rsdgc_plan_t *plan, const uint32_t *block_idx, const float *val,

@@ -137,7 +137,7 @@ class BlockSession:
 
     def __init__(self, shapes, p: int, alpha: float, ratios: Sequence[float],
                  p_per_layer: Optional[Sequence[int]] = None, device: str = "cuda:0", in_place: bool = False,
-                 work_feed: int = binding.FEED_AUTO):
+                 work_feed: int = binding.FEED_AUTO, momentum: Optional[float] = None):
         self.shapes = [(int(r), int(c)) for r, c in shapes]
         self.p_list = [int(x) for x in p_per_layer] if p_per_layer is not None else [int(p)] * len(self.shapes)
         self.plan = binding.rsdgc_plan_blocks(self.shapes, p, alpha, ratios, p_per_layer)
@@ -150,6 +150,11 @@ class BlockSession:
         self.residual = torch.zeros(n, dtype=torch.float32, device=dev)
         self.in_place = in_place
         self.residual_next = None if in_place else torch.zeros(n, dtype=torch.float32, device=dev)
+        self.m = momentum
+        self.momentum_buf = self.momentum_next = None
+        if momentum is not None:
+            self.momentum_buf = torch.zeros(n, dtype=torch.float32, device=dev)
+            self.momentum_next = None if in_place else torch.zeros(n, dtype=torch.float32, device=dev)
         self.out_blocks = torch.zeros(max(1, self.plan.centre_capacity), dtype=torch.int32, device=dev)
         self.out_val = torch.zeros(max(1, self.plan.out_capacity), dtype=torch.float32, device=dev)
         self.out_counts = torch.zeros(L, dtype=torch.int32, device=dev)
@@ -167,10 +172,21 @@ class BlockSession:
     def set_residual(self, arrays):
         self.pack(arrays, self.residual)
 
+    def set_momentum(self, arrays):
+        self.pack(arrays, self.momentum_buf)
+
     def compress(self, stream=None) -> None:
         target = self.residual if self.in_place else self.residual_next
-        binding.rsdgc_compress_blocks(self.plan, self.grad, self.residual, target, self.out_blocks,
-                                      self.out_val, self.out_counts, self.workspace, stream)
+        if self.m is not None:
+            u_target = self.momentum_buf if self.in_place else self.momentum_next
+            binding.rsdgc_compress_blocks_momentum(self.plan, self.grad, self.momentum_buf, u_target, self.m,
+                                                   self.residual, target, self.out_blocks, self.out_val,
+                                                   self.out_counts, self.workspace, stream)
+            if not self.in_place:
+                self.momentum_buf, self.momentum_next = self.momentum_next, self.momentum_buf
+        else:
+            binding.rsdgc_compress_blocks(self.plan, self.grad, self.residual, target, self.out_blocks,
+                                          self.out_val, self.out_counts, self.workspace, stream)
         if not self.in_place:
             self.residual, self.residual_next = self.residual_next, self.residual
 

@@ -202,30 +202,42 @@ def test_apply_at_vgg19_size_four_equal_messages():
         assert np.array_equal(after[l].reshape(-1).view(np.uint32), want.view(np.uint32)), l
 
 
-def test_vgg19_full_size_block_reading_against_oracle():
-    """Non-overlapping 3 x 3 neighbourhoods on the VGG-19-shaped gradient: kept blocks, values and
-    residual against the complete oracle, layer by layer."""
+@pytest.mark.parametrize("m", [None, 0.9], ids=["plain", "momentum"])
+def test_vgg19_full_size_block_reading_against_oracle(m):
+    """Non-overlapping 3 x 3 neighbourhoods on the VGG-19-shaped gradient: kept blocks, values,
+    residual (and, with Eq. 12's momentum, the new momentum) against the complete oracle, layer
+    by layer."""
     import torch
     from paper_2312_17530_amd.session import BlockSession
     w = synth.config(3)
-    sess = BlockSession(w.shapes, w.p, w.alpha, w.ratios)
+    sess = BlockSession(w.shapes, w.p, w.alpha, w.ratios, momentum=m)
     grads = synth.gradients(w, 0)
     resid = synth.gradients(w, 9)
+    mom = synth.gradients(w, 8) if m is not None else None
     sess.set_grad(grads)
     sess.set_residual(resid)
+    if m is not None:
+        sess.set_momentum(mom)
     sess.compress()
     torch.cuda.synchronize()
     res = sess.results()
     gpu_r = sess.unpack(sess.residual)
+    gpu_u = sess.unpack(sess.momentum_buf) if m is not None else None
     n_exact = 0
     for l, sh in enumerate(w.shapes):
         print("checking blocks", l, sh, flush=True)
-        o = oracle.compress_layer_blocks(grads[l], resid[l], w.p, w.alpha, w.ratios[l])
+        if m is None:
+            o = oracle.compress_layer_blocks(grads[l], resid[l], w.p, w.alpha, w.ratios[l])
+        else:
+            om = oracle.compress_layer_blocks_momentum(grads[l], mom[l], resid[l], m, w.p, w.alpha, w.ratios[l])
+            o = om.layer
         gb, gv = res[l]
         assert len(gb) == o.k == sess.plan.layer_k(l)
         if np.array_equal(gb, o.blocks):
             assert np.array_equal(gv.view(np.uint32), o.val.view(np.uint32)), l
             assert np.array_equal(gpu_r[l].view(np.uint32), o.r_new.view(np.uint32)), l
+            if m is not None:
+                assert np.array_equal(gpu_u[l].view(np.uint32), om.u_new.view(np.uint32)), l
             n_exact += 1
         else:                                   # only scores within the tolerance band may differ
             s = o.nsi.ravel().astype(np.float64)

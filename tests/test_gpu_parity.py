@@ -263,26 +263,37 @@ def test_apply_messages_of_three_nodes_matches_the_oracle():
         weights = got
 
 
-def run_and_check_blocks(shapes, p_list, alpha, ratios, grads_per_iter, name, in_place=False, work_feed=0):
-    """The block reading on GPU and oracle from identical state; returns (compared, exact)."""
+def run_and_check_blocks(shapes, p_list, alpha, ratios, grads_per_iter, name, in_place=False, work_feed=0,
+                         m=None, u0=None):
+    """The block reading on GPU and oracle from identical state; returns (compared, exact).
+    With m: Eq. 12's momentum carried beside the residual (u0: momentum before the first call)."""
     import torch
     from paper_2312_17530_amd.session import BlockSession
-    sess = BlockSession(shapes, p_list[0], alpha, ratios, p_list, in_place=in_place, work_feed=work_feed)
+    sess = BlockSession(shapes, p_list[0], alpha, ratios, p_list, in_place=in_place, work_feed=work_feed,
+                        momentum=m)
     resid = [np.zeros(sh, dtype=np.float32) for sh in shapes]
+    mom = None if m is None else (u0 if u0 is not None else [np.zeros(sh, dtype=np.float32) for sh in shapes])
     n_cmp = n_exact = 0
     for t, grads in enumerate(grads_per_iter):
         sess.set_grad(grads)
         sess.set_residual(resid)
+        if m is not None:
+            sess.set_momentum(mom)
         sess.compress()
         torch.cuda.synchronize()
         res = sess.results()
         gpu_r = sess.unpack(sess.residual)
+        gpu_u = sess.unpack(sess.momentum_buf) if m is not None else None
         dense = sess.unpack(sess.decompress(accumulate=False))
-        new_resid = []
+        new_resid, new_mom = [], []
         for l, sh in enumerate(shapes):
             p = p_list[l]
-            o = oracle.compress_layer_blocks(grads[l], resid[l], p, alpha, ratios[l])
-            tag = f"{name}[blocks,t={t},l={l},{sh},p={p}]"
+            if m is None:
+                o = oracle.compress_layer_blocks(grads[l], resid[l], p, alpha, ratios[l])
+            else:
+                om = oracle.compress_layer_blocks_momentum(grads[l], mom[l], resid[l], m, p, alpha, ratios[l])
+                o = om.layer
+            tag = f"{name}[blocks,t={t},l={l},{sh},p={p},m={m}]"
             gb, gv = res[l]
             assert sess.plan.layer_k(l) == o.k and len(gb) == o.k, tag
             assert np.all(np.diff(gb.astype(np.int64)) > 0), tag
@@ -311,14 +322,27 @@ def run_and_check_blocks(shapes, p_list, alpha, ratios, grads_per_iter, name, in
             assert np.array_equal(gpu_r[l].view(np.uint32), want_r.view(np.uint32)), f"{tag}: residual"
             assert np.array_equal((dense[l] + gpu_r[l]).view(np.uint32), v.view(np.uint32)) or \
                 np.array_equal(dense[l] + gpu_r[l], v), f"{tag}: decompress"
+            if m is not None:
+                # u_new = m*u + g in two roundings, +0 on the slots of the GPU's own kept blocks
+                want_u = np.float32(m) * mom[l] + grads[l]
+                want_u[want_r.view(np.uint32) != v.view(np.uint32)] = 0.0      # (slots the residual cleared)
+                for b in gb:
+                    bx, by = divmod(int(b), BC)
+                    want_u[bx * p:bx * p + p, by * p:by * p + p] = 0.0
+                assert np.array_equal(gpu_u[l].view(np.uint32), want_u.view(np.uint32)), f"{tag}: momentum"
             exact = np.array_equal(gb, o.blocks)
             if exact:
                 assert np.array_equal(gv.view(np.uint32), o.val.view(np.uint32)), tag
                 assert np.array_equal(gpu_r[l].view(np.uint32), o.r_new.view(np.uint32)), tag
+                if m is not None:
+                    assert np.array_equal(gpu_u[l].view(np.uint32), om.u_new.view(np.uint32)), tag
             n_cmp += 1
             n_exact += int(exact)
             new_resid.append(o.r_new)
+            if m is not None:
+                new_mom.append(om.u_new)
         resid = new_resid
+        mom = new_mom
     return n_cmp, n_exact
 
 
@@ -329,6 +353,58 @@ def test_blocks_ragged_shapes_mixed_p_two_iterations(in_place):
     its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 19, t, l) for l, sh in enumerate(shapes)] for t in range(2)]
     n, ex = run_and_check_blocks(shapes, p_list, 0.5, ratios, its, "ragged", in_place=in_place)
     assert n == 2 * len(shapes) and ex >= n - 2
+
+
+@pytest.mark.parametrize("m", [0.9, 0.0, 1.0])
+def test_blocks_momentum_ragged_shapes_mixed_p_three_iterations(m, in_place):
+    """Eq. 12 in full under the block reading: u and r carried over three iterations from a
+    non-zero momentum, every neighbourhood side, ragged shapes, both arena forms."""
+    shapes = RAGGED + [(300, 700), (512, 1152)]
+    p_list = [1, 3, 5, 7, 3, 5, 3, 3, 7, 5, 3, 1, 3, 5, 3, 3]
+    ratios = [1.0, 0.1, 0.1, 1.0, 0.02, 0.05, 0.02, 0.01, 0.3, 0.001, 0.5, 0.07, 0.0, 1.0, 0.02, 0.01]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 23, t, l) for l, sh in enumerate(shapes)] for t in range(3)]
+    u0 = [synth.layer_gradient(sh, 2e-3, 24, 0, l) for l, sh in enumerate(shapes)]
+    n, ex = run_and_check_blocks(shapes, p_list, 0.5, ratios, its, "ragged_momentum", in_place=in_place, m=m, u0=u0)
+    assert n == 3 * len(shapes) and ex >= n - 3
+
+
+def test_blocks_momentum_resnet18_shapes_with_the_work_feed():
+    w = synth.scaled_down(synth.config(1), 256, 1024)
+    its = [synth.gradients(w, t) for t in range(2)]
+    for feed in (FEED_AUTO, FEED_ON):
+        n, ex = run_and_check_blocks(w.shapes, [w.p] * len(w.shapes), w.alpha, w.ratios, its, "resnet18_momentum",
+                                     m=0.9, work_feed=feed)
+        assert ex >= n - 2
+
+
+def test_blocks_momentum_zero_gives_the_plain_block_message_and_refuses_overlapping_arenas():
+    import torch
+    from paper_2312_17530_amd import binding
+    from paper_2312_17530_amd.session import BlockSession
+    shapes, ratios = [(64, 100), (40, 52), (31, 29)], [0.1, 0.2, 0.1]
+    grads = [synth.layer_gradient(sh, 1e-2, 86, 0, l) for l, sh in enumerate(shapes)]
+    a = BlockSession(shapes, 3, 0.5, ratios)
+    b = BlockSession(shapes, 3, 0.5, ratios, momentum=0.0)
+    for s in (a, b):
+        s.set_grad(grads)
+    b.set_momentum([synth.layer_gradient(sh, 1.0, 87, 0, l) for l, sh in enumerate(shapes)])
+    a.compress()
+    b.compress()
+    for (b1, v1), (b2, v2) in zip(a.results(), b.results()):
+        assert np.array_equal(b1, b2) and np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
+    assert torch.equal(a.residual, b.residual)
+    # overlapping arenas (other than an output on its own input) are refused before any launch
+    s = b
+    bad = [dict(momentum_out=s.grad), dict(momentum_out=s.residual), dict(residual_out=s.momentum_buf),
+           dict(momentum=s.residual_next), dict(m=1.5), dict(m=float("nan"))]
+    for change in bad:
+        args = dict(grad=s.grad, momentum=s.momentum_buf, momentum_out=s.momentum_next, m=0.5,
+                    residual=s.residual, residual_out=s.residual_next)
+        args.update(change)
+        with pytest.raises(binding.RsdgcError):
+            binding.rsdgc_compress_blocks_momentum(s.plan, args["grad"], args["momentum"], args["momentum_out"],
+                                                   args["m"], args["residual"], args["residual_out"],
+                                                   s.out_blocks, s.out_val, s.out_counts, s.workspace)
 
 
 def test_blocks_degenerate_inputs_follow_index_tie_break():
