@@ -158,6 +158,18 @@ def bench_blocks(args, w, grads) -> int:
     dt = time.perf_counter() - t0
     counts = sess.out_counts.cpu().numpy()
     n_blocks = int(counts.sum())
+    # the receiving side (Eq. 12, third line): eight nodes' block messages (eight times this node's own)
+    from paper_2312_17530_amd import binding
+    w_arena = torch.randn(sess.grad.numel(), dtype=torch.float32, device="cuda")
+    peers = [(sess.out_blocks, sess.out_val, sess.out_counts)] * 8
+    binding.rsdgc_apply_blocks(sess.plan, peers, w_arena, 0.1, sess.workspace, stream)
+    torch.cuda.synchronize()
+    t4 = time.perf_counter()
+    for _ in range(20):
+        binding.rsdgc_apply_blocks(sess.plan, peers, w_arena, 0.1, sess.workspace, stream)
+    torch.cuda.synchronize()
+    apply_ms = (time.perf_counter() - t4) / 20 * 1e3
+    del w_arena
     # read g, read r, write v (with momentum also read u, write u); one score per block
     alg = (20.0 if args.momentum is not None else 12.0) * G + 4.0 * G / (w.p * w.p)
     out = {
@@ -171,6 +183,8 @@ def bench_blocks(args, w, grads) -> int:
                      "achieved": alg / (dt / args.steps) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": alg / (dt / args.steps) / 1e9 / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes": alg},
+        "apply_8_messages_ms": round(apply_ms, 5),
+        "workspace_bytes": sess.plan.workspace_bytes,
     }
     if not args.no_cpu_baseline:
         import oracle

@@ -104,9 +104,8 @@ int rsdgc_plan_set_path(rsdgc_plan_t *plan, int32_t path);
 #define RSDGC_FEED_ON    2
 int rsdgc_plan_set_work_feed(rsdgc_plan_t *plan, int32_t mode);
 
-/* A plan remembers the address of the workspace it last prepared (tables
- * uploaded, message accumulator cleared) and skips that work while the address
- * stays the same.  Call this when the memory at that address has been freed,
+/* A plan remembers the address of the workspace it last prepared (its tables
+ * uploaded) and skips that work while the address stays the same.  Call this when the memory at that address has been freed,
  * reused or overwritten in the meantime: the next call with any workspace
  * prepares it afresh.  Host side only; no GPU work.                          */
 int rsdgc_plan_forget_workspace(rsdgc_plan_t *plan);
@@ -326,8 +325,11 @@ int rsdgc_apply(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *idx,
 
 /* The same for a plan from rsdgc_plan_blocks and messages as produced by
  * rsdgc_compress_blocks: block_idx[k], val[k] (p*p values per block) and
- * counts[k] of node k.  rsdgc_apply refuses a block plan and this call an
- * element plan (RSDGC_EINVAL).                                               */
+ * counts[k] of node k.  Every layer's block indices must be ascending, as
+ * rsdgc_compress_blocks writes them: a block is applied once, by the first
+ * message that names it, which finds it in the later ones by binary search.
+ * One launch, no scratch memory.  rsdgc_apply refuses a block plan and this
+ * call an element plan (RSDGC_EINVAL).                                        */
 int rsdgc_apply_blocks(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const *block_idx,
                        const float *const *val, const int32_t *const *counts, float *weights,
                        float eta, void *workspace, void *stream);

@@ -273,7 +273,6 @@ struct rsdgc_plan_s {
     const void *uploaded_ws = nullptr;
     int calls_since_upload = 0;         // compress calls since the tables went to uploaded_ws (counted up to kSamplingCalls)
     uint64_t uploaded_version = 0;
-    const void *acc_zero_ws = nullptr;  // workspace whose message accumulator is known to be all zero
     // block reading (non-overlapping p x p neighbourhoods): this plan describes the element
     // matrices; `inner` describes the block grids as layers with p = 1 and the same k_l, and
     // the selection machinery runs on it.  The workspace is this plan's tables followed by

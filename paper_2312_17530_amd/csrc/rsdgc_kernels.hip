@@ -39,7 +39,7 @@
 //   emit             k_emit, k_emit_sparse, k_emit_centres
 //   decompress       k_zero_layers, k_scatter
 //   block reading    k_block_nsi, k_emit_blocks, k_scatter_blocks
-//   apply            k_apply, k_apply_blocks (receiving side)
+//   apply            k_apply_ranges, k_apply_chunks, k_apply_single, k_apply_blocks (receiving side)
 //   dynamic ratios   k_dyn_*
 //   host side        launch helpers and the extern "C" entry points
 #include <hip/hip_runtime.h>
@@ -2521,20 +2521,51 @@ __global__ __launch_bounds__(256) void k_apply_single(const LayerDev *__restrict
     if (__float_as_uint(sum) != 0u) weights[pos] = weights[pos] - __fmul_rn(eta, sum);
 }
 
-// Block messages keep the accumulator form: the messages are summed into an arena that is all zero
-// between calls (k_scatter_blocks, message by message), then one thread per kept block of every
-// message exchanges each slot's sum with +0 and whoever gets a non-zero sum applies it.
-struct ApplyBlockMsgs {
-    const uint32_t *idx[RSDGC_MAX_MSGS];
-    const int32_t *counts[RSDGC_MAX_MSGS];
-};
+// Block messages (the block reading): one thread per kept block of every message.  The block
+// belongs to the lowest-numbered message that names it (the others find it there by binary
+// search in the layer's ascending block list and step aside); its owner looks the block up in
+// the later messages, adds their values slot by slot in message order -- plain float32 adds
+// starting from +0, as for element messages -- and updates the block's slots inside the matrix.
+// No atomics, no scratch memory.
+template <int P>
+__device__ __forceinline__ void apply_block(const LayerDev &O, int layer, uint32_t b, int k, uint32_t q,
+                                            int n_msgs, const ApplyMsgs &msgs,
+                                            float *__restrict__ weights, float eta) {
+    float sum[P * P];
+    {
+        const float *__restrict__ src = msgs.val[k] + O.out_off + static_cast<size_t>(q) * (P * P);
+#pragma unroll
+        for (int s = 0; s < P * P; ++s) sum[s] = 0.f + src[s];
+    }
+    for (int k2 = k + 1; k2 < n_msgs; ++k2) {
+        const uint32_t n2 = static_cast<uint32_t>(min(max(msgs.counts[k2][layer], 0), static_cast<int32_t>(O.k)));
+        const uint32_t *__restrict__ seg = msgs.idx[k2] + O.centre_off;
+        const uint32_t pos = lower_bound_u32(seg, n2, b);
+        if (pos < n2 && seg[pos] == b) {
+            const float *__restrict__ src = msgs.val[k2] + O.out_off + static_cast<size_t>(pos) * (P * P);
+#pragma unroll
+            for (int s = 0; s < P * P; ++s) sum[s] = sum[s] + src[s];
+        }
+    }
+    const int R = static_cast<int>(O.R), C = static_cast<int>(O.C);
+    const uint32_t BC = (O.C + P - 1) / P;
+    const int bx = static_cast<int>(b / BC), by = static_cast<int>(b - static_cast<uint32_t>(bx) * BC);
+#pragma unroll
+    for (int dx = 0; dx < P; ++dx)
+#pragma unroll
+        for (int dy = 0; dy < P; ++dy) {
+            const int x = bx * P + dx, y = by * P + dy;
+            if (x < R && y < C) {
+                const size_t pos = static_cast<size_t>(O.elem_off) + static_cast<size_t>(x) * C + y;
+                const float t = sum[dx * P + dy];
+                if (__float_as_uint(t) != 0u) weights[pos] = weights[pos] - __fmul_rn(eta, t);
+            }
+        }
+}
 
-// The same for block messages (the block reading): one thread per kept block of every message
-// walks the block's slots inside the matrix.
 __global__ __launch_bounds__(256) void k_apply_blocks(const LayerDev *__restrict__ outer, int n_layers,
-                                                      long long capacity, const ApplyBlockMsgs msgs,
-                                                      float *__restrict__ acc, float *__restrict__ weights,
-                                                      float eta) {
+                                                      long long capacity, int n_msgs, const ApplyMsgs msgs,
+                                                      float *__restrict__ weights, float eta) {
     const long long j = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
     if (j >= capacity) return;
     const int k = blockIdx.y;
@@ -2546,26 +2577,21 @@ __global__ __launch_bounds__(256) void k_apply_blocks(const LayerDev *__restrict
     const LayerDev O = outer[lo];
     const long long q = j - O.centre_off;
     if (q >= msgs.counts[k][lo] || q >= static_cast<long long>(O.k)) return;
-    const int P = static_cast<int>(O.p), R = static_cast<int>(O.R), C = static_cast<int>(O.C);
     const uint32_t BC = (O.C + O.p - 1) / O.p, BR = (O.R + O.p - 1) / O.p;
     const uint32_t b = msgs.idx[k][j];
-    if (b >= BR * BC) return;             // malformed message: ignore the block (k_scatter_blocks did too)
-    const int bx = static_cast<int>(b / BC), by = static_cast<int>(b - static_cast<uint32_t>(bx) * BC);
-    for (int dx = 0; dx < P; ++dx)
-        for (int dy = 0; dy < P; ++dy) {
-            const int x = bx * P + dx, y = by * P + dy;
-            if (x < R && y < C) {
-                const size_t pos = static_cast<size_t>(O.elem_off) + static_cast<size_t>(x) * C + y;
-                const float sum = atomicExch(&acc[pos], 0.f);
-                if (__float_as_uint(sum) != 0u) weights[pos] = weights[pos] - __fmul_rn(eta, sum);
-            }
-        }
-}
-
-__global__ __launch_bounds__(256) void k_fill_zero(uint4 *__restrict__ p, size_t n16) {
-    const size_t stride = static_cast<size_t>(gridDim.x) * 256;
-    for (size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride)
-        p[i] = make_uint4(0, 0, 0, 0);
+    if (b >= BR * BC) return;             // malformed message: ignore the block
+    for (int k2 = 0; k2 < k; ++k2) {      // an earlier message that names the block owns it
+        const uint32_t n2 = static_cast<uint32_t>(min(max(msgs.counts[k2][lo], 0), static_cast<int32_t>(O.k)));
+        const uint32_t *__restrict__ seg = msgs.idx[k2] + O.centre_off;
+        const uint32_t pos = lower_bound_u32(seg, n2, b);
+        if (pos < n2 && seg[pos] == b) return;
+    }
+    switch (O.p) {
+        case 1: apply_block<1>(O, lo, b, k, static_cast<uint32_t>(q), n_msgs, msgs, weights, eta); break;
+        case 3: apply_block<3>(O, lo, b, k, static_cast<uint32_t>(q), n_msgs, msgs, weights, eta); break;
+        case 5: apply_block<5>(O, lo, b, k, static_cast<uint32_t>(q), n_msgs, msgs, weights, eta); break;
+        default: apply_block<7>(O, lo, b, k, static_cast<uint32_t>(q), n_msgs, msgs, weights, eta); break;
+    }
 }
 
 // ------------------------------------------------------- dynamic ratios --
@@ -3331,29 +3357,18 @@ int rsdgc_apply_blocks(rsdgc_plan_t *plan, int32_t n_msgs, const uint32_t *const
     int rc = upload_tables(plan, workspace, stream);
     if (rc != RSDGC_OK) return rc;
     const LayerDev *outer = reinterpret_cast<const LayerDev *>(ws + plan->ws.layers);
-    // a block plan's workspace: its tables, the inner plan's workspace, then the accumulator
-    float *acc = reinterpret_cast<float *>(ws + plan->ws.table_bytes + plan->inner->ws.total);
     if (plan->centre_capacity == 0) return RSDGC_OK;   // no message can hold a block
-    if (plan->acc_zero_ws != workspace) {              // first use of this workspace: clear the accumulator
-        const size_t n16 = static_cast<size_t>(plan->total_elems) * sizeof(float) / 16;
-        hipLaunchKernelGGL(k_fill_zero, dim3(kNumCUs * 8u), dim3(256), 0, stream,
-                           reinterpret_cast<uint4 *>(acc), n16);
-        HIP_TRY(hipGetLastError());
-    }
-    plan->acc_zero_ws = nullptr;                       // not known to be zero until the apply kernel is enqueued
     const unsigned blocks = static_cast<unsigned>((plan->centre_capacity + 255) / 256);
-    ApplyBlockMsgs m;
+    ApplyMsgs m;
     std::memset(&m, 0, sizeof(m));
-    for (int k = 0; k < n_msgs; ++k) {                 // the sum, message by message, in the order given
-        hipLaunchKernelGGL(k_scatter_blocks, dim3(blocks), dim3(256), 0, stream, outer, plan->n_layers,
-                           static_cast<long long>(plan->centre_capacity), block_idx[k], val[k], counts[k], acc, 1);
+    for (int k = 0; k < n_msgs; ++k) {
         m.idx[k] = block_idx[k];
+        m.val[k] = val[k];
         m.counts[k] = counts[k];
     }
     hipLaunchKernelGGL(k_apply_blocks, dim3(blocks, static_cast<unsigned>(n_msgs)), dim3(256), 0, stream, outer,
-                       plan->n_layers, static_cast<long long>(plan->centre_capacity), m, acc, weights, eta);
+                       plan->n_layers, static_cast<long long>(plan->centre_capacity), n_msgs, m, weights, eta);
     HIP_TRY(hipGetLastError());
-    plan->acc_zero_ws = workspace;
     return RSDGC_OK;
 }
 

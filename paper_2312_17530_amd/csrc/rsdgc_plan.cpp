@@ -405,8 +405,7 @@ int rsdgc_plan_set_work_feed(rsdgc_plan_t *plan, int32_t mode) {
 
 int rsdgc_plan_forget_workspace(rsdgc_plan_t *plan) {
     if (!plan) return RSDGC_EINVAL;
-    plan->uploaded_ws = nullptr;       // the next call uploads the tables again ...
-    plan->acc_zero_ws = nullptr;       // ... and clears the message accumulator before it is used
+    plan->uploaded_ws = nullptr;       // the next call uploads the tables again
     if (plan->inner) plan->inner->uploaded_ws = nullptr;
     return RSDGC_OK;
 }
@@ -447,11 +446,9 @@ int64_t rsdgc_centre_capacity(const rsdgc_plan_t *plan) {
 }
 size_t rsdgc_workspace_bytes(const rsdgc_plan_t *plan) {
     if (!plan) return 0;
-    // a block plan: its own tables, the workspace of the plan that ranks the block grids, and the
-    // message accumulator of rsdgc_apply_blocks (float[total_elems]); all multiples of 256
-    if (plan->blocks)
-        return plan->ws.table_bytes + plan->inner->ws.total +
-               align_up(sizeof(float) * static_cast<size_t>(plan->total_elems), 256);
+    // a block plan: its own tables, then the workspace of the plan that ranks the block grids
+    // (both multiples of 256)
+    if (plan->blocks) return plan->ws.table_bytes + plan->inner->ws.total;
     return plan->ws.total;
 }
 
