@@ -434,14 +434,6 @@ __device__ __forceinline__ WaveBucket wave_find_bucket(const uint32_t *__restric
     return r;
 }
 
-// Candidate bound of a large layer from the scores of its sampled tiles (12-bit histogram hs):
-// the lower edge of the bucket at which `target` sampled scores are reached from the top; 0 when
-// the sample cannot supply the target or supplies it only from bucket 0.
-__device__ __forceinline__ uint32_t wave_bound_from_sample(const uint32_t *__restrict__ hs, uint32_t target) {
-    const WaveBucket r = wave_find_bucket(hs, target);
-    return r.found ? r.bucket << kCoarseShift : 0u;
-}
-
 // Work unit: one 16 x 256 tile of one layer.  The tile of v = r + g plus a halo of
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
 // down the 16 rows of one column, keeping per-row horizontal sums of |w|, w and w^2
@@ -902,19 +894,47 @@ __device__ __forceinline__ void mark_window(const WindowGeom &g, uint32_t i, uin
 }
 
 // ----------------------------------------------------------------- hint --
-// First calls with a workspace only: one wave per large layer that has no predicted bound turns
-// the layer's sampled scores into its candidate bound.  A layer whose sample gives none goes to
-// the full map.
-__global__ __launch_bounds__(64) void k_hint(const LayerDev *__restrict__ layers,
-                                             SelState *__restrict__ state,
-                                             const uint32_t *__restrict__ hist_s,
-                                             uint32_t *__restrict__ flags) {
-    const int l = blockIdx.x;
+// First calls with a workspace only: one workgroup per large layer that has no predicted bound
+// turns the layer's sampled scores (12-bit histogram) into its candidate bound: the lower edge
+// of the bucket at which the target count is reached from the top.  A layer whose sample gives
+// none (too few scores, or the target only in bucket 0) goes to the full map.
+__global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layers,
+                                              SelState *__restrict__ state,
+                                              const uint32_t *__restrict__ hist_s,
+                                              uint32_t *__restrict__ flags) {
+    __shared__ uint32_t wave_tot[4];
+    __shared__ DigitResult res;
+    const int l = blockIdx.x, tid = threadIdx.x;
     const SelState st = state[l];
     const uint32_t target = layers[l].hint_target;
-    if (st.mode != kModeCandidates || st.hint_key != 0u) return;
-    const uint32_t key = wave_bound_from_sample(hist_s + static_cast<size_t>(l) * kHistBins, target);
-    if (threadIdx.x == 0) {
+    constexpr int per = kHistBins / 256;
+    const uint32_t *__restrict__ hs = hist_s + static_cast<size_t>(l) * kHistBins;
+    const int hi = kHistBins - tid * per;          // thread 0 holds the top buckets
+    uint32_t v[per];
+    uint32_t own = 0;
+#pragma unroll
+    for (int j = 0; j < per; ++j) {                // (independent loads: one round trip)
+        v[j] = hs[hi - 1 - j];
+        own += v[j];
+    }
+    if (st.mode != kModeCandidates || st.hint_key != 0u) return;    // uniform
+    if (tid == 0) res.found = 0;
+    const uint32_t incl = block_scan_incl(own, wave_tot);
+    const uint32_t excl = incl - own;
+    if (excl < target && target <= incl) {
+        uint32_t acc = excl;
+#pragma unroll
+        for (int j = 0; j < per; ++j) {
+            if (acc < target && acc + v[j] >= target) {
+                res.digit = static_cast<uint32_t>(hi - 1 - j);
+                res.found = 1;
+            }
+            acc += v[j];
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t key = res.found ? res.digit << kCoarseShift : 0u;
         if (key != 0u) {
             state[l].hint_key = key;
         } else {
@@ -3028,7 +3048,7 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
     if (rc != RSDGC_OK) return rc;
     if (sampling)
-        hipLaunchKernelGGL(k_hint, dim3(L), dim3(64), 0, stream, layers, state,
+        hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state,
                            reinterpret_cast<const uint32_t *>(ws + w.hist_s), flags);
     marks.close(1);
     if (plan->any_large) {
