@@ -1057,8 +1057,16 @@ __global__ __launch_bounds__(256) void k_find0(const LayerDev *__restrict__ laye
 constexpr int kStage = 2048;            // staged keys per workgroup (a round adds at most 1024)
 constexpr int kSlotsPerWave = kSlotGroup / 4;   // tile slots of a group that one wave of a gather workgroup takes
 
+constexpr int kTileMaskWords = kTileRows * kTileCols / 32;    // mask words of one tile (rows of 8 words)
+
 struct GatherShared {
-    unsigned long long ent[kStage];     // staged keys
+    union {
+        unsigned long long ent[kStage];               // score-map roles: staged keys
+        struct {                                      // slot role:
+            uint32_t bits[kSlotGroup * kTileMaskWords];   // mask words of the group of tiles being written
+            uint32_t spre[65];                            // entries before each of the (at most 54) slots around that group; [64]: all
+        };
+    };
     uint32_t hist[kLevel1Bins];         // second-digit counts
     DigitResult res;
     uint32_t n;                         // staged keys
@@ -1258,10 +1266,85 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
                 }
             }
         } else {
-            // each wave takes 4 of the group's tile slots; a round covers 64 entries of each
             const uint32_t slot_cap = L.slot_cap;
             const unsigned long long *__restrict__ ent0 =
                 a.slot_ent + L.slot_off + static_cast<size_t>(ge.slot0 - L.tile_begin_all) * slot_cap;
+            const WindowGeom geom = {static_cast<size_t>(L.elem_off), static_cast<int>(L.R), static_cast<int>(L.C),
+                                     (static_cast<int>(L.p) - 1) / 2};
+            if ((L.C & 31u) == 0u) {
+                // Rows of whole mask words: every mask word of the layer lies in exactly one tile.  The
+                // workgroup builds the words of its group of tiles in LDS from the group's own candidates
+                // and writes them with plain stores, whole cache lines at a time -- except the words that
+                // windows of other groups' candidates can reach (the h rows along a tile's upper and lower
+                // edge, the first and last word of the group's run of tiles): those, and the bits that the
+                // group's windows set in other groups' tiles, are ORed into the (cleared) mask.
+                const int h = geom.h, C = geom.C, R = geom.R;
+                const int tiles_x = static_cast<int>(L.tiles_x);
+                const int g0 = static_cast<int>(ge.slot0 - L.tile_begin_all), gn = static_cast<int>(ge.ntile);
+                __syncthreads();                                 // (the previous group's words are written)
+                for (int i = tid; i < kSlotGroup * kTileMaskWords; i += 256) sh.bits[i] = 0u;
+                __syncthreads();
+                {
+                    // sixteen lanes per tile slot; a round covers 16 entries of each
+                    const int sidx0 = tid >> 4;
+                    const uint32_t cnt = sidx0 < gn ? min(a.slot_cnt[ge.slot0 + static_cast<uint32_t>(sidx0)], slot_cap) : 0u;
+                    for (uint32_t j = static_cast<uint32_t>(tid) & 15u; j < cnt; j += 16u) {
+                        const unsigned long long K = ent0[static_cast<size_t>(sidx0) * slot_cap + j];
+                        const uint32_t score = static_cast<uint32_t>(K >> 32);
+                        if (score >= above) {                    // selected for certain: its window, tile by tile
+                            const uint32_t i = ~static_cast<uint32_t>(K);
+                            const int xc = static_cast<int>(i / static_cast<uint32_t>(C));
+                            const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * static_cast<uint32_t>(C));
+                            const int wx0 = max(0, xc - h), wx1 = min(R - 1, xc + h);
+                            const int wy0 = max(0, yc - h), wy1 = min(C - 1, yc + h);
+                            for (int tr = wx0 / kTileRows; tr <= wx1 / kTileRows; ++tr)
+                                for (int tc = wy0 / kTileCols; tc <= wy1 / kTileCols; ++tc) {
+                                    const int sidx = tr * tiles_x + tc - g0;
+                                    const bool mine = static_cast<uint32_t>(sidx) < static_cast<uint32_t>(gn);
+                                    const int r0 = tr * kTileRows, c0 = tc * kTileCols;
+                                    const int xa = max(r0, wx0), xb = min(r0 + kTileRows - 1, wx1);
+                                    const int ya = max(c0, wy0) - c0, yb = min(c0 + kTileCols - 1, wy1) - c0;
+                                    const uint32_t w0 = static_cast<uint32_t>(ya) >> 5, b0 = static_cast<uint32_t>(ya) & 31u;
+                                    const uint32_t len = static_cast<uint32_t>(yb - ya + 1);
+                                    const uint32_t run = (1u << len) - 1u;
+                                    for (int x = xa; x <= xb; ++x) {
+                                        uint32_t *row = mine ? sh.bits + sidx * kTileMaskWords + (x - r0) * (kTileCols / 32)
+                                                             : a.mask + ((geom.elem_off + static_cast<size_t>(x) * C + c0) >> 5);
+                                        atomicOr(&row[w0], run << b0);
+                                        if (b0 + len > 32u) atomicOr(&row[w0 + 1], run >> (32u - b0));
+                                    }
+                                }
+                            if (a.cmask) {
+                                const size_t pos = geom.elem_off + i;
+                                atomicOr(&a.cmask[pos >> 5], 1u << (pos & 31));
+                            }
+                        } else if (score - lo < width) {         // in the threshold bucket (never when the layer is done):
+                            const uint32_t pos = atomicAdd(list.cnt, 1u);       // few of them, one atomic each
+                            if (pos < list.cap) list.ent[pos] = K;
+                            atomicAdd(&sh.hist[(score - lo) >> shift1], 1u);
+                        }
+                    }
+                }
+                __syncthreads();
+                // The group's words.  Neighbouring tiles of one tile row are neighbours in memory:
+                // consecutive threads walk along a matrix row through the group's tiles, so a wave writes
+                // whole cache lines.  Words past the end of a matrix row or below the last row do not exist.
+                for (int i = tid; i < gn * kTileMaskWords; i += 256) {
+                    const int rr = i / (gn * 8), rem = i - rr * (gn * 8), sidx = rem >> 3, ww = rem & 7;
+                    const int local = g0 + sidx, tr = local / tiles_x, tc = local - tr * tiles_x;
+                    const int x = tr * kTileRows + rr, y = tc * kTileCols + 32 * ww;
+                    if (x < R && y < C) {
+                        const uint32_t word = sh.bits[sidx * kTileMaskWords + rr * 8 + ww];
+                        uint32_t *dst = a.mask + ((geom.elem_off + static_cast<size_t>(x) * C + y) >> 5);
+                        const bool shared = (rr < h && tr > 0) || (rr >= kTileRows - h && x + h >= (tr + 1) * kTileRows && (tr + 1) * kTileRows < R) ||
+                                            (ww == 0 && sidx == 0 && tc > 0) ||
+                                            (ww == 7 && sidx == gn - 1 && tc < tiles_x - 1);
+                        if (!shared) *dst = word;
+                        else if (word != 0u) atomicOr(dst, word);
+                    }
+                }
+            } else {
+            // each wave takes 4 of the group's tile slots; a round covers 64 entries of each
             uint32_t cnt[kSlotsPerWave];
             uint32_t longest = 0;
 #pragma unroll
@@ -1270,8 +1353,6 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
                 cnt[c] = s < ge.ntile ? min(a.slot_cnt[ge.slot0 + s], slot_cap) : 0u;
                 longest = max(longest, cnt[c]);                     // wave-uniform
             }
-            const WindowGeom geom = {static_cast<size_t>(L.elem_off), static_cast<int>(L.R), static_cast<int>(L.C),
-                                     (static_cast<int>(L.p) - 1) / 2};
             for (uint32_t j0 = 0; j0 < longest; j0 += 64) {
                 const uint32_t j = j0 + lane;
                 unsigned long long K[kSlotsPerWave];
@@ -1297,6 +1378,7 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
                         }
                     }
                 }
+            }
             }
         }
     }
@@ -3044,7 +3126,9 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     marks.close(0);
 
     // first pass: every tile of the layers ranked on the full map (scores, histogram, v) and, where a
-    // large layer has no predicted bound, its sampled tiles (histogram only) share one launch
+    // large layer has no predicted bound, its sampled tiles (histogram only) share one launch.
+    // (Running it on a second stream beside the main pass, which does not depend on it once the
+    // bounds are predicted, was measured: the two event waits cost more than the overlap gains.)
     rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
     if (rc != RSDGC_OK) return rc;
     if (sampling)
