@@ -79,14 +79,15 @@ int rsdgc_plan(const rsdgc_shape_t *shapes, int32_t n_layers, int32_t p,
 int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio);
 
 /* How the per-layer ranking (Algorithm 1) is carried out; the result is the same.
- *   RSDGC_PATH_AUTO      large layers record only the centres whose score reaches a
- *                        bound and rank those.  The bound comes from the thresholds
- *                        the same layer ended on in the two calls before (kept in the
- *                        workspace), or, in the first sixteen calls with a workspace,
- *                        from a sample of the layer's tiles.
- *                        A layer falls back to the full map within the call when the
- *                        bound turns out too high or a tile holds too many such
- *                        centres (default).
+ *   RSDGC_PATH_AUTO      every layer whose keep ratio leaves room for it (8 k_l per 16 x 256
+ *                        tile within a tile's 512 candidate entries: up to about 14 % for
+ *                        p = 3) records only the centres whose score reaches a bound and
+ *                        ranks those.  The bound comes from the thresholds the same layer
+ *                        ended on in the two calls before (kept in the workspace), or, in
+ *                        the first sixteen calls with a workspace, from a sample of the
+ *                        layer's tiles.  A layer falls back to the full map within the call
+ *                        when the bound turns out too high or a tile holds too many such
+ *                        centres (default).  The other layers are ranked on the full map.
  *   RSDGC_PATH_FULL_MAP  every layer writes its full score map and ranks it with
  *                        histogram passes over all elements.                       */
 #define RSDGC_PATH_AUTO      0
@@ -352,11 +353,10 @@ const char *rsdgc_stage_name(int32_t stage);
  * from the layer's earlier thresholds.  Waits for `stream`, then copies from the device.
  * The path never changes a result.  A layer that would take path 0 or 3 shows 1 when
  *   - its bound failed in this call (too few centres above it, or too many in one tile):
- *     the call then ranked the full map, the layer's safety margin is doubled and the
- *     prediction pauses for four calls;
- *   - no bound could be predicted (prediction paused, or the last two thresholds lie more
- *     than about 10 % apart) and the workspace is past its first sixteen calls, the only
- *     ones that sample tiles for a bound.                                              */
+ *     the call then ranked the full map, and the layer's safety margin is doubled; during
+ *     the first sixteen calls with a workspace the next four bounds are sampled ones;
+ *   - the workspace is past those sixteen calls, the only ones that sample tiles, and one
+ *     of the layer's last two thresholds is zero or subnormal (nothing to predict from). */
 int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream);
 
 /* ----------------------------------------------------------- diagnostics */

@@ -14,8 +14,7 @@ constexpr int kTileCols = 256;       // NSI tile: output columns per workgroup
 constexpr int kChunk = 8192;         // elements per workgroup in the 1-D passes
 constexpr int kHistBins = 4096;      // widest radix digit (12 bits)
 constexpr int kLayerAlign = 64;      // arena alignment of a layer, in elements
-constexpr int kSlotCap = 256;        // candidate centres one tile of a large layer can record ...
-constexpr int kSlotCapMax = 512;     // ... or twice that where the layer's keep ratio asks for it
+constexpr int kSlotCapMax = 512;     // candidate centres one tile of a layer on the candidate path can record
 constexpr int kSlotGroup = 16;       // tile slots per work item of the candidate passes (one per wave)
 constexpr int kFineShift = 13;       // candidate path: the first ranking digit counts score bits in steps of 2^13
 constexpr int kFineBins = 1024;      // ... relative to the candidate bound: 1024 bins = one binade above it
@@ -29,7 +28,6 @@ constexpr int kChunkGroup = 64;      // chunks per group in the two-level chunk 
 constexpr int kListShards = 16;      // a layer's threshold-bucket list is filled through this many counters
 constexpr int kListCntStride = 32;   // uint32 between two of them (one 128-byte line each)
 constexpr int kBigMapLayer = 1 << 20; // elements from which a full-map layer's bucket list goes through k_filter
-constexpr int kMinSampledTiles = 8;  // a layer takes the candidate path only with this many sampled tiles
 // Candidate bound predicted from the thresholds of the two calls before, on a log2 scale: used
 // while the threshold moved by at most kTrendMaxLog2 between those calls.
 constexpr float kTrendMaxLog2 = 0.14f;         // a factor of 1.10 per call
@@ -56,15 +54,16 @@ enum LayerMode : uint32_t {
 
 // Sampled tiles of a layer: one tile in 2^shift, picked by a multiplicative hash of the
 // tile's index inside the layer.  Larger layers are sampled more thinly (the estimate only
-// needs a few hundred tiles).
+// needs a few hundred tiles); a layer of fewer than 128 tiles is "sampled" whole, so its bound
+// comes from all of its scores.
 #if defined(__HIPCC__)
 __host__ __device__
 #endif
 inline bool tile_is_sampled(uint32_t local_tile, uint32_t shift) {
-    return ((local_tile * 2654435761u) >> (32u - shift)) == 0u;
+    return shift == 0u || ((local_tile * 2654435761u) >> (32u - shift)) == 0u;
 }
 inline uint32_t sample_shift(uint32_t n_tiles) {
-    return n_tiles >= 16384u ? 6u : n_tiles >= 4096u ? 5u : 4u;
+    return n_tiles >= 16384u ? 6u : n_tiles >= 4096u ? 5u : n_tiles >= 128u ? 4u : 0u;
 }
 
 // One layer as the kernels see it.
@@ -84,7 +83,7 @@ struct LayerDev {
     uint32_t n_sampled;     // sampled tiles of the layer
     uint32_t list_cap;      // capacity of the threshold-bucket list
     uint32_t list_shards;   // shards the list is split into (each list_cap / list_shards entries, own counter)
-    uint32_t slot_cap;      // entries per tile slot (kSlotCap or kSlotCapMax)
+    uint32_t slot_cap;      // entries per tile slot (kSlotCapMax)
 };
 static_assert(sizeof(LayerDev) == 120, "LayerDev layout");
 
@@ -227,8 +226,9 @@ struct PGroup {           // layers sharing one neighbourhood side: one launch p
     uint32_t n_tiles = 0;
     uint32_t dir_begin = 0;     // index of the group's first DirEntry in tile_dir
     uint32_t dir_count = 0;     // entries excluding the sentinel
-    uint32_t sample_begin = 0;  // index of the group's first SampleEntry
-    uint32_t n_samples = 0;
+    uint32_t sample_begin = 0;  // index of the group's first SampleEntry: first every tile of the layers that are
+    uint32_t n_map_samples = 0; // always ranked on the full map (n_map_samples entries), then the sampled tiles
+    uint32_t n_samples = 0;     // of the others (n_samples entries in all)
     // the group's large layers only (the main pass and its fallback walk no other tiles, so
     // that equal shares of the walk are equal shares of the work)
     uint32_t large_dir_begin = 0;   // index of the first DirEntry in large_dir

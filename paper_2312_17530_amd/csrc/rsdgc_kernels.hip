@@ -134,6 +134,12 @@ __device__ __forceinline__ uint32_t block_scan_incl(uint32_t v, uint32_t *wave_t
     return block_scan_incl_n<4>(v, wave_tot);
 }
 
+// Safety margin (in log2 of the score) of a layer's first predicted bounds: the k-th largest of few
+// scores moves more from call to call than that of many.
+__device__ __forceinline__ float margin_init_log2(uint32_t k) {
+    return fmaxf(kMarginInitLog2, 0.75f * rsqrtf(static_cast<float>(max(k, 1u))));
+}
+
 // ---------------------------------------------------------------- begin --
 // Start of a compress call: all workgroups but the last clear the histograms, counters and
 // bitmasks; the last one writes every layer's initial selection state.  A large layer gets its
@@ -169,14 +175,20 @@ __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16
             s.predicted = 0;
             if (pred && s.mode == kModeCandidates) {
                 const PredState ps = pred[l];
-                if (ps.cooldown > 0) {
-                    pred[l].cooldown = ps.cooldown - 1;
-                } else if (ps.tau1 >= (1u << 23) && ps.tau2 >= (1u << 23)) {   // (both in the normal float32 range)
+                // after a failed bound the layer goes back to sampled bounds for a few calls -- where there
+                // are any: past the calls that sample, the alternative would be the full map, and the
+                // widened margin is tried at once
+                if (ps.cooldown > 0) pred[l].cooldown = ps.cooldown - 1;
+                if ((ps.cooldown == 0 || !sampling) &&
+                    ps.tau1 >= (1u << 23) && ps.tau2 >= (1u << 23)) {   // (both in the normal float32 range)
                     const float l1 = __log2f(__uint_as_float(ps.tau1)), l2 = __log2f(__uint_as_float(ps.tau2));
                     const float d = l1 - l2;
-                    if (fabsf(d) <= kTrendMaxLog2) {
-                        const float margin = ps.margin > 0.f ? ps.margin : kMarginInitLog2;
-                        const float bound = exp2f(l1 + (d > 0.f ? 0.6f * d : 1.15f * d) - margin);
+                    // (a threshold that jumps: sampled bounds while there are any; later the trend is
+                    // taken as far as it is trusted -- a bound that fails costs less than the full map)
+                    if (fabsf(d) <= kTrendMaxLog2 || !sampling) {
+                        const float margin = ps.margin > 0.f ? ps.margin : margin_init_log2(L.k);
+                        const float dd = fminf(fmaxf(d, -2.f * kTrendMaxLog2), kTrendMaxLog2);
+                        const float bound = exp2f(l1 + (dd > 0.f ? 0.6f * dd : 1.15f * dd) - margin);
                         const uint32_t key = __float_as_uint(bound);
                         if (key >= (1u << 23) && key < 0x7f800000u) {
                             s.hint_key = key;
@@ -1009,7 +1021,7 @@ __global__ __launch_bounds__(256) void k_find0(const LayerDev *__restrict__ laye
             flags[0] = 1u;                 // the fallback pass has work
             PredState ps = pred[l];
             ps.cooldown = kCooldownCalls;
-            ps.margin = fminf(2.f * (ps.margin > 0.f ? ps.margin : kMarginInitLog2), kMarginMaxLog2);
+            ps.margin = fminf(2.f * (ps.margin > 0.f ? ps.margin : margin_init_log2(layers[l].k)), kMarginMaxLog2);
             pred[l] = ps;
         }
         return;
@@ -1939,13 +1951,12 @@ __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__res
 // kernel.  The first wave does it (independent loads issued with the workgroup's other loads,
 // one wave reduction) and leaves the sum in *s_prefix; the caller reads it after its next
 // barrier.
-__device__ __forceinline__ void chunk_prefix_wave0(const ChunkInfo &ci, uint32_t c,
-                                                   const uint32_t *__restrict__ chunk_cnt,
-                                                   const uint32_t *__restrict__ group_cnt,
-                                                   uint32_t *s_prefix) {
-    if (threadIdx.x >= 64) return;
-    const uint32_t g0 = ci.layer_first_group + threadIdx.x, g1 = ci.group;
-    const uint32_t cc = ci.group_first_chunk + threadIdx.x;     // at most kChunkGroup - 1 = 63 of them
+__device__ __forceinline__ uint32_t chunk_prefix_by_wave(const ChunkInfo &ci, uint32_t c,
+                                                         const uint32_t *__restrict__ chunk_cnt,
+                                                         const uint32_t *__restrict__ group_cnt) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t g0 = ci.layer_first_group + lane, g1 = ci.group;
+    const uint32_t cc = ci.group_first_chunk + lane;     // at most kChunkGroup - 1 = 63 of them
     uint32_t v[5];
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] = g0 + 64 * j < g1 ? group_cnt[g0 + 64 * j] : 0u;
@@ -1954,6 +1965,15 @@ __device__ __forceinline__ void chunk_prefix_wave0(const ChunkInfo &ci, uint32_t
     for (uint32_t g = g0 + 256; g < g1; g += 64) own += group_cnt[g];     // layers beyond 2^27 elements
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) own += __shfl_xor(own, d, 64);
+    return own;                    // the same in every lane of the wave
+}
+
+__device__ __forceinline__ void chunk_prefix_wave0(const ChunkInfo &ci, uint32_t c,
+                                                   const uint32_t *__restrict__ chunk_cnt,
+                                                   const uint32_t *__restrict__ group_cnt,
+                                                   uint32_t *s_prefix) {
+    if (threadIdx.x >= 64) return;
+    const uint32_t own = chunk_prefix_by_wave(ci, c, chunk_cnt, group_cnt);
     if (threadIdx.x == 0) *s_prefix = own;
 }
 
@@ -2077,6 +2097,9 @@ __global__ __launch_bounds__(256) void k_emit(const LayerDev *__restrict__ layer
 // residual arena, so only the kept elements are touched -- their value goes out and the
 // arena gets +0 there.  A chunk without kept elements costs one read of its mask words.  A
 // layer with k_l = 0 went through no NSI pass; its v is formed here.
+// (Four chunks per workgroup -- a quarter of the dependent chains of mask word, prefix and kept
+// values, four value requests per thread in flight -- was built and measured: no faster.  The
+// kernel is bound by the rate of its scattered 4-byte reads and writes, not by their latency.)
 __global__ __launch_bounds__(256) void k_emit_sparse(const ChunkInfo *__restrict__ chunk_info,
                                                      const SelState *__restrict__ state,
                                                      const float *__restrict__ grad,
@@ -2873,7 +2896,8 @@ struct Momentum {                 // Eq. 12's momentum term; all null / 0 withou
 
 template <int PASS>
 int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const float *resid,
-               float *nsi_out, float *v_out, const Momentum &mom, hipStream_t stream) {
+               float *nsi_out, float *v_out, const Momentum &mom, hipStream_t stream,
+               bool with_sampled_tiles = true) {
     NsiArgs a;
     a.v_out = v_out;
     a.mom = mom.in;
@@ -2909,7 +2933,9 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
         a.n_tiles = g.n_tiles;
         a.samples = samples + g.sample_begin;
         // work items of this launch and the number of workgroups that share them
-        const uint32_t items = PASS == kPassSample ? g.n_samples : kLargeOnly ? g.n_large_tiles : g.n_tiles;
+        // (the first pass without the sampled tiles: only the layers that are always ranked on the full map)
+        const uint32_t items = PASS == kPassSample ? (with_sampled_tiles ? g.n_samples : g.n_map_samples)
+                                                   : kLargeOnly ? g.n_large_tiles : g.n_tiles;
         if (items == 0) continue;
         a.n_tiles = items;
         a.feed_shift = 7;                  // 128 items per domain and stretch: one per resident workgroup of an XCD
@@ -3129,7 +3155,7 @@ static int compress_impl(rsdgc_plan_t *plan, const float *grad, const Momentum &
     // large layer has no predicted bound, its sampled tiles (histogram only) share one launch.
     // (Running it on a second stream beside the main pass, which does not depend on it once the
     // bounds are predicted, was measured: the two event waits cost more than the overlap gains.)
-    rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream);
+    rc = launch_nsi<kPassSample>(plan, ws, grad, residual, nsi, v_out, mom, stream, sampling);
     if (rc != RSDGC_OK) return rc;
     if (sampling)
         hipLaunchKernelGGL(k_hint, dim3(L), dim3(256), 0, stream, layers, state,

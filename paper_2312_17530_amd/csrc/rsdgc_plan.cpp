@@ -82,23 +82,22 @@ int build_tables(rsdgc_plan_s *plan) {
         list_off += d.list_cap;
 
         // Candidate path: only the centres whose score reaches a bound are recorded, per tile, and
-        // ranked.  The bound aims at up to two times k_l centres (a predicted bound at fewer); a layer
-        // is eligible when a sample of its tiles can estimate such a bound (first calls) and when
-        // 16 k_l / tiles -- eight times that aim, for tiles that hold more than their share -- fits a
-        // tile's slot, which has kSlotCap entries, or kSlotCapMax where the keep ratio asks for it.
-        // A tile that still overflows sends the layer to the full map for that call.  (Halving the
-        // factor would move a layer with a keep ratio of 10 % onto this path; measured, the call as a
-        // whole gains 0.4 % from that: such a layer has many candidates to evaluate.)
+        // ranked.  The bound aims at up to two times k_l centres (a predicted bound at fewer).  A layer
+        // is eligible when 8 k_l / tiles -- four times that aim, for tiles that hold more than their
+        // share -- fits a tile's slot of kSlotCapMax entries.  A tile that still overflows sends the
+        // layer to the full map for that call.  Small layers are eligible too: once their bounds are
+        // predicted, no layer of a typical plan needs the separate score-map pass any more.  (Their
+        // thresholds move more from call to call, so their bounds sit lower; a tile of a narrow
+        // layer has fewer elements than a slot has entries and cannot overflow at all.)
         uint32_t n_sampled = 0;
         const uint32_t sshift = sample_shift(d.n_tiles);
         for (uint32_t t = 0; t < d.n_tiles; ++t) n_sampled += tile_is_sampled(t, sshift) ? 1u : 0u;
         d.n_sampled = n_sampled;
         const double frac = d.n_tiles ? double(n_sampled) / double(d.n_tiles) : 0.0;
         const double want = 2.0 * double(k) * frac;
-        const double per_tile = d.n_tiles ? 16.0 * double(k) / double(d.n_tiles) : 0.0;
-        d.large = (plan->allow_candidates && k > 0 && n_sampled >= uint32_t(kMinSampledTiles) &&
-                   per_tile <= double(kSlotCapMax)) ? 1u : 0u;
-        d.slot_cap = per_tile <= double(kSlotCap) ? kSlotCap : kSlotCapMax;
+        const double per_tile = d.n_tiles ? 8.0 * double(k) / double(d.n_tiles) : 0.0;
+        d.large = (plan->allow_candidates && k > 0 && per_tile <= double(kSlotCapMax)) ? 1u : 0u;
+        d.slot_cap = kSlotCapMax;
         d.slot_off = static_cast<uint64_t>(tile_begin_all) * kSlotCapMax;   // (room for either size: the
                                                                             // layout does not move with the ratios)
         d.hint_target = d.large ? static_cast<uint32_t>(std::ceil(want + 4.0 * std::sqrt(want) + 8.0)) : 0u;
@@ -170,11 +169,20 @@ int build_tables(rsdgc_plan_s *plan) {
                 g.n_large_tiles += d.n_tiles;
                 ++g.large_dir_count;
             }
-            // tile list of the first NSI pass: the sampled tiles of a large layer, every tile
-            // of any other layer that selects something
-            for (uint32_t t = 0; t < d.n_tiles; ++t)
-                if (d.large ? tile_is_sampled(t, sample_shift(d.n_tiles)) : d.k > 0)
-                    plan->samples.push_back(SampleEntry{static_cast<uint32_t>(l), t});
+        }
+        // tile list of the first NSI pass: every tile of the layers that select something and are not
+        // on the candidate path, then the sampled tiles of those that are (wanted only while bounds
+        // are still sampled)
+        for (int part = 0; part < 2; ++part) {
+            for (int l = 0; l < L; ++l) {
+                if (plan->p[l] != p) continue;
+                const LayerDev &d = plan->layers[l];
+                if ((d.large != 0u) != (part == 1)) continue;
+                for (uint32_t t = 0; t < d.n_tiles; ++t)
+                    if (d.large ? tile_is_sampled(t, sample_shift(d.n_tiles)) : d.k > 0)
+                        plan->samples.push_back(SampleEntry{static_cast<uint32_t>(l), t});
+            }
+            if (part == 0) g.n_map_samples = static_cast<uint32_t>(plan->samples.size()) - g.sample_begin;
         }
         if (g.dir_count == 0) continue;
         g.n_samples = static_cast<uint32_t>(plan->samples.size()) - g.sample_begin;
