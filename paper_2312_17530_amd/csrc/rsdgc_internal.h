@@ -33,6 +33,8 @@ constexpr int kBigMapLayer = 1 << 20; // elements from which a full-map layer's 
 constexpr float kTrendMaxLog2 = 0.14f;         // a factor of 1.10 per call
 constexpr float kMarginInitLog2 = 0.02f;       // safety margin below the lowest threshold expected (1.4 %)
 constexpr float kMarginMaxLog2 = 0.25f;        // it doubles after every failed bound, up to this
+constexpr float kMarginDecay = 0.97f;          // per call, back towards the initial margin
+constexpr float kMarginSafety = 1.5f;          // a forecast that came out too high by s widens the margin to 1.5 s + 0.01
 constexpr uint32_t kCooldownCalls = 4;         // calls without a predicted bound after a failed one
 constexpr int kSamplingCalls = 16;             // first calls with a workspace: a layer without a predicted bound
                                                // takes one sampled from the call's own scores (later: the full map)
@@ -76,7 +78,8 @@ struct LayerDev {
     uint32_t R, C, G, k;
     uint32_t p, tiles_x, tile_begin, n_tiles;   // tile_begin: first tile inside its p-group launch
     uint32_t chunk_begin, n_chunks, cap, tile_begin_all;  // tile_begin_all: first tile over all layers
-    uint32_t large;         // 1: eligible for the candidate path
+    uint32_t large;         // 1: eligible for the candidate path ("large layer" in the comments of this code: the
+                            //    name is from when only layers of many tiles were; today the keep ratio decides)
     uint32_t group_begin;   // first slot group of the layer
     uint32_t n_groups;      // ceil(n_tiles / kSlotGroup)
     uint32_t hint_target;   // sampled scores wanted at or above the candidate bound
@@ -105,10 +108,12 @@ static_assert(sizeof(SelState) == 40, "SelState layout");
 struct PredState {
     uint32_t tau1;          // score bits of the last call's threshold (0: none yet)
     uint32_t tau2;          // ... and of the call before it
-    float margin;           // safety margin below the predicted threshold, in log2 units (0: kMarginInitLog2)
+    float margin;           // safety margin below the predicted threshold, in log2 units (0: the initial one)
     uint32_t cooldown;      // calls left that take the sampled bound (after a failed bound)
+    float forecast;         // log2 of the threshold this call was expected to end on, before the margin ...
+    uint32_t has_forecast;  // ... when two earlier thresholds allowed one (also in calls that sample their bound)
 };
-static_assert(sizeof(PredState) == 16, "PredState layout");
+static_assert(sizeof(PredState) == 24, "PredState layout");
 
 // State of the cross-layer ranking of |w| (rsdgc_dynamic_ratios).
 struct DynState {

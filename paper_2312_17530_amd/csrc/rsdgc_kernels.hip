@@ -1,27 +1,29 @@
 // HIP kernels (gfx950, wave64) and the device-facing entry points of the C ABI.
 //
-// Pipeline of one rsdgc_compress call, all layers per launch:
-//   begin      zero histograms, bitmasks, counters, flags; per-layer state; for every large layer
-//              the candidate bound predicted from the thresholds of the two calls before, if
-//              they moved little
-//   first pass every tile of the layers that are ranked on the full score map: v = r + g (Eq. 12),
-//              NSI (Eqs. 6-10), score map, exact 12-bit histogram; in the same launch one tile in
-//              16 .. 64 of the large layers that have no predicted bound (first calls, after a
-//              failure): their score histogram gives a bound with about 2 k_l centres expected
-//              above it (computed by the workgroup that finishes last)
-//   capture    the main pass: v = r + g and NSI for every element of the large layers; centres
-//              whose score reaches the bound are recorded per tile (no score map) and counted in
-//              fine bins above the bound; with a second residual arena v is stored there as it
-//              is formed
-//   find0      first ranking digit of every layer; a large layer whose bound caught fewer than
-//              k_l centres, or overfilled a tile, falls back to the full map (a flag tells the
+// Pipeline of one rsdgc_compress call, all layers per launch.  "Candidate path": a layer whose
+// keep ratio leaves room for it records only the centres whose score reaches a bound and ranks
+// those; the other layers are ranked on a full score map.  The result is the same on both.
+//   begin      zero histograms, bitmasks, counters, flags; per-layer state; for every layer on
+//              the candidate path the bound predicted from the thresholds of the two calls before
+//   first pass every tile of the layers that are always ranked on the full score map: v = r + g
+//              (Eq. 12), NSI (Eqs. 6-10), score map, exact 12-bit histogram; during the first calls
+//              with a workspace, in the same launch, one tile in 16 .. 64 of the candidate-path
+//              layers that have no predicted bound: their score histogram gives a bound with
+//              about 2 k_l centres expected above it (k_hint).  Not launched when it has no tiles.
+//   capture    the main pass: v = r + g and NSI for every element of the candidate-path layers;
+//              centres whose score reaches the bound are recorded per tile (no score map) and
+//              counted in fine bins above the bound; with a second residual arena v is stored
+//              there as it is formed
+//   find0      first ranking digit of every layer; a layer whose bound caught fewer than k_l
+//              centres, or overfilled a tile, falls back to the full map (a flag tells the
 //              fallback kernels there is work)
 //   fallback   score map + histogram of such layers (rare)
-//   select     gather: the keys of each layer's threshold bucket are copied to a list and their
-//              next digit counted; finish: one workgroup per layer resolves the remaining digits
-//              (Algorithm 1's ranking; Eq. 11's k_l)
-//   mark       selected centres set the bits of their p x p window (Section III-C: whole
-//              neighbourhoods are kept)
+//   select     gather: the candidates above each layer's threshold bucket are selected for certain
+//              and mark their windows; the bucket's keys are copied to a list and their next digit
+//              counted; finish: one workgroup per layer resolves the remaining digits
+//              (Algorithm 1's ranking; Eq. 11's k_l) and keeps the threshold for the next calls
+//   mark       the bucket's keys that reach the threshold set the bits of their p x p window
+//              (Section III-C: whole neighbourhoods are kept); full-map layers: every centre
 //   count      kept elements per chunk and per group of chunks (no scan kernel: each consumer
 //              adds up its own prefix from those)
 //   emit       ordered (index, value) pairs and the residual update (Eq. 12): either only the
@@ -33,7 +35,7 @@
 //   work feed        WorkFeed: tiles handed to persistent workgroups through per-XCD counters
 //   nsi              k_nsi<P, PASS, MOM, FEED>: the four NSI passes, with or without Eq. 12's momentum
 //   ranking digits   block_find_digit, publish_threshold
-//   find0 .. finish  k_find0, k_gather, k_finish: the radix select
+//   hint .. finish   k_hint, k_find0, k_gather, k_filter, k_finish: bounds and the radix select
 //   mark             k_mark: p x p windows into the bitmask
 //   count            k_count, chunk_prefix_wave0
 //   emit             k_emit, k_emit_sparse, k_emit_centres
@@ -174,21 +176,26 @@ __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16
             s.span = 0;
             s.predicted = 0;
             if (pred && s.mode == kModeCandidates) {
-                const PredState ps = pred[l];
+                PredState ps = pred[l];
                 // after a failed bound the layer goes back to sampled bounds for a few calls -- where there
                 // are any: past the calls that sample, the alternative would be the full map, and the
                 // widened margin is tried at once
-                if (ps.cooldown > 0) pred[l].cooldown = ps.cooldown - 1;
-                if ((ps.cooldown == 0 || !sampling) &&
-                    ps.tau1 >= (1u << 23) && ps.tau2 >= (1u << 23)) {   // (both in the normal float32 range)
+                const bool paused = ps.cooldown > 0 && sampling;
+                if (ps.cooldown > 0) ps.cooldown -= 1;
+                ps.has_forecast = 0;
+                if (ps.tau1 >= (1u << 23) && ps.tau2 >= (1u << 23)) {   // (both in the normal float32 range)
                     const float l1 = __log2f(__uint_as_float(ps.tau1)), l2 = __log2f(__uint_as_float(ps.tau2));
                     const float d = l1 - l2;
+                    const float dd = fminf(fmaxf(d, -2.f * kTrendMaxLog2), kTrendMaxLog2);
+                    // the forecast is made in every call, used or not: how far the threshold then ends
+                    // below it is what sizes the margin (publish_threshold)
+                    ps.forecast = l1 + (dd > 0.f ? 0.6f * dd : 1.15f * dd);
+                    ps.has_forecast = 1;
                     // (a threshold that jumps: sampled bounds while there are any; later the trend is
                     // taken as far as it is trusted -- a bound that fails costs less than the full map)
-                    if (fabsf(d) <= kTrendMaxLog2 || !sampling) {
+                    if (!paused && (fabsf(d) <= kTrendMaxLog2 || !sampling)) {
                         const float margin = ps.margin > 0.f ? ps.margin : margin_init_log2(L.k);
-                        const float dd = fminf(fmaxf(d, -2.f * kTrendMaxLog2), kTrendMaxLog2);
-                        const float bound = exp2f(l1 + (dd > 0.f ? 0.6f * dd : 1.15f * dd) - margin);
+                        const float bound = exp2f(ps.forecast - margin);
                         const uint32_t key = __float_as_uint(bound);
                         if (key >= (1u << 23) && key < 0x7f800000u) {
                             s.hint_key = key;
@@ -196,6 +203,7 @@ __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16
                         }
                     }
                 }
+                pred[l] = ps;
                 if (!s.predicted && !sampling) {
                     s.mode = kModeFullMap;
                     fallback_work = true;
@@ -865,13 +873,25 @@ __device__ __forceinline__ DigitResult block_find_digit(const uint32_t *h, int n
     return r;
 }
 
-// A large layer's threshold of this call, kept for the next call's candidate bound.
+// A candidate-path layer's threshold of this call, kept for the next calls' bounds.  The margin of
+// those bounds follows what the forecasts miss: it decays slowly towards its initial value, and a
+// threshold that ends s below this call's forecast (used for the bound or not) widens it to at
+// least 1.5 s + 0.01 -- so the layer learns how much its threshold jitters from call to call
+// without a bound having to fail first.
 __device__ __forceinline__ void publish_threshold(PredState *__restrict__ pred, uint32_t l, uint32_t large,
-                                                  unsigned long long T) {
+                                                  uint32_t k, unsigned long long T) {
     if (pred == nullptr || large == 0u) return;
     PredState ps = pred[l];
+    const uint32_t tau = static_cast<uint32_t>(T >> 32);
+    const float init = margin_init_log2(k);
+    float margin = fmaxf(init, (ps.margin > 0.f ? ps.margin : init) * kMarginDecay);
+    if (ps.has_forecast && tau >= (1u << 23)) {
+        const float shortfall = ps.forecast - __log2f(__uint_as_float(tau));
+        if (shortfall > 0.f) margin = fmaxf(margin, kMarginSafety * shortfall + 0.01f);
+    }
+    ps.margin = fminf(margin, kMarginMaxLog2);
     ps.tau2 = ps.tau1;
-    ps.tau1 = static_cast<uint32_t>(T >> 32);
+    ps.tau1 = tau;
     pred[l] = ps;
 }
 
@@ -1038,7 +1058,7 @@ __global__ __launch_bounds__(256) void k_find0(const LayerDev *__restrict__ laye
             ns.T = static_cast<unsigned long long>(ns.lo) << 32;
             if (r.count == ns.k_rem) {     // whole bucket taken: the threshold is its lower edge
                 ns.done = 1;
-                publish_threshold(pred, l, large, ns.T);
+                publish_threshold(pred, l, large, layers[l].k, ns.T);
             }
         }
         state[l] = ns;
@@ -1564,7 +1584,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
                 ns.k_rem = k_rem;
                 ns.done = 1;
                 state[l] = ns;
-                publish_threshold(pred, l, L.large, ns.T);
+                publish_threshold(pred, l, L.large, L.k, ns.T);
             }
             return;
         }
@@ -1657,7 +1677,7 @@ __global__ __launch_bounds__(kFinishThreads) void k_finish(const LayerDev *__res
         ns.lo = lo;
         ns.span = span;
         state[l] = ns;
-        publish_threshold(pred, l, L.large, T);
+        publish_threshold(pred, l, L.large, L.k, T);
     }
 }
 
