@@ -26,6 +26,8 @@ constexpr int kListDiv = 32;         // ... or 1/32 of the layer, whichever is l
 constexpr int kCountChunks = 16;     // chunks per workgroup of the count pass
 constexpr int kChunkGroup = 64;      // chunks per group in the two-level chunk prefix
 constexpr int kListShards = 16;      // a layer's threshold-bucket list is filled through this many counters
+constexpr int kGroupCntStride = 32;   // words between two chunk-group counters where many workgroups add to one: a cache line each
+constexpr uint32_t kInlineCountChunks = 4096;   // plans up to this many chunks (33 M elements) count their kept elements where the bits are set
 constexpr int kListCntStride = 32;   // uint32 between two of them (one 128-byte line each)
 constexpr int kBigMapLayer = 1 << 20; // elements from which a full-map layer's bucket list goes through k_filter
 // Candidate bound predicted from the thresholds of the two calls before, on a log2 scale: used
@@ -87,8 +89,10 @@ struct LayerDev {
     uint32_t list_cap;      // capacity of the threshold-bucket list
     uint32_t list_shards;   // shards the list is split into (each list_cap / list_shards entries, own counter)
     uint32_t slot_cap;      // entries per tile slot (kSlotCapMax)
+    uint32_t cgroup_begin;  // first chunk group (kChunkGroup chunks) of the layer, numbered over all layers
+    uint32_t pad_;
 };
-static_assert(sizeof(LayerDev) == 120, "LayerDev layout");
+static_assert(sizeof(LayerDev) == 128, "LayerDev layout");
 
 // Per-layer selection state (40 bytes), lives in the workspace, rewritten by every call.
 struct SelState {
@@ -177,8 +181,10 @@ struct ChunkInfo {
     uint32_t group_first_chunk;  // first chunk of that group
     uint32_t layer_first_group;  // first group of the layer
     uint32_t last;               // 1: the layer's last chunk (it reports the layer's total)
+    uint32_t gstride;            // words between two chunk-group counters: kGroupCntStride in a plan that counts
+    uint32_t pad_;               // its kept elements where their bits are set (many adds per counter), else 1
 };
-static_assert(sizeof(ChunkInfo) == 48, "ChunkInfo layout");
+static_assert(sizeof(ChunkInfo) == 56, "ChunkInfo layout");
 
 // Byte offsets of the workspace sections (all multiples of 256).
 struct WsLayout {
@@ -207,8 +213,8 @@ struct WsLayout {
     size_t hist1 = 0;        // uint32[n_layers][kLevel1Bins]  second ranking digit
     size_t chunk_cnt = 0;    // uint32[n_chunks]  kept elements per chunk
     size_t chunk_ccnt = 0;   // uint32[n_chunks]  selected centres per chunk
-    size_t group_cnt = 0;    // uint32[n_chunk_groups]  kept elements per chunk group
-    size_t group_ccnt = 0;   // uint32[n_chunk_groups]  selected centres per chunk group
+    size_t group_cnt = 0;    // uint32[n_chunk_groups * kGroupCntStride]  kept elements per chunk group, each counter on its own cache line
+    size_t group_ccnt = 0;   // the same for the selected centres
     size_t list_cnt = 0;     // uint32[n_layers][kListShards][kListCntStride]  keys gathered per list shard
     size_t list2_cnt = 0;    // uint32[n_layers]  of those, keys that k_filter picked for k_finish
     size_t feed = 0;         // uint32[16][8][32]  work-feed counters of the NSI launches

@@ -895,13 +895,73 @@ __device__ __forceinline__ void publish_threshold(PredState *__restrict__ pred, 
     pred[l] = ps;
 }
 
+// Small plans: whoever sets mask bits also counts them -- the kept elements per 8192-element chunk
+// and per group of kChunkGroup chunks, which the emit turns into output positions -- and the
+// counting pass over the finished mask (k_count, a launch of its own) is not needed.  A call on a
+// small plan is a chain of launches of a few microseconds each; on a large one the extra atomics
+// cost more than the launch (measured: VGG-19 +12 us, ResNet-18 -7 us), so large plans keep
+// k_count and pass no counters here.  A mask word lies in one chunk: chunks are 256 words long and
+// a layer starts at a word boundary.
+struct CountCtx {
+    uint32_t *chunk_cnt, *group_cnt;   // cleared at the start of the call; null: the plan counts with k_count instead
+    size_t word0;                      // the layer's first mask word
+    uint32_t chunk_begin, cgroup_begin;
+};
+__device__ __forceinline__ CountCtx count_ctx(const LayerDev &L, uint32_t *chunk_cnt, uint32_t *group_cnt) {
+    return CountCtx{chunk_cnt, group_cnt, static_cast<size_t>(L.elem_off) >> 5, L.chunk_begin, L.cgroup_begin};
+}
+// n more kept elements in the layer's chunk number cl / in its chunk group number gl.  Many
+// workgroups add to one group counter, so each has a cache line of its own (atomics on one line
+// are served one after the other, 11 ns each).
+__device__ __forceinline__ void count_add_chunk_only(const CountCtx &c, uint32_t cl, uint32_t n) {
+    atomicAdd(&c.chunk_cnt[c.chunk_begin + cl], n);
+}
+__device__ __forceinline__ void count_add_group(const CountCtx &c, uint32_t gl, uint32_t n) {
+    atomicAdd(&c.group_cnt[static_cast<size_t>(c.cgroup_begin + gl) * kGroupCntStride], n);
+}
+__device__ __forceinline__ void count_add_chunk(const CountCtx &c, uint32_t cl, uint32_t n) {
+    count_add_chunk_only(c, cl, n);
+    count_add_group(c, cl / kChunkGroup, n);
+}
+// The first wave of a workgroup hands over what the workgroup counted in LDS for the 64 chunks from
+// cl0 on (lane = chunk): one add per chunk that got something, and one per chunk group -- 64
+// consecutive chunks lie in at most two.
+__device__ __forceinline__ void count_flush_wave0(const CountCtx &c, uint32_t cl0, uint32_t n) {
+    const uint32_t lane = threadIdx.x & 63u;
+    if (n) count_add_chunk_only(c, cl0 + lane, n);
+    const uint32_t g0 = cl0 / kChunkGroup;
+    const bool first = (cl0 + lane) / kChunkGroup == g0;
+    uint32_t a = first ? n : 0u, b = first ? 0u : n;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        a += __shfl_xor(a, d, 64);
+        b += __shfl_xor(b, d, 64);
+    }
+    if (lane == 0) {
+        if (a) count_add_group(c, g0, a);
+        if (b) count_add_group(c, g0 + 1, b);
+    }
+}
+// ORs bits into mask word w and (COUNT) counts those that were not set before.
+template <bool COUNT>
+__device__ __forceinline__ void or_counted(const CountCtx &c, uint32_t *__restrict__ mask, size_t w, uint32_t bits) {
+    if (!COUNT) {
+        atomicOr(&mask[w], bits);
+        return;
+    }
+    const uint32_t old = atomicOr(&mask[w], bits);
+    const uint32_t n = __popc(bits & ~old);
+    if (n) count_add_chunk(c, static_cast<uint32_t>((w - c.word0) >> 8), n);
+}
+
 // Set nbits (<= RSDGC_MAX_P) consecutive mask bits starting at bit position pos.
-__device__ __forceinline__ void set_bits(uint32_t *__restrict__ mask, size_t pos, uint32_t nbits) {
+template <bool COUNT>
+__device__ __forceinline__ void set_bits(const CountCtx &c, uint32_t *__restrict__ mask, size_t pos, uint32_t nbits) {
     const size_t w = pos >> 5;
     const uint32_t b = static_cast<uint32_t>(pos & 31);
     const uint32_t bits = (1u << nbits) - 1u;
-    atomicOr(&mask[w], bits << b);
-    if (b + nbits > 32) atomicOr(&mask[w + 1], bits >> (32 - b));
+    or_counted<COUNT>(c, mask, w, bits << b);
+    if (b + nbits > 32) or_counted<COUNT>(c, mask, w + 1, bits >> (32 - b));
 }
 
 // A selected centre (flat index i inside its layer) ORs the bits of its p x p window into the
@@ -912,13 +972,14 @@ struct WindowGeom {
     size_t elem_off;
     int R, C, h;
 };
-__device__ __forceinline__ void mark_window(const WindowGeom &g, uint32_t i, uint32_t *__restrict__ mask,
-                                            uint32_t *__restrict__ cmask) {
+template <bool COUNT>
+__device__ __forceinline__ void mark_window(const WindowGeom &g, const CountCtx &c, uint32_t i,
+                                            uint32_t *__restrict__ mask, uint32_t *__restrict__ cmask) {
     const int xc = static_cast<int>(i / static_cast<uint32_t>(g.C));
     const int yc = static_cast<int>(i - static_cast<uint32_t>(xc) * static_cast<uint32_t>(g.C));
     const int ylo = max(0, yc - g.h), yhi = min(g.C - 1, yc + g.h);
     for (int x = max(0, xc - g.h); x <= min(g.R - 1, xc + g.h); ++x)
-        set_bits(mask, g.elem_off + static_cast<size_t>(x) * g.C + ylo, static_cast<uint32_t>(yhi - ylo + 1));
+        set_bits<COUNT>(c, mask, g.elem_off + static_cast<size_t>(x) * g.C + ylo, static_cast<uint32_t>(yhi - ylo + 1));
     if (cmask) {
         const size_t pos = g.elem_off + i;
         atomicOr(&cmask[pos >> 5], 1u << (pos & 31));
@@ -1090,13 +1151,14 @@ constexpr int kStage = 2048;            // staged keys per workgroup (a round ad
 constexpr int kSlotsPerWave = kSlotGroup / 4;   // tile slots of a group that one wave of a gather workgroup takes
 
 constexpr int kTileMaskWords = kTileRows * kTileCols / 32;    // mask words of one tile (rows of 8 words)
+constexpr int kGatherCountSlots = 64;                          // chunks a group of tiles counts for in LDS (the rest: directly)
 
 struct GatherShared {
     union {
         unsigned long long ent[kStage];               // score-map roles: staged keys
         struct {                                      // slot role:
             uint32_t bits[kSlotGroup * kTileMaskWords];   // mask words of the group of tiles being written
-            uint32_t spre[65];                            // entries before each of the (at most 54) slots around that group; [64]: all
+            uint32_t ccnt[kGatherCountSlots];             // bits set, per chunk from the group's first one on
         };
     };
     uint32_t hist[kLevel1Bins];         // second-digit counts
@@ -1125,6 +1187,7 @@ struct GatherArgs {
     uint32_t *hist1;                      // [n_layers][kLevel1Bins]
     const uint32_t *flags;
     uint32_t *mask, *cmask;               // kept-element bitmask; selected-centre bitmask (nullable)
+    uint32_t *chunk_cnt, *group_cnt;      // kept elements per chunk / chunk group, counted as the bits are set
 };
 
 // The list of the layer the workgroup is working on.
@@ -1167,6 +1230,7 @@ __device__ __forceinline__ void gather_stage_key(GatherShared &sh, bool hit, uns
     }
 }
 
+template <bool COUNT>
 __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const GatherLists gl) {
     __shared__ GatherShared sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -1303,6 +1367,7 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
                 a.slot_ent + L.slot_off + static_cast<size_t>(ge.slot0 - L.tile_begin_all) * slot_cap;
             const WindowGeom geom = {static_cast<size_t>(L.elem_off), static_cast<int>(L.R), static_cast<int>(L.C),
                                      (static_cast<int>(L.p) - 1) / 2};
+            const CountCtx cctx = count_ctx(L, a.chunk_cnt, a.group_cnt);
             if ((L.C & 31u) == 0u) {
                 // Rows of whole mask words: every mask word of the layer lies in exactly one tile.  The
                 // workgroup builds the words of its group of tiles in LDS from the group's own candidates
@@ -1310,11 +1375,19 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
                 // windows of other groups' candidates can reach (the h rows along a tile's upper and lower
                 // edge, the first and last word of the group's run of tiles): those, and the bits that the
                 // group's windows set in other groups' tiles, are ORed into the (cleared) mask.
+                // The bits are counted as they are set (an OR tells which were new), per chunk, in LDS
+                // first: a group of tiles lies in a few chunks.
                 const int h = geom.h, C = geom.C, R = geom.R;
                 const int tiles_x = static_cast<int>(L.tiles_x);
                 const int g0 = static_cast<int>(ge.slot0 - L.tile_begin_all), gn = static_cast<int>(ge.ntile);
+                // first chunk that the group's windows can reach: that of the element h rows above and h
+                // columns left of the first tile's corner
+                const uint32_t cl0 = static_cast<uint32_t>(
+                    (static_cast<size_t>(max(0, (g0 / tiles_x) * kTileRows - h)) * C +
+                     static_cast<size_t>(max(0, (g0 % tiles_x) * kTileCols - h))) / kChunk);
                 __syncthreads();                                 // (the previous group's words are written)
                 for (int i = tid; i < kSlotGroup * kTileMaskWords; i += 256) sh.bits[i] = 0u;
+                if (COUNT && tid < kGatherCountSlots) sh.ccnt[tid] = 0u;
                 __syncthreads();
                 {
                     // sixteen lanes per tile slot; a round covers 16 entries of each
@@ -1340,10 +1413,29 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
                                     const uint32_t len = static_cast<uint32_t>(yb - ya + 1);
                                     const uint32_t run = (1u << len) - 1u;
                                     for (int x = xa; x <= xb; ++x) {
-                                        uint32_t *row = mine ? sh.bits + sidx * kTileMaskWords + (x - r0) * (kTileCols / 32)
-                                                             : a.mask + ((geom.elem_off + static_cast<size_t>(x) * C + c0) >> 5);
-                                        atomicOr(&row[w0], run << b0);
-                                        if (b0 + len > 32u) atomicOr(&row[w0 + 1], run >> (32u - b0));
+                                        if (mine) {
+                                            uint32_t *row = sh.bits + sidx * kTileMaskWords + (x - r0) * (kTileCols / 32);
+                                            atomicOr(&row[w0], run << b0);
+                                            if (b0 + len > 32u) atomicOr(&row[w0 + 1], run >> (32u - b0));
+                                        } else if (!COUNT) { // another group's tile: straight into the mask
+                                            uint32_t *row = a.mask + ((geom.elem_off + static_cast<size_t>(x) * C + c0) >> 5);
+                                            atomicOr(&row[w0], run << b0);
+                                            if (b0 + len > 32u) atomicOr(&row[w0 + 1], run >> (32u - b0));
+                                        } else {             // ... and the new bits counted
+                                            const size_t wrow = (static_cast<size_t>(x) * C + c0) >> 5;   // first word of the tile row, inside the layer
+                                            uint32_t *row = a.mask + (geom.elem_off >> 5) + wrow;
+#pragma unroll
+                                            for (uint32_t part = 0; part < 2u; ++part) {
+                                                const uint32_t bits = part == 0u ? run << b0 : (b0 + len > 32u ? run >> (32u - b0) : 0u);
+                                                if (bits == 0u) continue;
+                                                const uint32_t fresh = __popc(bits & ~atomicOr(&row[w0 + part], bits));
+                                                if (fresh) {
+                                                    const uint32_t slot = static_cast<uint32_t>((wrow + w0 + part) >> 8) - cl0;
+                                                    if (slot < static_cast<uint32_t>(kGatherCountSlots)) atomicAdd(&sh.ccnt[slot], fresh);
+                                                    else count_add_chunk(cctx, cl0 + slot, fresh);
+                                                }
+                                            }
+                                        }
                                     }
                                 }
                             if (a.cmask) {
@@ -1367,13 +1459,28 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
                     const int x = tr * kTileRows + rr, y = tc * kTileCols + 32 * ww;
                     if (x < R && y < C) {
                         const uint32_t word = sh.bits[sidx * kTileMaskWords + rr * 8 + ww];
-                        uint32_t *dst = a.mask + ((geom.elem_off + static_cast<size_t>(x) * C + y) >> 5);
+                        const size_t e0 = static_cast<size_t>(x) * C + y;
+                        uint32_t *dst = a.mask + ((geom.elem_off + e0) >> 5);
                         const bool shared = (rr < h && tr > 0) || (rr >= kTileRows - h && x + h >= (tr + 1) * kTileRows && (tr + 1) * kTileRows < R) ||
                                             (ww == 0 && sidx == 0 && tc > 0) ||
                                             (ww == 7 && sidx == gn - 1 && tc < tiles_x - 1);
+                        uint32_t fresh = word;
                         if (!shared) *dst = word;
-                        else if (word != 0u) atomicOr(dst, word);
+                        else if (word != 0u) {
+                            if (COUNT) fresh = word & ~atomicOr(dst, word);
+                            else atomicOr(dst, word);
+                        }
+                        if (COUNT && fresh) {
+                            const uint32_t slot = static_cast<uint32_t>(e0 / kChunk) - cl0;
+                            if (slot < static_cast<uint32_t>(kGatherCountSlots)) atomicAdd(&sh.ccnt[slot], __popc(fresh));
+                            else count_add_chunk(cctx, cl0 + slot, __popc(fresh));
+                        }
                     }
+                }
+                static_assert(kGatherCountSlots == 64, "one lane of the first wave per counted chunk");
+                if (COUNT) {
+                    __syncthreads();
+                    if (tid < 64) count_flush_wave0(cctx, cl0, sh.ccnt[tid]);
                 }
             } else {
             // each wave takes 4 of the group's tile slots; a round covers 64 entries of each
@@ -1395,7 +1502,7 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
                 for (int c = 0; c < kSlotsPerWave; ++c) {
                     const uint32_t score = static_cast<uint32_t>(K[c] >> 32);
                     const bool valid = j < cnt[c];
-                    if (valid && score >= above) mark_window(geom, ~static_cast<uint32_t>(K[c]), a.mask, a.cmask);
+                    if (valid && score >= above) mark_window<COUNT>(geom, cctx, ~static_cast<uint32_t>(K[c]), a.mask, a.cmask);
                     const bool hit = valid && score < above && score - lo < width;    // (never when the layer is done)
                     const unsigned long long m = __ballot(hit);
                     if (m != 0ull) {       // wave-uniform
@@ -1696,7 +1803,6 @@ __device__ __forceinline__ void or_bits_shared(uint32_t *__restrict__ mask, size
     if (p1) atomicOr(&mask[w + 1], p1);
     if (p2) atomicOr(&mask[w + 2], p2);
 }
-
 // Full-map layers: workgroups stride over the 16 x 256 tiles (the NSI tiling).  Every centre
 // of a tile and of a halo of h rows / columns is compared with the layer's threshold; the
 // per-row results become 64-bit ballot words in LDS, the p x p box dilation (Section III-C:
@@ -1711,6 +1817,8 @@ __device__ __forceinline__ void or_bits_shared(uint32_t *__restrict__ mask, size
 // next n_list_wgs workgroups stride over the plan's list of tiles of the layers that are
 // always ranked on the full map; the others run only when some large layer fell back to it,
 // walk all tiles and take those of such layers.
+constexpr int kMarkCountSlots = 64;   // chunks a tile counts for in LDS (more only for rows beyond 32 K elements: directly)
+
 struct MarkArgs {
     const LayerDev *layers;
     const SelState *state;
@@ -1726,13 +1834,16 @@ struct MarkArgs {
     const uint32_t *flags;
     const uint32_t *keys;            // score map
     uint32_t *mask, *cmask;
+    uint32_t *chunk_cnt, *group_cnt; // kept elements per chunk / chunk group, counted as the bits are set
 };
 
+template <bool COUNT>
 __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
     constexpr int MAXH = (RSDGC_MAX_P - 1) / 2;
     constexpr int NSEG = kTileCols / 64;       // 64-column segments of a tile row
     static_assert(kTileRows * NSEG == 64, "one lane of wave 0 per row segment");
     __shared__ unsigned long long bits[kTileRows + 2 * MAXH][NSEG + 2];   // [row][left, segments, right]
+    __shared__ uint32_t ccnt[kMarkCountSlots];      // bits set by the tile, per chunk from the tile's first one on
     const LayerDev *__restrict__ layers = m.layers;
     const DirEntry *__restrict__ dir = m.dir;
     const SampleEntry *__restrict__ map_tiles = m.map_tiles;
@@ -1754,12 +1865,13 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
                                  (static_cast<int>(Lc.p) - 1) / 2};
         const uint32_t shards = Lc.list_shards, cap = Lc.list_cap / shards;
         if (shard >= shards) return;
+        const CountCtx cctx = count_ctx(Lc, m.chunk_cnt, m.group_cnt);
         if (__ballot(c > cap) == 0ull) {       // every shard fits: this workgroup takes its shard
             const uint32_t n = __shfl(c, static_cast<int>(shard), 64);
             const unsigned long long *__restrict__ part = m.list_ent + Lc.list_off + static_cast<size_t>(shard) * cap;
             for (uint32_t i = tid; i < n; i += 256) {
                 const unsigned long long K = part[i];
-                if (K >= Tc) mark_window(geom, ~static_cast<uint32_t>(K), mask, cmask);
+                if (K >= Tc) mark_window<COUNT>(geom, cctx, ~static_cast<uint32_t>(K), mask, cmask);
             }
         } else {                               // the list overflowed: the bucket's keys are still in the tile slots
             const unsigned long long bucket_end = (static_cast<unsigned long long>(st.lo) + (1ull << st.span)) << 32;
@@ -1768,7 +1880,7 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
                 const unsigned long long *__restrict__ ent = m.slot_ent + Lc.slot_off + static_cast<size_t>(t) * Lc.slot_cap;
                 for (uint32_t i = tid; i < n; i += 256) {
                     const unsigned long long K = ent[i];
-                    if (K >= Tc && K < bucket_end) mark_window(geom, ~static_cast<uint32_t>(K), mask, cmask);
+                    if (K >= Tc && K < bucket_end) mark_window<COUNT>(geom, cctx, ~static_cast<uint32_t>(K), mask, cmask);
                 }
             }
         }
@@ -1781,6 +1893,7 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
     const uint32_t n_items = listed ? m.n_map_tiles : m.n_tiles;
     if (first >= n_items) return;
     if (!listed && m.flags[0] == 0u) return;
+    if (COUNT && tid < kMarkCountSlots) ccnt[tid] = 0u;       // (the tile loop's barriers come before the first use)
     uint32_t e = listed ? 0u : dir_lookup(dir, n_layers, first);
     uint32_t cur_l = 0xffffffffu;
     bool active = false;
@@ -1818,6 +1931,8 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
         const int R = static_cast<int>(L.R), C = static_cast<int>(L.C);
         const int x0 = trow * kTileRows, y0 = tcol * kTileCols;
         const uint32_t *__restrict__ src = keys + L.elem_off;
+        const CountCtx cctx = count_ctx(L, m.chunk_cnt, m.group_cnt);
+        const uint32_t cl0 = static_cast<uint32_t>((static_cast<size_t>(x0) * C + y0) / kChunk);   // the tile's first chunk
 
         // wave w takes segment w of every row: all its keys are requested before any is compared
         static_assert(NSEG == 4, "one wave per 64-column segment");
@@ -1885,18 +2000,51 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
                     cmask[w] = static_cast<uint32_t>(own);
                     if (ncols > 32) cmask[w + 1] = static_cast<uint32_t>(own >> 32);
                 }
-            } else {
+                // its bits, per chunk (the two words may lie in different chunks)
+#pragma unroll
+                for (int part = 0; part < 2; ++part) {
+                    const uint32_t n = COUNT ? __popc(static_cast<uint32_t>(acc >> (32 * part))) : 0u;
+                    if (n) {
+                        const uint32_t slot = static_cast<uint32_t>((w + part - cctx.word0) >> 8) - cl0;
+                        if (slot < static_cast<uint32_t>(kMarkCountSlots)) atomicAdd(&ccnt[slot], n);
+                        else count_add_chunk(cctx, cl0 + slot, n);
+                    }
+                }
+            } else if (!COUNT) {
                 or_bits_shared(mask, pos, acc);
+                if (cmask) or_bits_shared(cmask, pos, own);
+            } else {                                 // shared words: an OR tells which bits were new
+                const size_t w = pos >> 5;
+                const uint32_t b = static_cast<uint32_t>(pos & 31);
+                const uint32_t part[3] = {static_cast<uint32_t>(acc << b),
+                                          static_cast<uint32_t>(b ? (acc >> (32 - b)) : (acc >> 32)),
+                                          b ? static_cast<uint32_t>(acc >> (64 - b)) : 0u};
+#pragma unroll
+                for (int j = 0; j < 3; ++j) {
+                    if (part[j] == 0u) continue;
+                    const uint32_t n = __popc(part[j] & ~atomicOr(&mask[w + j], part[j]));
+                    if (n) {
+                        const uint32_t slot = static_cast<uint32_t>((w + j - cctx.word0) >> 8) - cl0;
+                        if (slot < static_cast<uint32_t>(kMarkCountSlots)) atomicAdd(&ccnt[slot], n);
+                        else count_add_chunk(cctx, cl0 + slot, n);
+                    }
+                }
                 if (cmask) or_bits_shared(cmask, pos, own);
             }
         }
         __syncthreads();                        // the ballot words are reused by the next tile
+        static_assert(kMarkCountSlots == 64, "one lane of the first wave per counted chunk");
+        if (COUNT && tid < 64) {
+            count_flush_wave0(cctx, cl0, ccnt[tid]);
+            ccnt[tid] = 0u;
+        }
     }
 }
 
 // ---------------------------------------------------------------- count --
-// Kept elements (and selected centres) per chunk and per group of kChunkGroup chunks: one
-// workgroup per kCountChunks = 16 chunks; 16 adjacent threads read the 256 mask words of one
+// Kept elements (and selected centres) per chunk and per group of kChunkGroup chunks, from the
+// finished masks -- for plans of many chunks; a small plan's kept elements are counted where their
+// bits are set (CountCtx) and `mask` is null here.  One workgroup per kCountChunks = 16 chunks; 16 adjacent threads read the 256 mask words of one
 // chunk (16 consecutive words each, as independent 8-byte loads) and add their popcounts with
 // four shuffles.  A workgroup adds its total to its chunk group's with one atomic -- four per
 // group (one atomic per chunk put 17 k of them on 9 cache lines and cost 18 us).
@@ -1908,7 +2056,7 @@ __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__res
                                                          uint32_t *__restrict__ chunk_cnt,
                                                          uint32_t *__restrict__ chunk_ccnt,
                                                          uint32_t *__restrict__ group_cnt,
-                                                         uint32_t *__restrict__ group_ccnt) {
+                                                         uint32_t *__restrict__ group_ccnt, uint32_t gstride) {
     constexpr int kPerThread = kChunk / 32 / 16;    // 16 words
     static_assert(kCountChunks <= 64, "one lane of the first wave per chunk");
     __shared__ uint32_t lcnt[2][kCountChunks];
@@ -1923,10 +2071,10 @@ __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__res
         wa[j] = make_uint2(0u, 0u);
         wb[j] = make_uint2(0u, 0u);
         if (i + 1 < gr.n_words) {
-            wa[j] = *reinterpret_cast<const uint2 *>(mask + gr.word0 + i);
+            if (mask) wa[j] = *reinterpret_cast<const uint2 *>(mask + gr.word0 + i);
             if (cmask) wb[j] = *reinterpret_cast<const uint2 *>(cmask + gr.word0 + i);
         } else if (i < gr.n_words) {
-            wa[j].x = mask[gr.word0 + i];
+            if (mask) wa[j].x = mask[gr.word0 + i];
             if (cmask) wb[j].x = cmask[gr.word0 + i];
         }
     }
@@ -1950,7 +2098,7 @@ __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__res
         a = tid < kCountChunks ? lcnt[0][tid] : 0u;
         b = tid < kCountChunks ? lcnt[1][tid] : 0u;
         if (static_cast<uint32_t>(tid) < gr.n_chunks) {
-            chunk_cnt[gr.first_chunk + tid] = a;
+            if (mask) chunk_cnt[gr.first_chunk + tid] = a;
             if (cmask) chunk_ccnt[gr.first_chunk + tid] = b;
         }
 #pragma unroll
@@ -1959,8 +2107,8 @@ __global__ __launch_bounds__(kCountThreads) void k_count(const CountGroup *__res
             b += __shfl_xor(b, d, 64);
         }
         if (tid == 0) {                    // (the group totals are cleared at the start of the call)
-            if (a) atomicAdd(&group_cnt[gr.group], a);
-            if (cmask && b) atomicAdd(&group_ccnt[gr.group], b);
+            if (mask && a) atomicAdd(&group_cnt[static_cast<size_t>(gr.group) * gstride], a);
+            if (cmask && b) atomicAdd(&group_ccnt[static_cast<size_t>(gr.group) * gstride], b);
         }
     }
 }
@@ -1979,10 +2127,10 @@ __device__ __forceinline__ uint32_t chunk_prefix_by_wave(const ChunkInfo &ci, ui
     const uint32_t cc = ci.group_first_chunk + lane;     // at most kChunkGroup - 1 = 63 of them
     uint32_t v[5];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = g0 + 64 * j < g1 ? group_cnt[g0 + 64 * j] : 0u;
+    for (int j = 0; j < 4; ++j) v[j] = g0 + 64 * j < g1 ? group_cnt[static_cast<size_t>(g0 + 64 * j) * ci.gstride] : 0u;
     v[4] = cc < c ? chunk_cnt[cc] : 0u;
     uint32_t own = v[0] + v[1] + v[2] + v[3] + v[4];
-    for (uint32_t g = g0 + 256; g < g1; g += 64) own += group_cnt[g];     // layers beyond 2^27 elements
+    for (uint32_t g = g0 + 256; g < g1; g += 64) own += group_cnt[static_cast<size_t>(g) * ci.gstride];     // layers beyond 2^27 elements
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) own += __shfl_xor(own, d, 64);
     return own;                    // the same in every lane of the wave
@@ -3041,6 +3189,7 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
     uint32_t *mask = reinterpret_cast<uint32_t *>(ws + w.mask);
     uint32_t *cmask = want_centres ? reinterpret_cast<uint32_t *>(ws + w.cmask) : nullptr;
     float *nsi = reinterpret_cast<float *>(ws + w.nsi);
+    const bool inline_count = n_chunks <= kInlineCountChunks;    // small plan: count where the bits are set, no k_count
     const GroupEntry *cand_groups = reinterpret_cast<const GroupEntry *>(ws + w.cand_groups);
     const uint32_t n_cand_groups = static_cast<uint32_t>(plan->cand_groups.size());
     const uint32_t *slot_cnt = reinterpret_cast<const uint32_t *>(ws + w.slot_cnt);
@@ -3061,6 +3210,8 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         a.flags = flags;
         a.mask = mask;
         a.cmask = cmask;
+        a.chunk_cnt = inline_count ? chunk_cnt : nullptr;
+        a.group_cnt = inline_count ? reinterpret_cast<uint32_t *>(ws + w.group_cnt) : nullptr;
         GatherLists gl;
         gl.chunk_dir = chunk_dir;
         gl.map_chunks = reinterpret_cast<const ChunkEntry *>(ws + w.map_chunks);
@@ -3073,7 +3224,11 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         gl.n_slot_wgs = std::min<uint32_t>(n_cand_groups, kNumCUs * 8u);
         const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(n_chunks, kNumCUs * 2u) : 0u;
         if (gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs > 0)
-            hipLaunchKernelGGL(k_gather, dim3(gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs), dim3(256), 0, stream, a, gl);
+        {
+            const dim3 grid(gl.n_map_wgs + gl.n_slot_wgs + n_fb_wgs);
+            if (inline_count) hipLaunchKernelGGL(k_gather<true>, grid, dim3(256), 0, stream, a, gl);
+            else hipLaunchKernelGGL(k_gather<false>, grid, dim3(256), 0, stream, a, gl);
+        }
         uint32_t *list2_cnt = reinterpret_cast<uint32_t *>(ws + w.list2_cnt);
         unsigned long long *list2_ent = reinterpret_cast<unsigned long long *>(ws + w.list2_ent);
         if (plan->big_map_layers)          // long threshold-bucket lists: many workgroups pick the keys k_finish needs
@@ -3099,6 +3254,8 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         m.keys = reinterpret_cast<const uint32_t *>(nsi);
         m.mask = mask;
         m.cmask = cmask;
+        m.chunk_cnt = inline_count ? chunk_cnt : nullptr;
+        m.group_cnt = inline_count ? reinterpret_cast<uint32_t *>(ws + w.group_cnt) : nullptr;
         const uint32_t n_fb_wgs = plan->any_large ? std::min<uint32_t>(plan->n_tiles_all, kNumCUs * 4u) : 0u;
         m.n_bucket_wgs = plan->any_large ? static_cast<uint32_t>(L) * kListShards : 0u;
         m.list_cnt = reinterpret_cast<const uint32_t *>(ws + w.list_cnt);
@@ -3106,12 +3263,20 @@ static int select_mark_count(rsdgc_plan_s *plan, char *ws, bool want_centres, St
         m.slot_cnt = slot_cnt;
         m.slot_ent = slot_ent;
         const uint32_t n_wgs = m.n_bucket_wgs + m.n_list_wgs + n_fb_wgs;
-        if (n_wgs > 0) hipLaunchKernelGGL(k_mark, dim3(n_wgs), dim3(256), 0, stream, m);
+        if (n_wgs > 0) {
+            if (inline_count) hipLaunchKernelGGL(k_mark<true>, dim3(n_wgs), dim3(256), 0, stream, m);
+            else hipLaunchKernelGGL(k_mark<false>, dim3(n_wgs), dim3(256), 0, stream, m);
+        }
     }
     marks.close(5);
-    hipLaunchKernelGGL(k_count, dim3(plan->n_count_groups), dim3(kCountThreads), 0, stream,
-                       reinterpret_cast<const CountGroup *>(ws + w.count_groups), mask, cmask, chunk_cnt, chunk_ccnt,
-                       reinterpret_cast<uint32_t *>(ws + w.group_cnt), reinterpret_cast<uint32_t *>(ws + w.group_ccnt));
+    // a small plan's kept elements were counted by the kernels that set their bits; the selected
+    // centres, when their lists are wanted, are counted from the centre mask either way
+    if (!inline_count || cmask)
+        hipLaunchKernelGGL(k_count, dim3(plan->n_count_groups), dim3(kCountThreads), 0, stream,
+                           reinterpret_cast<const CountGroup *>(ws + w.count_groups), inline_count ? nullptr : mask,
+                           cmask, chunk_cnt, chunk_ccnt, reinterpret_cast<uint32_t *>(ws + w.group_cnt),
+                           reinterpret_cast<uint32_t *>(ws + w.group_ccnt),
+                           inline_count ? static_cast<uint32_t>(kGroupCntStride) : 1u);
     marks.close(6);
     return RSDGC_OK;
 }

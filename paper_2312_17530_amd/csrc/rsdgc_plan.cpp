@@ -39,7 +39,7 @@ int build_tables(rsdgc_plan_s *plan) {
     plan->big_map_layers = false;
 
     int64_t elem_off = 0, out_off = 0, centre_off = 0;
-    uint32_t chunk_begin = 0, tile_begin_all = 0, group_begin = 0;
+    uint32_t chunk_begin = 0, tile_begin_all = 0, group_begin = 0, cgroup_begin = 0;
     uint64_t list_off = 0;
     for (int l = 0; l < L; ++l) {
         LayerDev &d = plan->layers[l];
@@ -68,6 +68,8 @@ int build_tables(rsdgc_plan_s *plan) {
         d.cap = static_cast<uint32_t>(cap);
         d.tile_begin_all = tile_begin_all;
         d.group_begin = group_begin;
+        d.cgroup_begin = cgroup_begin;
+        d.pad_ = 0;
         d.n_groups = (d.n_tiles + kSlotGroup - 1) / kSlotGroup;
         d.list_off = list_off;
         // a block grid is ranked on its full score map whatever its size: its threshold bucket may hold
@@ -109,6 +111,7 @@ int build_tables(rsdgc_plan_s *plan) {
         chunk_begin += d.n_chunks;
         tile_begin_all += d.n_tiles;
         group_begin += d.n_groups;
+        cgroup_begin += (d.n_chunks + kChunkGroup - 1) / kChunkGroup;
         elem_off += (G + kLayerAlign - 1) / kLayerAlign * kLayerAlign;
         out_off += cap;
         centre_off += k;
@@ -220,8 +223,8 @@ int build_tables(rsdgc_plan_s *plan) {
     w.hist1 = off;        off = align_up(off + sizeof(uint32_t) * kLevel1Bins * L, A);
     w.chunk_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
     w.chunk_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunks, A);
-    w.group_cnt = off;    off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
-    w.group_ccnt = off;   off = align_up(off + sizeof(uint32_t) * plan->n_chunk_groups, A);
+    w.group_cnt = off;    off = align_up(off + sizeof(uint32_t) * kGroupCntStride * plan->n_chunk_groups, A);
+    w.group_ccnt = off;   off = align_up(off + sizeof(uint32_t) * kGroupCntStride * plan->n_chunk_groups, A);
     w.list_cnt = off;     off = align_up(off + sizeof(uint32_t) * kListShards * kListCntStride * size_t(L), A);
     w.list2_cnt = off;    off = align_up(off + sizeof(uint32_t) * L, A);
     w.feed = off;         off = align_up(off + sizeof(uint32_t) * 16 * 8 * 32, A);
@@ -280,7 +283,8 @@ int build_tables(rsdgc_plan_s *plan) {
                                                   start, std::min<uint32_t>(kChunk, d.G - start), d.cap,
                                                   first_group + c / kChunkGroup,
                                                   d.chunk_begin + c / kChunkGroup * kChunkGroup, first_group,
-                                                  c + 1 == d.n_chunks ? 1u : 0u};
+                                                  c + 1 == d.n_chunks ? 1u : 0u,
+                                                  plan->n_chunks <= kInlineCountChunks ? uint32_t(kGroupCntStride) : 1u, 0u};
             }
             first_group += (d.n_chunks + kChunkGroup - 1) / kChunkGroup;
         }

@@ -998,6 +998,30 @@ def test_thirty_calls_from_a_zero_residual_hardly_ever_fall_back():
         assert all(h[l] == 3 for h in history[20:] for l in large), f"fresh={fresh}"
 
 
+def test_heavy_tailed_gradients_fed_in_turn_do_not_cost_failed_bounds():
+    """The stress recipe (Student-t noise, p = 5, 0.1 % kept) on a 4096 x 4096 layer, four gradients
+    fed in turn over 40 calls: the threshold jumps with the gradient's turn, and the layer has to
+    learn that from its forecasts while bounds are still sampled -- after the sixteen calls that
+    sample, at most one bound may fail."""
+    import torch
+    from paper_2312_17530_amd import binding
+    w = synth.scaled_down(synth.config(4), 4096, 4096)
+    sess = _session(w.shapes, w.p, w.alpha, w.ratios)
+    arenas = []
+    for t in range(4):
+        sess.set_grad(synth.gradients(w, t))
+        arenas.append(sess.grad.clone())
+    history = []
+    for t in range(40):
+        sess.grad = arenas[t % 4]
+        sess.compress()
+        torch.cuda.synchronize()
+        history.append(binding.rsdgc_last_paths(sess.plan, sess.workspace)[0])
+    assert all(h in (0, 1, 3) for h in history)
+    assert history[16:].count(1) <= 1, history
+    assert history[20:].count(3) >= 19, history
+
+
 def test_set_ratios_and_determinism():
     import torch
     w = synth.scaled_down(synth.config(2), 256, 512)
