@@ -375,7 +375,8 @@ def main() -> int:
         n_cand = sum(r * c for (r, c), pth in zip(w.shapes, paths) if pth in (0, 3))   # candidate path
         dom = max(("first_pass", "capture", "emit"), key=lambda s: stages.get(s, 0.0))
         dur_s = stages[dom] * 1e-3
-        variant = "in_place" if args.in_place else "momentum" if args.momentum is not None else "two_arenas"
+        variant = ("in_place" if args.in_place else "momentum" if args.momentum is not None else
+                   "full_map" if args.full_map else "centres" if args.centres else "two_arenas")
         traffic, traffic_src = measured_traffic(w.name, variant, dom)
         alg = stage_algorithmic_bytes(dom, G, n_pairs, n_cand, args.in_place, args.momentum is not None)
         per_elem = 20.0 if args.momentum is not None else 12.0     # whole path: read g, (u,) r; write (u,) r
