@@ -838,6 +838,19 @@ def test_large_layers_with_rows_that_are_not_whole_mask_words(in_place):
     assert paths[0] == 0 and paths[3] == 0, "expected the candidate path"
 
 
+@pytest.mark.parametrize("path", [AUTO, FULL_MAP])
+def test_wide_layers_whose_rows_span_many_chunks(path):
+    """Rows of 65536 and 40000 elements: the 16 rows of a tile lie in sixteen different groups of
+    chunks, further apart than the kernels that count kept elements as they mark them keep
+    counters for in LDS (those go to the global counters one by one).  One aligned layer, one whose
+    rows are no whole mask words; candidate path and full map."""
+    shapes = [(40, 65536), (33, 40000), (64, 256)]
+    ratios = [0.02, 0.03, 0.05]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 61, t, l) for l, sh in enumerate(shapes)] for t in range(2)]
+    n, ex = run_and_check(shapes, [3, 5, 3], 0.5, ratios, its, "wide_rows", path=path)
+    assert n == 6 and ex >= 5
+
+
 @pytest.mark.parametrize("in_place", [False, True], ids=["two_arenas", "in_place"])
 def test_work_feed_on_small_launches(in_place):
     """The main pass can hand out its tiles through per-XCD work counters; by default it does so
