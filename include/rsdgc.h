@@ -84,7 +84,7 @@ int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio);
  *                        p = 3) records only the centres whose score reaches a bound and
  *                        ranks those.  The bound comes from the thresholds the same layer
  *                        ended on in the two calls before (kept in the workspace), or, in
- *                        the first sixteen calls with a workspace, from a sample of the
+ *                        the first ten calls with a workspace, from a sample of the
  *                        layer's tiles.  A layer falls back to the full map within the call
  *                        when the bound turns out too high or a tile holds too many such
  *                        centres (default).  The other layers are ranked on the full map.
@@ -354,8 +354,9 @@ const char *rsdgc_stage_name(int32_t stage);
  * The path never changes a result.  A layer that would take path 0 or 3 shows 1 when
  *   - its bound failed in this call (too few centres above it, or too many in one tile):
  *     the call then ranked the full map, and the layer's safety margin is doubled; during
- *     the first sixteen calls with a workspace the next four bounds are sampled ones;
- *   - the workspace is past those sixteen calls, the only ones that sample tiles, and one
+ *     the first ten calls with a workspace the next four bounds are sampled ones; later
+ *     the next bound is set below this call's threshold, without a trend;
+ *   - the workspace is past those ten calls, the only ones that sample tiles, and one
  *     of the layer's last two thresholds is zero or subnormal (nothing to predict from). */
 int rsdgc_last_paths(rsdgc_plan_t *plan, const void *workspace, int32_t *paths, void *stream);
 

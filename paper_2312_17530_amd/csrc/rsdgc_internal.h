@@ -38,7 +38,7 @@ constexpr float kMarginMaxLog2 = 0.25f;        // it doubles after every failed 
 constexpr float kMarginDecay = 0.97f;          // per call, back towards the initial margin
 constexpr float kMarginSafety = 1.5f;          // a forecast that came out too high by s widens the margin to 1.5 s + 0.01
 constexpr uint32_t kCooldownCalls = 4;         // calls without a predicted bound after a failed one
-constexpr int kSamplingCalls = 16;             // first calls with a workspace: a layer without a predicted bound
+constexpr int kSamplingCalls = 10;             // first calls with a workspace: a layer without a predicted bound
                                                // takes one sampled from the call's own scores (later: the full map)
 
 // Tile of the block-score kernel (block reading): kBlockTileRows block rows by

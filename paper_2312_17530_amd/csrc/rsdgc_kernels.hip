@@ -181,19 +181,22 @@ __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16
                 // are any: past the calls that sample, the alternative would be the full map, and the
                 // widened margin is tried at once
                 const bool paused = ps.cooldown > 0 && sampling;
+                // the call before failed: its threshold was a jump, not part of a trend -- the forecast
+                // is that threshold itself
+                const bool just_failed = ps.cooldown == kCooldownCalls;
                 if (ps.cooldown > 0) ps.cooldown -= 1;
                 ps.has_forecast = 0;
                 if (ps.tau1 >= (1u << 23) && ps.tau2 >= (1u << 23)) {   // (both in the normal float32 range)
                     const float l1 = __log2f(__uint_as_float(ps.tau1)), l2 = __log2f(__uint_as_float(ps.tau2));
                     const float d = l1 - l2;
-                    const float dd = fminf(fmaxf(d, -2.f * kTrendMaxLog2), kTrendMaxLog2);
+                    const float dd = just_failed ? 0.f : fminf(fmaxf(d, -2.f * kTrendMaxLog2), kTrendMaxLog2);
                     // the forecast is made in every call, used or not: how far the threshold then ends
                     // below it is what sizes the margin (publish_threshold)
                     ps.forecast = l1 + (dd > 0.f ? 0.6f * dd : 1.15f * dd);
                     ps.has_forecast = 1;
                     // (a threshold that jumps: sampled bounds while there are any; later the trend is
                     // taken as far as it is trusted -- a bound that fails costs less than the full map)
-                    if (!paused && (fabsf(d) <= kTrendMaxLog2 || !sampling)) {
+                    if (!paused && (fabsf(d) <= kTrendMaxLog2 || !sampling)) {   // (d, not dd: a jump is sampled)
                         const float margin = ps.margin > 0.f ? ps.margin : margin_init_log2(L.k);
                         const float bound = exp2f(ps.forecast - margin);
                         const uint32_t key = __float_as_uint(bound);
@@ -887,7 +890,9 @@ __device__ __forceinline__ void publish_threshold(PredState *__restrict__ pred, 
     float margin = fmaxf(init, (ps.margin > 0.f ? ps.margin : init) * kMarginDecay);
     if (ps.has_forecast && tau >= (1u << 23)) {
         const float shortfall = ps.forecast - __log2f(__uint_as_float(tau));
-        if (shortfall > 0.f) margin = fmaxf(margin, kMarginSafety * shortfall + 0.01f);
+        // (a shortfall beyond the widest margin is a jump of the gradient's scale, not jitter: no
+        // margin would have covered it, and none is sized by it)
+        if (shortfall > 0.f && shortfall <= kMarginMaxLog2) margin = fmaxf(margin, kMarginSafety * shortfall + 0.01f);
     }
     ps.margin = fminf(margin, kMarginMaxLog2);
     ps.tau2 = ps.tau1;

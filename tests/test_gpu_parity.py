@@ -970,7 +970,9 @@ def test_candidate_bound_is_predicted_from_earlier_calls_and_recovers_from_failu
     # the gradient shrinks tenfold from one call to the next: the predicted bound lies far too high
     small = [g * np.float32(0.1) for g in (base, other)]
     assert call(small, "shrunk") == [1, 1]
-    assert call(small, "shrunk again") == [0, 0]
+    # the call after a failed bound does not extend the jump into a trend: its bound is sampled or
+    # taken from the last threshold alone, and holds
+    assert all(p in (0, 3) for p in call(small, "shrunk again"))
     # and grows a hundredfold: the bound is far too low, every tile overflows -- or the sample decides
     big = [g * np.float32(10.0) for g in (base, other)]
     for i in range(8):
@@ -1014,7 +1016,7 @@ def test_thirty_calls_from_a_zero_residual_hardly_ever_fall_back():
 def test_heavy_tailed_gradients_fed_in_turn_do_not_cost_failed_bounds():
     """The stress recipe (Student-t noise, p = 5, 0.1 % kept) on a 4096 x 4096 layer, four gradients
     fed in turn over 40 calls: the threshold jumps with the gradient's turn, and the layer has to
-    learn that from its forecasts while bounds are still sampled -- after the sixteen calls that
+    learn that from its forecasts while bounds are still sampled -- after the ten calls that
     sample, at most one bound may fail."""
     import torch
     from paper_2312_17530_amd import binding
