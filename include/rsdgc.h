@@ -353,7 +353,8 @@ const char *rsdgc_stage_name(int32_t stage);
  * from the layer's earlier thresholds.  Waits for `stream`, then copies from the device.
  * The path never changes a result.  A layer that would take path 0 or 3 shows 1 when
  *   - its bound failed in this call (too few centres above it, or too many in one tile):
- *     the call then ranked the full map, and the layer's safety margin is doubled; during
+ *     the call then ranked the full map, and the safety margin of the layer's predicted
+ *     bounds is doubled (too few above) or halved, down to its start value (too many); during
  *     the first ten calls with a workspace the next four bounds are sampled ones; later
  *     the next bound is set below this call's threshold, without a trend;
  *   - the workspace is past those ten calls, the only ones that sample tiles, and one

@@ -34,7 +34,7 @@ constexpr int kBigMapLayer = 1 << 20; // elements from which a full-map layer's 
 // while the threshold moved by at most kTrendMaxLog2 between those calls.
 constexpr float kTrendMaxLog2 = 0.14f;         // a factor of 1.10 per call
 constexpr float kMarginInitLog2 = 0.02f;       // safety margin below the lowest threshold expected (1.4 %)
-constexpr float kMarginMaxLog2 = 0.25f;        // it doubles after every failed bound, up to this
+constexpr float kMarginMaxLog2 = 0.25f;        // it doubles after every bound that lay too high, up to this
 constexpr float kMarginDecay = 0.97f;          // per call, back towards the initial margin
 constexpr float kMarginSafety = 1.5f;          // a forecast that came out too high by s widens the margin to 1.5 s + 0.01
 constexpr uint32_t kCooldownCalls = 4;         // calls without a predicted bound after a failed one

@@ -149,7 +149,8 @@ __device__ __forceinline__ float margin_init_log2(uint32_t k) {
 // together.  While a residual builds up, the threshold keeps moving in one direction by steps
 // that, on a logarithmic scale, shrink smoothly from call to call; so after a step d of
 // log2(threshold) the next one is taken to lie between 0.6 d and 1.15 d, and the bound sits a
-// margin below the lowest threshold that allows.  The margin doubles after every failed bound.
+// margin below the lowest threshold that allows.  The margin doubles after a bound that lay too high
+// and halves after one that lay too low (k_find0).
 // The result of the call never depends on the bound -- only whether the layer has to be redone
 // through the full map.  Without a usable history (first calls, after a failure, a threshold
 // that jumps) the bound comes from a sample of this call's scores (k_hint) during the first
@@ -1107,7 +1108,15 @@ __global__ __launch_bounds__(256) void k_find0(const LayerDev *__restrict__ laye
             flags[0] = 1u;                 // the fallback pass has work
             PredState ps = pred[l];
             ps.cooldown = kCooldownCalls;
-            ps.margin = fminf(2.f * (ps.margin > 0.f ? ps.margin : margin_init_log2(layers[l].k)), kMarginMaxLog2);
+            if (st.predicted) {
+                // the margin of the predicted bounds follows the way this one failed: too few centres above
+                // it -- twice the margin; a tile with too many, or a threshold beyond the bins -- the bound
+                // lay too low, and a wider margin would only repeat that: half of it, down to its start value
+                const float init = margin_init_log2(layers[l].k);
+                const float m = ps.margin > 0.f ? ps.margin : init;
+                const bool too_low = st.overflow != 0u || (r.found && r.digit == static_cast<uint32_t>(kFineBins - 1));
+                ps.margin = too_low ? fmaxf(0.5f * m, init) : fminf(2.f * m, kMarginMaxLog2);
+            }
             pred[l] = ps;
         }
         return;
