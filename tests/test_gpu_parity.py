@@ -1037,6 +1037,41 @@ def test_heavy_tailed_gradients_fed_in_turn_do_not_cost_failed_bounds():
     assert history[20:].count(3) >= 19, history
 
 
+def test_a_bound_that_fails_because_a_tile_overflows_does_not_widen_the_margin():
+    """A 64 x 576 layer with p = 7 and k_l = 25: the scores of neighbouring centres share most of
+    their 49 elements, so hundreds of centres of one tile lie within a few per cent of the
+    threshold.  A bound set further below the threshold after such a tile overflowed would overflow
+    again, call after call; the margin has to shrink instead, and the layer comes back to predicted
+    bounds.  Every call gives the oracle's result, carried residual included."""
+    import torch
+    from paper_2312_17530_amd import binding
+    w = synth.config(3)
+    shape, ratio, p = w.shapes[1], w.ratios[1], 7
+    assert shape == (64, 576)
+    grads = [synth.gradients(w, t)[1] for t in range(4)]
+    sess = _session([shape], p, w.alpha, [ratio])
+    r = np.zeros(shape, np.float32)
+    history = []
+    for t in range(40):
+        g = grads[t % 4]
+        sess.set_grad([g])
+        sess.compress()
+        torch.cuda.synchronize()
+        path = binding.rsdgc_last_paths(sess.plan, sess.workspace)[0]
+        history.append(path)
+        o = oracle.compress_layer(g, r, p, w.alpha, ratio)
+        assert o.k == 25
+        gi, gv, gc, gn = sess.results()[0]
+        gpu_r = sess.unpack(sess.residual)[0]
+        assert parity.check_layer(f"call {t}, path {path}", shape, p, o.k, o.tau, o.nsi, o.centres,
+                                  o.idx, o.val, o.r_new, o.v, gi, gv, gc, gn, gpu_r)
+        r = gpu_r.copy()     # (equal to the oracle's where the selections agree; the next call starts from the same state)
+        sess.set_residual([r])
+    assert all(h in (0, 1, 3) for h in history)
+    assert history[24:].count(1) <= 4, history
+    assert history[24:].count(3) >= 12, history
+
+
 def test_set_ratios_and_determinism():
     import torch
     w = synth.scaled_down(synth.config(2), 256, 512)
