@@ -25,8 +25,12 @@
  *     RSDGC_E* code.  Arguments are validated before anything is enqueued, so
  *     on RSDGC_EINVAL no buffer has been touched.  Nothing throws or aborts
  *     across this boundary.
- *   - Non-finite gradient values are not detected; results for them are
- *     unspecified (the paper does not treat them).
+ *   - Non-finite gradient values are not detected, and which neighbourhoods win
+ *     next to them is unspecified (the paper does not treat them).  A call on
+ *     them is still well formed -- k_l neighbourhoods per layer, ascending
+ *     indices, values and residual copied bit for bit, no access out of
+ *     bounds -- and leaves nothing behind that changes the result of a later
+ *     call.
  *   - A plan may be used by one stream at a time.
  */
 #ifndef RSDGC_H

@@ -1072,6 +1072,75 @@ def test_a_bound_that_fails_because_a_tile_overflows_does_not_widen_the_margin()
     assert history[24:].count(3) >= 12, history
 
 
+def _same_floats(a, b):
+    a, b = np.asarray(a, np.float32).reshape(-1), np.asarray(b, np.float32).reshape(-1)
+    return a.shape == b.shape and bool(np.all((a.view(np.uint32) == b.view(np.uint32)) | (np.isnan(a) & np.isnan(b))))
+
+
+@pytest.mark.parametrize("path", [AUTO, FULL_MAP])
+def test_non_finite_gradients_give_a_well_formed_result_and_leave_no_trace(path):
+    """NaN and infinite gradient values are not detected and which centres win next to them is
+    unspecified -- but a call on them must still be well formed (k_l centres per layer, ascending
+    indices inside the layer, the kept elements exactly the windows of those centres, values and
+    residual copied bit for bit), and the thresholds it leaves in the workspace (infinite, NaN)
+    must not spoil later calls: those give the oracle's result again."""
+    import torch
+    shapes, ratios, p = [(512, 4608), (64, 576), (300, 77)], [0.02, 0.05, 0.03], 3
+    rng = np.random.default_rng(77)
+    clean = [(rng.standard_normal(sh) * 1e-3).astype(np.float32) for sh in shapes]
+    zero = [np.zeros(sh, np.float32) for sh in shapes]
+    sess = _session(shapes, p, 0.5, ratios, path=path)
+
+    def oracle_call(tag):
+        sess.set_grad(clean)
+        sess.set_residual(zero)
+        sess.compress()
+        torch.cuda.synchronize()
+        res, gpu_r = sess.results(), sess.unpack(sess.residual)
+        for l, sh in enumerate(shapes):
+            o = oracle.compress_layer(clean[l], zero[l], p, 0.5, ratios[l])
+            gi, gv, gc, gn = res[l]
+            parity.check_layer(f"{tag}[l={l}]", sh, p, o.k, o.tau, o.nsi, o.centres, o.idx, o.val, o.r_new, o.v,
+                               gi, gv, gc, gn, gpu_r[l])
+
+    for _ in range(3):
+        oracle_call("before")                  # (three calls: the candidate path now predicts its bounds)
+    scattered = [g.copy() for g in clean]
+    for g in scattered:
+        flat = g.reshape(-1)
+        at = rng.choice(flat.size, size=max(4, flat.size // 5000), replace=False)
+        flat[at[0::4]] = np.nan
+        flat[at[1::4]] = np.inf
+        flat[at[2::4]] = -np.inf
+        flat[at[3::4]] = np.float32(3e38)      # squares overflow float32, not the sums kept in double
+    tile_of_inf = [g.copy() for g in clean]
+    tile_of_inf[0][32:64, 1024:1536] = np.inf
+    all_nan = [g.copy() for g in clean]
+    all_nan[1][:] = np.nan
+    all_nan[2][:] = np.inf
+    for tag, grads in [("scattered", scattered), ("tile of inf", tile_of_inf), ("whole layers", all_nan),
+                       ("scattered again", scattered)]:
+        sess.set_grad(grads)
+        sess.set_residual(zero)
+        sess.compress()
+        torch.cuda.synchronize()
+        res, gpu_r = sess.results(), sess.unpack(sess.residual)
+        for l, (R, C) in enumerate(shapes):
+            gi, gv, gc, gn = res[l]
+            k = int(np.ceil(R * C / (p * p) * ratios[l]))
+            assert gn == k and len(gc) == k, f"{tag}[l={l}]"
+            assert np.all(np.diff(gc.astype(np.int64)) > 0) and int(gc[-1]) < R * C
+            want = np.flatnonzero(parity.dilate_np(gc, R, C, p)).astype(np.uint32)
+            assert np.array_equal(gi, want), f"{tag}[l={l}]: kept indices are not the windows of the centres"
+            v = grads[l].reshape(-1)
+            assert _same_floats(gv, v[want]), f"{tag}[l={l}]: values"
+            r_want = v.copy()
+            r_want[want] = 0.0
+            assert _same_floats(gpu_r[l], r_want), f"{tag}[l={l}]: residual"
+        oracle_call(f"after {tag}")
+        oracle_call(f"after {tag}, second call")
+
+
 def test_set_ratios_and_determinism():
     import torch
     w = synth.scaled_down(synth.config(2), 256, 512)
