@@ -1141,6 +1141,70 @@ def test_non_finite_gradients_give_a_well_formed_result_and_leave_no_trace(path)
         oracle_call(f"after {tag}, second call")
 
 
+def test_non_finite_gradients_with_momentum_and_in_the_block_reading():
+    """The same for Eq. 12's momentum (u = m u + g carries the NaN on; the kept elements of u and r
+    are still cleared) and for the reading with non-overlapping neighbourhoods: k_l centres or
+    blocks, ascending, values and arenas bit for bit from the call's own kept set."""
+    import torch
+    from paper_2312_17530_amd.session import Session, BlockSession
+    shapes, ratios, p, m = [(256, 1152), (64, 576), (300, 77)], [0.02, 0.05, 0.03], 3, 0.9
+    rng = np.random.default_rng(78)
+    grads = [(rng.standard_normal(sh) * 1e-3).astype(np.float32) for sh in shapes]
+    u0 = [(rng.standard_normal(sh) * 1e-3).astype(np.float32) for sh in shapes]
+    for g in grads:
+        flat = g.reshape(-1)
+        at = rng.choice(flat.size, size=max(3, flat.size // 3000), replace=False)
+        flat[at[0::3]] = np.nan
+        flat[at[1::3]] = np.inf
+        flat[at[2::3]] = -np.inf
+    grads[1][8:24, 100:400] = np.inf
+    zero = [np.zeros(sh, np.float32) for sh in shapes]
+
+    sess = Session(shapes, p, 0.5, ratios, momentum=float(m))
+    for _ in range(2):
+        sess.set_grad(grads)
+        sess.set_residual(zero)
+        sess.set_momentum(u0)
+        sess.compress()
+        torch.cuda.synchronize()
+        res, gpu_r, gpu_u = sess.results(), sess.unpack(sess.residual), sess.unpack(sess.momentum_buf)
+        for l, (R, C) in enumerate(shapes):
+            gi, gv, gc, gn = res[l]
+            k = int(np.ceil(R * C / (p * p) * ratios[l]))
+            assert gn == k and len(gc) == k and np.all(np.diff(gc.astype(np.int64)) > 0) and int(gc[-1]) < R * C
+            want = np.flatnonzero(parity.dilate_np(gc, R, C, p)).astype(np.uint32)
+            assert np.array_equal(gi, want)
+            un, vn = oracle.momentum_accumulate(u0[l], grads[l], zero[l], float(m))   # elementwise: u = m u + g, v = r + u
+            u, v = un.reshape(-1).copy(), vn.reshape(-1).copy()
+            assert _same_floats(gv, v[want]), f"momentum[l={l}]: values"
+            u[want] = 0.0
+            v[want] = 0.0
+            assert _same_floats(gpu_u[l], u) and _same_floats(gpu_r[l], v), f"momentum[l={l}]: arenas"
+
+    bs = BlockSession(shapes, p, 0.5, ratios)
+    bs.set_grad(grads)
+    bs.set_residual(zero)
+    bs.compress()
+    torch.cuda.synchronize()
+    res, gpu_r = bs.results(), bs.unpack(bs.residual)
+    for l, (R, C) in enumerate(shapes):
+        gb, gv = res[l]
+        BR, BC = -(-R // p), -(-C // p)
+        assert len(gb) == bs.plan.layer_k(l) and np.all(np.diff(gb.astype(np.int64)) > 0) and int(gb[-1]) < BR * BC
+        v = grads[l]
+        want_r = v.copy()
+        want_val = np.zeros(len(gb) * p * p, np.float32)
+        for j, b in enumerate(gb):
+            bx, by = divmod(int(b), BC)
+            x1, y1 = min(R, bx * p + p), min(C, by * p + p)
+            blk = np.zeros((p, p), np.float32)
+            blk[:x1 - bx * p, :y1 - by * p] = v[bx * p:x1, by * p:y1]
+            want_val[j * p * p:(j + 1) * p * p] = blk.ravel()
+            want_r[bx * p:x1, by * p:y1] = 0.0
+        assert _same_floats(gv, want_val), f"blocks[l={l}]: values"
+        assert _same_floats(gpu_r[l], want_r), f"blocks[l={l}]: residual"
+
+
 def test_set_ratios_and_determinism():
     import torch
     w = synth.scaled_down(synth.config(2), 256, 512)
