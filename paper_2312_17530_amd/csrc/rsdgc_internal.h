@@ -88,7 +88,7 @@ struct LayerDev {
     uint32_t n_sampled;     // sampled tiles of the layer
     uint32_t list_cap;      // capacity of the threshold-bucket list
     uint32_t list_shards;   // shards the list is split into (each list_cap / list_shards entries, own counter)
-    uint32_t slot_cap;      // entries per tile slot (kSlotCapMax)
+    uint32_t slot_cap;      // entries per tile slot: kSlotCapMax, or what a tile of the layer can hold if that is less
     uint32_t cgroup_begin;  // first chunk group (kChunkGroup chunks) of the layer, numbered over all layers
     uint32_t pad_;
 };
@@ -223,7 +223,7 @@ struct WsLayout {
     size_t zero_end = 0;
     // not cleared
     size_t slot_cnt = 0;     // uint32[n_tiles_all]  candidates recorded per tile
-    size_t slot_ent = 0;     // uint64[sum over large layers of n_tiles * slot_cap]  their composite keys
+    size_t slot_ent = 0;     // uint64[sum over the layers of n_tiles * slot_cap]  their composite keys
     size_t list_ent = 0;     // uint64[sum list_cap]  composite keys of each layer's threshold bucket
     size_t list2_ent = 0;    // uint64[n_layers][2048]  keys sharing the first two digits (plans with big_map_layers)
     size_t nsi = 0;          // float[total_elems]  score map (full-map layers only)
@@ -266,6 +266,7 @@ struct rsdgc_plan_s {
     std::vector<rsdgc::ChunkEntry> map_chunks;
     std::vector<rsdgc::SampleEntry> map_tiles;
     uint32_t n_tiles_all = 0;
+    uint64_t slot_entries = 0;          // composite keys in all tile slots together
     uint32_t n_slot_groups = 0;
     bool any_large = false;
     bool big_map_layers = false;        // some layer of a million elements or more is ranked on the full map

@@ -89,6 +89,17 @@ __device__ __forceinline__ uint32_t dir_lookup(const DirEntry *__restrict__ dir,
     return lo;
 }
 
+// The same from entry e, which lies at or before the wanted one: a workgroup's next item is often in
+// the same layer or the next, but in a plan of many small layers it may lie hundreds of layers on --
+// stepping there entry by entry is a chain of dependent loads that costs more than the tile itself.
+__device__ __forceinline__ uint32_t dir_advance(const DirEntry *__restrict__ dir, uint32_t n, uint32_t e,
+                                                uint32_t id) {
+    if (id < dir[e + 1].begin) return e;
+    ++e;
+    if (id < dir[e + 1].begin) return e;
+    return e + 1 + dir_lookup(dir + e + 1, n - (e + 1), id);    // (id < dir[n].begin, so e + 1 < n)
+}
+
 // Workgroups are handed to the 8 XCDs round-robin by id; give each XCD one contiguous
 // range of tiles so that neighbouring tiles (which share halo rows/columns) meet in
 // the same L2.
@@ -543,7 +554,7 @@ void k_nsi(const NsiArgs a) {
             l = se.layer;
             local = se.local_tile;
         } else {
-            while (t >= a.dir[e + 1].begin) ++e;
+            e = dir_advance(a.dir, a.n_dir, e, t);
             l = a.dir[e].layer;
             local = t - a.dir[e].begin;
         }
@@ -1281,7 +1292,7 @@ __global__ __launch_bounds__(256) void k_gather(const GatherArgs a, const Gather
             ge = gl.cand_groups[it];
             l = ge.layer;
         } else {
-            while (it >= dir[e + 1].begin) ++e;
+            e = dir_advance(dir, gl.n_layers, e, it);
             l = dir[e].layer;
         }
         if (l != cur_l) {
@@ -1920,7 +1931,7 @@ __global__ __launch_bounds__(256) void k_mark(const MarkArgs m) {
             l = se.layer;
             local = se.local_tile;
         } else {
-            while (t >= dir[e + 1].begin) ++e;
+            e = dir_advance(dir, n_layers, e, t);
             l = dir[e].layer;
             local = t - dir[e].begin;
         }
@@ -2487,7 +2498,7 @@ __global__ __launch_bounds__(256) void k_block_nsi(const LayerDev *__restrict__ 
     LayerDev O, I;
     for (uint32_t t = first; FEED ? t != kNoItem : t < n_tiles;
          t = FEED ? feed.next(feed_slot) : t + stride) {
-        while (t >= tile_dir[e + 1].begin) ++e;
+        e = dir_advance(tile_dir, n_layers, e, t);
         const uint32_t l = tile_dir[e].layer;
         if (l != cur_l) {
             if (active) {                              // flush the finished layer's counts

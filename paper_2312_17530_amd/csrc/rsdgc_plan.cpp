@@ -40,11 +40,16 @@ int build_tables(rsdgc_plan_s *plan) {
 
     int64_t elem_off = 0, out_off = 0, centre_off = 0;
     uint32_t chunk_begin = 0, tile_begin_all = 0, group_begin = 0, cgroup_begin = 0;
-    uint64_t list_off = 0;
+    uint64_t list_off = 0, slot_off = 0;
     for (int l = 0; l < L; ++l) {
         LayerDev &d = plan->layers[l];
-        const int64_t R = plan->shapes[l].rows, C = plan->shapes[l].cols, G = R * C;
+        int64_t R = plan->shapes[l].rows, C = plan->shapes[l].cols;
+        const int64_t G = R * C;
         const int p = plan->p[l];
+        // A single column is handled as a single row: the same elements at the same flat indices with
+        // the same neighbours (Eq. 7's distance on one axis only), and rows are what the tiles stream.
+        // (Not for a block grid, whose wire format depends on the orientation of the p x p blocks.)
+        if (C == 1 && !plan->blocks && plan->k_override.empty()) std::swap(R, C);
         const int64_t k = plan->k_override.empty() ? keep_count(G, p, plan->ratio[l]) : plan->k_override[l];
         int64_t cap = k * p * p;
         if (cap > G && !plan->blocks) cap = G;   // (a kept block always sends p*p values, padding included)
@@ -99,9 +104,12 @@ int build_tables(rsdgc_plan_s *plan) {
         const double want = 2.0 * double(k) * frac;
         const double per_tile = d.n_tiles ? 8.0 * double(k) / double(d.n_tiles) : 0.0;
         d.large = (plan->allow_candidates && k > 0 && per_tile <= double(kSlotCapMax)) ? 1u : 0u;
-        d.slot_cap = kSlotCapMax;
-        d.slot_off = static_cast<uint64_t>(tile_begin_all) * kSlotCapMax;   // (room for either size: the
-                                                                            // layout does not move with the ratios)
+        // (a tile of a narrow or flat layer holds fewer elements than kSlotCapMax: its slots are that short.
+        // The size follows from the shape alone, so the layout does not move with the ratios.)
+        const int64_t tile_elems = std::min<int64_t>(R, kTileRows) * std::min<int64_t>(C, kTileCols);
+        d.slot_cap = static_cast<uint32_t>(std::min<int64_t>(kSlotCapMax, (tile_elems + 1) & ~int64_t(1)));
+        d.slot_off = slot_off;
+        slot_off += static_cast<uint64_t>(d.n_tiles) * d.slot_cap;
         d.hint_target = d.large ? static_cast<uint32_t>(std::ceil(want + 4.0 * std::sqrt(want) + 8.0)) : 0u;
         plan->any_large = plan->any_large || d.large;
         plan->big_map_layers = plan->big_map_layers || (!d.large && k > 0 && G >= kBigMapLayer);
@@ -126,6 +134,7 @@ int build_tables(rsdgc_plan_s *plan) {
         plan->n_count_groups += (d.n_chunks + kCountChunks - 1) / kCountChunks;
     }
     plan->n_tiles_all = tile_begin_all;
+    plan->slot_entries = slot_off;
     plan->n_slot_groups = group_begin;
     plan->total_elems = elem_off;
     plan->out_capacity = out_off;
@@ -233,7 +242,7 @@ int build_tables(rsdgc_plan_s *plan) {
     w.zero_end = off;
     w.slot_cnt = off;     off = align_up(off + sizeof(uint32_t) * plan->n_tiles_all, A);
     // (the plan of a block grid never takes the candidate path and has no tile slots)
-    w.slot_ent = off;     off = align_up(off + (plan->k_override.empty() ? sizeof(uint64_t) * kSlotCapMax * size_t(plan->n_tiles_all) : 0), A);
+    w.slot_ent = off;     off = align_up(off + (plan->k_override.empty() ? sizeof(uint64_t) * size_t(plan->slot_entries) : 0), A);
     w.list_ent = off;     off = align_up(off + sizeof(uint64_t) * static_cast<size_t>(list_off), A);
     w.list2_ent = off;    off = align_up(off + sizeof(uint64_t) * 2048 * size_t(L), A);
     // the score map covers every layer: which layers are ranked on it depends on the keep ratios

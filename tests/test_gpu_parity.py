@@ -610,6 +610,34 @@ def test_ragged_shapes_mixed_p_two_iterations(alpha, in_place):
     assert ex >= n - 2          # the tolerance band is allowed, but should hardly ever be needed
 
 
+@pytest.mark.parametrize("path", [AUTO, FULL_MAP])
+def test_long_vectors_and_narrow_layers(path):
+    """One-dimensional parameters given as a column or as a row, and tall layers of a few columns:
+    three iterations against the oracle on each ranking path (a column is handled as a row inside
+    the library; the flat indices are the same), and a workspace that stays in proportion -- the
+    tile slots of such layers are as short as their tiles."""
+    shapes = [(50000, 1), (1, 50000), (30000, 7), (3, 40000), (2500, 20)]
+    p_list = [3, 3, 5, 3, 7]
+    ratios = [0.02, 0.02, 0.01, 0.05, 0.02]
+    its = [[synth.layer_gradient(sh, 1e-3 * (l + 1), 23, t, l) for l, sh in enumerate(shapes)] for t in range(3)]
+    n, ex = run_and_check(shapes, p_list, 0.5, ratios, its, "vectors", path=path)
+    assert n == 3 * len(shapes) and ex >= n - 2
+    G = sum(r * c for r, c in shapes)
+    ws = _session(shapes, 3, 0.5, ratios, p_list, path=path).plan.workspace_bytes
+    assert ws <= 20 * G + (4 << 20), ws
+    # the column and the row of the same values give the same pairs
+    g = synth.layer_gradient((50000, 1), 1e-3, 23, 0, 0)
+    col = _session([(50000, 1)], 3, 0.5, [0.02], path=path)
+    row = _session([(1, 50000)], 3, 0.5, [0.02], path=path)
+    col.set_grad([g])
+    row.set_grad([g.reshape(1, -1)])
+    col.compress()
+    row.compress()
+    (ci, cv, cc, cn), (ri, rv, rc, rn) = col.results()[0], row.results()[0]
+    assert cn == rn and np.array_equal(cc, rc) and np.array_equal(ci, ri)
+    assert np.array_equal(cv.view(np.uint32), rv.view(np.uint32))
+
+
 def _draw_small(seed):
     """A seeded small plan: 1-5 layers of up to 90 x 400 elements, a neighbourhood side per
     layer, keep ratios from 0 to 1, a mix from 0 to 1, two iterations of ordinary noise or of
