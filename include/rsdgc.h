@@ -91,7 +91,9 @@ int rsdgc_plan_set_ratios(rsdgc_plan_t *plan, const double *keep_ratio);
  *                        the first ten calls with a workspace, from a sample of the
  *                        layer's tiles.  A layer falls back to the full map within the call
  *                        when the bound turns out too high or a tile holds too many such
- *                        centres (default).  The other layers are ranked on the full map.
+ *                        centres (default).  The other layers are ranked on the full map,
+ *                        and so is a layer whose bound would lie outside 2^-40 .. 2^40
+ *                        (scores of the order of 1e-12 or 1e12).
  *   RSDGC_PATH_FULL_MAP  every layer writes its full score map and ranks it with
  *                        histogram passes over all elements.                       */
 #define RSDGC_PATH_AUTO      0

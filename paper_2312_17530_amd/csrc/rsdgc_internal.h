@@ -38,6 +38,11 @@ constexpr float kMarginMaxLog2 = 0.25f;        // it doubles after every bound t
 constexpr float kMarginDecay = 0.97f;          // per call, back towards the initial margin
 constexpr float kMarginSafety = 1.5f;          // a forecast that came out too high by s widens the margin to 1.5 s + 0.01
 constexpr uint32_t kCooldownCalls = 4;         // calls without a predicted bound after a failed one
+// Candidate bounds lie between 2^-40 and 2^40 (float32 bit patterns): the main pass tests scores
+// against them in float32, and its error bounds need that range.  A layer whose bound would fall
+// outside (gradients of the order of 1e-12 or 1e12) is ranked on the full map.
+constexpr uint32_t kPreF32MinKey = (127u - 40u) << 23;
+constexpr uint32_t kPreF32MaxKey = (127u + 40u) << 23;
 constexpr int kSamplingCalls = 10;             // first calls with a workspace: a layer without a predicted bound
                                                // takes one sampled from the call's own scores (later: the full map)
 

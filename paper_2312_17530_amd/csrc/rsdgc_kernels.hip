@@ -212,7 +212,7 @@ __global__ __launch_bounds__(256) void k_begin(uint4 *__restrict__ p, size_t n16
                         const float margin = ps.margin > 0.f ? ps.margin : margin_init_log2(L.k);
                         const float bound = exp2f(ps.forecast - margin);
                         const uint32_t key = __float_as_uint(bound);
-                        if (key >= (1u << 23) && key < 0x7f800000u) {
+                        if (key >= kPreF32MinKey && key <= kPreF32MaxKey) {   // (else: no bound, the full map)
                             s.hint_key = key;
                             s.predicted = 1;
                         }
@@ -252,12 +252,9 @@ __device__ __forceinline__ float4 load_streaming(const float *__restrict__ src) 
     return make_float4(t.x, t.y, t.z, t.w);
 }
 
-// A double that is the same in every lane, moved to scalar registers.
-__device__ __forceinline__ double uniform_f64(double x) {
-    const unsigned long long b = static_cast<unsigned long long>(__double_as_longlong(x));
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b >> 32));
-    return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
+// A float that is the same in every lane, moved to a scalar register.
+__device__ __forceinline__ float uniform_f32(float x) {
+    return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(x)));
 }
 
 // Eqs. 8-10 from the window sums sa = sum|w|, ss = sum w, sq = sum w^2 (n = p*p slots):
@@ -270,9 +267,28 @@ __device__ __forceinline__ double uniform_f64(double x) {
 // is therefore evaluated again the way Eq. 10 is printed -- window_ssd below -- and only the
 // others (relative error of the one-pass form below 3e-9) keep the one-pass value.
 constexpr double kCancelFrac = 1.0 / 1048576.0;
-// More than the absolute error of the one-pass d, as a fraction of n*sq (a product, a square and
-// the p*p roundings of sum w^2: below 52 * 2^-53 for p <= 7).
-constexpr double kOnePassErr = 1e-13;
+// The main pass rules out the centres below the bound in float32 where the bound's magnitude allows
+// it (half the registers of the double form, no conversions).  It must never rule out a centre that
+// the evaluation in full would record, so every float32 quantity is bounded against the exact one.
+// With u = 2^-24, n = p*p, exact window sums SA = sum|w|, SS = sum w, SQ = sum w^2, D = n SQ - SS^2
+// (SA^2 <= n SQ, |SS| <= SA), and a bound B in [2^-40, 2^40] (nothing of weight under- or overflows):
+//   sa = SA (1 + t), |t| <= (n-1) u          (non-negative terms)
+//   n sq - ss^2 differs from D by at most (3n + 3) u * n SQ: n u from the roundings of sq and of the
+//     product with n, 2n u from ss (off by at most (n-1) u SA) squared, the rest from the last fma;
+//     d_hi = that + kPreSlack<P> * n sq with kPreSlack = 1.3 (3n + 3) u is therefore at least D;
+//   rest = B' - ca sa with B' = B (1 - 2^-22 - 2.04 n u), rounded down: at most the exact
+//     B (1 - 2^-22) - ca SA whenever ca SA < 2 B, and negative otherwise;
+//   the centre stays unless rest > 0 and cb^2 d_hi < rest^2 (1 - 1e-6): the seven roundings between
+//     the two sides change their ratio by less than 8 u < 1e-6.
+// The comparison is written so that a NaN on either side keeps the centre, and an infinite sum does:
+// such windows are left to the evaluation in full.  Squares of values below 2^-63 underflow; what is
+// lost (below 2^-126 each) is far less than either slack for a bound of at least 2^-40.  Outside
+// that range no bound is handed out: the layer is ranked on the full map (k_begin, k_hint).
+template <int P> struct PreF32 {
+    static constexpr float kSlack = 1.3f * (3.f * P * P + 3.f) * 5.9604645e-8f;
+    static constexpr double kBoundFactor = 1.0 - 1.0 / 4194304.0 - 2.04 * (P * P) * 5.9604645e-8;
+};
+
 constexpr int kQueueCap = 1024;      // centres one tile can queue for full evaluation (twice the largest slot)
 
 __device__ __forceinline__ double var_n2_one_pass(double ss, double nsq) {
@@ -533,7 +549,6 @@ void k_nsi(const NsiArgs a) {
     uint32_t cur_l = 0xffffffffu;         // layer whose counts sit in lhist
     uint32_t hint_key = 0;
     uint32_t *hist_base = a.hist;         // first pass: a.hist_s for the sampled tiles of a large layer
-    double bound_lo = 0.0;                // capture: a conservative form of the candidate bound
     bool active = true;
     bool whole = true;                    // every tile of the layer is visited: v and the scores go out
     LayerDev L;
@@ -542,7 +557,8 @@ void k_nsi(const NsiArgs a) {
     // (kernel arguments: the same in every lane, so they stay in scalar registers -- the scalar unit
     // has no floating point, a uniform value computed here would occupy vector registers)
     const double ca = a.ca, cb = a.cb;
-    const double cb2 = uniform_f64(cb * cb);
+    const float caf = uniform_f32(static_cast<float>(ca)), cb2f = uniform_f32(static_cast<float>(cb * cb));
+    float bound_lof = 0.f;                // capture: a conservative form of the candidate bound (PreF32)
     static_assert(kTileCols * (kTileRows / RPT) == 256, "one thread per RPT rows of one column");
     const int c0 = tid % kTileCols, ty = tid / kTileCols;
     const int row_base = ty * RPT;
@@ -579,8 +595,13 @@ void k_nsi(const NsiArgs a) {
                 else active = st.mode == kModeCandidates;
                 if (CAPTURE) {
                     hint_key = st.hint_key;
-                    // below every double that rounds to a float32 at or above the bound
-                    bound_lo = uniform_f64(static_cast<double>(__uint_as_float(hint_key)) * (1.0 - 1.0 / 4194304.0));
+                    bound_lof = uniform_f32(__double2float_rd(static_cast<double>(__uint_as_float(hint_key)) * PreF32<P>::kBoundFactor));
+                    // (k_begin and k_hint give no bound outside the range of the float32 test; should one
+                    // arrive all the same, the layer is not captured and k_find0 sends it to the full map)
+                    if (active && (hint_key < kPreF32MinKey || hint_key > kPreF32MaxKey)) {
+                        active = false;
+                        if (tid == 0 && hint_key != 0u) a.state_rw[l].overflow = 1u;
+                    }
                 }
             }
             if (PASS == kPassSample) hist_base = whole ? a.hist : a.hist_s;
@@ -711,6 +732,52 @@ void k_nsi(const NsiArgs a) {
         // entries of the thread once, outside the loop over the tiles, and keeps them in registers)
         int c0q = c0;
         asm volatile("" : "+v"(c0q));
+        if (CAPTURE) {
+            // Only the centres that reach the bound are wanted, and about 99.5 % do not.  A test
+            // without the square root rules those out:
+            //   NSI >= B  <=>  cb*sqrt(d) >= B - ca*sa  <=>  rest <= 0  or  cb^2 * d >= rest^2
+            // in float32, with the slacks of PreF32 (a window whose variance cancels is never ruled out
+            // on a value that is too small).  Each thread walks down its column keeping the last P row
+            // sums.  The few centres that remain are queued and evaluated in full after the sweep, one
+            // per thread.
+            const float nf = static_cast<float>(P * P);
+            float fs_a[P], fs_s[P], fs_q[P];
+#pragma unroll
+            for (int i = 0; i < RPT + 2 * H; ++i) {
+                const float *row = &tile[(row_base + i) * PITCH + PADL + c0 - H];
+                {
+                    float sa = fabsf(row[0]), ss = row[0], sq = row[0] * row[0];
+#pragma unroll
+                    for (int j = 1; j < P; ++j) {
+                        sa += fabsf(row[j]);
+                        ss += row[j];
+                        sq = fmaf(row[j], row[j], sq);
+                    }
+                    fs_a[i % P] = sa;
+                    fs_s[i % P] = ss;
+                    fs_q[i % P] = sq;
+                }
+                if (i >= 2 * H) {
+                    const int o = i - 2 * H;
+                    float sa = fs_a[o % P], ss = fs_s[o % P], sq = fs_q[o % P];
+#pragma unroll
+                    for (int j = 1; j < P; ++j) {
+                        sa += fs_a[(o + j) % P];
+                        ss += fs_s[(o + j) % P];
+                        sq += fs_q[(o + j) % P];
+                    }
+                    const float nsq = nf * sq;
+                    const float d_hi = fmaf(PreF32<P>::kSlack, nsq, fmaf(-ss, ss, nsq));
+                    const float rest = fmaf(-caf, sa, bound_lof);
+                    const int x = x0 + row_base + o, y = y0 + c0;
+                    if ((rest <= 0.f || !(cb2f * d_hi < rest * rest * (1.f - 1e-6f))) && x < R && y < C) {
+                        const uint32_t pos = atomicAdd(&nqueue, 1u);
+                        if (pos < static_cast<uint32_t>(kQueueCap))
+                            queue[pos] = static_cast<uint16_t>((row_base + o) * kTileCols + c0q);
+                    }
+                }
+            }
+        } else {
         double hs_a[P], hs_s[P], hs_q[P];
 #pragma unroll
         for (int i = 0; i < RPT + 2 * H; ++i) {
@@ -742,23 +809,7 @@ void k_nsi(const NsiArgs a) {
                 const double nsq = __dmul_rn(n, sq);
                 double d = var_n2_one_pass(ss, nsq);
                 const int x = x0 + row_base + o, y = y0 + c0;
-                if (CAPTURE) {
-                    // Only the centres that reach the bound are wanted, and about 99.5 % do not.  A
-                    // test without the square root rules those out:
-                    //   NSI >= B  <=>  cb*sqrt(d) >= B - ca*sa  <=>  rest <= 0  or  cb^2 * d >= rest^2
-                    // with slack far beyond the rounding errors of the double arithmetic and the last
-                    // float32 bit of the bound, and with d raised by more than the error the one-pass
-                    // form can have (so that a window whose variance cancels is never ruled out on a
-                    // value that is too small).  The few that remain are queued and evaluated in
-                    // full after the sweep, one per thread.
-                    const double rest = bound_lo - ca * sa;
-                    const double d_hi = fma(kOnePassErr, nsq, d);
-                    if ((rest <= 0.0 || cb2 * d_hi >= rest * rest * (1.0 - 1e-9)) && x < R && y < C) {
-                        const uint32_t pos = atomicAdd(&nqueue, 1u);
-                        if (pos < static_cast<uint32_t>(kQueueCap))
-                            queue[pos] = static_cast<uint16_t>((row_base + o) * kTileCols + c0q);
-                    }
-                } else {
+                {
                     // the one-pass variance cancelled (rare; never for P = 1, where it is 0 by definition)
                     if (P > 1 && d < kCancelFrac * nsq)
                         d = __dmul_rn(n, window_ssd<P>(&tile[(row_base + o) * PITCH + PADL + c0 - H], PITCH, ss / n));
@@ -770,6 +821,7 @@ void k_nsi(const NsiArgs a) {
                     }
                 }
             }
+        }
         }
         __syncthreads();                  // the sweep is complete (the tile is still needed by the queue)
 
@@ -1045,7 +1097,7 @@ __global__ __launch_bounds__(256) void k_hint(const LayerDev *__restrict__ layer
     __syncthreads();
     if (tid == 0) {
         const uint32_t key = res.found ? res.digit << kCoarseShift : 0u;
-        if (key != 0u) {
+        if (key >= kPreF32MinKey && key <= kPreF32MaxKey) {      // (a bound the main pass can test in float32)
             state[l].hint_key = key;
         } else {
             state[l].mode = kModeFullMap;

@@ -1100,6 +1100,35 @@ def test_a_bound_that_fails_because_a_tile_overflows_does_not_widen_the_margin()
     assert history[24:].count(3) >= 12, history
 
 
+def test_gradients_at_the_edges_of_the_range_of_candidate_bounds():
+    """The main pass tests scores against a layer's bound in float32, which its error bounds allow
+    for bounds between 2^-40 and 2^40; a layer whose bound would lie outside is ranked on the full
+    map.  Gradients scaled to either side of both ends: the oracle's result at every scale, the
+    candidate path (predicted bounds by the third call) inside the range, the full map outside."""
+    import torch
+    from paper_2312_17530_amd import binding
+    R, C, p, ratio = 256, 2304, 3, 0.02
+    rng = np.random.default_rng(91)
+    base = rng.standard_normal((R, C)).astype(np.float32)
+    zero = np.zeros((R, C), np.float32)
+    for scale, inside in [(2.0 ** -42, False), (2.0 ** -41.5, False), (2.0 ** -39, True), (2.0 ** -36, True),
+                          (2.0 ** 36, True), (2.0 ** 38.5, True), (2.0 ** 40.5, False), (2.0 ** 43, False)]:
+        g = (base * np.float32(scale)).astype(np.float32)
+        sess = _session([(R, C)], p, 0.5, [ratio])
+        o = oracle.compress_layer(g, zero, p, 0.5, ratio)
+        assert (2.0 ** -40 <= float(o.tau) <= 2.0 ** 40) == inside, (scale, float(o.tau))
+        for call in range(3):
+            sess.set_grad([g])
+            sess.set_residual([zero])
+            sess.compress()
+            torch.cuda.synchronize()
+            path = binding.rsdgc_last_paths(sess.plan, sess.workspace)[0]
+            gi, gv, gc, gn = sess.results()[0]
+            parity.check_layer(f"scale 2^{np.log2(scale):.1f}, call {call}, path {path}", (R, C), p, o.k, o.tau, o.nsi,
+                               o.centres, o.idx, o.val, o.r_new, o.v, gi, gv, gc, gn, sess.unpack(sess.residual)[0])
+        assert path == (3 if inside else 1), (scale, path)
+
+
 def _same_floats(a, b):
     a, b = np.asarray(a, np.float32).reshape(-1), np.asarray(b, np.float32).reshape(-1)
     return a.shape == b.shape and bool(np.all((a.view(np.uint32) == b.view(np.uint32)) | (np.isnan(a) & np.isnan(b))))
