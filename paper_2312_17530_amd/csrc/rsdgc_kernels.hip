@@ -501,7 +501,7 @@ __device__ __forceinline__ WaveBucket wave_find_bucket(const uint32_t *__restric
 // MOM: with Eq. 12's momentum term (a.mom, a.mom_out, a.m).  FEED: the workgroups take their
 // tiles from the launch's work feed instead of a fixed strided share.
 template <int P, int PASS, bool MOM, bool FEED>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(FEED && !MOM ? (P <= 3 ? 5 : P == 5 ? 4 : 3) : 1, 8)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(PASS == kPassCapture && !MOM ? (P <= 3 ? 5 : 4) : 1, 8)))
 void k_nsi(const NsiArgs a) {
     constexpr int H = (P - 1) / 2;
     constexpr int ROWS = kTileRows + 2 * H;
