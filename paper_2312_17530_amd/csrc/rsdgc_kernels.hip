@@ -3190,7 +3190,11 @@ int launch_nsi(const rsdgc_plan_s *plan, char *ws, const float *grad, const floa
 #define RSDGC_NSI_LAUNCH(PP, MM, FF)                                                        \
     {                                                                                       \
         static const uint32_t resident = resident_workgroups(k_nsi<PP, PASS, MM, FF>);      \
-        const dim3 grid(std::min<uint32_t>(items, resident));                               \
+        /* fixed shares: as many workgroups as give every one the same number of tiles    \
+           (2786 tiles on 1280 resident workgroups take three rounds either way; 929       \
+           workgroups of three tiles each leave the CUs less crowded in all three) */      \
+        const uint32_t rounds = (items + resident - 1) / resident;                          \
+        const dim3 grid(FF ? std::min<uint32_t>(items, resident) : (items + rounds - 1) / rounds); \
         hipLaunchKernelGGL((k_nsi<PP, PASS, MM, FF>), grid, block, 0, stream, a);           \
     }
 #define RSDGC_NSI_CASE(PP)                                                                  \
