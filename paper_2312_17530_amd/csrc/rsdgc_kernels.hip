@@ -488,10 +488,14 @@ __device__ __forceinline__ WaveBucket wave_find_bucket(const uint32_t *__restric
 // Work unit: one 16 x 256 tile of one layer.  The tile of v = r + g plus a halo of
 // h = (P-1)/2 rows and 4 columns (16-byte aligned) goes to LDS; each thread then walks
 // down the 16 rows of one column, keeping per-row horizontal sums of |w|, w and w^2
-// (double) for the last P rows in registers.  The variance is formed as
-// (P^2 * sum w^2 - (sum w)^2) / P^4 in double, or -- where that form cancels -- from the
-// tile again as Eq. 10 prints it; either way equal windows get equal scores wherever they
-// lie and a constant window gets a variance of exactly 0.
+// for the last P rows in registers.  Every score that is stored, counted or recorded is
+// computed in double: the variance as (P^2 * sum w^2 - (sum w)^2) / P^4, or -- where that
+// form cancels -- from the tile again as Eq. 10 prints it; either way equal windows get
+// equal scores wherever they lie and a constant window gets a variance of exactly 0.  The
+// main pass (capture) runs the sweep in float32 instead and only decides there which centres
+// cannot reach the layer's bound (PreF32 above); the others it evaluates in double as said.
+// The capture variants are held to five waves per SIMD for p <= 3 and four for p = 5, 7
+// (what their registers allow without spilling; measured faster than one wave less).
 //
 // A workgroup takes tiles b, b + W, ... of the launch (W workgroups, laid out so that each XCD
 // gets one contiguous part of every stretch of W tiles: neighbouring tiles share halo rows in
