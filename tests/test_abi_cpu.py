@@ -255,6 +255,30 @@ def test_plans_near_the_32_bit_limits():
     del plan, lib
 
 
+def test_workspace_of_vectors_and_narrow_layers_stays_in_proportion():
+    """A tile's candidate slot is no longer than the tile (16 rows x 256 columns of the layer, or
+    what the layer has of them), and a single column is laid out as a single row: the workspace of
+    a long vector or of a tall layer of a few columns is a few bytes per element, the same for
+    N x 1 as for 1 x N, and does not move with the keep ratios."""
+    def ws(shapes, ratios=None, p=3):
+        return binding.rsdgc_plan(shapes, p, 0.5, ratios or [0.02] * len(shapes)).workspace_bytes
+    n = 2_000_000
+    col, row = ws([(n, 1)]), ws([(1, n)])
+    assert col == row
+    assert col < 16 * n + (1 << 20)                      # (it was 260 bytes per element: 512 entries per 16-element tile)
+    narrow = ws([(n // 7, 7)])
+    assert narrow < 16 * n + (1 << 20)                   # 16 x 7 elements per tile: 112 entries
+    # ordinary layers keep their 512 entries per tile: 1 byte per element for the slots
+    wide = ws([(1024, 4096)])
+    assert ws([(1024, 4096)], [0.0005]) == wide == ws([(1024, 4096)], [0.3])
+    plan = binding.rsdgc_plan([(n, 1), (300, 77)], 3, 0.5, [0.02, 0.05])
+    before = plan.workspace_bytes
+    binding.rsdgc_plan_set_ratios(plan, [0.001, 0.5])
+    assert plan.workspace_bytes == before
+    # counts, offsets and capacities are those of the shape as given
+    assert plan.layer_elems(0) == n and plan.layer_k(0) == math.ceil(n / 9 * 0.001)
+
+
 def test_static_workspace_entry_point_validates_on_the_host():
     """rsdgc_compress_static refuses a null or block plan and a plan beyond its built-in workspace
     before it touches the GPU (this box may have none)."""
