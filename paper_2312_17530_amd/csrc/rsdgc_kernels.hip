@@ -267,16 +267,17 @@ __device__ __forceinline__ float uniform_f32(float x) {
 // is therefore evaluated again the way Eq. 10 is printed -- window_ssd below -- and only the
 // others (relative error of the one-pass form below 3e-9) keep the one-pass value.
 constexpr double kCancelFrac = 1.0 / 1048576.0;
-// The main pass rules out the centres below the bound in float32 where the bound's magnitude allows
-// it (half the registers of the double form, no conversions).  It must never rule out a centre that
+
+// The main pass rules out the centres below the bound in float32 (half the registers of the same
+// test in double, no conversions).  It must never rule out a centre that
 // the evaluation in full would record, so every float32 quantity is bounded against the exact one.
 // With u = 2^-24, n = p*p, exact window sums SA = sum|w|, SS = sum w, SQ = sum w^2, D = n SQ - SS^2
 // (SA^2 <= n SQ, |SS| <= SA), and a bound B in [2^-40, 2^40] (nothing of weight under- or overflows):
 //   sa = SA (1 + t), |t| <= (n-1) u          (non-negative terms)
 //   n sq - ss^2 differs from D by at most (3n + 3) u * n SQ: n u from the roundings of sq and of the
 //     product with n, 2n u from ss (off by at most (n-1) u SA) squared, the rest from the last fma;
-//     d_hi = that + kPreSlack<P> * n sq with kPreSlack = 1.3 (3n + 3) u is therefore at least D;
-//   rest = B' - ca sa with B' = B (1 - 2^-22 - 2.04 n u), rounded down: at most the exact
+//     d_hi = that + kSlack * n sq with kSlack = 1.3 (3n + 3) u is therefore at least D;
+//   rest = B' - ca sa with B' = B * kBoundFactor = B (1 - 2^-22 - 2.04 n u), rounded down: at most the exact
 //     B (1 - 2^-22) - ca SA whenever ca SA < 2 B, and negative otherwise;
 //   the centre stays unless rest > 0 and cb^2 d_hi < rest^2 (1 - 1e-6): the seven roundings between
 //     the two sides change their ratio by less than 8 u < 1e-6.
